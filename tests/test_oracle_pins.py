@@ -1,0 +1,417 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+Each test ties one part of ``oracle/`` to what the paper or the mathematics
+fixes: the prefix-sum definition of sampling (Eq. 1) by brute force with exact
+rational arithmetic, closed forms, the parent-equals-sum-of-children invariant
+(Section V-A), textbook special cases, and a chi-square test of the sampling
+distribution Pr(i) = P(i) / sum P (Section II-A).
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle.per_oracle import (FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL, Oracle)
+from paper_2311_09445_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+KS = [2, 4, 8, 16, 32, 64]
+
+
+def filled(K, leaves, fields=(), **kw):
+    leaves = np.asarray(leaves, dtype=np.float32)
+    o = Oracle(K, len(leaves), fields, **kw)
+    o.insert(len(leaves), None, leaves)
+    return o
+
+
+def pairwise_f32(x):
+    """Balanced pairwise fp32 sum over the last axis (length a power of two)."""
+    x = np.asarray(x, dtype=np.float32)
+    while x.shape[-1] > 1:
+        x = (x[..., 0::2] + x[..., 1::2]).astype(np.float32)
+    return x[..., 0]
+
+
+def check_invariant(o):
+    """Every stored node is the pairwise fp32 sum of its K children (zero padded)."""
+    K = o.K
+    lvl = o.read_level(0)
+    for h in range(1, o.H + 1):
+        up = o.read_level(h)
+        pad = np.zeros(len(up) * K, dtype=np.float32)
+        pad[:len(lvl)] = lvl
+        want = pairwise_f32(pad.reshape(len(up), K))
+        assert up.tobytes() == want.tobytes(), f"height {h}"
+        lvl = up
+    assert len(lvl) == 1 and lvl[0] == np.float32(o.total)
+
+
+# ---------------------------------------------------------------- golden example
+def _golden():
+    d = {}
+    with open(os.path.join(GOLDEN, "eq1_worked_example.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, *v = line.split()
+            d[k] = [float(x) for x in v]
+    return d
+
+
+@pytest.mark.parametrize("K", [2, 4, 8])
+def test_golden_worked_example(K):
+    g = _golden()
+    o = filled(K, g["leaves"])
+    idx, w, v = o.sample(np.array(g["u"], np.float32), beta=g["beta"][0])
+    assert idx.tolist() == [int(x) for x in g["idx"]]
+    assert v.tolist() == g["prio"]
+    np.testing.assert_allclose(w, g["weight"], rtol=1e-7)
+    h = 1
+    while f"k{K}_h{h}" in g:
+        assert o.read_level(h).tolist() == g[f"k{K}_h{h}"]
+        h += 1
+    assert h - 1 == o.H
+
+
+# ------------------------------------------------------------- brute force, exact
+def brute_force_index(leaves, t):
+    """min{i : prefix(i) > t} with exact rationals: the half-open reading of Eq. 1."""
+    acc = Fraction(0)
+    for i, p in enumerate(leaves):
+        acc += Fraction(float(p))
+        if acc > t:
+            return i
+    raise AssertionError("target beyond total")
+
+
+@pytest.mark.parametrize("K", KS)
+@pytest.mark.parametrize("N", [1, 2, 7, 33, 64, 100])
+def test_bruteforce_prefix_search_exact(K, N):
+    rng = np.random.default_rng(1000 * K + N)
+    for trial in range(6):
+        # small integers times a dyadic scale: every fp32 sum and difference is exact
+        scale = 2.0 ** rng.integers(-3, 3)
+        leaves = (rng.integers(0, 8, N) * (rng.random(N) < 0.7)).astype(np.float32) * np.float32(scale)
+        if leaves.sum() == 0:
+            leaves[rng.integers(N)] = np.float32(scale)
+        o = filled(K, leaves)
+        total = Fraction(float(leaves.astype(np.float64).sum()))
+        assert Fraction(o.total) == total
+        for B in (1, 4, 64):
+            u = rng.integers(0, 64, B).astype(np.float32) / np.float32(64)
+            idx, _, v = o.sample(u, want_weights=False)
+            for i in range(B):
+                t = (Fraction(i) + Fraction(float(u[i]))) * total / B
+                assert idx[i] == brute_force_index(leaves, t), (K, N, B, i)
+                assert v[i] == leaves[idx[i]] and v[i] > 0
+
+
+@pytest.mark.parametrize("K", [2, 16])
+@pytest.mark.parametrize("B", [3, 5, 7, 48])
+def test_bruteforce_non_power_of_two_batch(K, B):
+    """total/B is rounded once; the brute force takes the same fp32 target, then scans exactly."""
+    rng = np.random.default_rng(B)
+    leaves = rng.integers(0, 8, 50).astype(np.float32)
+    leaves[0] = 1
+    o = filled(K, leaves)
+    u = rng.integers(0, 64, B).astype(np.float32) / np.float32(64)
+    seg = np.float32(o.total) / np.float32(B)
+    idx, _, _ = o.sample(u, want_weights=False)
+    for i in range(B):
+        t = (np.float32(i) + u[i]) * seg
+        assert isinstance(t, np.float32)
+        assert idx[i] == brute_force_index(leaves, Fraction(float(t)))
+
+
+# ------------------------------------------------------ bracket on arbitrary floats
+@pytest.mark.parametrize("K", KS)
+@pytest.mark.parametrize("dist", ["uniform_1e-3_1", "lognormal_0_1", "exponential_1", "pareto_1.5"])
+def test_bracket_against_fp64_prefix(K, dist):
+    rng = np.random.default_rng(7)
+    N, B = 5000, 512
+    leaves = wl._draw_priorities(dist, rng, (N,))
+    leaves[rng.random(N) < 0.05] = 0
+    o = filled(K, leaves)
+    u = wl.uniform01(rng, (B,))
+    idx, _, v = o.sample(u, want_weights=False)
+    prefix = np.concatenate([[0.0], np.cumsum(leaves.astype(np.float64))])
+    total = np.float32(o.total)
+    seg = total / np.float32(B)
+    tol = 4 * o.HB * 2.0 ** -24 * float(total)
+    for i in range(B):
+        t = float((np.float32(i) + u[i]) * seg)
+        assert prefix[idx[i]] - tol <= t <= prefix[idx[i] + 1] + tol
+        assert v[i] == leaves[idx[i]] and v[i] > 0
+    assert np.all(np.diff(idx.astype(np.int64)) >= 0)          # sorted targets -> sorted indices
+    assert abs(float(total) - prefix[-1]) <= tol
+
+
+# ------------------------------------------------------------------- closed forms
+@pytest.mark.parametrize("K", KS)
+def test_all_ones_closed_form(K):
+    N = 4096
+    o = filled(K, np.ones(N, np.float32))
+    assert o.total == N
+    rng = np.random.default_rng(3)
+    for B in (64, 4096):
+        u = wl.uniform01(rng, (B,))
+        idx, w, v = o.sample(u, beta=0.7)
+        pos = (np.arange(B, dtype=np.float32) + u).astype(np.float32)
+        want = np.floor(pos.astype(np.float64) * (N / B)).astype(np.int64)
+        assert np.array_equal(idx, want)
+        assert np.all(w == 1.0) and np.all(v == 1.0)
+    idx, _, _ = o.sample(np.full(N, 0.5, np.float32))
+    assert np.array_equal(idx, np.arange(N))
+
+
+@pytest.mark.parametrize("K", KS)
+@pytest.mark.parametrize("where", [0, 1, 500, 998, 999])
+def test_single_nonzero_leaf(K, where):
+    leaves = np.zeros(1000, np.float32)
+    leaves[where] = 0.37
+    o = filled(K, leaves)
+    u = wl.uniform01(np.random.default_rng(0), (128,))
+    u[0], u[-1] = 0.0, np.float32(1 - 2.0 ** -24)
+    idx, w, v = o.sample(u)
+    assert np.all(idx == where) and np.all(v == np.float32(0.37)) and np.all(w == 1.0)
+
+
+def test_zero_leaves_and_unfilled_slots_never_sampled():
+    rng = np.random.default_rng(5)
+    N = 3000
+    o = Oracle(16, N)
+    leaves = wl._draw_priorities("pareto_1.5", rng, (2000,))
+    leaves[rng.random(2000) < 0.3] = 0
+    leaves[-1] = 0.0
+    o.insert(2000, None, leaves)
+    assert o.size == 2000
+    for _ in range(20):
+        idx, _, v = o.sample(wl.uniform01(rng, (256,)))
+        assert np.all(idx < 2000) and np.all(leaves[idx] > 0) and np.all(v == leaves[idx])
+
+
+def test_target_inside_its_stratum():
+    """Sample i draws from stratum i: with B = number of equal-mass blocks, sample i lands in block i."""
+    K, blocks, per = 4, 16, 8
+    rng = np.random.default_rng(11)
+    leaves = np.zeros(blocks * per, np.float32)
+    for b in range(blocks):                       # each block holds mass exactly 8 spread unevenly
+        cuts = np.sort(rng.choice(np.arange(1, 8), 3, replace=False))
+        parts = np.diff(np.concatenate([[0], cuts, [8]]))
+        leaves[b * per + rng.choice(per, 4, replace=False)] = parts
+    o = filled(K, leaves)
+    for _ in range(10):
+        idx, _, _ = o.sample(wl.uniform01(rng, (blocks,)))
+        assert np.array_equal(idx // per, np.arange(blocks))
+
+
+# ------------------------------------------------------------ tree values / update
+@pytest.mark.parametrize("K", KS)
+@pytest.mark.parametrize("N", [1, 5, 64, 1000, 4097])
+def test_invariant_after_insert_and_update(K, N):
+    rng = np.random.default_rng(K * 31 + N)
+    leaves = wl._draw_priorities("lognormal_0_1", rng, (N,))
+    o = filled(K, leaves)
+    check_invariant(o)
+    assert np.array_equal(o.read_level(0), leaves)
+    for _ in range(5):
+        B = 97
+        idx = rng.integers(0, N, B).astype(np.uint32)
+        pr = wl._draw_updates("absnormal1_eps_pow0.6", rng, (B,))
+        o.update(idx, pr)
+        for j in range(B):                         # plain sequential semantics on a flat array
+            leaves[idx[j]] = pr[j]
+        check_invariant(o)
+        assert np.array_equal(o.read_level(0), leaves)
+    # equals a from-scratch build of the final leaves, and an idempotent update changes no bit
+    fresh = filled(K, leaves)
+    for h in range(o.H + 1):
+        assert o.read_level(h).tobytes() == fresh.read_level(h).tobytes()
+    before = [o.read_level(h).tobytes() for h in range(o.H + 1)]
+    all_idx = np.arange(N, dtype=np.uint32)
+    o.update(all_idx, leaves)
+    assert before == [o.read_level(h).tobytes() for h in range(o.H + 1)]
+
+
+def test_root_is_exact_total_for_dyadic_leaves():
+    rng = np.random.default_rng(2)
+    leaves = (rng.integers(0, 1024, 3000) / 64.0).astype(np.float32)
+    for K in KS:
+        o = filled(K, leaves)
+        assert Fraction(o.total) == sum(Fraction(float(x)) for x in leaves)
+        # a K-group's parent is the exact sum of its K children
+        lvl1 = o.read_level(1)
+        for j in (0, len(lvl1) // 2, len(lvl1) - 1):
+            assert Fraction(float(lvl1[j])) == sum(Fraction(float(x)) for x in leaves[j * K:(j + 1) * K])
+
+
+def test_last_writer_wins_on_duplicates():
+    rng = np.random.default_rng(9)
+    N = 257
+    o = filled(8, np.ones(N, np.float32))
+    shadow = np.ones(N, np.float32)
+    batches = [
+        (np.full(64, 5, np.uint32), rng.random(64).astype(np.float32)),                 # all equal
+        (np.tile(np.array([3, 200], np.uint32), 50), rng.random(100).astype(np.float32)),  # alternating
+        (rng.integers(0, 16, 300).astype(np.uint32), rng.random(300).astype(np.float32)),
+    ]
+    for idx, pr in batches:
+        o.update(idx, pr)
+        last = {}
+        for j, i in enumerate(idx):
+            last[int(i)] = pr[j]
+        for i, v in last.items():
+            shadow[i] = v
+        assert np.array_equal(o.read_level(0), shadow)
+        check_invariant(o)
+
+
+def test_k_invariance_reduces_every_fanout_to_the_binary_tree():
+    """Same leaves, same uniforms: identical indices, and identical sums wherever binary depths coincide."""
+    rng = np.random.default_rng(4)
+    N = 4096
+    leaves = wl._draw_priorities("exponential_1", rng, (N,))
+    leaves[rng.random(N) < 0.1] = 0
+    u = wl.uniform01(rng, (1024,))
+    ref = filled(2, leaves)                         # K = 2 is the textbook binary sum tree
+    ridx, rw, rv = ref.sample(u, beta=0.5)
+    for K in KS[1:]:
+        o = filled(K, leaves)
+        idx, w, v = o.sample(u, beta=0.5)
+        assert np.array_equal(idx, ridx) and np.array_equal(v, rv) and np.array_equal(w, rw)
+        shift = o.HB - ref.HB                      # extra all-zero-right levels above the real root
+        assert shift >= 0
+        for h in range(o.H + 1):
+            d = o.HB - h * (o.K.bit_length() - 1)  # binary depth of K-ary height h
+            if d - shift < 0:
+                continue
+            mine = o.read_level(h)
+            theirs = ref.read_binary_depth(d - shift)[:len(mine)]
+            assert mine.tobytes() == theirs.tobytes()
+        assert o.total == ref.total
+
+
+def test_denormals_and_negative_zero():
+    tiny = np.float32(1e-42)                        # subnormal
+    leaves = np.array([0.0, -0.0, tiny, 0.0, tiny, -0.0, tiny, tiny], np.float32)
+    for K in (2, 4, 8):
+        o = filled(K, leaves)
+        assert o.total == np.float32(4) * tiny and o.total > 0
+        assert o.status == 0                        # -0.0 is a valid priority
+        idx, w, v = o.sample(np.array([0.0, 0.5, 0.5, 0.99], np.float32))
+        assert idx.tolist() == [2, 4, 6, 7] and np.all(v == tiny) and np.all(w == 1.0)
+
+
+# -------------------------------------------------------------------- distribution
+def test_sampling_frequency_is_proportional_to_priority():
+    rng = np.random.default_rng(12345)
+    N, B, steps = 256, 64, 2000
+    leaves = td = wl.td_to_priority(rng.standard_normal(N), 1e-6, 0.6)
+    o = filled(16, leaves)
+    counts = np.zeros(N)
+    for _ in range(steps):
+        idx, _, _ = o.sample(wl.uniform01(rng, (B,)), want_weights=False)
+        np.add.at(counts, idx, 1)
+    expect = B * steps * td.astype(np.float64) / td.astype(np.float64).sum()
+    x2 = float(((counts - expect) ** 2 / expect).sum())
+    assert x2 < stats.chi2.ppf(0.9999, N - 1)
+    # and the test has teeth: the same counts are rejected against a uniform law
+    flat = np.full(N, B * steps / N)
+    assert float(((counts - flat) ** 2 / flat).sum()) > stats.chi2.ppf(0.9999, N - 1)
+
+
+# ------------------------------------------------------------- importance weights
+def test_importance_weights():
+    rng = np.random.default_rng(8)
+    N = 2000
+    leaves = wl._draw_priorities("lognormal_0_1", rng, (N,))
+    o = Oracle(16, 3000)
+    o.insert(N, None, leaves)
+    u = wl.uniform01(rng, (256,))
+    for beta in (0.0, 0.4, 1.0):
+        idx, w, v = o.sample(u, beta=beta)
+        assert w.max() == 1.0 and np.all(w > 0) and np.all(w <= 1)
+        if beta == 0.0:
+            assert np.all(w == 1.0)
+        # definition: w_i = (size * P(i))^-beta / max_j(...), P(i) = v_i / total; size = filled rows
+        P = v.astype(np.float64) / float(np.float32(o.total))
+        raw = (N * P) ** (-beta)
+        np.testing.assert_allclose(w, raw / raw.max(), rtol=2e-7)
+        i, j = 3, 200
+        np.testing.assert_allclose(w[i] / w[j], (float(v[j]) / float(v[i])) ** beta, rtol=1e-6)
+    o2 = filled(4, np.full(64, 0.25, np.float32))
+    assert np.all(o2.sample(u[:32], beta=0.9)[1] == 1.0)
+
+
+# ----------------------------------------------------------- insert / ring / gather
+def test_ring_insert_gather_and_max_priority():
+    w = wl.WORKLOADS["c1_binary_small"]
+    N, fb = 50, w.field_bytes
+    o = Oracle(4, N, fb, init_max=1.0)
+    counter = 0
+
+    def rows(n):
+        nonlocal counter
+        c = np.arange(counter, counter + n)
+        counter += n
+        return [wl.row_bytes(0, c, f, b) for f, b in enumerate(fb)]
+
+    slots = o.insert(30, rows(30))
+    assert slots.tolist() == list(range(30)) and o.size == 30 and o.cursor == 30
+    assert np.all(o.read_level(0)[:30] == 1.0) and np.all(o.read_level(0)[30:] == 0.0)
+    o.update(np.array([3, 4], np.uint32), np.array([2.5, 0.5], np.float32))
+    assert o.max_priority == 2.5
+    slots = o.insert(30, rows(30))                  # wraps: slots 30..49 then 0..9
+    assert slots.tolist() == list(range(30, 50)) + list(range(10))
+    assert o.size == N and o.cursor == 10
+    lv = o.read_level(0)
+    assert np.all(lv[:10] == 2.5) and lv[10] == 1.0 and np.all(lv[30:] == 2.5)
+    check_invariant(o)
+    # slot s holds the row with the largest insert counter that mapped to it
+    holder = {}
+    for c in range(60):
+        holder[c % N] = c
+    idx = np.array([0, 9, 10, 29, 30, 49, 7, 7], np.uint32)
+    got = o.gather(idx)
+    for f, b in enumerate(fb):
+        want = wl.row_bytes(0, [holder[int(i)] for i in idx], f, b)
+        assert np.array_equal(got[f], want)
+    # explicit priorities raise the running max only after the call; invalid ones are skipped
+    o.insert(3, rows(3), np.array([7.0, np.nan, -1.0], np.float32))
+    assert o.max_priority == 7.0 and o.status == FLAG_BAD_PRIORITY
+    lv = o.read_level(0)
+    assert lv[10] == 7.0 and lv[11] == 1.0 and lv[12] == 1.0
+    with pytest.raises(ValueError):
+        o.insert(N + 1)
+
+
+def test_status_flags_and_skips():
+    o = Oracle(2, 16, (4,))
+    idx, w, v = o.sample(np.zeros(4, np.float32))
+    assert np.all(idx == 0xFFFFFFFF) and np.all(w == 0) and o.status == FLAG_ZERO_TOTAL
+    o.clear_status()
+    o.insert(8, None, np.ones(8, np.float32))
+    o.update(np.array([1, 8, 2, 3, 4], np.uint32), np.array([2, 2, np.inf, -1, np.nan], np.float32))
+    assert o.status == FLAG_BAD_INDEX | FLAG_BAD_PRIORITY
+    assert o.read_level(0).tolist() == [1, 2, 1, 1, 1, 1, 1, 1] + [0] * 8
+    assert o.max_priority == 2.0
+    o.clear_status()
+    g = o.gather(np.array([0, 16, 0xFFFFFFFF], np.uint32))
+    assert np.all(g[0][1:] == 0) and o.status == FLAG_BAD_INDEX
+    assert o.get_priority(np.array([1, 99], np.uint32)).tolist() == [2.0, 0.0]
+
+
+def test_level_shapes_follow_ceil_division():
+    for K, N in [(32, 1 << 14), (16, 1 << 10), (16, 10000), (2, 4096), (32, 33)]:
+        o = Oracle(K, N, with_payload=False)
+        n, h = N, 0
+        while True:
+            assert o.level_count(h) == n
+            if n == 1 and h >= 1:
+                break
+            n = -(-n // K)
+            h += 1
+        assert o.H == h
