@@ -1,0 +1,148 @@
+/*
+ * per.h -- C-ABI of the MI355X prioritized replay buffer (K-ary sum tree).
+ *
+ * The operations are the paper's Replay Manager requests (Section V-A:
+ * priority sampling, priority retrieval, priority update, insertion) plus the
+ * read of sampled rows from Data Storage (Section II-A "Learner"; Listing 2,
+ * `sampled_data = D_storage[sampled_indices]`), batched over B requests and
+ * over T independent buffers.
+ *
+ * Conventions
+ *  - Pointers named d_* are DEVICE pointers owned by the caller; they must stay
+ *    valid until the work enqueued by the call has finished.  All other
+ *    pointers are HOST pointers.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Every
+ *    call only enqueues work on `stream` and returns; nothing synchronises
+ *    except per_status.  Calls on one buffer must be issued in order on one
+ *    stream (or be ordered by the caller with events).
+ *  - The library never allocates device memory: the caller provides one arena
+ *    (per_arena_bytes tells how large) that holds tree levels, payload columns
+ *    and all scratch.
+ *  - Arrays carry a leading tree dimension: "[T][B]" means T*B contiguous
+ *    elements, tree-major.
+ *  - Tree values are fp32.  The tree stores the value it is given (the caller
+ *    applies any exponent alpha beforehand).  A K-child sum is the balanced
+ *    pairwise fp32 sum over child positions, so results do not depend on the
+ *    launch shape and equal those of a binary sum tree.
+ *  - Return value: 0 on success; a negative PER_E* code on an error detected on
+ *    the host, in which case no work was enqueued.  Conditions only the device
+ *    can see set sticky bits (PER_FLAG_*) read by per_status.
+ *  - A batch of size 0 is valid and enqueues nothing.
+ */
+#ifndef PER_H_
+#define PER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PER_MAX_FIELDS 8
+
+#define PER_OK       0
+#define PER_EINVAL  (-1)  /* null/misaligned pointer, bad fanout, bad field table, bad beta ...   */
+#define PER_ENOMEM  (-2)  /* arena too small                                                    */
+#define PER_EEMPTY  (-3)  /* sample on a buffer that holds no rows                              */
+#define PER_ERANGE  (-4)  /* insert of more rows than the capacity, height out of range ...     */
+#define PER_EHIP    (-5)  /* a HIP call or kernel launch failed                                 */
+
+#define PER_FLAG_BAD_INDEX    1u  /* index >= capacity (gather / get_priority) or >= size (update): element skipped;
+                                     gather and get_priority write zeros for it                                   */
+#define PER_FLAG_BAD_PRIORITY 2u  /* NaN, infinite or negative value: leaf write skipped                          */
+#define PER_FLAG_ZERO_TOTAL   4u  /* sample on a tree whose root is not > 0: indices 0xFFFFFFFF, weights 0        */
+
+typedef struct per_buffer per_t;   /* opaque host object */
+
+typedef struct per_config {
+  uint32_t struct_size;                 /* sizeof(per_config): ABI check                              */
+  uint32_t fanout;                      /* K in {2,4,8,16,32,64} (the paper's "fanout", Listing 1)    */
+  uint64_t capacity;                    /* N leaves per tree, 1 <= N <= 2^31 (the paper's "size")     */
+  uint32_t n_trees;                     /* T >= 1 independent buffers                                 */
+  uint32_t n_fields;                    /* payload columns per row, 0..PER_MAX_FIELDS, stored SoA     */
+  uint32_t field_bytes[PER_MAX_FIELDS]; /* bytes per row of each column, e.g. {68,24,4,68,1}          */
+  float    init_max_priority;           /* value given to the first inserted rows; finite and > 0     */
+} per_config;
+
+/* Size and alignment the arena must have for this configuration. */
+int per_arena_bytes(const per_config* cfg, size_t* bytes, size_t* align);
+
+/* Lays the tree levels, payload columns and scratch out in `d_arena` (device memory,
+ * at least per_arena_bytes large and aligned), zero-fills tree and scratch on `stream`
+ * and returns a host handle.  The arena stays the caller's; it must outlive the handle. */
+int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* stream, per_t** out);
+
+/* Frees the host handle only. */
+int per_destroy(per_t* p);
+
+/* Insertion (Section V-A; Listing 2, "Populate Replay memory").  Row j of every tree goes
+ * to ring slot (cursor + j) mod N; its leaf is set to d_prio[t][j], or, when d_prio is
+ * NULL, to the running maximum of all valid values written so far (as it was when the
+ * call started).  Ancestors are re-summed.  n <= N.
+ *   d_field_src : HOST array of n_fields DEVICE pointers, each [T][n][field_bytes[f]];
+ *                 may be NULL (or hold NULLs) to leave payload columns untouched.
+ *   d_out_idx   : [T][n] slots written, or NULL.
+ * An invalid explicit priority skips the leaf write (row is still stored) and sets
+ * PER_FLAG_BAD_PRIORITY. */
+int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_prio,
+               uint32_t* d_out_idx, void* stream);
+
+/* Priority sampling (Eq. 1; Section V-A "traversing the tree performing prefix sum from
+ * root to leaf"), stratified: sample i of a tree takes the target
+ *   ((float)i + u[i]) * (total / (float)B)
+ * and returns the leaf whose half-open prefix interval contains it.  Leaves with value 0
+ * and slots never written are never returned.
+ *   d_u          : [T][B] uniforms in [0,1)
+ *   d_out_idx    : [T][B]
+ *   d_out_weight : [T][B] importance weights (size * P(i))^-beta divided by the batch
+ *                  maximum, so the largest is 1; or NULL.  beta must be finite and >= 0.
+ *   d_out_prio   : [T][B] value of each sampled leaf; or NULL. */
+int per_sample(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx,
+               float* d_out_weight, float* d_out_prio, void* stream);
+
+/* Data Storage read: d_field_dst[f][t][i] = column f, row d_idx[t][i].
+ *   d_field_dst : HOST array of n_fields DEVICE pointers, each [T][B][field_bytes[f]];
+ *                 a NULL entry skips that column. */
+int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field_dst, void* stream);
+
+/* Priority update (Section V-A), in the set-and-re-sum form: every valid element sets its
+ * leaf; when an index occurs more than once the element latest in the batch wins;
+ * afterwards every ancestor of a touched leaf equals the pairwise sum of its children.
+ * Valid means d_idx < size and d_prio finite and >= 0. */
+int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio, void* stream);
+
+/* Priority retrieval (Section V-A): d_out[t][i] = leaf d_idx[t][i]. */
+int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream);
+
+/* Copies the n_h real nodes of height `height` (0 = leaves, H = root) of one tree to d_out
+ * (may be NULL to only query the count).  *count receives n_h. */
+int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint64_t* count,
+                   void* stream);
+
+/* d_out[t] = root of tree t. */
+int per_total(per_t* p, float* d_out, void* stream);
+
+/* d_out[t] = running maximum priority of tree t. */
+int per_max_priority(per_t* p, float* d_out, void* stream);
+
+/* Synchronises `stream`, then ORs the sticky device flags of all trees into *flags. */
+int per_status(per_t* p, void* stream, uint32_t* flags);
+int per_clear_status(per_t* p, void* stream);
+
+/* Host-side mirrors (pure functions of the call sequence). */
+uint32_t per_height(const per_t* p);     /* H                                   */
+uint64_t per_size(const per_t* p);       /* filled rows per tree                */
+uint64_t per_cursor(const per_t* p);     /* next ring slot                      */
+
+/* Performance knobs; results never depend on them.
+ *   "lds_budget_bytes" : upper tree levels are staged in LDS while they fit this many bytes
+ *   "sample_block", "update_block", "gather_block" : workgroup sizes (multiples of 64, <= 1024) */
+int per_set_tuning(per_t* p, const char* name, int64_t value);
+
+const char* per_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PER_H_ */

@@ -1,0 +1,337 @@
+// C-ABI of the prioritized replay buffer: argument checks, arena layout and the host-side
+// mirrors (ring cursor, fill count, stamp counter).  All device work is in per_kernels.hip.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/per.h"
+#include "per_geom.h"
+
+using namespace per;
+
+struct per_buffer {
+  per_config cfg;
+  Geom g;
+  Tuning tn;
+  uint8_t* arena;
+  size_t arena_bytes;
+  uint8_t* col[kMaxFields];
+  uint64_t col_stride[kMaxFields];
+  uint64_t cursor, size;
+  uint64_t stamp_next;       // next unused last-writer stamp (stamps 1 .. 2^32-1)
+  uint32_t weight_calls;     // number of per_sample calls that produced weights
+  int device;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+  uint32_t logK, H;
+  uint32_t n[kMaxHeight + 1];
+  uint32_t stride[kMaxHeight + 1];
+  size_t level_off[kMaxHeight + 1];
+  size_t scalars_off, owner_off, col_off[kMaxFields];
+  uint64_t col_stride[kMaxFields];
+  uint32_t owner_stride;
+  size_t tree_end;            // bytes up to here are zero-filled as 32-bit words at create
+  size_t total;
+};
+
+int check_config(const per_config* c) {
+  if (!c || c->struct_size != sizeof(per_config)) return PER_EINVAL;
+  const uint32_t K = c->fanout;
+  if (K < 2 || K > 64 || (K & (K - 1))) return PER_EINVAL;
+  if (c->capacity < 1 || c->capacity > (1ull << 31)) return PER_EINVAL;
+  if (c->n_trees < 1 || c->n_trees > 65535) return PER_EINVAL;
+  if (c->n_fields > PER_MAX_FIELDS) return PER_EINVAL;
+  for (uint32_t f = 0; f < c->n_fields; ++f)
+    if (c->field_bytes[f] == 0 || c->field_bytes[f] > (1u << 20)) return PER_EINVAL;
+  if (!(c->init_max_priority > 0.0f) || !isfinite(c->init_max_priority)) return PER_EINVAL;
+  return PER_OK;
+}
+
+void make_layout(const per_config* c, Layout* L) {
+  const uint32_t K = c->fanout, T = c->n_trees;
+  L->logK = 0;
+  while ((1u << L->logK) < K) L->logK++;
+  uint64_t n = c->capacity;
+  uint32_t h = 0;
+  L->n[0] = (uint32_t)n;
+  do {
+    n = (n + K - 1) / K;
+    L->n[++h] = (uint32_t)n;
+  } while (n > 1);
+  L->H = h;
+  size_t off = 0;
+  L->scalars_off = off;                         // max_v[T], status[T], vmin[2][T]
+  off = round_up(off + (size_t)4 * T * 4, kAlign);
+  for (uint32_t l = 0; l <= L->H; ++l) {
+    const uint64_t padded = ((uint64_t)L->n[l] + K - 1) / K * K;
+    L->stride[l] = (uint32_t)round_up(padded, 64);
+    L->level_off[l] = off;
+    off = round_up(off + (size_t)L->stride[l] * T * 4, kAlign);
+  }
+  L->owner_stride = (uint32_t)round_up(c->capacity, 64);
+  L->owner_off = off;
+  off = round_up(off + (size_t)L->owner_stride * T * 4, kAlign);
+  L->tree_end = off;
+  for (uint32_t f = 0; f < c->n_fields; ++f) {
+    L->col_stride[f] = round_up((size_t)c->capacity * c->field_bytes[f], kAlign);
+    L->col_off[f] = off;
+    off += (size_t)L->col_stride[f] * T;
+  }
+  L->total = round_up(off, kAlign);
+}
+
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+// widest power-of-two access (<= 16 bytes) that divides the row size and the pointer
+uint32_t vec_width(uint32_t bytes, const void* io) {
+  uint32_t v = 16;
+  while (v > 1 && (bytes % v != 0 || misaligned(io, v))) v >>= 1;
+  return v;
+}
+
+int fill_fields(per_t* p, void* const* io, FieldTable* ft) {
+  memset(ft, 0, sizeof(*ft));
+  ft->n_fields = p->cfg.n_fields;
+  bool any = false;
+  for (uint32_t f = 0; f < ft->n_fields; ++f) {
+    ft->col[f] = p->col[f];
+    ft->col_stride[f] = p->col_stride[f];
+    ft->bytes[f] = p->cfg.field_bytes[f];
+    ft->io[f] = io ? static_cast<uint8_t*>(io[f]) : nullptr;
+    ft->vec[f] = vec_width(ft->bytes[f], ft->io[f]);
+    any = any || ft->io[f] != nullptr;
+  }
+  return any ? 1 : 0;
+}
+
+int hip_rc(hipError_t e) { return e == hipSuccess ? PER_OK : PER_EHIP; }
+
+}  // namespace
+
+extern "C" {
+
+int per_arena_bytes(const per_config* cfg, size_t* bytes, size_t* align) {
+  int rc = check_config(cfg);
+  if (rc != PER_OK) return rc;
+  if (!bytes) return PER_EINVAL;
+  Layout L;
+  make_layout(cfg, &L);
+  *bytes = L.total;
+  if (align) *align = kAlign;
+  return PER_OK;
+}
+
+int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* stream, per_t** out) {
+  int rc = check_config(cfg);
+  if (rc != PER_OK) return rc;
+  if (!out || !d_arena || misaligned(d_arena, kAlign)) return PER_EINVAL;
+  Layout L;
+  make_layout(cfg, &L);
+  if (arena_bytes < L.total) return PER_ENOMEM;
+
+  per_t* p = new (std::nothrow) per_buffer();
+  if (!p) return PER_ENOMEM;
+  memset(p, 0, sizeof(*p));
+  p->cfg = *cfg;
+  p->arena = static_cast<uint8_t*>(d_arena);
+  p->arena_bytes = arena_bytes;
+  Geom& g = p->g;
+  g.K = cfg->fanout;
+  g.logK = L.logK;
+  g.H = L.H;
+  g.T = cfg->n_trees;
+  g.N = (uint32_t)cfg->capacity;
+  for (uint32_t l = 0; l <= L.H; ++l) {
+    g.n[l] = L.n[l];
+    g.stride[l] = L.stride[l];
+    g.level[l] = reinterpret_cast<float*>(p->arena + L.level_off[l]);
+  }
+  g.owner = reinterpret_cast<uint32_t*>(p->arena + L.owner_off);
+  g.owner_stride = L.owner_stride;
+  g.max_v = reinterpret_cast<float*>(p->arena + L.scalars_off);
+  g.status = reinterpret_cast<uint32_t*>(g.max_v + g.T);
+  g.vmin = g.status + g.T;
+  for (uint32_t f = 0; f < cfg->n_fields; ++f) {
+    p->col[f] = p->arena + L.col_off[f];
+    p->col_stride[f] = L.col_stride[f];
+  }
+  p->tn.lds_budget_bytes = 64 * 1024;
+  p->tn.sample_block = 256;
+  p->tn.update_block = 256;
+  p->tn.gather_block = 256;
+  p->stamp_next = 1;
+  if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // zero everything (tree levels, stamps and payload), then the scalars
+  hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(p->arena), L.total / 4, 0u, s);
+  if (e == hipSuccess) e = launch_init_scalars(g, cfg->init_max_priority, s);
+  if (e != hipSuccess) { delete p; return PER_EHIP; }
+  *out = p;
+  return PER_OK;
+}
+
+int per_destroy(per_t* p) {
+  if (!p) return PER_EINVAL;
+  delete p;
+  return PER_OK;
+}
+
+int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_prio, uint32_t* d_out_idx,
+               void* stream) {
+  if (!p) return PER_EINVAL;
+  if (n > p->cfg.capacity) return PER_ERANGE;
+  if (misaligned(d_prio, 4) || misaligned(d_out_idx, 4)) return PER_EINVAL;
+  if (n == 0) return PER_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint64_t N = p->cfg.capacity;
+  const uint32_t cursor = (uint32_t)p->cursor;
+  FieldTable ft;
+  hipError_t e = hipSuccess;
+  if (fill_fields(p, const_cast<void* const*>(reinterpret_cast<const void* const*>(d_field_src)), &ft))
+    e = launch_scatter(p->g, p->tn, ft, n, cursor, s);
+  if (e == hipSuccess) e = launch_insert_leaves(p->g, p->tn, n, cursor, d_prio, d_out_idx, s);
+  if (e == hipSuccess) {
+    Range2 r;
+    const uint64_t end = p->cursor + n;
+    r.a0 = cursor;
+    r.b0 = (uint32_t)(end < N ? end : N);
+    r.a1 = 0;
+    r.b1 = (uint32_t)(end > N ? end - N : 0);
+    e = launch_resum_ranges(p->g, p->tn, r, s);
+  }
+  // the mirrors advance even if a later launch failed: rows already enqueued have been placed
+  p->cursor = (p->cursor + n) % N;
+  p->size = p->size + n > N ? N : p->size + n;
+  return hip_rc(e);
+}
+
+int per_sample(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
+               float* d_out_prio, void* stream) {
+  if (!p) return PER_EINVAL;
+  if (B == 0) return PER_OK;
+  if (!d_u || !d_out_idx || misaligned(d_u, 4) || misaligned(d_out_idx, 4) || misaligned(d_out_weight, 4) ||
+      misaligned(d_out_prio, 4))
+    return PER_EINVAL;
+  if (!isfinite(beta) || beta < 0.0f) return PER_EINVAL;
+  if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
+  if (p->size == 0) return PER_EEMPTY;
+  const uint32_t parity = p->weight_calls & 1u;
+  if (d_out_weight) p->weight_calls++;
+  return hip_rc(launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, d_out_idx, d_out_weight, d_out_prio,
+                              parity, static_cast<hipStream_t>(stream)));
+}
+
+int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field_dst, void* stream) {
+  if (!p) return PER_EINVAL;
+  if (B == 0) return PER_OK;
+  if (!d_idx || misaligned(d_idx, 4) || !d_field_dst) return PER_EINVAL;
+  FieldTable ft;
+  if (!fill_fields(p, d_field_dst, &ft)) return PER_OK;
+  return hip_rc(launch_gather(p->g, p->tn, ft, B, d_idx, static_cast<hipStream_t>(stream)));
+}
+
+int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio, void* stream) {
+  if (!p) return PER_EINVAL;
+  if (B == 0) return PER_OK;
+  if (!d_idx || !d_prio || misaligned(d_idx, 4) || misaligned(d_prio, 4)) return PER_EINVAL;
+  if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p->stamp_next + B > 0xFFFFFFFFull) {   // stamps exhausted: start over from a cleared array
+    hipError_t e = launch_fill_u32(p->g.owner, (uint64_t)p->g.owner_stride * p->g.T, 0u, s);
+    if (e != hipSuccess) return PER_EHIP;
+    p->stamp_next = 1;
+  }
+  const uint32_t base = (uint32_t)p->stamp_next;
+  p->stamp_next += B;
+  return hip_rc(launch_update(p->g, p->tn, B, (uint32_t)p->size, d_idx, d_prio, base, s));
+}
+
+int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream) {
+  if (!p) return PER_EINVAL;
+  if (n == 0) return PER_OK;
+  if (!d_idx || !d_out || misaligned(d_idx, 4) || misaligned(d_out, 4)) return PER_EINVAL;
+  return hip_rc(launch_get_priority(p->g, n, d_idx, d_out, static_cast<hipStream_t>(stream)));
+}
+
+int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint64_t* count, void* stream) {
+  if (!p) return PER_EINVAL;
+  if (tree >= p->g.T || height > p->g.H) return PER_ERANGE;
+  if (count) *count = p->g.n[height];
+  if (!d_out) return PER_OK;
+  if (misaligned(d_out, 4)) return PER_EINVAL;
+  const float* src = p->g.level[height] + (size_t)tree * p->g.stride[height];
+  return hip_rc(hipMemcpyAsync(d_out, src, (size_t)p->g.n[height] * 4, hipMemcpyDeviceToDevice,
+                               static_cast<hipStream_t>(stream)));
+}
+
+int per_total(per_t* p, float* d_out, void* stream) {
+  if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
+  return hip_rc(launch_read_scalars(p->g, 0, d_out, static_cast<hipStream_t>(stream)));
+}
+
+int per_max_priority(per_t* p, float* d_out, void* stream) {
+  if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
+  return hip_rc(launch_read_scalars(p->g, 1, d_out, static_cast<hipStream_t>(stream)));
+}
+
+int per_status(per_t* p, void* stream, uint32_t* flags) {
+  if (!p || !flags) return PER_EINVAL;
+  if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return PER_EHIP;
+  uint32_t acc = 0;
+  uint32_t buf[256];
+  for (uint32_t t0 = 0; t0 < p->g.T; t0 += 256) {
+    const uint32_t m = p->g.T - t0 < 256 ? p->g.T - t0 : 256;
+    if (hipMemcpy(buf, p->g.status + t0, m * 4, hipMemcpyDeviceToHost) != hipSuccess) return PER_EHIP;
+    for (uint32_t i = 0; i < m; ++i) acc |= buf[i];
+  }
+  *flags = acc;
+  return PER_OK;
+}
+
+int per_clear_status(per_t* p, void* stream) {
+  if (!p) return PER_EINVAL;
+  return hip_rc(launch_clear_status(p->g, static_cast<hipStream_t>(stream)));
+}
+
+uint32_t per_height(const per_t* p) { return p ? p->g.H : 0; }
+uint64_t per_size(const per_t* p) { return p ? p->size : 0; }
+uint64_t per_cursor(const per_t* p) { return p ? p->cursor : 0; }
+
+int per_set_tuning(per_t* p, const char* name, int64_t value) {
+  if (!p || !name) return PER_EINVAL;
+  if (!strcmp(name, "lds_budget_bytes")) {
+    if (value < 0 || value > 160 * 1024) return PER_EINVAL;
+    p->tn.lds_budget_bytes = (uint32_t)value;
+    return PER_OK;
+  }
+  uint32_t* blk = !strcmp(name, "sample_block") ? &p->tn.sample_block
+                : !strcmp(name, "update_block") ? &p->tn.update_block
+                : !strcmp(name, "gather_block") ? &p->tn.gather_block : nullptr;
+  if (!blk) return PER_EINVAL;
+  if (value < 64 || value > 1024 || value % 64) return PER_EINVAL;
+  *blk = (uint32_t)value;
+  return PER_OK;
+}
+
+const char* per_strerror(int code) {
+  switch (code) {
+    case PER_OK: return "ok";
+    case PER_EINVAL: return "invalid argument";
+    case PER_ENOMEM: return "arena too small";
+    case PER_EEMPTY: return "buffer holds no rows";
+    case PER_ERANGE: return "size out of range";
+    case PER_EHIP: return "HIP call or kernel launch failed";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,64 @@
+// Internal: tree geometry shared by the C-ABI layer and the kernels.
+//
+// Height h counts from the leaves: n[0] = N, n[h+1] = ceil(n[h] / K), root at
+// height H.  Each stored level is zero-padded to a multiple of K so every child
+// group is K wide ("a parent node stores the sum of priorities of its
+// children", Section V-A); one array per level, as in the paper's FPGA design
+// where every pipeline stage owns one tree level.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace per {
+
+constexpr int kMaxHeight = 32;   // K = 2, N = 2^31 gives H = 31
+constexpr int kMaxFields = 8;
+
+struct Geom {
+  uint32_t K, logK, H, T;
+  uint32_t N;                       // leaves per tree (<= 2^31)
+  uint32_t n[kMaxHeight + 1];       // real nodes per level
+  uint32_t stride[kMaxHeight + 1];  // floats between consecutive trees of a level (multiple of 64)
+  float*   level[kMaxHeight + 1];   // level h of tree 0
+  uint32_t* owner;                  // [T][owner_stride] last-writer stamps
+  uint32_t owner_stride;
+  float*    max_v;                  // [T] running max priority
+  uint32_t* status;                 // [T] sticky flags
+  uint32_t* vmin;                   // [2][T] batch minimum of sampled values (fp32 bits), double-buffered
+};
+
+struct FieldTable {
+  uint8_t* col[kMaxFields];         // column f of tree 0
+  uint8_t* io[kMaxFields];          // caller's dense [T][B][bytes] array (source or destination)
+  uint64_t col_stride[kMaxFields];  // bytes between trees of a column
+  uint32_t bytes[kMaxFields];       // bytes per row
+  uint32_t vec[kMaxFields];         // bytes moved per lane: 16, 8, 4, 2 or 1
+  uint32_t n_fields;
+};
+
+struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b0) u [a1,b1)
+
+struct Tuning {
+  uint32_t lds_budget_bytes;
+  uint32_t sample_block, update_block, gather_block;
+};
+
+// Launchers (per_kernels.hip).  All enqueue on `s` and return hipGetLastError().
+hipError_t launch_fill_u32(uint32_t* p, uint64_t count, uint32_t value, hipStream_t s);
+hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
+hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
+                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t parity, hipStream_t s);
+hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
+                         hipStream_t s);
+hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t n, uint32_t cursor,
+                          hipStream_t s);
+hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uint32_t cursor, const float* prio,
+                                uint32_t* out_idx, hipStream_t s);
+hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipStream_t s);
+hipError_t launch_update(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
+                         const float* prio, uint32_t stamp_base, hipStream_t s);
+hipError_t launch_get_priority(const Geom& g, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
+hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s);
+hipError_t launch_clear_status(const Geom& g, hipStream_t s);
+
+}  // namespace per

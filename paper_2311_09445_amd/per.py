@@ -1,0 +1,280 @@
+"""Thin ctypes binding of ``libper_hip.so`` (the C-ABI declared in ``include/per.h``).
+
+Argument marshalling only: every step runs in the library's HIP kernels.  PyTorch
+supplies device memory (the arena and the I/O arrays are torch tensors) and the
+stream.  There is no CPU fallback: if the library has not been built, loading
+fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libper_hip.so")
+MAX_FIELDS = 8
+
+OK, EINVAL, ENOMEM, EEMPTY, ERANGE, EHIP = 0, -1, -2, -3, -4, -5
+FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
+
+EXPORTS = [
+    "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_gather",
+    "per_update", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
+    "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_tuning",
+    "per_strerror",
+]
+
+
+class PerConfig(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("fanout", C.c_uint32),
+        ("capacity", C.c_uint64),
+        ("n_trees", C.c_uint32),
+        ("n_fields", C.c_uint32),
+        ("field_bytes", C.c_uint32 * MAX_FIELDS),
+        ("init_max_priority", C.c_float),
+    ]
+
+
+class PerError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {code} ({_lib().per_strerror(code).decode()})")
+
+
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2311_09445_amd.build` "
+            "(hipcc, gfx950). There is no CPU fallback.")
+    lib = C.CDLL(LIB_PATH)
+    vp, u32, u64, i64, f32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int64, C.c_float
+    cfgp = C.POINTER(PerConfig)
+    sig = {
+        "per_arena_bytes": (C.c_int, [cfgp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+        "per_create": (C.c_int, [cfgp, vp, C.c_size_t, vp, C.POINTER(vp)]),
+        "per_destroy": (C.c_int, [vp]),
+        "per_insert": (C.c_int, [vp, u32, vp, vp, vp, vp]),
+        "per_sample": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp]),
+        "per_gather": (C.c_int, [vp, u32, vp, vp, vp]),
+        "per_update": (C.c_int, [vp, u32, vp, vp, vp]),
+        "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
+        "per_read_level": (C.c_int, [vp, u32, u32, vp, C.POINTER(u64), vp]),
+        "per_total": (C.c_int, [vp, vp, vp]),
+        "per_max_priority": (C.c_int, [vp, vp, vp]),
+        "per_status": (C.c_int, [vp, vp, C.POINTER(u32)]),
+        "per_clear_status": (C.c_int, [vp, vp]),
+        "per_height": (u32, [vp]),
+        "per_size": (u64, [vp]),
+        "per_cursor": (u64, [vp]),
+        "per_set_tuning": (C.c_int, [vp, C.c_char_p, i64]),
+        "per_strerror": (C.c_char_p, [C.c_int]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _LIB = lib
+    return lib
+
+
+def make_config(fanout: int, capacity: int, n_trees: int = 1, field_bytes: Sequence[int] = (),
+                init_max_priority: float = 1.0) -> PerConfig:
+    cfg = PerConfig()
+    cfg.struct_size = C.sizeof(PerConfig)
+    cfg.fanout = fanout
+    cfg.capacity = capacity
+    cfg.n_trees = n_trees
+    cfg.n_fields = len(field_bytes)
+    for i, b in enumerate(field_bytes[:MAX_FIELDS]):
+        cfg.field_bytes[i] = b
+    cfg.init_max_priority = init_max_priority
+    return cfg
+
+
+def arena_bytes(cfg: PerConfig):
+    nbytes, align = C.c_size_t(0), C.c_size_t(0)
+    rc = _lib().per_arena_bytes(C.byref(cfg), C.byref(nbytes), C.byref(align))
+    if rc != OK:
+        raise PerError(rc, "per_arena_bytes")
+    return nbytes.value, align.value
+
+
+def _dptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+class PrioritizedReplay:
+    """T prioritized replay buffers of capacity N with fanout K on the current device.
+
+    Mirrors the paper's library interface ``PER(size=..., fanout=...)`` (Listing 2).
+    All array arguments are contiguous device tensors shaped [T, ...] (a leading
+    dimension of size T may be omitted when T == 1).
+    """
+
+    def __init__(self, fanout: int, capacity: int, n_trees: int = 1, field_bytes: Sequence[int] = (),
+                 init_max_priority: float = 1.0, device="cuda"):
+        import torch
+        self._torch = torch
+        self.lib = _lib()
+        self.K, self.N, self.T = int(fanout), int(capacity), int(n_trees)
+        self.field_bytes = tuple(int(b) for b in field_bytes)
+        if len(self.field_bytes) > MAX_FIELDS:
+            raise PerError(EINVAL, "per_create")
+        self.cfg = make_config(self.K, self.N, self.T, self.field_bytes, init_max_priority)
+        nbytes, _ = arena_bytes(self.cfg)
+        self.device = torch.device(device)
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        h = C.c_void_p()
+        rc = self.lib.per_create(C.byref(self.cfg), C.c_void_p(self.arena.data_ptr()), nbytes,
+                                 self._stream(), C.byref(h))
+        if rc != OK:
+            raise PerError(rc, "per_create")
+        self._h = h
+        self.H = self.lib.per_height(self._h)
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h:
+            self.lib.per_destroy(h)
+            self._h = None
+
+    def _stream(self):
+        return C.c_void_p(self._torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _check(self, rc, what):
+        if rc != OK:
+            raise PerError(rc, what)
+
+    def _ptr_array(self, tensors, n_rows):
+        if tensors is None:
+            return None, None
+        if len(tensors) != len(self.field_bytes):
+            raise ValueError("one tensor (or None) per payload field is required")
+        arr = (C.c_void_p * max(1, len(tensors)))()
+        for f, t in enumerate(tensors):
+            if t is None:
+                arr[f] = None
+                continue
+            if t.numel() * t.element_size() != self.T * n_rows * self.field_bytes[f]:
+                raise ValueError(f"field {f}: expected {self.T}x{n_rows}x{self.field_bytes[f]} bytes")
+            arr[f] = _dptr(t).value
+        return arr, C.cast(arr, C.c_void_p)
+
+    # ---------------------------------------------------------------- operations
+    def insert(self, n: int, rows=None, prio=None, out_idx=None):
+        torch = self._torch
+        _keep, src = self._ptr_array(rows, n)
+        if prio is not None and prio.numel() != self.T * n:
+            raise ValueError("prio must hold T*n values")
+        if out_idx is not None and out_idx.numel() != self.T * n:
+            raise ValueError("out_idx must hold T*n values")
+        rc = self.lib.per_insert(self._h, n, src, _dptr(prio, torch.float32), _dptr(out_idx, torch.int32),
+                                 self._stream())
+        self._check(rc, "per_insert")
+
+    def sample(self, u, beta: float = 0.4, want_weights: bool = True, want_prio: bool = True,
+               out_idx=None, out_weight=None, out_prio=None):
+        """Returns (idx int32 [T,B] holding uint32 bit patterns, weights or None, prio or None)."""
+        torch = self._torch
+        B = u.numel() // self.T
+        if u.numel() != B * self.T:
+            raise ValueError("u must hold T*B values")
+        shape = (self.T, B)
+        if out_idx is None:
+            out_idx = torch.empty(shape, dtype=torch.int32, device=self.device)
+        if want_weights and out_weight is None:
+            out_weight = torch.empty(shape, dtype=torch.float32, device=self.device)
+        if want_prio and out_prio is None:
+            out_prio = torch.empty(shape, dtype=torch.float32, device=self.device)
+        rc = self.lib.per_sample(self._h, B, float(beta), _dptr(u, torch.float32), _dptr(out_idx, torch.int32),
+                                 _dptr(out_weight, torch.float32) if want_weights else None,
+                                 _dptr(out_prio, torch.float32) if want_prio else None, self._stream())
+        self._check(rc, "per_sample")
+        return out_idx, (out_weight if want_weights else None), (out_prio if want_prio else None)
+
+    def gather(self, idx, out=None):
+        torch = self._torch
+        B = idx.numel() // self.T
+        if out is None:
+            out = [torch.empty((self.T, B, b), dtype=torch.uint8, device=self.device) for b in self.field_bytes]
+        _keep, dst = self._ptr_array(out, B)
+        rc = self.lib.per_gather(self._h, B, _dptr(idx, torch.int32), dst, self._stream())
+        self._check(rc, "per_gather")
+        return out
+
+    def update(self, idx, prio):
+        torch = self._torch
+        B = idx.numel() // self.T
+        if prio.numel() != idx.numel():
+            raise ValueError("idx and prio must have the same number of elements")
+        rc = self.lib.per_update(self._h, B, _dptr(idx, torch.int32), _dptr(prio, torch.float32), self._stream())
+        self._check(rc, "per_update")
+
+    def get_priority(self, idx, out=None):
+        torch = self._torch
+        n = idx.numel() // self.T
+        if out is None:
+            out = torch.empty((self.T, n), dtype=torch.float32, device=self.device)
+        rc = self.lib.per_get_priority(self._h, n, _dptr(idx, torch.int32), _dptr(out, torch.float32),
+                                       self._stream())
+        self._check(rc, "per_get_priority")
+        return out
+
+    # ---------------------------------------------------------------- inspection
+    def level_count(self, height: int) -> int:
+        cnt = C.c_uint64(0)
+        self._check(self.lib.per_read_level(self._h, 0, height, None, C.byref(cnt), self._stream()),
+                    "per_read_level")
+        return cnt.value
+
+    def read_level(self, tree: int, height: int):
+        torch = self._torch
+        out = torch.empty(self.level_count(height), dtype=torch.float32, device=self.device)
+        cnt = C.c_uint64(0)
+        self._check(self.lib.per_read_level(self._h, tree, height, _dptr(out), C.byref(cnt), self._stream()),
+                    "per_read_level")
+        return out
+
+    def total(self):
+        out = self._torch.empty(self.T, dtype=self._torch.float32, device=self.device)
+        self._check(self.lib.per_total(self._h, _dptr(out), self._stream()), "per_total")
+        return out
+
+    def max_priority(self):
+        out = self._torch.empty(self.T, dtype=self._torch.float32, device=self.device)
+        self._check(self.lib.per_max_priority(self._h, _dptr(out), self._stream()), "per_max_priority")
+        return out
+
+    def status(self) -> int:
+        flags = C.c_uint32(0)
+        self._check(self.lib.per_status(self._h, self._stream(), C.byref(flags)), "per_status")
+        return flags.value
+
+    def clear_status(self):
+        self._check(self.lib.per_clear_status(self._h, self._stream()), "per_clear_status")
+
+    @property
+    def size(self) -> int:
+        return int(self.lib.per_size(self._h))
+
+    @property
+    def cursor(self) -> int:
+        return int(self.lib.per_cursor(self._h))
+
+    def set_tuning(self, name: str, value: int):
+        self._check(self.lib.per_set_tuning(self._h, name.encode(), int(value)), "per_set_tuning")

@@ -20,7 +20,7 @@ import numpy as np
 
 __all__ = [
     "Workload", "WORKLOADS", "uniform01", "initial_priorities", "step_inputs",
-    "row_bytes", "row_bytes_torch", "td_to_priority",
+    "row_bytes", "row_bytes_torch", "td_to_priority", "apply_dup_map",
 ]
 
 

@@ -1,0 +1,129 @@
+"""Test-side driver that applies the same calls to the HIP library and to the CPU oracle
+and compares what comes back: indices, leaf values and tree nodes bit for bit, gathered
+rows byte for byte, importance weights within 1e-6 relative."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle.per_oracle import MultiOracle
+from paper_2311_09445_amd import workloads as wl
+from paper_2311_09445_amd.per import PrioritizedReplay
+
+WEIGHT_RTOL = 1e-6   # stated in the build's target: weights within 1e-6 relative
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def idx_to_dev(idx_u32: np.ndarray):
+    return dev(np.ascontiguousarray(idx_u32, dtype=np.uint32).view(np.int32))
+
+
+def idx_to_host(t) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+class Mirror:
+    """One HIP buffer set and one oracle set driven in lockstep."""
+
+    def __init__(self, K, N, T=1, field_bytes=(), init_max=1.0, oracle_payload=True):
+        self.K, self.N, self.T = K, N, T
+        self.fb = tuple(field_bytes)
+        self.gpu = PrioritizedReplay(K, N, T, self.fb, init_max)
+        self.cpu = MultiOracle(T, K, N, self.fb, init_max, with_payload=oracle_payload)
+        self.oracle_payload = oracle_payload
+        self.counter = 0                                   # rows inserted so far per tree
+        self.holder = np.full((T, N), -1, dtype=np.int64)  # slot -> insert counter of the row it holds
+        assert self.gpu.H == self.cpu.H
+
+    # ---------------------------------------------------------------- operations
+    def insert(self, n, prio=None, with_rows=True, chunk=None):
+        """Insert n rows per tree (row bytes = hash of tree / insert counter / field / offset)."""
+        chunk = n if chunk is None else chunk
+        done = 0
+        while done < n:
+            m = min(chunk, n - done)
+            counters = np.arange(self.counter, self.counter + m)
+            p = None if prio is None else np.ascontiguousarray(prio[:, done:done + m], dtype=np.float32)
+            g_rows = c_rows = None
+            if with_rows and self.fb:
+                cd = dev(counters)
+                g_rows = [torch.stack([wl.row_bytes_torch(t, cd, f, b) for t in range(self.T)])
+                          for f, b in enumerate(self.fb)]
+                if self.oracle_payload:
+                    c_rows = [np.stack([wl.row_bytes(t, counters, f, b) for t in range(self.T)])
+                              for f, b in enumerate(self.fb)]
+            out = torch.empty((self.T, m), dtype=torch.int32, device="cuda")
+            self.gpu.insert(m, g_rows, None if p is None else dev(p), out)
+            slots = self.cpu.insert(m, c_rows, p)
+            assert np.array_equal(idx_to_host(out), slots), "insert slots"
+            if with_rows:
+                for t in range(self.T):
+                    self.holder[t, slots[t]] = counters
+            self.counter += m
+            done += m
+
+    def sample(self, u, beta=0.4, want_weights=True):
+        gi, gw, gv = self.gpu.sample(dev(u), beta, want_weights=want_weights, want_prio=True)
+        ci, cw, cv = self.cpu.sample(u, beta, want_weights)
+        gi_h = idx_to_host(gi)
+        assert np.array_equal(gi_h, ci), f"sampled indices differ at {np.argwhere(gi_h != ci)[:5]}"
+        assert gv.cpu().numpy().tobytes() == cv.tobytes(), "sampled leaf values"
+        if want_weights:
+            np.testing.assert_allclose(gw.cpu().numpy(), cw, rtol=WEIGHT_RTOL, atol=0)
+        return gi, ci
+
+    def gather(self, idx_dev, idx_host):
+        got = [g.cpu().numpy() for g in self.gpu.gather(idx_dev)]
+        if self.oracle_payload:
+            want = self.cpu.gather(idx_host)
+        else:   # expected bytes straight from the row hash of the counter each slot holds
+            want = []
+            for f, b in enumerate(self.fb):
+                per_tree = []
+                for t in range(self.T):
+                    ok = idx_host[t] < self.N
+                    cnt = np.where(ok, self.holder[t, np.where(ok, idx_host[t], 0)], -1)
+                    rows = wl.row_bytes(t, np.where(cnt >= 0, cnt, 0), f, b)
+                    rows[cnt < 0] = 0
+                    per_tree.append(rows)
+                want.append(np.stack(per_tree))
+        for f in range(len(self.fb)):
+            assert np.array_equal(got[f].reshape(want[f].shape), want[f]), f"gathered field {f}"
+
+    def update(self, idx_host, prio):
+        self.gpu.update(idx_to_dev(idx_host), dev(prio))
+        self.cpu.update(np.ascontiguousarray(idx_host, dtype=np.uint32), prio)
+
+    # ---------------------------------------------------------------- comparisons
+    def compare_tree(self, heights=None):
+        heights = range(self.gpu.H + 1) if heights is None else heights
+        for t in range(self.T):
+            for h in heights:
+                g = self.gpu.read_level(t, h).cpu().numpy()
+                c = self.cpu.read_level(t, h)
+                if g.tobytes() != c.tobytes():
+                    bad = np.argwhere(g.view(np.uint32) != c.view(np.uint32))[:5].ravel()
+                    raise AssertionError(f"tree {t} height {h}: nodes {bad} differ: {g[bad]} vs {c[bad]}")
+        assert self.gpu.total().cpu().numpy().tobytes() == self.cpu.total.tobytes(), "root"
+        mx = np.array([o.max_priority for o in self.cpu.trees], dtype=np.float32)
+        assert self.gpu.max_priority().cpu().numpy().tobytes() == mx.tobytes(), "running max priority"
+
+    def compare_status(self):
+        assert self.gpu.status() == self.cpu.status, (self.gpu.status(), self.cpu.status)
+
+    def step(self, w: wl.Workload, step: int, seed: int = 0, B=None, check_tree=True):
+        """One step in the order insert -> sample -> gather -> update (update targets the sampled rows)."""
+        inp = wl.step_inputs(w, step, seed, B)
+        if w.n_insert:
+            self.insert(w.n_insert)
+        gi, ci = self.sample(inp["u"], inp["beta"], w.weights)
+        self.gather(gi, ci)
+        self.update(wl.apply_dup_map(ci, inp), inp["upd_prio"])
+        if check_tree:
+            self.compare_tree()

@@ -1,0 +1,266 @@
+"""Parity of the HIP path (through the C-ABI) with the CPU oracle, element by element."""
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():   # collected everywhere, run only where a GPU is present
+    pytest.skip("needs a GPU", allow_module_level=True)
+
+from scipy import stats  # noqa: E402
+
+from paper_2311_09445_amd import workloads as wl  # noqa: E402
+from paper_2311_09445_amd.per import (EEMPTY, EINVAL, ERANGE, FLAG_BAD_INDEX, FLAG_BAD_PRIORITY,  # noqa: E402
+                                      FLAG_ZERO_TOTAL, PerError, PrioritizedReplay)
+from tests.harness import Mirror, dev, idx_to_dev, idx_to_host  # noqa: E402
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+FIELDS = (16, 4, 4, 16, 1)
+
+
+def log(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ small, every fanout
+@pytest.mark.parametrize("K", [2, 4, 8, 16, 32, 64])
+@pytest.mark.parametrize("N,T", [(1, 1), (5, 2), (1000, 1), (4097, 3), (70000, 1)])
+def test_random_operation_mix(K, N, T):
+    """Several tiles and a ragged tail: inserts (explicit and max priority, with wrap), samples with
+    batch sizes that are not powers of two, gathers, updates with duplicates and invalid elements."""
+    log(f"mix K={K} N={N} T={T}")
+    rng = np.random.default_rng(K * 1000003 + N * 7 + T)
+    m = Mirror(K, N, T, FIELDS)
+    first = max(1, (2 * N) // 3)
+    m.insert(first, prio=wl._draw_priorities("lognormal_0_1", rng, (T, first)))
+    m.compare_tree()
+    for it in range(4):
+        B = int(rng.choice([1, 3, 64, 257, 1500]))
+        u = wl.uniform01(rng, (T, B))
+        gi, ci = m.sample(u, beta=float(rng.choice([0.0, 0.4, 1.0])))
+        m.gather(gi, ci)
+        upd_idx = ci.copy()
+        upd_prio = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B))
+        if B > 4:   # duplicates, an out-of-range index and invalid values
+            upd_idx[:, B // 2:] = upd_idx[:, : B - B // 2]
+            upd_idx[:, 0] = m.N + 5
+            upd_prio[:, 1] = np.nan
+            upd_prio[:, 2] = -1.0
+            upd_prio[:, 3] = np.inf
+        m.update(upd_idx, upd_prio)
+        m.compare_tree()
+        n_ins = int(rng.integers(1, max(2, N // 2)))
+        m.insert(n_ins, prio=None if it % 2 == 0 else wl._draw_priorities("exponential_1", rng, (T, n_ins)))
+        m.compare_tree()
+    m.compare_status()
+
+
+def test_golden_worked_example_on_gpu():
+    g = {}
+    with open(os.path.join(GOLDEN, "eq1_worked_example.txt")) as f:
+        for line in f:
+            if not line.startswith("#") and line.strip():
+                k, *v = line.split()
+                g[k] = [float(x) for x in v]
+    for K in (2, 4, 8):
+        p = PrioritizedReplay(K, 8)
+        p.insert(8, None, dev(np.array([g["leaves"]], np.float32)))
+        idx, w, v = p.sample(dev(np.array([g["u"]], np.float32)), beta=g["beta"][0])
+        assert idx_to_host(idx)[0].tolist() == [int(x) for x in g["idx"]]
+        assert v.cpu().numpy()[0].tolist() == g["prio"]
+        np.testing.assert_allclose(w.cpu().numpy()[0], g["weight"], rtol=1e-6)
+        h = 1
+        while f"k{K}_h{h}" in g:
+            assert p.read_level(0, h).cpu().numpy().tolist() == g[f"k{K}_h{h}"]
+            h += 1
+
+
+# ------------------------------------------------------------------ last writer
+@pytest.mark.parametrize("K", [2, 16, 32])
+def test_last_writer_adversarial(K):
+    log(f"last writer K={K}")
+    rng = np.random.default_rng(K)
+    N, T = 5000, 2
+    m = Mirror(K, N, T, ())
+    m.insert(N, prio=np.ones((T, N), np.float32), with_rows=False)
+    B = 3000                                            # spans many workgroups
+    cases = [
+        np.full((T, B), 77, np.uint32),                 # every element hits one leaf
+        np.tile(np.array([3, 4000], np.uint32), (T, B // 2)),      # two leaves alternating
+        np.repeat(np.arange(B // 250, dtype=np.uint32), 250)[None].repeat(T, 0),  # runs straddling blocks
+        rng.integers(0, 64, (T, B)).astype(np.uint32),  # heavy random duplication
+        rng.integers(0, N, (T, B)).astype(np.uint32),
+    ]
+    for idx in cases:
+        m.update(idx, rng.random((T, B)).astype(np.float32))
+        m.compare_tree()
+    m.compare_status()
+
+
+def test_determinism_same_state_same_bits():
+    rng = np.random.default_rng(0)
+    N, B = 100000, 4096
+    leaves = wl._draw_priorities("pareto_1.5", rng, (1, N))
+    u = wl.uniform01(rng, (1, B))
+    idx = rng.integers(0, N, (1, B)).astype(np.uint32)
+    pr = rng.random((1, B)).astype(np.float32)
+    outs = []
+    for rep in range(2):
+        p = PrioritizedReplay(16, N)
+        p.insert(N, None, dev(leaves))
+        p.update(idx_to_dev(idx), dev(pr))
+        i, w, v = p.sample(dev(u), 0.4)
+        outs.append([i.cpu().numpy().tobytes(), w.cpu().numpy().tobytes(), v.cpu().numpy().tobytes()] +
+                    [p.read_level(0, h).cpu().numpy().tobytes() for h in range(p.H + 1)])
+    assert outs[0] == outs[1]
+
+
+# ------------------------------------------------------------------ edge cases
+def test_denormals_and_negative_zero_on_gpu():
+    tiny = np.float32(1e-42)
+    leaves = np.array([[0.0, -0.0, tiny, 0.0, tiny, -0.0, tiny, tiny]], np.float32)
+    for K in (2, 4, 8):
+        m = Mirror(K, 8, 1, ())
+        m.insert(8, prio=leaves, with_rows=False)
+        m.compare_tree()
+        gi, ci = m.sample(np.array([[0.0, 0.5, 0.5, 0.99]], np.float32))
+        assert ci[0].tolist() == [2, 4, 6, 7]
+        m.compare_status()
+
+
+def test_zero_total_empty_and_error_codes():
+    p = PrioritizedReplay(4, 100, 2, (8,))
+    u = dev(np.zeros((2, 16), np.float32))
+    with pytest.raises(PerError) as e:
+        p.sample(u)
+    assert e.value.code == EEMPTY
+    p.insert(10, None, dev(np.zeros((2, 10), np.float32)))     # rows present, all priorities zero
+    idx, w, v = p.sample(u)
+    assert np.all(idx_to_host(idx) == 0xFFFFFFFF) and np.all(w.cpu().numpy() == 0) and np.all(v.cpu().numpy() == 0)
+    assert p.status() == FLAG_ZERO_TOTAL
+    rows = p.gather(idx)                                        # sentinel indices gather zeros
+    assert np.all(rows[0].cpu().numpy() == 0) and p.status() == FLAG_ZERO_TOTAL | FLAG_BAD_INDEX
+    p.clear_status()
+    assert p.status() == 0
+    with pytest.raises(PerError) as e:
+        p.insert(101)
+    assert e.value.code == ERANGE
+    with pytest.raises(PerError) as e:
+        p.sample(u, beta=-1.0)
+    assert e.value.code == EINVAL
+    # empty batches are valid and change nothing
+    p.update(torch.empty((2, 0), dtype=torch.int32, device="cuda"), torch.empty((2, 0), device="cuda"))
+    p.insert(0)
+    assert p.size == 10 and p.cursor == 10
+    for bad in [dict(fanout=3), dict(fanout=128), dict(capacity=0), dict(n_trees=0), dict(init_max_priority=0.0)]:
+        kw = dict(fanout=4, capacity=10)
+        kw.update(bad)
+        with pytest.raises(PerError):
+            PrioritizedReplay(**kw)
+
+
+def test_priority_retrieval_and_flags():
+    m = Mirror(16, 300, 2, ())
+    rng = np.random.default_rng(1)
+    m.insert(200, prio=rng.random((2, 200)).astype(np.float32), with_rows=False)
+    idx = rng.integers(0, 300, (2, 64)).astype(np.uint32)
+    idx[:, 5] = 300
+    got = m.gpu.get_priority(idx_to_dev(idx)).cpu().numpy()
+    want = m.cpu.get_priority(idx)
+    assert got.tobytes() == want.tobytes()
+    m.compare_status()
+    assert m.gpu.status() == FLAG_BAD_INDEX
+
+
+@pytest.mark.parametrize("K", [16, 32])
+def test_results_do_not_depend_on_tuning(K):
+    rng = np.random.default_rng(3)
+    N, B = 1 << 16, 5000
+    leaves = wl._draw_priorities("pareto_1.5", rng, (1, N))
+    u = wl.uniform01(rng, (1, B))
+    ref = None
+    for lds, blk in [(0, 64), (4096, 256), (64 * 1024, 256), (96 * 1024, 1024), (160 * 1024, 512)]:
+        p = PrioritizedReplay(K, N)
+        p.set_tuning("lds_budget_bytes", lds)
+        for name in ("sample_block", "update_block", "gather_block"):
+            p.set_tuning(name, blk)
+        p.insert(N, None, dev(leaves))
+        i, w, v = p.sample(dev(u), 0.5)
+        p.update(i, dev(rng.random((1, B)).astype(np.float32) * 0 + 0.25))
+        out = [i.cpu().numpy().tobytes(), v.cpu().numpy().tobytes(), w.cpu().numpy().tobytes()] + \
+              [p.read_level(0, h).cpu().numpy().tobytes() for h in range(p.H + 1)]
+        if ref is None:
+            ref = out
+        assert out == ref, (lds, blk)
+
+
+def test_sampling_frequency_on_gpu():
+    rng = np.random.default_rng(12345)
+    N, B, steps = 256, 64, 2000
+    td = wl.td_to_priority(rng.standard_normal(N), 1e-6, 0.6)
+    p = PrioritizedReplay(16, N)
+    p.insert(N, None, dev(td[None]))
+    u = dev(wl.uniform01(rng, (steps, B)))
+    counts = np.zeros(N)
+    for s in range(steps):
+        idx, _, _ = p.sample(u[s:s + 1], want_weights=False, want_prio=False)
+        np.add.at(counts, idx_to_host(idx)[0], 1)
+    expect = B * steps * td.astype(np.float64) / td.astype(np.float64).sum()
+    assert float(((counts - expect) ** 2 / expect).sum()) < stats.chi2.ppf(0.9999, N - 1)
+
+
+# ------------------------------------------------------------------ whole workloads
+@pytest.mark.parametrize("name,steps,tree_every", [
+    ("c1_binary_small", 100, 1),
+    ("c2_dqn", 300, 25),
+    ("c3_ddpg", 60, 10),
+])
+def test_workload_parity(name, steps, tree_every):
+    w = wl.WORKLOADS[name]
+    log(f"workload {name}: {steps} steps")
+    m = Mirror(w.K, w.N, w.T, w.field_bytes)
+    m.insert(w.N, prio=wl.initial_priorities(w, 0), chunk=1 << 18)
+    m.compare_tree()
+    for s in range(steps):
+        m.step(w, s, check_tree=(s % tree_every == 0 or s == steps - 1))
+    m.compare_status()
+
+
+def test_workload_c5_many_trees():
+    w = wl.WORKLOADS["c5_multi"]
+    log("workload c5_multi")
+    m = Mirror(w.K, w.N, w.T, w.field_bytes, oracle_payload=False)
+    m.insert(w.N, prio=wl.initial_priorities(w, 0), chunk=1 << 16)
+    m.compare_tree(heights=range(1, m.gpu.H + 1))
+    for s in range(12):
+        m.step(w, s, check_tree=False)
+        if s % 4 == 3:
+            m.compare_tree(heights=range(1, m.gpu.H + 1))
+    m.compare_tree()
+    m.compare_status()
+
+
+def test_workload_c4_full_size():
+    """N = 2^24, B = 65536 in the launch configuration the bench times.  The oracle runs the full
+    descent and update; gathered rows are checked against the row hash of the slot they came from."""
+    w = wl.WORKLOADS["c4_stress"]
+    log("workload c4_stress (full size)")
+    m = Mirror(w.K, w.N, w.T, w.field_bytes, oracle_payload=False)
+    v0 = wl.initial_priorities(w, 0)
+    m.insert(w.N, prio=v0, chunk=1 << 20)
+    log("  filled")
+    m.compare_tree()
+    for s in range(4):
+        inp = wl.step_inputs(w, s, 0)
+        gi, ci = m.sample(inp["u"], inp["beta"], True)
+        leaves = m.cpu.read_level(0, 0)
+        assert np.all(leaves[ci[0]] > 0), "a zero-priority row was sampled"
+        m.gather(gi, ci)
+        m.update(wl.apply_dup_map(ci, inp), inp["upd_prio"])
+        m.compare_tree(heights=range(1, m.gpu.H + 1))
+        log(f"  step {s} ok")
+    m.compare_tree()
+    m.compare_status()
