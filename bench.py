@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Throughput of the prioritized-replay hot path on one MI355X.
+
+One step = priority sampling (with importance weights) -> row gather -> priority
+update over one batch of synthetic input, on the workload the headline metric is
+quoted on (N = 2^24 leaves, K = 32, B = 65536, 128-byte rows, 10 % duplicated
+update indices).  Prints ONE JSON line: transitions/s, the roofline figure of the
+dominant kernel (HIP-event timed inside this run) and the CPU oracle's rate on a
+bounded sample of the same steps.
+
+All inputs are resident in HBM before the timed region.  The update indices of
+step s are the indices sampled in step s with the workload's duplicate map
+applied; they are produced by an untimed recording pass from the same initial
+state (the arena is snapshotted and restored), so that the timed region contains
+only the library's own kernels.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c4_stress")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the oracle leg (0: skip)")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps eagerly instead of as one HIP graph")
+    ap.add_argument("--tune", action="append", default=[], help="name=value passed to per_set_tuning")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(w, idx, upd_idx, K, H, n_levels, h_lds, weights):
+    """Bytes the method itself must move in one step, each distinct K-group counted once per
+    phase (what a perfect cache would move).  idx / upd_idx: [T, B] uint32 of one step."""
+    logK = K.bit_length() - 1
+    T, B = idx.shape
+    E = w.row_bytes
+    a_sample = a_gather = a_update = 0
+    per_kernel = {}
+    for t in range(T):
+        i64 = idx[t].astype(np.int64)
+        g = 0
+        for h in range(0, min(h_lds, H)):          # groups at height h read from memory
+            g += len(np.unique(i64 >> ((h + 1) * logK))) * 4 * K
+        s = 4 * B + g + 4 * B + 4 * B + (4 * B if weights else 0)   # u, groups, idx, prio, (value for weights)
+        a_sample += s
+        R = len(np.unique(i64))
+        a_gather += 4 * B + E * R + E * B
+        u64 = upd_idx[t].astype(np.int64)
+        U = len(np.unique(u64))
+        a_update += 8 * B + 4 * U
+        for h in range(1, H + 1):
+            Q = len(np.unique(u64 >> (h * logK)))
+            a_update += 4 * K * Q + 4 * Q
+    per_kernel["k_sample"] = a_sample
+    per_kernel["k_rows_gather"] = a_gather
+    return a_sample, a_gather, a_update
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2311_09445_amd import workloads as wl
+    from paper_2311_09445_amd.per import PrioritizedReplay
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    K, N, T, B = w.K, w.N, w.T, w.B
+    steps, warmup = args.steps, args.warmup
+    total_steps = steps + warmup
+    t_setup = time.time()
+
+    # ---------------------------------------------------------------- state
+    buf = PrioritizedReplay(K, N, T, w.field_bytes)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        buf.set_tuning(k, int(v))
+    prio0 = wl.initial_priorities(w, args.seed)
+    chunk = 1 << 20
+    for lo in range(0, N, chunk):
+        m = min(chunk, N - lo)
+        cnt = torch.arange(lo, lo + m, device="cuda")
+        rows = [torch.stack([wl.row_bytes_torch(t, cnt, f, b) for t in range(T)]) for f, b in enumerate(w.field_bytes)]
+        buf.insert(m, rows, torch.from_numpy(np.ascontiguousarray(prio0[:, lo:lo + m])).cuda())
+    del rows
+    counter = N
+
+    # ---------------------------------------------------------------- inputs, resident on the device
+    inputs = [wl.step_inputs(w, s, args.seed) for s in range(total_steps)]
+    d_u = torch.from_numpy(np.stack([i["u"] for i in inputs])).cuda()
+    d_prio = torch.from_numpy(np.stack([i["upd_prio"] for i in inputs])).cuda()
+    d_idx = torch.empty((total_steps, T, B), dtype=torch.int32, device="cuda")
+    d_upd_idx = torch.empty((total_steps, T, B), dtype=torch.int32, device="cuda")
+    d_w = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    d_v = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    d_rows = [torch.empty((T, B, b), dtype=torch.uint8, device="cuda") for b in w.field_bytes]
+    ins_rows = None
+    if w.n_insert:
+        ins_rows = []
+        for s in range(total_steps):
+            cnt = torch.arange(counter + s * w.n_insert, counter + (s + 1) * w.n_insert, device="cuda")
+            ins_rows.append([torch.stack([wl.row_bytes_torch(t, cnt, f, b) for t in range(T)])
+                             for f, b in enumerate(w.field_bytes)])
+    has_dup = "dup_dst" in inputs[0]
+    if has_dup:
+        d_dst = torch.from_numpy(np.stack([i["dup_dst"] for i in inputs])).cuda()
+        d_src = torch.from_numpy(np.stack([i["dup_src"] for i in inputs])).cuda()
+
+    def step(s, recording=False):
+        if w.n_insert:
+            buf.insert(w.n_insert, ins_rows[s])
+        buf.sample(d_u[s], inputs[s]["beta"], want_weights=w.weights, want_prio=True,
+                   out_idx=d_idx[s], out_weight=d_w, out_prio=d_v)
+        buf.gather(d_idx[s], d_rows)
+        if recording:     # synthesise this step's update indices (input generation, untimed pass only)
+            d_upd_idx[s].copy_(d_idx[s])
+            if has_dup:
+                for t in range(T):
+                    d_upd_idx[s, t, d_dst[s, t]] = d_idx[s, t, d_src[s, t]]
+        buf.update(d_upd_idx[s], d_prio[s])
+
+    # ---------------------------------------------------------------- recording pass (untimed)
+    torch.cuda.synchronize()
+    snapshot = buf.arena.clone()
+    cursor0 = (buf.cursor, buf.size)
+    for s in range(total_steps):
+        step(s, recording=True)
+    torch.cuda.synchronize()
+    status_record = buf.status()
+    rec_idx = d_idx.cpu().numpy().view(np.uint32)
+    rec_upd = d_upd_idx.cpu().numpy().view(np.uint32)
+    final_root = buf.total().cpu().numpy().copy()
+
+    def restore():
+        buf.arena.copy_(snapshot)
+        buf.set_ring(*cursor0)
+        torch.cuda.synchronize()
+
+    # per-kernel durations with HIP events (separate pass: events add gaps between kernels)
+    restore_ok = True
+    restore()
+    for s in range(warmup):
+        step(s)
+    buf.profile(True)
+    for s in range(warmup, total_steps):
+        step(s)
+    torch.cuda.synchronize()
+    kernels = buf.profile_read()
+    buf.profile(False)
+
+    # ---------------------------------------------------------------- timed run
+    if restore_ok:
+        restore()
+    stream = torch.cuda.current_stream()
+    for s in range(warmup):
+        step(s)
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for s in range(warmup, total_steps):
+                step(s)
+        torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record(stream)
+    if graph is not None:
+        graph.replay()
+    else:
+        for s in range(warmup, total_steps):
+            step(s)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms_total = ev0.elapsed_time(ev1)
+    ms_per_step = ms_total / steps
+    if restore_ok:   # the timed run must have reproduced the recorded trajectory
+        assert np.array_equal(d_idx.cpu().numpy().view(np.uint32)[warmup:], rec_idx[warmup:]), "timed run diverged"
+        assert buf.total().cpu().numpy().tobytes() == final_root.tobytes(), "timed run ended in a different state"
+
+    # ---------------------------------------------------------------- algorithmic bytes and roofline
+    H = buf.H
+    lvl_n = [buf.level_count(h) for h in range(H + 1)]
+    lds_budget = 64 * 1024
+    for kv in args.tune:
+        if kv.startswith("lds_budget_bytes="):
+            lds_budget = int(kv.split("=")[1])
+    h_lds, acc = H, 0
+    for l in range(H - 1, -1, -1):
+        add = lvl_n[l + 1] * K * 4
+        if acc + add > lds_budget:
+            break
+        acc += add
+        h_lds = l
+    sel = list(range(warmup, total_steps, max(1, steps // 16)))
+    parts = np.array([algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, lvl_n, h_lds, w.weights) for s in sel],
+                     dtype=np.float64).mean(axis=0)
+    a_sample, a_gather, a_update = parts
+    a_step = float(parts.sum())
+    kern_ms = {k: v[0] / max(1, v[1]) for k, v in kernels.items()}
+    kern_per_step = {k: v[1] / steps for k, v in kernels.items()}
+    dominant = max(kernels, key=lambda k: kernels[k][0])
+    alg = {"k_sample": a_sample, "k_rows_gather": a_gather}
+    dom_bytes = alg.get(dominant)
+    if dom_bytes is None:   # an update kernel: attribute the whole update phase's bytes to its launches per step
+        dom_bytes = a_update / max(1.0, sum(v for k, v in kern_per_step.items()
+                                            if k.startswith("k_update") or k.startswith("k_resum")))
+    dom_gbs = dom_bytes / (kern_ms[dominant] * 1e-3) / 1e9
+    roofline = {
+        "kernel": dominant, "bound": "hbm", "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+        "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(kern_ms[dominant] * 1e3, 2),
+    }
+    step_gbs = a_step / (ms_per_step * 1e-3) / 1e9
+
+    # ---------------------------------------------------------------- CPU oracle on a bounded sample
+    cpu = None
+    if args.cpu_seconds > 0:
+        from oracle.per_oracle import MultiOracle
+        orc = MultiOracle(T, K, N, w.field_bytes, with_payload=True)
+        for lo in range(0, N, chunk):
+            m = min(chunk, N - lo)
+            cnt = np.arange(lo, lo + m)
+            rows = [np.stack([wl.row_bytes(t, cnt, f, b) for t in range(T)]) for f, b in enumerate(w.field_bytes)]
+            orc.insert(m, rows, prio0[:, lo:lo + m])
+        done, t_cpu = 0, 0.0
+        while done < total_steps and (t_cpu < args.cpu_seconds or done < 3):
+            inp = inputs[done]
+            ins = None
+            if w.n_insert:
+                cnt = np.arange(counter + done * w.n_insert, counter + (done + 1) * w.n_insert)
+                ins = [np.stack([wl.row_bytes(t, cnt, f, b) for t in range(T)]) for f, b in enumerate(w.field_bytes)]
+            t0 = time.perf_counter()
+            if w.n_insert:
+                orc.insert(w.n_insert, ins)
+            ci, cw, cv = orc.sample(inp["u"], inp["beta"], w.weights)
+            orc.gather(ci)
+            upd = wl.apply_dup_map(ci, inp)
+            orc.update(upd, inp["upd_prio"])
+            t_cpu += time.perf_counter() - t0
+            if restore_ok or done == 0:
+                assert np.array_equal(ci, rec_idx[done]), f"oracle and GPU disagree on step {done}"
+            done += 1
+        cpu = {"value": round(T * B * done / t_cpu, 1), "unit": "transitions/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {done} steps of the same workload and inputs, {t_cpu:.1f} s of CPU time, "
+                         f"{os.cpu_count()} host cores visible, single thread used"}
+
+    out = {
+        "metric": "sampled+updated transitions/s per step; % of HBM peak at N=2^24, B=65536",
+        "value": round(T * B / (ms_per_step * 1e-3), 1), "unit": "transitions/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "K": K, "N": N, "T": T, "B": B, "row_bytes": w.row_bytes,
+                   "insert_per_step": w.n_insert, "launch": "hip_graph" if graph is not None else "eager"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "step_algorithmic_bytes": int(a_step),
+        "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
+        "phase_algorithmic_bytes": {"sample": int(a_sample), "gather": int(a_gather), "update": int(a_update)},
+        "kernels_us": {k: round(v * 1e3, 2) for k, v in sorted(kern_ms.items())},
+        "kernels_per_step": {k: round(v, 2) for k, v in sorted(kern_per_step.items())},
+        "device_status_flags": status_record,
+        "setup_s": round(time.time() - t_setup, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

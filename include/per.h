@@ -135,10 +135,29 @@ uint32_t per_height(const per_t* p);     /* H                                   
 uint64_t per_size(const per_t* p);       /* filled rows per tree                */
 uint64_t per_cursor(const per_t* p);     /* next ring slot                      */
 
+/* Checkpoint / resume: a byte copy of the arena plus (cursor, size) is the whole state of a
+ * buffer.  After the caller has copied a saved arena back, this sets the host mirrors to the
+ * values saved with it.  cursor < N, size <= N. */
+int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
+
 /* Performance knobs; results never depend on them.
  *   "lds_budget_bytes" : upper tree levels are staged in LDS while they fit this many bytes
- *   "sample_block", "update_block", "gather_block" : workgroup sizes (multiples of 64, <= 1024) */
+ *   "sample_block", "update_block", "gather_block" : workgroup sizes (multiples of 64, <= 1024)
+ *   "tree_block" : workgroup size of the update's tree pass (multiple of 64, <= 1024; 0 = chosen per launch)
+ *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
+ *                  the next call that reads them; 0 makes per_update finish them itself */
 int per_set_tuning(per_t* p, const char* name, int64_t value);
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch of this buffer is
+ * bracketed by a pair of HIP events on its stream (this adds gaps between kernels, so
+ * whole-step times must be taken with profiling off).  per_profile(p, 1) clears the
+ * totals and starts; per_profile(p, 0) stops.  per_profile_read waits for the recorded
+ * events and fills, for each kernel launched since the totals were cleared, its name
+ * (static string), summed duration in ms and launch count; *n_entries receives how many
+ * kernels there are (entries beyond max_entries are not written). */
+int per_profile(per_t* p, int enable);
+int per_profile_read(per_t* p, uint32_t max_entries, const char** names, double* total_ms,
+                     uint64_t* launches, uint32_t* n_entries);
 
 const char* per_strerror(int code);
 

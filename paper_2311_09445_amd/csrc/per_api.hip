@@ -20,8 +20,10 @@ struct per_buffer {
   uint64_t col_stride[kMaxFields];
   uint64_t cursor, size;
   uint64_t stamp_next;       // next unused last-writer stamp (stamps 1 .. 2^32-1)
-  uint32_t weight_calls;     // number of per_sample calls that produced weights
+  uint32_t weight_calls;     // number of per_sample calls that used the partial-minimum buffers
+  uint32_t stale_hb;         // != 0: the last update left the heights above this one to their next reader
   int device;
+  Profiler prof;
 };
 
 namespace {
@@ -35,7 +37,8 @@ struct Layout {
   uint32_t n[kMaxHeight + 1];
   uint32_t stride[kMaxHeight + 1];
   size_t level_off[kMaxHeight + 1];
-  size_t scalars_off, owner_off, col_off[kMaxFields];
+  size_t scalars_off, owner_off, dirty_off, arrive_off, col_off[kMaxFields];
+  uint32_t dirty_stride, arrive_stride, arrive_level_off[kMaxHeight + 1];
   uint64_t col_stride[kMaxFields];
   uint32_t owner_stride;
   size_t tree_end;            // bytes up to here are zero-filled as 32-bit words at create
@@ -68,8 +71,8 @@ void make_layout(const per_config* c, Layout* L) {
   } while (n > 1);
   L->H = h;
   size_t off = 0;
-  L->scalars_off = off;                         // max_v[T], status[T], vmin[2][T]
-  off = round_up(off + (size_t)4 * T * 4, kAlign);
+  L->scalars_off = off;                         // max_v[T], status[T], vmin[2][T][kVminSlots]
+  off = round_up(off + (size_t)(2 + 2 * kVminSlots) * T * 4, kAlign);
   for (uint32_t l = 0; l <= L->H; ++l) {
     const uint64_t padded = ((uint64_t)L->n[l] + K - 1) / K * K;
     L->stride[l] = (uint32_t)round_up(padded, 64);
@@ -78,7 +81,18 @@ void make_layout(const per_config* c, Layout* L) {
   }
   L->owner_stride = (uint32_t)round_up(c->capacity, 64);
   L->owner_off = off;
-  off = round_up(off + (size_t)L->owner_stride * T * 4, kAlign);
+  off = round_up(off + (size_t)L->owner_stride * T * 8, kAlign);
+  L->dirty_stride = (uint32_t)round_up((size_t)L->n[1], 256);
+  L->dirty_off = off;
+  off = round_up(off + (size_t)L->dirty_stride * T, kAlign);
+  uint32_t counters = 0;
+  for (uint32_t l = 0; l <= L->H; ++l) {
+    L->arrive_level_off[l] = counters;
+    if (l >= 2) counters += L->n[l];
+  }
+  L->arrive_stride = (uint32_t)round_up((size_t)counters + 1, 64);
+  L->arrive_off = off;
+  off = round_up(off + (size_t)L->arrive_stride * T * 4, kAlign);
   L->tree_end = off;
   for (uint32_t f = 0; f < c->n_fields; ++f) {
     L->col_stride[f] = round_up((size_t)c->capacity * c->field_bytes[f], kAlign);
@@ -114,6 +128,14 @@ int fill_fields(per_t* p, void* const* io, FieldTable* ft) {
 
 int hip_rc(hipError_t e) { return e == hipSuccess ? PER_OK : PER_EHIP; }
 
+// Rebuilds the heights an update left stale, for readers that take them from memory.
+hipError_t ensure_top(per_t* p, hipStream_t s) {
+  if (!p->stale_hb) return hipSuccess;
+  hipError_t e = launch_resum_top(p->g, p->tn, p->stale_hb, s);
+  if (e == hipSuccess) p->stale_hb = 0;
+  return e;
+}
+
 }  // namespace
 
 extern "C" {
@@ -139,7 +161,6 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
 
   per_t* p = new (std::nothrow) per_buffer();
   if (!p) return PER_ENOMEM;
-  memset(p, 0, sizeof(*p));
   p->cfg = *cfg;
   p->arena = static_cast<uint8_t*>(d_arena);
   p->arena_bytes = arena_bytes;
@@ -154,8 +175,15 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
     g.stride[l] = L.stride[l];
     g.level[l] = reinterpret_cast<float*>(p->arena + L.level_off[l]);
   }
-  g.owner = reinterpret_cast<uint32_t*>(p->arena + L.owner_off);
+  g.root = g.level[L.H];
+  g.root_stride = g.stride[L.H];
+  g.owner = reinterpret_cast<uint64_t*>(p->arena + L.owner_off);
   g.owner_stride = L.owner_stride;
+  g.dirty = p->arena + L.dirty_off;
+  g.dirty_stride = L.dirty_stride;
+  g.arrive = reinterpret_cast<uint32_t*>(p->arena + L.arrive_off);
+  g.arrive_stride = L.arrive_stride;
+  for (uint32_t l = 0; l <= L.H; ++l) g.arrive_off[l] = L.arrive_level_off[l];
   g.max_v = reinterpret_cast<float*>(p->arena + L.scalars_off);
   g.status = reinterpret_cast<uint32_t*>(g.max_v + g.T);
   g.vmin = g.status + g.T;
@@ -167,12 +195,15 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.sample_block = 256;
   p->tn.update_block = 256;
   p->tn.gather_block = 256;
+  p->tn.tree_block = 0;   // chosen per launch
+  p->tn.lazy_top = 1;
+  p->tn.prof = &p->prof;
   p->stamp_next = 1;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   // zero everything (tree levels, stamps and payload), then the scalars
-  hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(p->arena), L.total / 4, 0u, s);
+  hipError_t e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(p->arena), L.total / 4, 0u, s);
   if (e == hipSuccess) e = launch_init_scalars(g, cfg->init_max_priority, s);
   if (e != hipSuccess) { delete p; return PER_EHIP; }
   *out = p;
@@ -181,6 +212,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
 
 int per_destroy(per_t* p) {
   if (!p) return PER_EINVAL;
+  p->prof.reset();
   delete p;
   return PER_OK;
 }
@@ -195,8 +227,8 @@ int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float
   const uint64_t N = p->cfg.capacity;
   const uint32_t cursor = (uint32_t)p->cursor;
   FieldTable ft;
-  hipError_t e = hipSuccess;
-  if (fill_fields(p, const_cast<void* const*>(reinterpret_cast<const void* const*>(d_field_src)), &ft))
+  hipError_t e = ensure_top(p, s);
+  if (e == hipSuccess && fill_fields(p, const_cast<void* const*>(reinterpret_cast<const void* const*>(d_field_src)), &ft))
     e = launch_scatter(p->g, p->tn, ft, n, cursor, s);
   if (e == hipSuccess) e = launch_insert_leaves(p->g, p->tn, n, cursor, d_prio, d_out_idx, s);
   if (e == hipSuccess) {
@@ -224,10 +256,10 @@ int per_sample(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_o
   if (!isfinite(beta) || beta < 0.0f) return PER_EINVAL;
   if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
   if (p->size == 0) return PER_EEMPTY;
-  const uint32_t parity = p->weight_calls & 1u;
-  if (d_out_weight) p->weight_calls++;
+  const uint32_t stale = p->stale_hb;
+  p->stale_hb = 0;   // the sampling kernel rebuilds and stores the stale heights
   return hip_rc(launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, d_out_idx, d_out_weight, d_out_prio,
-                              parity, static_cast<hipStream_t>(stream)));
+                              &p->weight_calls, stale, static_cast<hipStream_t>(stream)));
 }
 
 int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field_dst, void* stream) {
@@ -246,20 +278,22 @@ int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio,
   if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (p->stamp_next + B > 0xFFFFFFFFull) {   // stamps exhausted: start over from a cleared array
-    hipError_t e = launch_fill_u32(p->g.owner, (uint64_t)p->g.owner_stride * p->g.T, 0u, s);
+    hipError_t e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(p->g.owner), 2ull * p->g.owner_stride * p->g.T, 0u, s);
     if (e != hipSuccess) return PER_EHIP;
     p->stamp_next = 1;
   }
   const uint32_t base = (uint32_t)p->stamp_next;
   p->stamp_next += B;
-  return hip_rc(launch_update(p->g, p->tn, B, (uint32_t)p->size, d_idx, d_prio, base, s));
+  hipError_t e = launch_update(p->g, p->tn, B, (uint32_t)p->size, d_idx, d_prio, base, s);
+  if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
+  return hip_rc(e);
 }
 
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream) {
   if (!p) return PER_EINVAL;
   if (n == 0) return PER_OK;
   if (!d_idx || !d_out || misaligned(d_idx, 4) || misaligned(d_out, 4)) return PER_EINVAL;
-  return hip_rc(launch_get_priority(p->g, n, d_idx, d_out, static_cast<hipStream_t>(stream)));
+  return hip_rc(launch_get_priority(p->g, p->tn, n, d_idx, d_out, static_cast<hipStream_t>(stream)));
 }
 
 int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint64_t* count, void* stream) {
@@ -268,6 +302,8 @@ int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint6
   if (count) *count = p->g.n[height];
   if (!d_out) return PER_OK;
   if (misaligned(d_out, 4)) return PER_EINVAL;
+  if (p->stale_hb && height > p->stale_hb && ensure_top(p, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return PER_EHIP;
   const float* src = p->g.level[height] + (size_t)tree * p->g.stride[height];
   return hip_rc(hipMemcpyAsync(d_out, src, (size_t)p->g.n[height] * 4, hipMemcpyDeviceToDevice,
                                static_cast<hipStream_t>(stream)));
@@ -275,6 +311,7 @@ int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint6
 
 int per_total(per_t* p, float* d_out, void* stream) {
   if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
+  if (ensure_top(p, static_cast<hipStream_t>(stream)) != hipSuccess) return PER_EHIP;
   return hip_rc(launch_read_scalars(p->g, 0, d_out, static_cast<hipStream_t>(stream)));
 }
 
@@ -306,6 +343,15 @@ uint32_t per_height(const per_t* p) { return p ? p->g.H : 0; }
 uint64_t per_size(const per_t* p) { return p ? p->size : 0; }
 uint64_t per_cursor(const per_t* p) { return p ? p->cursor : 0; }
 
+int per_set_ring(per_t* p, uint64_t cursor, uint64_t size) {
+  if (!p) return PER_EINVAL;
+  if (size > p->cfg.capacity || cursor >= p->cfg.capacity) return PER_ERANGE;
+  p->cursor = cursor;
+  p->size = size;
+  p->stale_hb = lazy_top_height(p->g, p->tn);   // a saved arena may predate the rebuild of its top heights
+  return PER_OK;
+}
+
 int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!p || !name) return PER_EINVAL;
   if (!strcmp(name, "lds_budget_bytes")) {
@@ -313,12 +359,44 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
     p->tn.lds_budget_bytes = (uint32_t)value;
     return PER_OK;
   }
+  if (!strcmp(name, "lazy_top")) {
+    if (value != 0 && value != 1) return PER_EINVAL;
+    p->tn.lazy_top = (uint32_t)value;
+    return PER_OK;
+  }
   uint32_t* blk = !strcmp(name, "sample_block") ? &p->tn.sample_block
                 : !strcmp(name, "update_block") ? &p->tn.update_block
-                : !strcmp(name, "gather_block") ? &p->tn.gather_block : nullptr;
+                : !strcmp(name, "gather_block") ? &p->tn.gather_block
+                : !strcmp(name, "tree_block") ? &p->tn.tree_block : nullptr;
   if (!blk) return PER_EINVAL;
+  if (blk == &p->tn.tree_block && value == 0) { *blk = 0; return PER_OK; }
   if (value < 64 || value > 1024 || value % 64) return PER_EINVAL;
   *blk = (uint32_t)value;
+  return PER_OK;
+}
+
+int per_profile(per_t* p, int enable) {
+  if (!p) return PER_EINVAL;
+  p->prof.reset();
+  p->prof.on = enable != 0;
+  return PER_OK;
+}
+
+int per_profile_read(per_t* p, uint32_t max_entries, const char** names, double* total_ms, uint64_t* launches,
+                     uint32_t* n_entries) {
+  if (!p || !n_entries || (max_entries && (!names || !total_ms || !launches))) return PER_EINVAL;
+  if (p->prof.collect() != hipSuccess) return PER_EHIP;
+  uint32_t n = 0;
+  for (int k = 0; k < KID_COUNT; ++k) {
+    if (p->prof.launches[k] == 0) continue;
+    if (n < max_entries) {
+      names[n] = kernel_name(k);
+      total_ms[n] = p->prof.total_ms[k];
+      launches[n] = p->prof.launches[k];
+    }
+    ++n;
+  }
+  *n_entries = n;
   return PER_OK;
 }
 

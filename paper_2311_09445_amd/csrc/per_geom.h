@@ -9,10 +9,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 namespace per {
 
 constexpr int kMaxHeight = 32;   // K = 2, N = 2^31 gives H = 31
 constexpr int kMaxFields = 8;
+constexpr uint32_t kVminSlots = 256;   // partial batch minima per tree and buffer
 
 struct Geom {
   uint32_t K, logK, H, T;
@@ -20,11 +23,18 @@ struct Geom {
   uint32_t n[kMaxHeight + 1];       // real nodes per level
   uint32_t stride[kMaxHeight + 1];  // floats between consecutive trees of a level (multiple of 64)
   float*   level[kMaxHeight + 1];   // level h of tree 0
-  uint32_t* owner;                  // [T][owner_stride] last-writer stamps
+  float*   root;                    // == level[H]; at a fixed offset so kernels need no dependent load
+  uint32_t root_stride;             // == stride[H]
+  uint64_t* owner;                  // [T][owner_stride] last-writer stamps: (stamp << 32) | fp32 bits of the value
   uint32_t owner_stride;
+  uint8_t* dirty;                   // [T][dirty_stride] one byte per height-1 node: a leaf below it was claimed
+  uint32_t dirty_stride;
+  uint32_t* arrive;                 // [T][arrive_stride] arrival counters of the nodes of heights >= 2
+  uint32_t arrive_stride;
+  uint32_t arrive_off[kMaxHeight + 1];   // offset of height h (>= 2) inside a tree's counters
   float*    max_v;                  // [T] running max priority
   uint32_t* status;                 // [T] sticky flags
-  uint32_t* vmin;                   // [2][T] batch minimum of sampled values (fp32 bits), double-buffered
+  uint32_t* vmin;                   // [2][T][kVminSlots] partial batch minima of sampled values (fp32 bits)
 };
 
 struct FieldTable {
@@ -38,16 +48,44 @@ struct FieldTable {
 
 struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b0) u [a1,b1)
 
+// Optional per-kernel timing with HIP events on the launch stream (off by default).
+enum KernelId {
+  KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
+  KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_GET_PRIORITY, KID_COUNT
+};
+const char* kernel_name(int kid);
+
+struct Profiler {
+  struct Rec { hipEvent_t start, stop; int kid; };
+  bool on = false;
+  std::vector<Rec> recs;
+  double total_ms[KID_COUNT] = {};
+  uint64_t launches[KID_COUNT] = {};
+  void reset();                 // drops pending events and zeroes the totals
+  hipError_t collect();         // waits for pending events and folds them into the totals
+};
+
+struct ProfScope {              // records an event pair around one launch when profiling is on
+  Profiler* p;
+  hipStream_t s;
+  hipEvent_t stop = nullptr;
+  ProfScope(Profiler* prof, int kid, hipStream_t stream);
+  ~ProfScope();
+};
+
 struct Tuning {
   uint32_t lds_budget_bytes;
-  uint32_t sample_block, update_block, gather_block;
+  uint32_t sample_block, update_block, gather_block, tree_block;
+  uint32_t lazy_top;   // updates may leave the few topmost heights to their next reader
+  Profiler* prof;
 };
 
 // Launchers (per_kernels.hip).  All enqueue on `s` and return hipGetLastError().
-hipError_t launch_fill_u32(uint32_t* p, uint64_t count, uint32_t value, hipStream_t s);
+hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32_t value, hipStream_t s);
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
-                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t parity, hipStream_t s);
+                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
+                         hipStream_t s);
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s);
 hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t n, uint32_t cursor,
@@ -55,9 +93,11 @@ hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft,
 hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uint32_t cursor, const float* prio,
                                 uint32_t* out_idx, hipStream_t s);
 hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipStream_t s);
+hipError_t launch_resum_top(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
+uint32_t lazy_top_height(const Geom& g, const Tuning& tn);
 hipError_t launch_update(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
                          const float* prio, uint32_t stamp_base, hipStream_t s);
-hipError_t launch_get_priority(const Geom& g, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
+hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
 hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s);
 hipError_t launch_clear_status(const Geom& g, hipStream_t s);
 

@@ -10,7 +10,84 @@
 // identical bits.
 #include "per_geom.h"
 
+#include <type_traits>
+
 namespace per {
+
+// ---------------------------------------------------------------------------------
+// per-kernel timing
+// ---------------------------------------------------------------------------------
+const char* kernel_name(int kid) {
+  static const char* const names[KID_COUNT] = {
+      "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_rows_scatter", "k_insert_leaves",
+      "k_resum_dense", "k_resum_tail", "k_update_claim", "k_update_tree", "k_get_priority"};
+  return kid >= 0 && kid < KID_COUNT ? names[kid] : "?";
+}
+
+void Profiler::reset() {
+  for (Rec& r : recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  recs.clear();
+  for (int k = 0; k < KID_COUNT; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
+}
+
+hipError_t Profiler::collect() {
+  hipError_t first = hipSuccess;
+  for (Rec& r : recs) {
+    float ms = 0.0f;
+    hipError_t e = hipEventSynchronize(r.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+    if (e == hipSuccess) { total_ms[r.kid] += ms; launches[r.kid] += 1; }
+    else if (first == hipSuccess) first = e;
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  recs.clear();
+  return first;
+}
+
+ProfScope::ProfScope(Profiler* prof, int kid, hipStream_t stream) : p(prof && prof->on ? prof : nullptr), s(stream) {
+  if (!p) return;
+  Profiler::Rec r;
+  r.kid = kid;
+  if (hipEventCreate(&r.start) != hipSuccess) { p = nullptr; return; }
+  if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); p = nullptr; return; }
+  (void)hipEventRecord(r.start, s);
+  stop = r.stop;
+  p->recs.push_back(r);
+}
+
+ProfScope::~ProfScope() {
+  if (p) (void)hipEventRecord(stop, s);
+}
+
+#define PER_LAUNCH(KID, KERNEL, GRID, BLOCK, LDS, STREAM, ...)            \
+  do {                                                                    \
+    ProfScope prof_scope_(tn.prof, KID, STREAM);                          \
+    KERNEL<<<GRID, BLOCK, LDS, STREAM>>>(__VA_ARGS__);                    \
+  } while (0)
+
+// ---------------------------------------------------------------------------------
+// optional in-kernel time stamps (development builds with -DPER_TRACE only)
+// ---------------------------------------------------------------------------------
+#ifdef PER_TRACE
+constexpr int kTraceMarks = 16, kTraceBlocks = 2048;
+__device__ unsigned long long g_trace[kTraceBlocks * kTraceMarks];
+#define PER_MARK(i)                                                                            \
+  do {                                                                                         \
+    if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < kTraceBlocks)                      \
+      g_trace[blockIdx.x * kTraceMarks + (i)] = wall_clock64();                                \
+  } while (0)
+extern "C" int per_trace_read(unsigned long long* host, int clear) {
+  if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(g_trace)) != hipSuccess) return -1;
+  if (clear) {
+    static unsigned long long zeros[kTraceBlocks * kTraceMarks];
+    if (hipMemcpyToSymbol(HIP_SYMBOL(g_trace), zeros, sizeof(zeros)) != hipSuccess) return -1;
+  }
+  return kTraceBlocks * kTraceMarks;
+}
+#else
+#define PER_MARK(i) do { } while (0)
+#endif
 
 // ---------------------------------------------------------------------------------
 // small helpers
@@ -45,12 +122,40 @@ __device__ __forceinline__ float group_sum(const float* grp, unsigned q) {
 }
 
 // One K-ary level of the prefix-sum traversal (Section V-A "traversing the tree
-// performing prefix sum from root to leaf"), as log2(K) binary steps:
+// performing prefix sum from root to leaf"), done by a single lane as log2(K) binary steps:
 //   go right iff the right block is non-zero and not (r < left block); then r -= left.
-// On return all lanes of the group hold the chosen child, its value and the residual.
+//
+// walk_chunks: s[] holds the 2^M chunk sums of the group (a chunk = 4 adjacent children,
+// summed (c0+c1)+(c2+c3)).  The recursion first builds the pairwise sums above the chunks,
+// walks those levels from the top, and then decides between the two chunks below the node
+// it arrived at.  The pair is picked with a select chain, so everything stays in registers.
+template <int M>
+__device__ __forceinline__ unsigned walk_chunks(const float (&s)[1 << M], float& r) {
+  if constexpr (M == 0) {
+    return 0u;
+  } else {
+    constexpr int HALF = 1 << (M - 1);
+    float up[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) up[i] = s[2 * i] + s[2 * i + 1];
+    const unsigned pos = walk_chunks<M - 1>(up, r);
+    float L = s[0], R = s[1];
+#pragma unroll
+    for (int i = 1; i < HALF; ++i) {
+      const bool here = pos == (unsigned)i;
+      L = here ? s[2 * i] : L;
+      R = here ? s[2 * i + 1] : R;
+    }
+    const bool right = (R != 0.0f) && !(r < L);
+    r = right ? r - L : r;
+    return 2u * pos + (right ? 1u : 0u);
+  }
+}
+
+// grp points at the K children (LDS or global).  Returns the chosen child, its value and the
+// residual.  The chosen chunk is read a second time instead of keeping all K children live.
 template <int LOGK>
-__device__ __forceinline__ void descend_group(const float* grp, unsigned q, unsigned lane, float& r,
-                                              unsigned& child, float& val) {
+__device__ __forceinline__ void descend_lane(const float* grp, float& r, unsigned& child, float& val) {
   if constexpr (LOGK == 1) {
     const float2 c = *reinterpret_cast<const float2*>(grp);
     const bool right = (c.y != 0.0f) && !(r < c.x);
@@ -58,52 +163,24 @@ __device__ __forceinline__ void descend_group(const float* grp, unsigned q, unsi
     child = right ? 1u : 0u;
     val = right ? c.y : c.x;
   } else {
-    constexpr int LOGLPS = Fan<LOGK>::LOGLPS;
-    constexpr int LPS = Fan<LOGK>::LPS;
-    const float4 c = *reinterpret_cast<const float4*>(grp + 4 * q);
-    const float p0 = c.x + c.y, p1 = c.z + c.w;
-    float mine[LOGLPS + 1];
-    float sib[LOGLPS + 1];
-    mine[0] = p0 + p1;
+    constexpr int C = (1 << LOGK) / 4;
+    const float4* g4 = reinterpret_cast<const float4*>(grp);
+    float s[C];
 #pragma unroll
-    for (int k = 0; k < LOGLPS; ++k) {
-      sib[k] = __shfl_xor(mine[k], 1 << k);
-      mine[k + 1] = mine[k] + sib[k];
+    for (int c = 0; c < C; ++c) {
+      const float4 x = g4[c];
+      s[c] = (x.x + x.y) + (x.z + x.w);
     }
-    // Walk the blocks of 4*2^k children from the top.  A lane stays "on path" while the
-    // decisions match its own position bits; exactly one lane of the group stays on path,
-    // and up to that point it has seen the true left/right sums and residual.
-    float rr = r;
-    bool on = true;
-#pragma unroll
-    for (int k = LOGLPS - 1; k >= 0; --k) {
-      const bool bit = (q >> k) & 1u;
-      const float L = bit ? sib[k] : mine[k];
-      const float R = bit ? mine[k] : sib[k];
-      const bool right = (R != 0.0f) && !(rr < L);
-      rr = right ? rr - L : rr;
-      on = on && (right == bit);
-    }
-    // last two binary steps inside this lane's four children
-    const bool r1 = (p1 != 0.0f) && !(rr < p0);
-    rr = r1 ? rr - p0 : rr;
-    const float a = r1 ? c.z : c.x, b = r1 ? c.w : c.y;
-    const bool r0 = (b != 0.0f) && !(rr < a);
-    rr = r0 ? rr - a : rr;
-    float v = r0 ? b : a;
-    unsigned ch = 4u * q + (r1 ? 2u : 0u) + (r0 ? 1u : 0u);
-    if constexpr (LPS > 1) {
-      const unsigned long long m = __ballot(on);
-      const unsigned base = lane & ~(unsigned)(LPS - 1);
-      const unsigned bits = (unsigned)(m >> base) & ((1u << LPS) - 1u);
-      const int src = (int)base + (__ffs((int)bits) - 1);
-      rr = __shfl(rr, src);
-      v = __shfl(v, src);
-      ch = (unsigned)__shfl((int)ch, src);
-    }
-    r = rr;
-    child = ch;
-    val = v;
+    const unsigned pos = walk_chunks<LOGK - 2>(s, r);
+    const float4 x = g4[pos];
+    const float p0 = x.x + x.y, p1 = x.z + x.w;
+    const bool r1 = (p1 != 0.0f) && !(r < p0);
+    r = r1 ? r - p0 : r;
+    const float a = r1 ? x.z : x.x, b = r1 ? x.w : x.y;
+    const bool r0 = (b != 0.0f) && !(r < a);
+    r = r0 ? r - a : r;
+    val = r0 ? b : a;
+    child = 4u * pos + (r1 ? 2u : 0u) + (r0 ? 1u : 0u);
   }
 }
 
@@ -124,6 +201,24 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
   return x;
 }
 
+// Running maximum priority: mx = fp32 bits of this lane's valid positive value (0: none).  One
+// atomic per wave, and only when the wave would actually raise the maximum; the plain read may
+// be stale, which can only cause a redundant atomic, never a missed one (the value only grows).
+__device__ __forceinline__ void raise_max(const Geom& g, uint32_t t, uint32_t mx) {
+  mx = wave_max_u32(mx);
+  uint32_t* addr = reinterpret_cast<uint32_t*>(&g.max_v[t]);
+  if ((threadIdx.x & 63u) == 0 && mx > *reinterpret_cast<volatile uint32_t*>(addr)) atomicMax(addr, mx);
+}
+
+// Importance weight (prioritized experience replay, cited in Section II-A):
+// w = (size * v / total)^-beta / max over the batch, the maximum being reached at the batch
+// minimum of v.  fp64, so that the result stays within 1e-6 of an fp64 reference.
+__device__ __forceinline__ float importance_weight(float v, float vmin, float total, uint32_t size, float beta) {
+  const double nb = -(double)beta;
+  const double scale = (double)size / (double)total;
+  return (float)(pow(scale * (double)v, nb) / pow(scale * (double)vmin, nb));
+}
+
 // ---------------------------------------------------------------------------------
 // fills and scalars
 // ---------------------------------------------------------------------------------
@@ -137,12 +232,12 @@ __global__ void k_fill_u32(uint32_t* p, uint64_t count, uint32_t value) {
   for (uint64_t i = n4 * 4 + i0; i < count; i += stride) p[i] = value;
 }
 
-hipError_t launch_fill_u32(uint32_t* p, uint64_t count, uint32_t value, hipStream_t s) {
+hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32_t value, hipStream_t s) {
   if (count == 0) return hipSuccess;
   uint64_t blocks = (count / 4 + 255) / 256;
   if (blocks < 1) blocks = 1;
   if (blocks > 16384) blocks = 16384;
-  k_fill_u32<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(p, count, value);
+  PER_LAUNCH(KID_FILL, k_fill_u32, dim3((unsigned)blocks), dim3(256), 0, s, p, count, value);
   return hipGetLastError();
 }
 
@@ -151,8 +246,7 @@ __global__ void k_init_scalars(Geom g, float init_max) {
   if (t >= g.T) return;
   g.max_v[t] = init_max;
   g.status[t] = 0;
-  g.vmin[t] = 0x7F800000u;
-  g.vmin[g.T + t] = 0x7F800000u;
+  for (uint32_t k = 0; k < 2 * kVminSlots; ++k) g.vmin[(size_t)k * g.T + t] = 0x7F800000u;
 }
 
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s) {
@@ -164,7 +258,7 @@ hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s) {
 __global__ void k_read_scalars(Geom g, int which, float* out) {
   const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= g.T) return;
-  out[t] = which == 0 ? g.level[g.H][(size_t)t * g.stride[g.H]] : g.max_v[t];
+  out[t] = which == 0 ? g.root[(size_t)t * g.root_stride] : g.max_v[t];
 }
 
 hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s) {
@@ -185,47 +279,110 @@ hipError_t launch_clear_status(const Geom& g, hipStream_t s) {
 // ---------------------------------------------------------------------------------
 // priority sampling
 // ---------------------------------------------------------------------------------
-// grid (ceil(B*LPS / block), T).  Heights h_lds .. H-1 of the block's tree are staged in
-// LDS first; lower heights are read from memory, one coalesced group per sample and level.
+// The topmost heights below the root are copied to LDS (at most kTopSlots of them, highest
+// first).  Their descriptors sit at fixed kernel-argument offsets, so the kernel fetches all of
+// them with one batch of scalar loads instead of a chain of dependent ones.
+constexpr int kTopSlots = 4;
+struct TopCopy {
+  const float* ptr[kTopSlots];     // that height of tree 0
+  uint32_t stride[kTopSlots];      // floats between trees
+  uint32_t cnt[kTopSlots];         // floats copied: whole child groups, n[l+1] * K
+  uint32_t nreal[kTopSlots];       // real nodes n[l]
+  uint32_t nslots;
+  const float* root;               // root of tree 0
+  uint32_t root_stride;
+};
+
+// One lane per sample; grid (ceil(B / block), T).  Dynamic LDS holds the top copy followed by
+// one staging area per wave.  Below the copy each level costs one trip to memory: the wave
+// fetches its 64 child groups with fully coalesced 16-byte loads (K/4 adjacent lanes per
+// group), parks them in LDS rows of K+4 floats (the pad keeps 16-byte row reads conflict-free),
+// and every lane then walks its own row.
+//
+// stale < 0: the tree in memory is whole.  stale >= 0: the last update left the root and the
+// `stale` topmost copied heights to this kernel; they are rebuilt here from the highest fresh
+// height (which is in the copy), and the first workgroup of each tree stores them back.
 template <int LOGK>
-__global__ void k_sample(Geom g, uint32_t B, const float* __restrict__ u, uint32_t* __restrict__ out_idx,
-                         float* __restrict__ out_prio, float* __restrict__ out_w, uint32_t parity,
-                         uint32_t h_lds) {
+__global__ void __launch_bounds__(1024)
+k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float* __restrict__ u,
+         uint32_t* __restrict__ out_idx, float* __restrict__ out_prio, float* __restrict__ out_w,
+         uint32_t parity, int stale) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
-  extern __shared__ float lds[];
+  constexpr int C = K >= 4 ? K / 4 : 1;       // 16-byte chunks per group
+  constexpr int ROW = K + 4;                  // staging row, floats
+  using Vec = typename std::conditional<LOGK == 1, float2, float4>::type;
+  constexpr int VF = sizeof(Vec) / 4;
+  extern __shared__ __attribute__((aligned(16))) float lds[];   // 16-byte LDS accesses need the alignment
+  __shared__ uint32_t s_min[16];
+  __shared__ float s_total;
   const uint32_t t = blockIdx.y;
   const uint32_t H = g.H;
-
-  if (h_lds < H) {
-    uint32_t off = 0;
-    for (int l = (int)H - 1; l >= (int)h_lds; --l) {
-      const uint32_t cnt = g.n[l + 1] * (uint32_t)K;
-      const float* src = g.level[l] + (size_t)t * g.stride[l];
-      if constexpr (LOGK >= 2) {
-        const float4* s4 = reinterpret_cast<const float4*>(src);
-        float4* d4 = reinterpret_cast<float4*>(lds + off);
-        for (uint32_t i = threadIdx.x; i < cnt / 4; i += blockDim.x) d4[i] = s4[i];
-      } else {
-        for (uint32_t i = threadIdx.x; i < cnt; i += blockDim.x) lds[off + i] = src[i];
-      }
-      off += cnt;
-    }
-    __syncthreads();
-  }
-
-  const uint32_t gt = blockIdx.x * blockDim.x + threadIdx.x;
-  const uint32_t s_raw = gt / LPS;
-  const unsigned q = gt % LPS;
   const unsigned lane = threadIdx.x & 63u;
+  const unsigned wave = threadIdx.x >> 6;
+  const int nslots = (int)tc.nslots;
+
+  PER_MARK(0);
+  const uint32_t s_raw = blockIdx.x * blockDim.x + threadIdx.x;
   const bool active = s_raw < B;
   const uint32_t s = active ? s_raw : B - 1;
   const size_t o = (size_t)t * B + s;
+  // the root, this lane's uniform and the top copy are all fetched in the same trip
+  float total = tc.root[(size_t)t * tc.root_stride];
+  const float u_s = u[o];
 
-  const float total = g.level[H][(size_t)t * g.stride[H]];
-  if (blockIdx.x == 0 && threadIdx.x == 0 && out_w) g.vmin[(parity ^ 1u) * g.T + t] = 0x7F800000u;
-  if (!(total > 0.0f)) {   // nothing can be sampled from this tree
-    if (active && q == 0) {
+  uint32_t off[kTopSlots + 1];
+  off[0] = 0;
+#pragma unroll
+  for (int i = 0; i < kTopSlots; ++i) off[i + 1] = off[i] + (i < nslots ? tc.cnt[i] : 0u);
+  const uint32_t top_floats = off[kTopSlots];
+
+  if (nslots > 0) {
+    // one flat loop over the vectors of all copied heights (stale ones are skipped)
+    const uint32_t v_lo = stale > 0 ? off[stale < kTopSlots ? stale : kTopSlots] / VF : 0u;
+    for (uint32_t e = v_lo + threadIdx.x; e < top_floats / VF; e += blockDim.x) {
+      const uint32_t f = e * VF;
+      const float* src = tc.ptr[0] + (size_t)t * tc.stride[0];
+      uint32_t base = 0;
+#pragma unroll
+      for (int i = 1; i < kTopSlots; ++i) {
+        const bool here = i < nslots && f >= off[i];
+        src = here ? tc.ptr[i] + (size_t)t * tc.stride[i] : src;
+        base = here ? off[i] : base;
+      }
+      *reinterpret_cast<Vec*>(lds + f) = *reinterpret_cast<const Vec*>(src + (f - base));
+    }
+    __syncthreads();
+    PER_MARK(1);
+    if (stale >= 0) {   // rebuild slots stale-1 .. 0 and the root, bottom-up
+      const unsigned q = threadIdx.x % LPS;
+      const uint32_t grp = threadIdx.x / LPS, ngrp = blockDim.x / LPS;
+#pragma unroll
+      for (int i = kTopSlots - 1; i >= -1; --i) {
+        if (i < stale && i + 1 < nslots) {
+          const uint32_t nl = i >= 0 ? tc.nreal[i] : 1u;
+          const uint32_t cnt = i >= 0 ? tc.cnt[i] : 0u;
+          const uint32_t off_l = i >= 0 ? off[i] : 0u;
+          const uint32_t height = H - 1 - (uint32_t)i;
+          for (uint32_t base = 0; base < nl; base += ngrp) {
+            const uint32_t j = base + grp;
+            const bool real = j < nl;
+            const float sum = group_sum<LOGK>(lds + off[i + 1] + (size_t)(real ? j : 0u) * K, q);
+            if (q == 0 && real) {
+              if (i >= 0) lds[off_l + j] = sum; else s_total = sum;
+              if (blockIdx.x == 0) g.level[height][(size_t)t * g.stride[height] + j] = sum;
+            }
+          }
+          for (uint32_t j = nl + threadIdx.x; j < cnt; j += blockDim.x) lds[off_l + j] = 0.0f;   // group padding
+          __syncthreads();
+        }
+      }
+      total = s_total;
+    }
+  }
+
+  if (!(total > 0.0f)) {   // nothing can be sampled from this tree (uniform over the block)
+    if (active) {
       out_idx[o] = 0xFFFFFFFFu;
       if (out_prio) out_prio[o] = 0.0f;
       if (out_w) out_w[o] = 0.0f;
@@ -234,81 +391,158 @@ __global__ void k_sample(Geom g, uint32_t B, const float* __restrict__ u, uint32
     return;
   }
 
+  PER_MARK(2);
   const float seg = total / (float)B;
-  const float pos = (float)s + u[o];
+  const float pos = (float)s + u_s;
   float r = pos * seg;
 
   uint32_t node = 0;
   float val = total;
-  uint32_t off = 0;
-  for (int l = (int)H - 1; l >= 0; --l) {
+#pragma unroll
+  for (int i = 0; i < kTopSlots; ++i) {
+    if (i < nslots) {
+      unsigned child;
+      descend_lane<LOGK>(lds + off[i] + (size_t)node * K, r, child, val);
+      node = node * K + child;
+    }
+  }
+
+  PER_MARK(3);
+  float* stage = lds + top_floats + (size_t)wave * 64 * ROW;
+  const int l0 = (int)H - 1 - nslots;     // highest height read from memory
+  // the pointer of the next level is fetched while the current one is processed
+  const float* lvl_next = l0 >= 0 ? g.level[l0] + (size_t)t * g.stride[l0] : nullptr;
+  for (int l = l0; l >= 0; --l) {
+    const float* lvl = lvl_next;
+    if (l > 0) lvl_next = g.level[l - 1] + (size_t)t * g.stride[l - 1];
     unsigned child;
-    if ((uint32_t)l >= h_lds) {
-      descend_group<LOGK>(lds + off + (size_t)node * K, q, lane, r, child, val);
-      off += g.n[l + 1] * (uint32_t)K;
+    if constexpr (LOGK <= 2) {
+      descend_lane<LOGK>(lvl + (size_t)node * K, r, child, val);
     } else {
-      descend_group<LOGK>(g.level[l] + (size_t)t * g.stride[l] + (size_t)node * K, q, lane, r, child, val);
+      float4 x[C];
+#pragma unroll
+      for (int it = 0; it < C; ++it) {       // chunk (it*64 + lane) of the wave's 64*C chunks
+        const unsigned gch = (unsigned)it * 64u + lane;
+        const uint32_t nd = (uint32_t)__shfl((int)node, (int)(gch / C));
+        x[it] = *reinterpret_cast<const float4*>(lvl + (size_t)nd * K + (gch % C) * 4u);
+      }
+#pragma unroll
+      for (int it = 0; it < C; ++it) {
+        const unsigned gch = (unsigned)it * 64u + lane;
+        *reinterpret_cast<float4*>(stage + (gch / C) * ROW + (gch % C) * 4u) = x[it];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      descend_lane<LOGK>(stage + lane * ROW, r, child, val);
+      __builtin_amdgcn_wave_barrier();
     }
     node = node * K + child;
+    PER_MARK(4 + (l0 - l));
   }
 
-  if (active && q == 0) {
+  if (active) {
     out_idx[o] = node;
     if (out_prio) out_prio[o] = val;
-    if (out_w) out_w[o] = val;   // turned into the weight by k_weights
   }
-  if (out_w) {
-    const uint32_t m = wave_min_u32(active ? __float_as_uint(val) : 0x7F800000u);
-    if (lane == 0) atomicMin(&g.vmin[parity * g.T + t], m);
+  PER_MARK(12);
+  if (!out_w) return;
+  // Importance weights need the batch minimum of the sampled values.
+  const uint32_t m = wave_min_u32(active ? __float_as_uint(val) : 0x7F800000u);
+  if (gridDim.x == 1) {   // the whole batch of this tree is in this block: finish here
+    if (lane == 0) s_min[wave] = m;
+    __syncthreads();
+    uint32_t mm = 0x7F800000u;
+    for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_min[wv] < mm ? s_min[wv] : mm;
+    if (active) out_w[o] = importance_weight(val, __uint_as_float(mm), total, size, beta);
+  } else {                // partial minima, spread over kVminSlots addresses; k_weights finishes
+    if (active) out_w[o] = val;
+    if (lane == 0)
+      atomicMin(&g.vmin[((size_t)parity * g.T + t) * kVminSlots + ((blockIdx.x * (blockDim.x >> 6) + wave) % kVminSlots)], m);
   }
 }
 
-// Importance weights (prioritized experience replay, cited in Section II-A):
-// w_i = (size * v_i / total)^-beta / max_j(...), the maximum being reached at the batch
-// minimum of v.  fp64 so that the result stays within 1e-6 of an fp64 reference.
 __global__ void k_weights(Geom g, uint32_t B, uint32_t size, float beta, float* __restrict__ w, uint32_t parity) {
+  __shared__ uint32_t s_min[4];
   const uint32_t t = blockIdx.y;
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  // every block folds the partial minima of this call (blockDim.x == kVminSlots)
+  const uint32_t* part = g.vmin + ((size_t)parity * g.T + t) * kVminSlots;
+  const uint32_t m = wave_min_u32(part[threadIdx.x]);
+  if ((threadIdx.x & 63u) == 0) s_min[threadIdx.x >> 6] = m;
+  // and the first block re-arms the other buffer for the next call that wants weights
+  if (blockIdx.x == 0) g.vmin[((size_t)(parity ^ 1u) * g.T + t) * kVminSlots + threadIdx.x] = 0x7F800000u;
+  __syncthreads();
   if (i >= B) return;
-  const float total = g.level[g.H][(size_t)t * g.stride[g.H]];
+  const float total = g.root[(size_t)t * g.root_stride];
   const size_t o = (size_t)t * B + i;
   if (!(total > 0.0f)) { w[o] = 0.0f; return; }
-  const double nb = -(double)beta;
-  const double scale = (double)size / (double)total;
-  const double vmin = (double)__uint_as_float(g.vmin[parity * g.T + t]);
-  const double wt = pow(scale * (double)w[o], nb);
-  const double wm = pow(scale * vmin, nb);
-  w[o] = (float)(wt / wm);
+  const uint32_t m01 = s_min[0] < s_min[1] ? s_min[0] : s_min[1];
+  const uint32_t m23 = s_min[2] < s_min[3] ? s_min[2] : s_min[3];
+  w[o] = importance_weight(w[o], __uint_as_float(m01 < m23 ? m01 : m23), total, size, beta);
 }
+
+template <int LOGK>
+static hipError_t launch_resum_top_k(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
 
 template <int LOGK>
 static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
                                   const float* u, uint32_t* out_idx, float* out_w, float* out_prio,
-                                  uint32_t parity, hipStream_t s) {
+                                  uint32_t* weight_calls, uint32_t stale_hb, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
-  constexpr int LPS = Fan<LOGK>::LPS;
-  // lowest height whose levels (that height and all above, below the root) fit the LDS budget
-  uint32_t h_lds = g.H;
-  uint64_t bytes = 0;
-  for (int l = (int)g.H - 1; l >= 0; --l) {
+  constexpr uint32_t kLdsCap = 128 * 1024;
+  const uint32_t wave_bytes = LOGK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
+  // topmost heights (below the root) that fit the LDS budget, at most kTopSlots of them
+  TopCopy tc{};
+  uint64_t top = 0;
+  for (int l = (int)g.H - 1; l >= 0 && tc.nslots < (uint32_t)kTopSlots; --l) {
     const uint64_t add = (uint64_t)g.n[l + 1] * K * 4;
-    if (bytes + add > tn.lds_budget_bytes) break;
-    bytes += add;
-    h_lds = (uint32_t)l;
+    if (top + add > tn.lds_budget_bytes || top + add + wave_bytes > kLdsCap) break;
+    top += add;
+    const uint32_t i = tc.nslots++;
+    tc.ptr[i] = g.level[l];
+    tc.stride[i] = g.stride[l];
+    tc.cnt[i] = g.n[l + 1] * K;
+    tc.nreal[i] = g.n[l];
   }
-  const uint32_t block = tn.sample_block;
-  const uint64_t threads = (uint64_t)B * LPS;
-  const uint32_t gx = (uint32_t)((threads + block - 1) / block);
+  tc.root = g.root;
+  tc.root_stride = g.root_stride;
+  uint32_t max_waves = wave_bytes ? (uint32_t)((kLdsCap - top) / wave_bytes) : 16u;
+  if (max_waves > 16) max_waves = 16;
+  uint32_t waves = tn.sample_block / 64;
+  const uint32_t need = (B + 63) / 64;
+  if (need <= max_waves) waves = need;          // whole batch in one block per tree: weights are finished in-kernel
+  if (waves > max_waves) waves = max_waves;
+  const uint32_t block = waves * 64;
+  const uint32_t gx = (B + block - 1) / block;
+  const size_t bytes = (size_t)top + (size_t)waves * wave_bytes;
+  // The two buffers of partial minima alternate between the calls that use them (k_weights of
+  // one call re-arms the buffer of the next).
+  const uint32_t parity = *weight_calls & 1u;
+  if (out_w && gx > 1) ++*weight_calls;
   hipError_t e;
+  int stale = -1;
+  if (stale_hb) {
+    // copied heights above stale_hb are rebuilt in LDS; the copy must reach down to stale_hb
+    const int lowest_copied = (int)g.H - (int)tc.nslots;
+    if (tc.nslots > 0 && lowest_copied <= (int)stale_hb) {
+      stale = (int)g.H - 1 - (int)stale_hb;
+    } else {
+      e = launch_resum_top_k<LOGK>(g, tn, stale_hb, s);
+      if (e != hipSuccess) return e;
+    }
+  }
   if (bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be requested per kernel
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sample<LOGK>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
   }
-  k_sample<LOGK><<<dim3(gx, g.T), dim3(block), (size_t)bytes, s>>>(g, B, u, out_idx, out_prio, out_w, parity, h_lds);
+  PER_LAUNCH(KID_SAMPLE, k_sample<LOGK>, dim3(gx, g.T), dim3(block), bytes, s, g, tc, B, size, beta, u, out_idx,
+             out_prio, out_w, parity, stale);
   e = hipGetLastError();
-  if (e != hipSuccess || !out_w) return e;
-  k_weights<<<dim3((B + 255) / 256, g.T), dim3(256), 0, s>>>(g, B, size, beta, out_w, parity);
+  if (e != hipSuccess || !out_w || gx == 1) return e;
+  static_assert(kVminSlots == 256, "k_weights folds one partial minimum per thread of a 256-thread block");
+  PER_LAUNCH(KID_WEIGHTS, k_weights, dim3((B + 255) / 256, g.T), dim3(256), 0, s, g, B, size, beta, out_w, parity);
   return hipGetLastError();
 }
 
@@ -324,8 +558,9 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   }
 
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
-                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t parity, hipStream_t s) {
-#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, parity, s)
+                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
+                         hipStream_t s) {
+#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, weight_calls, stale_hb, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }
@@ -398,7 +633,8 @@ hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, 
                          hipStream_t s) {
   if (ft.n_fields == 0) return hipSuccess;
   const uint32_t block = tn.gather_block;
-  k_rows<true><<<dim3(rows_grid_x(ft, B, block), ft.n_fields, g.T), dim3(block), 0, s>>>(ft, B, idx, 0, g.N, g.status);
+  PER_LAUNCH(KID_GATHER, k_rows<true>, dim3(rows_grid_x(ft, B, block), ft.n_fields, g.T), dim3(block), 0, s, ft, B,
+             idx, 0, g.N, g.status);
   return hipGetLastError();
 }
 
@@ -406,7 +642,8 @@ hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft,
                           hipStream_t s) {
   if (ft.n_fields == 0) return hipSuccess;
   const uint32_t block = tn.gather_block;
-  k_rows<false><<<dim3(rows_grid_x(ft, n, block), ft.n_fields, g.T), dim3(block), 0, s>>>(ft, n, nullptr, cursor, g.N, g.status);
+  PER_LAUNCH(KID_SCATTER, k_rows<false>, dim3(rows_grid_x(ft, n, block), ft.n_fields, g.T), dim3(block), 0, s, ft,
+             n, nullptr, cursor, g.N, g.status);
   return hipGetLastError();
 }
 
@@ -428,31 +665,10 @@ __global__ void k_resum_dense(Geom g, uint32_t h, uint32_t a, uint32_t count) {
   if (active && q == 0) g.level[h][(size_t)t * g.stride[h] + node] = sum;
 }
 
-// Recompute, for every valid update element, its ancestor at height h.  Duplicated
-// ancestors are recomputed to the same bits by several groups, which is harmless.
-template <int LOGK>
-__global__ void k_resum_sparse(Geom g, uint32_t h, uint32_t B, uint32_t size, const uint32_t* __restrict__ idx,
-                               const float* __restrict__ prio) {
-  constexpr int K = Fan<LOGK>::K;
-  constexpr int LPS = Fan<LOGK>::LPS;
-  const uint32_t t = blockIdx.y;
-  const uint32_t gt = blockIdx.x * blockDim.x + threadIdx.x;
-  const uint32_t e = gt / LPS;
-  const unsigned q = gt % LPS;
-  const uint32_t ec = e < B ? e : B - 1;
-  const uint32_t i = idx[(size_t)t * B + ec];
-  const bool ok = e < B && i < size && valid_priority(prio[(size_t)t * B + ec]);
-  const uint32_t node = ok ? shr64(i, h * LOGK) : 0u;
-  const float sum = group_sum<LOGK>(g.level[h - 1] + (size_t)t * g.stride[h - 1] + (size_t)node * K, q);
-  if (ok && q == 0) g.level[h][(size_t)t * g.stride[h] + node] = sum;
-}
-
-// One workgroup per tree finishes heights h_start .. H.  Heights <= sparse_hi are done per
-// update element (idx != null), the others densely over the node ranges in r (given at
+// One workgroup per tree finishes heights h_start .. H over the node ranges in r (given at
 // height h_start and narrowed by K per height).
 template <int LOGK>
-__global__ void k_resum_tail(Geom g, uint32_t h_start, Range2 r, const uint32_t* __restrict__ idx,
-                             const float* __restrict__ prio, uint32_t B, uint32_t size, uint32_t sparse_hi) {
+__global__ void k_resum_tail(Geom g, uint32_t h_start, Range2 r) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   const uint32_t t = blockIdx.x;
@@ -462,26 +678,14 @@ __global__ void k_resum_tail(Geom g, uint32_t h_start, Range2 r, const uint32_t*
   for (uint32_t h = h_start; h <= g.H; ++h) {
     const float* child = g.level[h - 1] + (size_t)t * g.stride[h - 1];
     float* par = g.level[h] + (size_t)t * g.stride[h];
-    if (idx != nullptr && h <= sparse_hi) {
-      for (uint32_t base = 0; base < B; base += ngrp) {
+    for (int part = 0; part < 2; ++part) {
+      const uint32_t a = part ? r.a1 : r.a0, b = part ? r.b1 : r.b0;
+      for (uint32_t base = a; base < b; base += ngrp) {
         const uint32_t e = base + grp;
-        const uint32_t ec = e < B ? e : B - 1;
-        const uint32_t i = idx[(size_t)t * B + ec];
-        const bool ok = e < B && i < size && valid_priority(prio[(size_t)t * B + ec]);
-        const uint32_t node = ok ? shr64(i, h * LOGK) : 0u;
+        const bool ok = e < b;
+        const uint32_t node = ok ? e : a;
         const float sum = group_sum<LOGK>(child + (size_t)node * K, q);
         if (ok && q == 0) par[node] = sum;
-      }
-    } else {
-      for (int part = 0; part < 2; ++part) {
-        const uint32_t a = part ? r.a1 : r.a0, b = part ? r.b1 : r.b0;
-        for (uint32_t base = a; base < b; base += ngrp) {
-          const uint32_t e = base + grp;
-          const bool ok = e < b;
-          const uint32_t node = ok ? e : a;
-          const float sum = group_sum<LOGK>(child + (size_t)node * K, q);
-          if (ok && q == 0) par[node] = sum;
-        }
       }
     }
     __syncthreads();
@@ -509,16 +713,32 @@ static hipError_t launch_resum_ranges_k(const Geom& g, const Tuning& tn, Range2 
       const uint32_t a = part ? r.a1 : r.a0, b = part ? r.b1 : r.b0;
       if (b <= a) continue;
       const uint64_t threads = (uint64_t)(b - a) * LPS;
-      k_resum_dense<LOGK><<<dim3((uint32_t)((threads + block - 1) / block), g.T), dim3(block), 0, s>>>(g, h, a, b - a);
+      PER_LAUNCH(KID_RESUM_DENSE, k_resum_dense<LOGK>, dim3((uint32_t)((threads + block - 1) / block), g.T),
+                 dim3(block), 0, s, g, h, a, b - a);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
   }
   if (h <= g.H) {
-    k_resum_tail<LOGK><<<dim3(g.T), dim3(1024), 0, s>>>(g, h, r, nullptr, nullptr, 0, 0, 0);
+    PER_LAUNCH(KID_RESUM_TAIL, k_resum_tail<LOGK>, dim3(g.T), dim3(1024), 0, s, g, h, r);
     return hipGetLastError();
   }
   return hipSuccess;
+}
+
+// Recompute every node above height hb (after an update that left them stale).
+template <int LOGK>
+static hipError_t launch_resum_top_k(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s) {
+  if (hb >= g.H) return hipSuccess;
+  Range2 r{0, g.n[hb + 1], 0, 0};
+  PER_LAUNCH(KID_RESUM_TAIL, k_resum_tail<LOGK>, dim3(g.T), dim3(1024), 0, s, g, hb + 1, r);
+  return hipGetLastError();
+}
+
+hipError_t launch_resum_top(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s) {
+#define CALL(L) launch_resum_top_k<L>(g, tn, hb, s)
+  PER_DISPATCH_LOGK(g.logK, CALL)
+#undef CALL
 }
 
 hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipStream_t s) {
@@ -555,24 +775,26 @@ __global__ void k_insert_leaves(Geom g, uint32_t n, uint32_t cursor, const float
     }
   }
   if (prio) {
-    mx = wave_max_u32(mx);
-    if ((threadIdx.x & 63u) == 0 && mx != 0) atomicMax(reinterpret_cast<uint32_t*>(&g.max_v[t]), mx);
+    raise_max(g, t, mx);
     if (bad) atomicOr(&g.status[t], 2u);
   }
 }
 
 hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uint32_t cursor, const float* prio,
                                 uint32_t* out_idx, hipStream_t s) {
-  (void)tn;
-  k_insert_leaves<<<dim3((n + 255) / 256, g.T), dim3(256), 0, s>>>(g, n, cursor, prio, out_idx);
+  PER_LAUNCH(KID_INSERT_LEAVES, k_insert_leaves, dim3((n + 255) / 256, g.T), dim3(256), 0, s, g, n, cursor, prio,
+             out_idx);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------
-// priority update: claim (last writer), leaf write, re-summation
+// priority update: claim (last writer), then one tree pass
 // ---------------------------------------------------------------------------------
-// Element j stamps its leaf with stamp_base + j by atomic max.  Stamps grow from call to
-// call, so stale stamps never win and the array needs no clearing between calls.
+// Claim: element j raises the 64-bit stamp of its leaf to (stamp_base + j) << 32 | value bits
+// by atomic max, and flags the leaf's parent as dirty.  The largest j wins and carries its
+// value with it.  Stamps grow from call to call, so stale stamps never win and the stamp
+// array needs no clearing between calls.
+template <int LOGK>
 __global__ void k_update_claim(Geom g, uint32_t B, uint32_t size, const uint32_t* __restrict__ idx,
                                const float* __restrict__ prio, uint32_t stamp_base) {
   const uint32_t t = blockIdx.y;
@@ -585,59 +807,237 @@ __global__ void k_update_claim(Geom g, uint32_t B, uint32_t size, const uint32_t
     if (!(i < size)) flags = 1u;
     else if (!valid_priority(v)) flags = 2u;
     else {
-      atomicMax(&g.owner[(size_t)t * g.owner_stride + i], stamp_base + j);
+      const unsigned long long stamp = ((unsigned long long)(stamp_base + j) << 32) | __float_as_uint(v);
+      atomicMax(reinterpret_cast<unsigned long long*>(g.owner) + (size_t)t * g.owner_stride + i, stamp);
+      g.dirty[(size_t)t * g.dirty_stride + (i >> LOGK)] = 1;
       mx = v > 0.0f ? __float_as_uint(v) : 0u;
     }
   }
-  mx = wave_max_u32(mx);
-  if ((threadIdx.x & 63u) == 0 && mx != 0) atomicMax(reinterpret_cast<uint32_t*>(&g.max_v[t]), mx);
+  raise_max(g, t, mx);
   if (flags) atomicOr(&g.status[t], flags);
 }
 
-__global__ void k_update_write(Geom g, uint32_t B, uint32_t size, const uint32_t* __restrict__ idx,
-                               const float* __restrict__ prio, uint32_t stamp_base) {
+// Heights 1 .. hb of the tree pass at fixed kernel-argument offsets (slot j = height j + 1).
+constexpr int kSubSlots = 13;
+struct SubLevels {
+  float* ptr[kSubSlots];          // that height of tree 0
+  uint32_t stride[kSubSlots];     // floats between trees
+  uint32_t n[kSubSlots];          // real nodes of that height
+  uint32_t lds_off[kSubSlots];    // where the workgroup keeps its part of that height (floats)
+  uint32_t lds_floats;            // total
+  uint32_t hb;
+};
+
+// Tree pass.  Workgroup b of tree t owns the subtree under node b of height hb and keeps the
+// subtree's nodes of heights 1 .. hb in LDS.
+//  0. In one trip it fetches its height-1 nodes and their dirty flags (and clears the flags).
+//  1. Each dirty height-1 node is rebuilt by LPS lanes: they read its K leaves and their K
+//     stamps; a stamp whose upper word lies in [stamp_base, stamp_base + B) belongs to the
+//     batch element that won that leaf, and its lower word is the new value, which replaces
+//     the leaf (and is stored); the K values are summed pairwise.
+//  2. Heights 2 .. hb of the subtree are recomputed from LDS and stored.
+//  3. Above hb every node counts the arrivals of its children's workgroups; the last one to
+//     arrive recomputes it and carries on upwards, so the root is written by whichever
+//     workgroup finishes last.  No workgroup ever waits for another.  When there are only a
+//     few nodes at height hb this step is skipped (chain == 0): the agent-scope fences it
+//     needs cost more than recomputing those heights in the next kernel that reads them.
+constexpr uint32_t kDirtyListCap = 4096;
+constexpr uint32_t kLazyTopNodes = 4096;
+
+template <int LOGK>
+__global__ void __launch_bounds__(1024)
+k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t chain) {
+  constexpr int K = Fan<LOGK>::K;
+  constexpr int LPS = Fan<LOGK>::LPS;
+  extern __shared__ __attribute__((aligned(16))) float sub[];   // 16-byte LDS accesses need the alignment
+  __shared__ uint32_t s_list[kDirtyListCap];
+  __shared__ uint32_t s_count;
+  __shared__ uint32_t s_last;
   const uint32_t t = blockIdx.y;
-  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= B) return;
-  const uint32_t i = idx[(size_t)t * B + j];
-  const float v = prio[(size_t)t * B + j];
-  if (i < size && valid_priority(v) && g.owner[(size_t)t * g.owner_stride + i] == stamp_base + j)
-    g.level[0][(size_t)t * g.stride[0] + i] = v;
+  const uint32_t b = blockIdx.x;
+  const uint32_t hb = sl.hb;
+  const unsigned lane = threadIdx.x & 63u;
+  const unsigned q = threadIdx.x % LPS;
+  const uint32_t grp = threadIdx.x / LPS;
+  const uint32_t ngrp = blockDim.x / LPS;
+
+  PER_MARK(0);
+  // ---- 0. this subtree's height-1 nodes and their dirty flags
+  const uint32_t sh1 = (hb - 1) * LOGK;
+  const uint32_t n1 = sl.n[0];
+  const uint32_t n1_pad = (n1 + K - 1) / K * K;
+  const uint32_t lo1 = b << sh1;
+  const uint32_t hi1 = min(n1, (b + 1) << sh1);
+  float* lvl1 = sl.ptr[0] + (size_t)t * sl.stride[0];
+  uint8_t* dirty = g.dirty + (size_t)t * g.dirty_stride;
+  if (threadIdx.x == 0) s_count = 0;
+  // four flags per thread; the first word is fetched together with the height-1 nodes
+  const uint32_t w_first = lo1 + 4 * threadIdx.x;
+  uint32_t bits_first = 0;
+  if (w_first < hi1) bits_first = *reinterpret_cast<const uint32_t*>(dirty + w_first);
+  for (uint32_t i = threadIdx.x; i < sl.lds_floats; i += blockDim.x) {
+    const uint32_t gi = lo1 + i;
+    sub[i] = (i < sl.lds_off[1] || hb == 1) && gi < n1_pad ? lvl1[gi] : 0.0f;   // slot 0 from memory, the rest zero
+  }
+  __syncthreads();
+  for (uint32_t w0 = lo1; w0 < hi1; w0 += 4 * blockDim.x) {
+    const uint32_t w = w0 + 4 * threadIdx.x;
+    uint32_t bits = 0;
+    if (w0 == lo1) bits = bits_first;
+    else if (w < hi1) bits = *reinterpret_cast<const uint32_t*>(dirty + w);
+    if (bits) {
+      *reinterpret_cast<uint32_t*>(dirty + w) = 0;
+      const uint32_t cnt = ((bits & 0xFFu) != 0) + ((bits & 0xFF00u) != 0) + ((bits & 0xFF0000u) != 0) + ((bits >> 24) != 0);
+      uint32_t at = atomicAdd(&s_count, cnt);
+#pragma unroll
+      for (uint32_t k = 0; k < 4; ++k)
+        if ((bits >> (8 * k)) & 0xFFu) s_list[at++] = w + k;
+    }
+  }
+  __syncthreads();
+  const uint32_t nd = s_count;
+  PER_MARK(1);
+
+  if (nd > 0) {
+    // ---- 1. rebuild the dirty height-1 nodes (list order is irrelevant: nodes are independent)
+    float* leaves = g.level[0] + (size_t)t * g.stride[0];
+    const uint2* owner = reinterpret_cast<const uint2*>(g.owner) + (size_t)t * g.owner_stride;   // (value, stamp)
+    for (uint32_t base = 0; base < nd; base += ngrp) {
+      const uint32_t item = base + grp;
+      const bool ok = item < nd;
+      const uint32_t node = s_list[ok ? item : nd - 1];
+      float sum;
+      if constexpr (LOGK == 1) {
+        float2 c = *reinterpret_cast<const float2*>(leaves + (size_t)node * 2);
+        const uint4 o = *reinterpret_cast<const uint4*>(owner + (size_t)node * 2);
+        const bool w0 = o.y - stamp_base < B, w1 = o.w - stamp_base < B;
+        if (w0) c.x = __uint_as_float(o.x);
+        if (w1) c.y = __uint_as_float(o.z);
+        if (ok && (w0 || w1)) *reinterpret_cast<float2*>(leaves + (size_t)node * 2) = c;
+        sum = c.x + c.y;
+      } else {
+        const size_t at = (size_t)node * K + 4 * q;
+        float4 c = *reinterpret_cast<const float4*>(leaves + at);
+        const uint4 oa = *reinterpret_cast<const uint4*>(owner + at);
+        const uint4 ob = *reinterpret_cast<const uint4*>(owner + at + 2);
+        const bool w0 = oa.y - stamp_base < B, w1 = oa.w - stamp_base < B;
+        const bool w2 = ob.y - stamp_base < B, w3 = ob.w - stamp_base < B;
+        if (w0) c.x = __uint_as_float(oa.x);
+        if (w1) c.y = __uint_as_float(oa.z);
+        if (w2) c.z = __uint_as_float(ob.x);
+        if (w3) c.w = __uint_as_float(ob.z);
+        if (ok && (w0 || w1 || w2 || w3)) *reinterpret_cast<float4*>(leaves + at) = c;
+        sum = (c.x + c.y) + (c.z + c.w);
+#pragma unroll
+        for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) sum = sum + __shfl_xor(sum, 1 << k);
+      }
+      if (ok && q == 0) {
+        lvl1[node] = sum;
+        sub[node - lo1] = sum;
+      }
+    }
+    PER_MARK(2);
+    // ---- 2. heights 2 .. hb of this subtree, from LDS
+#pragma unroll
+    for (int j = 1; j < kSubSlots; ++j) {
+      if ((uint32_t)j < hb) {
+        __syncthreads();
+        const uint32_t sh = (hb - 1 - (uint32_t)j) * LOGK;
+        const uint32_t a = b << sh;
+        const uint32_t cnt = min(sl.n[j], (b + 1) << sh) - a;   // real nodes of this height in the subtree
+        float* par = sl.ptr[j] + (size_t)t * sl.stride[j];
+        for (uint32_t base = 0; base < cnt; base += ngrp) {
+          const uint32_t e = base + grp;
+          const bool ok = e < cnt;
+          const float sum = group_sum<LOGK>(sub + sl.lds_off[j - 1] + (size_t)(ok ? e : 0u) * K, q);
+          if (ok && q == 0) {
+            par[a + e] = sum;
+            sub[sl.lds_off[j] + e] = sum;
+          }
+        }
+      }
+    }
+  }
+
+  PER_MARK(3);
+  // ---- 3. above the subtree: the last child to arrive recomputes the parent
+  if (!chain) return;   // the heights above hb are left to their next reader
+  uint32_t node = b;
+  for (uint32_t h = hb + 1; h <= g.H; ++h) {
+    const uint32_t parent = node >> LOGK;
+    const uint32_t nchild = min((uint32_t)K, g.n[h - 1] - parent * K);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      __threadfence();   // this workgroup's node writes are visible before its arrival is counted
+      uint32_t* cnt = g.arrive + (size_t)t * g.arrive_stride + g.arrive_off[h] + parent;
+      const uint32_t old = atomicAdd(cnt, 1u);
+      const bool last = old == nchild - 1;
+      if (last) *cnt = 0;   // ready for the next call
+      s_last = last ? 1u : 0u;
+      __threadfence();   // and the siblings' writes are visible to the reads below
+    }
+    __syncthreads();
+    if (!s_last) return;
+    if (threadIdx.x < 64) {
+      const float sum = group_sum<LOGK>(g.level[h - 1] + (size_t)t * g.stride[h - 1] + (size_t)parent * K, lane % LPS);
+      if (lane == 0) g.level[h][(size_t)t * g.stride[h] + parent] = sum;
+    }
+    node = parent;
+  }
+}
+
+// Height of the workgroup roots of the tree pass: the whole tree for small trees, else the
+// lowest height whose subtrees hold at least 64 height-1 nodes (so that dirty words are never
+// shared between workgroups).
+static uint32_t tree_pass_height(const Geom& g) {
+  if (g.n[1] <= kDirtyListCap) return g.H;
+  uint32_t hb = 1;
+  while (hb < g.H && (1ull << ((hb - 1) * g.logK)) < 64) ++hb;
+  return hb;
+}
+
+// Heights above this one may be left stale by an update (0: never).
+uint32_t lazy_top_height(const Geom& g, const Tuning& tn) {
+  const uint32_t hb = tree_pass_height(g);
+  return tn.lazy_top && hb < g.H && g.n[hb] <= kLazyTopNodes ? hb : 0u;
 }
 
 template <int LOGK>
 static hipError_t launch_update_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
                                   const float* prio, uint32_t stamp_base, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
-  constexpr int LPS = Fan<LOGK>::LPS;
   const uint32_t block = tn.update_block;
   hipError_t e;
-  k_update_claim<<<dim3((B + block - 1) / block, g.T), dim3(block), 0, s>>>(g, B, size, idx, prio, stamp_base);
+  PER_LAUNCH(KID_UPDATE_CLAIM, k_update_claim<LOGK>, dim3((B + block - 1) / block, g.T), dim3(block), 0, s, g, B, size,
+             idx, prio, stamp_base);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  k_update_write<<<dim3((B + block - 1) / block, g.T), dim3(block), 0, s>>>(g, B, size, idx, prio, stamp_base);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-
-  // heights with fewer update elements than nodes are re-summed per element, the rest densely
-  uint32_t sparse_hi = 0;
-  for (uint32_t h = 1; h <= g.H; ++h)
-    if (B < g.n[h]) sparse_hi = h;
-  uint32_t h = 1;
-  for (; h <= g.H; ++h) {
-    const bool sparse = h <= sparse_hi;
-    const uint64_t groups = sparse ? B : g.n[h];
-    if (groups * K <= kTailFloats) break;
-    const uint64_t threads = groups * LPS;
-    const dim3 grid((uint32_t)((threads + block - 1) / block), g.T);
-    if (sparse) k_resum_sparse<LOGK><<<grid, dim3(block), 0, s>>>(g, h, B, size, idx, prio);
-    else k_resum_dense<LOGK><<<grid, dim3(block), 0, s>>>(g, h, 0, g.n[h]);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+  const uint32_t hb = tree_pass_height(g);
+  if (hb > (uint32_t)kSubSlots) return hipErrorInvalidValue;   // cannot happen for fanouts and capacities accepted at create
+  SubLevels sl{};
+  sl.hb = hb;
+  uint32_t off = 0;
+  for (uint32_t h = 1; h <= hb; ++h) {
+    const uint32_t j = h - 1;
+    sl.ptr[j] = g.level[h];
+    sl.stride[j] = g.stride[h];
+    sl.n[j] = g.n[h];
+    sl.lds_off[j] = off;
+    // nodes of this height under one workgroup root, padded to whole child groups
+    const uint64_t full = 1ull << ((hb - h) * LOGK);
+    const uint64_t padded = h < hb ? ((uint64_t)g.n[h] + K - 1) / K * K : 1;
+    off += (uint32_t)(full < padded ? full : padded);
   }
-  if (h <= g.H) {
-    Range2 r{0, g.n[h], 0, 0};
-    k_resum_tail<LOGK><<<dim3(g.T), dim3(1024), 0, s>>>(g, h, r, idx, prio, B, size, sparse_hi);
-    return hipGetLastError();
+  sl.lds_floats = off;
+  // enough lane groups to rebuild every height-1 node of a subtree in one sweep, unless told otherwise
+  uint32_t tblock = tn.tree_block;
+  if (tblock == 0) {
+    const uint64_t want = (uint64_t)sl.lds_off[hb > 1 ? 1 : 0] * Fan<LOGK>::LPS;
+    tblock = hb > 1 ? (uint32_t)(want > 1024 ? 1024 : (want + 63) / 64 * 64) : 64u;
+    if (tblock < 64) tblock = 64;
   }
-  return hipSuccess;
+  PER_LAUNCH(KID_UPDATE_TREE, k_update_tree<LOGK>, dim3(g.n[hb], g.T), dim3(tblock), (size_t)off * 4, s, g, sl, B,
+             stamp_base, lazy_top_height(g, tn) ? 0u : 1u);
+  return hipGetLastError();
 }
 
 hipError_t launch_update(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
@@ -663,8 +1063,9 @@ __global__ void k_get_priority(Geom g, uint32_t n, const uint32_t* __restrict__ 
   }
 }
 
-hipError_t launch_get_priority(const Geom& g, uint32_t n, const uint32_t* idx, float* out, hipStream_t s) {
-  k_get_priority<<<dim3((n + 255) / 256, g.T), dim3(256), 0, s>>>(g, n, idx, out);
+hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out,
+                               hipStream_t s) {
+  PER_LAUNCH(KID_GET_PRIORITY, k_get_priority, dim3((n + 255) / 256, g.T), dim3(256), 0, s, g, n, idx, out);
   return hipGetLastError();
 }
 

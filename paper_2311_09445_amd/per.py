@@ -21,8 +21,8 @@ FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_gather",
     "per_update", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
-    "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_tuning",
-    "per_strerror",
+    "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
+    "per_profile", "per_profile_read", "per_strerror",
 ]
 
 
@@ -75,7 +75,11 @@ def _lib():
         "per_height": (u32, [vp]),
         "per_size": (u64, [vp]),
         "per_cursor": (u64, [vp]),
+        "per_set_ring": (C.c_int, [vp, u64, u64]),
         "per_set_tuning": (C.c_int, [vp, C.c_char_p, i64]),
+        "per_profile": (C.c_int, [vp, C.c_int]),
+        "per_profile_read": (C.c_int, [vp, u32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
+                                       C.POINTER(u64), C.POINTER(u32)]),
         "per_strerror": (C.c_char_p, [C.c_int]),
     }
     for name, (res, args) in sig.items():
@@ -276,5 +280,22 @@ class PrioritizedReplay:
     def cursor(self) -> int:
         return int(self.lib.per_cursor(self._h))
 
+    def set_ring(self, cursor: int, size: int):
+        """Host mirrors of a restored arena (checkpoint / resume)."""
+        self._check(self.lib.per_set_ring(self._h, int(cursor), int(size)), "per_set_ring")
+
     def set_tuning(self, name: str, value: int):
         self._check(self.lib.per_set_tuning(self._h, name.encode(), int(value)), "per_set_tuning")
+
+    def profile(self, enable: bool):
+        self._check(self.lib.per_profile(self._h, 1 if enable else 0), "per_profile")
+
+    def profile_read(self):
+        """{kernel name: (total ms, launches)} since profiling was last enabled."""
+        cap = 32
+        names = (C.c_char_p * cap)()
+        ms = (C.c_double * cap)()
+        cnt = (C.c_uint64 * cap)()
+        n = C.c_uint32(0)
+        self._check(self.lib.per_profile_read(self._h, cap, names, ms, cnt, C.byref(n)), "per_profile_read")
+        return {names[i].decode(): (ms[i], cnt[i]) for i in range(min(n.value, cap))}

@@ -182,19 +182,44 @@ def test_results_do_not_depend_on_tuning(K):
     leaves = wl._draw_priorities("pareto_1.5", rng, (1, N))
     u = wl.uniform01(rng, (1, B))
     ref = None
-    for lds, blk in [(0, 64), (4096, 256), (64 * 1024, 256), (96 * 1024, 1024), (160 * 1024, 512)]:
+    for lds, blk, lazy in [(0, 64, 1), (4096, 256, 0), (64 * 1024, 256, 1), (96 * 1024, 1024, 0), (160 * 1024, 512, 1)]:
         p = PrioritizedReplay(K, N)
         p.set_tuning("lds_budget_bytes", lds)
-        for name in ("sample_block", "update_block", "gather_block"):
+        p.set_tuning("lazy_top", lazy)
+        for name in ("sample_block", "update_block", "gather_block", "tree_block"):
             p.set_tuning(name, blk)
         p.insert(N, None, dev(leaves))
         i, w, v = p.sample(dev(u), 0.5)
-        p.update(i, dev(rng.random((1, B)).astype(np.float32) * 0 + 0.25))
-        out = [i.cpu().numpy().tobytes(), v.cpu().numpy().tobytes(), w.cpu().numpy().tobytes()] + \
+        p.update(i, dev(np.full((1, B), 0.25, np.float32)))
+        i2, w2, v2 = p.sample(dev(u), 0.5)          # reads the tree the update left behind
+        p.update(i2, dev(np.full((1, B), 0.75, np.float32)))
+        out = [x.cpu().numpy().tobytes() for x in (i, v, w, i2, v2, w2)] + \
               [p.read_level(0, h).cpu().numpy().tobytes() for h in range(p.H + 1)]
         if ref is None:
             ref = out
         assert out == ref, (lds, blk)
+
+
+@pytest.mark.parametrize("K,N", [(2, (1 << 20) + 77), (8, 3 << 20), (16, 1 << 16)])
+def test_update_sample_chain(K, N):
+    """Update -> sample -> update -> insert chains, on trees large enough that the update finishes the
+    top heights itself (K = 2, 8) and on one where it leaves them to the next reader (K = 16)."""
+    log(f"chain K={K} N={N}")
+    rng = np.random.default_rng(N + K)
+    m = Mirror(K, N, 1, ())
+    m.insert(N, prio=wl._draw_priorities("exponential_1", rng, (1, N)), with_rows=False)
+    for it in range(3):
+        B = 2000
+        idx = rng.integers(0, N, (1, B)).astype(np.uint32)
+        m.update(idx, rng.random((1, B)).astype(np.float32))
+        gi, ci = m.sample(wl.uniform01(rng, (1, 777)), 0.4)
+        m.update(ci, rng.random((1, 777)).astype(np.float32))
+        if it == 1:
+            m.compare_tree()
+        m.update(idx, rng.random((1, B)).astype(np.float32))     # two updates in a row
+        m.insert(100)                                             # insert right after an update
+        m.compare_tree()
+    m.compare_status()
 
 
 def test_sampling_frequency_on_gpu():

@@ -43,7 +43,7 @@ def test_arena_size_covers_tree_and_payload(name):
         if n == 1:
             break
         n = -(-n // w.K)
-    need = w.T * (tree + w.N * 4 + w.N * w.row_bytes)      # levels + last-writer stamps + rows
+    need = w.T * (tree + w.N * 8 + w.N * w.row_bytes)      # levels + last-writer stamps + rows
     assert need <= nbytes <= need * 1.02 + (1 << 20)
 
 
