@@ -40,6 +40,10 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the oracle leg (0: skip)")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps eagerly instead of as one HIP graph")
+    ap.add_argument("--separate-gather", action="store_true",
+                    help="call per_sample and per_gather separately instead of the fused per_sample_gather")
+    ap.add_argument("--overlap", action="store_true",
+                    help="with --separate-gather: run the row gather on a second stream beside the update")
     ap.add_argument("--tune", action="append", default=[], help="name=value passed to per_set_tuning")
     return ap.parse_args()
 
@@ -126,12 +130,33 @@ def main():
         d_dst = torch.from_numpy(np.stack([i["dup_dst"] for i in inputs])).cuda()
         d_src = torch.from_numpy(np.stack([i["dup_src"] for i in inputs])).cuda()
 
-    def step(s, recording=False):
+    side = torch.cuda.Stream()
+    gather_done = [None]
+    fused = not args.separate_gather
+
+    def step(s, recording=False, overlap=False):
+        """insert -> sample -> gather -> update.  With overlap the row gather (which only reads the
+        sampled indices and the payload) runs on a second stream beside the update, as the paper's
+        runtime overlaps data movement with the replay operations; the tree work stays in order."""
+        main = torch.cuda.current_stream()
         if w.n_insert:
+            if overlap and gather_done[0] is not None:
+                main.wait_event(gather_done[0])      # an insert may overwrite a row the last gather reads
             buf.insert(w.n_insert, ins_rows[s])
         buf.sample(d_u[s], inputs[s]["beta"], want_weights=w.weights, want_prio=True,
-                   out_idx=d_idx[s], out_weight=d_w, out_prio=d_v)
-        buf.gather(d_idx[s], d_rows)
+                   out_idx=d_idx[s], out_weight=d_w, out_prio=d_v, rows_out=d_rows if fused else None)
+        if fused:
+            pass
+        elif overlap:
+            sampled = torch.cuda.Event()
+            sampled.record(main)
+            with torch.cuda.stream(side):
+                side.wait_event(sampled)
+                buf.gather(d_idx[s], d_rows)
+                gather_done[0] = torch.cuda.Event()
+                gather_done[0].record(side)
+        else:
+            buf.gather(d_idx[s], d_rows)
         if recording:     # synthesise this step's update indices (input generation, untimed pass only)
             d_upd_idx[s].copy_(d_idx[s])
             if has_dup:
@@ -172,6 +197,8 @@ def main():
     if restore_ok:
         restore()
     stream = torch.cuda.current_stream()
+    overlap = args.overlap and not fused
+    gather_done[0] = None
     for s in range(warmup):
         step(s)
     torch.cuda.synchronize()
@@ -180,7 +207,9 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for s in range(warmup, total_steps):
-                step(s)
+                step(s, overlap=overlap)
+            if overlap:
+                torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -189,7 +218,9 @@ def main():
         graph.replay()
     else:
         for s in range(warmup, total_steps):
-            step(s)
+            step(s, overlap=overlap)
+        if overlap:
+            stream.wait_stream(side)
     ev1.record(stream)
     torch.cuda.synchronize()
     ms_total = ev0.elapsed_time(ev1)
@@ -220,7 +251,7 @@ def main():
     kern_ms = {k: v[0] / max(1, v[1]) for k, v in kernels.items()}
     kern_per_step = {k: v[1] / steps for k, v in kernels.items()}
     dominant = max(kernels, key=lambda k: kernels[k][0])
-    alg = {"k_sample": a_sample, "k_rows_gather": a_gather}
+    alg = {"k_sample": a_sample, "k_rows_gather": a_gather, "k_rows_gather_weights": a_gather}
     dom_bytes = alg.get(dominant)
     if dom_bytes is None:   # an update kernel: attribute the whole update phase's bytes to its launches per step
         dom_bytes = a_update / max(1.0, sum(v for k, v in kern_per_step.items()
@@ -271,7 +302,8 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "K": K, "N": N, "T": T, "B": B, "row_bytes": w.row_bytes,
-                   "insert_per_step": w.n_insert, "launch": "hip_graph" if graph is not None else "eager"},
+                   "insert_per_step": w.n_insert, "launch": "hip_graph" if graph is not None else "eager",
+                   "streams": 2 if overlap else 1, "sample_and_gather": "fused" if fused else "separate"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "step_algorithmic_bytes": int(a_step),

@@ -106,6 +106,13 @@ int per_sample(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_o
  *                 a NULL entry skips that column. */
 int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field_dst, void* stream);
 
+/* per_sample followed by per_gather of the sampled indices, as one call (the paper's mode where
+ * Replay Manager and consumer share a device, Section IV-A "setting 2"): the kernel that reads
+ * the rows also finishes the importance weights, which saves a launch on the critical path.
+ * Same arguments and results as the two separate calls. */
+int per_sample_gather(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx,
+                      float* d_out_weight, float* d_out_prio, void* const* d_field_dst, void* stream);
+
 /* Priority update (Section V-A), in the set-and-re-sum form: every valid element sets its
  * leaf; when an index occurs more than once the element latest in the batch wins;
  * afterwards every ancestor of a touched leaf equals the pairwise sum of its children.

@@ -197,6 +197,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.gather_block = 256;
   p->tn.tree_block = 0;   // chosen per launch
   p->tn.lazy_top = 1;
+  p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->stamp_next = 1;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
@@ -246,8 +247,8 @@ int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float
   return hip_rc(e);
 }
 
-int per_sample(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
-               float* d_out_prio, void* stream) {
+static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
+                       float* d_out_prio, void* const* d_field_dst, void* stream) {
   if (!p) return PER_EINVAL;
   if (B == 0) return PER_OK;
   if (!d_u || !d_out_idx || misaligned(d_u, 4) || misaligned(d_out_idx, 4) || misaligned(d_out_weight, 4) ||
@@ -256,10 +257,23 @@ int per_sample(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_o
   if (!isfinite(beta) || beta < 0.0f) return PER_EINVAL;
   if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
   if (p->size == 0) return PER_EEMPTY;
+  FieldTable ft;
+  const bool fused = d_field_dst && fill_fields(p, d_field_dst, &ft);
   const uint32_t stale = p->stale_hb;
   p->stale_hb = 0;   // the sampling kernel rebuilds and stores the stale heights
   return hip_rc(launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, d_out_idx, d_out_weight, d_out_prio,
-                              &p->weight_calls, stale, static_cast<hipStream_t>(stream)));
+                              &p->weight_calls, stale, fused ? &ft : nullptr, static_cast<hipStream_t>(stream)));
+}
+
+int per_sample(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
+               float* d_out_prio, void* stream) {
+  return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, nullptr, stream);
+}
+
+int per_sample_gather(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
+                      float* d_out_prio, void* const* d_field_dst, void* stream) {
+  if (!d_field_dst) return PER_EINVAL;
+  return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, stream);
 }
 
 int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field_dst, void* stream) {
@@ -357,6 +371,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "lds_budget_bytes")) {
     if (value < 0 || value > 160 * 1024) return PER_EINVAL;
     p->tn.lds_budget_bytes = (uint32_t)value;
+    return PER_OK;
+  }
+  if (!strcmp(name, "sample_min_lds")) {
+    if (value < 0 || value > 160 * 1024) return PER_EINVAL;
+    p->tn.sample_min_lds = (uint32_t)value;
     return PER_OK;
   }
   if (!strcmp(name, "lazy_top")) {

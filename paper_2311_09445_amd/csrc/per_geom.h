@@ -50,7 +50,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 
 // Optional per-kernel timing with HIP events on the launch stream (off by default).
 enum KernelId {
-  KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
+  KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_GATHER_WEIGHTS, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_GET_PRIORITY, KID_COUNT
 };
 const char* kernel_name(int kid);
@@ -76,6 +76,7 @@ struct ProfScope {              // records an event pair around one launch when 
 struct Tuning {
   uint32_t lds_budget_bytes;
   uint32_t sample_block, update_block, gather_block, tree_block;
+  uint32_t sample_min_lds;   // lower bound of the sampling kernel's LDS request, bytes
   uint32_t lazy_top;   // updates may leave the few topmost heights to their next reader
   Profiler* prof;
 };
@@ -85,7 +86,7 @@ hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
-                         hipStream_t s);
+                         const FieldTable* rows, hipStream_t s);
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s);
 hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t n, uint32_t cursor,

@@ -19,7 +19,7 @@ namespace per {
 // ---------------------------------------------------------------------------------
 const char* kernel_name(int kid) {
   static const char* const names[KID_COUNT] = {
-      "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_rows_scatter", "k_insert_leaves",
+      "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_rows_gather_weights", "k_rows_scatter", "k_insert_leaves",
       "k_resum_dense", "k_resum_tail", "k_update_claim", "k_update_tree", "k_get_priority"};
   return kid >= 0 && kid < KID_COUNT ? names[kid] : "?";
 }
@@ -70,12 +70,23 @@ ProfScope::~ProfScope() {
 // optional in-kernel time stamps (development builds with -DPER_TRACE only)
 // ---------------------------------------------------------------------------------
 #ifdef PER_TRACE
+// Time stamps are kept in registers and stored when the kernel ends, so that taking them does
+// not add memory traffic (or waits for it) to the phases being timed.
 constexpr int kTraceMarks = 16, kTraceBlocks = 2048;
 __device__ unsigned long long g_trace[kTraceBlocks * kTraceMarks];
-#define PER_MARK(i)                                                                            \
+#define PER_TRACE_DECL unsigned long long tm_[kTraceMarks] = {}
+#define PER_MARK(i) do { tm_[(i)] = wall_clock64(); } while (0)
+#define PER_MARK_DYN(i)                                                                        \
   do {                                                                                         \
-    if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < kTraceBlocks)                      \
-      g_trace[blockIdx.x * kTraceMarks + (i)] = wall_clock64();                                \
+    const unsigned long long now_ = wall_clock64();                                            \
+    _Pragma("unroll") for (int k_ = 0; k_ < kTraceMarks; ++k_) if (k_ == (int)(i)) tm_[k_] = now_; \
+  } while (0)
+#define PER_FLUSH()                                                                            \
+  do {                                                                                         \
+    if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < kTraceBlocks) {                    \
+      _Pragma("unroll") for (int k_ = 0; k_ < kTraceMarks; ++k_)                               \
+        g_trace[blockIdx.x * kTraceMarks + k_] = tm_[k_];                                      \
+    }                                                                                          \
   } while (0)
 extern "C" int per_trace_read(unsigned long long* host, int clear) {
   if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(g_trace)) != hipSuccess) return -1;
@@ -86,7 +97,10 @@ extern "C" int per_trace_read(unsigned long long* host, int clear) {
   return kTraceBlocks * kTraceMarks;
 }
 #else
+#define PER_TRACE_DECL do { } while (0)
 #define PER_MARK(i) do { } while (0)
+#define PER_MARK_DYN(i) do { } while (0)
+#define PER_FLUSH() do { } while (0)
 #endif
 
 // ---------------------------------------------------------------------------------
@@ -322,6 +336,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   const unsigned wave = threadIdx.x >> 6;
   const int nslots = (int)tc.nslots;
 
+  PER_TRACE_DECL;
   PER_MARK(0);
   const uint32_t s_raw = blockIdx.x * blockDim.x + threadIdx.x;
   const bool active = s_raw < B;
@@ -363,14 +378,12 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
           const uint32_t nl = i >= 0 ? tc.nreal[i] : 1u;
           const uint32_t cnt = i >= 0 ? tc.cnt[i] : 0u;
           const uint32_t off_l = i >= 0 ? off[i] : 0u;
-          const uint32_t height = H - 1 - (uint32_t)i;
           for (uint32_t base = 0; base < nl; base += ngrp) {
             const uint32_t j = base + grp;
             const bool real = j < nl;
             const float sum = group_sum<LOGK>(lds + off[i + 1] + (size_t)(real ? j : 0u) * K, q);
             if (q == 0 && real) {
               if (i >= 0) lds[off_l + j] = sum; else s_total = sum;
-              if (blockIdx.x == 0) g.level[height][(size_t)t * g.stride[height] + j] = sum;
             }
           }
           for (uint32_t j = nl + threadIdx.x; j < cnt; j += blockDim.x) lds[off_l + j] = 0.0f;   // group padding
@@ -438,14 +451,26 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
       __builtin_amdgcn_wave_barrier();
     }
     node = node * K + child;
-    PER_MARK(4 + (l0 - l));
+    PER_MARK_DYN(4 + (l0 - l));
   }
 
   if (active) {
     out_idx[o] = node;
     if (out_prio) out_prio[o] = val;
   }
+  // Stores come last on purpose: on this hardware a wait for loaded data also waits for every
+  // earlier store of the wave.  The first workgroup of each tree puts the rebuilt heights back.
+  if (stale >= 0 && blockIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < kTopSlots; ++i)
+      if (i < stale) {
+        float* dst = g.level[H - 1 - (uint32_t)i] + (size_t)t * g.stride[H - 1 - (uint32_t)i];
+        for (uint32_t j = threadIdx.x; j < tc.nreal[i]; j += blockDim.x) dst[j] = lds[off[i] + j];
+      }
+    if (threadIdx.x == 0) g.root[(size_t)t * g.root_stride] = total;
+  }
   PER_MARK(12);
+  PER_FLUSH();
   if (!out_w) return;
   // Importance weights need the batch minimum of the sampled values.
   const uint32_t m = wave_min_u32(active ? __float_as_uint(val) : 0x7F800000u);
@@ -462,33 +487,46 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   }
 }
 
-__global__ void k_weights(Geom g, uint32_t B, uint32_t size, float beta, float* __restrict__ w, uint32_t parity) {
-  __shared__ uint32_t s_min[4];
-  const uint32_t t = blockIdx.y;
-  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  // every block folds the partial minima of this call (blockDim.x == kVminSlots)
+// Finishes the importance weights of tree t: folds the partial minima of this call, re-arms
+// the other buffer for the next call, and turns the sampled values left in w into weights.
+// Called by whole workgroups of any size; `first` marks the one that re-arms.
+__device__ __forceinline__ void weights_job(const Geom& g, uint32_t t, uint32_t B, uint32_t size, float beta,
+                                            float* __restrict__ w, uint32_t parity, uint32_t job_block,
+                                            uint32_t job_blocks) {
+  __shared__ uint32_t s_wmin[16];
+  if (job_block != 0 && job_block * blockDim.x >= B) return;   // nothing to do for this workgroup
   const uint32_t* part = g.vmin + ((size_t)parity * g.T + t) * kVminSlots;
-  const uint32_t m = wave_min_u32(part[threadIdx.x]);
-  if ((threadIdx.x & 63u) == 0) s_min[threadIdx.x >> 6] = m;
-  // and the first block re-arms the other buffer for the next call that wants weights
-  if (blockIdx.x == 0) g.vmin[((size_t)(parity ^ 1u) * g.T + t) * kVminSlots + threadIdx.x] = 0x7F800000u;
+  uint32_t m = 0x7F800000u;
+  for (uint32_t j = threadIdx.x; j < kVminSlots; j += blockDim.x) m = part[j] < m ? part[j] : m;
+  m = wave_min_u32(m);
+  if ((threadIdx.x & 63u) == 0) s_wmin[threadIdx.x >> 6] = m;
+  if (job_block == 0)
+    for (uint32_t j = threadIdx.x; j < kVminSlots; j += blockDim.x)
+      g.vmin[((size_t)(parity ^ 1u) * g.T + t) * kVminSlots + j] = 0x7F800000u;
   __syncthreads();
-  if (i >= B) return;
+  uint32_t mm = 0x7F800000u;
+  for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_wmin[wv] < mm ? s_wmin[wv] : mm;
   const float total = g.root[(size_t)t * g.root_stride];
-  const size_t o = (size_t)t * B + i;
-  if (!(total > 0.0f)) { w[o] = 0.0f; return; }
-  const uint32_t m01 = s_min[0] < s_min[1] ? s_min[0] : s_min[1];
-  const uint32_t m23 = s_min[2] < s_min[3] ? s_min[2] : s_min[3];
-  w[o] = importance_weight(w[o], __uint_as_float(m01 < m23 ? m01 : m23), total, size, beta);
+  for (uint32_t i = job_block * blockDim.x + threadIdx.x; i < B; i += job_blocks * blockDim.x) {
+    const size_t o = (size_t)t * B + i;
+    w[o] = total > 0.0f ? importance_weight(w[o], __uint_as_float(mm), total, size, beta) : 0.0f;
+  }
+}
+
+__global__ void k_weights(Geom g, uint32_t B, uint32_t size, float beta, float* __restrict__ w, uint32_t parity) {
+  weights_job(g, blockIdx.y, B, size, beta, w, parity, blockIdx.x, gridDim.x);
 }
 
 template <int LOGK>
 static hipError_t launch_resum_top_k(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
+static hipError_t launch_gather_weights(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B,
+                                        const uint32_t* idx, float* w, uint32_t size, float beta, uint32_t parity,
+                                        hipStream_t s);
 
 template <int LOGK>
 static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
                                   const float* u, uint32_t* out_idx, float* out_w, float* out_prio,
-                                  uint32_t* weight_calls, uint32_t stale_hb, hipStream_t s) {
+                                  uint32_t* weight_calls, uint32_t stale_hb, const FieldTable* rows, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
   constexpr uint32_t kLdsCap = 128 * 1024;
   const uint32_t wave_bytes = LOGK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
@@ -515,7 +553,8 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   if (waves > max_waves) waves = max_waves;
   const uint32_t block = waves * 64;
   const uint32_t gx = (B + block - 1) / block;
-  const size_t bytes = (size_t)top + (size_t)waves * wave_bytes;
+  size_t bytes = (size_t)top + (size_t)waves * wave_bytes;
+  if (bytes < tn.sample_min_lds) bytes = tn.sample_min_lds;   // asking for more LDS than needed spreads workgroups over more CUs
   // The two buffers of partial minima alternate between the calls that use them (k_weights of
   // one call re-arms the buffer of the next).
   const uint32_t parity = *weight_calls & 1u;
@@ -540,8 +579,11 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   PER_LAUNCH(KID_SAMPLE, k_sample<LOGK>, dim3(gx, g.T), dim3(block), bytes, s, g, tc, B, size, beta, u, out_idx,
              out_prio, out_w, parity, stale);
   e = hipGetLastError();
-  if (e != hipSuccess || !out_w || gx == 1) return e;
-  static_assert(kVminSlots == 256, "k_weights folds one partial minimum per thread of a 256-thread block");
+  if (e != hipSuccess) return e;
+  const bool finish_weights = out_w && gx > 1;
+  if (rows)   // fused call: the rows are gathered by a second kernel that also finishes the weights
+    return launch_gather_weights(g, tn, *rows, B, out_idx, finish_weights ? out_w : nullptr, size, beta, parity, s);
+  if (!finish_weights) return e;
   PER_LAUNCH(KID_WEIGHTS, k_weights, dim3((B + 255) / 256, g.T), dim3(256), 0, s, g, B, size, beta, out_w, parity);
   return hipGetLastError();
 }
@@ -559,8 +601,8 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
 
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
-                         hipStream_t s) {
-#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, weight_calls, stale_hb, s)
+                         const FieldTable* rows, hipStream_t s) {
+#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, weight_calls, stale_hb, rows, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }
@@ -603,6 +645,27 @@ __device__ __forceinline__ void move_rows(const FieldTable& ft, uint32_t f, uint
   if (bad) atomicOr(&status[t], 1u);
 }
 
+// Row gather of a fused sample+gather call: the workgroups with blockIdx.y == 0 finish the
+// importance weights instead of moving rows (they are dispatched first, so the fp64 work runs
+// beside the row traffic), the others move field blockIdx.y - 1.
+__global__ void k_rows_weights(FieldTable ft, Geom g, uint32_t B, const uint32_t* __restrict__ idx, float* __restrict__ w,
+                               uint32_t size, float beta, uint32_t parity) {
+  const uint32_t t = blockIdx.z;
+  if (blockIdx.y == 0) {
+    weights_job(g, t, B, size, beta, w, parity, blockIdx.x, gridDim.x);
+    return;
+  }
+  const uint32_t f = blockIdx.y - 1;
+  if (ft.io[f] == nullptr) return;
+  switch (ft.vec[f]) {
+    case 16: move_rows<uint4, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
+    case 8: move_rows<uint2, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
+    case 4: move_rows<uint32_t, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
+    case 2: move_rows<uint16_t, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
+    default: move_rows<uint8_t, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
+  }
+}
+
 template <bool GATHER>
 __global__ void k_rows(FieldTable ft, uint32_t B, const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
                        uint32_t* status) {
@@ -635,6 +698,16 @@ hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, 
   const uint32_t block = tn.gather_block;
   PER_LAUNCH(KID_GATHER, k_rows<true>, dim3(rows_grid_x(ft, B, block), ft.n_fields, g.T), dim3(block), 0, s, ft, B,
              idx, 0, g.N, g.status);
+  return hipGetLastError();
+}
+
+static hipError_t launch_gather_weights(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B,
+                                        const uint32_t* idx, float* w, uint32_t size, float beta, uint32_t parity,
+                                        hipStream_t s) {
+  if (!w) return launch_gather(g, tn, ft, B, idx, s);
+  const uint32_t block = tn.gather_block;
+  PER_LAUNCH(KID_GATHER_WEIGHTS, k_rows_weights, dim3(rows_grid_x(ft, B, block), ft.n_fields + 1, g.T), dim3(block), 0,
+             s, ft, g, B, idx, w, size, beta, parity);
   return hipGetLastError();
 }
 
@@ -851,7 +924,7 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   constexpr int LPS = Fan<LOGK>::LPS;
   extern __shared__ __attribute__((aligned(16))) float sub[];   // 16-byte LDS accesses need the alignment
   __shared__ uint32_t s_list[kDirtyListCap];
-  __shared__ uint32_t s_count;
+  __shared__ uint32_t s_wave[16];
   __shared__ uint32_t s_last;
   const uint32_t t = blockIdx.y;
   const uint32_t b = blockIdx.x;
@@ -861,6 +934,7 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   const uint32_t grp = threadIdx.x / LPS;
   const uint32_t ngrp = blockDim.x / LPS;
 
+  PER_TRACE_DECL;
   PER_MARK(0);
   // ---- 0. this subtree's height-1 nodes and their dirty flags
   const uint32_t sh1 = (hb - 1) * LOGK;
@@ -870,42 +944,47 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   const uint32_t hi1 = min(n1, (b + 1) << sh1);
   float* lvl1 = sl.ptr[0] + (size_t)t * sl.stride[0];
   uint8_t* dirty = g.dirty + (size_t)t * g.dirty_stride;
-  if (threadIdx.x == 0) s_count = 0;
-  // four flags per thread; the first word is fetched together with the height-1 nodes
-  const uint32_t w_first = lo1 + 4 * threadIdx.x;
-  uint32_t bits_first = 0;
-  if (w_first < hi1) bits_first = *reinterpret_cast<const uint32_t*>(dirty + w_first);
+  float* leaves = g.level[0] + (size_t)t * g.stride[0];
+  const uint2* owner = reinterpret_cast<const uint2*>(g.owner) + (size_t)t * g.owner_stride;   // (value, stamp)
+  // one flag per thread and sweep; the first sweep's flag is fetched together with the height-1 nodes
+  const uint32_t f_first = lo1 + threadIdx.x;
+  uint32_t flag_first = 0;
+  if (f_first < hi1) flag_first = dirty[f_first];
   for (uint32_t i = threadIdx.x; i < sl.lds_floats; i += blockDim.x) {
     const uint32_t gi = lo1 + i;
     sub[i] = (i < sl.lds_off[1] || hb == 1) && gi < n1_pad ? lvl1[gi] : 0.0f;   // slot 0 from memory, the rest zero
   }
-  __syncthreads();
-  for (uint32_t w0 = lo1; w0 < hi1; w0 += 4 * blockDim.x) {
-    const uint32_t w = w0 + 4 * threadIdx.x;
-    uint32_t bits = 0;
-    if (w0 == lo1) bits = bits_first;
-    else if (w < hi1) bits = *reinterpret_cast<const uint32_t*>(dirty + w);
-    if (bits) {
-      *reinterpret_cast<uint32_t*>(dirty + w) = 0;
-      const uint32_t cnt = ((bits & 0xFFu) != 0) + ((bits & 0xFF00u) != 0) + ((bits & 0xFF0000u) != 0) + ((bits >> 24) != 0);
-      uint32_t at = atomicAdd(&s_count, cnt);
-#pragma unroll
-      for (uint32_t k = 0; k < 4; ++k)
-        if ((bits >> (8 * k)) & 0xFFu) s_list[at++] = w + k;
+  // compact the dirty nodes into s_list: ballot within the wave, wave totals through LDS
+  const uint32_t nwaves = blockDim.x >> 6;
+  uint32_t nd = 0;
+  for (uint32_t f0 = lo1; f0 < hi1; f0 += blockDim.x) {
+    const uint32_t f = f0 + threadIdx.x;
+    uint32_t flag = 0;
+    if (f0 == lo1) flag = flag_first;
+    else if (f < hi1) flag = dirty[f];
+    const unsigned long long m = __ballot(flag != 0);
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    if (lane == 0) s_wave[threadIdx.x >> 6] = (uint32_t)__popcll(m);
+    __syncthreads();
+    uint32_t before = nd, total = nd;
+    for (uint32_t wv = 0; wv < nwaves; ++wv) {
+      const uint32_t c = s_wave[wv];
+      if (wv < (threadIdx.x >> 6)) before += c;
+      total += c;
     }
+    if (flag) s_list[before + rank] = f;
+    nd = total;
+    __syncthreads();
   }
-  __syncthreads();
-  const uint32_t nd = s_count;
   PER_MARK(1);
 
   if (nd > 0) {
     // ---- 1. rebuild the dirty height-1 nodes (list order is irrelevant: nodes are independent)
-    float* leaves = g.level[0] + (size_t)t * g.stride[0];
-    const uint2* owner = reinterpret_cast<const uint2*>(g.owner) + (size_t)t * g.owner_stride;   // (value, stamp)
     for (uint32_t base = 0; base < nd; base += ngrp) {
       const uint32_t item = base + grp;
       const bool ok = item < nd;
       const uint32_t node = s_list[ok ? item : nd - 1];
+      PER_MARK(4);
       float sum;
       if constexpr (LOGK == 1) {
         float2 c = *reinterpret_cast<const float2*>(leaves + (size_t)node * 2);
@@ -928,8 +1007,10 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
         if (w3) c.w = __uint_as_float(ob.z);
         if (ok && (w0 || w1 || w2 || w3)) *reinterpret_cast<float4*>(leaves + at) = c;
         sum = (c.x + c.y) + (c.z + c.w);
+        PER_MARK(5);
 #pragma unroll
         for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) sum = sum + __shfl_xor(sum, 1 << k);
+        PER_MARK(6);
       }
       if (ok && q == 0) {
         lvl1[node] = sum;
@@ -960,6 +1041,10 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   }
 
   PER_MARK(3);
+  PER_FLUSH();
+  // The flags are cleared only now: a wait for loaded data also waits for every earlier store
+  // of the wave, so stores that nothing depends on go last.
+  for (uint32_t i = threadIdx.x; i < nd; i += blockDim.x) dirty[s_list[i]] = 0;
   // ---- 3. above the subtree: the last child to arrive recomputes the parent
   if (!chain) return;   // the heights above hb are left to their next reader
   uint32_t node = b;

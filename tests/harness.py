@@ -68,18 +68,25 @@ class Mirror:
             self.counter += m
             done += m
 
-    def sample(self, u, beta=0.4, want_weights=True):
-        gi, gw, gv = self.gpu.sample(dev(u), beta, want_weights=want_weights, want_prio=True)
+    def sample(self, u, beta=0.4, want_weights=True, fused_rows=False):
+        """fused_rows: use per_sample_gather and check the rows it returns as well."""
+        rows = None
+        if fused_rows:
+            B = u.shape[-1]
+            rows = [torch.empty((self.T, B, b), dtype=torch.uint8, device="cuda") for b in self.fb]
+        gi, gw, gv = self.gpu.sample(dev(u), beta, want_weights=want_weights, want_prio=True, rows_out=rows)
         ci, cw, cv = self.cpu.sample(u, beta, want_weights)
         gi_h = idx_to_host(gi)
         assert np.array_equal(gi_h, ci), f"sampled indices differ at {np.argwhere(gi_h != ci)[:5]}"
         assert gv.cpu().numpy().tobytes() == cv.tobytes(), "sampled leaf values"
         if want_weights:
             np.testing.assert_allclose(gw.cpu().numpy(), cw, rtol=WEIGHT_RTOL, atol=0)
+        if fused_rows:
+            self.gather(gi, ci, got=rows)
         return gi, ci
 
-    def gather(self, idx_dev, idx_host):
-        got = [g.cpu().numpy() for g in self.gpu.gather(idx_dev)]
+    def gather(self, idx_dev, idx_host, got=None):
+        got = [g.cpu().numpy() for g in (self.gpu.gather(idx_dev) if got is None else got)]
         if self.oracle_payload:
             want = self.cpu.gather(idx_host)
         else:   # expected bytes straight from the row hash of the counter each slot holds
@@ -122,8 +129,10 @@ class Mirror:
         inp = wl.step_inputs(w, step, seed, B)
         if w.n_insert:
             self.insert(w.n_insert)
-        gi, ci = self.sample(inp["u"], inp["beta"], w.weights)
-        self.gather(gi, ci)
+        fused = step % 2 == 1     # alternate between the separate calls and the fused one
+        gi, ci = self.sample(inp["u"], inp["beta"], w.weights, fused_rows=fused)
+        if not fused:
+            self.gather(gi, ci)
         self.update(wl.apply_dup_map(ci, inp), inp["upd_prio"])
         if check_tree:
             self.compare_tree()

@@ -40,7 +40,7 @@ def test_random_operation_mix(K, N, T):
     for it in range(4):
         B = int(rng.choice([1, 3, 64, 257, 1500]))
         u = wl.uniform01(rng, (T, B))
-        gi, ci = m.sample(u, beta=float(rng.choice([0.0, 0.4, 1.0])))
+        gi, ci = m.sample(u, beta=float(rng.choice([0.0, 0.4, 1.0])), fused_rows=(it % 2 == 0))
         m.gather(gi, ci)
         upd_idx = ci.copy()
         upd_prio = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B))
@@ -143,6 +143,11 @@ def test_zero_total_empty_and_error_codes():
     assert p.status() == FLAG_ZERO_TOTAL
     rows = p.gather(idx)                                        # sentinel indices gather zeros
     assert np.all(rows[0].cpu().numpy() == 0) and p.status() == FLAG_ZERO_TOTAL | FLAG_BAD_INDEX
+    p.clear_status()
+    fused = [torch.full((2, 16, 8), 7, dtype=torch.uint8, device="cuda")]
+    idx, w, v = p.sample(u, rows_out=fused)                     # same through the fused call
+    assert np.all(idx_to_host(idx) == 0xFFFFFFFF) and np.all(fused[0].cpu().numpy() == 0)
+    assert p.status() == FLAG_ZERO_TOTAL | FLAG_BAD_INDEX
     p.clear_status()
     assert p.status() == 0
     with pytest.raises(PerError) as e:
@@ -280,7 +285,7 @@ def test_workload_c4_full_size():
     m.compare_tree()
     for s in range(4):
         inp = wl.step_inputs(w, s, 0)
-        gi, ci = m.sample(inp["u"], inp["beta"], True)
+        gi, ci = m.sample(inp["u"], inp["beta"], True, fused_rows=(s % 2 == 0))
         leaves = m.cpu.read_level(0, 0)
         assert np.all(leaves[ci[0]] > 0), "a zero-priority row was sampled"
         m.gather(gi, ci)
