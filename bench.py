@@ -48,32 +48,44 @@ def parse():
     return ap.parse_args()
 
 
-def algorithmic_bytes(w, idx, upd_idx, K, H, n_levels, h_lds, weights):
-    """Bytes the method itself must move in one step, each distinct K-group counted once per
-    phase (what a perfect cache would move).  idx / upd_idx: [T, B] uint32 of one step."""
+def algorithmic_bytes(w, idx, upd_idx, K, H, h_mem, weights, fused):
+    """Bytes the method itself must move in one step, per kernel, each distinct K-group counted once
+    per phase (what a perfect cache would move).  idx / upd_idx: [T, B] uint32 of one step.
+    h_mem: heights below it are read from memory by the descent (the ones above sit in LDS)."""
     logK = K.bit_length() - 1
     T, B = idx.shape
     E = w.row_bytes
-    a_sample = a_gather = a_update = 0
-    per_kernel = {}
+    out = {"k_sample": 0, "k_weights": 0, "k_rows_gather": 0, "k_update_claim": 0, "k_update_tree": 0}
     for t in range(T):
         i64 = idx[t].astype(np.int64)
-        g = 0
-        for h in range(0, min(h_lds, H)):          # groups at height h read from memory
-            g += len(np.unique(i64 >> ((h + 1) * logK))) * 4 * K
-        s = 4 * B + g + 4 * B + 4 * B + (4 * B if weights else 0)   # u, groups, idx, prio, (value for weights)
-        a_sample += s
-        R = len(np.unique(i64))
-        a_gather += 4 * B + E * R + E * B
+        groups = sum(len(np.unique(i64 >> ((h + 1) * logK))) * 4 * K for h in range(0, min(h_mem, H)))
+        out["k_sample"] += 4 * B + groups + 4 * B + 4 * B + (4 * B if weights else 0)   # u, groups, idx, prio, value
+        out["k_weights"] += 8 * B if weights else 0                                       # value in, weight out
+        out["k_rows_gather"] += 4 * B + E * len(np.unique(i64)) + E * B                   # idx, distinct rows, dense rows
         u64 = upd_idx[t].astype(np.int64)
-        U = len(np.unique(u64))
-        a_update += 8 * B + 4 * U
+        out["k_update_claim"] += 8 * B                                                    # idx, prio
+        out["k_update_tree"] += 4 * len(np.unique(u64))                                   # leaf writes
         for h in range(1, H + 1):
-            Q = len(np.unique(u64 >> (h * logK)))
-            a_update += 4 * K * Q + 4 * Q
-    per_kernel["k_sample"] = a_sample
-    per_kernel["k_rows_gather"] = a_gather
-    return a_sample, a_gather, a_update
+            q = len(np.unique(u64 >> (h * logK)))
+            out["k_update_tree"] += 4 * K * q + 4 * q                                     # child groups in, node out
+    out["k_rows_gather_weights"] = out["k_rows_gather"] + out["k_weights"]
+    return out
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the rocprofv3 counter runs summarised under profiles/
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); None if no summary exists."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel:
+            try:
+                return int(float(parts[1]))
+            except ValueError:
+                return None
+    return None
 
 
 def main():
@@ -236,30 +248,30 @@ def main():
     for kv in args.tune:
         if kv.startswith("lds_budget_bytes="):
             lds_budget = int(kv.split("=")[1])
-    h_lds, acc = H, 0
+    h_mem, acc, slots = H, 0, 0     # mirrors the library's choice of the heights it copies to LDS
     for l in range(H - 1, -1, -1):
         add = lvl_n[l + 1] * K * 4
-        if acc + add > lds_budget:
+        if acc + add > lds_budget or slots == 4:
             break
         acc += add
-        h_lds = l
+        slots += 1
+        h_mem = l
     sel = list(range(warmup, total_steps, max(1, steps // 16)))
-    parts = np.array([algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, lvl_n, h_lds, w.weights) for s in sel],
-                     dtype=np.float64).mean(axis=0)
-    a_sample, a_gather, a_update = parts
-    a_step = float(parts.sum())
+    per_step = [algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, h_mem, w.weights, fused) for s in sel]
+    alg = {k: float(np.mean([p[k] for p in per_step])) for k in per_step[0]}
+    a_sample = alg["k_sample"]
+    a_gather = alg["k_rows_gather"] + alg["k_weights"]
+    a_update = alg["k_update_claim"] + alg["k_update_tree"]
+    a_step = a_sample + a_gather + a_update
     kern_ms = {k: v[0] / max(1, v[1]) for k, v in kernels.items()}
     kern_per_step = {k: v[1] / steps for k, v in kernels.items()}
-    dominant = max(kernels, key=lambda k: kernels[k][0])
-    alg = {"k_sample": a_sample, "k_rows_gather": a_gather, "k_rows_gather_weights": a_gather}
-    dom_bytes = alg.get(dominant)
-    if dom_bytes is None:   # an update kernel: attribute the whole update phase's bytes to its launches per step
-        dom_bytes = a_update / max(1.0, sum(v for k, v in kern_per_step.items()
-                                            if k.startswith("k_update") or k.startswith("k_resum")))
+    step_kernels = [k for k in kernels if k in alg]
+    dominant = max(step_kernels, key=lambda k: kernels[k][0])
+    dom_bytes = alg[dominant] / max(1e-9, kern_per_step[dominant])
     dom_gbs = dom_bytes / (kern_ms[dominant] * 1e-3) / 1e9
     roofline = {
         "kernel": dominant, "bound": "hbm", "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+        "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(w.name, dominant),
         "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(kern_ms[dominant] * 1e3, 2),
     }
     step_gbs = a_step / (ms_per_step * 1e-3) / 1e9
@@ -308,7 +320,8 @@ def main():
         "cpu_baseline": cpu,
         "step_algorithmic_bytes": int(a_step),
         "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
-        "phase_algorithmic_bytes": {"sample": int(a_sample), "gather": int(a_gather), "update": int(a_update)},
+        "phase_algorithmic_bytes": {"sample": int(a_sample), "gather_and_weights": int(a_gather), "update": int(a_update)},
+        "kernel_algorithmic_bytes": {k: int(alg[k]) for k in sorted(step_kernels)},
         "kernels_us": {k: round(v * 1e3, 2) for k, v in sorted(kern_ms.items())},
         "kernels_per_step": {k: round(v, 2) for k, v in sorted(kern_per_step.items())},
         "device_status_flags": status_record,

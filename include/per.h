@@ -155,9 +155,9 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
  *                  the next call that reads them; 0 makes per_update finish them itself */
 int per_set_tuning(per_t* p, const char* name, int64_t value);
 
-/* Per-kernel timing for benchmarks.  While enabled, every kernel launch of this buffer is
- * bracketed by a pair of HIP events on its stream (this adds gaps between kernels, so
- * whole-step times must be taken with profiling off).  per_profile(p, 1) clears the
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch of this buffer carries a
+ * pair of HIP events stamped at the start and end of the kernel's execution (this slows the
+ * launches down, so whole-step times must be taken with profiling off).  per_profile(p, 1) clears the
  * totals and starts; per_profile(p, 0) stops.  per_profile_read waits for the recorded
  * events and fills, for each kernel launched since the totals were cleared, its name
  * (static string), summed duration in ms and launch count; *n_entries receives how many

@@ -48,7 +48,7 @@ struct FieldTable {
 
 struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b0) u [a1,b1)
 
-// Optional per-kernel timing with HIP events on the launch stream (off by default).
+// Optional per-kernel timing with HIP events attached to each launch (off by default).
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_GATHER_WEIGHTS, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_GET_PRIORITY, KID_COUNT
@@ -61,16 +61,9 @@ struct Profiler {
   std::vector<Rec> recs;
   double total_ms[KID_COUNT] = {};
   uint64_t launches[KID_COUNT] = {};
+  bool begin(int kid, hipEvent_t* start, hipEvent_t* stop);   // a fresh event pair for one launch (false: not profiling)
   void reset();                 // drops pending events and zeroes the totals
   hipError_t collect();         // waits for pending events and folds them into the totals
-};
-
-struct ProfScope {              // records an event pair around one launch when profiling is on
-  Profiler* p;
-  hipStream_t s;
-  hipEvent_t stop = nullptr;
-  ProfScope(Profiler* prof, int kid, hipStream_t stream);
-  ~ProfScope();
 };
 
 struct Tuning {

@@ -10,6 +10,8 @@
 // identical bits.
 #include "per_geom.h"
 
+#include <hip/hip_ext.h>
+
 #include <type_traits>
 
 namespace per {
@@ -45,25 +47,28 @@ hipError_t Profiler::collect() {
   return first;
 }
 
-ProfScope::ProfScope(Profiler* prof, int kid, hipStream_t stream) : p(prof && prof->on ? prof : nullptr), s(stream) {
-  if (!p) return;
-  Profiler::Rec r;
+// When profiling is on, the launch carries its own pair of events (hipExtLaunchKernelGGL stamps
+// them at the start and at the end of the kernel's execution, not at enqueue time), so the
+// durations are those of the kernels themselves.
+bool Profiler::begin(int kid, hipEvent_t* start, hipEvent_t* stop) {
+  if (!on) return false;
+  Rec r;
   r.kid = kid;
-  if (hipEventCreate(&r.start) != hipSuccess) { p = nullptr; return; }
-  if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); p = nullptr; return; }
-  (void)hipEventRecord(r.start, s);
-  stop = r.stop;
-  p->recs.push_back(r);
+  if (hipEventCreate(&r.start) != hipSuccess) return false;
+  if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return false; }
+  recs.push_back(r);
+  *start = r.start;
+  *stop = r.stop;
+  return true;
 }
 
-ProfScope::~ProfScope() {
-  if (p) (void)hipEventRecord(stop, s);
-}
-
-#define PER_LAUNCH(KID, KERNEL, GRID, BLOCK, LDS, STREAM, ...)            \
-  do {                                                                    \
-    ProfScope prof_scope_(tn.prof, KID, STREAM);                          \
-    KERNEL<<<GRID, BLOCK, LDS, STREAM>>>(__VA_ARGS__);                    \
+#define PER_LAUNCH(KID, KERNEL, GRID, BLOCK, LDS, STREAM, ...)                                     \
+  do {                                                                                             \
+    hipEvent_t ev_start_, ev_stop_;                                                                \
+    if (tn.prof && tn.prof->begin(KID, &ev_start_, &ev_stop_))                                     \
+      hipExtLaunchKernelGGL((KERNEL), GRID, BLOCK, LDS, STREAM, ev_start_, ev_stop_, 0, __VA_ARGS__); \
+    else                                                                                           \
+      KERNEL<<<GRID, BLOCK, LDS, STREAM>>>(__VA_ARGS__);                                           \
   } while (0)
 
 // ---------------------------------------------------------------------------------
