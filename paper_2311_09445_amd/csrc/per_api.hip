@@ -82,9 +82,9 @@ void make_layout(const per_config* c, Layout* L) {
   L->owner_stride = (uint32_t)round_up(c->capacity, 64);
   L->owner_off = off;
   off = round_up(off + (size_t)L->owner_stride * T * 8, kAlign);
-  L->dirty_stride = (uint32_t)round_up((size_t)L->n[1], 256);
+  L->dirty_stride = (uint32_t)round_up(((size_t)L->n[1] * K + 31) / 32, 64);   // one bit per (padded) leaf
   L->dirty_off = off;
-  off = round_up(off + (size_t)L->dirty_stride * T, kAlign);
+  off = round_up(off + (size_t)L->dirty_stride * T * 4, kAlign);
   uint32_t counters = 0;
   for (uint32_t l = 0; l <= L->H; ++l) {
     L->arrive_level_off[l] = counters;
@@ -179,7 +179,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.root_stride = g.stride[L.H];
   g.owner = reinterpret_cast<uint64_t*>(p->arena + L.owner_off);
   g.owner_stride = L.owner_stride;
-  g.dirty = p->arena + L.dirty_off;
+  g.dirty = reinterpret_cast<uint32_t*>(p->arena + L.dirty_off);
   g.dirty_stride = L.dirty_stride;
   g.arrive = reinterpret_cast<uint32_t*>(p->arena + L.arrive_off);
   g.arrive_stride = L.arrive_stride;

@@ -27,7 +27,7 @@ struct Geom {
   uint32_t root_stride;             // == stride[H]
   uint64_t* owner;                  // [T][owner_stride] last-writer stamps: (stamp << 32) | fp32 bits of the value
   uint32_t owner_stride;
-  uint8_t* dirty;                   // [T][dirty_stride] one byte per height-1 node: a leaf below it was claimed
+  uint32_t* dirty;                  // [T][dirty_stride] words of one bit per leaf: the leaf was claimed by the current update
   uint32_t dirty_stride;
   uint32_t* arrive;                 // [T][arrive_stride] arrival counters of the nodes of heights >= 2
   uint32_t arrive_stride;

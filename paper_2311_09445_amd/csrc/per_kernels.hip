@@ -223,10 +223,13 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
 // Running maximum priority: mx = fp32 bits of this lane's valid positive value (0: none).  One
 // atomic per wave, and only when the wave would actually raise the maximum; the plain read may
 // be stale, which can only cause a redundant atomic, never a missed one (the value only grows).
-__device__ __forceinline__ void raise_max(const Geom& g, uint32_t t, uint32_t mx) {
+// `seen` is the value read when the kernel started (so the read overlaps the other loads).
+__device__ __forceinline__ uint32_t read_max_bits(const Geom& g, uint32_t t) {
+  return *reinterpret_cast<volatile uint32_t*>(&g.max_v[t]);
+}
+__device__ __forceinline__ void raise_max(const Geom& g, uint32_t t, uint32_t mx, uint32_t seen) {
   mx = wave_max_u32(mx);
-  uint32_t* addr = reinterpret_cast<uint32_t*>(&g.max_v[t]);
-  if ((threadIdx.x & 63u) == 0 && mx > *reinterpret_cast<volatile uint32_t*>(addr)) atomicMax(addr, mx);
+  if ((threadIdx.x & 63u) == 0 && mx > seen) atomicMax(reinterpret_cast<uint32_t*>(&g.max_v[t]), mx);
 }
 
 // Importance weight (prioritized experience replay, cited in Section II-A):
@@ -535,12 +538,27 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   constexpr int K = Fan<LOGK>::K;
   constexpr uint32_t kLdsCap = 128 * 1024;
   const uint32_t wave_bytes = LOGK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
-  // topmost heights (below the root) that fit the LDS budget, at most kTopSlots of them
+  // workgroup size: the whole batch in one workgroup when it is small (the weights are then finished
+  // in-kernel), else the configured size; bounded by the LDS the staging rows need
+  uint32_t max_waves = wave_bytes ? (uint32_t)(kLdsCap / 2 / wave_bytes) : 16u;
+  if (max_waves > 16) max_waves = 16;
+  if (max_waves < 1) max_waves = 1;
+  uint32_t waves = tn.sample_block / 64;
+  const uint32_t need = (B + 63) / 64;
+  if (need <= max_waves) waves = need;
+  if (waves > max_waves) waves = max_waves;
+  const uint32_t block = waves * 64;
+  const uint32_t gx = (B + block - 1) / block;
+  // topmost heights (below the root) copied to LDS: at most kTopSlots, within the LDS budget, and only
+  // while a height is small next to what the workgroup's samples would fetch from it one by one
   TopCopy tc{};
   uint64_t top = 0;
   for (int l = (int)g.H - 1; l >= 0 && tc.nslots < (uint32_t)kTopSlots; --l) {
-    const uint64_t add = (uint64_t)g.n[l + 1] * K * 4;
-    if (top + add > tn.lds_budget_bytes || top + add + wave_bytes > kLdsCap) break;
+    const uint64_t cnt = (uint64_t)g.n[l + 1] * K;
+    const uint64_t add = cnt * 4;
+    if (top + add > tn.lds_budget_bytes || top + add + (uint64_t)waves * wave_bytes > kLdsCap) break;
+    const bool needed_for_rebuild = stale_hb && (uint32_t)l >= stale_hb;   // the rebuild of stale heights reads it
+    if (cnt > 8ull * block && tn.lds_budget_bytes <= 64 * 1024 && !needed_for_rebuild) break;
     top += add;
     const uint32_t i = tc.nslots++;
     tc.ptr[i] = g.level[l];
@@ -550,14 +568,6 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   }
   tc.root = g.root;
   tc.root_stride = g.root_stride;
-  uint32_t max_waves = wave_bytes ? (uint32_t)((kLdsCap - top) / wave_bytes) : 16u;
-  if (max_waves > 16) max_waves = 16;
-  uint32_t waves = tn.sample_block / 64;
-  const uint32_t need = (B + 63) / 64;
-  if (need <= max_waves) waves = need;          // whole batch in one block per tree: weights are finished in-kernel
-  if (waves > max_waves) waves = max_waves;
-  const uint32_t block = waves * 64;
-  const uint32_t gx = (B + block - 1) / block;
   size_t bytes = (size_t)top + (size_t)waves * wave_bytes;
   if (bytes < tn.sample_min_lds) bytes = tn.sample_min_lds;   // asking for more LDS than needed spreads workgroups over more CUs
   // The two buffers of partial minima alternate between the calls that use them (k_weights of
@@ -853,7 +863,7 @@ __global__ void k_insert_leaves(Geom g, uint32_t n, uint32_t cursor, const float
     }
   }
   if (prio) {
-    raise_max(g, t, mx);
+    raise_max(g, t, mx, read_max_bits(g, t));
     if (bad) atomicOr(&g.status[t], 2u);
   }
 }
@@ -869,7 +879,7 @@ hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uin
 // priority update: claim (last writer), then one tree pass
 // ---------------------------------------------------------------------------------
 // Claim: element j raises the 64-bit stamp of its leaf to (stamp_base + j) << 32 | value bits
-// by atomic max, and flags the leaf's parent as dirty.  The largest j wins and carries its
+// by atomic max, and sets the leaf's bit in the dirty mask (one bit per leaf).  The largest j wins and carries its
 // value with it.  Stamps grow from call to call, so stale stamps never win and the stamp
 // array needs no clearing between calls.
 template <int LOGK>
@@ -877,6 +887,7 @@ __global__ void k_update_claim(Geom g, uint32_t B, uint32_t size, const uint32_t
                                const float* __restrict__ prio, uint32_t stamp_base) {
   const uint32_t t = blockIdx.y;
   const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t max_seen = read_max_bits(g, t);
   uint32_t mx = 0;
   uint32_t flags = 0;
   if (j < B) {
@@ -887,11 +898,11 @@ __global__ void k_update_claim(Geom g, uint32_t B, uint32_t size, const uint32_t
     else {
       const unsigned long long stamp = ((unsigned long long)(stamp_base + j) << 32) | __float_as_uint(v);
       atomicMax(reinterpret_cast<unsigned long long*>(g.owner) + (size_t)t * g.owner_stride + i, stamp);
-      g.dirty[(size_t)t * g.dirty_stride + (i >> LOGK)] = 1;
+      atomicOr(&g.dirty[(size_t)t * g.dirty_stride + (i >> 5)], 1u << (i & 31u));
       mx = v > 0.0f ? __float_as_uint(v) : 0u;
     }
   }
-  raise_max(g, t, mx);
+  raise_max(g, t, mx, max_seen);
   if (flags) atomicOr(&g.status[t], flags);
 }
 
@@ -908,18 +919,18 @@ struct SubLevels {
 
 // Tree pass.  Workgroup b of tree t owns the subtree under node b of height hb and keeps the
 // subtree's nodes of heights 1 .. hb in LDS.
-//  0. In one trip it fetches its height-1 nodes and their dirty flags (and clears the flags).
-//  1. Each dirty height-1 node is rebuilt by LPS lanes: they read its K leaves and their K
-//     stamps; a stamp whose upper word lies in [stamp_base, stamp_base + B) belongs to the
-//     batch element that won that leaf, and its lower word is the new value, which replaces
-//     the leaf (and is stored); the K values are summed pairwise.
+//  0. In one trip it fetches its height-1 nodes and the dirty bits of the leaves below them.
+//  1. Each height-1 node with a dirty leaf is rebuilt by LPS lanes: they read its K leaves and,
+//     for the dirty ones only, the stamp entry, whose lower word is the value of the batch
+//     element that won that leaf; it replaces the leaf (and is stored); the K values are
+//     summed pairwise.  The dirty bits are cleared at the end.
 //  2. Heights 2 .. hb of the subtree are recomputed from LDS and stored.
 //  3. Above hb every node counts the arrivals of its children's workgroups; the last one to
 //     arrive recomputes it and carries on upwards, so the root is written by whichever
 //     workgroup finishes last.  No workgroup ever waits for another.  When there are only a
 //     few nodes at height hb this step is skipped (chain == 0): the agent-scope fences it
 //     needs cost more than recomputing those heights in the next kernel that reads them.
-constexpr uint32_t kDirtyListCap = 4096;
+constexpr uint32_t kDirtyListCap = 2048;
 constexpr uint32_t kLazyTopNodes = 4096;
 
 template <int LOGK>
@@ -929,6 +940,8 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   constexpr int LPS = Fan<LOGK>::LPS;
   extern __shared__ __attribute__((aligned(16))) float sub[];   // 16-byte LDS accesses need the alignment
   __shared__ uint32_t s_list[kDirtyListCap];
+  __shared__ uint32_t s_bits[kDirtyListCap];
+  __shared__ uint32_t s_bits_hi[LOGK == 6 ? kDirtyListCap : 1];
   __shared__ uint32_t s_wave[16];
   __shared__ uint32_t s_last;
   const uint32_t t = blockIdx.y;
@@ -948,26 +961,38 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   const uint32_t lo1 = b << sh1;
   const uint32_t hi1 = min(n1, (b + 1) << sh1);
   float* lvl1 = sl.ptr[0] + (size_t)t * sl.stride[0];
-  uint8_t* dirty = g.dirty + (size_t)t * g.dirty_stride;
+  uint32_t* dirty = g.dirty + (size_t)t * g.dirty_stride;
   float* leaves = g.level[0] + (size_t)t * g.stride[0];
   const uint2* owner = reinterpret_cast<const uint2*>(g.owner) + (size_t)t * g.owner_stride;   // (value, stamp)
-  // one flag per thread and sweep; the first sweep's flag is fetched together with the height-1 nodes
+  // the K dirty bits of one height-1 node
+  auto node_bits = [&](uint32_t node) -> unsigned long long {
+    if constexpr (LOGK == 6) {
+      const uint2 w = *reinterpret_cast<const uint2*>(dirty + 2 * (size_t)node);
+      return ((unsigned long long)w.y << 32) | w.x;
+    } else if constexpr (LOGK == 5) {
+      return dirty[node];
+    } else {
+      const uint32_t bit0 = node << LOGK;
+      return (dirty[bit0 >> 5] >> (bit0 & 31u)) & ((1u << K) - 1u);
+    }
+  };
+  // one node per thread and sweep; the first sweep's bits are fetched together with the height-1 nodes
   const uint32_t f_first = lo1 + threadIdx.x;
-  uint32_t flag_first = 0;
-  if (f_first < hi1) flag_first = dirty[f_first];
+  unsigned long long bits_first = 0;
+  if (f_first < hi1) bits_first = node_bits(f_first);
   for (uint32_t i = threadIdx.x; i < sl.lds_floats; i += blockDim.x) {
     const uint32_t gi = lo1 + i;
     sub[i] = (i < sl.lds_off[1] || hb == 1) && gi < n1_pad ? lvl1[gi] : 0.0f;   // slot 0 from memory, the rest zero
   }
-  // compact the dirty nodes into s_list: ballot within the wave, wave totals through LDS
+  // compact the dirty nodes into s_list / s_bits: ballot within the wave, wave totals through LDS
   const uint32_t nwaves = blockDim.x >> 6;
   uint32_t nd = 0;
   for (uint32_t f0 = lo1; f0 < hi1; f0 += blockDim.x) {
     const uint32_t f = f0 + threadIdx.x;
-    uint32_t flag = 0;
-    if (f0 == lo1) flag = flag_first;
-    else if (f < hi1) flag = dirty[f];
-    const unsigned long long m = __ballot(flag != 0);
+    unsigned long long bits = 0;
+    if (f0 == lo1) bits = bits_first;
+    else if (f < hi1) bits = node_bits(f);
+    const unsigned long long m = __ballot(bits != 0);
     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
     if (lane == 0) s_wave[threadIdx.x >> 6] = (uint32_t)__popcll(m);
     __syncthreads();
@@ -977,7 +1002,11 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
       if (wv < (threadIdx.x >> 6)) before += c;
       total += c;
     }
-    if (flag) s_list[before + rank] = f;
+    if (bits != 0) {
+      s_list[before + rank] = f;
+      s_bits[before + rank] = (uint32_t)bits;
+      if constexpr (LOGK == 6) s_bits_hi[before + rank] = (uint32_t)(bits >> 32);
+    }
     nd = total;
     __syncthreads();
   }
@@ -988,29 +1017,37 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
     for (uint32_t base = 0; base < nd; base += ngrp) {
       const uint32_t item = base + grp;
       const bool ok = item < nd;
-      const uint32_t node = s_list[ok ? item : nd - 1];
+      const uint32_t li = ok ? item : nd - 1;
+      const uint32_t node = s_list[li];
+      unsigned long long bits = s_bits[li];
+      if constexpr (LOGK == 6) bits |= (unsigned long long)s_bits_hi[li] << 32;
       PER_MARK(4);
+      // A set bit means the leaf was claimed in this batch: its stamp entry holds the winner's value.
       float sum;
       if constexpr (LOGK == 1) {
+        const uint32_t my = (uint32_t)bits & 3u;
         float2 c = *reinterpret_cast<const float2*>(leaves + (size_t)node * 2);
-        const uint4 o = *reinterpret_cast<const uint4*>(owner + (size_t)node * 2);
-        const bool w0 = o.y - stamp_base < B, w1 = o.w - stamp_base < B;
-        if (w0) c.x = __uint_as_float(o.x);
-        if (w1) c.y = __uint_as_float(o.z);
-        if (ok && (w0 || w1)) *reinterpret_cast<float2*>(leaves + (size_t)node * 2) = c;
+        uint2 s0 = make_uint2(0, 0), s1 = make_uint2(0, 0);
+        if (my & 1u) s0 = owner[(size_t)node * 2];
+        if (my & 2u) s1 = owner[(size_t)node * 2 + 1];
+        if (my & 1u) c.x = __uint_as_float(s0.x);
+        if (my & 2u) c.y = __uint_as_float(s1.x);
+        if (ok && my) *reinterpret_cast<float2*>(leaves + (size_t)node * 2) = c;
         sum = c.x + c.y;
       } else {
+        const uint32_t my = (uint32_t)(bits >> (4 * q)) & 0xFu;
         const size_t at = (size_t)node * K + 4 * q;
         float4 c = *reinterpret_cast<const float4*>(leaves + at);
-        const uint4 oa = *reinterpret_cast<const uint4*>(owner + at);
-        const uint4 ob = *reinterpret_cast<const uint4*>(owner + at + 2);
-        const bool w0 = oa.y - stamp_base < B, w1 = oa.w - stamp_base < B;
-        const bool w2 = ob.y - stamp_base < B, w3 = ob.w - stamp_base < B;
-        if (w0) c.x = __uint_as_float(oa.x);
-        if (w1) c.y = __uint_as_float(oa.z);
-        if (w2) c.z = __uint_as_float(ob.x);
-        if (w3) c.w = __uint_as_float(ob.z);
-        if (ok && (w0 || w1 || w2 || w3)) *reinterpret_cast<float4*>(leaves + at) = c;
+        uint2 s0 = make_uint2(0, 0), s1 = s0, s2 = s0, s3 = s0;
+        if (my & 1u) s0 = owner[at];
+        if (my & 2u) s1 = owner[at + 1];
+        if (my & 4u) s2 = owner[at + 2];
+        if (my & 8u) s3 = owner[at + 3];
+        if (my & 1u) c.x = __uint_as_float(s0.x);
+        if (my & 2u) c.y = __uint_as_float(s1.x);
+        if (my & 4u) c.z = __uint_as_float(s2.x);
+        if (my & 8u) c.w = __uint_as_float(s3.x);
+        if (ok && my) *reinterpret_cast<float4*>(leaves + at) = c;
         sum = (c.x + c.y) + (c.z + c.w);
         PER_MARK(5);
 #pragma unroll
@@ -1049,7 +1086,15 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   PER_FLUSH();
   // The flags are cleared only now: a wait for loaded data also waits for every earlier store
   // of the wave, so stores that nothing depends on go last.
-  for (uint32_t i = threadIdx.x; i < nd; i += blockDim.x) dirty[s_list[i]] = 0;
+  for (uint32_t i = threadIdx.x; i < nd; i += blockDim.x) {
+    const uint32_t node = s_list[i];
+    if constexpr (LOGK == 6) {
+      dirty[2 * (size_t)node] = 0;
+      dirty[2 * (size_t)node + 1] = 0;
+    } else {
+      dirty[(node << LOGK) >> 5] = 0;   // for K < 32 the word is shared with neighbours of the same subtree
+    }
+  }
   // ---- 3. above the subtree: the last child to arrive recomputes the parent
   if (!chain) return;   // the heights above hb are left to their next reader
   uint32_t node = b;
@@ -1118,11 +1163,19 @@ static hipError_t launch_update_k(const Geom& g, const Tuning& tn, uint32_t B, u
     off += (uint32_t)(full < padded ? full : padded);
   }
   sl.lds_floats = off;
-  // enough lane groups to rebuild every height-1 node of a subtree in one sweep, unless told otherwise
+  // Unless told otherwise: enough lane groups to rebuild in one sweep twice the dirty height-1 nodes a
+  // subtree gets on average (never more than it has), so that small batches do not launch idle waves.
   uint32_t tblock = tn.tree_block;
   if (tblock == 0) {
-    const uint64_t want = (uint64_t)sl.lds_off[hb > 1 ? 1 : 0] * Fan<LOGK>::LPS;
-    tblock = hb > 1 ? (uint32_t)(want > 1024 ? 1024 : (want + 63) / 64 * 64) : 64u;
+    const uint64_t per_subtree = hb > 1 ? sl.lds_off[1] : 1;
+    uint64_t expect = 2 * ((uint64_t)B + g.n[hb] - 1) / g.n[hb];
+    if (expect > per_subtree) expect = per_subtree;
+    uint64_t want = expect * Fan<LOGK>::LPS;
+    if (hb > 2) {   // the dense heights of the subtree want a lane group per height-2 node
+      const uint64_t dense = (uint64_t)(sl.lds_off[2] - sl.lds_off[1]) * Fan<LOGK>::LPS;
+      if (dense > want) want = dense;
+    }
+    tblock = (uint32_t)(want > 1024 ? 1024 : (want + 63) / 64 * 64);
     if (tblock < 64) tblock = 64;
   }
   PER_LAUNCH(KID_UPDATE_TREE, k_update_tree<LOGK>, dim3(g.n[hb], g.T), dim3(tblock), (size_t)off * 4, s, g, sl, B,
