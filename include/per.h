@@ -151,6 +151,9 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
  *   "lds_budget_bytes" : upper tree levels are staged in LDS while they fit this many bytes
  *   "sample_block", "update_block", "gather_block" : workgroup sizes (multiples of 64, <= 1024)
  *   "tree_block" : workgroup size of the update's tree pass (multiple of 64, <= 1024; 0 = chosen per launch)
+ *   "sample_min_lds" : lower bound in bytes of the sampling kernel's LDS request
+ *   "stamp_next" : moves the last-writer stamp counter forward (never back); stamps are 32 bits and
+ *                  the library clears the stamp array and starts over when they run out
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
  *                  the next call that reads them; 0 makes per_update finish them itself */
 int per_set_tuning(per_t* p, const char* name, int64_t value);

@@ -373,6 +373,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
     p->tn.lds_budget_bytes = (uint32_t)value;
     return PER_OK;
   }
+  if (!strcmp(name, "stamp_next")) {   // test hook: move the last-writer stamp counter (e.g. close to its wrap)
+    if (value < (int64_t)p->stamp_next || value > 0xFFFFFFFFll) return PER_EINVAL;
+    p->stamp_next = (uint64_t)value;
+    return PER_OK;
+  }
   if (!strcmp(name, "sample_min_lds")) {
     if (value < 0 || value > 160 * 1024) return PER_EINVAL;
     p->tn.sample_min_lds = (uint32_t)value;

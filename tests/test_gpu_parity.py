@@ -100,6 +100,21 @@ def test_last_writer_adversarial(K):
     m.compare_status()
 
 
+def test_last_writer_stamps_wrap_around():
+    """The 32-bit stamp counter is pushed to just below its end: the next updates must clear the stamp
+    array, start over, and still pick the last writer."""
+    rng = np.random.default_rng(5)
+    N, T, B = 20000, 2, 3000
+    m = Mirror(16, N, T, ())
+    m.insert(N, prio=rng.random((T, N)).astype(np.float32), with_rows=False)
+    m.update(rng.integers(0, 200, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
+    m.gpu.set_tuning("stamp_next", 0xFFFFFFFF - 2 * B - 5)
+    for it in range(4):        # the third call no longer fits below 2^32
+        m.update(rng.integers(0, 200, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
+        m.compare_tree()
+    m.compare_status()
+
+
 def test_determinism_same_state_same_bits():
     rng = np.random.default_rng(0)
     N, B = 100000, 4096
@@ -205,7 +220,7 @@ def test_results_do_not_depend_on_tuning(K):
         assert out == ref, (lds, blk)
 
 
-@pytest.mark.parametrize("K,N", [(2, (1 << 20) + 77), (8, 3 << 20), (16, 1 << 16)])
+@pytest.mark.parametrize("K,N", [(2, (1 << 20) + 77), (8, 3 << 20), (16, 1 << 16), (64, 300001), (4, 70001)])
 def test_update_sample_chain(K, N):
     """Update -> sample -> update -> insert chains, on trees large enough that the update finishes the
     top heights itself (K = 2, 8) and on one where it leaves them to the next reader (K = 16)."""
