@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps eagerly instead of as one HIP graph")
     ap.add_argument("--separate-gather", action="store_true",
                     help="call per_sample and per_gather separately instead of the fused per_sample_gather")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="call per_update by itself instead of per_sample_gather_update")
     ap.add_argument("--overlap", action="store_true",
                     help="with --separate-gather: run the row gather on a second stream beside the update")
     ap.add_argument("--tune", action="append", default=[], help="name=value passed to per_set_tuning")
@@ -55,7 +57,7 @@ def algorithmic_bytes(w, idx, upd_idx, K, H, h_mem, weights, fused):
     logK = K.bit_length() - 1
     T, B = idx.shape
     E = w.row_bytes
-    out = {"k_sample": 0, "k_weights": 0, "k_rows_gather": 0, "k_update_claim": 0, "k_update_tree": 0}
+    out = {"k_sample": 0, "k_weights": 0, "k_rows_gather": 0, "k_update_claim": 0, "k_update_tree": 0}   # k_finish below
     for t in range(T):
         i64 = idx[t].astype(np.int64)
         groups = sum(len(np.unique(i64 >> ((h + 1) * logK))) * 4 * K for h in range(0, min(h_mem, H)))
@@ -68,7 +70,7 @@ def algorithmic_bytes(w, idx, upd_idx, K, H, h_mem, weights, fused):
         for h in range(1, H + 1):
             q = len(np.unique(u64 >> (h * logK)))
             out["k_update_tree"] += 4 * K * q + 4 * q                                     # child groups in, node out
-    out["k_rows_gather_weights"] = out["k_rows_gather"] + out["k_weights"]
+    out["k_finish"] = out["k_rows_gather"] + out["k_weights"] + (out["k_update_claim"] if fused == "step" else 0)
     return out
 
 
@@ -145,6 +147,7 @@ def main():
     side = torch.cuda.Stream()
     gather_done = [None]
     fused = not args.separate_gather
+    fused_step = fused and not args.separate_update
 
     def step(s, recording=False, overlap=False):
         """insert -> sample -> gather -> update.  With overlap the row gather (which only reads the
@@ -155,8 +158,12 @@ def main():
             if overlap and gather_done[0] is not None:
                 main.wait_event(gather_done[0])      # an insert may overwrite a row the last gather reads
             buf.insert(w.n_insert, ins_rows[s])
+        whole = fused_step and not recording     # the recording pass has to build the update indices in between
         buf.sample(d_u[s], inputs[s]["beta"], want_weights=w.weights, want_prio=True,
-                   out_idx=d_idx[s], out_weight=d_w, out_prio=d_v, rows_out=d_rows if fused else None)
+                   out_idx=d_idx[s], out_weight=d_w, out_prio=d_v, rows_out=d_rows if fused else None,
+                   update=(d_upd_idx[s], d_prio[s]) if whole else None)
+        if whole:
+            return
         if fused:
             pass
         elif overlap:
@@ -257,7 +264,8 @@ def main():
         slots += 1
         h_mem = l
     sel = list(range(warmup, total_steps, max(1, steps // 16)))
-    per_step = [algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, h_mem, w.weights, fused) for s in sel]
+    per_step = [algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, h_mem, w.weights,
+                                  "step" if fused_step else fused) for s in sel]
     alg = {k: float(np.mean([p[k] for p in per_step])) for k in per_step[0]}
     a_sample = alg["k_sample"]
     a_gather = alg["k_rows_gather"] + alg["k_weights"]
@@ -315,7 +323,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "K": K, "N": N, "T": T, "B": B, "row_bytes": w.row_bytes,
                    "insert_per_step": w.n_insert, "launch": "hip_graph" if graph is not None else "eager",
-                   "streams": 2 if overlap else 1, "sample_and_gather": "fused" if fused else "separate"},
+                   "streams": 2 if overlap else 1, "calls_per_step": "per_sample_gather_update" if fused_step else
+                   ("per_sample_gather, per_update" if fused else "per_sample, per_gather, per_update")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "step_algorithmic_bytes": int(a_step),

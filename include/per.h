@@ -113,6 +113,17 @@ int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field
 int per_sample_gather(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx,
                       float* d_out_weight, float* d_out_prio, void* const* d_field_dst, void* stream);
 
+/* per_sample_gather followed by per_update(upd_B, d_upd_idx, d_upd_prio), as one call with the same
+ * results: the update's claim phase, which does not touch what sampling reads, rides in the kernel
+ * that gathers the rows, so the pair costs three launches instead of four.  This is the steady
+ * state of a pipelined trainer: draw the next batch, then apply the priorities computed for an
+ * earlier one.  d_upd_idx may alias d_out_idx (update the rows just drawn).  d_field_dst may be
+ * NULL (no gather).  upd_B == 0 makes it per_sample_gather. */
+int per_sample_gather_update(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx,
+                             float* d_out_weight, float* d_out_prio, void* const* d_field_dst,
+                             uint32_t upd_B, const uint32_t* d_upd_idx, const float* d_upd_prio,
+                             void* stream);
+
 /* Priority update (Section V-A), in the set-and-re-sum form: every valid element sets its
  * leaf; when an index occurs more than once the element latest in the batch wins;
  * afterwards every ancestor of a touched leaf equals the pairwise sum of its children.

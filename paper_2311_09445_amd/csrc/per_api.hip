@@ -247,8 +247,30 @@ int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float
   return hip_rc(e);
 }
 
+// Takes the stamps of one update batch from the host counter (clearing the stamp array when the
+// 32-bit stamps run out).
+static int reserve_stamps(per_t* p, uint32_t B, hipStream_t s, uint32_t* base) {
+  if (p->stamp_next + B > 0xFFFFFFFFull) {
+    hipError_t e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(p->g.owner), 2ull * p->g.owner_stride * p->g.T, 0u, s);
+    if (e != hipSuccess) return PER_EHIP;
+    p->stamp_next = 1;
+  }
+  *base = (uint32_t)p->stamp_next;
+  p->stamp_next += B;
+  return PER_OK;
+}
+
+static int check_update_args(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio) {
+  if (!p) return PER_EINVAL;
+  if (B == 0) return PER_OK;
+  if (!d_idx || !d_prio || misaligned(d_idx, 4) || misaligned(d_prio, 4)) return PER_EINVAL;
+  if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
+  return PER_OK;
+}
+
 static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
-                       float* d_out_prio, void* const* d_field_dst, void* stream) {
+                       float* d_out_prio, void* const* d_field_dst, uint32_t upd_B, const uint32_t* d_upd_idx,
+                       const float* d_upd_prio, void* stream) {
   if (!p) return PER_EINVAL;
   if (B == 0) return PER_OK;
   if (!d_u || !d_out_idx || misaligned(d_u, 4) || misaligned(d_out_idx, 4) || misaligned(d_out_weight, 4) ||
@@ -257,23 +279,49 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
   if (!isfinite(beta) || beta < 0.0f) return PER_EINVAL;
   if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
   if (p->size == 0) return PER_EEMPTY;
+  hipStream_t s = static_cast<hipStream_t>(stream);
   FieldTable ft;
   const bool fused = d_field_dst && fill_fields(p, d_field_dst, &ft);
+  ClaimArgs claim{};
+  if (upd_B) {
+    claim.B = upd_B;
+    claim.size = (uint32_t)p->size;
+    claim.idx = d_upd_idx;
+    claim.prio = d_upd_prio;
+    int rc = reserve_stamps(p, upd_B, s, &claim.stamp_base);
+    if (rc != PER_OK) return rc;
+  }
   const uint32_t stale = p->stale_hb;
   p->stale_hb = 0;   // the sampling kernel rebuilds and stores the stale heights
-  return hip_rc(launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, d_out_idx, d_out_weight, d_out_prio,
-                              &p->weight_calls, stale, fused ? &ft : nullptr, static_cast<hipStream_t>(stream)));
+  hipError_t e = launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, d_out_idx, d_out_weight, d_out_prio,
+                               &p->weight_calls, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr, s);
+  if (e == hipSuccess && upd_B) {
+    e = launch_update(p->g, p->tn, claim, true, s);
+    if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
+  }
+  return hip_rc(e);
 }
 
 int per_sample(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
                float* d_out_prio, void* stream) {
-  return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, nullptr, stream);
+  return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, nullptr, 0, nullptr, nullptr, stream);
 }
 
 int per_sample_gather(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
                       float* d_out_prio, void* const* d_field_dst, void* stream) {
   if (!d_field_dst) return PER_EINVAL;
-  return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, stream);
+  return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, 0, nullptr, nullptr, stream);
+}
+
+int per_sample_gather_update(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx,
+                             float* d_out_weight, float* d_out_prio, void* const* d_field_dst, uint32_t upd_B,
+                             const uint32_t* d_upd_idx, const float* d_upd_prio, void* stream) {
+  int rc = check_update_args(p, upd_B, d_upd_idx, d_upd_prio);
+  if (rc != PER_OK) return rc;
+  if (B == 0)   // nothing to sample: plain update
+    return upd_B ? per_update(p, upd_B, d_upd_idx, d_upd_prio, stream) : PER_OK;
+  return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, upd_B, d_upd_idx, d_upd_prio,
+                     stream);
 }
 
 int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field_dst, void* stream) {
@@ -286,19 +334,17 @@ int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field
 }
 
 int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio, void* stream) {
-  if (!p) return PER_EINVAL;
-  if (B == 0) return PER_OK;
-  if (!d_idx || !d_prio || misaligned(d_idx, 4) || misaligned(d_prio, 4)) return PER_EINVAL;
-  if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
+  int rc = check_update_args(p, B, d_idx, d_prio);
+  if (rc != PER_OK || B == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (p->stamp_next + B > 0xFFFFFFFFull) {   // stamps exhausted: start over from a cleared array
-    hipError_t e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(p->g.owner), 2ull * p->g.owner_stride * p->g.T, 0u, s);
-    if (e != hipSuccess) return PER_EHIP;
-    p->stamp_next = 1;
-  }
-  const uint32_t base = (uint32_t)p->stamp_next;
-  p->stamp_next += B;
-  hipError_t e = launch_update(p->g, p->tn, B, (uint32_t)p->size, d_idx, d_prio, base, s);
+  ClaimArgs claim{};
+  claim.B = B;
+  claim.size = (uint32_t)p->size;
+  claim.idx = d_idx;
+  claim.prio = d_prio;
+  rc = reserve_stamps(p, B, s, &claim.stamp_base);
+  if (rc != PER_OK) return rc;
+  hipError_t e = launch_update(p->g, p->tn, claim, false, s);
   if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
   return hip_rc(e);
 }

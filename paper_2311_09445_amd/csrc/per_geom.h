@@ -46,11 +46,36 @@ struct FieldTable {
   uint32_t n_fields;
 };
 
+// Claim phase of a priority update (first half of per_update).
+struct ClaimArgs {
+  uint32_t B, size, stamp_base;
+  const uint32_t* idx;     // [T][B]
+  const float* prio;       // [T][B]
+};
+
+// Jobs of the second kernel of the fused calls (see k_finish).
+struct FinishArgs {
+  uint32_t B;              // sampled batch
+  const uint32_t* idx;     // [T][B] sampled indices
+  float* w;                // [T][B] sampled values in, weights out; nullptr: no weights job
+  uint32_t size;
+  float beta;
+  uint32_t parity;
+  uint32_t has_claim;
+  ClaimArgs claim;
+};
+
+// Workgroup ranges of the jobs sharing one launch: [first[j], first[j+1]) for job j, where job 0 is the
+// weights, job 1 the claim and job 2 + f the rows of payload field f.
+struct JobRanges {
+  uint32_t first[3 + kMaxFields];
+};
+
 struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b0) u [a1,b1)
 
 // Optional per-kernel timing with HIP events attached to each launch (off by default).
 enum KernelId {
-  KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_GATHER_WEIGHTS, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
+  KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_GET_PRIORITY, KID_COUNT
 };
 const char* kernel_name(int kid);
@@ -79,7 +104,7 @@ hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
-                         const FieldTable* rows, hipStream_t s);
+                         const FieldTable* rows, const ClaimArgs* claim, hipStream_t s);
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s);
 hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t n, uint32_t cursor,
@@ -89,8 +114,7 @@ hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uin
 hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipStream_t s);
 hipError_t launch_resum_top(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
 uint32_t lazy_top_height(const Geom& g, const Tuning& tn);
-hipError_t launch_update(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
-                         const float* prio, uint32_t stamp_base, hipStream_t s);
+hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, bool claimed, hipStream_t s);
 hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
 hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s);
 hipError_t launch_clear_status(const Geom& g, hipStream_t s);

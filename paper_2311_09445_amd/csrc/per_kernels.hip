@@ -21,7 +21,7 @@ namespace per {
 // ---------------------------------------------------------------------------------
 const char* kernel_name(int kid) {
   static const char* const names[KID_COUNT] = {
-      "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_rows_gather_weights", "k_rows_scatter", "k_insert_leaves",
+      "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_finish", "k_rows_scatter", "k_insert_leaves",
       "k_resum_dense", "k_resum_tail", "k_update_claim", "k_update_tree", "k_get_priority"};
   return kid >= 0 && kid < KID_COUNT ? names[kid] : "?";
 }
@@ -527,14 +527,14 @@ __global__ void k_weights(Geom g, uint32_t B, uint32_t size, float beta, float* 
 
 template <int LOGK>
 static hipError_t launch_resum_top_k(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
-static hipError_t launch_gather_weights(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B,
-                                        const uint32_t* idx, float* w, uint32_t size, float beta, uint32_t parity,
-                                        hipStream_t s);
+static hipError_t launch_finish(const Geom& g, const Tuning& tn, const FieldTable* rows, const FinishArgs& a,
+                                hipStream_t s);
 
 template <int LOGK>
 static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
                                   const float* u, uint32_t* out_idx, float* out_w, float* out_prio,
-                                  uint32_t* weight_calls, uint32_t stale_hb, const FieldTable* rows, hipStream_t s) {
+                                  uint32_t* weight_calls, uint32_t stale_hb, const FieldTable* rows,
+                                  const ClaimArgs* claim, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
   constexpr uint32_t kLdsCap = 128 * 1024;
   const uint32_t wave_bytes = LOGK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
@@ -596,8 +596,18 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const bool finish_weights = out_w && gx > 1;
-  if (rows)   // fused call: the rows are gathered by a second kernel that also finishes the weights
-    return launch_gather_weights(g, tn, *rows, B, out_idx, finish_weights ? out_w : nullptr, size, beta, parity, s);
+  if (rows || claim) {   // fused call: one more kernel gathers the rows, finishes the weights and claims the update
+    FinishArgs a{};
+    a.B = B;
+    a.idx = out_idx;
+    a.w = finish_weights ? out_w : nullptr;
+    a.size = size;
+    a.beta = beta;
+    a.parity = parity;
+    a.has_claim = claim ? 1u : 0u;
+    if (claim) a.claim = *claim;
+    return launch_finish(g, tn, rows, a, s);
+  }
   if (!finish_weights) return e;
   PER_LAUNCH(KID_WEIGHTS, k_weights, dim3((B + 255) / 256, g.T), dim3(256), 0, s, g, B, size, beta, out_w, parity);
   return hipGetLastError();
@@ -616,11 +626,46 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
 
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
-                         const FieldTable* rows, hipStream_t s) {
-#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, weight_calls, stale_hb, rows, s)
+                         const FieldTable* rows, const ClaimArgs* claim, hipStream_t s) {
+#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, weight_calls, stale_hb, rows, claim, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }
+
+// ---------------------------------------------------------------------------------
+// priority update, first half: claim
+// ---------------------------------------------------------------------------------
+// Element j raises the 64-bit stamp of its leaf to (stamp_base + j) << 32 | value bits by
+// atomic max, and sets the leaf's bit in the dirty mask (one bit per leaf).  The largest j wins
+// and carries its value with it.  Stamps grow from call to call, so stale stamps never win
+// and the stamp array needs no clearing between calls.  Called by whole workgroups.
+__device__ __forceinline__ void claim_job(const Geom& g, uint32_t t, const ClaimArgs& c, uint32_t job_block,
+                                          uint32_t job_blocks) {
+  if (job_block * blockDim.x >= c.B) return;   // nothing to do for this workgroup
+  const uint32_t max_seen = read_max_bits(g, t);
+  uint32_t mx = 0;
+  uint32_t flags = 0;
+  for (uint32_t base = job_block * blockDim.x; base < c.B; base += job_blocks * blockDim.x) {
+    const uint32_t j = base + threadIdx.x;
+    if (j < c.B) {
+      const uint32_t i = c.idx[(size_t)t * c.B + j];
+      const float v = c.prio[(size_t)t * c.B + j];
+      if (!(i < c.size)) flags |= 1u;
+      else if (!valid_priority(v)) flags |= 2u;
+      else {
+        const unsigned long long stamp = ((unsigned long long)(c.stamp_base + j) << 32) | __float_as_uint(v);
+        atomicMax(reinterpret_cast<unsigned long long*>(g.owner) + (size_t)t * g.owner_stride + i, stamp);
+        atomicOr(&g.dirty[(size_t)t * g.dirty_stride + (i >> 5)], 1u << (i & 31u));
+        const uint32_t vb = v > 0.0f ? __float_as_uint(v) : 0u;
+        mx = vb > mx ? vb : mx;
+      }
+    }
+  }
+  raise_max(g, t, mx, max_seen);
+  if (flags) atomicOr(&g.status[t], flags);
+}
+
+__global__ void k_update_claim(Geom g, ClaimArgs c) { claim_job(g, blockIdx.y, c, blockIdx.x, gridDim.x); }
 
 // ---------------------------------------------------------------------------------
 // Data Storage: row gather and row scatter
@@ -630,108 +675,152 @@ hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t s
 template <typename V, bool GATHER>
 __device__ __forceinline__ void move_rows(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
                                           const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
-                                          uint32_t* status) {
+                                          uint32_t* status, uint32_t job_block, uint32_t job_blocks) {
   const uint32_t E = ft.bytes[f];
   const uint32_t epr = E / (uint32_t)sizeof(V);
   const uint64_t total = (uint64_t)B * epr;
   uint8_t* col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
   uint8_t* io = ft.io[f] + (uint64_t)t * B * E;
   bool bad = false;
-  for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
-    const uint32_t row = (uint32_t)(e / epr);
-    const uint32_t k = (uint32_t)(e - (uint64_t)row * epr);
-    V* dense = reinterpret_cast<V*>(io + (uint64_t)row * E) + k;
+  // Two elements per lane and sweep, both loads issued before the first store: a wait for loaded
+  // data also waits for earlier stores, so load -> store -> load would cost two memory trips.
+  const uint64_t stride = (uint64_t)job_blocks * blockDim.x;
+  for (uint64_t e0 = (uint64_t)job_block * blockDim.x + threadIdx.x; e0 < total; e0 += 2 * stride) {
+    const uint64_t e1 = e0 + stride;
+    const bool live1 = e1 < total;
+    const uint64_t e1c = live1 ? e1 : e0;
+    const uint32_t row0 = (uint32_t)(e0 / epr), row1 = (uint32_t)(e1c / epr);
+    const uint32_t k0 = (uint32_t)(e0 - (uint64_t)row0 * epr), k1 = (uint32_t)(e1c - (uint64_t)row1 * epr);
+    V* dense0 = reinterpret_cast<V*>(io + (uint64_t)row0 * E) + k0;
+    V* dense1 = reinterpret_cast<V*>(io + (uint64_t)row1 * E) + k1;
     if constexpr (GATHER) {
-      const uint32_t i = idx[(size_t)t * B + row];
-      if (i < N) {
-        *dense = *(reinterpret_cast<const V*>(col + (uint64_t)i * E) + k);
-      } else {
-        V z;
-        __builtin_memset(&z, 0, sizeof(V));
-        *dense = z;
-        bad = true;
-      }
+      const uint32_t i0 = idx[(size_t)t * B + row0];
+      const uint32_t i1 = idx[(size_t)t * B + row1];
+      const bool ok0 = i0 < N, ok1 = i1 < N;
+      V v0 = *(reinterpret_cast<const V*>(col + (uint64_t)(ok0 ? i0 : 0u) * E) + k0);
+      V v1 = *(reinterpret_cast<const V*>(col + (uint64_t)(ok1 ? i1 : 0u) * E) + k1);
+      if (!ok0) __builtin_memset(&v0, 0, sizeof(V));
+      if (!ok1) __builtin_memset(&v1, 0, sizeof(V));
+      bad |= !ok0 || (live1 && !ok1);
+      *dense0 = v0;
+      if (live1) *dense1 = v1;
     } else {
-      uint64_t slot = (uint64_t)cursor + row;
-      if (slot >= N) slot -= N;
-      *(reinterpret_cast<V*>(col + slot * E) + k) = *dense;
+      uint64_t slot0 = (uint64_t)cursor + row0, slot1 = (uint64_t)cursor + row1;
+      if (slot0 >= N) slot0 -= N;
+      if (slot1 >= N) slot1 -= N;
+      const V v0 = *dense0;
+      const V v1 = *dense1;
+      *(reinterpret_cast<V*>(col + slot0 * E) + k0) = v0;
+      if (live1) *(reinterpret_cast<V*>(col + slot1 * E) + k1) = v1;
     }
   }
   if (bad) atomicOr(&status[t], 1u);
 }
 
-// Row gather of a fused sample+gather call: the workgroups with blockIdx.y == 0 finish the
-// importance weights instead of moving rows (they are dispatched first, so the fp64 work runs
-// beside the row traffic), the others move field blockIdx.y - 1.
-__global__ void k_rows_weights(FieldTable ft, Geom g, uint32_t B, const uint32_t* __restrict__ idx, float* __restrict__ w,
-                               uint32_t size, float beta, uint32_t parity) {
-  const uint32_t t = blockIdx.z;
-  if (blockIdx.y == 0) {
-    weights_job(g, t, B, size, beta, w, parity, blockIdx.x, gridDim.x);
+// Moves the rows of one payload field; the workgroup is number job_block of job_blocks on that field.
+template <bool GATHER>
+__device__ __forceinline__ void rows_job(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
+                                         const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
+                                         uint32_t* status, uint32_t job_block, uint32_t job_blocks) {
+  switch (ft.vec[f]) {
+    case 16: move_rows<uint4, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
+    case 8: move_rows<uint2, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
+    case 4: move_rows<uint32_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
+    case 2: move_rows<uint16_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
+    default: move_rows<uint8_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
+  }
+}
+
+// Second kernel of the fused calls.  Its workgroups (blockIdx.x) split into jobs, each with as many
+// workgroups as it needs (JobRanges): first the importance weights of the batch just sampled (if
+// asked for), then the claim phase of a priority update (if one is fused in), then one job per
+// payload field of the sampled rows.  The small jobs come first, so their latency hides behind the
+// row traffic.
+__global__ void k_finish(FieldTable ft, JobRanges jr, Geom g, FinishArgs a) {
+  const uint32_t t = blockIdx.y;
+  const uint32_t b = blockIdx.x;
+  if (b < jr.first[1]) {
+    weights_job(g, t, a.B, a.size, a.beta, a.w, a.parity, b, jr.first[1]);
     return;
   }
-  const uint32_t f = blockIdx.y - 1;
-  if (ft.io[f] == nullptr) return;
-  switch (ft.vec[f]) {
-    case 16: move_rows<uint4, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
-    case 8: move_rows<uint2, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
-    case 4: move_rows<uint32_t, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
-    case 2: move_rows<uint16_t, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
-    default: move_rows<uint8_t, true>(ft, f, t, B, idx, 0, g.N, g.status); break;
+  if (b < jr.first[2]) {
+    claim_job(g, t, a.claim, b - jr.first[1], jr.first[2] - jr.first[1]);
+    return;
   }
+#pragma unroll
+  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
+    if (b >= jr.first[2 + f] && b < jr.first[3 + f]) {
+      rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+      return;
+    }
 }
 
+// Stand-alone gather (GATHER) and insert scatter: one job per payload field.
 template <bool GATHER>
-__global__ void k_rows(FieldTable ft, uint32_t B, const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
-                       uint32_t* status) {
-  const uint32_t f = blockIdx.y, t = blockIdx.z;
-  if (ft.io[f] == nullptr) return;
-  switch (ft.vec[f]) {
-    case 16: move_rows<uint4, GATHER>(ft, f, t, B, idx, cursor, N, status); break;
-    case 8: move_rows<uint2, GATHER>(ft, f, t, B, idx, cursor, N, status); break;
-    case 4: move_rows<uint32_t, GATHER>(ft, f, t, B, idx, cursor, N, status); break;
-    case 2: move_rows<uint16_t, GATHER>(ft, f, t, B, idx, cursor, N, status); break;
-    default: move_rows<uint8_t, GATHER>(ft, f, t, B, idx, cursor, N, status); break;
-  }
+__global__ void k_rows(FieldTable ft, JobRanges jr, uint32_t B, const uint32_t* __restrict__ idx, uint32_t cursor,
+                       uint32_t N, uint32_t* status) {
+  const uint32_t t = blockIdx.y;
+  const uint32_t b = blockIdx.x;
+#pragma unroll
+  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
+    if (b >= jr.first[2 + f] && b < jr.first[3 + f]) {
+      rows_job<GATHER>(ft, f, t, B, idx, cursor, N, status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+      return;
+    }
 }
 
-static uint32_t rows_grid_x(const FieldTable& ft, uint32_t B, uint32_t block) {
-  uint64_t most = 1;
-  for (uint32_t f = 0; f < ft.n_fields; ++f) {
-    if (!ft.io[f]) continue;
-    const uint64_t e = (uint64_t)B * (ft.bytes[f] / ft.vec[f]);
-    if (e > most) most = e;
+// Workgroups per job: weights, claim, then each field with a destination (a field's count is what
+// one pass over its elements needs, capped; the movers stride when capped).
+static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block, uint32_t weights_B, uint32_t claim_B) {
+  JobRanges jr{};
+  uint32_t at = 0;
+  jr.first[0] = at;
+  at += (weights_B + block - 1) / block;
+  jr.first[1] = at;
+  at += (claim_B + block - 1) / block;
+  jr.first[2] = at;
+  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f) {
+    if (ft && f < ft->n_fields && ft->io[f]) {
+      // two elements per lane once a field is large enough to matter, so that the whole launch stays resident
+      const uint64_t elems = (uint64_t)rows * (ft->bytes[f] / ft->vec[f]);
+      uint64_t n = (elems + block - 1) / block;
+      if (n > 512) n = (elems + 2 * block - 1) / (2 * block);
+      if (n > (1u << 20)) n = 1u << 20;
+      at += (uint32_t)n;
+    }
+    jr.first[3 + f] = at;
   }
-  uint64_t gx = (most + block - 1) / block;
-  if (gx > 65535u * 16u) gx = 65535u * 16u;
-  return (uint32_t)gx;
+  return jr;
 }
 
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s) {
-  if (ft.n_fields == 0) return hipSuccess;
   const uint32_t block = tn.gather_block;
-  PER_LAUNCH(KID_GATHER, k_rows<true>, dim3(rows_grid_x(ft, B, block), ft.n_fields, g.T), dim3(block), 0, s, ft, B,
-             idx, 0, g.N, g.status);
+  const JobRanges jr = job_ranges(&ft, B, block, 0, 0);
+  const uint32_t gx = jr.first[2 + kMaxFields];
+  if (gx == 0) return hipSuccess;
+  PER_LAUNCH(KID_GATHER, k_rows<true>, dim3(gx, g.T), dim3(block), 0, s, ft, jr, B, idx, 0, g.N, g.status);
   return hipGetLastError();
 }
 
-static hipError_t launch_gather_weights(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B,
-                                        const uint32_t* idx, float* w, uint32_t size, float beta, uint32_t parity,
-                                        hipStream_t s) {
-  if (!w) return launch_gather(g, tn, ft, B, idx, s);
+static hipError_t launch_finish(const Geom& g, const Tuning& tn, const FieldTable* rows, const FinishArgs& a,
+                                hipStream_t s) {
+  FieldTable ft{};
+  if (rows) ft = *rows;
+  if (!a.w && !a.has_claim) return rows ? launch_gather(g, tn, ft, a.B, a.idx, s) : hipSuccess;
   const uint32_t block = tn.gather_block;
-  PER_LAUNCH(KID_GATHER_WEIGHTS, k_rows_weights, dim3(rows_grid_x(ft, B, block), ft.n_fields + 1, g.T), dim3(block), 0,
-             s, ft, g, B, idx, w, size, beta, parity);
+  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, block, a.w ? a.B : 0u, a.has_claim ? a.claim.B : 0u);
+  PER_LAUNCH(KID_FINISH, k_finish, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), 0, s, ft, jr, g, a);
   return hipGetLastError();
 }
 
 hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t n, uint32_t cursor,
                           hipStream_t s) {
-  if (ft.n_fields == 0) return hipSuccess;
   const uint32_t block = tn.gather_block;
-  PER_LAUNCH(KID_SCATTER, k_rows<false>, dim3(rows_grid_x(ft, n, block), ft.n_fields, g.T), dim3(block), 0, s, ft,
-             n, nullptr, cursor, g.N, g.status);
+  const JobRanges jr = job_ranges(&ft, n, block, 0, 0);
+  const uint32_t gx = jr.first[2 + kMaxFields];
+  if (gx == 0) return hipSuccess;
+  PER_LAUNCH(KID_SCATTER, k_rows<false>, dim3(gx, g.T), dim3(block), 0, s, ft, jr, n, nullptr, cursor, g.N, g.status);
   return hipGetLastError();
 }
 
@@ -878,34 +967,6 @@ hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uin
 // ---------------------------------------------------------------------------------
 // priority update: claim (last writer), then one tree pass
 // ---------------------------------------------------------------------------------
-// Claim: element j raises the 64-bit stamp of its leaf to (stamp_base + j) << 32 | value bits
-// by atomic max, and sets the leaf's bit in the dirty mask (one bit per leaf).  The largest j wins and carries its
-// value with it.  Stamps grow from call to call, so stale stamps never win and the stamp
-// array needs no clearing between calls.
-template <int LOGK>
-__global__ void k_update_claim(Geom g, uint32_t B, uint32_t size, const uint32_t* __restrict__ idx,
-                               const float* __restrict__ prio, uint32_t stamp_base) {
-  const uint32_t t = blockIdx.y;
-  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  const uint32_t max_seen = read_max_bits(g, t);
-  uint32_t mx = 0;
-  uint32_t flags = 0;
-  if (j < B) {
-    const uint32_t i = idx[(size_t)t * B + j];
-    const float v = prio[(size_t)t * B + j];
-    if (!(i < size)) flags = 1u;
-    else if (!valid_priority(v)) flags = 2u;
-    else {
-      const unsigned long long stamp = ((unsigned long long)(stamp_base + j) << 32) | __float_as_uint(v);
-      atomicMax(reinterpret_cast<unsigned long long*>(g.owner) + (size_t)t * g.owner_stride + i, stamp);
-      atomicOr(&g.dirty[(size_t)t * g.dirty_stride + (i >> 5)], 1u << (i & 31u));
-      mx = v > 0.0f ? __float_as_uint(v) : 0u;
-    }
-  }
-  raise_max(g, t, mx, max_seen);
-  if (flags) atomicOr(&g.status[t], flags);
-}
-
 // Heights 1 .. hb of the tree pass at fixed kernel-argument offsets (slot j = height j + 1).
 constexpr int kSubSlots = 13;
 struct SubLevels {
@@ -1138,14 +1199,16 @@ uint32_t lazy_top_height(const Geom& g, const Tuning& tn) {
 }
 
 template <int LOGK>
-static hipError_t launch_update_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
-                                  const float* prio, uint32_t stamp_base, hipStream_t s) {
+static hipError_t launch_update_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, bool claimed, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
+  const uint32_t B = c.B;
+  const uint32_t stamp_base = c.stamp_base;
   const uint32_t block = tn.update_block;
   hipError_t e;
-  PER_LAUNCH(KID_UPDATE_CLAIM, k_update_claim<LOGK>, dim3((B + block - 1) / block, g.T), dim3(block), 0, s, g, B, size,
-             idx, prio, stamp_base);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (!claimed) {   // (a fused call has already run the claim phase in its second kernel)
+    PER_LAUNCH(KID_UPDATE_CLAIM, k_update_claim, dim3((B + block - 1) / block, g.T), dim3(block), 0, s, g, c);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   const uint32_t hb = tree_pass_height(g);
   if (hb > (uint32_t)kSubSlots) return hipErrorInvalidValue;   // cannot happen for fanouts and capacities accepted at create
   SubLevels sl{};
@@ -1183,9 +1246,8 @@ static hipError_t launch_update_k(const Geom& g, const Tuning& tn, uint32_t B, u
   return hipGetLastError();
 }
 
-hipError_t launch_update(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
-                         const float* prio, uint32_t stamp_base, hipStream_t s) {
-#define CALL(L) launch_update_k<L>(g, tn, B, size, idx, prio, stamp_base, s)
+hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, bool claimed, hipStream_t s) {
+#define CALL(L) launch_update_k<L>(g, tn, c, claimed, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

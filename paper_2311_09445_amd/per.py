@@ -19,7 +19,8 @@ OK, EINVAL, ENOMEM, EEMPTY, ERANGE, EHIP = 0, -1, -2, -3, -4, -5
 FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 
 EXPORTS = [
-    "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_sample_gather", "per_gather",
+    "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_sample_gather",
+    "per_sample_gather_update", "per_gather",
     "per_update", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
@@ -65,6 +66,7 @@ def _lib():
         "per_insert": (C.c_int, [vp, u32, vp, vp, vp, vp]),
         "per_sample": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp]),
         "per_sample_gather": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, vp]),
+        "per_sample_gather_update": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, u32, vp, vp, vp]),
         "per_gather": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
@@ -193,11 +195,12 @@ class PrioritizedReplay:
         self._check(rc, "per_insert")
 
     def sample(self, u, beta: float = 0.4, want_weights: bool = True, want_prio: bool = True,
-               out_idx=None, out_weight=None, out_prio=None, rows_out=None):
+               out_idx=None, out_weight=None, out_prio=None, rows_out=None, update=None):
         """Returns (idx int32 [T,B] holding uint32 bit patterns, weights or None, prio or None).
 
         With ``rows_out`` (one [T,B,bytes] uint8 tensor or None per field) the sampled rows are
-        gathered in the same launch (per_sample_gather)."""
+        gathered by the same call (per_sample_gather).  With ``update=(idx, prio)`` that priority
+        update is applied after the sampling, still in the same call (per_sample_gather_update)."""
         torch = self._torch
         B = u.numel() // self.T
         if u.numel() != B * self.T:
@@ -212,10 +215,18 @@ class PrioritizedReplay:
         args = (self._h, B, float(beta), _dptr(u, torch.float32), _dptr(out_idx, torch.int32),
                 _dptr(out_weight, torch.float32) if want_weights else None,
                 _dptr(out_prio, torch.float32) if want_prio else None)
-        if rows_out is None:
+        dst = None
+        if rows_out is not None:
+            _keep, dst = self._ptr_array(rows_out, B)
+        if update is not None:
+            uidx, uprio = update
+            if uprio.numel() != uidx.numel():
+                raise ValueError("update idx and prio must have the same number of elements")
+            rc = self.lib.per_sample_gather_update(*args, dst, uidx.numel() // self.T, _dptr(uidx, torch.int32),
+                                                   _dptr(uprio, torch.float32), self._stream())
+        elif rows_out is None:
             rc = self.lib.per_sample(*args, self._stream())
         else:
-            _keep, dst = self._ptr_array(rows_out, B)
             rc = self.lib.per_sample_gather(*args, dst, self._stream())
         self._check(rc, "per_sample")
         return out_idx, (out_weight if want_weights else None), (out_prio if want_prio else None)

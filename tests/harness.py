@@ -103,6 +103,27 @@ class Mirror:
         for f in range(len(self.fb)):
             assert np.array_equal(got[f].reshape(want[f].shape), want[f]), f"gathered field {f}"
 
+    def sample_gather_update(self, u, beta, want_weights, upd_prio, dup=None, alias=False):
+        """per_sample_gather_update against oracle sample -> gather -> update.  The update targets the
+        sampled indices: either through the very output array (alias=True) or through a separate array
+        built from the oracle's indices with the duplicate map applied."""
+        B = u.shape[-1]
+        ci, cw, cv = self.cpu.sample(u, beta, want_weights)
+        upd_idx = ci if dup is None else wl.apply_dup_map(ci, dup)
+        rows = [torch.empty((self.T, B, b), dtype=torch.uint8, device="cuda") for b in self.fb]
+        out_idx = torch.empty((self.T, B), dtype=torch.int32, device="cuda")
+        upd_dev = out_idx if alias else idx_to_dev(upd_idx)
+        gi, gw, gv = self.gpu.sample(dev(u), beta, want_weights=want_weights, want_prio=True, out_idx=out_idx,
+                                     rows_out=rows if self.fb else None, update=(upd_dev, dev(upd_prio)))
+        assert np.array_equal(idx_to_host(gi), ci), "sampled indices (fused step)"
+        assert gv.cpu().numpy().tobytes() == cv.tobytes(), "sampled leaf values (fused step)"
+        if want_weights:
+            np.testing.assert_allclose(gw.cpu().numpy(), cw, rtol=WEIGHT_RTOL, atol=0)
+        if self.fb:
+            self.gather(gi, ci, got=rows)
+        self.cpu.update(np.ascontiguousarray(upd_idx, dtype=np.uint32), upd_prio)
+        return gi, ci
+
     def update(self, idx_host, prio):
         self.gpu.update(idx_to_dev(idx_host), dev(prio))
         self.cpu.update(np.ascontiguousarray(idx_host, dtype=np.uint32), prio)
@@ -129,10 +150,14 @@ class Mirror:
         inp = wl.step_inputs(w, step, seed, B)
         if w.n_insert:
             self.insert(w.n_insert)
-        fused = step % 2 == 1     # alternate between the separate calls and the fused one
-        gi, ci = self.sample(inp["u"], inp["beta"], w.weights, fused_rows=fused)
-        if not fused:
-            self.gather(gi, ci)
-        self.update(wl.apply_dup_map(ci, inp), inp["upd_prio"])
+        mode = step % 3           # rotate: separate calls, sample+gather fused, whole step fused
+        if mode == 2:
+            self.sample_gather_update(inp["u"], inp["beta"], w.weights, inp["upd_prio"], dup=inp,
+                                      alias=("dup_dst" not in inp and step % 2 == 0))
+        else:
+            gi, ci = self.sample(inp["u"], inp["beta"], w.weights, fused_rows=(mode == 1))
+            if mode == 0:
+                self.gather(gi, ci)
+            self.update(wl.apply_dup_map(ci, inp), inp["upd_prio"])
         if check_tree:
             self.compare_tree()

@@ -237,6 +237,8 @@ def test_update_sample_chain(K, N):
         if it == 1:
             m.compare_tree()
         m.update(idx, rng.random((1, B)).astype(np.float32))     # two updates in a row
+        m.sample_gather_update(wl.uniform01(rng, (1, 500)), 0.7, True, rng.random((1, 500)).astype(np.float32),
+                               alias=(it % 2 == 0))                # fused step right after an update
         m.insert(100)                                             # insert right after an update
         m.compare_tree()
     m.compare_status()
@@ -300,11 +302,15 @@ def test_workload_c4_full_size():
     m.compare_tree()
     for s in range(4):
         inp = wl.step_inputs(w, s, 0)
-        gi, ci = m.sample(inp["u"], inp["beta"], True, fused_rows=(s % 2 == 0))
-        leaves = m.cpu.read_level(0, 0)
-        assert np.all(leaves[ci[0]] > 0), "a zero-priority row was sampled"
-        m.gather(gi, ci)
-        m.update(wl.apply_dup_map(ci, inp), inp["upd_prio"])
+        if s % 2 == 0:     # the call sequence the bench times: whole step fused
+            leaves = m.cpu.read_level(0, 0)
+            gi, ci = m.sample_gather_update(inp["u"], inp["beta"], True, inp["upd_prio"], dup=inp)
+            assert np.all(leaves[ci[0]] > 0), "a zero-priority row was sampled"
+        else:
+            gi, ci = m.sample(inp["u"], inp["beta"], True, fused_rows=True)
+            assert np.all(m.cpu.read_level(0, 0)[ci[0]] > 0), "a zero-priority row was sampled"
+            m.gather(gi, ci)
+            m.update(wl.apply_dup_map(ci, inp), inp["upd_prio"])
         m.compare_tree(heights=range(1, m.gpu.H + 1))
         log(f"  step {s} ok")
     m.compare_tree()
