@@ -81,6 +81,11 @@ constexpr int kTraceMarks = 16, kTraceBlocks = 2048;
 __device__ unsigned long long g_trace[kTraceBlocks * kTraceMarks];
 #define PER_TRACE_DECL unsigned long long tm_[kTraceMarks] = {}
 #define PER_MARK(i) do { tm_[(i)] = wall_clock64(); } while (0)
+#define PER_MARK_HWID(i) /* XCC id and HW_ID (SE, CU, SIMD, wave slot) of the calling wave */    \
+  do {                                                                                         \
+    tm_[(i)] = ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |        \
+               (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);                            \
+  } while (0)
 #define PER_MARK_DYN(i)                                                                        \
   do {                                                                                         \
     const unsigned long long now_ = wall_clock64();                                            \
@@ -104,6 +109,7 @@ extern "C" int per_trace_read(unsigned long long* host, int clear) {
 #else
 #define PER_TRACE_DECL do { } while (0)
 #define PER_MARK(i) do { } while (0)
+#define PER_MARK_HWID(i) do { } while (0)
 #define PER_MARK_DYN(i) do { } while (0)
 #define PER_FLUSH() do { } while (0)
 #endif
@@ -995,7 +1001,10 @@ constexpr uint32_t kDirtyListCap = 2048;
 constexpr uint32_t kLazyTopNodes = 4096;
 
 template <int LOGK>
-__global__ void __launch_bounds__(1024)
+// Two 1024-lane workgroups share a compute unit only while a wave stays within an eighth of the
+// SIMD's scalar and vector registers; with one more scalar register than that the second workgroup
+// waits for the first to end and the kernel takes half as long again.
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8)))
 k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t chain) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
@@ -1015,6 +1024,7 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
 
   PER_TRACE_DECL;
   PER_MARK(0);
+  PER_MARK_HWID(15);
   // ---- 0. this subtree's height-1 nodes and their dirty flags
   const uint32_t sh1 = (hb - 1) * LOGK;
   const uint32_t n1 = sl.n[0];
