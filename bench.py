@@ -50,14 +50,14 @@ def parse():
     return ap.parse_args()
 
 
-def algorithmic_bytes(w, idx, upd_idx, K, H, h_mem, weights, fused):
-    """Bytes the method itself must move in one step, per kernel, each distinct K-group counted once
-    per phase (what a perfect cache would move).  idx / upd_idx: [T, B] uint32 of one step.
+def algorithmic_bytes(w, idx, upd_idx, K, H, h_mem, weights):
+    """Bytes the method itself must move in one step, per part of the step, each distinct K-group counted
+    once per phase (what a perfect cache would move).  idx / upd_idx: [T, B] uint32 of one step.
     h_mem: heights below it are read from memory by the descent (the ones above sit in LDS)."""
     logK = K.bit_length() - 1
     T, B = idx.shape
     E = w.row_bytes
-    out = {"k_sample": 0, "k_weights": 0, "k_rows_gather": 0, "k_update_claim": 0, "k_update_tree": 0}   # k_finish below
+    out = {"k_sample": 0, "k_weights": 0, "k_rows_gather": 0, "k_update_claim": 0, "k_update_tree": 0}
     for t in range(T):
         i64 = idx[t].astype(np.int64)
         groups = sum(len(np.unique(i64 >> ((h + 1) * logK))) * 4 * K for h in range(0, min(h_mem, H)))
@@ -70,8 +70,19 @@ def algorithmic_bytes(w, idx, upd_idx, K, H, h_mem, weights, fused):
         for h in range(1, H + 1):
             q = len(np.unique(u64 >> (h * logK)))
             out["k_update_tree"] += 4 * K * q + 4 * q                                     # child groups in, node out
-    out["k_finish"] = out["k_rows_gather"] + out["k_weights"] + (out["k_update_claim"] if fused == "step" else 0)
     return out
+
+
+def per_launched_kernel(parts, launched):
+    """Algorithmic bytes of the kernels that were launched, from the parts of the step each one carries."""
+    alg = dict(parts)
+    if "k_tree_finish" in launched:     # two-kernel step: claim in the sampling kernel, tree pass beside rows and weights
+        alg["k_sample"] = parts["k_sample"] + parts["k_update_claim"]
+        alg["k_tree_finish"] = parts["k_update_tree"] + parts["k_rows_gather"] + parts["k_weights"]
+    elif "k_finish" in launched:        # second kernel: rows and weights, plus the claim when no claim kernel ran
+        alg["k_finish"] = parts["k_rows_gather"] + parts["k_weights"] + \
+            (0 if "k_update_claim" in launched else parts["k_update_claim"])
+    return alg
 
 
 def measured_traffic(workload, kernel):
@@ -264,13 +275,13 @@ def main():
         slots += 1
         h_mem = l
     sel = list(range(warmup, total_steps, max(1, steps // 16)))
-    per_step = [algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, h_mem, w.weights,
-                                  "step" if fused_step else fused) for s in sel]
-    alg = {k: float(np.mean([p[k] for p in per_step])) for k in per_step[0]}
-    a_sample = alg["k_sample"]
-    a_gather = alg["k_rows_gather"] + alg["k_weights"]
-    a_update = alg["k_update_claim"] + alg["k_update_tree"]
+    per_step = [algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, h_mem, w.weights) for s in sel]
+    parts = {k: float(np.mean([p[k] for p in per_step])) for k in per_step[0]}
+    a_sample = parts["k_sample"]
+    a_gather = parts["k_rows_gather"] + parts["k_weights"]
+    a_update = parts["k_update_claim"] + parts["k_update_tree"]
     a_step = a_sample + a_gather + a_update
+    alg = per_launched_kernel(parts, set(kernels))
     kern_ms = {k: v[0] / max(1, v[1]) for k, v in kernels.items()}
     kern_per_step = {k: v[1] / steps for k, v in kernels.items()}
     step_kernels = [k for k in kernels if k in alg]

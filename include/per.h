@@ -114,11 +114,16 @@ int per_sample_gather(per_t* p, uint32_t B, float beta, const float* d_u, uint32
                       float* d_out_weight, float* d_out_prio, void* const* d_field_dst, void* stream);
 
 /* per_sample_gather followed by per_update(upd_B, d_upd_idx, d_upd_prio), as one call with the same
- * results: the update's claim phase, which does not touch what sampling reads, rides in the kernel
- * that gathers the rows, so the pair costs three launches instead of four.  This is the steady
- * state of a pipelined trainer: draw the next batch, then apply the priorities computed for an
- * earlier one.  d_upd_idx may alias d_out_idx (update the rows just drawn).  d_field_dst may be
- * NULL (no gather).  upd_B == 0 makes it per_sample_gather. */
+ * results (one iteration of Listing 2: draw a batch, read its rows, apply a priority update).  The
+ * update's first phase (last-writer claim) touches nothing that sampling reads, so it runs inside
+ * the sampling kernel, and the tree pass shares the second kernel with the row gather and the
+ * importance weights: two launches for the whole step.  That holds when the update batch is the
+ * sampled batch itself (d_upd_idx == d_out_idx and upd_B == B: update the rows just drawn, element i
+ * gets d_upd_prio[i]) or lies in memory apart from d_out_idx / d_out_weight / d_out_prio (the
+ * priorities computed for an earlier batch).  Any other overlap between the update batch and the
+ * sampling outputs is still correct (the update then reads them after sampling has written them)
+ * and costs a third launch.  d_field_dst may be NULL (no gather).  upd_B == 0 makes it
+ * per_sample_gather. */
 int per_sample_gather_update(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx,
                              float* d_out_weight, float* d_out_prio, void* const* d_field_dst,
                              uint32_t upd_B, const uint32_t* d_upd_idx, const float* d_upd_prio,
@@ -166,7 +171,10 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
  *   "stamp_next" : moves the last-writer stamp counter forward (never back); stamps are 32 bits and
  *                  the library clears the stamp array and starts over when they run out
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
- *                  the next call that reads them; 0 makes per_update finish them itself */
+ *                  the next call that reads them; 0 makes per_update finish them itself
+ *   "claim_in_sample" : 1 (default) lets per_sample_gather_update run the first phase of its update
+ *                  inside the sampling kernel (two kernels per step) whenever the update batch is the
+ *                  sampled batch itself or lies apart from the sampling outputs; 0: always three kernels */
 int per_set_tuning(per_t* p, const char* name, int64_t value);
 
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch of this buffer carries a

@@ -197,6 +197,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.gather_block = 256;
   p->tn.tree_block = 0;   // chosen per launch
   p->tn.lazy_top = 1;
+  p->tn.claim_in_sample = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->stamp_next = 1;
@@ -268,6 +269,13 @@ static int check_update_args(per_t* p, uint32_t B, const uint32_t* d_idx, const 
   return PER_OK;
 }
 
+// true when byte ranges [a, a+na) and [b, b+nb) share a byte (null ranges share nothing)
+static bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
+  if (!a || !b) return false;
+  const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+  return x < y + nb && y < x + na;
+}
+
 static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
                        float* d_out_prio, void* const* d_field_dst, uint32_t upd_B, const uint32_t* d_upd_idx,
                        const float* d_upd_prio, void* stream) {
@@ -283,6 +291,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
   FieldTable ft;
   const bool fused = d_field_dst && fill_fields(p, d_field_dst, &ft);
   ClaimArgs claim{};
+  int claim_mode = CLAIM_NONE;
   if (upd_B) {
     claim.B = upd_B;
     claim.size = (uint32_t)p->size;
@@ -290,15 +299,27 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
     claim.prio = d_upd_prio;
     int rc = reserve_stamps(p, upd_B, s, &claim.stamp_base);
     if (rc != PER_OK) return rc;
+    // The claim phase reads the update batch.  It may run inside the sampling kernel when that
+    // kernel does not write what it reads: the batch is either the sampled batch itself (same
+    // index array, element for element) or lies apart from every output of the sampling kernel.
+    const size_t n_out = (size_t)p->g.T * B * 4, n_upd = (size_t)p->g.T * upd_B * 4;
+    const void* outs[3] = {d_out_idx, d_out_weight, d_out_prio};
+    bool prio_apart = true, idx_apart = true;
+    for (const void* o : outs) {
+      prio_apart = prio_apart && !ranges_overlap(d_upd_prio, n_upd, o, n_out);
+      idx_apart = idx_apart && !ranges_overlap(d_upd_idx, n_upd, o, n_out);
+    }
+    claim_mode = CLAIM_FINISH;
+    if (p->tn.claim_in_sample && prio_apart) {
+      if (d_upd_idx == d_out_idx && upd_B == B) claim_mode = CLAIM_INLINE;
+      else if (idx_apart) claim_mode = CLAIM_BLOCKS;
+    }
   }
   const uint32_t stale = p->stale_hb;
   p->stale_hb = 0;   // the sampling kernel rebuilds and stores the stale heights
   hipError_t e = launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, d_out_idx, d_out_weight, d_out_prio,
-                               &p->weight_calls, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr, s);
-  if (e == hipSuccess && upd_B) {
-    e = launch_update(p->g, p->tn, claim, true, s);
-    if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
-  }
+                               &p->weight_calls, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr, claim_mode, s);
+  if (e == hipSuccess && upd_B) p->stale_hb = lazy_top_height(p->g, p->tn);   // the tree pass ran
   return hip_rc(e);
 }
 
@@ -344,7 +365,7 @@ int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio,
   claim.prio = d_prio;
   rc = reserve_stamps(p, B, s, &claim.stamp_base);
   if (rc != PER_OK) return rc;
-  hipError_t e = launch_update(p->g, p->tn, claim, false, s);
+  hipError_t e = launch_update(p->g, p->tn, claim, s);
   if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
   return hip_rc(e);
 }
@@ -432,6 +453,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "lazy_top")) {
     if (value != 0 && value != 1) return PER_EINVAL;
     p->tn.lazy_top = (uint32_t)value;
+    return PER_OK;
+  }
+  if (!strcmp(name, "claim_in_sample")) {
+    if (value != 0 && value != 1) return PER_EINVAL;
+    p->tn.claim_in_sample = (uint32_t)value;
     return PER_OK;
   }
   uint32_t* blk = !strcmp(name, "sample_block") ? &p->tn.sample_block

@@ -53,6 +53,14 @@ struct ClaimArgs {
   const float* prio;       // [T][B]
 };
 
+// Where the claim phase of an update fused into a sampling call runs.
+enum ClaimMode {
+  CLAIM_NONE = 0,
+  CLAIM_INLINE = 1,   // by the sampling lanes: the update batch is the sampled batch (same index array)
+  CLAIM_BLOCKS = 2,   // by extra workgroups of the sampling kernel: the update batch lies in other memory
+  CLAIM_FINISH = 3    // in the second kernel, after sampling: the update batch overlaps the sampling outputs
+};
+
 // Jobs of the second kernel of the fused calls (see k_finish).
 struct FinishArgs {
   uint32_t B;              // sampled batch
@@ -76,7 +84,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 // Optional per-kernel timing with HIP events attached to each launch (off by default).
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
-  KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_GET_PRIORITY, KID_COUNT
+  KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_GET_PRIORITY, KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -96,6 +104,7 @@ struct Tuning {
   uint32_t sample_block, update_block, gather_block, tree_block;
   uint32_t sample_min_lds;   // lower bound of the sampling kernel's LDS request, bytes
   uint32_t lazy_top;   // updates may leave the few topmost heights to their next reader
+  uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   Profiler* prof;
 };
 
@@ -104,7 +113,7 @@ hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
-                         const FieldTable* rows, const ClaimArgs* claim, hipStream_t s);
+                         const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s);
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s);
 hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t n, uint32_t cursor,
@@ -114,7 +123,7 @@ hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uin
 hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipStream_t s);
 hipError_t launch_resum_top(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
 uint32_t lazy_top_height(const Geom& g, const Tuning& tn);
-hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, bool claimed, hipStream_t s);
+hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s);
 hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
 hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s);
 hipError_t launch_clear_status(const Geom& g, hipStream_t s);

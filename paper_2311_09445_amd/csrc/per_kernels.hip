@@ -22,7 +22,7 @@ namespace per {
 const char* kernel_name(int kid) {
   static const char* const names[KID_COUNT] = {
       "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_finish", "k_rows_scatter", "k_insert_leaves",
-      "k_resum_dense", "k_resum_tail", "k_update_claim", "k_update_tree", "k_get_priority"};
+      "k_resum_dense", "k_resum_tail", "k_update_claim", "k_update_tree", "k_tree_finish", "k_get_priority"};
   return kid >= 0 && kid < KID_COUNT ? names[kid] : "?";
 }
 
@@ -305,6 +305,44 @@ hipError_t launch_clear_status(const Geom& g, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------
+// priority update, first half: claim
+// ---------------------------------------------------------------------------------
+// Element j raises the 64-bit stamp of its leaf to (stamp_base + j) << 32 | value bits by
+// atomic max, and sets the leaf's bit in the dirty mask (one bit per leaf).  The largest j wins
+// and carries its value with it.  Stamps grow from call to call, so stale stamps never win
+// and the stamp array needs no clearing between calls.
+__device__ __forceinline__ void claim_element(const Geom& g, uint32_t t, uint32_t size, uint32_t stamp_base, uint32_t j,
+                                              uint32_t i, float v, uint32_t& mx, uint32_t& flags) {
+  if (!(i < size)) flags |= 1u;
+  else if (!valid_priority(v)) flags |= 2u;
+  else {
+    const unsigned long long stamp = ((unsigned long long)(stamp_base + j) << 32) | __float_as_uint(v);
+    atomicMax(reinterpret_cast<unsigned long long*>(g.owner) + (size_t)t * g.owner_stride + i, stamp);
+    atomicOr(&g.dirty[(size_t)t * g.dirty_stride + (i >> 5)], 1u << (i & 31u));
+    const uint32_t vb = v > 0.0f ? __float_as_uint(v) : 0u;
+    mx = vb > mx ? vb : mx;
+  }
+}
+
+// Claims elements of the batch, strided over the job's workgroups.  Called by whole workgroups.
+__device__ __forceinline__ void claim_job(const Geom& g, uint32_t t, const ClaimArgs& c, uint32_t job_block,
+                                          uint32_t job_blocks) {
+  if (job_block * blockDim.x >= c.B) return;   // nothing to do for this workgroup
+  const uint32_t max_seen = read_max_bits(g, t);
+  uint32_t mx = 0;
+  uint32_t flags = 0;
+  for (uint32_t base = job_block * blockDim.x; base < c.B; base += job_blocks * blockDim.x) {
+    const uint32_t j = base + threadIdx.x;
+    if (j < c.B)
+      claim_element(g, t, c.size, c.stamp_base, j, c.idx[(size_t)t * c.B + j], c.prio[(size_t)t * c.B + j], mx, flags);
+  }
+  raise_max(g, t, mx, max_seen);
+  if (flags) atomicOr(&g.status[t], flags);
+}
+
+__global__ void k_update_claim(Geom g, ClaimArgs c) { claim_job(g, blockIdx.y, c, blockIdx.x, gridDim.x); }
+
+// ---------------------------------------------------------------------------------
 // priority sampling
 // ---------------------------------------------------------------------------------
 // The topmost heights below the root are copied to LDS (at most kTopSlots of them, highest
@@ -327,17 +365,40 @@ struct TopCopy {
 // group), parks them in LDS rows of K+4 floats (the pad keeps 16-byte row reads conflict-free),
 // and every lane then walks its own row.
 //
+// Chunk (IT*64 + lane) of the wave's 64*C 16-byte chunks, for IT = 0 .. C-1: fetched from the
+// group of the lane that owns it and parked in that lane's staging row.  Written as a recursion over
+// IT (not a loop over an array of registers) so that every fetch is issued before the first LDS store
+// without the compiler having to promote an array.
+template <int LOGK, int IT>
+__device__ __forceinline__ void stage_groups(const float* __restrict__ lvl, uint32_t node, unsigned lane, float* stage) {
+  constexpr int K = Fan<LOGK>::K;
+  constexpr int C = K / 4;
+  constexpr int ROW = K + 4;
+  if constexpr (IT < C) {
+    const unsigned gch = (unsigned)IT * 64u + lane;
+    const uint32_t nd = (uint32_t)__shfl((int)node, (int)(gch / C));
+    const float4 x = *reinterpret_cast<const float4*>(lvl + (size_t)nd * K + (gch % C) * 4u);
+    stage_groups<LOGK, IT + 1>(lvl, node, lane, stage);
+    *reinterpret_cast<float4*>(stage + (gch / C) * ROW + (gch % C) * 4u) = x;
+  }
+}
+
 // stale < 0: the tree in memory is whole.  stale >= 0: the last update left the root and the
 // `stale` topmost copied heights to this kernel; they are rebuilt here from the highest fresh
 // height (which is in the copy), and the first workgroup of each tree stores them back.
+//
+// The claim phase of a priority update fused into the call can ride along (it touches stamps, dirty
+// bits and the running maximum only, none of which sampling reads).  claim_mode 1: the update targets
+// exactly the indices sampled here, element by element, so every lane claims its own sample when it has
+// it.  claim_mode 2: the update batch lies in other memory; the first claim_blocks workgroups of the
+// grid are claim workgroups.  claim_mode 0: no claim here.
 template <int LOGK>
 __global__ void __launch_bounds__(1024)
 k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float* __restrict__ u,
          uint32_t* __restrict__ out_idx, float* __restrict__ out_prio, float* __restrict__ out_w,
-         uint32_t parity, int stale) {
+         uint32_t parity, int stale, uint32_t claim_blocks, ClaimArgs c, int claim_mode) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
-  constexpr int C = K >= 4 ? K / 4 : 1;       // 16-byte chunks per group
   constexpr int ROW = K + 4;                  // staging row, floats
   using Vec = typename std::conditional<LOGK == 1, float2, float4>::type;
   constexpr int VF = sizeof(Vec) / 4;
@@ -349,16 +410,29 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   const unsigned lane = threadIdx.x & 63u;
   const unsigned wave = threadIdx.x >> 6;
   const int nslots = (int)tc.nslots;
+  if (blockIdx.x < claim_blocks) {   // claim workgroups come first: their atomics are under way before the descent loads start
+    claim_job(g, t, c, blockIdx.x, claim_blocks);
+    return;
+  }
+  const uint32_t bx = blockIdx.x - claim_blocks;            // sampling workgroup number
+  const uint32_t sample_blocks = gridDim.x - claim_blocks;
 
   PER_TRACE_DECL;
   PER_MARK(0);
-  const uint32_t s_raw = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t s_raw = bx * blockDim.x + threadIdx.x;
   const bool active = s_raw < B;
   const uint32_t s = active ? s_raw : B - 1;
   const size_t o = (size_t)t * B + s;
   // the root, this lane's uniform and the top copy are all fetched in the same trip
   float total = tc.root[(size_t)t * tc.root_stride];
   const float u_s = u[o];
+  // the new priority of this lane's sample and the running maximum, fetched in that same trip
+  float upd_v = 0.0f;
+  uint32_t max_seen = 0;
+  if (claim_mode == 1) {
+    upd_v = c.prio[o];
+    max_seen = read_max_bits(g, t);
+  }
 
   uint32_t off[kTopSlots + 1];
   off[0] = 0;
@@ -368,7 +442,10 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
 
   if (nslots > 0) {
     // one flat loop over the vectors of all copied heights (stale ones are skipped)
-    const uint32_t v_lo = stale > 0 ? off[stale < kTopSlots ? stale : kTopSlots] / VF : 0u;
+    uint32_t v_lo = 0;   // off[min(stale, kTopSlots)] / VF, without indexing the array by a run-time value
+#pragma unroll
+    for (int i = 1; i <= kTopSlots; ++i)
+      if (stale >= i) v_lo = off[i] / VF;
     for (uint32_t e = v_lo + threadIdx.x; e < top_floats / VF; e += blockDim.x) {
       const uint32_t f = e * VF;
       const float* src = tc.ptr[0] + (size_t)t * tc.stride[0];
@@ -414,7 +491,8 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
       if (out_prio) out_prio[o] = 0.0f;
       if (out_w) out_w[o] = 0.0f;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&g.status[t], 4u);
+    // (a fused update of these samples finds no valid index: every element is out of range)
+    if (bx == 0 && threadIdx.x == 0) atomicOr(&g.status[t], claim_mode == 1 ? 5u : 4u);
     return;
   }
 
@@ -446,18 +524,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
     if constexpr (LOGK <= 2) {
       descend_lane<LOGK>(lvl + (size_t)node * K, r, child, val);
     } else {
-      float4 x[C];
-#pragma unroll
-      for (int it = 0; it < C; ++it) {       // chunk (it*64 + lane) of the wave's 64*C chunks
-        const unsigned gch = (unsigned)it * 64u + lane;
-        const uint32_t nd = (uint32_t)__shfl((int)node, (int)(gch / C));
-        x[it] = *reinterpret_cast<const float4*>(lvl + (size_t)nd * K + (gch % C) * 4u);
-      }
-#pragma unroll
-      for (int it = 0; it < C; ++it) {
-        const unsigned gch = (unsigned)it * 64u + lane;
-        *reinterpret_cast<float4*>(stage + (gch / C) * ROW + (gch % C) * 4u) = x[it];
-      }
+      stage_groups<LOGK, 0>(lvl, node, lane, stage);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -474,7 +541,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   }
   // Stores come last on purpose: on this hardware a wait for loaded data also waits for every
   // earlier store of the wave.  The first workgroup of each tree puts the rebuilt heights back.
-  if (stale >= 0 && blockIdx.x == 0) {
+  if (stale >= 0 && bx == 0) {
 #pragma unroll
     for (int i = 0; i < kTopSlots; ++i)
       if (i < stale) {
@@ -485,19 +552,26 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   }
   PER_MARK(12);
   PER_FLUSH();
-  if (!out_w) return;
-  // Importance weights need the batch minimum of the sampled values.
-  const uint32_t m = wave_min_u32(active ? __float_as_uint(val) : 0x7F800000u);
-  if (gridDim.x == 1) {   // the whole batch of this tree is in this block: finish here
-    if (lane == 0) s_min[wave] = m;
-    __syncthreads();
-    uint32_t mm = 0x7F800000u;
-    for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_min[wv] < mm ? s_min[wv] : mm;
-    if (active) out_w[o] = importance_weight(val, __uint_as_float(mm), total, size, beta);
-  } else {                // partial minima, spread over kVminSlots addresses; k_weights finishes
-    if (active) out_w[o] = val;
-    if (lane == 0)
-      atomicMin(&g.vmin[((size_t)parity * g.T + t) * kVminSlots + ((blockIdx.x * (blockDim.x >> 6) + wave) % kVminSlots)], m);
+  if (out_w) {
+    // Importance weights need the batch minimum of the sampled values.
+    const uint32_t m = wave_min_u32(active ? __float_as_uint(val) : 0x7F800000u);
+    if (sample_blocks == 1) {   // the whole batch of this tree is in this block: finish here
+      if (lane == 0) s_min[wave] = m;
+      __syncthreads();
+      uint32_t mm = 0x7F800000u;
+      for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_min[wv] < mm ? s_min[wv] : mm;
+      if (active) out_w[o] = importance_weight(val, __uint_as_float(mm), total, size, beta);
+    } else {                // partial minima, spread over kVminSlots addresses; the weights job finishes
+      if (active) out_w[o] = val;
+      if (lane == 0)
+        atomicMin(&g.vmin[((size_t)parity * g.T + t) * kVminSlots + ((bx * (blockDim.x >> 6) + wave) % kVminSlots)], m);
+    }
+  }
+  if (claim_mode == 1) {   // element s of the update batch is this lane's own sample
+    uint32_t mx = 0, flags = 0;
+    if (active) claim_element(g, t, size, c.stamp_base, s, node, upd_v, mx, flags);
+    raise_max(g, t, mx, max_seen);
+    if (flags) atomicOr(&g.status[t], flags);
   }
 }
 
@@ -535,12 +609,21 @@ template <int LOGK>
 static hipError_t launch_resum_top_k(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
 static hipError_t launch_finish(const Geom& g, const Tuning& tn, const FieldTable* rows, const FinishArgs& a,
                                 hipStream_t s);
+template <int LOGK>
+static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, uint32_t B, hipStream_t s);
+template <int LOGK>
+static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, uint32_t B, const FieldTable* rows,
+                                       const FinishArgs& a, hipStream_t s);
 
+// Sampling call with whatever is fused into it.  rows: gather of the sampled rows.  claim: a priority
+// update whose claim phase runs where claim_mode says (CLAIM_INLINE / CLAIM_BLOCKS: in the sampling
+// kernel, the tree pass then shares the second kernel with the weights and row jobs; CLAIM_FINISH: in
+// the second kernel, the tree pass is a third).
 template <int LOGK>
 static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
                                   const float* u, uint32_t* out_idx, float* out_w, float* out_prio,
                                   uint32_t* weight_calls, uint32_t stale_hb, const FieldTable* rows,
-                                  const ClaimArgs* claim, hipStream_t s) {
+                                  const ClaimArgs* claim, int claim_mode, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
   constexpr uint32_t kLdsCap = 128 * 1024;
   const uint32_t wave_bytes = LOGK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
@@ -597,12 +680,20 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
   }
-  PER_LAUNCH(KID_SAMPLE, k_sample<LOGK>, dim3(gx, g.T), dim3(block), bytes, s, g, tc, B, size, beta, u, out_idx,
-             out_prio, out_w, parity, stale);
+  if (!claim) claim_mode = CLAIM_NONE;
+  const bool claim_here = claim_mode == CLAIM_INLINE || claim_mode == CLAIM_BLOCKS;
+  uint32_t claim_blocks = 0;
+  if (claim_mode == CLAIM_BLOCKS) {
+    claim_blocks = (claim->B + block - 1) / block;
+    if (claim_blocks > 4096) claim_blocks = 4096;   // the claim job strides
+  }
+  PER_LAUNCH(KID_SAMPLE, k_sample<LOGK>, dim3(gx + claim_blocks, g.T), dim3(block), bytes, s, g, tc, B, size, beta, u,
+             out_idx, out_prio, out_w, parity, stale, claim_blocks, claim_here ? *claim : ClaimArgs{},
+             claim_here ? claim_mode : (int)CLAIM_NONE);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const bool finish_weights = out_w && gx > 1;
-  if (rows || claim) {   // fused call: one more kernel gathers the rows, finishes the weights and claims the update
+  if (rows || claim) {   // fused call
     FinishArgs a{};
     a.B = B;
     a.idx = out_idx;
@@ -610,9 +701,16 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
     a.size = size;
     a.beta = beta;
     a.parity = parity;
+    if (claim_here) {   // second kernel: tree pass beside the weights and the rows
+      if (rows || finish_weights) return launch_tree_finish_k<LOGK>(g, tn, claim->B, rows, a, s);
+      return launch_tree_k<LOGK>(g, tn, claim->B, s);
+    }
+    // second kernel: rows, weights and the claim phase; the tree pass follows
     a.has_claim = claim ? 1u : 0u;
     if (claim) a.claim = *claim;
-    return launch_finish(g, tn, rows, a, s);
+    e = launch_finish(g, tn, rows, a, s);
+    if (e != hipSuccess || !claim) return e;
+    return launch_tree_k<LOGK>(g, tn, claim->B, s);
   }
   if (!finish_weights) return e;
   PER_LAUNCH(KID_WEIGHTS, k_weights, dim3((B + 255) / 256, g.T), dim3(256), 0, s, g, B, size, beta, out_w, parity);
@@ -632,46 +730,11 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
 
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
-                         const FieldTable* rows, const ClaimArgs* claim, hipStream_t s) {
-#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, weight_calls, stale_hb, rows, claim, s)
+                         const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s) {
+#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, weight_calls, stale_hb, rows, claim, claim_mode, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }
-
-// ---------------------------------------------------------------------------------
-// priority update, first half: claim
-// ---------------------------------------------------------------------------------
-// Element j raises the 64-bit stamp of its leaf to (stamp_base + j) << 32 | value bits by
-// atomic max, and sets the leaf's bit in the dirty mask (one bit per leaf).  The largest j wins
-// and carries its value with it.  Stamps grow from call to call, so stale stamps never win
-// and the stamp array needs no clearing between calls.  Called by whole workgroups.
-__device__ __forceinline__ void claim_job(const Geom& g, uint32_t t, const ClaimArgs& c, uint32_t job_block,
-                                          uint32_t job_blocks) {
-  if (job_block * blockDim.x >= c.B) return;   // nothing to do for this workgroup
-  const uint32_t max_seen = read_max_bits(g, t);
-  uint32_t mx = 0;
-  uint32_t flags = 0;
-  for (uint32_t base = job_block * blockDim.x; base < c.B; base += job_blocks * blockDim.x) {
-    const uint32_t j = base + threadIdx.x;
-    if (j < c.B) {
-      const uint32_t i = c.idx[(size_t)t * c.B + j];
-      const float v = c.prio[(size_t)t * c.B + j];
-      if (!(i < c.size)) flags |= 1u;
-      else if (!valid_priority(v)) flags |= 2u;
-      else {
-        const unsigned long long stamp = ((unsigned long long)(c.stamp_base + j) << 32) | __float_as_uint(v);
-        atomicMax(reinterpret_cast<unsigned long long*>(g.owner) + (size_t)t * g.owner_stride + i, stamp);
-        atomicOr(&g.dirty[(size_t)t * g.dirty_stride + (i >> 5)], 1u << (i & 31u));
-        const uint32_t vb = v > 0.0f ? __float_as_uint(v) : 0u;
-        mx = vb > mx ? vb : mx;
-      }
-    }
-  }
-  raise_max(g, t, mx, max_seen);
-  if (flags) atomicOr(&g.status[t], flags);
-}
-
-__global__ void k_update_claim(Geom g, ClaimArgs c) { claim_job(g, blockIdx.y, c, blockIdx.x, gridDim.x); }
 
 // ---------------------------------------------------------------------------------
 // Data Storage: row gather and row scatter
@@ -1000,12 +1063,9 @@ struct SubLevels {
 constexpr uint32_t kDirtyListCap = 2048;
 constexpr uint32_t kLazyTopNodes = 4096;
 
+// The work of workgroup b of tree t (b = its subtree's root at height hb).
 template <int LOGK>
-// Two 1024-lane workgroups share a compute unit only while a wave stays within an eighth of the
-// SIMD's scalar and vector registers; with one more scalar register than that the second workgroup
-// waits for the first to end and the kernel takes half as long again.
-__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8)))
-k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t chain) {
+__device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uint32_t t, uint32_t b, uint32_t chain) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   extern __shared__ __attribute__((aligned(16))) float sub[];   // 16-byte LDS accesses need the alignment
@@ -1014,8 +1074,6 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   __shared__ uint32_t s_bits_hi[LOGK == 6 ? kDirtyListCap : 1];
   __shared__ uint32_t s_wave[16];
   __shared__ uint32_t s_last;
-  const uint32_t t = blockIdx.y;
-  const uint32_t b = blockIdx.x;
   const uint32_t hb = sl.hb;
   const unsigned lane = threadIdx.x & 63u;
   const unsigned q = threadIdx.x % LPS;
@@ -1192,6 +1250,41 @@ k_update_tree(Geom g, SubLevels sl, uint32_t B, uint32_t stamp_base, uint32_t ch
   }
 }
 
+// Two 1024-lane workgroups share a compute unit only while a wave stays within an eighth of the
+// SIMD's scalar and vector registers; with one more scalar register than that the second workgroup
+// waits for the first to end and the kernel takes half as long again.
+template <int LOGK>
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8)))
+k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
+  tree_job<LOGK>(g, sl, blockIdx.y, blockIdx.x, chain);
+}
+
+// Second kernel of a fused step whose claim phase rode in the sampling kernel: the tree pass
+// (workgroups 0 .. tree_blocks-1) and, beside it, what is left of the sampling call: the
+// importance weights and the rows of the sampled indices (JobRanges, offset by tree_blocks).  The
+// tree pass is a chain of dependent memory trips and the row traffic fills the gaps; launched with
+// workgroups of at most 512 lanes so that the two kinds share the compute units.
+template <int LOGK>
+__global__ void __launch_bounds__(512)
+k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldTable ft, JobRanges jr, FinishArgs a) {
+  const uint32_t t = blockIdx.y;
+  if (blockIdx.x < tree_blocks) {
+    tree_job<LOGK>(g, sl, t, blockIdx.x, chain);
+    return;
+  }
+  const uint32_t b = blockIdx.x - tree_blocks;
+  if (b < jr.first[1]) {
+    weights_job(g, t, a.B, a.size, a.beta, a.w, a.parity, b, jr.first[1]);
+    return;
+  }
+#pragma unroll
+  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
+    if (b >= jr.first[2 + f] && b < jr.first[3 + f]) {
+      rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+      return;
+    }
+}
+
 // Height of the workgroup roots of the tree pass: the whole tree for small trees, else the
 // lowest height whose subtrees hold at least 64 height-1 nodes (so that dirty words are never
 // shared between workgroups).
@@ -1208,17 +1301,10 @@ uint32_t lazy_top_height(const Geom& g, const Tuning& tn) {
   return tn.lazy_top && hb < g.H && g.n[hb] <= kLazyTopNodes ? hb : 0u;
 }
 
+// Sub-level descriptors, workgroup size and LDS floats of the tree pass for update batches of B.
 template <int LOGK>
-static hipError_t launch_update_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, bool claimed, hipStream_t s) {
+static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, uint32_t B, SubLevels* out, uint32_t* tblock_out) {
   constexpr int K = Fan<LOGK>::K;
-  const uint32_t B = c.B;
-  const uint32_t stamp_base = c.stamp_base;
-  const uint32_t block = tn.update_block;
-  hipError_t e;
-  if (!claimed) {   // (a fused call has already run the claim phase in its second kernel)
-    PER_LAUNCH(KID_UPDATE_CLAIM, k_update_claim, dim3((B + block - 1) / block, g.T), dim3(block), 0, s, g, c);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-  }
   const uint32_t hb = tree_pass_height(g);
   if (hb > (uint32_t)kSubSlots) return hipErrorInvalidValue;   // cannot happen for fanouts and capacities accepted at create
   SubLevels sl{};
@@ -1251,13 +1337,51 @@ static hipError_t launch_update_k(const Geom& g, const Tuning& tn, const ClaimAr
     tblock = (uint32_t)(want > 1024 ? 1024 : (want + 63) / 64 * 64);
     if (tblock < 64) tblock = 64;
   }
-  PER_LAUNCH(KID_UPDATE_TREE, k_update_tree<LOGK>, dim3(g.n[hb], g.T), dim3(tblock), (size_t)off * 4, s, g, sl, B,
-             stamp_base, lazy_top_height(g, tn) ? 0u : 1u);
+  *out = sl;
+  *tblock_out = tblock;
+  return hipSuccess;
+}
+
+template <int LOGK>
+static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, uint32_t B, hipStream_t s) {
+  SubLevels sl;
+  uint32_t tblock;
+  hipError_t e = tree_pass_shape<LOGK>(g, tn, B, &sl, &tblock);
+  if (e != hipSuccess) return e;
+  PER_LAUNCH(KID_UPDATE_TREE, k_update_tree<LOGK>, dim3(g.n[sl.hb], g.T), dim3(tblock), (size_t)sl.lds_floats * 4, s, g,
+             sl, lazy_top_height(g, tn) ? 0u : 1u);
   return hipGetLastError();
 }
 
-hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, bool claimed, hipStream_t s) {
-#define CALL(L) launch_update_k<L>(g, tn, c, claimed, s)
+// The tree pass of an update batch of B together with the weights and row jobs in `a` / `rows`.
+template <int LOGK>
+static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, uint32_t B, const FieldTable* rows,
+                                       const FinishArgs& a, hipStream_t s) {
+  SubLevels sl;
+  uint32_t tblock;
+  hipError_t e = tree_pass_shape<LOGK>(g, tn, B, &sl, &tblock);
+  if (e != hipSuccess) return e;
+  if (tblock > 512) tblock = 512;   // half the lanes of a compute unit are left to the other jobs
+  FieldTable ft{};
+  if (rows) ft = *rows;
+  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u);
+  const uint32_t tree_blocks = g.n[sl.hb];
+  PER_LAUNCH(KID_TREE_FINISH, k_tree_finish<LOGK>, dim3(tree_blocks + jr.first[2 + kMaxFields], g.T), dim3(tblock),
+             (size_t)sl.lds_floats * 4, s, g, sl, lazy_top_height(g, tn) ? 0u : 1u, tree_blocks, ft, jr, a);
+  return hipGetLastError();
+}
+
+template <int LOGK>
+static hipError_t launch_update_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s) {
+  const uint32_t block = tn.update_block;
+  PER_LAUNCH(KID_UPDATE_CLAIM, k_update_claim, dim3((c.B + block - 1) / block, g.T), dim3(block), 0, s, g, c);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_tree_k<LOGK>(g, tn, c.B, s);
+}
+
+hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s) {
+#define CALL(L) launch_update_k<L>(g, tn, c, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

@@ -103,16 +103,23 @@ class Mirror:
         for f in range(len(self.fb)):
             assert np.array_equal(got[f].reshape(want[f].shape), want[f]), f"gathered field {f}"
 
-    def sample_gather_update(self, u, beta, want_weights, upd_prio, dup=None, alias=False):
+    def sample_gather_update(self, u, beta, want_weights, upd_prio, dup=None, alias=False, tail=0):
         """per_sample_gather_update against oracle sample -> gather -> update.  The update targets the
-        sampled indices: either through the very output array (alias=True) or through a separate array
-        built from the oracle's indices with the duplicate map applied."""
+        sampled indices: through the very output array (alias=True), through its last `tail` elements
+        only (a batch that overlaps the sampling output without being it; one tree only), or through
+        a separate array built from the oracle's indices with the duplicate map applied."""
         B = u.shape[-1]
         ci, cw, cv = self.cpu.sample(u, beta, want_weights)
         upd_idx = ci if dup is None else wl.apply_dup_map(ci, dup)
         rows = [torch.empty((self.T, B, b), dtype=torch.uint8, device="cuda") for b in self.fb]
         out_idx = torch.empty((self.T, B), dtype=torch.int32, device="cuda")
-        upd_dev = out_idx if alias else idx_to_dev(upd_idx)
+        if tail:
+            assert self.T == 1 and dup is None and 0 < tail < B
+            upd_idx = ci[:, B - tail:]
+            upd_prio = np.ascontiguousarray(upd_prio[:, :tail])
+            upd_dev = out_idx.view(-1)[B - tail:]
+        else:
+            upd_dev = out_idx if alias else idx_to_dev(upd_idx)
         gi, gw, gv = self.gpu.sample(dev(u), beta, want_weights=want_weights, want_prio=True, out_idx=out_idx,
                                      rows_out=rows if self.fb else None, update=(upd_dev, dev(upd_prio)))
         assert np.array_equal(idx_to_host(gi), ci), "sampled indices (fused step)"

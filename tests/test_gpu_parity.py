@@ -244,6 +244,38 @@ def test_update_sample_chain(K, N):
     m.compare_status()
 
 
+@pytest.mark.parametrize("K,N,B,fb", [(32, 1 << 17, 3000, (128,)), (16, 50000, 700, (68, 24, 4, 68, 1)), (2, 5000, 64, ())])
+def test_fused_step_wherever_the_update_batch_lies(K, N, B, fb):
+    """per_sample_gather_update places the claim phase of its update by where the update batch lies: the
+    sampled batch itself, memory apart from the sampling outputs (also with another batch size), or a
+    part of the output index array.  All three, and the three-kernel form forced by the tuning knob,
+    against the oracle."""
+    log(f"fused step placements K={K} N={N} B={B}")
+    rng = np.random.default_rng(K * N + B)
+    m = Mirror(K, N, 1, fb)
+    m.insert(N, prio=wl._draw_priorities("pareto_1.5", rng, (1, N)))
+    for knob in (1, 0):
+        m.gpu.set_tuning("claim_in_sample", knob)
+        for want_w in (True, False):
+            pr = lambda n: rng.random((1, n)).astype(np.float32)
+            m.sample_gather_update(wl.uniform01(rng, (1, B)), 0.5, want_w, pr(B), alias=True)
+            m.compare_tree()
+            m.sample_gather_update(wl.uniform01(rng, (1, B)), 0.5, want_w, pr(B), alias=False)
+            m.compare_tree()
+            m.sample_gather_update(wl.uniform01(rng, (1, B)), 0.5, want_w, pr(B), tail=B // 3)
+            m.compare_tree()
+            # an update batch of another size than the sampled one, in memory of its own
+            idx = rng.integers(0, N, (1, 2 * B + 5)).astype(np.uint32)
+            ci, cw, cv = m.cpu.sample(u := wl.uniform01(rng, (1, B)), 0.5, want_w)
+            up = pr(2 * B + 5)
+            gi, gw, gv = m.gpu.sample(dev(u), 0.5, want_weights=want_w, want_prio=True,
+                                      update=(idx_to_dev(idx), dev(up)))
+            assert np.array_equal(idx_to_host(gi), ci)
+            m.cpu.update(idx, up)
+            m.compare_tree()
+    m.compare_status()
+
+
 def test_sampling_frequency_on_gpu():
     rng = np.random.default_rng(12345)
     N, B, steps = 256, 64, 2000
