@@ -294,6 +294,21 @@ def main():
         "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(kern_ms[dominant] * 1e3, 2),
     }
     step_gbs = a_step / (ms_per_step * 1e-3) / 1e9
+    # what a plain streaming device copy reaches on this GPU in this run (read + written bytes per second)
+    src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * src.numel() / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+    roofline["measured_copy_GBps"] = round(copy_gbs, 1)
+    roofline["frac_of_measured_copy"] = round(dom_gbs / copy_gbs, 4)
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
@@ -323,9 +338,18 @@ def main():
             if restore_ok or done == 0:
                 assert np.array_equal(ci, rec_idx[done]), f"oracle and GPU disagree on step {done}"
             done += 1
+        model = "unknown CPU"
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
+        affinity = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
         cpu = {"value": round(T * B * done / t_cpu, 1), "unit": "transitions/s", "cores": 1, "kind": "oracle",
                "sample": f"first {done} steps of the same workload and inputs, {t_cpu:.1f} s of CPU time, "
-                         f"{os.cpu_count()} host cores visible, single thread used"}
+                         f"single thread; host: {model}, {os.cpu_count()} cores visible, {affinity} in the affinity mask"}
 
     out = {
         "metric": "sampled+updated transitions/s per step; % of HBM peak at N=2^24, B=65536",

@@ -1142,50 +1142,79 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   PER_MARK(1);
 
   if (nd > 0) {
-    // ---- 1. rebuild the dirty height-1 nodes (list order is irrelevant: nodes are independent)
-    for (uint32_t base = 0; base < nd; base += ngrp) {
-      const uint32_t item = base + grp;
-      const bool ok = item < nd;
-      const uint32_t li = ok ? item : nd - 1;
-      const uint32_t node = s_list[li];
+    // ---- 1. rebuild the dirty height-1 nodes (list order is irrelevant: nodes are independent).
+    // Two nodes per lane group and sweep, the loads of both issued before the first store: a
+    // second sweep would otherwise cost a second trip to memory.
+    using LeafVec = typename std::conditional<LOGK == 1, float2, float4>::type;
+    struct Item {
+      bool ok;
+      uint32_t node, my;
+      size_t at;
+      LeafVec c;
+      uint2 s[4];
+    };
+    // A set bit means the leaf was claimed in this batch: its stamp entry holds the winner's value.
+    auto fetch = [&](uint32_t item) -> Item {
+      Item it;
+      it.ok = item < nd;
+      const uint32_t li = it.ok ? item : nd - 1;
+      it.node = s_list[li];
       unsigned long long bits = s_bits[li];
       if constexpr (LOGK == 6) bits |= (unsigned long long)s_bits_hi[li] << 32;
-      PER_MARK(4);
-      // A set bit means the leaf was claimed in this batch: its stamp entry holds the winner's value.
+      if constexpr (LOGK == 1) {
+        it.my = (uint32_t)bits & 3u;
+        it.at = (size_t)it.node * 2;
+      } else {
+        it.my = (uint32_t)(bits >> (4 * q)) & 0xFu;
+        it.at = (size_t)it.node * K + 4 * q;
+      }
+      it.c = *reinterpret_cast<const LeafVec*>(leaves + it.at);
+#pragma unroll
+      for (int k = 0; k < (LOGK == 1 ? 2 : 4); ++k) {
+        it.s[k] = make_uint2(0, 0);
+        if (it.my & (1u << k)) it.s[k] = owner[it.at + k];
+      }
+      return it;
+    };
+    auto finish = [&](Item& it) {
       float sum;
       if constexpr (LOGK == 1) {
-        const uint32_t my = (uint32_t)bits & 3u;
-        float2 c = *reinterpret_cast<const float2*>(leaves + (size_t)node * 2);
-        uint2 s0 = make_uint2(0, 0), s1 = make_uint2(0, 0);
-        if (my & 1u) s0 = owner[(size_t)node * 2];
-        if (my & 2u) s1 = owner[(size_t)node * 2 + 1];
-        if (my & 1u) c.x = __uint_as_float(s0.x);
-        if (my & 2u) c.y = __uint_as_float(s1.x);
-        if (ok && my) *reinterpret_cast<float2*>(leaves + (size_t)node * 2) = c;
-        sum = c.x + c.y;
+        if (it.my & 1u) it.c.x = __uint_as_float(it.s[0].x);
+        if (it.my & 2u) it.c.y = __uint_as_float(it.s[1].x);
+        sum = it.c.x + it.c.y;
       } else {
-        const uint32_t my = (uint32_t)(bits >> (4 * q)) & 0xFu;
-        const size_t at = (size_t)node * K + 4 * q;
-        float4 c = *reinterpret_cast<const float4*>(leaves + at);
-        uint2 s0 = make_uint2(0, 0), s1 = s0, s2 = s0, s3 = s0;
-        if (my & 1u) s0 = owner[at];
-        if (my & 2u) s1 = owner[at + 1];
-        if (my & 4u) s2 = owner[at + 2];
-        if (my & 8u) s3 = owner[at + 3];
-        if (my & 1u) c.x = __uint_as_float(s0.x);
-        if (my & 2u) c.y = __uint_as_float(s1.x);
-        if (my & 4u) c.z = __uint_as_float(s2.x);
-        if (my & 8u) c.w = __uint_as_float(s3.x);
-        if (ok && my) *reinterpret_cast<float4*>(leaves + at) = c;
-        sum = (c.x + c.y) + (c.z + c.w);
-        PER_MARK(5);
+        if (it.my & 1u) it.c.x = __uint_as_float(it.s[0].x);
+        if (it.my & 2u) it.c.y = __uint_as_float(it.s[1].x);
+        if (it.my & 4u) it.c.z = __uint_as_float(it.s[2].x);
+        if (it.my & 8u) it.c.w = __uint_as_float(it.s[3].x);
+        sum = (it.c.x + it.c.y) + (it.c.z + it.c.w);
 #pragma unroll
         for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) sum = sum + __shfl_xor(sum, 1 << k);
-        PER_MARK(6);
       }
-      if (ok && q == 0) {
-        lvl1[node] = sum;
-        sub[node - lo1] = sum;
+      return sum;
+    };
+    auto store = [&](const Item& it, float sum) {
+      if (it.ok && it.my) *reinterpret_cast<LeafVec*>(leaves + it.at) = it.c;
+      if (it.ok && q == 0) {
+        lvl1[it.node] = sum;
+        sub[it.node - lo1] = sum;
+      }
+    };
+    for (uint32_t base = 0; base < nd; base += 2 * ngrp) {
+      Item i0 = fetch(base + grp);
+      if (base + ngrp < nd) {   // uniform over the workgroup
+        Item i1 = fetch(base + ngrp + grp);
+        PER_MARK(4);
+        const float sum0 = finish(i0);
+        const float sum1 = finish(i1);
+        PER_MARK(5);
+        store(i0, sum0);
+        store(i1, sum1);
+      } else {
+        PER_MARK(4);
+        const float sum0 = finish(i0);
+        PER_MARK(5);
+        store(i0, sum0);
       }
     }
     PER_MARK(2);
