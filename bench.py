@@ -312,6 +312,7 @@ def main():
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
+    cpu_workers = None
     if args.cpu_seconds > 0:
         from oracle.per_oracle import MultiOracle
         orc = MultiOracle(T, K, N, w.field_bytes, with_payload=True)
@@ -321,8 +322,12 @@ def main():
             rows = [np.stack([wl.row_bytes(t, cnt, f, b) for t in range(T)]) for f, b in enumerate(w.field_bytes)]
             orc.insert(m, rows, prio0[:, lo:lo + m])
         done, t_cpu = 0, 0.0
-        while done < total_steps and (t_cpu < args.cpu_seconds or done < 3):
-            inp = inputs[done]
+
+        def cpu_inputs(s):   # the recorded steps first, then further steps of the same generator
+            return inputs[s] if s < total_steps else wl.step_inputs(w, s, args.seed)
+
+        while t_cpu < args.cpu_seconds or done < 3:
+            inp = cpu_inputs(done)
             ins = None
             if w.n_insert:
                 cnt = np.arange(counter + done * w.n_insert, counter + (done + 1) * w.n_insert)
@@ -335,7 +340,7 @@ def main():
             upd = wl.apply_dup_map(ci, inp)
             orc.update(upd, inp["upd_prio"])
             t_cpu += time.perf_counter() - t0
-            if restore_ok or done == 0:
+            if done < total_steps and (restore_ok or done == 0):
                 assert np.array_equal(ci, rec_idx[done]), f"oracle and GPU disagree on step {done}"
             done += 1
         model = "unknown CPU"
@@ -351,6 +356,38 @@ def main():
                "sample": f"first {done} steps of the same workload and inputs, {t_cpu:.1f} s of CPU time, "
                          f"single thread; host: {model}, {os.cpu_count()} cores visible, {affinity} in the affinity mask"}
 
+        # Second CPU baseline: the same arithmetic on worker threads (Section V-A's CPU kernel splits
+        # the batch of requests over workers), continuing on the oracle's state with the next steps.
+        from oracle.per_workers import Workers
+        wks = [Workers(o) for o in orc.trees]
+        s_w, done_w, t_w = done, 0, 0.0
+        while t_w < args.cpu_seconds / 2 or done_w < 3:
+            inp = cpu_inputs(s_w)
+            ins = None
+            if w.n_insert:
+                cnt = np.arange(counter + s_w * w.n_insert, counter + (s_w + 1) * w.n_insert)
+                ins = [np.stack([wl.row_bytes(t, cnt, f, b) for t in range(T)]) for f, b in enumerate(w.field_bytes)]
+            t0 = time.perf_counter()
+            if w.n_insert:
+                orc.insert(w.n_insert, ins)
+            ci = np.empty((T, B), dtype=np.uint32)
+            for t in range(T):
+                ci[t], _, _ = wks[t].sample(inp["u"][t], inp["beta"], w.weights)
+                wks[t].gather(ci[t])
+            upd = wl.apply_dup_map(ci, inp)
+            for t in range(T):
+                wks[t].update(upd[t], inp["upd_prio"][t])
+            t_w += time.perf_counter() - t0
+            if s_w < total_steps and restore_ok:
+                assert np.array_equal(ci, rec_idx[s_w]), f"worker baseline and GPU disagree on step {s_w}"
+            s_w += 1
+            done_w += 1
+        if done_w:
+            cpu_workers = {"value": round(T * B * done_w / t_w, 1), "unit": "transitions/s", "cores": wks[0].threads,
+                           "kind": "oracle arithmetic on worker threads (OpenMP), bit-identical to the oracle",
+                           "sample": f"steps {done}..{s_w - 1} of the same workload and inputs, {t_w:.1f} s"}
+        del wks
+
     out = {
         "metric": "sampled+updated transitions/s per step; % of HBM peak at N=2^24, B=65536",
         "value": round(T * B / (ms_per_step * 1e-3), 1), "unit": "transitions/s",
@@ -362,6 +399,7 @@ def main():
                    ("per_sample_gather, per_update" if fused else "per_sample, per_gather, per_update")},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "cpu_workers_baseline": cpu_workers,
         "step_algorithmic_bytes": int(a_step),
         "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
         "phase_algorithmic_bytes": {"sample": int(a_sample), "gather_and_weights": int(a_gather), "update": int(a_update)},

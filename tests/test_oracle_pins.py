@@ -415,3 +415,43 @@ def test_level_shapes_follow_ceil_division():
             n = -(-n // K)
             h += 1
         assert o.H == h
+
+
+# ---------------------------------------------------------------------------------------------
+# The multi-threaded CPU baseline (oracle/per_workers.c) must be the oracle, bit for bit.
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K,N,B", [(2, 1000, 257), (16, 70001, 4096), (32, 1 << 16, 20000), (64, 5000, 33)])
+def test_worker_threads_reproduce_the_oracle(K, N, B):
+    from oracle.per_workers import Workers
+    rng = np.random.default_rng(K * 1000 + B)
+    fb = (12, 1)
+    leaves = rng.pareto(1.5, N).astype(np.float32)
+    leaves[rng.random(N) < 0.01] = 0.0
+    a, b = Oracle(K, N, fb), Oracle(K, N, fb)
+    rows = [rng.integers(0, 256, (N, e), dtype=np.uint8) for e in fb]
+    for o in (a, b):
+        o.insert(N, rows, leaves)
+    wk = Workers(b, threads=5)
+    for step in range(4):
+        u = (rng.integers(0, 1 << 24, B).astype(np.float32) / np.float32(1 << 24)).astype(np.float32)
+        ia, wa, va = a.sample(u, 0.6)
+        ib, wb, vb = wk.sample(u, 0.6)
+        assert np.array_equal(ia, ib) and va.tobytes() == vb.tobytes() and wa.tobytes() == wb.tobytes()
+        for ra, rb in zip(a.gather(ia), wk.gather(ib)):
+            assert np.array_equal(ra, rb)
+        # update batch: the sampled indices, some slots repeated out of order, some invalid elements
+        idx = ia.copy()
+        dst = rng.integers(0, B, B // 5)
+        idx[dst] = ia[rng.integers(0, B, B // 5)]
+        prio = rng.random(B).astype(np.float32)
+        if step == 1:
+            rng.shuffle(idx)                     # an unsorted batch
+        if step == 2:
+            prio[::7] = np.float32("nan")
+            prio[3::11] = -1.0
+            idx[5::13] = N + 3                   # out of range
+        a.update(idx, prio)
+        wk.update(idx, prio)
+        for d in range(a.HB + 1):
+            assert a.read_binary_depth(d).tobytes() == b.read_binary_depth(d).tobytes(), (step, d)
+        assert a.max_priority == b.max_priority and a.status == b.status
