@@ -25,8 +25,9 @@
  *     interval [prefix(i-1), prefix(i)) contains the target (go left iff
  *     r < L), and a subtree whose sum is 0 is never entered;
  *   - targets are stratified: t_i = ((float)i + u_i) * (total / (float)B);
- *   - update *sets* the leaf and re-sums its ancestors (no delta propagation),
- *     batch order, so the last writer of a duplicated index wins;
+ *   - update *sets* the leaf and re-sums its ancestors, batch order, so the last
+ *     writer of a duplicated index wins (the paper's delta propagation is a
+ *     separate operation, oracle_update_delta);
  *   - new rows get the running maximum of all values ever written;
  *   - importance weights are normalised by the batch maximum, in fp64.
  *
@@ -106,6 +107,26 @@ void oracle_update(oracle_t* o, uint32_t B, const uint32_t* idx, const float* pr
     if (!valid_priority(prio[j])) { o->status |= ORACLE_FLAG_BAD_PRIORITY; continue; }
     set_leaf(o, idx[j], prio[j]);
     if (prio[j] > o->max_v) o->max_v = prio[j];
+  }
+}
+
+/* Priority update in the paper's own form (Section V-A): the inputs are indices and changes
+ * delta; every node on the path from the root down to the leaf gets the change added, level by
+ * level.  Sequential batch order; duplicated indices simply add up.  Unlike the set-and-re-sum
+ * form above, a node is then no longer the rounded sum of its children but the running result of
+ * its own additions, so two orders of the same batch may differ in the last bits.  The running
+ * maximum is left alone (the operation never sees a priority, only its change).  Valid means
+ * idx < size and delta finite. */
+void oracle_update_delta(oracle_t* o, uint32_t B, const uint32_t* idx, const float* delta) {
+  float* t = o->tree;
+  for (uint32_t j = 0; j < B; ++j) {
+    if (!(idx[j] < o->size)) { o->status |= ORACLE_FLAG_BAD_INDEX; continue; }
+    if (!isfinite(delta[j])) { o->status |= ORACLE_FLAG_BAD_PRIORITY; continue; }
+    const uint64_t leaf = o->P + idx[j];
+    for (uint32_t depth = 0; depth <= o->HB; ++depth) {   /* root (depth 0) first, leaf last */
+      const uint64_t node = leaf >> (o->HB - depth);
+      t[node] = t[node] + delta[j];
+    }
   }
 }
 

@@ -43,6 +43,7 @@ def _load():
     lib.oracle_create.argtypes = [u32, u64, u32, C.POINTER(u32), f32, C.c_int]
     lib.oracle_destroy.argtypes = [vp]
     lib.oracle_update.argtypes = [vp, u32, vp, vp]
+    lib.oracle_update_delta.argtypes = [vp, u32, vp, vp]
     lib.oracle_insert.restype = C.c_int
     lib.oracle_insert.argtypes = [vp, u32, vp, vp, vp]
     lib.oracle_sample.restype = C.c_int
@@ -136,6 +137,12 @@ class Oracle:
         assert idx.shape == prio.shape and idx.ndim == 1
         self._lib.oracle_update(self._h, idx.shape[0], _ptr(idx), _ptr(prio))
 
+    def update_delta(self, idx: np.ndarray, delta: np.ndarray) -> None:
+        idx = np.ascontiguousarray(idx, dtype=np.uint32)
+        delta = np.ascontiguousarray(delta, dtype=np.float32)
+        assert idx.shape == delta.shape and idx.ndim == 1
+        self._lib.oracle_update_delta(self._h, idx.shape[0], _ptr(idx), _ptr(delta))
+
     def get_priority(self, idx: np.ndarray) -> np.ndarray:
         idx = np.ascontiguousarray(idx, dtype=np.uint32)
         out = np.empty(idx.shape[0], dtype=np.float32)
@@ -212,6 +219,10 @@ class MultiOracle:
     def update(self, idx, prio):
         for t, o in enumerate(self.trees):
             o.update(idx[t], prio[t])
+
+    def update_delta(self, idx, delta):
+        for t, o in enumerate(self.trees):
+            o.update_delta(idx[t], delta[t])
 
     def get_priority(self, idx):
         return np.stack([o.get_priority(idx[t]) for t, o in enumerate(self.trees)])

@@ -455,3 +455,85 @@ def test_worker_threads_reproduce_the_oracle(K, N, B):
         for d in range(a.HB + 1):
             assert a.read_binary_depth(d).tobytes() == b.read_binary_depth(d).tobytes(), (step, d)
         assert a.max_priority == b.max_priority and a.status == b.status
+
+
+# ---------------------------------------------------------------------------------------------
+# Priority update in the paper's own form (Section V-A): add delta to every node from the root down
+# to the leaf.  Pinned by exact arithmetic (dyadic values: every fp32 sum is exact, so every node must
+# be the exact sum of the leaves below it and the result must coincide with the set form), by the
+# additivity of duplicates, by an fp64 bound on arbitrary floats, and by its validity rules.
+# ---------------------------------------------------------------------------------------------
+def _exact_level(leaves_int, K, N, h):
+    """Sums of integer leaves per K-ary node of height h, by plain integer arithmetic."""
+    n = N
+    for _ in range(h):
+        n = -(-n // K)
+    span = K ** h
+    pad = np.zeros(n * span, dtype=np.int64)
+    pad[:N] = leaves_int
+    return pad.reshape(n, span).sum(axis=1)
+
+
+@pytest.mark.parametrize("K,N", [(2, 37), (4, 1000), (16, 4097), (32, 70000), (64, 300)])
+def test_delta_update_on_dyadic_values_is_exact_and_equals_the_set_form(K, N):
+    rng = np.random.default_rng(K + N)
+    scale = np.float32(2.0 ** -6)
+    top = max(2, min(1 << 10, (1 << 23) // N))        # every partial sum stays below 2^24 units: exact in fp32
+    leaves_int = rng.integers(0, top, N)
+    a, b = Oracle(K, N), Oracle(K, N)
+    for o in (a, b):
+        o.insert(N, None, (leaves_int * scale).astype(np.float32))
+    for _ in range(3):
+        B = 500
+        idx = rng.choice(N, size=min(B, N), replace=False).astype(np.uint32)       # distinct indices
+        new_int = rng.integers(0, top, idx.size)
+        old = a.get_priority(idx)
+        delta = (new_int * scale).astype(np.float32) - old                         # retrieval, then the change
+        a.update_delta(idx, delta)
+        b.update(idx, (new_int * scale).astype(np.float32))
+        leaves_int[idx] = new_int
+        for h in range(a.H + 1):
+            want = (_exact_level(leaves_int, K, N, h) * float(scale)).astype(np.float32)
+            assert a.read_level(h).tobytes() == want.tobytes(), h
+            assert a.read_level(h).tobytes() == b.read_level(h).tobytes(), h
+    assert a.status == 0
+
+
+def test_delta_update_duplicates_add_up_and_invalid_elements_are_skipped():
+    K, N = 8, 100
+    o = Oracle(K, N)
+    o.insert(60, None, np.full(60, 2.0, np.float32))          # size 60 of capacity 100
+    before = [o.read_level(h).copy() for h in range(o.H + 1)]
+    o.update_delta(np.array([5, 5, 5, 70, 7, 8], np.uint32),
+                   np.array([0.5, 0.25, -1.0, 1.0, np.nan, np.inf], np.float32))
+    assert o.status == FLAG_BAD_INDEX | FLAG_BAD_PRIORITY
+    leaf = o.read_level(0)
+    assert leaf[5] == np.float32(1.75) and leaf[7] == 2.0 and leaf[8] == 2.0 and leaf[70] == 0.0
+    for h in range(1, o.H + 1):                               # only the ancestors of leaf 5 moved, by -0.25
+        d = o.read_level(h) - before[h]
+        assert d[5 // K ** h] == np.float32(-0.25) and np.count_nonzero(d) == 1, h
+    assert o.max_priority == 2.0                              # the running maximum never sees a change
+
+
+@pytest.mark.parametrize("K,N", [(16, 5000), (2, 777)])
+def test_delta_update_stays_within_the_rounding_bound_of_the_true_sums(K, N):
+    rng = np.random.default_rng(N)
+    o = Oracle(K, N)
+    leaves = rng.exponential(1.0, N).astype(np.float32)
+    o.insert(N, None, leaves)
+    truth = leaves.astype(np.float64)
+    steps, B = 20, 300
+    for _ in range(steps):
+        idx = rng.integers(0, N, B).astype(np.uint32)
+        delta = (rng.standard_normal(B) * 0.1).astype(np.float32)
+        o.update_delta(idx, delta)
+        np.add.at(truth, idx, delta.astype(np.float64))
+    for h in range(o.H + 1):
+        n = o.level_count(h)
+        pad = np.zeros(n * K ** h)
+        pad[:N] = truth
+        want = pad.reshape(n, K ** h).sum(axis=1)
+        mag = np.zeros(n * K ** h)
+        mag[:N] = np.abs(leaves.astype(np.float64)) + 0.1 * 4 * steps
+        bound = 2.0 ** -23 * (o.HB + steps * B) * mag.reshape(n, K ** h).sum(axis=1)
+        assert np.all(np.abs(o.read_level(h).astype(np.float64) - want) <= bound), h
