@@ -46,6 +46,8 @@ def parse():
                     help="call per_update by itself instead of per_sample_gather_update")
     ap.add_argument("--overlap", action="store_true",
                     help="with --separate-gather: run the row gather on a second stream beside the update")
+    ap.add_argument("--no-delta-form", action="store_true",
+                    help="skip the extra timing of the step with the paper's delta-propagation update")
     ap.add_argument("--tune", action="append", default=[], help="name=value passed to per_set_tuning")
     return ap.parse_args()
 
@@ -294,6 +296,61 @@ def main():
         "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(kern_ms[dominant] * 1e3, 2),
     }
     step_gbs = a_step / (ms_per_step * 1e-3) / 1e9
+
+    # ---------------------------------------------------------------- the paper's own update form, for comparison
+    # Same step with the update done as the paper does it (Section V-A): retrieve the old priorities, form
+    # delta = new - old, add delta along every path (per_get_priority, one subtraction, per_update_delta).
+    # Changes meet in no fixed order there, so this run is timed but not compared with a recorded trajectory.
+    delta_form = None
+    if fused and not args.no_delta_form:
+        d_old = torch.empty((T, B), dtype=torch.float32, device="cuda")
+        d_delta = torch.empty((T, B), dtype=torch.float32, device="cuda")
+
+        def delta_step(s):
+            if w.n_insert:
+                buf.insert(w.n_insert, ins_rows[s])
+            buf.sample(d_u[s], inputs[s]["beta"], want_weights=w.weights, want_prio=True,
+                       out_idx=d_idx[s], out_weight=d_w, out_prio=d_v, rows_out=d_rows)
+            buf.get_priority(d_upd_idx[s], out=d_old)
+            torch.sub(d_prio[s], d_old, out=d_delta)
+            buf.update_delta(d_upd_idx[s], d_delta)
+
+        restore()
+        for s in range(warmup):
+            delta_step(s)
+        buf.profile(True)
+        for s in range(warmup, total_steps):
+            delta_step(s)
+        torch.cuda.synchronize()
+        dk = buf.profile_read()
+        buf.profile(False)
+        restore()
+        for s in range(warmup):
+            delta_step(s)
+        torch.cuda.synchronize()
+        g2 = None
+        if not args.no_graph:
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                for s in range(warmup, total_steps):
+                    delta_step(s)
+            torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        if g2 is not None:
+            g2.replay()
+        else:
+            for s in range(warmup, total_steps):
+                delta_step(s)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms_delta = e0.elapsed_time(e1) / steps
+        delta_form = {"ms_per_step": round(ms_delta, 5), "value": round(T * B / (ms_delta * 1e-3), 1),
+                      "unit": "transitions/s", "status_flags": buf.status(),
+                      "calls_per_step": "per_sample_gather, per_get_priority, (new - old), per_update_delta",
+                      "kernels_us": {k: round(v[0] / max(1, v[1]) * 1e3, 2) for k, v in sorted(dk.items())},
+                      "update_algorithmic_bytes": int(T * (8 * B + 4 * B + 8 * B * (H + 1)))}
+        del g2
     # what a plain streaming device copy reaches on this GPU in this run (read + written bytes per second)
     src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
@@ -400,6 +457,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "cpu_workers_baseline": cpu_workers,
+        "paper_update_form": delta_form,
         "step_algorithmic_bytes": int(a_step),
         "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
         "phase_algorithmic_bytes": {"sample": int(a_sample), "gather_and_weights": int(a_gather), "update": int(a_update)},

@@ -135,6 +135,19 @@ int per_sample_gather_update(per_t* p, uint32_t B, float beta, const float* d_u,
  * Valid means d_idx < size and d_prio finite and >= 0. */
 int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio, void* stream);
 
+/* Priority update in the paper's own form (Section V-A: "the inputs are the indices of the
+ * experiences and the changes to their priorities"): d_delta[j] is added to the leaf d_idx[j] and to
+ * every stored ancestor up to the root.  Together with per_get_priority it realises the paper's
+ * "priority retrievals followed by priority updates": retrieve the old values, form
+ * delta = new - old, apply.  Changes to the same node meet in no fixed order (hardware float
+ * atomics), so a node equals the sequential result only up to fp32 rounding, no longer the
+ * exact pairwise sum of its children; per_update restores that for the paths it touches.
+ * Duplicated indices add up.  The running maximum priority is not touched (the call never sees a
+ * priority).  Valid means d_idx < size and d_delta finite; other elements are skipped and flagged
+ * (BAD_INDEX, BAD_PRIORITY).  The caller keeps leaves non-negative. */
+int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx /*[T][B]*/, const float* d_delta /*[T][B]*/,
+                     void* stream);
+
 /* Priority retrieval (Section V-A): d_out[t][i] = leaf d_idx[t][i]. */
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream);
 

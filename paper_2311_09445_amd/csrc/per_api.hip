@@ -370,6 +370,15 @@ int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio,
   return hip_rc(e);
 }
 
+int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_delta, void* stream) {
+  int rc = check_update_args(p, B, d_idx, d_delta);
+  if (rc != PER_OK || B == 0) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = ensure_top(p, s);   // changes are added to whole nodes: the top heights must be current
+  if (e == hipSuccess) e = launch_update_delta(p->g, p->tn, B, (uint32_t)p->size, d_idx, d_delta, s);
+  return hip_rc(e);
+}
+
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream) {
   if (!p) return PER_EINVAL;
   if (n == 0) return PER_OK;

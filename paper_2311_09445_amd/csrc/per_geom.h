@@ -84,7 +84,8 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 // Optional per-kernel timing with HIP events attached to each launch (off by default).
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
-  KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_GET_PRIORITY, KID_COUNT
+  KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_UPDATE_DELTA, KID_GET_PRIORITY,
+  KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -124,6 +125,8 @@ hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipSt
 hipError_t launch_resum_top(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
 uint32_t lazy_top_height(const Geom& g, const Tuning& tn);
 hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s);
+hipError_t launch_update_delta(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
+                               const float* delta, hipStream_t s);
 hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
 hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s);
 hipError_t launch_clear_status(const Geom& g, hipStream_t s);

@@ -21,7 +21,7 @@ FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_sample_gather",
     "per_sample_gather_update", "per_gather",
-    "per_update", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
+    "per_update", "per_update_delta", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
 ]
@@ -69,6 +69,7 @@ def _lib():
         "per_sample_gather_update": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, u32, vp, vp, vp]),
         "per_gather": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update": (C.c_int, [vp, u32, vp, vp, vp]),
+        "per_update_delta": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_read_level": (C.c_int, [vp, u32, u32, vp, C.POINTER(u64), vp]),
         "per_total": (C.c_int, [vp, vp, vp]),
@@ -248,6 +249,15 @@ class PrioritizedReplay:
             raise ValueError("idx and prio must have the same number of elements")
         rc = self.lib.per_update(self._h, B, _dptr(idx, torch.int32), _dptr(prio, torch.float32), self._stream())
         self._check(rc, "per_update")
+
+    def update_delta(self, idx, delta):
+        """The paper's form of the update: add delta[j] to leaf idx[j] and to all its ancestors."""
+        torch = self._torch
+        B = idx.numel() // self.T
+        if delta.numel() != idx.numel():
+            raise ValueError("idx and delta must have the same number of elements")
+        rc = self.lib.per_update_delta(self._h, B, _dptr(idx, torch.int32), _dptr(delta, torch.float32), self._stream())
+        self._check(rc, "per_update_delta")
 
     def get_priority(self, idx, out=None):
         torch = self._torch

@@ -347,3 +347,80 @@ def test_workload_c4_full_size():
         log(f"  step {s} ok")
     m.compare_tree()
     m.compare_status()
+
+
+# ---------------------------------------------------------------------------------------------
+# Priority update in the paper's form (per_update_delta, Section V-A).  Changes meet in no fixed order,
+# so: bit-exact against the oracle where every fp32 sum is exact (dyadic values: any order gives the same
+# bits, which checks every index, level and sign), and within a rounding bound of the fp64 sums elsewhere.
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K,N,T,B", [(2, 5000, 1, 700), (4, 70001, 2, 3000), (16, 1 << 18, 3, 4096),
+                                     (32, 1 << 20, 1, 65536), (64, 300001, 1, 9000)])
+def test_delta_update_is_exact_on_dyadic_values(K, N, T, B):
+    log(f"delta update, dyadic K={K} N={N} T={T} B={B}")
+    rng = np.random.default_rng(K + N + B)
+    scale = np.float32(2.0 ** -5)
+    top = max(4, min(1 << 10, (1 << 22) // N))         # all partial sums (also with duplicates) stay exact
+    m = Mirror(K, N, T, ())
+    m.insert(N, prio=(rng.integers(top // 2, top, (T, N)) * scale).astype(np.float32), with_rows=False)
+    for it in range(3):
+        idx = rng.integers(0, N, (T, B)).astype(np.uint32)          # duplicates add up
+        delta = (rng.integers(-(top // 4) // 8, top // 4, (T, B)) * scale).astype(np.float32)
+        if it == 1:                                                  # a few elements that must be skipped
+            idx[:, ::97] = N + 5
+            delta[:, 5::101] = np.float32("inf")
+        if it == 2:                                                  # right after an update that left the top stale
+            ui = rng.integers(0, N, (T, 100)).astype(np.uint32)
+            m.update(ui, (rng.integers(1, top, (T, 100)) * scale).astype(np.float32))
+        m.gpu.update_delta(idx_to_dev(idx), dev(delta))
+        m.cpu.update_delta(idx, delta)
+        m.compare_tree()
+    assert m.gpu.status() == m.cpu.status == (FLAG_BAD_INDEX | FLAG_BAD_PRIORITY)
+
+
+def test_retrieval_then_delta_update_equals_the_set_form_on_dyadic_values():
+    """The paper realises a priority update as retrieval followed by the delta update."""
+    K, N, B = 16, 1 << 16, 5000
+    rng = np.random.default_rng(5)
+    scale = np.float32(2.0 ** -4)
+    m = Mirror(K, N, 1, ())
+    m.insert(N, prio=(rng.integers(1, 64, (1, N)) * scale).astype(np.float32), with_rows=False)
+    idx = rng.choice(N, size=(1, B), replace=False).astype(np.uint32)
+    new = (rng.integers(0, 64, (1, B)) * scale).astype(np.float32)
+    di = idx_to_dev(idx)
+    old = m.gpu.get_priority(di)
+    m.gpu.update_delta(di, dev(new) - old)
+    m.cpu.update(idx, new)                       # the oracle's set form
+    m.compare_tree(heights=range(m.gpu.H + 1))
+
+
+@pytest.mark.parametrize("K,N,B", [(32, 1 << 20, 65536), (8, 100000, 4000)])
+def test_delta_update_stays_within_the_rounding_bound(K, N, B):
+    log(f"delta update, floats K={K} N={N} B={B}")
+    rng = np.random.default_rng(N + B)
+    leaves = rng.exponential(1.0, (1, N)).astype(np.float32)
+    p = PrioritizedReplay(K, N)
+    p.insert(N, None, dev(leaves))
+    truth = leaves[0].astype(np.float64)
+    steps = 5
+    for _ in range(steps):
+        idx = rng.integers(0, N, (1, B)).astype(np.uint32)
+        delta = (rng.standard_normal((1, B)) * 0.1).astype(np.float32)
+        p.update_delta(idx_to_dev(idx), dev(delta))
+        np.add.at(truth, idx[0], delta[0].astype(np.float64))
+    HB = p.H * (K.bit_length() - 1)
+    for h in range(p.H + 1):
+        got = p.read_level(0, h).cpu().numpy().astype(np.float64)
+        n, span = got.size, K ** h
+        pad = np.zeros(n * span)
+        pad[:N] = truth
+        mag = np.zeros(n * span)
+        mag[:N] = np.abs(leaves[0].astype(np.float64)) + 0.1 * 4 * steps
+        # every addition rounds by at most half an ulp of a partial result bounded by the magnitudes below the node
+        adds = HB + steps * B
+        bound = 2.0 ** -23 * np.minimum(adds, span * 64 + 64) * mag.reshape(n, span).sum(axis=1)
+        assert np.all(np.abs(got - pad.reshape(n, span).sum(axis=1)) <= bound), h
+    assert p.status() == 0
+    # sampling still works on the drifted tree
+    i, w, v = p.sample(dev(wl.uniform01(rng, (1, 1000))), 0.4)
+    assert int(idx_to_host(i).max()) < N
