@@ -185,6 +185,7 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
  *                  the library clears the stamp array and starts over when they run out
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
  *                  the next call that reads them; 0 makes per_update finish them itself
+ *   "insert_small" : 1 (default) runs an insert of few rows as a single kernel, one workgroup per tree
  *   "claim_in_sample" : 1 (default) lets per_sample_gather_update run the first phase of its update
  *                  inside the sampling kernel (two kernels per step) whenever the update batch is the
  *                  sampled batch itself or lies apart from the sampling outputs; 0: always three kernels */

@@ -198,6 +198,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.tree_block = 0;   // chosen per launch
   p->tn.lazy_top = 1;
   p->tn.claim_in_sample = 1;
+  p->tn.insert_small = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->stamp_next = 1;
@@ -229,9 +230,17 @@ int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float
   const uint64_t N = p->cfg.capacity;
   const uint32_t cursor = (uint32_t)p->cursor;
   FieldTable ft;
+  const bool has_rows = fill_fields(p, const_cast<void* const*>(reinterpret_cast<const void* const*>(d_field_src)), &ft);
+  if (p->tn.insert_small && insert_fits_one_workgroup(p->g, has_rows ? &ft : nullptr, n)) {
+    // one kernel: rows, leaves, ancestors, and the heights an update may have left stale
+    hipError_t e1 = launch_insert_small(p->g, p->tn, has_rows ? &ft : nullptr, n, cursor, d_prio, d_out_idx, p->stale_hb, s);
+    if (e1 == hipSuccess) p->stale_hb = 0;
+    p->cursor = (p->cursor + n) % N;
+    p->size = p->size + n > N ? N : p->size + n;
+    return hip_rc(e1);
+  }
   hipError_t e = ensure_top(p, s);
-  if (e == hipSuccess && fill_fields(p, const_cast<void* const*>(reinterpret_cast<const void* const*>(d_field_src)), &ft))
-    e = launch_scatter(p->g, p->tn, ft, n, cursor, s);
+  if (e == hipSuccess && has_rows) e = launch_scatter(p->g, p->tn, ft, n, cursor, s);
   if (e == hipSuccess) e = launch_insert_leaves(p->g, p->tn, n, cursor, d_prio, d_out_idx, s);
   if (e == hipSuccess) {
     Range2 r;
@@ -462,6 +471,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "lazy_top")) {
     if (value != 0 && value != 1) return PER_EINVAL;
     p->tn.lazy_top = (uint32_t)value;
+    return PER_OK;
+  }
+  if (!strcmp(name, "insert_small")) {
+    if (value != 0 && value != 1) return PER_EINVAL;
+    p->tn.insert_small = (uint32_t)value;
     return PER_OK;
   }
   if (!strcmp(name, "claim_in_sample")) {

@@ -85,7 +85,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_UPDATE_DELTA, KID_GET_PRIORITY,
-  KID_COUNT
+  KID_INSERT_SMALL, KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -105,6 +105,7 @@ struct Tuning {
   uint32_t sample_block, update_block, gather_block, tree_block;
   uint32_t sample_min_lds;   // lower bound of the sampling kernel's LDS request, bytes
   uint32_t lazy_top;   // updates may leave the few topmost heights to their next reader
+  uint32_t insert_small;      // small inserts run as one kernel (one workgroup per tree)
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   Profiler* prof;
 };
@@ -121,6 +122,9 @@ hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft,
                           hipStream_t s);
 hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uint32_t cursor, const float* prio,
                                 uint32_t* out_idx, hipStream_t s);
+bool insert_fits_one_workgroup(const Geom& g, const FieldTable* ft, uint32_t n);
+hipError_t launch_insert_small(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n, uint32_t cursor,
+                               const float* prio, uint32_t* out_idx, uint32_t stale_hb, hipStream_t s);
 hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipStream_t s);
 hipError_t launch_resum_top(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
 uint32_t lazy_top_height(const Geom& g, const Tuning& tn);

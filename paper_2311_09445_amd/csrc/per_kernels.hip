@@ -23,7 +23,7 @@ const char* kernel_name(int kid) {
   static const char* const names[KID_COUNT] = {
       "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_finish", "k_rows_scatter", "k_insert_leaves",
       "k_resum_dense", "k_resum_tail", "k_update_claim", "k_update_tree", "k_tree_finish", "k_update_delta",
-      "k_get_priority"};
+      "k_get_priority", "k_insert_small"};
   return kid >= 0 && kid < KID_COUNT ? names[kid] : "?";
 }
 
@@ -125,6 +125,12 @@ struct Fan {
   static constexpr int LOGLPS = LOGK >= 2 ? LOGK - 2 : 0;
 };
 
+// Workgroup barrier for phases that hand data over through LDS only.  Unlike __syncthreads() it does
+// not wait for this wave's outstanding global stores (which nothing in the workgroup reads back).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ bool valid_priority(float v) {
   return v >= 0.0f && v <= 3.402823466e38f;   // finite and >= 0 (false for NaN); -0.0f passes
 }
@@ -144,6 +150,28 @@ __device__ __forceinline__ float group_sum(const float* grp, unsigned q) {
 #pragma unroll
     for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) s = s + __shfl_xor(s, 1 << k);
     return s;
+  }
+}
+
+// Per-height facts of one tree, kept in LDS by kernels that loop over heights: indexing the
+// kernel arguments by a run-time height costs a dependent scalar load from memory per use.  The
+// kernel-argument segment is ordinary read-only memory, so lane h fetches the entries of height h
+// from it with a vector load and all heights arrive in one trip.  Only for kernels whose FIRST
+// argument is the Geom (it then sits at offset 0 of the segment).
+struct LevelTable {
+  float* lvl[kMaxHeight + 1];   // level h of this tree
+  uint32_t n[kMaxHeight + 1];   // its real nodes
+};
+template <typename T>
+__device__ __forceinline__ const T* kernarg_at(size_t offset) {
+  return (const T*)((const char*)__builtin_amdgcn_kernarg_segment_ptr() + offset);
+}
+__device__ __forceinline__ void fill_level_table(uint32_t H, uint32_t t, LevelTable* tab) {
+  const Geom* gk = kernarg_at<Geom>(0);
+  const uint32_t h = threadIdx.x;
+  if (h <= H) {
+    tab->lvl[h] = gk->level[h] + (size_t)t * gk->stride[h];
+    tab->n[h] = gk->n[h];
   }
 }
 
@@ -801,6 +829,56 @@ __device__ __forceinline__ void rows_job(const FieldTable& ft, uint32_t f, uint3
   }
 }
 
+// Row scatter of a small insert by one workgroup: the elements of all fields form one flat index
+// space shared out over the lanes.  Addresses are worked out first (the part that differs by
+// field), then every lane issues its one load and, after it, its one store: the lanes of a wave
+// that serve different fields do not wait for each other's trips to memory.
+__device__ __forceinline__ void scatter_rows_one_workgroup(const FieldTable& ft, uint32_t t, uint32_t n, uint32_t cursor,
+                                                           uint32_t N) {
+  uint32_t first[kMaxFields + 1];
+  first[0] = 0;
+#pragma unroll
+  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
+    first[f + 1] = first[f] + (f < ft.n_fields && ft.io[f] ? n * (ft.bytes[f] / ft.vec[f]) : 0u);
+  for (uint32_t e = threadIdx.x; e < first[kMaxFields]; e += blockDim.x) {
+    // the field of this element, picked with selects; the divisions are done once, after the choice
+    const uint8_t* io = nullptr;
+    uint8_t* col = nullptr;
+    uint32_t E = 1, w = 1, base = 0;
+#pragma unroll
+    for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f) {
+      const bool here = e >= first[f] && e < first[f + 1];
+      io = here ? ft.io[f] : io;
+      col = here ? ft.col[f] + (uint64_t)t * ft.col_stride[f] : col;
+      E = here ? ft.bytes[f] : E;
+      w = here ? ft.vec[f] : w;
+      base = here ? first[f] : base;
+    }
+    const uint32_t epr = E / w;
+    const uint32_t el = e - base;
+    const uint32_t row = el / epr, k = el - row * epr;
+    uint64_t slot = (uint64_t)cursor + row;
+    if (slot >= N) slot -= N;
+    const uint8_t* src = io + ((uint64_t)t * n + row) * E + (uint64_t)k * w;
+    uint8_t* dst = col + slot * E + (uint64_t)k * w;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    switch (w) {
+      case 16: v = *reinterpret_cast<const uint4*>(src); break;
+      case 8: { const uint2 x = *reinterpret_cast<const uint2*>(src); v.x = x.x; v.y = x.y; } break;
+      case 4: v.x = *reinterpret_cast<const uint32_t*>(src); break;
+      case 2: v.x = *reinterpret_cast<const uint16_t*>(src); break;
+      default: v.x = *src; break;
+    }
+    switch (w) {
+      case 16: *reinterpret_cast<uint4*>(dst) = v; break;
+      case 8: *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.y); break;
+      case 4: *reinterpret_cast<uint32_t*>(dst) = v.x; break;
+      case 2: *reinterpret_cast<uint16_t*>(dst) = (uint16_t)v.x; break;
+      default: *dst = (uint8_t)v.x; break;
+    }
+  }
+}
+
 // Second kernel of the fused calls.  Its workgroups (blockIdx.x) split into jobs, each with as many
 // workgroups as it needs (JobRanges): first the importance weights of the batch just sampled (if
 // asked for), then the claim phase of a priority update (if one is fused in), then one job per
@@ -914,27 +992,33 @@ __global__ void k_resum_dense(Geom g, uint32_t h, uint32_t a, uint32_t count) {
 
 // One workgroup per tree finishes heights h_start .. H over the node ranges in r (given at
 // height h_start and narrowed by K per height).
+// The workgroup recomputes the nodes of height h in the two ranges of r from their children.
 template <int LOGK>
-__global__ void k_resum_tail(Geom g, uint32_t h_start, Range2 r) {
+__device__ __forceinline__ void resum_level(const Geom& g, uint32_t t, uint32_t h, const Range2& r) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
-  const uint32_t t = blockIdx.x;
   const unsigned q = threadIdx.x % LPS;
   const uint32_t grp = threadIdx.x / LPS;
   const uint32_t ngrp = blockDim.x / LPS;
-  for (uint32_t h = h_start; h <= g.H; ++h) {
-    const float* child = g.level[h - 1] + (size_t)t * g.stride[h - 1];
-    float* par = g.level[h] + (size_t)t * g.stride[h];
-    for (int part = 0; part < 2; ++part) {
-      const uint32_t a = part ? r.a1 : r.a0, b = part ? r.b1 : r.b0;
-      for (uint32_t base = a; base < b; base += ngrp) {
-        const uint32_t e = base + grp;
-        const bool ok = e < b;
-        const uint32_t node = ok ? e : a;
-        const float sum = group_sum<LOGK>(child + (size_t)node * K, q);
-        if (ok && q == 0) par[node] = sum;
-      }
+  const float* child = g.level[h - 1] + (size_t)t * g.stride[h - 1];
+  float* par = g.level[h] + (size_t)t * g.stride[h];
+  for (int part = 0; part < 2; ++part) {
+    const uint32_t a = part ? r.a1 : r.a0, b = part ? r.b1 : r.b0;
+    for (uint32_t base = a; base < b; base += ngrp) {
+      const uint32_t e = base + grp;
+      const bool ok = e < b;
+      const uint32_t node = ok ? e : a;
+      const float sum = group_sum<LOGK>(child + (size_t)node * K, q);
+      if (ok && q == 0) par[node] = sum;
     }
+  }
+}
+
+template <int LOGK>
+__global__ void k_resum_tail(Geom g, uint32_t h_start, Range2 r) {
+  const uint32_t t = blockIdx.x;
+  for (uint32_t h = h_start; h <= g.H; ++h) {
+    resum_level<LOGK>(g, t, h, r);
     __syncthreads();
     if (r.b0 > r.a0) { r.a0 >>= LOGK; r.b0 = ((r.b0 - 1) >> LOGK) + 1; }
     if (r.b1 > r.a1) { r.a1 >>= LOGK; r.b1 = ((r.b1 - 1) >> LOGK) + 1; }
@@ -997,34 +1081,153 @@ hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipSt
 // ---------------------------------------------------------------------------------
 // insertion: leaf writes (rows go through k_rows<false>)
 // ---------------------------------------------------------------------------------
+// Leaf of inserted row j (ring slot cursor + j): the given value, or the running maximum.
+__device__ __forceinline__ void insert_leaf(const Geom& g, uint32_t t, uint32_t n, uint32_t cursor, uint32_t j,
+                                            const float* __restrict__ prio, float max_on_entry,
+                                            uint32_t* __restrict__ out_idx, uint32_t& mx, bool& bad) {
+  uint64_t slot = (uint64_t)cursor + j;
+  if (slot >= g.N) slot -= g.N;
+  if (out_idx) out_idx[(size_t)t * n + j] = (uint32_t)slot;
+  float* leaf = g.level[0] + (size_t)t * g.stride[0] + slot;
+  if (prio) {
+    const float v = prio[(size_t)t * n + j];
+    if (valid_priority(v)) {
+      *leaf = v;
+      const uint32_t vb = v > 0.0f ? __float_as_uint(v) : 0u;
+      mx = vb > mx ? vb : mx;
+    } else {
+      bad = true;
+    }
+  } else {
+    *leaf = max_on_entry;   // running maximum as it was when the call started
+  }
+}
+
 __global__ void k_insert_leaves(Geom g, uint32_t n, uint32_t cursor, const float* __restrict__ prio,
                                 uint32_t* __restrict__ out_idx) {
   const uint32_t t = blockIdx.y;
   const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  const bool active = j < n;
   uint32_t mx = 0;
   bool bad = false;
-  if (active) {
-    uint64_t slot = (uint64_t)cursor + j;
-    if (slot >= g.N) slot -= g.N;
-    if (out_idx) out_idx[(size_t)t * n + j] = (uint32_t)slot;
-    float* leaf = g.level[0] + (size_t)t * g.stride[0] + slot;
-    if (prio) {
-      const float v = prio[(size_t)t * n + j];
-      if (valid_priority(v)) {
-        *leaf = v;
-        mx = v > 0.0f ? __float_as_uint(v) : 0u;
-      } else {
-        bad = true;
-      }
-    } else {
-      *leaf = g.max_v[t];   // running maximum as it was when the call started
-    }
-  }
+  if (j < n) insert_leaf(g, t, n, cursor, j, prio, prio ? 0.0f : g.max_v[t], out_idx, mx, bad);
   if (prio) {
     raise_max(g, t, mx, read_max_bits(g, t));
     if (bad) atomicOr(&g.status[t], 2u);
   }
+}
+
+// A small insert as one kernel, one workgroup per tree: the rows, the leaves, and every ancestor
+// of the touched ring slots up to the root.  The touched nodes of a height form at most two
+// contiguous ranges (narrowed by K per height), known before anything is read, so the child groups
+// of all of them, at every height, are fetched into LDS in one trip; the new leaves and then each
+// height's new sums are patched into the staged groups of the height above, and the heights are
+// finished from LDS without going back to memory.
+// stale_hb != 0: the last update left the heights above stale_hb to their next reader; they are
+// then recomputed here in full instead of only over the touched ranges.
+constexpr int kInsertHeights = 32;
+struct InsertPlan {
+  Range2 r[kInsertHeights];        // touched nodes of height h + 1
+  uint32_t off[kInsertHeights];    // where their child groups start in LDS (floats)
+};
+struct InsertArgs {                // one kernel argument, so that both parts sit at known offsets of the segment
+  Geom g;
+  InsertPlan plan;
+};
+
+// position of node among the touched nodes of its height (the two ranges back to back)
+__device__ __forceinline__ uint32_t plan_pos(const Range2& r, uint32_t node) {
+  return node >= r.a0 && node < r.b0 ? node - r.a0 : (r.b0 - r.a0) + (node - r.a1);
+}
+
+template <int LOGK>
+__global__ void __launch_bounds__(1024)
+k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const float* __restrict__ prio,
+               uint32_t* __restrict__ out_idx) {
+  const Geom& g = a.g;
+  constexpr int K = Fan<LOGK>::K;
+  constexpr int LPS = Fan<LOGK>::LPS;
+  extern __shared__ __attribute__((aligned(16))) float staged[];
+  __shared__ LevelTable tab;
+  __shared__ Range2 s_r[kInsertHeights];
+  __shared__ uint32_t s_off[kInsertHeights];
+  const uint32_t t = blockIdx.x;
+  const uint32_t H = g.H;
+  PER_TRACE_DECL;
+  PER_MARK(0);
+  fill_level_table(H, t, &tab);
+  if (threadIdx.x >= 64 && threadIdx.x < 64 + H) {
+    const InsertPlan* pk = kernarg_at<InsertPlan>(offsetof(InsertArgs, plan));
+    s_r[threadIdx.x - 64] = pk->r[threadIdx.x - 64];
+    s_off[threadIdx.x - 64] = pk->off[threadIdx.x - 64];
+  }
+  // the rows need none of the tables: their trip to memory overlaps the fetch of the tables
+  scatter_rows_one_workgroup(ft, t, n, cursor, g.N);
+  __syncthreads();
+  PER_MARK(1);
+  // ---- everything that is read: the child groups of all touched nodes, the running maximum
+  for (uint32_t h = 1; h <= H; ++h) {
+    const Range2 r = s_r[h - 1];
+    const uint32_t c0 = r.b0 - r.a0, cnt = c0 + (r.b1 - r.a1);
+    const float* child = tab.lvl[h - 1];
+    for (uint32_t e = threadIdx.x; e < cnt * K; e += blockDim.x) {
+      const uint32_t pos = e >> LOGK;
+      const uint32_t node = pos < c0 ? r.a0 + pos : r.a1 + (pos - c0);
+      staged[s_off[h - 1] + e] = child[(size_t)node * K + (e & (K - 1))];
+    }
+  }
+  const float max_on_entry = prio ? 0.0f : g.max_v[t];
+  uint32_t max_seen = 0;
+  if (prio) max_seen = read_max_bits(g, t);
+  __syncthreads();
+  PER_MARK(2);
+  // ---- leaves (stores only), the new ones also into their staged groups
+  uint32_t mx = 0;
+  bool bad = false;
+  for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) {
+    uint64_t slot = (uint64_t)cursor + j;
+    if (slot >= g.N) slot -= g.N;
+    if (out_idx) out_idx[(size_t)t * n + j] = (uint32_t)slot;
+    float v = max_on_entry;
+    bool ok = true;
+    if (prio) {
+      v = prio[(size_t)t * n + j];
+      ok = valid_priority(v);
+      const uint32_t vb = ok && v > 0.0f ? __float_as_uint(v) : 0u;
+      mx = vb > mx ? vb : mx;
+      bad = bad || !ok;
+    }
+    if (ok) {
+      tab.lvl[0][slot] = v;
+      staged[s_off[0] + plan_pos(s_r[0], (uint32_t)(slot >> LOGK)) * K + ((uint32_t)slot & (K - 1))] = v;
+    }
+  }
+  if (prio) {
+    raise_max(g, t, mx, max_seen);
+    if (bad) atomicOr(&g.status[t], 2u);
+  }
+  __syncthreads();
+  PER_MARK(3);
+  // ---- heights 1 .. H from the staged groups
+  const unsigned q = threadIdx.x % LPS;
+  const uint32_t grp = threadIdx.x / LPS, ngrp = blockDim.x / LPS;
+  for (uint32_t h = 1; h <= H; ++h) {
+    const Range2 r = s_r[h - 1];
+    const uint32_t c0 = r.b0 - r.a0, cnt = c0 + (r.b1 - r.a1);
+    float* par = tab.lvl[h];
+    for (uint32_t base = 0; base < cnt; base += ngrp) {
+      const uint32_t pos = base + grp;
+      const bool ok = pos < cnt;
+      const float sum = group_sum<LOGK>(staged + s_off[h - 1] + (size_t)(ok ? pos : 0u) * K, q);
+      if (ok && q == 0) {
+        const uint32_t node = pos < c0 ? r.a0 + pos : r.a1 + (pos - c0);
+        par[node] = sum;
+        if (h < H) staged[s_off[h] + plan_pos(s_r[h], node >> LOGK) * K + (node & (K - 1))] = sum;
+      }
+    }
+    lds_barrier();   // the next height reads the staged groups only
+  }
+  PER_MARK(4);
+  PER_FLUSH();
 }
 
 hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uint32_t cursor, const float* prio,
@@ -1032,6 +1235,57 @@ hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uin
   PER_LAUNCH(KID_INSERT_LEAVES, k_insert_leaves, dim3((n + 255) / 256, g.T), dim3(256), 0, s, g, n, cursor, prio,
              out_idx);
   return hipGetLastError();
+}
+
+// True when an insert of n rows is small enough for k_insert_small: few bytes to move and few
+// nodes per height for one workgroup.
+bool insert_fits_one_workgroup(const Geom& g, const FieldTable* ft, uint32_t n) {
+  uint64_t bytes = 0;
+  if (ft)
+    for (uint32_t f = 0; f < ft->n_fields; ++f)
+      if (ft->io[f]) bytes += (uint64_t)n * ft->bytes[f];
+  return n <= 4096 && bytes <= 256 * 1024;
+}
+
+template <int LOGK>
+static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n,
+                                        uint32_t cursor, const float* prio, uint32_t* out_idx, uint32_t stale_hb,
+                                        hipStream_t s) {
+  constexpr int K = Fan<LOGK>::K;
+  FieldTable f{};
+  if (ft) f = *ft;
+  InsertArgs a{};
+  a.g = g;
+  InsertPlan& plan = a.plan;
+  const uint64_t end = (uint64_t)cursor + n;
+  Range2 r;
+  r.a0 = cursor;
+  r.b0 = (uint32_t)(end < g.N ? end : g.N);
+  r.a1 = 0;
+  r.b1 = (uint32_t)(end > g.N ? end - g.N : 0);
+  uint32_t floats = 0;
+  for (uint32_t h = 1; h <= g.H; ++h) {
+    if (r.b0 > r.a0) { r.a0 >>= LOGK; r.b0 = ((r.b0 - 1) >> LOGK) + 1; }
+    if (r.b1 > r.a1) { r.a1 >>= LOGK; r.b1 = ((r.b1 - 1) >> LOGK) + 1; }
+    if (r.b1 > r.a1 && r.a0 < r.b1) { r.a0 = 0; r.a1 = r.b1 = 0; }   // the two ranges met: one range
+    if (stale_hb && h > stale_hb) r = Range2{0, g.n[h], 0, 0};
+    plan.r[h - 1] = r;
+    plan.off[h - 1] = floats;
+    floats += ((r.b0 - r.a0) + (r.b1 - r.a1)) * K;
+  }
+  uint32_t block = (n * Fan<LOGK>::LPS + 63) / 64 * 64;
+  if (block < 256) block = 256;
+  if (block > 1024) block = 1024;
+  PER_LAUNCH(KID_INSERT_SMALL, k_insert_small<LOGK>, dim3(g.T), dim3(block), (size_t)floats * 4, s, a, f, n, cursor, prio,
+             out_idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_insert_small(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n, uint32_t cursor,
+                               const float* prio, uint32_t* out_idx, uint32_t stale_hb, hipStream_t s) {
+#define CALL(L) launch_insert_small_k<L>(g, tn, ft, n, cursor, prio, out_idx, stale_hb, s)
+  PER_DISPATCH_LOGK(g.logK, CALL)
+#undef CALL
 }
 
 // ---------------------------------------------------------------------------------
@@ -1428,8 +1682,10 @@ hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hi
 __global__ void k_update_delta(Geom g, uint32_t B, uint32_t size, const uint32_t* __restrict__ idx,
                                const float* __restrict__ delta, uint32_t h_lds, uint32_t acc_floats) {
   extern __shared__ __attribute__((aligned(16))) float acc[];
+  __shared__ LevelTable tab;
   const uint32_t t = blockIdx.y;
   const uint32_t H = g.H;
+  fill_level_table(H, t, &tab);
   for (uint32_t e = threadIdx.x; e < acc_floats; e += blockDim.x) acc[e] = 0.0f;
   __syncthreads();
   const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1450,31 +1706,31 @@ __global__ void k_update_delta(Geom g, uint32_t B, uint32_t size, const uint32_t
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) wave_sum += __shfl_xor(wave_sum, m);
   uint32_t off_root = 0;   // the LDS copy holds heights h_lds .. H in that order
-  for (uint32_t h = h_lds; h < H; ++h) off_root += g.n[h];
+  for (uint32_t h = h_lds; h < H; ++h) off_root += tab.n[h];
   if (h_lds <= H && (threadIdx.x & 63u) == 0 && wave_sum != 0.0f) atomicAdd(&acc[off_root], wave_sum);
   if (ok) {
     uint32_t off = off_root;
     for (uint32_t h = H; h-- > 0;) {   // heights H-1 .. 0 (the root is done above, or here when it is not in LDS)
       const uint32_t node = i >> (h * g.logK);
       if (h >= h_lds) {
-        off -= g.n[h];
+        off -= tab.n[h];
         atomicAdd(&acc[off + node], d);
       } else {
-        unsafeAtomicAdd(g.level[h] + (size_t)t * g.stride[h] + node, d);
+        unsafeAtomicAdd(tab.lvl[h] + node, d);
       }
     }
-    if (h_lds > H) unsafeAtomicAdd(g.level[H] + (size_t)t * g.stride[H], d);
+    if (h_lds > H) unsafeAtomicAdd(tab.lvl[H], d);
   }
   if (flags) atomicOr(&g.status[t], flags);
   __syncthreads();
   uint32_t off = 0;
   for (uint32_t h = h_lds; h <= H; ++h) {
-    float* lvl = g.level[h] + (size_t)t * g.stride[h];
-    for (uint32_t e = threadIdx.x; e < g.n[h]; e += blockDim.x) {
+    float* lvl = tab.lvl[h];
+    for (uint32_t e = threadIdx.x; e < tab.n[h]; e += blockDim.x) {
       const float v = acc[off + e];
       if (v != 0.0f) unsafeAtomicAdd(lvl + e, v);
     }
-    off += g.n[h];
+    off += tab.n[h];
   }
 }
 

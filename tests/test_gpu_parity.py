@@ -424,3 +424,32 @@ def test_delta_update_stays_within_the_rounding_bound(K, N, B):
     # sampling still works on the drifted tree
     i, w, v = p.sample(dev(wl.uniform01(rng, (1, 1000))), 0.4)
     assert int(idx_to_host(i).max()) < N
+
+
+@pytest.mark.parametrize("K,N,T,fb", [(2, 1000, 1, (5,)), (16, 5000, 3, (68, 24, 4, 68, 1)), (32, 40000, 1, (128,)),
+                                      (64, 4097, 2, ())])
+@pytest.mark.parametrize("one_kernel", [1, 0])
+def test_small_inserts_in_one_kernel_or_several(K, N, T, fb, one_kernel):
+    """Few rows per insert take a single-kernel path (rows, leaves and ancestors by one workgroup per tree);
+    it must behave like the general path: ring wrap-around, explicit and default priorities, invalid
+    priorities, and heights that the preceding update left to its next reader."""
+    log(f"small inserts K={K} N={N} T={T} one_kernel={one_kernel}")
+    rng = np.random.default_rng(K + N + T)
+    m = Mirror(K, N, T, fb)
+    m.gpu.set_tuning("insert_small", one_kernel)
+    m.insert(N - 7, prio=wl._draw_priorities("exponential_1", rng, (T, N - 7)), chunk=3000)   # ring almost full
+    for it, n in enumerate([1, 5, 16, 3, 200, 64, 1000, 7]):
+        if it % 2 == 0:
+            m.insert(n)                                   # running maximum; the ring wraps during these steps
+        else:
+            pr = rng.random((T, n)).astype(np.float32) * 3
+            if it == 3:
+                pr[:, 1] = np.float32("nan")
+            m.insert(n, prio=pr)
+        m.compare_tree()
+        idx = rng.integers(0, N, (T, 300)).astype(np.uint32)
+        m.update(idx, rng.random((T, 300)).astype(np.float32) * 5)     # leaves the top heights stale on larger trees
+    gi, ci = m.sample(wl.uniform01(rng, (T, 256)), 0.4)
+    m.gather(gi, ci)
+    m.compare_tree()
+    m.compare_status()
