@@ -1682,10 +1682,8 @@ hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hi
 __global__ void k_update_delta(Geom g, uint32_t B, uint32_t size, const uint32_t* __restrict__ idx,
                                const float* __restrict__ delta, uint32_t h_lds, uint32_t acc_floats) {
   extern __shared__ __attribute__((aligned(16))) float acc[];
-  __shared__ LevelTable tab;
   const uint32_t t = blockIdx.y;
   const uint32_t H = g.H;
-  fill_level_table(H, t, &tab);
   for (uint32_t e = threadIdx.x; e < acc_floats; e += blockDim.x) acc[e] = 0.0f;
   __syncthreads();
   const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1706,31 +1704,31 @@ __global__ void k_update_delta(Geom g, uint32_t B, uint32_t size, const uint32_t
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) wave_sum += __shfl_xor(wave_sum, m);
   uint32_t off_root = 0;   // the LDS copy holds heights h_lds .. H in that order
-  for (uint32_t h = h_lds; h < H; ++h) off_root += tab.n[h];
+  for (uint32_t h = h_lds; h < H; ++h) off_root += g.n[h];
   if (h_lds <= H && (threadIdx.x & 63u) == 0 && wave_sum != 0.0f) atomicAdd(&acc[off_root], wave_sum);
   if (ok) {
     uint32_t off = off_root;
     for (uint32_t h = H; h-- > 0;) {   // heights H-1 .. 0 (the root is done above, or here when it is not in LDS)
       const uint32_t node = i >> (h * g.logK);
       if (h >= h_lds) {
-        off -= tab.n[h];
+        off -= g.n[h];
         atomicAdd(&acc[off + node], d);
       } else {
-        unsafeAtomicAdd(tab.lvl[h] + node, d);
+        unsafeAtomicAdd(g.level[h] + (size_t)t * g.stride[h] + node, d);
       }
     }
-    if (h_lds > H) unsafeAtomicAdd(tab.lvl[H], d);
+    if (h_lds > H) unsafeAtomicAdd(g.level[H] + (size_t)t * g.stride[H], d);
   }
   if (flags) atomicOr(&g.status[t], flags);
   __syncthreads();
   uint32_t off = 0;
   for (uint32_t h = h_lds; h <= H; ++h) {
-    float* lvl = tab.lvl[h];
-    for (uint32_t e = threadIdx.x; e < tab.n[h]; e += blockDim.x) {
+    float* lvl = g.level[h] + (size_t)t * g.stride[h];
+    for (uint32_t e = threadIdx.x; e < g.n[h]; e += blockDim.x) {
       const float v = acc[off + e];
       if (v != 0.0f) unsafeAtomicAdd(lvl + e, v);
     }
-    off += tab.n[h];
+    off += g.n[h];
   }
 }
 
