@@ -135,6 +135,14 @@ int per_sample_gather_update(per_t* p, uint32_t B, float beta, const float* d_u,
  * Valid means d_idx < size and d_prio finite and >= 0. */
 int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio, void* stream);
 
+/* per_update from temporal-difference errors: the tree value of element j is
+ * (|d_td[j]| + eps)^alpha, the priority of prioritized experience replay that the paper's sampling
+ * follows (Section II-A: experiences are drawn in proportion to the policy loss), evaluated in fp64
+ * on the device and rounded once to fp32; everything else as per_update.  A non-finite error is
+ * skipped and flagged BAD_PRIORITY.  eps >= 0 and alpha >= 0, both finite, else PER_EINVAL. */
+int per_update_td(per_t* p, uint32_t B, const uint32_t* d_idx /*[T][B]*/, const float* d_td /*[T][B]*/,
+                  double eps, double alpha, void* stream);
+
 /* Priority update in the paper's own form (Section V-A: "the inputs are the indices of the
  * experiences and the changes to their priorities"): d_delta[j] is added to the leaf d_idx[j] and to
  * every stored ancestor up to the root.  Together with per_get_priority it realises the paper's

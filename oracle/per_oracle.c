@@ -110,6 +110,20 @@ void oracle_update(oracle_t* o, uint32_t B, const uint32_t* idx, const float* pr
   }
 }
 
+/* Priority update from temporal-difference errors: the priority of prioritized experience replay
+ * (cited in Section II-A), value = (|td| + eps)^alpha, evaluated in fp64 and rounded once to fp32,
+ * then the set-and-re-sum update above.  Valid means idx < size and td finite. */
+void oracle_update_td(oracle_t* o, uint32_t B, const uint32_t* idx, const float* td, double eps, double alpha) {
+  for (uint32_t j = 0; j < B; ++j) {
+    if (!(idx[j] < o->size)) { o->status |= ORACLE_FLAG_BAD_INDEX; continue; }
+    if (!isfinite(td[j])) { o->status |= ORACLE_FLAG_BAD_PRIORITY; continue; }
+    const float v = (float)pow(fabs((double)td[j]) + eps, alpha);
+    if (!valid_priority(v)) { o->status |= ORACLE_FLAG_BAD_PRIORITY; continue; }
+    set_leaf(o, idx[j], v);
+    if (v > o->max_v) o->max_v = v;
+  }
+}
+
 /* Priority update in the paper's own form (Section V-A): the inputs are indices and changes
  * delta; every node on the path from the root down to the leaf gets the change added, level by
  * level.  Sequential batch order; duplicated indices simply add up.  Unlike the set-and-re-sum

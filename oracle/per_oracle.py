@@ -44,6 +44,7 @@ def _load():
     lib.oracle_destroy.argtypes = [vp]
     lib.oracle_update.argtypes = [vp, u32, vp, vp]
     lib.oracle_update_delta.argtypes = [vp, u32, vp, vp]
+    lib.oracle_update_td.argtypes = [vp, u32, vp, vp, C.c_double, C.c_double]
     lib.oracle_insert.restype = C.c_int
     lib.oracle_insert.argtypes = [vp, u32, vp, vp, vp]
     lib.oracle_sample.restype = C.c_int
@@ -137,6 +138,12 @@ class Oracle:
         assert idx.shape == prio.shape and idx.ndim == 1
         self._lib.oracle_update(self._h, idx.shape[0], _ptr(idx), _ptr(prio))
 
+    def update_td(self, idx: np.ndarray, td: np.ndarray, eps: float, alpha: float) -> None:
+        idx = np.ascontiguousarray(idx, dtype=np.uint32)
+        td = np.ascontiguousarray(td, dtype=np.float32)
+        assert idx.shape == td.shape and idx.ndim == 1
+        self._lib.oracle_update_td(self._h, idx.shape[0], _ptr(idx), _ptr(td), float(eps), float(alpha))
+
     def update_delta(self, idx: np.ndarray, delta: np.ndarray) -> None:
         idx = np.ascontiguousarray(idx, dtype=np.uint32)
         delta = np.ascontiguousarray(delta, dtype=np.float32)
@@ -219,6 +226,10 @@ class MultiOracle:
     def update(self, idx, prio):
         for t, o in enumerate(self.trees):
             o.update(idx[t], prio[t])
+
+    def update_td(self, idx, td, eps, alpha):
+        for t, o in enumerate(self.trees):
+            o.update_td(idx[t], td[t], eps, alpha)
 
     def update_delta(self, idx, delta):
         for t, o in enumerate(self.trees):

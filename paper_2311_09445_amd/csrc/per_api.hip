@@ -379,6 +379,27 @@ int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio,
   return hip_rc(e);
 }
 
+int per_update_td(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_td, double eps, double alpha,
+                  void* stream) {
+  int rc = check_update_args(p, B, d_idx, d_td);
+  if (rc != PER_OK || B == 0) return rc;
+  if (!(eps >= 0.0) || !isfinite(eps) || !(alpha >= 0.0) || !isfinite(alpha)) return PER_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  ClaimArgs claim{};
+  claim.B = B;
+  claim.size = (uint32_t)p->size;
+  claim.idx = d_idx;
+  claim.prio = d_td;
+  claim.from_td = 1;
+  claim.td_eps = eps;
+  claim.td_alpha = alpha;
+  rc = reserve_stamps(p, B, s, &claim.stamp_base);
+  if (rc != PER_OK) return rc;
+  hipError_t e = launch_update(p->g, p->tn, claim, s);
+  if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
+  return hip_rc(e);
+}
+
 int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_delta, void* stream) {
   int rc = check_update_args(p, B, d_idx, d_delta);
   if (rc != PER_OK || B == 0) return rc;

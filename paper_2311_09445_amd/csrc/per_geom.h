@@ -50,7 +50,9 @@ struct FieldTable {
 struct ClaimArgs {
   uint32_t B, size, stamp_base;
   const uint32_t* idx;     // [T][B]
-  const float* prio;       // [T][B]
+  const float* prio;       // [T][B] tree values, or temporal-difference errors when from_td is set
+  uint32_t from_td;        // value = (|prio| + td_eps)^td_alpha, fp64, rounded once
+  double td_eps, td_alpha;
 };
 
 // Where the claim phase of an update fused into a sampling call runs.

@@ -354,6 +354,9 @@ __device__ __forceinline__ void claim_element(const Geom& g, uint32_t t, uint32_
 }
 
 // Claims elements of the batch, strided over the job's workgroups.  Called by whole workgroups.
+// TD: the batch may hold temporal-difference errors to be turned into priorities first (only the
+// stand-alone claim kernel carries that code).
+template <bool TD = false>
 __device__ __forceinline__ void claim_job(const Geom& g, uint32_t t, const ClaimArgs& c, uint32_t job_block,
                                           uint32_t job_blocks) {
   if (job_block * blockDim.x >= c.B) return;   // nothing to do for this workgroup
@@ -362,14 +365,20 @@ __device__ __forceinline__ void claim_job(const Geom& g, uint32_t t, const Claim
   uint32_t flags = 0;
   for (uint32_t base = job_block * blockDim.x; base < c.B; base += job_blocks * blockDim.x) {
     const uint32_t j = base + threadIdx.x;
-    if (j < c.B)
-      claim_element(g, t, c.size, c.stamp_base, j, c.idx[(size_t)t * c.B + j], c.prio[(size_t)t * c.B + j], mx, flags);
+    if (j < c.B) {
+      float v = c.prio[(size_t)t * c.B + j];
+      if constexpr (TD) {
+        if (c.from_td)   // priority of a temporal-difference error; a non-finite error stays non-finite and is rejected
+          v = (float)pow(fabs((double)v) + c.td_eps, c.td_alpha);
+      }
+      claim_element(g, t, c.size, c.stamp_base, j, c.idx[(size_t)t * c.B + j], v, mx, flags);
+    }
   }
   raise_max(g, t, mx, max_seen);
   if (flags) atomicOr(&g.status[t], flags);
 }
 
-__global__ void k_update_claim(Geom g, ClaimArgs c) { claim_job(g, blockIdx.y, c, blockIdx.x, gridDim.x); }
+__global__ void k_update_claim(Geom g, ClaimArgs c) { claim_job<true>(g, blockIdx.y, c, blockIdx.x, gridDim.x); }
 
 // ---------------------------------------------------------------------------------
 // priority sampling

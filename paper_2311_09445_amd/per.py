@@ -21,7 +21,7 @@ FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_sample_gather",
     "per_sample_gather_update", "per_gather",
-    "per_update", "per_update_delta", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
+    "per_update", "per_update_td", "per_update_delta", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
 ]
@@ -70,6 +70,7 @@ def _lib():
         "per_gather": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update_delta": (C.c_int, [vp, u32, vp, vp, vp]),
+        "per_update_td": (C.c_int, [vp, u32, vp, vp, C.c_double, C.c_double, vp]),
         "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_read_level": (C.c_int, [vp, u32, u32, vp, C.POINTER(u64), vp]),
         "per_total": (C.c_int, [vp, vp, vp]),
@@ -249,6 +250,16 @@ class PrioritizedReplay:
             raise ValueError("idx and prio must have the same number of elements")
         rc = self.lib.per_update(self._h, B, _dptr(idx, torch.int32), _dptr(prio, torch.float32), self._stream())
         self._check(rc, "per_update")
+
+    def update_td(self, idx, td, eps: float = 1e-6, alpha: float = 0.6):
+        """per_update with the priorities computed on the device from temporal-difference errors."""
+        torch = self._torch
+        B = idx.numel() // self.T
+        if td.numel() != idx.numel():
+            raise ValueError("idx and td must have the same number of elements")
+        rc = self.lib.per_update_td(self._h, B, _dptr(idx, torch.int32), _dptr(td, torch.float32), float(eps),
+                                    float(alpha), self._stream())
+        self._check(rc, "per_update_td")
 
     def update_delta(self, idx, delta):
         """The paper's form of the update: add delta[j] to leaf idx[j] and to all its ancestors."""

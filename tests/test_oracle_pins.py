@@ -537,3 +537,44 @@ def test_delta_update_stays_within_the_rounding_bound_of_the_true_sums(K, N):
         mag[:N] = np.abs(leaves.astype(np.float64)) + 0.1 * 4 * steps
         bound = 2.0 ** -23 * (o.HB + steps * B) * mag.reshape(n, K ** h).sum(axis=1)
         assert np.all(np.abs(o.read_level(h).astype(np.float64) - want) <= bound), h
+
+
+# ---------------------------------------------------------------------------------------------
+# Update from temporal-difference errors: value = (|td| + eps)^alpha.  Pinned by closed forms
+# (alpha = 1, alpha = 0, exact squares with alpha = 0.5, td = 0) and by an independent evaluation
+# of the power (numpy's, in fp64) within one fp32 rounding; the tree below is the set form's.
+# ---------------------------------------------------------------------------------------------
+def test_td_update_closed_forms_and_validity():
+    N = 64
+    o = Oracle(4, N)
+    o.insert(N, None, np.ones(N, np.float32))
+    idx = np.arange(8, dtype=np.uint32)
+    td = np.array([-3.0, 0.25, 0.0, 16.0, -9.0, np.nan, np.inf, 2.0], np.float32)
+    o.update_td(idx, td, 0.0, 1.0)                       # alpha = 1, eps = 0: |td|
+    assert o.read_level(0)[:5].tolist() == [3.0, 0.25, 0.0, 16.0, 9.0]
+    assert o.read_level(0)[5] == 1.0 and o.read_level(0)[6] == 1.0 and o.status == FLAG_BAD_PRIORITY
+    assert o.max_priority == 16.0
+    o.update_td(idx[:5], td[:5], 0.0, 0.5)               # exact squares
+    assert o.read_level(0)[[3, 4]].tolist() == [4.0, 3.0]
+    o.update_td(idx[:5], td[:5], 0.5, 0.0)               # alpha = 0: 1 everywhere
+    assert o.read_level(0)[:5].tolist() == [1.0] * 5
+    o.update_td(np.array([2, 70], np.uint32), np.array([0.0, 1.0], np.float32), 1e-6, 0.6)   # td = 0: eps^alpha
+    assert abs(float(o.read_level(0)[2]) - (1e-6) ** 0.6) <= 1e-7 * (1e-6) ** 0.6
+    assert o.status == FLAG_BAD_PRIORITY | FLAG_BAD_INDEX
+    ref = Oracle(4, N)                                   # the tree is the set form's for the same leaf values
+    ref.insert(N, None, o.read_level(0).copy())
+    for h in range(o.H + 1):
+        assert o.read_level(h).tobytes() == ref.read_level(h).tobytes()
+
+
+def test_td_update_matches_an_independent_power_within_one_rounding():
+    rng = np.random.default_rng(11)
+    N, B = 5000, 3000
+    o = Oracle(16, N)
+    o.insert(N, None, np.ones(N, np.float32))
+    idx = rng.choice(N, B, replace=False).astype(np.uint32)
+    td = (rng.standard_normal(B) * 3).astype(np.float32)
+    o.update_td(idx, td, 1e-6, 0.6)
+    want = np.power(np.abs(td.astype(np.float64)) + 1e-6, 0.6)
+    got = o.read_level(0)[idx].astype(np.float64)
+    assert np.all(np.abs(got - want) <= 2.0 ** -23 * want)
