@@ -93,7 +93,7 @@ int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float
  *   ((float)i + u[i]) * (total / (float)B)
  * and returns the leaf whose half-open prefix interval contains it.  Leaves with value 0
  * and slots never written are never returned.
- *   d_u          : [T][B] uniforms in [0,1)
+ *   d_u          : [T][B] uniforms in [0,1); or NULL after per_set_rng: the call then draws its own
  *   d_out_idx    : [T][B]
  *   d_out_weight : [T][B] importance weights (size * P(i))^-beta divided by the batch
  *                  maximum, so the largest is 1; or NULL.  beta must be finite and >= 0.
@@ -183,6 +183,15 @@ uint64_t per_cursor(const per_t* p);     /* next ring slot                      
  * buffer.  After the caller has copied a saved arena back, this sets the host mirrors to the
  * values saved with it.  cursor < N, size <= N. */
 int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
+
+/* Uniforms drawn on the device ("uniformly generated random", Section II-A), for sampling calls that
+ * pass d_u == NULL.  The generator is counter-based (Philox4x32-10), so the uniforms are a pure
+ * function of (seed, number of the sampling call, tree, sample): sample i of tree t in call number c
+ * uses the counter (i, c low word, c high word, t) under the key (seed low, seed high), and its
+ * uniform is the first output word's top 24 bits times 2^-24.  next_call is the number the next such
+ * call gets (0 at the start; the saved value when resuming).  per_rng_calls returns the current one. */
+int per_set_rng(per_t* p, uint64_t seed, uint64_t next_call);
+uint64_t per_rng_calls(const per_t* p);
 
 /* Performance knobs; results never depend on them.
  *   "lds_budget_bytes" : upper tree levels are staged in LDS while they fit this many bytes

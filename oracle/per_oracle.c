@@ -215,6 +215,34 @@ int oracle_sample(oracle_t* o, uint32_t B, float beta, const float* u, uint32_t*
   return 0;
 }
 
+/* Uniforms from a counter-based generator instead of an input array ("uniformly generated random",
+ * Section II-A).  Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as
+ * 1, 2, 3", SC 2011): ten rounds of two 32x32->64 multiplications on a 4-word counter, the 2-word
+ * key bumped by Weyl constants between rounds.  Sample i of tree t in sampling call number `call`
+ * uses the counter (i, call low, call high, t) and the key (seed low, seed high); its uniform is
+ * the first output word, (x >> 8) * 2^-24. */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+void oracle_uniforms(uint64_t seed, uint64_t call, uint32_t tree, uint32_t B, float* u) {
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  for (uint32_t i = 0; i < B; ++i) {
+    const uint32_t ctr[4] = {i, (uint32_t)call, (uint32_t)(call >> 32), tree};
+    uint32_t x[4];
+    oracle_philox4x32_10(ctr, key, x);
+    u[i] = (float)(x[0] >> 8) * (1.0f / 16777216.0f);
+  }
+}
+
 /* Data Storage read: sampled_data = D_storage[sampled_indices] (Listing 2). */
 void oracle_gather(oracle_t* o, uint32_t B, const uint32_t* idx, void* const* field_dst) {
   for (uint32_t f = 0; f < o->n_fields; ++f) {

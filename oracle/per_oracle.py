@@ -50,6 +50,8 @@ def _load():
     lib.oracle_sample.restype = C.c_int
     lib.oracle_sample.argtypes = [vp, u32, f32, vp, vp, vp, vp]
     lib.oracle_gather.argtypes = [vp, u32, vp, vp]
+    lib.oracle_philox4x32_10.argtypes = [vp, vp, vp]
+    lib.oracle_uniforms.argtypes = [u64, u64, u32, u32, vp]
     lib.oracle_get_priority.argtypes = [vp, u32, vp, vp]
     lib.oracle_level_count.restype = u64
     lib.oracle_level_count.argtypes = [vp, u32]
@@ -69,6 +71,22 @@ def _load():
 
 def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    """One block of the counter-based generator (4 counter words, 2 key words -> 4 output words)."""
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    _load().oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def uniforms(seed: int, call: int, tree: int, B: int) -> np.ndarray:
+    """The uniforms of sampling call number `call` of tree `tree` under `seed`."""
+    u = np.empty(B, dtype=np.float32)
+    _load().oracle_uniforms(int(seed), int(call), int(tree), int(B), _ptr(u))
+    return u
 
 
 class Oracle:

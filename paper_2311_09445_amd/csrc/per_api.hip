@@ -22,6 +22,8 @@ struct per_buffer {
   uint64_t stamp_next;       // next unused last-writer stamp (stamps 1 .. 2^32-1)
   uint32_t weight_calls;     // number of per_sample calls that used the partial-minimum buffers
   uint32_t stale_hb;         // != 0: the last update left the heights above this one to their next reader
+  bool rng_on;               // per_set_rng was called: sampling calls without uniforms draw their own
+  uint64_t rng_seed, rng_calls;   // key of the generator; number of sampling calls that drew from it
   int device;
   Profiler prof;
 };
@@ -290,8 +292,8 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
                        const float* d_upd_prio, void* stream) {
   if (!p) return PER_EINVAL;
   if (B == 0) return PER_OK;
-  if (!d_u || !d_out_idx || misaligned(d_u, 4) || misaligned(d_out_idx, 4) || misaligned(d_out_weight, 4) ||
-      misaligned(d_out_prio, 4))
+  if ((!d_u && !p->rng_on) || !d_out_idx || misaligned(d_u, 4) || misaligned(d_out_idx, 4) ||
+      misaligned(d_out_weight, 4) || misaligned(d_out_prio, 4))
     return PER_EINVAL;
   if (!isfinite(beta) || beta < 0.0f) return PER_EINVAL;
   if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
@@ -324,9 +326,18 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
       else if (idx_apart) claim_mode = CLAIM_BLOCKS;
     }
   }
+  RngArgs rng{};
+  if (!d_u) {   // this call draws its own uniforms: call number rng_calls of the generator
+    rng.on = 1;
+    rng.seed_lo = (uint32_t)p->rng_seed;
+    rng.seed_hi = (uint32_t)(p->rng_seed >> 32);
+    rng.call_lo = (uint32_t)p->rng_calls;
+    rng.call_hi = (uint32_t)(p->rng_calls >> 32);
+    ++p->rng_calls;
+  }
   const uint32_t stale = p->stale_hb;
   p->stale_hb = 0;   // the sampling kernel rebuilds and stores the stale heights
-  hipError_t e = launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, d_out_idx, d_out_weight, d_out_prio,
+  hipError_t e = launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, rng, d_out_idx, d_out_weight, d_out_prio,
                                &p->weight_calls, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr, claim_mode, s);
   if (e == hipSuccess && upd_B) p->stale_hb = lazy_top_height(p->g, p->tn);   // the tree pass ran
   return hip_rc(e);
@@ -471,6 +482,16 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size) {
   p->stale_hb = lazy_top_height(p->g, p->tn);   // a saved arena may predate the rebuild of its top heights
   return PER_OK;
 }
+
+int per_set_rng(per_t* p, uint64_t seed, uint64_t next_call) {
+  if (!p) return PER_EINVAL;
+  p->rng_on = true;
+  p->rng_seed = seed;
+  p->rng_calls = next_call;
+  return PER_OK;
+}
+
+uint64_t per_rng_calls(const per_t* p) { return p ? p->rng_calls : 0; }
 
 int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!p || !name) return PER_EINVAL;

@@ -55,6 +55,13 @@ struct ClaimArgs {
   double td_eps, td_alpha;
 };
 
+// Source of the uniforms of a sampling call when the caller passes none: a counter-based generator,
+// counter (sample, call low, call high, tree), key (seed low, seed high).
+struct RngArgs {
+  uint32_t on;
+  uint32_t seed_lo, seed_hi, call_lo, call_hi;
+};
+
 // Where the claim phase of an update fused into a sampling call runs.
 enum ClaimMode {
   CLAIM_NONE = 0,
@@ -116,6 +123,7 @@ struct Tuning {
 hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32_t value, hipStream_t s);
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
+                         const RngArgs& rng,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
                          const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s);
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,

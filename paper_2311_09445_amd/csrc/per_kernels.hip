@@ -403,6 +403,29 @@ struct TopCopy {
 // group), parks them in LDS rows of K+4 floats (the pad keeps 16-byte row reads conflict-free),
 // and every lane then walks its own row.
 //
+// Uniform of sample i of tree t when the caller supplies none ("uniformly generated random",
+// Section II-A): Philox4x32-10 (Salmon et al., SC 2011), ten rounds of two 32x32->64
+// multiplications on the counter (i, call low, call high, t) with the key (seed low, seed high)
+// bumped by Weyl constants between rounds; first output word, top 24 bits, scaled by 2^-24.
+__device__ __forceinline__ float counter_uniform(const RngArgs& rng, uint32_t i, uint32_t t) {
+  uint32_t c0 = i, c1 = rng.call_lo, c2 = rng.call_hi, c3 = t;
+  uint32_t k0 = rng.seed_lo, k1 = rng.seed_hi;
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+  }
+  return (float)(c0 >> 8) * (1.0f / 16777216.0f);
+}
+
 // Chunk (IT*64 + lane) of the wave's 64*C 16-byte chunks, for IT = 0 .. C-1: fetched from the
 // group of the lane that owns it and parked in that lane's staging row.  Written as a recursion over
 // IT (not a loop over an array of registers) so that every fetch is issued before the first LDS store
@@ -434,7 +457,7 @@ template <int LOGK>
 __global__ void __launch_bounds__(1024)
 k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float* __restrict__ u,
          uint32_t* __restrict__ out_idx, float* __restrict__ out_prio, float* __restrict__ out_w,
-         uint32_t parity, int stale, uint32_t claim_blocks, ClaimArgs c, int claim_mode) {
+         uint32_t parity, int stale, uint32_t claim_blocks, ClaimArgs c, int claim_mode, RngArgs rng) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   constexpr int ROW = K + 4;                  // staging row, floats
@@ -463,7 +486,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   const size_t o = (size_t)t * B + s;
   // the root, this lane's uniform and the top copy are all fetched in the same trip
   float total = tc.root[(size_t)t * tc.root_stride];
-  const float u_s = u[o];
+  const float u_s = rng.on ? counter_uniform(rng, s, t) : u[o];
   // the new priority of this lane's sample and the running maximum, fetched in that same trip
   float upd_v = 0.0f;
   uint32_t max_seen = 0;
@@ -659,8 +682,8 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, uint32_t
 // the second kernel, the tree pass is a third).
 template <int LOGK>
 static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
-                                  const float* u, uint32_t* out_idx, float* out_w, float* out_prio,
-                                  uint32_t* weight_calls, uint32_t stale_hb, const FieldTable* rows,
+                                  const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w,
+                                  float* out_prio, uint32_t* weight_calls, uint32_t stale_hb, const FieldTable* rows,
                                   const ClaimArgs* claim, int claim_mode, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
   constexpr uint32_t kLdsCap = 128 * 1024;
@@ -727,7 +750,7 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   }
   PER_LAUNCH(KID_SAMPLE, k_sample<LOGK>, dim3(gx + claim_blocks, g.T), dim3(block), bytes, s, g, tc, B, size, beta, u,
              out_idx, out_prio, out_w, parity, stale, claim_blocks, claim_here ? *claim : ClaimArgs{},
-             claim_here ? claim_mode : (int)CLAIM_NONE);
+             claim_here ? claim_mode : (int)CLAIM_NONE, rng);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const bool finish_weights = out_w && gx > 1;
@@ -767,9 +790,9 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   }
 
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
-                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
+                         const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
                          const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s) {
-#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, out_idx, out_w, out_prio, weight_calls, stale_hb, rows, claim, claim_mode, s)
+#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, rng, out_idx, out_w, out_prio, weight_calls, stale_hb, rows, claim, claim_mode, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

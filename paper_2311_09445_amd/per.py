@@ -21,7 +21,7 @@ FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_sample_gather",
     "per_sample_gather_update", "per_gather",
-    "per_update", "per_update_td", "per_update_delta", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
+    "per_update", "per_update_td", "per_update_delta", "per_set_rng", "per_rng_calls", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
 ]
@@ -70,6 +70,8 @@ def _lib():
         "per_gather": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update_delta": (C.c_int, [vp, u32, vp, vp, vp]),
+        "per_set_rng": (C.c_int, [vp, C.c_uint64, C.c_uint64]),
+        "per_rng_calls": (C.c_uint64, [vp]),
         "per_update_td": (C.c_int, [vp, u32, vp, vp, C.c_double, C.c_double, vp]),
         "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_read_level": (C.c_int, [vp, u32, u32, vp, C.POINTER(u64), vp]),
@@ -197,16 +199,22 @@ class PrioritizedReplay:
         self._check(rc, "per_insert")
 
     def sample(self, u, beta: float = 0.4, want_weights: bool = True, want_prio: bool = True,
-               out_idx=None, out_weight=None, out_prio=None, rows_out=None, update=None):
+               out_idx=None, out_weight=None, out_prio=None, rows_out=None, update=None, B=None):
         """Returns (idx int32 [T,B] holding uint32 bit patterns, weights or None, prio or None).
+
+        ``u=None`` with ``B`` given: the call draws its own uniforms (after ``set_rng``).
 
         With ``rows_out`` (one [T,B,bytes] uint8 tensor or None per field) the sampled rows are
         gathered by the same call (per_sample_gather).  With ``update=(idx, prio)`` that priority
         update is applied after the sampling, still in the same call (per_sample_gather_update)."""
         torch = self._torch
-        B = u.numel() // self.T
-        if u.numel() != B * self.T:
-            raise ValueError("u must hold T*B values")
+        if u is None:
+            if B is None:
+                raise ValueError("without uniforms the batch size B must be given")
+        else:
+            B = u.numel() // self.T
+            if u.numel() != B * self.T:
+                raise ValueError("u must hold T*B values")
         shape = (self.T, B)
         if out_idx is None:
             out_idx = torch.empty(shape, dtype=torch.int32, device=self.device)
@@ -232,6 +240,13 @@ class PrioritizedReplay:
             rc = self.lib.per_sample_gather(*args, dst, self._stream())
         self._check(rc, "per_sample")
         return out_idx, (out_weight if want_weights else None), (out_prio if want_prio else None)
+
+    def set_rng(self, seed: int, next_call: int = 0):
+        """Sampling calls without uniforms draw them from a counter-based generator keyed by ``seed``."""
+        self._check(self.lib.per_set_rng(self._h, int(seed), int(next_call)), "per_set_rng")
+
+    def rng_calls(self) -> int:
+        return int(self.lib.per_rng_calls(self._h))
 
     def gather(self, idx, out=None):
         torch = self._torch

@@ -480,3 +480,35 @@ def test_update_from_td_errors(K, N, T, B):
             assert m.gpu.read_level(t, h).cpu().numpy().tobytes() == ref.read_level(0, h).tobytes(), (t, h)
     assert m.gpu.status() == m.cpu.status == FLAG_BAD_PRIORITY
     assert np.allclose(m.gpu.max_priority().cpu().numpy(), [o.max_priority for o in m.cpu.trees], rtol=2.0 ** -23)
+
+
+@pytest.mark.parametrize("K,N,T,B", [(16, 1 << 16, 3, 1000), (32, 1 << 20, 1, 65536), (2, 4096, 1, 64)])
+def test_sampling_with_uniforms_drawn_on_the_device(K, N, T, B):
+    """Sampling calls without a uniform array draw from the counter-based generator; the oracle side has its
+    own implementation of the same published generator, so indices, values and rows must match bit for bit."""
+    from oracle.per_oracle import uniforms
+    log(f"device uniforms K={K} N={N} T={T} B={B}")
+    rng = np.random.default_rng(K * B)
+    fb = (12,)
+    m = Mirror(K, N, T, fb)
+    m.insert(N, prio=wl._draw_priorities("lognormal_0_1", rng, (T, N)))
+    seed = 0xC0FFEE1234567890
+    with pytest.raises(Exception):
+        m.gpu.sample(None, 0.4, B=B)                       # no generator set up yet
+    m.gpu.set_rng(seed, next_call=(1 << 32) - 1)           # the call counter crosses a word boundary below
+    for step in range(3):
+        call = m.gpu.rng_calls()
+        u = np.stack([uniforms(seed, call, t, B) for t in range(T)])
+        rows = [torch.empty((T, B, b), dtype=torch.uint8, device="cuda") for b in fb]
+        upd = rng.random((T, B)).astype(np.float32)
+        out_idx = torch.empty((T, B), dtype=torch.int32, device="cuda")
+        gi, gw, gv = m.gpu.sample(None, 0.5, B=B, out_idx=out_idx, rows_out=rows,
+                                  update=(out_idx, dev(upd)) if step < 2 else None)
+        ci, cw, cv = m.cpu.sample(u, 0.5, True)
+        assert np.array_equal(idx_to_host(gi), ci) and gv.cpu().numpy().tobytes() == cv.tobytes()
+        np.testing.assert_allclose(gw.cpu().numpy(), cw, rtol=1e-6, atol=0)
+        m.gather(gi, ci, got=rows)
+        if step < 2:
+            m.cpu.update(ci, upd)
+        assert m.gpu.rng_calls() == call + 1
+    m.compare_tree()

@@ -578,3 +578,30 @@ def test_td_update_matches_an_independent_power_within_one_rounding():
     want = np.power(np.abs(td.astype(np.float64)) + 1e-6, 0.6)
     got = o.read_level(0)[idx].astype(np.float64)
     assert np.all(np.abs(got - want) <= 2.0 ** -23 * want)
+
+
+# ---------------------------------------------------------------------------------------------
+# Counter-based uniforms (Philox4x32-10): pinned by the generator's published known-answer vectors,
+# by the [0,1) range and 2^-24 grid of the uniforms, and by a chi-square test of their distribution.
+# ---------------------------------------------------------------------------------------------
+def test_philox_known_answers():
+    from oracle.per_oracle import philox4x32_10
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        assert philox4x32_10(w[0:4], w[4:6]).tolist() == w[6:10]
+
+
+def test_counter_based_uniforms():
+    from oracle.per_oracle import philox4x32_10, uniforms
+    u = uniforms(seed=0x123456789ABCDEF0, call=(7 << 32) | 5, tree=3, B=50000)
+    assert u.dtype == np.float32 and u.min() >= 0.0 and u.max() < 1.0
+    assert np.all(u * 16777216.0 == np.floor(u * 16777216.0))                 # on the 2^-24 grid
+    x = philox4x32_10([12345, 5, 7, 3], [0x9ABCDEF0, 0x12345678])             # counter (i, call lo, call hi, tree)
+    assert u[12345] == np.float32(x[0] >> 8) * np.float32(2.0 ** -24)
+    counts = np.bincount((u * 64).astype(int), minlength=64)
+    assert float(((counts - 50000 / 64) ** 2 / (50000 / 64)).sum()) < stats.chi2.ppf(0.9999, 63)
+    assert not np.array_equal(u, uniforms(0x123456789ABCDEF0, (7 << 32) | 6, 3, 50000))   # next call: new stream
+    assert not np.array_equal(u, uniforms(0x123456789ABCDEF0, (7 << 32) | 5, 4, 50000))   # other tree
