@@ -28,6 +28,11 @@
  *    the host, in which case no work was enqueued.  Conditions only the device
  *    can see set sticky bits (PER_FLAG_*) read by per_status.
  *  - A batch of size 0 is valid and enqueues nothing.
+ *  - The ring cursor, the filled size, the last-writer stamps of updates and a few similar
+ *    counters are kept on the host (they are pure functions of the call sequence) and enter the
+ *    kernels as arguments.  Calls may therefore be captured into a HIP graph, but the graph then
+ *    stands for exactly the captured calls: launch it once, on the buffer state it was captured
+ *    on, and capture again for the next stretch of calls.
  */
 #ifndef PER_H_
 #define PER_H_
