@@ -351,6 +351,41 @@ def main():
                       "kernels_us": {k: round(v[0] / max(1, v[1]) * 1e3, 2) for k, v in sorted(dk.items())},
                       "update_algorithmic_bytes": int(T * (8 * B + 4 * B + 8 * B * (H + 1)))}
         del g2
+    # ---------------------------------------------------------------- the same steps as one launch (small buffers)
+    # When a whole tree fits the LDS of a compute unit, per_run_steps runs the list of steps in one kernel,
+    # one workgroup per tree (the paper's on-chip tree and request stream, Section V-A "RM on FPGA").
+    step_stream = None
+    if fused_step and buf.run_steps_fits() and B <= 1024 and w.n_insert <= 1024:
+        restore()
+        o_idx = torch.empty((total_steps, T, B), dtype=torch.int32, device="cuda")
+        o_w = torch.empty((total_steps, T, B), dtype=torch.float32, device="cuda") if w.weights else None
+        o_v = torch.empty((total_steps, T, B), dtype=torch.float32, device="cuda")
+        o_rows = [torch.empty((total_steps, T, B, b), dtype=torch.uint8, device="cuda") for b in w.field_bytes]
+        d_beta = torch.tensor([inputs[s]["beta"] for s in range(total_steps)], dtype=torch.float32, device="cuda")
+        i_rows = None
+        if w.n_insert:
+            i_rows = [torch.stack([ins_rows[s][f] for s in range(total_steps)]) for f in range(len(w.field_bytes))]
+
+        def run(lo, hi):
+            buf.run_steps(d_u[lo:hi], d_beta[lo:hi], o_idx[lo:hi], None if o_w is None else o_w[lo:hi], o_v[lo:hi],
+                          [r[lo:hi] for r in o_rows], upd_prio=d_prio[lo:hi], upd_idx=d_upd_idx[lo:hi],
+                          n_insert=w.n_insert, ins_rows=None if i_rows is None else [r[lo:hi] for r in i_rows])
+
+        run(0, warmup)
+        torch.cuda.synchronize()
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record(stream)
+        run(warmup, total_steps)
+        s1.record(stream)
+        torch.cuda.synchronize()
+        ms_stream = s0.elapsed_time(s1) / steps
+        assert np.array_equal(o_idx.cpu().numpy().view(np.uint32), rec_idx), "step kernel diverged from the separate calls"
+        assert buf.total().cpu().numpy().tobytes() == final_root.tobytes(), "step kernel ended in a different state"
+        step_stream = {"ms_per_step": round(ms_stream, 5), "value": round(T * B / (ms_stream * 1e-3), 1),
+                       "unit": "transitions/s", "launches": 1, "steps_per_launch": steps,
+                       "call": "per_run_steps (tree held in LDS, one workgroup per tree)"}
+        del o_idx, o_w, o_v, o_rows
+
     # what a plain streaming device copy reaches on this GPU in this run (read + written bytes per second)
     src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
@@ -458,6 +493,7 @@ def main():
         "cpu_baseline": cpu,
         "cpu_workers_baseline": cpu_workers,
         "paper_update_form": delta_form,
+        "step_stream": step_stream,
         "step_algorithmic_bytes": int(a_step),
         "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
         "phase_algorithmic_bytes": {"sample": int(a_sample), "gather_and_weights": int(a_gather), "update": int(a_update)},

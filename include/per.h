@@ -161,6 +161,40 @@ int per_update_td(per_t* p, uint32_t B, const uint32_t* d_idx /*[T][B]*/, const 
 int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx /*[T][B]*/, const float* d_delta /*[T][B]*/,
                      void* stream);
 
+/* A list of steps in one launch, for buffers small enough that every height of a tree fits the LDS
+ * of one compute unit (about 150 KB: e.g. 32768 leaves at fanout 16).  The paper keeps the sum tree of
+ * its Replay Manager in on-chip memory and lets a kernel that is started once work through a stream
+ * of requests (Section V-A, "RM on FPGA"); here one workgroup per tree loads the tree, runs step
+ * after step against the LDS copy and stores it back at the end.  Step s is, in this order,
+ *   per_insert(n_insert rows)  ->  per_sample(B)  ->  per_gather  ->  per_update(B),
+ * with the same results as those calls.  All arrays carry a leading step dimension:
+ *   d_ins_rows   : [n_fields] device pointers, each [steps][T][n_insert][field_bytes]; NULL entries or a
+ *                  NULL table skip the payload
+ *   d_ins_prio   : [steps][T][n_insert] tree values of the new rows, or NULL: the running maximum
+ *   d_u, d_beta  : [steps][T][B] uniforms in [0,1); [steps] exponents of the importance weights
+ *   d_out_idx    : [steps][T][B];  d_out_weight, d_out_prio: same shape, or NULL
+ *   d_rows_out   : [n_fields] device pointers, each [steps][T][B][field_bytes], or NULL
+ *   d_upd_prio   : [steps][T][B] new tree values, or NULL: no update
+ *   d_upd_idx    : [steps][T][B] indices to update; NULL with d_upd_prio given: step s updates the batch
+ *                  it has just sampled
+ * n_insert <= 1024 (0: no insertion), 1 <= B <= 1024.  PER_ERANGE when the tree does not fit
+ * (per_run_steps_fits tells beforehand) or a count is out of range. */
+typedef struct {
+  uint32_t struct_size;            /* sizeof(per_stream_io) */
+  const void* const* d_ins_rows;
+  const float* d_ins_prio;
+  const float* d_u;
+  const float* d_beta;
+  uint32_t* d_out_idx;
+  float* d_out_weight;
+  float* d_out_prio;
+  void* const* d_rows_out;
+  const uint32_t* d_upd_idx;
+  const float* d_upd_prio;
+} per_stream_io;
+int per_run_steps(per_t* p, uint32_t n_steps, uint32_t n_insert, uint32_t B, const per_stream_io* io, void* stream);
+int per_run_steps_fits(const per_t* p);   /* 1: the trees of this buffer fit, 0: they do not */
+
 /* Priority retrieval (Section V-A): d_out[t][i] = leaf d_idx[t][i]. */
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream);
 

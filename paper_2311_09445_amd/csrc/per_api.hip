@@ -420,6 +420,45 @@ int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d
   return hip_rc(e);
 }
 
+int per_run_steps_fits(const per_t* p) { return p && stream_tree_floats(p->g, nullptr) ? 1 : 0; }
+
+int per_run_steps(per_t* p, uint32_t n_steps, uint32_t n_insert, uint32_t B, const per_stream_io* io, void* stream) {
+  if (!p || !io || io->struct_size != sizeof(per_stream_io)) return PER_EINVAL;
+  if (n_steps == 0) return PER_OK;
+  if (B == 0 || B > 1024 || n_insert > 1024 || n_insert > p->cfg.capacity) return PER_ERANGE;
+  if (!stream_tree_floats(p->g, nullptr)) return PER_ERANGE;   // the tree does not fit the LDS of a compute unit
+  if (!io->d_u || !io->d_beta || !io->d_out_idx || misaligned(io->d_u, 4) || misaligned(io->d_beta, 4) ||
+      misaligned(io->d_out_idx, 4) || misaligned(io->d_out_weight, 4) || misaligned(io->d_out_prio, 4) ||
+      misaligned(io->d_upd_idx, 4) || misaligned(io->d_upd_prio, 4) || misaligned(io->d_ins_prio, 4))
+    return PER_EINVAL;
+  if (io->d_upd_idx && !io->d_upd_prio) return PER_EINVAL;
+  if (p->size == 0 && n_insert == 0) return PER_EEMPTY;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  StreamArgs a{};
+  a.n_steps = n_steps;
+  a.n_insert = n_insert;
+  a.B = B;
+  a.cursor = (uint32_t)p->cursor;
+  a.size = (uint32_t)p->size;
+  a.upd_is_sampled = io->d_upd_prio && !io->d_upd_idx ? 1u : 0u;
+  a.u = io->d_u;
+  a.beta = io->d_beta;
+  a.out_idx = io->d_out_idx;
+  a.out_w = io->d_out_weight;
+  a.out_prio = io->d_out_prio;
+  a.upd_idx = io->d_upd_idx;
+  a.upd_prio = io->d_upd_prio;
+  a.ins_prio = io->d_ins_prio;
+  if (n_insert) (void)fill_fields(p, const_cast<void* const*>(reinterpret_cast<const void* const*>(io->d_ins_rows)), &a.ins);
+  (void)fill_fields(p, io->d_rows_out, &a.rows);
+  hipError_t e = ensure_top(p, s);   // the kernel loads whole heights from memory
+  if (e == hipSuccess) e = launch_run_steps(p->g, p->tn, a, s);
+  const uint64_t N = p->cfg.capacity, added = (uint64_t)n_steps * n_insert;
+  p->cursor = (p->cursor + added) % N;
+  p->size = p->size + added > N ? N : p->size + added;
+  return hip_rc(e);
+}
+
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream) {
   if (!p) return PER_EINVAL;
   if (n == 0) return PER_OK;

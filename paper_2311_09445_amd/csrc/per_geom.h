@@ -82,6 +82,23 @@ struct FinishArgs {
   ClaimArgs claim;
 };
 
+// A list of steps run by one workgroup per tree on an LDS copy of the tree (see k_run_steps).
+struct StreamArgs {
+  uint32_t n_steps, n_insert, B;
+  uint32_t cursor, size;            // ring state before the first step
+  uint32_t upd_is_sampled;          // a step updates the batch it has just sampled
+  const float* u;                   // [steps][T][B]
+  const float* beta;                // [steps]
+  uint32_t* out_idx;                // [steps][T][B]
+  float* out_w;                     // [steps][T][B] or null
+  float* out_prio;                  // [steps][T][B] or null
+  const uint32_t* upd_idx;          // [steps][T][B] (unused when upd_is_sampled)
+  const float* upd_prio;            // [steps][T][B] or null: no update
+  const float* ins_prio;            // [steps][T][n_insert] or null: running maximum
+  FieldTable ins, rows;             // io arrays hold [steps][T][n][bytes]; io all null: nothing to move
+  uint32_t off[kMaxHeight + 2];     // where height h starts in LDS (floats); off[H + 1] = all floats
+};
+
 // Workgroup ranges of the jobs sharing one launch: [first[j], first[j+1]) for job j, where job 0 is the
 // weights, job 1 the claim and job 2 + f the rows of payload field f.
 struct JobRanges {
@@ -94,7 +111,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_UPDATE_DELTA, KID_GET_PRIORITY,
-  KID_INSERT_SMALL, KID_COUNT
+  KID_INSERT_SMALL, KID_RUN_STEPS, KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -141,6 +158,8 @@ uint32_t lazy_top_height(const Geom& g, const Tuning& tn);
 hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s);
 hipError_t launch_update_delta(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
                                const float* delta, hipStream_t s);
+uint32_t stream_tree_floats(const Geom& g, uint32_t* off);
+hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s);
 hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
 hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s);
 hipError_t launch_clear_status(const Geom& g, hipStream_t s);

@@ -21,7 +21,8 @@ FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_sample_gather",
     "per_sample_gather_update", "per_gather",
-    "per_update", "per_update_td", "per_update_delta", "per_set_rng", "per_rng_calls", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
+    "per_update", "per_update_td", "per_update_delta", "per_set_rng", "per_rng_calls", "per_run_steps",
+    "per_run_steps_fits", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
 ]
@@ -36,6 +37,22 @@ class PerConfig(C.Structure):
         ("n_fields", C.c_uint32),
         ("field_bytes", C.c_uint32 * MAX_FIELDS),
         ("init_max_priority", C.c_float),
+    ]
+
+
+class PerStreamIO(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("d_ins_rows", C.c_void_p),
+        ("d_ins_prio", C.c_void_p),
+        ("d_u", C.c_void_p),
+        ("d_beta", C.c_void_p),
+        ("d_out_idx", C.c_void_p),
+        ("d_out_weight", C.c_void_p),
+        ("d_out_prio", C.c_void_p),
+        ("d_rows_out", C.c_void_p),
+        ("d_upd_idx", C.c_void_p),
+        ("d_upd_prio", C.c_void_p),
     ]
 
 
@@ -72,6 +89,8 @@ def _lib():
         "per_update_delta": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_set_rng": (C.c_int, [vp, C.c_uint64, C.c_uint64]),
         "per_rng_calls": (C.c_uint64, [vp]),
+        "per_run_steps": (C.c_int, [vp, u32, u32, u32, C.POINTER(PerStreamIO), vp]),
+        "per_run_steps_fits": (C.c_int, [vp]),
         "per_update_td": (C.c_int, [vp, u32, vp, vp, C.c_double, C.c_double, vp]),
         "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_read_level": (C.c_int, [vp, u32, u32, vp, C.POINTER(u64), vp]),
@@ -240,6 +259,61 @@ class PrioritizedReplay:
             rc = self.lib.per_sample_gather(*args, dst, self._stream())
         self._check(rc, "per_sample")
         return out_idx, (out_weight if want_weights else None), (out_prio if want_prio else None)
+
+    def run_steps_fits(self) -> bool:
+        return bool(self.lib.per_run_steps_fits(self._h))
+
+    def run_steps(self, u, beta, out_idx, out_weight=None, out_prio=None, rows_out=None, upd_prio=None, upd_idx=None,
+                  n_insert: int = 0, ins_rows=None, ins_prio=None):
+        """A list of steps (insert -> sample -> gather -> update) in one launch on an LDS copy of the tree.
+        ``u``: [steps, T, B]; ``beta``: [steps] device tensor; the other arrays as in per.h (leading step
+        dimension).  ``upd_prio`` without ``upd_idx`` updates, in every step, the batch just sampled."""
+        torch = self._torch
+        steps, B = int(u.shape[0]), int(u.shape[-1])
+        if u.numel() != steps * self.T * B or beta.numel() != steps:
+            raise ValueError("u must be [steps, T, B] and beta [steps]")
+        for name, x in (("out_idx", out_idx), ("out_weight", out_weight), ("out_prio", out_prio),
+                        ("upd_prio", upd_prio), ("upd_idx", upd_idx)):
+            if x is not None and x.numel() != u.numel():
+                raise ValueError(f"{name} must hold steps*T*B values")
+        if ins_prio is not None and ins_prio.numel() != steps * self.T * n_insert:
+            raise ValueError("ins_prio must hold steps*T*n_insert values")
+        io = PerStreamIO()
+        io.struct_size = C.sizeof(PerStreamIO)
+        keep = []
+
+        def table(tensors, rows_per_tree):
+            if tensors is None:
+                return None
+            if len(tensors) != len(self.field_bytes):
+                raise ValueError("one tensor (or None) per payload field is required")
+            arr = (C.c_void_p * max(1, len(tensors)))()
+            for f, t in enumerate(tensors):
+                if t is None:
+                    arr[f] = None
+                    continue
+                if t.numel() * t.element_size() != steps * self.T * rows_per_tree * self.field_bytes[f]:
+                    raise ValueError(f"field {f}: expected steps*T*rows*{self.field_bytes[f]} bytes")
+                arr[f] = _dptr(t).value
+            keep.append(arr)
+            return C.cast(arr, C.c_void_p)
+
+        def ptr(x, dtype):
+            p = _dptr(x, dtype)
+            return None if p is None else p.value
+
+        io.d_ins_rows = table(ins_rows, n_insert)
+        io.d_ins_prio = ptr(ins_prio, torch.float32)
+        io.d_u = ptr(u, torch.float32)
+        io.d_beta = ptr(beta, torch.float32)
+        io.d_out_idx = ptr(out_idx, torch.int32)
+        io.d_out_weight = ptr(out_weight, torch.float32)
+        io.d_out_prio = ptr(out_prio, torch.float32)
+        io.d_rows_out = table(rows_out, B)
+        io.d_upd_idx = ptr(upd_idx, torch.int32)
+        io.d_upd_prio = ptr(upd_prio, torch.float32)
+        rc = self.lib.per_run_steps(self._h, steps, int(n_insert), B, C.byref(io), self._stream())
+        self._check(rc, "per_run_steps")
 
     def set_rng(self, seed: int, next_call: int = 0):
         """Sampling calls without uniforms draw them from a counter-based generator keyed by ``seed``."""

@@ -512,3 +512,78 @@ def test_sampling_with_uniforms_drawn_on_the_device(K, N, T, B):
             m.cpu.update(ci, upd)
         assert m.gpu.rng_calls() == call + 1
     m.compare_tree()
+
+
+# ---------------------------------------------------------------------------------------------
+# per_run_steps: a list of steps in one launch on an LDS copy of the tree.  Same results as the calls.
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K,N,T,B,n_ins,fb,explicit", [
+    (2, 4096, 1, 64, 4, (16, 4, 4, 16, 1), False), (16, 30000, 2, 512, 16, (12,), True),
+    (32, 32768, 1, 1024, 0, (128,), False), (4, 1000, 3, 100, 7, (), True), (64, 20000, 1, 33, 1, (5,), False)])
+@pytest.mark.parametrize("own_batch", [True, False])
+def test_run_steps_equals_the_separate_calls(K, N, T, B, n_ins, fb, explicit, own_batch):
+    log(f"run_steps K={K} N={N} T={T} B={B} n_ins={n_ins} own_batch={own_batch}")
+    rng = np.random.default_rng(K * N + B + n_ins)
+    m = Mirror(K, N, T, fb)
+    assert m.gpu.run_steps_fits()
+    m.insert(N - 10, prio=wl._draw_priorities("exponential_1", rng, (T, N - 10)), chunk=5000)   # the ring wraps below
+    steps = 6
+    u = wl.uniform01(rng, (steps, T, B))
+    beta = np.linspace(0.4, 1.0, steps).astype(np.float32)
+    upd_prio = (rng.random((steps, T, B)) * 4).astype(np.float32)
+    upd_prio[2, :, ::7] = np.float32("nan")
+    upd_prio[3, :, 1::9] = -1.0
+    upd_idx = rng.integers(0, N, (steps, T, B)).astype(np.uint32)
+    upd_idx[:, :, 1::2] = upd_idx[:, :, 0::2][:, :, :upd_idx[:, :, 1::2].shape[2]]   # every other element repeats its neighbour
+    upd_idx[4, :, 0] = N + 3                                                        # out of range
+    counters = m.counter + np.arange(steps * n_ins).reshape(steps, n_ins) if n_ins else None
+    ins_rows = [np.stack([np.stack([wl.row_bytes(t, counters[s], f, b) for t in range(T)]) for s in range(steps)])
+                for f, b in enumerate(fb)] if n_ins and fb else None
+    ins_prio = (rng.random((steps, T, n_ins)) * 6).astype(np.float32) if explicit and n_ins else None
+    if ins_prio is not None:
+        ins_prio[1, :, 0] = np.float32("inf")
+    out_idx = torch.empty((steps, T, B), dtype=torch.int32, device="cuda")
+    out_w = torch.empty((steps, T, B), dtype=torch.float32, device="cuda")
+    out_v = torch.empty((steps, T, B), dtype=torch.float32, device="cuda")
+    rows_out = [torch.empty((steps, T, B, b), dtype=torch.uint8, device="cuda") for b in fb] if fb else None
+    m.gpu.run_steps(dev(u), dev(beta), out_idx, out_w, out_v, rows_out, upd_prio=dev(upd_prio),
+                    upd_idx=None if own_batch else idx_to_dev(upd_idx), n_insert=n_ins,
+                    ins_rows=[dev(r) for r in ins_rows] if ins_rows else None,
+                    ins_prio=None if ins_prio is None else dev(ins_prio))
+    gi = idx_to_host(out_idx)
+    gw, gv = out_w.cpu().numpy(), out_v.cpu().numpy()
+    grows = [r.cpu().numpy() for r in rows_out] if fb else []
+    for s in range(steps):
+        if n_ins:
+            m.cpu.insert(n_ins, [r[s] for r in ins_rows] if ins_rows else None, None if ins_prio is None else ins_prio[s])
+        ci, cw, cv = m.cpu.sample(u[s], float(beta[s]), True)
+        assert np.array_equal(gi[s], ci), f"step {s}: sampled indices"
+        assert gv[s].tobytes() == cv.tobytes(), f"step {s}: sampled values"
+        np.testing.assert_allclose(gw[s], cw, rtol=1e-6, atol=0)
+        for f, want in enumerate(m.cpu.gather(ci)):
+            assert np.array_equal(grows[f][s], want), f"step {s}: rows of field {f}"
+        m.cpu.update(ci if own_batch else upd_idx[s], upd_prio[s])
+    m.counter += steps * n_ins
+    m.compare_tree()
+    m.compare_status()
+    assert m.gpu.cursor == m.cpu.trees[0].cursor and m.gpu.size == m.cpu.trees[0].size
+    if not fb:   # the separate calls carry on from the state the step kernel left
+        m.update(rng.integers(0, N, (T, 50)).astype(np.uint32), rng.random((T, 50)).astype(np.float32))
+        m.sample(wl.uniform01(rng, (T, B)), 0.4)
+        m.compare_tree()
+
+
+def test_run_steps_limits_and_empty_tree():
+    p = PrioritizedReplay(16, 1 << 20)
+    assert not p.run_steps_fits()
+    z = torch.zeros((1, 1, 8), device="cuda")
+    with pytest.raises(PerError) as e:
+        p.run_steps(z, torch.zeros(1, device="cuda"), torch.zeros((1, 1, 8), dtype=torch.int32, device="cuda"))
+    assert e.value.code == ERANGE
+    q = PrioritizedReplay(4, 256)
+    q.insert(256, None, torch.zeros((1, 256), device="cuda"))          # nothing can be sampled
+    oi = torch.zeros((2, 1, 8), dtype=torch.int32, device="cuda")
+    ow = torch.ones((2, 1, 8), device="cuda")
+    q.run_steps(torch.zeros((2, 1, 8), device="cuda"), torch.zeros(2, device="cuda"), oi, ow)
+    assert np.all(idx_to_host(oi) == 0xFFFFFFFF) and float(ow.abs().max()) == 0.0
+    assert q.status() == FLAG_ZERO_TOTAL
