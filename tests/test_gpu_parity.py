@@ -587,3 +587,76 @@ def test_run_steps_limits_and_empty_tree():
     q.run_steps(torch.zeros((2, 1, 8), device="cuda"), torch.zeros(2, device="cuda"), oi, ow)
     assert np.all(idx_to_host(oi) == 0xFFFFFFFF) and float(ow.abs().max()) == 0.0
     assert q.status() == FLAG_ZERO_TOTAL
+
+
+@pytest.mark.parametrize("K,N,T,seed", [(16, 20000, 2, 1), (2, 3000, 1, 2), (32, 32768, 1, 3), (4, 25000, 3, 4)])
+def test_interleaved_operations(K, N, T, seed):
+    """Every entry point in random order on one buffer, the tree compared with the oracle after each call.  All
+    values are small multiples of 2^-6, so every fp32 sum is exact and the delta-form update (which is
+    order-dependent in general) stays bit-comparable too; what is tested here is the hand-over of state
+    between the calls (stale top heights, stamps, dirty bits, ring position, LDS copy of the step kernel)."""
+    from oracle.per_oracle import uniforms
+    log(f"interleaved K={K} N={N} T={T} seed={seed}")
+    rng = np.random.default_rng(seed)
+    scale = np.float32(2.0 ** -6)
+    top = max(8, (1 << 22) // N)
+
+    def values(shape, lo=0):
+        return (rng.integers(lo, top, shape) * scale).astype(np.float32)
+
+    fb = (8, 3)
+    m = Mirror(K, N, T, fb)
+    m.insert(N - 50, prio=values((T, N - 50), 1), chunk=6000)
+    m.gpu.set_rng(99)
+    fits = m.gpu.run_steps_fits()
+    ops = ["insert_small", "insert_large", "sample", "fused_own", "fused_other", "update", "delta", "rng", "retrieve"]
+    if fits:
+        ops.append("stream")
+    for it in range(28):
+        op = ops[int(rng.integers(0, len(ops)))]
+        B = int(rng.choice([7, 64, 300, 1024]))
+        if op == "insert_small":
+            n = int(rng.integers(1, 40))
+            m.insert(n, prio=None if it % 2 else values((T, n)))
+        elif op == "insert_large":
+            n = int(rng.integers(4097, 6000)) if N > 8000 else int(rng.integers(100, N // 2))
+            m.insert(n, prio=values((T, n), 1))
+        elif op == "sample":
+            gi, ci = m.sample(wl.uniform01(rng, (T, B)), 0.5, fused_rows=bool(it % 2))
+        elif op == "fused_own":
+            m.sample_gather_update(wl.uniform01(rng, (T, B)), 0.5, True, values((T, B)), alias=True)
+        elif op == "fused_other":
+            gi, ci = m.sample(wl.uniform01(rng, (T, B)), 0.5)
+            m.sample_gather_update(wl.uniform01(rng, (T, B)), 0.5, bool(it % 2), values((T, B)),
+                                   dup={"dup_dst": np.stack([rng.integers(0, B, B // 4 + 1) for _ in range(T)]),
+                                        "dup_src": np.stack([rng.integers(0, B, B // 4 + 1) for _ in range(T)])})
+        elif op == "update":
+            m.update(rng.integers(0, N, (T, B)).astype(np.uint32), values((T, B)))
+        elif op == "delta":
+            idx = np.stack([rng.choice(N, B, replace=False) for _ in range(T)]).astype(np.uint32)
+            old = np.stack([o.get_priority(idx[t]) for t, o in enumerate(m.cpu.trees)])
+            delta = values((T, B)) - old                      # exact: both are multiples of 2^-6
+            m.gpu.update_delta(idx_to_dev(idx), dev(delta))
+            m.cpu.update_delta(idx, delta)
+        elif op == "rng":
+            call = m.gpu.rng_calls()
+            u = np.stack([uniforms(99, call, t, B) for t in range(T)])
+            gi, _, gv = m.gpu.sample(None, 0.4, B=B, want_weights=False)
+            ci, _, cv = m.cpu.sample(u, 0.4, False)
+            assert np.array_equal(idx_to_host(gi), ci) and gv.cpu().numpy().tobytes() == cv.tobytes()
+        elif op == "retrieve":
+            idx = rng.integers(0, N, (T, B)).astype(np.uint32)
+            got = m.gpu.get_priority(idx_to_dev(idx)).cpu().numpy()
+            assert got.tobytes() == m.cpu.get_priority(idx).tobytes()
+        elif op == "stream":
+            steps, Bs = 3, min(B, 512)
+            u = wl.uniform01(rng, (steps, T, Bs))
+            up = values((steps, T, Bs))
+            oi = torch.empty((steps, T, Bs), dtype=torch.int32, device="cuda")
+            m.gpu.run_steps(dev(u), dev(np.full(steps, 0.4, np.float32)), oi, upd_prio=dev(up))
+            for s in range(steps):
+                ci, _, _ = m.cpu.sample(u[s], 0.4, False)
+                assert np.array_equal(idx_to_host(oi[s]), ci), f"stream step {s}"
+                m.cpu.update(ci, up[s])
+        m.compare_tree()
+    m.compare_status()
