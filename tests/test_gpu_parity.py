@@ -660,3 +660,48 @@ def test_interleaved_operations(K, N, T, seed):
                 m.cpu.update(ci, up[s])
         m.compare_tree()
     m.compare_status()
+
+
+@pytest.mark.parametrize("K", [32, 2])
+def test_largest_capacity(K):
+    """N = 2^31 leaves per tree, the most the interface accepts (8 GiB of leaves, 16 GiB of stamps; with K = 2
+    the deepest tree, 31 heights).  No oracle of that size: every leaf is 1 and later 1 + a multiple of 256,
+    so every fp32 sum on the way to the root is exact and the results have closed forms (Eq. 1 on a
+    uniform tree: sample i of B with u = 0.5 is leaf (i + 0.5) * N / B)."""
+    N, B = 1 << 31, 4096
+    log(f"largest capacity K={K}")
+    p = PrioritizedReplay(K, N)
+    chunk = 1 << 26
+    ones = torch.ones((1, chunk), device="cuda")
+    for _ in range(N // chunk):
+        p.insert(chunk, None, ones)
+    del ones
+    assert p.size == N and p.cursor == 0
+    assert float(p.total().cpu()[0]) == float(N)
+    half = torch.full((1, B), 0.5, device="cuda")
+    idx, w, v = p.sample(half, 0.4)
+    want = (np.arange(B, dtype=np.int64) << 19) + (1 << 18)
+    assert np.array_equal(idx_to_host(idx)[0].astype(np.int64), want)
+    assert np.all(w.cpu().numpy() == 1.0) and np.all(v.cpu().numpy() == 1.0)
+    # updates at both ends and in the middle; changes are multiples of 256, so the root stays exact
+    ui = np.array([[0, 12345678, N - 1, (1 << 30) + 7, N - 1]], dtype=np.uint32)      # the last index twice: last writer
+    uv = np.array([[257.0, 513.0, 99.0, 769.0, 1025.0]], dtype=np.float32)
+    p.update(idx_to_dev(ui), dev(uv))
+    assert float(p.total().cpu()[0]) == float(N) + 256 + 512 + 768 + 1024
+    got = p.get_priority(idx_to_dev(ui)).cpu().numpy()[0]
+    assert got.tolist() == [257.0, 513.0, 1025.0, 769.0, 1025.0]
+    assert float(p.max_priority().cpu()[0]) == 1025.0
+    changed = {0: 256, 12345678: 512, N - 1: 1024, (1 << 30) + 7: 768}               # leaf -> change of its value
+    for h in (1, p.H - 1):                                                           # first and last node of two heights
+        lvl = p.read_level(0, h).cpu().numpy()
+        span = K ** h
+        for node in (0, lvl.size - 1):
+            extra = sum(d for leaf, d in changed.items() if leaf // span == node)
+            assert float(lvl[node]) == float(span + extra), (h, node)
+    # one whole step on the sampled batch itself with unchanged values: nothing may move
+    out_idx = torch.empty((1, B), dtype=torch.int32, device="cuda")
+    u = torch.rand((1, B), device="cuda")
+    i2, w2, v2 = p.sample(u, 0.4, out_idx=out_idx)
+    i3, w3, v3 = p.sample(u, 0.4, out_idx=out_idx, update=(out_idx, v2))
+    assert torch.equal(i2.cpu(), i3.cpu()) and int(idx_to_host(i3).max()) < N
+    assert float(p.total().cpu()[0]) == float(N) + 2560 and p.status() == 0
