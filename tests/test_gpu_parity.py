@@ -705,3 +705,19 @@ def test_largest_capacity(K):
     i3, w3, v3 = p.sample(u, 0.4, out_idx=out_idx, update=(out_idx, v2))
     assert torch.equal(i2.cpu(), i3.cpu()) and int(idx_to_host(i3).max()) < N
     assert float(p.total().cpu()[0]) == float(N) + 2560 and p.status() == 0
+
+
+def test_large_batch():
+    """A batch of 2^22 samples and updates on 2^24 leaves (64 times the headline batch): grids, job ranges and the
+    stamp counter far from their usual sizes; element by element against the oracle."""
+    K, N, B = 32, 1 << 24, 1 << 22
+    log("large batch")
+    rng = np.random.default_rng(77)
+    m = Mirror(K, N, 1, ())
+    m.insert(N, prio=wl._draw_priorities("pareto_1.5", rng, (1, N)), with_rows=False, chunk=1 << 22)
+    gi, ci = m.sample(wl.uniform01(rng, (1, B)), 0.4)
+    m.update(ci, rng.random((1, B)).astype(np.float32))
+    m.compare_tree()
+    m.sample_gather_update(wl.uniform01(rng, (1, B)), 0.7, True, rng.random((1, B)).astype(np.float32), alias=True)
+    m.compare_tree()
+    m.compare_status()
