@@ -1,0 +1,163 @@
+// Device helpers shared by the kernels: fanout constants, group sums, the walk inside a child group, wave reductions, the running maximum, importance weights.
+// Part of per_kernels.hip (included inside namespace per, in the order given there); not a stand-alone header.
+
+// ---------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------
+template <int LOGK>
+struct Fan {
+  static constexpr int K = 1 << LOGK;
+  static constexpr int LPS = K >= 4 ? K / 4 : 1;          // lanes per child group
+  static constexpr int LOGLPS = LOGK >= 2 ? LOGK - 2 : 0;
+};
+
+// Workgroup barrier for phases that hand data over through LDS only.  Unlike __syncthreads() it does
+// not wait for this wave's outstanding global stores (which nothing in the workgroup reads back).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ bool valid_priority(float v) {
+  return v >= 0.0f && v <= 3.402823466e38f;   // finite and >= 0 (false for NaN); -0.0f passes
+}
+
+__device__ __forceinline__ uint32_t shr64(uint32_t x, uint32_t sh) { return (uint32_t)((uint64_t)x >> sh); }
+
+// Sum of the K children starting at grp; q = lane position inside the LPS-lane group.
+// Every lane of the group returns the same value.
+template <int LOGK>
+__device__ __forceinline__ float group_sum(const float* grp, unsigned q) {
+  if constexpr (LOGK == 1) {
+    const float2 c = *reinterpret_cast<const float2*>(grp);
+    return c.x + c.y;
+  } else {
+    const float4 c = *reinterpret_cast<const float4*>(grp + 4 * q);
+    float s = (c.x + c.y) + (c.z + c.w);
+#pragma unroll
+    for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) s = s + __shfl_xor(s, 1 << k);
+    return s;
+  }
+}
+
+// Per-height facts of one tree, kept in LDS by kernels that loop over heights: indexing the
+// kernel arguments by a run-time height costs a dependent scalar load from memory per use.  The
+// kernel-argument segment is ordinary read-only memory, so lane h fetches the entries of height h
+// from it with a vector load and all heights arrive in one trip.  Only for kernels whose FIRST
+// argument is the Geom (it then sits at offset 0 of the segment).
+struct LevelTable {
+  float* lvl[kMaxHeight + 1];   // level h of this tree
+  uint32_t n[kMaxHeight + 1];   // its real nodes
+};
+template <typename T>
+__device__ __forceinline__ const T* kernarg_at(size_t offset) {
+  return (const T*)((const char*)__builtin_amdgcn_kernarg_segment_ptr() + offset);
+}
+__device__ __forceinline__ void fill_level_table(uint32_t H, uint32_t t, LevelTable* tab) {
+  const Geom* gk = kernarg_at<Geom>(0);
+  const uint32_t h = threadIdx.x;
+  if (h <= H) {
+    tab->lvl[h] = gk->level[h] + (size_t)t * gk->stride[h];
+    tab->n[h] = gk->n[h];
+  }
+}
+
+// One K-ary level of the prefix-sum traversal (Section V-A "traversing the tree
+// performing prefix sum from root to leaf"), done by a single lane as log2(K) binary steps:
+//   go right iff the right block is non-zero and not (r < left block); then r -= left.
+//
+// walk_chunks: s[] holds the 2^M chunk sums of the group (a chunk = 4 adjacent children,
+// summed (c0+c1)+(c2+c3)).  The recursion first builds the pairwise sums above the chunks,
+// walks those levels from the top, and then decides between the two chunks below the node
+// it arrived at.  The pair is picked with a select chain, so everything stays in registers.
+template <int M>
+__device__ __forceinline__ unsigned walk_chunks(const float (&s)[1 << M], float& r) {
+  if constexpr (M == 0) {
+    return 0u;
+  } else {
+    constexpr int HALF = 1 << (M - 1);
+    float up[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) up[i] = s[2 * i] + s[2 * i + 1];
+    const unsigned pos = walk_chunks<M - 1>(up, r);
+    float L = s[0], R = s[1];
+#pragma unroll
+    for (int i = 1; i < HALF; ++i) {
+      const bool here = pos == (unsigned)i;
+      L = here ? s[2 * i] : L;
+      R = here ? s[2 * i + 1] : R;
+    }
+    const bool right = (R != 0.0f) && !(r < L);
+    r = right ? r - L : r;
+    return 2u * pos + (right ? 1u : 0u);
+  }
+}
+
+// grp points at the K children (LDS or global).  Returns the chosen child, its value and the
+// residual.  The chosen chunk is read a second time instead of keeping all K children live.
+template <int LOGK>
+__device__ __forceinline__ void descend_lane(const float* grp, float& r, unsigned& child, float& val) {
+  if constexpr (LOGK == 1) {
+    const float2 c = *reinterpret_cast<const float2*>(grp);
+    const bool right = (c.y != 0.0f) && !(r < c.x);
+    r = right ? r - c.x : r;
+    child = right ? 1u : 0u;
+    val = right ? c.y : c.x;
+  } else {
+    constexpr int C = (1 << LOGK) / 4;
+    const float4* g4 = reinterpret_cast<const float4*>(grp);
+    float s[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      const float4 x = g4[c];
+      s[c] = (x.x + x.y) + (x.z + x.w);
+    }
+    const unsigned pos = walk_chunks<LOGK - 2>(s, r);
+    const float4 x = g4[pos];
+    const float p0 = x.x + x.y, p1 = x.z + x.w;
+    const bool r1 = (p1 != 0.0f) && !(r < p0);
+    r = r1 ? r - p0 : r;
+    const float a = r1 ? x.z : x.x, b = r1 ? x.w : x.y;
+    const bool r0 = (b != 0.0f) && !(r < a);
+    r = r0 ? r - a : r;
+    val = r0 ? b : a;
+    child = 4u * pos + (r1 ? 2u : 0u) + (r0 ? 1u : 0u);
+  }
+}
+
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const uint32_t y = (uint32_t)__shfl_xor((int)x, m);
+    x = y < x ? y : x;
+  }
+  return x;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const uint32_t y = (uint32_t)__shfl_xor((int)x, m);
+    x = y > x ? y : x;
+  }
+  return x;
+}
+
+// Running maximum priority: mx = fp32 bits of this lane's valid positive value (0: none).  One
+// atomic per wave, and only when the wave would actually raise the maximum; the plain read may
+// be stale, which can only cause a redundant atomic, never a missed one (the value only grows).
+// `seen` is the value read when the kernel started (so the read overlaps the other loads).
+__device__ __forceinline__ uint32_t read_max_bits(const Geom& g, uint32_t t) {
+  return *reinterpret_cast<volatile uint32_t*>(&g.max_v[t]);
+}
+__device__ __forceinline__ void raise_max(const Geom& g, uint32_t t, uint32_t mx, uint32_t seen) {
+  mx = wave_max_u32(mx);
+  if ((threadIdx.x & 63u) == 0 && mx > seen) atomicMax(reinterpret_cast<uint32_t*>(&g.max_v[t]), mx);
+}
+
+// Importance weight (prioritized experience replay, cited in Section II-A):
+// w = (size * v / total)^-beta / max over the batch, the maximum being reached at the batch
+// minimum of v.  fp64, so that the result stays within 1e-6 of an fp64 reference.
+__device__ __forceinline__ float importance_weight(float v, float vmin, float total, uint32_t size, float beta) {
+  const double nb = -(double)beta;
+  const double scale = (double)size / (double)total;
+  return (float)(pow(scale * (double)v, nb) / pow(scale * (double)vmin, nb));
+}

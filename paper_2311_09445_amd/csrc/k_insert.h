@@ -1,0 +1,212 @@
+// Insertion: leaf writes, and the single-kernel insert of a few rows.
+// Part of per_kernels.hip (included inside namespace per, in the order given there); not a stand-alone header.
+
+// ---------------------------------------------------------------------------------
+// insertion: leaf writes (rows go through k_rows<false>)
+// ---------------------------------------------------------------------------------
+// Leaf of inserted row j (ring slot cursor + j): the given value, or the running maximum.
+__device__ __forceinline__ void insert_leaf(const Geom& g, uint32_t t, uint32_t n, uint32_t cursor, uint32_t j,
+                                            const float* __restrict__ prio, float max_on_entry,
+                                            uint32_t* __restrict__ out_idx, uint32_t& mx, bool& bad) {
+  uint64_t slot = (uint64_t)cursor + j;
+  if (slot >= g.N) slot -= g.N;
+  if (out_idx) out_idx[(size_t)t * n + j] = (uint32_t)slot;
+  float* leaf = g.level[0] + (size_t)t * g.stride[0] + slot;
+  if (prio) {
+    const float v = prio[(size_t)t * n + j];
+    if (valid_priority(v)) {
+      *leaf = v;
+      const uint32_t vb = v > 0.0f ? __float_as_uint(v) : 0u;
+      mx = vb > mx ? vb : mx;
+    } else {
+      bad = true;
+    }
+  } else {
+    *leaf = max_on_entry;   // running maximum as it was when the call started
+  }
+}
+
+__global__ void k_insert_leaves(Geom g, uint32_t n, uint32_t cursor, const float* __restrict__ prio,
+                                uint32_t* __restrict__ out_idx) {
+  const uint32_t t = blockIdx.y;
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t mx = 0;
+  bool bad = false;
+  if (j < n) insert_leaf(g, t, n, cursor, j, prio, prio ? 0.0f : g.max_v[t], out_idx, mx, bad);
+  if (prio) {
+    raise_max(g, t, mx, read_max_bits(g, t));
+    if (bad) atomicOr(&g.status[t], 2u);
+  }
+}
+
+// A small insert as one kernel, one workgroup per tree: the rows, the leaves, and every ancestor
+// of the touched ring slots up to the root.  The touched nodes of a height form at most two
+// contiguous ranges (narrowed by K per height), known before anything is read, so the child groups
+// of all of them, at every height, are fetched into LDS in one trip; the new leaves and then each
+// height's new sums are patched into the staged groups of the height above, and the heights are
+// finished from LDS without going back to memory.
+// stale_hb != 0: the last update left the heights above stale_hb to their next reader; they are
+// then recomputed here in full instead of only over the touched ranges.
+constexpr int kInsertHeights = 32;
+struct InsertPlan {
+  Range2 r[kInsertHeights];        // touched nodes of height h + 1
+  uint32_t off[kInsertHeights];    // where their child groups start in LDS (floats)
+};
+struct InsertArgs {                // one kernel argument, so that both parts sit at known offsets of the segment
+  Geom g;
+  InsertPlan plan;
+};
+
+// position of node among the touched nodes of its height (the two ranges back to back)
+__device__ __forceinline__ uint32_t plan_pos(const Range2& r, uint32_t node) {
+  return node >= r.a0 && node < r.b0 ? node - r.a0 : (r.b0 - r.a0) + (node - r.a1);
+}
+
+template <int LOGK>
+__global__ void __launch_bounds__(1024)
+k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const float* __restrict__ prio,
+               uint32_t* __restrict__ out_idx) {
+  const Geom& g = a.g;
+  constexpr int K = Fan<LOGK>::K;
+  constexpr int LPS = Fan<LOGK>::LPS;
+  extern __shared__ __attribute__((aligned(16))) float staged[];
+  __shared__ LevelTable tab;
+  __shared__ Range2 s_r[kInsertHeights];
+  __shared__ uint32_t s_off[kInsertHeights];
+  const uint32_t t = blockIdx.x;
+  const uint32_t H = g.H;
+  PER_TRACE_DECL;
+  PER_MARK(0);
+  fill_level_table(H, t, &tab);
+  if (threadIdx.x >= 64 && threadIdx.x < 64 + H) {
+    const InsertPlan* pk = kernarg_at<InsertPlan>(offsetof(InsertArgs, plan));
+    s_r[threadIdx.x - 64] = pk->r[threadIdx.x - 64];
+    s_off[threadIdx.x - 64] = pk->off[threadIdx.x - 64];
+  }
+  // the rows need none of the tables: their trip to memory overlaps the fetch of the tables
+  (void)move_rows_one_workgroup<false>(ft, t, (uint64_t)t * n, n, cursor, g.N, nullptr);
+  __syncthreads();
+  PER_MARK(1);
+  // ---- everything that is read: the child groups of all touched nodes, the running maximum
+  for (uint32_t h = 1; h <= H; ++h) {
+    const Range2 r = s_r[h - 1];
+    const uint32_t c0 = r.b0 - r.a0, cnt = c0 + (r.b1 - r.a1);
+    const float* child = tab.lvl[h - 1];
+    for (uint32_t e = threadIdx.x; e < cnt * K; e += blockDim.x) {
+      const uint32_t pos = e >> LOGK;
+      const uint32_t node = pos < c0 ? r.a0 + pos : r.a1 + (pos - c0);
+      staged[s_off[h - 1] + e] = child[(size_t)node * K + (e & (K - 1))];
+    }
+  }
+  const float max_on_entry = prio ? 0.0f : g.max_v[t];
+  uint32_t max_seen = 0;
+  if (prio) max_seen = read_max_bits(g, t);
+  __syncthreads();
+  PER_MARK(2);
+  // ---- leaves (stores only), the new ones also into their staged groups
+  uint32_t mx = 0;
+  bool bad = false;
+  for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) {
+    uint64_t slot = (uint64_t)cursor + j;
+    if (slot >= g.N) slot -= g.N;
+    if (out_idx) out_idx[(size_t)t * n + j] = (uint32_t)slot;
+    float v = max_on_entry;
+    bool ok = true;
+    if (prio) {
+      v = prio[(size_t)t * n + j];
+      ok = valid_priority(v);
+      const uint32_t vb = ok && v > 0.0f ? __float_as_uint(v) : 0u;
+      mx = vb > mx ? vb : mx;
+      bad = bad || !ok;
+    }
+    if (ok) {
+      tab.lvl[0][slot] = v;
+      staged[s_off[0] + plan_pos(s_r[0], (uint32_t)(slot >> LOGK)) * K + ((uint32_t)slot & (K - 1))] = v;
+    }
+  }
+  if (prio) {
+    raise_max(g, t, mx, max_seen);
+    if (bad) atomicOr(&g.status[t], 2u);
+  }
+  __syncthreads();
+  PER_MARK(3);
+  // ---- heights 1 .. H from the staged groups
+  const unsigned q = threadIdx.x % LPS;
+  const uint32_t grp = threadIdx.x / LPS, ngrp = blockDim.x / LPS;
+  for (uint32_t h = 1; h <= H; ++h) {
+    const Range2 r = s_r[h - 1];
+    const uint32_t c0 = r.b0 - r.a0, cnt = c0 + (r.b1 - r.a1);
+    float* par = tab.lvl[h];
+    for (uint32_t base = 0; base < cnt; base += ngrp) {
+      const uint32_t pos = base + grp;
+      const bool ok = pos < cnt;
+      const float sum = group_sum<LOGK>(staged + s_off[h - 1] + (size_t)(ok ? pos : 0u) * K, q);
+      if (ok && q == 0) {
+        const uint32_t node = pos < c0 ? r.a0 + pos : r.a1 + (pos - c0);
+        par[node] = sum;
+        if (h < H) staged[s_off[h] + plan_pos(s_r[h], node >> LOGK) * K + (node & (K - 1))] = sum;
+      }
+    }
+    lds_barrier();   // the next height reads the staged groups only
+  }
+  PER_MARK(4);
+  PER_FLUSH();
+}
+
+hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uint32_t cursor, const float* prio,
+                                uint32_t* out_idx, hipStream_t s) {
+  PER_LAUNCH(KID_INSERT_LEAVES, k_insert_leaves, dim3((n + 255) / 256, g.T), dim3(256), 0, s, g, n, cursor, prio,
+             out_idx);
+  return hipGetLastError();
+}
+
+// True when an insert of n rows is small enough for k_insert_small: few bytes to move and few
+// nodes per height for one workgroup.
+bool insert_fits_one_workgroup(const Geom& g, const FieldTable* ft, uint32_t n) {
+  uint64_t bytes = 0;
+  if (ft)
+    for (uint32_t f = 0; f < ft->n_fields; ++f)
+      if (ft->io[f]) bytes += (uint64_t)n * ft->bytes[f];
+  return n <= 4096 && bytes <= 256 * 1024;
+}
+
+template <int LOGK>
+static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n,
+                                        uint32_t cursor, const float* prio, uint32_t* out_idx, uint32_t stale_hb,
+                                        hipStream_t s) {
+  constexpr int K = Fan<LOGK>::K;
+  FieldTable f{};
+  if (ft) f = *ft;
+  InsertArgs a{};
+  a.g = g;
+  InsertPlan& plan = a.plan;
+  const uint64_t end = (uint64_t)cursor + n;
+  Range2 r;
+  r.a0 = cursor;
+  r.b0 = (uint32_t)(end < g.N ? end : g.N);
+  r.a1 = 0;
+  r.b1 = (uint32_t)(end > g.N ? end - g.N : 0);
+  uint32_t floats = 0;
+  for (uint32_t h = 1; h <= g.H; ++h) {
+    if (r.b0 > r.a0) { r.a0 >>= LOGK; r.b0 = ((r.b0 - 1) >> LOGK) + 1; }
+    if (r.b1 > r.a1) { r.a1 >>= LOGK; r.b1 = ((r.b1 - 1) >> LOGK) + 1; }
+    if (r.b1 > r.a1 && r.a0 < r.b1) { r.a0 = 0; r.a1 = r.b1 = 0; }   // the two ranges met: one range
+    if (stale_hb && h > stale_hb) r = Range2{0, g.n[h], 0, 0};
+    plan.r[h - 1] = r;
+    plan.off[h - 1] = floats;
+    floats += ((r.b0 - r.a0) + (r.b1 - r.a1)) * K;
+  }
+  uint32_t block = (n * Fan<LOGK>::LPS + 63) / 64 * 64;
+  if (block < 256) block = 256;
+  if (block > 1024) block = 1024;
+  PER_LAUNCH(KID_INSERT_SMALL, k_insert_small<LOGK>, dim3(g.T), dim3(block), (size_t)floats * 4, s, a, f, n, cursor, prio,
+             out_idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_insert_small(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n, uint32_t cursor,
+                               const float* prio, uint32_t* out_idx, uint32_t stale_hb, hipStream_t s) {
+#define CALL(L) launch_insert_small_k<L>(g, tn, ft, n, cursor, prio, out_idx, stale_hb, s)
+  PER_DISPATCH_LOGK(g.logK, CALL)
+#undef CALL
+}

@@ -1,0 +1,384 @@
+// Second half of a priority update: the tree pass (alone, or beside the row gather and the weights).
+// Part of per_kernels.hip (included inside namespace per, in the order given there); not a stand-alone header.
+
+// ---------------------------------------------------------------------------------
+// priority update: claim (last writer), then one tree pass
+// ---------------------------------------------------------------------------------
+// Heights 1 .. hb of the tree pass at fixed kernel-argument offsets (slot j = height j + 1).
+constexpr int kSubSlots = 13;
+struct SubLevels {
+  float* ptr[kSubSlots];          // that height of tree 0
+  uint32_t stride[kSubSlots];     // floats between trees
+  uint32_t n[kSubSlots];          // real nodes of that height
+  uint32_t lds_off[kSubSlots];    // where the workgroup keeps its part of that height (floats)
+  uint32_t lds_floats;            // total
+  uint32_t hb;
+};
+
+// Tree pass.  Workgroup b of tree t owns the subtree under node b of height hb and keeps the
+// subtree's nodes of heights 1 .. hb in LDS.
+//  0. In one trip it fetches its height-1 nodes and the dirty bits of the leaves below them.
+//  1. Each height-1 node with a dirty leaf is rebuilt by LPS lanes: they read its K leaves and,
+//     for the dirty ones only, the stamp entry, whose lower word is the value of the batch
+//     element that won that leaf; it replaces the leaf (and is stored); the K values are
+//     summed pairwise.  The dirty bits are cleared at the end.
+//  2. Heights 2 .. hb of the subtree are recomputed from LDS and stored.
+//  3. Above hb every node counts the arrivals of its children's workgroups; the last one to
+//     arrive recomputes it and carries on upwards, so the root is written by whichever
+//     workgroup finishes last.  No workgroup ever waits for another.  When there are only a
+//     few nodes at height hb this step is skipped (chain == 0): the agent-scope fences it
+//     needs cost more than recomputing those heights in the next kernel that reads them.
+constexpr uint32_t kDirtyListCap = 2048;
+constexpr uint32_t kLazyTopNodes = 4096;
+
+// The work of workgroup b of tree t (b = its subtree's root at height hb).
+template <int LOGK>
+__device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uint32_t t, uint32_t b, uint32_t chain) {
+  constexpr int K = Fan<LOGK>::K;
+  constexpr int LPS = Fan<LOGK>::LPS;
+  extern __shared__ __attribute__((aligned(16))) float sub[];   // 16-byte LDS accesses need the alignment
+  __shared__ uint32_t s_list[kDirtyListCap];
+  __shared__ uint32_t s_bits[kDirtyListCap];
+  __shared__ uint32_t s_bits_hi[LOGK == 6 ? kDirtyListCap : 1];
+  __shared__ uint32_t s_wave[16];
+  __shared__ uint32_t s_last;
+  const uint32_t hb = sl.hb;
+  const unsigned lane = threadIdx.x & 63u;
+  const unsigned q = threadIdx.x % LPS;
+  const uint32_t grp = threadIdx.x / LPS;
+  const uint32_t ngrp = blockDim.x / LPS;
+
+  PER_TRACE_DECL;
+  PER_MARK(0);
+  PER_MARK_HWID(15);
+  // ---- 0. this subtree's height-1 nodes and their dirty flags
+  const uint32_t sh1 = (hb - 1) * LOGK;
+  const uint32_t n1 = sl.n[0];
+  const uint32_t n1_pad = (n1 + K - 1) / K * K;
+  const uint32_t lo1 = b << sh1;
+  const uint32_t hi1 = min(n1, (b + 1) << sh1);
+  float* lvl1 = sl.ptr[0] + (size_t)t * sl.stride[0];
+  uint32_t* dirty = g.dirty + (size_t)t * g.dirty_stride;
+  float* leaves = g.level[0] + (size_t)t * g.stride[0];
+  const uint2* owner = reinterpret_cast<const uint2*>(g.owner) + (size_t)t * g.owner_stride;   // (value, stamp)
+  // the K dirty bits of one height-1 node
+  auto node_bits = [&](uint32_t node) -> unsigned long long {
+    if constexpr (LOGK == 6) {
+      const uint2 w = *reinterpret_cast<const uint2*>(dirty + 2 * (size_t)node);
+      return ((unsigned long long)w.y << 32) | w.x;
+    } else if constexpr (LOGK == 5) {
+      return dirty[node];
+    } else {
+      const uint32_t bit0 = node << LOGK;
+      return (dirty[bit0 >> 5] >> (bit0 & 31u)) & ((1u << K) - 1u);
+    }
+  };
+  // one node per thread and sweep; the first sweep's bits are fetched together with the height-1 nodes
+  const uint32_t f_first = lo1 + threadIdx.x;
+  unsigned long long bits_first = 0;
+  if (f_first < hi1) bits_first = node_bits(f_first);
+  for (uint32_t i = threadIdx.x; i < sl.lds_floats; i += blockDim.x) {
+    const uint32_t gi = lo1 + i;
+    sub[i] = (i < sl.lds_off[1] || hb == 1) && gi < n1_pad ? lvl1[gi] : 0.0f;   // slot 0 from memory, the rest zero
+  }
+  // compact the dirty nodes into s_list / s_bits: ballot within the wave, wave totals through LDS
+  const uint32_t nwaves = blockDim.x >> 6;
+  uint32_t nd = 0;
+  for (uint32_t f0 = lo1; f0 < hi1; f0 += blockDim.x) {
+    const uint32_t f = f0 + threadIdx.x;
+    unsigned long long bits = 0;
+    if (f0 == lo1) bits = bits_first;
+    else if (f < hi1) bits = node_bits(f);
+    const unsigned long long m = __ballot(bits != 0);
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    if (lane == 0) s_wave[threadIdx.x >> 6] = (uint32_t)__popcll(m);
+    __syncthreads();
+    uint32_t before = nd, total = nd;
+    for (uint32_t wv = 0; wv < nwaves; ++wv) {
+      const uint32_t c = s_wave[wv];
+      if (wv < (threadIdx.x >> 6)) before += c;
+      total += c;
+    }
+    if (bits != 0) {
+      s_list[before + rank] = f;
+      s_bits[before + rank] = (uint32_t)bits;
+      if constexpr (LOGK == 6) s_bits_hi[before + rank] = (uint32_t)(bits >> 32);
+    }
+    nd = total;
+    __syncthreads();
+  }
+  PER_MARK(1);
+
+  if (nd > 0) {
+    // ---- 1. rebuild the dirty height-1 nodes (list order is irrelevant: nodes are independent).
+    // Two nodes per lane group and sweep, the loads of both issued before the first store: a
+    // second sweep would otherwise cost a second trip to memory.
+    using LeafVec = typename std::conditional<LOGK == 1, float2, float4>::type;
+    struct Item {
+      bool ok;
+      uint32_t node, my;
+      size_t at;
+      LeafVec c;
+      uint2 s[4];
+    };
+    // A set bit means the leaf was claimed in this batch: its stamp entry holds the winner's value.
+    auto fetch = [&](uint32_t item) -> Item {
+      Item it;
+      it.ok = item < nd;
+      const uint32_t li = it.ok ? item : nd - 1;
+      it.node = s_list[li];
+      unsigned long long bits = s_bits[li];
+      if constexpr (LOGK == 6) bits |= (unsigned long long)s_bits_hi[li] << 32;
+      if constexpr (LOGK == 1) {
+        it.my = (uint32_t)bits & 3u;
+        it.at = (size_t)it.node * 2;
+      } else {
+        it.my = (uint32_t)(bits >> (4 * q)) & 0xFu;
+        it.at = (size_t)it.node * K + 4 * q;
+      }
+      it.c = *reinterpret_cast<const LeafVec*>(leaves + it.at);
+#pragma unroll
+      for (int k = 0; k < (LOGK == 1 ? 2 : 4); ++k) {
+        it.s[k] = make_uint2(0, 0);
+        if (it.my & (1u << k)) it.s[k] = owner[it.at + k];
+      }
+      return it;
+    };
+    auto finish = [&](Item& it) {
+      float sum;
+      if constexpr (LOGK == 1) {
+        if (it.my & 1u) it.c.x = __uint_as_float(it.s[0].x);
+        if (it.my & 2u) it.c.y = __uint_as_float(it.s[1].x);
+        sum = it.c.x + it.c.y;
+      } else {
+        if (it.my & 1u) it.c.x = __uint_as_float(it.s[0].x);
+        if (it.my & 2u) it.c.y = __uint_as_float(it.s[1].x);
+        if (it.my & 4u) it.c.z = __uint_as_float(it.s[2].x);
+        if (it.my & 8u) it.c.w = __uint_as_float(it.s[3].x);
+        sum = (it.c.x + it.c.y) + (it.c.z + it.c.w);
+#pragma unroll
+        for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) sum = sum + __shfl_xor(sum, 1 << k);
+      }
+      return sum;
+    };
+    auto store = [&](const Item& it, float sum) {
+      if (it.ok && it.my) *reinterpret_cast<LeafVec*>(leaves + it.at) = it.c;
+      if (it.ok && q == 0) {
+        lvl1[it.node] = sum;
+        sub[it.node - lo1] = sum;
+      }
+    };
+    for (uint32_t base = 0; base < nd; base += 2 * ngrp) {
+      Item i0 = fetch(base + grp);
+      if (base + ngrp < nd) {   // uniform over the workgroup
+        Item i1 = fetch(base + ngrp + grp);
+        PER_MARK(4);
+        const float sum0 = finish(i0);
+        const float sum1 = finish(i1);
+        PER_MARK(5);
+        store(i0, sum0);
+        store(i1, sum1);
+      } else {
+        PER_MARK(4);
+        const float sum0 = finish(i0);
+        PER_MARK(5);
+        store(i0, sum0);
+      }
+    }
+    PER_MARK(2);
+    // ---- 2. heights 2 .. hb of this subtree, from LDS
+#pragma unroll
+    for (int j = 1; j < kSubSlots; ++j) {
+      if ((uint32_t)j < hb) {
+        __syncthreads();
+        const uint32_t sh = (hb - 1 - (uint32_t)j) * LOGK;
+        const uint32_t a = b << sh;
+        const uint32_t cnt = min(sl.n[j], (b + 1) << sh) - a;   // real nodes of this height in the subtree
+        float* par = sl.ptr[j] + (size_t)t * sl.stride[j];
+        for (uint32_t base = 0; base < cnt; base += ngrp) {
+          const uint32_t e = base + grp;
+          const bool ok = e < cnt;
+          const float sum = group_sum<LOGK>(sub + sl.lds_off[j - 1] + (size_t)(ok ? e : 0u) * K, q);
+          if (ok && q == 0) {
+            par[a + e] = sum;
+            sub[sl.lds_off[j] + e] = sum;
+          }
+        }
+      }
+    }
+  }
+
+  PER_MARK(3);
+  PER_FLUSH();
+  // The flags are cleared only now: a wait for loaded data also waits for every earlier store
+  // of the wave, so stores that nothing depends on go last.
+  for (uint32_t i = threadIdx.x; i < nd; i += blockDim.x) {
+    const uint32_t node = s_list[i];
+    if constexpr (LOGK == 6) {
+      dirty[2 * (size_t)node] = 0;
+      dirty[2 * (size_t)node + 1] = 0;
+    } else {
+      dirty[(node << LOGK) >> 5] = 0;   // for K < 32 the word is shared with neighbours of the same subtree
+    }
+  }
+  // ---- 3. above the subtree: the last child to arrive recomputes the parent
+  if (!chain) return;   // the heights above hb are left to their next reader
+  uint32_t node = b;
+  for (uint32_t h = hb + 1; h <= g.H; ++h) {
+    const uint32_t parent = node >> LOGK;
+    const uint32_t nchild = min((uint32_t)K, g.n[h - 1] - parent * K);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      __threadfence();   // this workgroup's node writes are visible before its arrival is counted
+      uint32_t* cnt = g.arrive + (size_t)t * g.arrive_stride + g.arrive_off[h] + parent;
+      const uint32_t old = atomicAdd(cnt, 1u);
+      const bool last = old == nchild - 1;
+      if (last) *cnt = 0;   // ready for the next call
+      s_last = last ? 1u : 0u;
+      __threadfence();   // and the siblings' writes are visible to the reads below
+    }
+    __syncthreads();
+    if (!s_last) return;
+    if (threadIdx.x < 64) {
+      const float sum = group_sum<LOGK>(g.level[h - 1] + (size_t)t * g.stride[h - 1] + (size_t)parent * K, lane % LPS);
+      if (lane == 0) g.level[h][(size_t)t * g.stride[h] + parent] = sum;
+    }
+    node = parent;
+  }
+}
+
+// Two 1024-lane workgroups share a compute unit only while a wave stays within an eighth of the
+// SIMD's scalar and vector registers; with one more scalar register than that the second workgroup
+// waits for the first to end and the kernel takes half as long again.
+template <int LOGK>
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8)))
+k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
+  tree_job<LOGK>(g, sl, blockIdx.y, blockIdx.x, chain);
+}
+
+// Second kernel of a fused step whose claim phase rode in the sampling kernel: the tree pass
+// (workgroups 0 .. tree_blocks-1) and, beside it, what is left of the sampling call: the
+// importance weights and the rows of the sampled indices (JobRanges, offset by tree_blocks).  The
+// tree pass is a chain of dependent memory trips and the row traffic fills the gaps; launched with
+// workgroups of at most 512 lanes so that the two kinds share the compute units.
+template <int LOGK>
+__global__ void __launch_bounds__(512)
+k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldTable ft, JobRanges jr, FinishArgs a) {
+  const uint32_t t = blockIdx.y;
+  if (blockIdx.x < tree_blocks) {
+    tree_job<LOGK>(g, sl, t, blockIdx.x, chain);
+    return;
+  }
+  const uint32_t b = blockIdx.x - tree_blocks;
+  if (b < jr.first[1]) {
+    weights_job(g, t, a.B, a.size, a.beta, a.w, a.parity, b, jr.first[1]);
+    return;
+  }
+#pragma unroll
+  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
+    if (b >= jr.first[2 + f] && b < jr.first[3 + f]) {
+      rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+      return;
+    }
+}
+
+// Height of the workgroup roots of the tree pass: the whole tree for small trees, else the
+// lowest height whose subtrees hold at least 64 height-1 nodes (so that dirty words are never
+// shared between workgroups).
+static uint32_t tree_pass_height(const Geom& g) {
+  if (g.n[1] <= kDirtyListCap) return g.H;
+  uint32_t hb = 1;
+  while (hb < g.H && (1ull << ((hb - 1) * g.logK)) < 64) ++hb;
+  return hb;
+}
+
+// Heights above this one may be left stale by an update (0: never).
+uint32_t lazy_top_height(const Geom& g, const Tuning& tn) {
+  const uint32_t hb = tree_pass_height(g);
+  return tn.lazy_top && hb < g.H && g.n[hb] <= kLazyTopNodes ? hb : 0u;
+}
+
+// Sub-level descriptors, workgroup size and LDS floats of the tree pass for update batches of B.
+template <int LOGK>
+static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, uint32_t B, SubLevels* out, uint32_t* tblock_out) {
+  constexpr int K = Fan<LOGK>::K;
+  const uint32_t hb = tree_pass_height(g);
+  if (hb > (uint32_t)kSubSlots) return hipErrorInvalidValue;   // cannot happen for fanouts and capacities accepted at create
+  SubLevels sl{};
+  sl.hb = hb;
+  uint32_t off = 0;
+  for (uint32_t h = 1; h <= hb; ++h) {
+    const uint32_t j = h - 1;
+    sl.ptr[j] = g.level[h];
+    sl.stride[j] = g.stride[h];
+    sl.n[j] = g.n[h];
+    sl.lds_off[j] = off;
+    // nodes of this height under one workgroup root, padded to whole child groups
+    const uint64_t full = 1ull << ((hb - h) * LOGK);
+    const uint64_t padded = h < hb ? ((uint64_t)g.n[h] + K - 1) / K * K : 1;
+    off += (uint32_t)(full < padded ? full : padded);
+  }
+  sl.lds_floats = off;
+  // Unless told otherwise: enough lane groups to rebuild in one sweep twice the dirty height-1 nodes a
+  // subtree gets on average (never more than it has), so that small batches do not launch idle waves.
+  uint32_t tblock = tn.tree_block;
+  if (tblock == 0) {
+    const uint64_t per_subtree = hb > 1 ? sl.lds_off[1] : 1;
+    uint64_t expect = 2 * ((uint64_t)B + g.n[hb] - 1) / g.n[hb];
+    if (expect > per_subtree) expect = per_subtree;
+    uint64_t want = expect * Fan<LOGK>::LPS;
+    if (hb > 2) {   // the dense heights of the subtree want a lane group per height-2 node
+      const uint64_t dense = (uint64_t)(sl.lds_off[2] - sl.lds_off[1]) * Fan<LOGK>::LPS;
+      if (dense > want) want = dense;
+    }
+    tblock = (uint32_t)(want > 1024 ? 1024 : (want + 63) / 64 * 64);
+    if (tblock < 64) tblock = 64;
+  }
+  *out = sl;
+  *tblock_out = tblock;
+  return hipSuccess;
+}
+
+template <int LOGK>
+static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, uint32_t B, hipStream_t s) {
+  SubLevels sl;
+  uint32_t tblock;
+  hipError_t e = tree_pass_shape<LOGK>(g, tn, B, &sl, &tblock);
+  if (e != hipSuccess) return e;
+  PER_LAUNCH(KID_UPDATE_TREE, k_update_tree<LOGK>, dim3(g.n[sl.hb], g.T), dim3(tblock), (size_t)sl.lds_floats * 4, s, g,
+             sl, lazy_top_height(g, tn) ? 0u : 1u);
+  return hipGetLastError();
+}
+
+// The tree pass of an update batch of B together with the weights and row jobs in `a` / `rows`.
+template <int LOGK>
+static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, uint32_t B, const FieldTable* rows,
+                                       const FinishArgs& a, hipStream_t s) {
+  SubLevels sl;
+  uint32_t tblock;
+  hipError_t e = tree_pass_shape<LOGK>(g, tn, B, &sl, &tblock);
+  if (e != hipSuccess) return e;
+  if (tblock > 512) tblock = 512;   // half the lanes of a compute unit are left to the other jobs
+  FieldTable ft{};
+  if (rows) ft = *rows;
+  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u);
+  const uint32_t tree_blocks = g.n[sl.hb];
+  PER_LAUNCH(KID_TREE_FINISH, k_tree_finish<LOGK>, dim3(tree_blocks + jr.first[2 + kMaxFields], g.T), dim3(tblock),
+             (size_t)sl.lds_floats * 4, s, g, sl, lazy_top_height(g, tn) ? 0u : 1u, tree_blocks, ft, jr, a);
+  return hipGetLastError();
+}
+
+template <int LOGK>
+static hipError_t launch_update_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s) {
+  const uint32_t block = tn.update_block;
+  PER_LAUNCH(KID_UPDATE_CLAIM, k_update_claim, dim3((c.B + block - 1) / block, g.T), dim3(block), 0, s, g, c);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_tree_k<LOGK>(g, tn, c.B, s);
+}
+
+hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s) {
+#define CALL(L) launch_update_k<L>(g, tn, c, s)
+  PER_DISPATCH_LOGK(g.logK, CALL)
+#undef CALL
+}
