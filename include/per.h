@@ -93,6 +93,18 @@ int per_destroy(per_t* p);
 int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_prio,
                uint32_t* d_out_idx, void* stream);
 
+/* Collision-free insertion (Section IV-B "Replay-Collision-Free Scheduling": insertions are scheduled
+ * after sampling and the insertion index is compared against the sampled indices, so that rows the
+ * Learner is still working on are not overwritten).  As per_insert, except that a row whose ring slot
+ * is one of d_protect_idx[T][n_protect] (say, the batch sampled last and not yet updated) is deferred:
+ * neither its payload nor its leaf is written, d_out_idx reports 0xFFFFFFFF for it, and the caller
+ * keeps it for its next insertion.  The ring advances by n all the same.  What happens to a colliding
+ * experience is not stated in the paper; this is the reading taken here.  Small inserts only
+ * (at most 4096 rows and 256 KiB of payload per tree), else PER_ERANGE. */
+int per_insert_protected(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_prio_or_null,
+                         uint32_t* d_out_idx_or_null, uint32_t n_protect, const uint32_t* d_protect_idx,
+                         void* stream);
+
 /* Priority sampling (Eq. 1; Section V-A "traversing the tree performing prefix sum from
  * root to leaf"), stratified: sample i of a tree takes the target
  *   ((float)i + u[i]) * (total / (float)B)

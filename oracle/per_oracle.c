@@ -172,6 +172,42 @@ int oracle_insert(oracle_t* o, uint32_t n, const void* const* field_src,
   return 0;
 }
 
+/* Collision-free insertion (Section IV-B, "Replay-Collision-Free Scheduling": the insertion index is
+ * compared against the sampled indices so that rows the Learner is still working on are not
+ * overwritten).  The paper does not say what happens to a colliding experience; the reading here:
+ * row j targets ring slot (cursor + j) mod N as always; if that slot is one of the protected
+ * indices the row is deferred (nothing is written, out_idx[j] = 0xFFFFFFFF, the caller keeps it
+ * for the next insertion), and the ring advances by n all the same. */
+int oracle_insert_protected(oracle_t* o, uint32_t n, const void* const* field_src, const float* prio_or_null,
+                            uint32_t* out_idx_or_null, uint32_t n_protect, const uint32_t* protect) {
+  if (n > o->N) return -4;
+  const float m = o->max_v;
+  for (uint32_t j = 0; j < n; ++j) {
+    uint64_t slot = (o->cursor + j) % o->N;
+    int deferred = 0;
+    for (uint32_t k = 0; k < n_protect && !deferred; ++k) deferred = protect[k] == slot;
+    if (deferred) {
+      if (out_idx_or_null) out_idx_or_null[j] = 0xFFFFFFFFu;
+      continue;
+    }
+    for (uint32_t f = 0; f < o->n_fields; ++f)
+      if (o->col[f] && field_src && field_src[f])
+        memcpy(o->col[f] + slot * o->field_bytes[f],
+               (const uint8_t*)field_src[f] + (uint64_t)j * o->field_bytes[f], o->field_bytes[f]);
+    if (out_idx_or_null) out_idx_or_null[j] = (uint32_t)slot;
+    if (prio_or_null) {
+      if (!valid_priority(prio_or_null[j])) { o->status |= ORACLE_FLAG_BAD_PRIORITY; continue; }
+      set_leaf(o, slot, prio_or_null[j]);
+      if (prio_or_null[j] > o->max_v) o->max_v = prio_or_null[j];
+    } else {
+      set_leaf(o, slot, m);
+    }
+  }
+  o->cursor = (o->cursor + n) % o->N;
+  o->size = (o->size + n > o->N) ? o->N : o->size + n;
+  return 0;
+}
+
 /* Priority sampling (Eq. 1 via root-to-leaf prefix-sum traversal, Section V-A),
  * stratified targets, plus importance weights. */
 int oracle_sample(oracle_t* o, uint32_t B, float beta, const float* u, uint32_t* out_idx,

@@ -47,6 +47,8 @@ def _load():
     lib.oracle_update_td.argtypes = [vp, u32, vp, vp, C.c_double, C.c_double]
     lib.oracle_insert.restype = C.c_int
     lib.oracle_insert.argtypes = [vp, u32, vp, vp, vp]
+    lib.oracle_insert_protected.restype = C.c_int
+    lib.oracle_insert_protected.argtypes = [vp, u32, vp, vp, vp, u32, vp]
     lib.oracle_sample.restype = C.c_int
     lib.oracle_sample.argtypes = [vp, u32, f32, vp, vp, vp, vp]
     lib.oracle_gather.argtypes = [vp, u32, vp, vp]
@@ -113,7 +115,8 @@ class Oracle:
 
     # -- operations -----------------------------------------------------------------
     def insert(self, n: int, rows: Optional[Sequence[np.ndarray]] = None,
-               prio: Optional[np.ndarray] = None) -> np.ndarray:
+               prio: Optional[np.ndarray] = None, protect: Optional[np.ndarray] = None) -> np.ndarray:
+        """protect: indices whose slots must not be overwritten (their rows are deferred, slot 0xFFFFFFFF)."""
         out = np.empty(n, dtype=np.uint32)
         src = None
         keep = []
@@ -128,7 +131,11 @@ class Oracle:
         p = None if prio is None else np.ascontiguousarray(prio, dtype=np.float32)
         if p is not None:
             assert p.shape == (n,)
-        rc = self._lib.oracle_insert(self._h, n, src, _ptr(p), _ptr(out))
+        if protect is not None:
+            pr = np.ascontiguousarray(protect, dtype=np.uint32).ravel()
+            rc = self._lib.oracle_insert_protected(self._h, n, src, _ptr(p), _ptr(out), pr.size, _ptr(pr))
+        else:
+            rc = self._lib.oracle_insert(self._h, n, src, _ptr(p), _ptr(out))
         if rc != 0:
             raise ValueError(f"oracle_insert rc={rc}")
         return out
@@ -225,10 +232,11 @@ class MultiOracle:
         self.field_bytes = tuple(field_bytes)
         self.H = self.trees[0].H
 
-    def insert(self, n, rows=None, prio=None):
+    def insert(self, n, rows=None, prio=None, protect=None):
         return np.stack([
             o.insert(n, None if rows is None else [r[t] for r in rows],
-                     None if prio is None else prio[t]) for t, o in enumerate(self.trees)])
+                     None if prio is None else prio[t],
+                     None if protect is None else protect[t]) for t, o in enumerate(self.trees)])
 
     def sample(self, u, beta=0.4, want_weights=True):
         res = [o.sample(u[t], beta, want_weights) for t, o in enumerate(self.trees)]

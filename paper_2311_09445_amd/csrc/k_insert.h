@@ -48,6 +48,7 @@ __global__ void k_insert_leaves(Geom g, uint32_t n, uint32_t cursor, const float
 // stale_hb != 0: the last update left the heights above stale_hb to their next reader; they are
 // then recomputed here in full instead of only over the touched ranges.
 constexpr int kInsertHeights = 32;
+constexpr uint32_t kInsertSmallRows = 4096;   // most rows one workgroup takes
 struct InsertPlan {
   Range2 r[kInsertHeights];        // touched nodes of height h + 1
   uint32_t off[kInsertHeights];    // where their child groups start in LDS (floats)
@@ -65,7 +66,7 @@ __device__ __forceinline__ uint32_t plan_pos(const Range2& r, uint32_t node) {
 template <int LOGK>
 __global__ void __launch_bounds__(1024)
 k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const float* __restrict__ prio,
-               uint32_t* __restrict__ out_idx) {
+               uint32_t* __restrict__ out_idx, const uint32_t* __restrict__ protect, uint32_t n_protect) {
   const Geom& g = a.g;
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
@@ -73,6 +74,7 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
   __shared__ LevelTable tab;
   __shared__ Range2 s_r[kInsertHeights];
   __shared__ uint32_t s_off[kInsertHeights];
+  __shared__ uint32_t s_skip[kInsertSmallRows / 32];   // bit j: row j is deferred (its slot is protected)
   const uint32_t t = blockIdx.x;
   const uint32_t H = g.H;
   PER_TRACE_DECL;
@@ -83,8 +85,22 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
     s_r[threadIdx.x - 64] = pk->r[threadIdx.x - 64];
     s_off[threadIdx.x - 64] = pk->off[threadIdx.x - 64];
   }
+  // Collision-free insertion (Section IV-B): a row whose ring slot is named by the protected batch is
+  // deferred.  The batch is scanned once; an index inside the ring window [cursor, cursor + n) marks its row.
+  if (protect) {
+    for (uint32_t w = threadIdx.x; w < kInsertSmallRows / 32; w += blockDim.x) s_skip[w] = 0;
+    __syncthreads();
+    for (uint32_t k = threadIdx.x; k < n_protect; k += blockDim.x) {
+      const uint32_t i = protect[(size_t)t * n_protect + k];
+      if (i < g.N) {
+        const uint32_t j = i >= cursor ? i - cursor : i + (g.N - cursor);   // position in the ring window
+        if (j < n) atomicOr(&s_skip[j >> 5], 1u << (j & 31u));
+      }
+    }
+    __syncthreads();
+  }
   // the rows need none of the tables: their trip to memory overlaps the fetch of the tables
-  (void)move_rows_one_workgroup<false>(ft, t, (uint64_t)t * n, n, cursor, g.N, nullptr);
+  (void)move_rows_one_workgroup<false>(ft, t, (uint64_t)t * n, n, cursor, g.N, nullptr, protect ? s_skip : nullptr);
   __syncthreads();
   PER_MARK(1);
   // ---- everything that is read: the child groups of all touched nodes, the running maximum
@@ -109,7 +125,9 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
   for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) {
     uint64_t slot = (uint64_t)cursor + j;
     if (slot >= g.N) slot -= g.N;
-    if (out_idx) out_idx[(size_t)t * n + j] = (uint32_t)slot;
+    const bool deferred = protect && ((s_skip[j >> 5] >> (j & 31u)) & 1u);
+    if (out_idx) out_idx[(size_t)t * n + j] = deferred ? 0xFFFFFFFFu : (uint32_t)slot;
+    if (deferred) continue;
     float v = max_on_entry;
     bool ok = true;
     if (prio) {
@@ -167,13 +185,13 @@ bool insert_fits_one_workgroup(const Geom& g, const FieldTable* ft, uint32_t n) 
   if (ft)
     for (uint32_t f = 0; f < ft->n_fields; ++f)
       if (ft->io[f]) bytes += (uint64_t)n * ft->bytes[f];
-  return n <= 4096 && bytes <= 256 * 1024;
+  return n <= kInsertSmallRows && bytes <= 256 * 1024;
 }
 
 template <int LOGK>
 static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n,
                                         uint32_t cursor, const float* prio, uint32_t* out_idx, uint32_t stale_hb,
-                                        hipStream_t s) {
+                                        const uint32_t* protect, uint32_t n_protect, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
   FieldTable f{};
   if (ft) f = *ft;
@@ -200,13 +218,14 @@ static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const F
   if (block < 256) block = 256;
   if (block > 1024) block = 1024;
   PER_LAUNCH(KID_INSERT_SMALL, k_insert_small<LOGK>, dim3(g.T), dim3(block), (size_t)floats * 4, s, a, f, n, cursor, prio,
-             out_idx);
+             out_idx, protect, n_protect);
   return hipGetLastError();
 }
 
 hipError_t launch_insert_small(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n, uint32_t cursor,
-                               const float* prio, uint32_t* out_idx, uint32_t stale_hb, hipStream_t s) {
-#define CALL(L) launch_insert_small_k<L>(g, tn, ft, n, cursor, prio, out_idx, stale_hb, s)
+                               const float* prio, uint32_t* out_idx, uint32_t stale_hb, const uint32_t* protect,
+                               uint32_t n_protect, hipStream_t s) {
+#define CALL(L) launch_insert_small_k<L>(g, tn, ft, n, cursor, prio, out_idx, stale_hb, protect, n_protect, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

@@ -71,10 +71,12 @@ __device__ __forceinline__ void rows_job(const FieldTable& ft, uint32_t f, uint3
 // one store: the lanes of a wave that serve different fields do not wait for each other's trips
 // to memory.  The caller's dense rows start at row dense_row0 of each field's array.
 // GATHER: row j comes from slot idx[j] (idx may live in LDS); slots >= N give zero bytes and the
-// return value true.  Otherwise row j goes to ring slot cursor + j.
+// return value true.  Otherwise row j goes to ring slot cursor + j, unless bit j of skip_bits
+// (a bit mask in LDS, or null) says that the row is not to be written.
 template <bool GATHER>
 __device__ __forceinline__ bool move_rows_one_workgroup(const FieldTable& ft, uint32_t t, uint64_t dense_row0, uint32_t n,
-                                                        uint32_t cursor, uint32_t N, const uint32_t* idx) {
+                                                        uint32_t cursor, uint32_t N, const uint32_t* idx,
+                                                        const uint32_t* skip_bits = nullptr) {
   uint32_t first[kMaxFields + 1];
   first[0] = 0;
 #pragma unroll
@@ -108,6 +110,7 @@ __device__ __forceinline__ bool move_rows_one_workgroup(const FieldTable& ft, ui
     } else {
       slot = (uint64_t)cursor + row;
       if (slot >= N) slot -= N;
+      if (skip_bits && ((skip_bits[row >> 5] >> (row & 31u)) & 1u)) continue;
     }
     uint8_t* dense = io + (dense_row0 + row) * E + (uint64_t)k * w;
     uint8_t* stored = col + slot * E + (uint64_t)k * w;

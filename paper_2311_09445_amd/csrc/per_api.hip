@@ -222,20 +222,24 @@ int per_destroy(per_t* p) {
   return PER_OK;
 }
 
-int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_prio, uint32_t* d_out_idx,
-               void* stream) {
+static int insert_impl(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_prio, uint32_t* d_out_idx,
+                       uint32_t n_protect, const uint32_t* d_protect, void* stream) {
   if (!p) return PER_EINVAL;
   if (n > p->cfg.capacity) return PER_ERANGE;
-  if (misaligned(d_prio, 4) || misaligned(d_out_idx, 4)) return PER_EINVAL;
+  if (misaligned(d_prio, 4) || misaligned(d_out_idx, 4) || misaligned(d_protect, 4)) return PER_EINVAL;
   if (n == 0) return PER_OK;
+  if (!d_protect) n_protect = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const uint64_t N = p->cfg.capacity;
   const uint32_t cursor = (uint32_t)p->cursor;
   FieldTable ft;
   const bool has_rows = fill_fields(p, const_cast<void* const*>(reinterpret_cast<const void* const*>(d_field_src)), &ft);
-  if (p->tn.insert_small && insert_fits_one_workgroup(p->g, has_rows ? &ft : nullptr, n)) {
+  const bool one_workgroup = insert_fits_one_workgroup(p->g, has_rows ? &ft : nullptr, n);
+  if (n_protect && !one_workgroup) return PER_ERANGE;   // the protected form exists for small inserts only
+  if ((p->tn.insert_small || n_protect) && one_workgroup) {
     // one kernel: rows, leaves, ancestors, and the heights an update may have left stale
-    hipError_t e1 = launch_insert_small(p->g, p->tn, has_rows ? &ft : nullptr, n, cursor, d_prio, d_out_idx, p->stale_hb, s);
+    hipError_t e1 = launch_insert_small(p->g, p->tn, has_rows ? &ft : nullptr, n, cursor, d_prio, d_out_idx, p->stale_hb,
+                                        n_protect ? d_protect : nullptr, n_protect, s);
     if (e1 == hipSuccess) p->stale_hb = 0;
     p->cursor = (p->cursor + n) % N;
     p->size = p->size + n > N ? N : p->size + n;
@@ -257,6 +261,16 @@ int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float
   p->cursor = (p->cursor + n) % N;
   p->size = p->size + n > N ? N : p->size + n;
   return hip_rc(e);
+}
+
+int per_insert(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_prio, uint32_t* d_out_idx,
+               void* stream) {
+  return insert_impl(p, n, d_field_src, d_prio, d_out_idx, 0, nullptr, stream);
+}
+
+int per_insert_protected(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_prio, uint32_t* d_out_idx,
+                         uint32_t n_protect, const uint32_t* d_protect_idx, void* stream) {
+  return insert_impl(p, n, d_field_src, d_prio, d_out_idx, n_protect, d_protect_idx, stream);
 }
 
 // Takes the stamps of one update batch from the host counter (clearing the stamp array when the

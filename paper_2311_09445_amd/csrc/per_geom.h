@@ -151,7 +151,8 @@ hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uin
                                 uint32_t* out_idx, hipStream_t s);
 bool insert_fits_one_workgroup(const Geom& g, const FieldTable* ft, uint32_t n);
 hipError_t launch_insert_small(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n, uint32_t cursor,
-                               const float* prio, uint32_t* out_idx, uint32_t stale_hb, hipStream_t s);
+                               const float* prio, uint32_t* out_idx, uint32_t stale_hb, const uint32_t* protect,
+                               uint32_t n_protect, hipStream_t s);
 hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipStream_t s);
 hipError_t launch_resum_top(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
 uint32_t lazy_top_height(const Geom& g, const Tuning& tn);

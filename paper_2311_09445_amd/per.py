@@ -19,7 +19,7 @@ OK, EINVAL, ENOMEM, EEMPTY, ERANGE, EHIP = 0, -1, -2, -3, -4, -5
 FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 
 EXPORTS = [
-    "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_sample", "per_sample_gather",
+    "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_insert_protected", "per_sample", "per_sample_gather",
     "per_sample_gather_update", "per_gather",
     "per_update", "per_update_td", "per_update_delta", "per_set_rng", "per_rng_calls", "per_run_steps",
     "per_run_steps_fits", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
@@ -81,6 +81,7 @@ def _lib():
         "per_create": (C.c_int, [cfgp, vp, C.c_size_t, vp, C.POINTER(vp)]),
         "per_destroy": (C.c_int, [vp]),
         "per_insert": (C.c_int, [vp, u32, vp, vp, vp, vp]),
+        "per_insert_protected": (C.c_int, [vp, u32, vp, vp, vp, u32, vp, vp]),
         "per_sample": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp]),
         "per_sample_gather": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, vp]),
         "per_sample_gather_update": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, u32, vp, vp, vp]),
@@ -206,15 +207,20 @@ class PrioritizedReplay:
         return arr, C.cast(arr, C.c_void_p)
 
     # ---------------------------------------------------------------- operations
-    def insert(self, n: int, rows=None, prio=None, out_idx=None):
+    def insert(self, n: int, rows=None, prio=None, out_idx=None, protect=None):
+        """``protect`` ([T, m] indices): rows whose ring slot is among them are deferred (per_insert_protected)."""
         torch = self._torch
         _keep, src = self._ptr_array(rows, n)
         if prio is not None and prio.numel() != self.T * n:
             raise ValueError("prio must hold T*n values")
         if out_idx is not None and out_idx.numel() != self.T * n:
             raise ValueError("out_idx must hold T*n values")
-        rc = self.lib.per_insert(self._h, n, src, _dptr(prio, torch.float32), _dptr(out_idx, torch.int32),
-                                 self._stream())
+        if protect is not None:
+            rc = self.lib.per_insert_protected(self._h, n, src, _dptr(prio, torch.float32), _dptr(out_idx, torch.int32),
+                                               protect.numel() // self.T, _dptr(protect, torch.int32), self._stream())
+        else:
+            rc = self.lib.per_insert(self._h, n, src, _dptr(prio, torch.float32), _dptr(out_idx, torch.int32),
+                                     self._stream())
         self._check(rc, "per_insert")
 
     def sample(self, u, beta: float = 0.4, want_weights: bool = True, want_prio: bool = True,

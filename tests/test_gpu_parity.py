@@ -721,3 +721,44 @@ def test_large_batch():
     m.sample_gather_update(wl.uniform01(rng, (1, B)), 0.7, True, rng.random((1, B)).astype(np.float32), alias=True)
     m.compare_tree()
     m.compare_status()
+
+
+@pytest.mark.parametrize("K,N,T,fb", [(16, 5000, 2, (68, 24, 4, 68, 1)), (2, 300, 1, (5,)), (32, 40000, 1, ())])
+def test_collision_free_insert(K, N, T, fb):
+    """per_insert_protected: rows aimed at a slot of the protected batch are deferred (Section IV-B)."""
+    log(f"protected insert K={K} N={N} T={T}")
+    rng = np.random.default_rng(N + K)
+    m = Mirror(K, N, T, fb)
+    m.insert(N - 20, prio=wl._draw_priorities("exponential_1", rng, (T, N - 20)), chunk=3000)
+    deferred_total = 0
+    for it in range(6):
+        gi, ci = m.sample(wl.uniform01(rng, (T, 200)), 0.4)            # the batch "in flight"
+        n = int(rng.choice([3, 40, 250]))
+        protect = ci.copy()
+        if it % 2:                                                      # some that certainly collide, one out of range
+            protect[:, :5] = (m.gpu.cursor + np.arange(5)) % N
+            protect[:, 5] = N + 9
+        counters = np.arange(m.counter, m.counter + n)
+        rows_np = [np.stack([wl.row_bytes(t, counters, f, b) for t in range(T)]) for f, b in enumerate(fb)]
+        prio = (rng.random((T, n)) * 3).astype(np.float32) if it % 3 == 0 else None
+        out = torch.empty((T, n), dtype=torch.int32, device="cuda")
+        m.gpu.insert(n, [dev(r) for r in rows_np] if fb else None, None if prio is None else dev(prio), out,
+                     protect=idx_to_dev(protect))
+        slots = m.cpu.insert(n, rows_np if fb else None, prio, protect)
+        assert np.array_equal(idx_to_host(out), slots)
+        deferred_total += int((slots == 0xFFFFFFFF).sum())
+        m.counter += n
+        m.compare_tree()
+        if fb:                                                          # payload of the whole ring
+            allidx = np.broadcast_to(np.arange(N, dtype=np.uint32), (T, N)).copy()
+            want = m.cpu.gather(allidx)
+            got = m.gpu.gather(idx_to_dev(allidx))
+            for f in range(len(fb)):
+                assert np.array_equal(got[f].cpu().numpy(), want[f]), f
+        m.update(ci, rng.random((T, 200)).astype(np.float32))          # the batch comes back from the Learner
+    assert deferred_total > 0
+    m.compare_status()
+    with pytest.raises(PerError) as e:                                  # the protected form is for small inserts
+        big = PrioritizedReplay(16, 100000)
+        big.insert(5000, None, None, None, protect=torch.zeros((1, 4), dtype=torch.int32, device="cuda"))
+    assert e.value.code == ERANGE

@@ -605,3 +605,46 @@ def test_counter_based_uniforms():
     assert float(((counts - 50000 / 64) ** 2 / (50000 / 64)).sum()) < stats.chi2.ppf(0.9999, 63)
     assert not np.array_equal(u, uniforms(0x123456789ABCDEF0, (7 << 32) | 6, 3, 50000))   # next call: new stream
     assert not np.array_equal(u, uniforms(0x123456789ABCDEF0, (7 << 32) | 5, 4, 50000))   # other tree
+
+
+# ---------------------------------------------------------------------------------------------
+# Collision-free insertion (Section IV-B): slots named by the protected batch keep their rows and
+# priorities; the rows aimed at them are reported as deferred; everything else as a plain insert.
+# Pinned against a dictionary model of the ring.
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K,N", [(4, 50), (16, 1000)])
+def test_protected_insert_against_a_ring_model(K, N):
+    rng = np.random.default_rng(N)
+    fb = (3,)
+    o = Oracle(K, N, fb)
+    model_rows, model_prio = {}, {}
+    cursor, size, counter, maxv = 0, 0, 0, 1.0
+    for it in range(12):
+        n = int(rng.integers(1, N // 2))
+        protect = rng.integers(0, N + 3, int(rng.integers(0, 20))).astype(np.uint32) if it % 3 else None
+        rows = rng.integers(0, 256, (n, 3), dtype=np.uint8)
+        prio = (rng.random(n) * 5).astype(np.float32) if it % 2 else None
+        out = o.insert(n, [rows], prio, protect)
+        entry_max = maxv
+        for j in range(n):
+            slot = (cursor + j) % N
+            if protect is not None and slot in set(protect.tolist()):
+                assert out[j] == 0xFFFFFFFF
+                continue
+            assert out[j] == slot
+            model_rows[slot] = rows[j].copy()
+            model_prio[slot] = float(prio[j]) if prio is not None else entry_max
+            if prio is not None:
+                maxv = max(maxv, float(prio[j]))
+        cursor, size = (cursor + n) % N, min(N, size + n)
+        assert o.cursor == cursor and o.size == size and o.max_priority == np.float32(maxv)
+        leaves = o.read_level(0)
+        for slot in range(N):
+            assert leaves[slot] == np.float32(model_prio.get(slot, 0.0)), (it, slot)
+        got = o.gather(np.arange(N, dtype=np.uint32))[0]
+        for slot, r in model_rows.items():
+            assert np.array_equal(got[slot], r)
+        ref = Oracle(K, N)                       # ancestors: the set form of the same leaves
+        ref.insert(N, None, leaves.copy())
+        for h in range(o.H + 1):
+            assert o.read_level(h).tobytes() == ref.read_level(h).tobytes()
