@@ -73,16 +73,22 @@ __device__ __forceinline__ void rows_job(const FieldTable& ft, uint32_t f, uint3
 // GATHER: row j comes from slot idx[j] (idx may live in LDS); slots >= N give zero bytes and the
 // return value true.  Otherwise row j goes to ring slot cursor + j, unless bit j of skip_bits
 // (a bit mask in LDS, or null) says that the row is not to be written.
-template <bool GATHER>
+// `between` is work of the caller's that every lane runs exactly once, after the lane's first load has
+// been issued and before its first store (or at the end, for lanes that move nothing): per-lane
+// arithmetic placed there overlaps the rows' trip to memory.  It must not contain barriers or
+// cross-lane operations.
+struct NothingBetween { __device__ __forceinline__ void operator()() const {} };
+template <bool GATHER, typename Between = NothingBetween>
 __device__ __forceinline__ bool move_rows_one_workgroup(const FieldTable& ft, uint32_t t, uint64_t dense_row0, uint32_t n,
                                                         uint32_t cursor, uint32_t N, const uint32_t* idx,
-                                                        const uint32_t* skip_bits = nullptr) {
+                                                        const uint32_t* skip_bits = nullptr, Between between = Between{}) {
   uint32_t first[kMaxFields + 1];
   first[0] = 0;
 #pragma unroll
   for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
     first[f + 1] = first[f] + (f < ft.n_fields && ft.io[f] ? n * (ft.bytes[f] / ft.vec[f]) : 0u);
   bool bad = false;
+  bool between_done = false;
   for (uint32_t e = threadIdx.x; e < first[kMaxFields]; e += blockDim.x) {
     // the field of this element, picked with selects; the divisions are done once, after the choice
     uint8_t* io = nullptr;
@@ -125,6 +131,10 @@ __device__ __forceinline__ bool move_rows_one_workgroup(const FieldTable& ft, ui
       default: v.x = *src; break;
     }
     if (!live) v = make_uint4(0, 0, 0, 0);
+    if (!between_done) {
+      between();
+      between_done = true;
+    }
     switch (w) {
       case 16: *reinterpret_cast<uint4*>(dst) = v; break;
       case 8: *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.y); break;
@@ -133,6 +143,7 @@ __device__ __forceinline__ bool move_rows_one_workgroup(const FieldTable& ft, ui
       default: *dst = (uint8_t)v.x; break;
     }
   }
+  if (!between_done) between();
   return bad;
 }
 

@@ -242,7 +242,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
       __syncthreads();
       uint32_t mm = 0x7F800000u;
       for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_min[wv] < mm ? s_min[wv] : mm;
-      if (active) out_w[o] = importance_weight(val, __uint_as_float(mm), total, size, beta);
+      if (active) out_w[o] = importance_weight(val, __uint_as_float(mm), beta);
     } else {                // partial minima, spread over kVminSlots addresses; the weights job finishes
       if (active) out_w[o] = val;
       if (lane == 0)
@@ -279,7 +279,7 @@ __device__ __forceinline__ void weights_job(const Geom& g, uint32_t t, uint32_t 
   const float total = g.root[(size_t)t * g.root_stride];
   for (uint32_t i = job_block * blockDim.x + threadIdx.x; i < B; i += job_blocks * blockDim.x) {
     const size_t o = (size_t)t * B + i;
-    w[o] = total > 0.0f ? importance_weight(w[o], __uint_as_float(mm), total, size, beta) : 0.0f;
+    w[o] = total > 0.0f ? importance_weight(w[o], __uint_as_float(mm), beta) : 0.0f;
   }
 }
 

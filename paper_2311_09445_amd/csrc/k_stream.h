@@ -157,12 +157,16 @@ k_run_steps(StreamKernelArgs ka) {
       if (a.out_prio) a.out_prio[bo] = val;
     }
     __syncthreads();
-    if (a.out_w && tid < B)
-      a.out_w[bo] = total > 0.0f ? importance_weight(val, __uint_as_float(s_vmin), total, size, beta) : 0.0f;
 
     PER_MARK(2);
     // ---- rows of the sampled indices
-    if (move_rows_one_workgroup<true>(a.rows, t, ((uint64_t)s * T + t) * B, B, 0, N, s_idx)) flags |= 1u;
+    // (the weights, a power per sample, are computed while the rows are on their way: every lane that
+    // owns a sample also owns a row element of the first sweep, so no wave runs the power twice)
+    auto weights = [&]() {
+      if (a.out_w && tid < B)
+        a.out_w[bo] = total > 0.0f ? importance_weight(val, __uint_as_float(s_vmin), beta) : 0.0f;
+    };
+    if (move_rows_one_workgroup<true>(a.rows, t, ((uint64_t)s * T + t) * B, B, 0, N, s_idx, nullptr, weights)) flags |= 1u;
 
     PER_MARK(3);
     // ---- priority update: last writer by LDS atomics, then the ancestors
