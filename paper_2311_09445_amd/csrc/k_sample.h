@@ -276,10 +276,12 @@ __device__ __forceinline__ void weights_job(const Geom& g, uint32_t t, uint32_t 
   __syncthreads();
   uint32_t mm = 0x7F800000u;
   for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_wmin[wv] < mm ? s_wmin[wv] : mm;
-  const float total = g.root[(size_t)t * g.root_stride];
+  // No minimum at all means that nothing could be sampled (the tree's total was zero): weights 0.  (The root
+  // itself must not be consulted here: a tree pass running beside this job may already have rewritten it.)
+  const bool nothing_sampled = mm == 0x7F800000u;
   for (uint32_t i = job_block * blockDim.x + threadIdx.x; i < B; i += job_blocks * blockDim.x) {
     const size_t o = (size_t)t * B + i;
-    w[o] = total > 0.0f ? importance_weight(w[o], __uint_as_float(mm), beta) : 0.0f;
+    w[o] = nothing_sampled ? 0.0f : importance_weight(w[o], __uint_as_float(mm), beta);
   }
 }
 

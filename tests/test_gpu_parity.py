@@ -762,3 +762,28 @@ def test_collision_free_insert(K, N, T, fb):
         big = PrioritizedReplay(16, 100000)
         big.insert(5000, None, None, None, protect=torch.zeros((1, 4), dtype=torch.int32, device="cuda"))
     assert e.value.code == ERANGE
+
+
+@pytest.mark.parametrize("K,N", [(2, 3000), (16, 1 << 16)])
+def test_fused_step_on_an_empty_total_that_the_update_fills(K, N):
+    """Sampling finds a total of zero (weights 0, index 0xFFFFFFFF) while the update fused into the same call
+    makes the tree non-zero: the weights job runs beside the tree pass and must not look at the new root."""
+    log(f"fused step, zero total then filled K={K} N={N}")
+    rng = np.random.default_rng(N)
+    B = 3000                                                  # several sampling workgroups: weights finished by the job
+    m = Mirror(K, N, 1, (4,))
+    m.insert(N, prio=np.zeros((1, N), np.float32))
+    upd_idx = rng.integers(0, N, (1, B)).astype(np.uint32)
+    upd_prio = (rng.random((1, B)) + 0.5).astype(np.float32)
+    u = wl.uniform01(rng, (1, B))
+    rows = [torch.empty((1, B, 4), dtype=torch.uint8, device="cuda")]
+    gi, gw, gv = m.gpu.sample(dev(u), 0.4, rows_out=rows, update=(idx_to_dev(upd_idx), dev(upd_prio)))
+    ci, cw, cv = m.cpu.sample(u, 0.4, True)
+    m.cpu.gather(ci)
+    m.cpu.update(upd_idx, upd_prio)
+    assert np.all(idx_to_host(gi) == 0xFFFFFFFF) and np.array_equal(idx_to_host(gi), ci)
+    assert float(gw.abs().max()) == 0.0 and np.all(cw == 0.0)
+    m.compare_tree()
+    m.compare_status()
+    m.step(wl.WORKLOADS["c3_ddpg"], 2, B=700)                 # and the next step samples the filled tree
+    m.compare_tree()
