@@ -232,7 +232,9 @@ uint64_t per_cursor(const per_t* p);     /* next ring slot                      
 
 /* Checkpoint / resume: a byte copy of the arena plus (cursor, size) is the whole state of a
  * buffer.  After the caller has copied a saved arena back, this sets the host mirrors to the
- * values saved with it.  cursor < N, size <= N. */
+ * values saved with it.  cursor < N, size <= N.  (The last-writer stamps inside a saved arena were
+ * taken from the counter of the buffer that wrote them: the next update after this call clears
+ * the stamp arrays first.) */
 int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
 
 /* Uniforms drawn on the device ("uniformly generated random", Section II-A), for sampling calls that
@@ -250,7 +252,14 @@ uint64_t per_rng_calls(const per_t* p);
  *   "tree_block" : workgroup size of the update's tree pass (multiple of 64, <= 1024; 0 = chosen per launch)
  *   "sample_min_lds" : lower bound in bytes of the sampling kernel's LDS request
  *   "stamp_next" : moves the last-writer stamp counter forward (never back); stamps are 32 bits and
- *                  the library clears the stamp array and starts over when they run out
+ *                  the library clears the stamp array and starts over when they run out; the claim
+ *                  group entries keep 26 of the bits and are cleared whenever a batch would cross a
+ *                  multiple of 2^26
+ *   "group_claim" : how per_update and the fused step find the last writer of a leaf.  0: every element
+ *                  raises the 64-bit stamp of its leaf; 1 (default): every element raises the entry shared
+ *                  by a group of 32 leaves (64 for K = 64), an array small enough to stay in cache, and
+ *                  goes to its leaf's own stamp only when two leaves of one group meet in a batch
+ *                  (batches of 2^26 - 2 elements and more always use form 0)
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
  *                  the next call that reads them; 0 makes per_update finish them itself
  *   "insert_small" : 1 (default) runs an insert of few rows as a single kernel, one workgroup per tree

@@ -251,7 +251,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   }
   if (claim_mode == 1) {   // element s of the update batch is this lane's own sample
     uint32_t mx = 0, flags = 0;
-    if (active) claim_element(g, t, size, c.stamp_base, s, node, upd_v, mx, flags);
+    if (active) claim_element(g, t, size, c.stamp_base, c.group_mode, s, node, upd_v, mx, flags);
     raise_max(g, t, mx, max_seen);
     if (flags) atomicOr(&g.status[t], flags);
   }
@@ -294,9 +294,9 @@ static hipError_t launch_resum_top_k(const Geom& g, const Tuning& tn, uint32_t h
 static hipError_t launch_finish(const Geom& g, const Tuning& tn, const FieldTable* rows, const FinishArgs& a,
                                 hipStream_t s);
 template <int LOGK>
-static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, uint32_t B, hipStream_t s);
+static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s);
 template <int LOGK>
-static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, uint32_t B, const FieldTable* rows,
+static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, const FieldTable* rows,
                                        const FinishArgs& a, hipStream_t s);
 
 // Sampling call with whatever is fused into it.  rows: gather of the sampled rows.  claim: a priority
@@ -386,15 +386,15 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
     a.beta = beta;
     a.parity = parity;
     if (claim_here) {   // second kernel: tree pass beside the weights and the rows
-      if (rows || finish_weights) return launch_tree_finish_k<LOGK>(g, tn, claim->B, rows, a, s);
-      return launch_tree_k<LOGK>(g, tn, claim->B, s);
+      if (rows || finish_weights) return launch_tree_finish_k<LOGK>(g, tn, *claim, rows, a, s);
+      return launch_tree_k<LOGK>(g, tn, *claim, s);
     }
     // second kernel: rows, weights and the claim phase; the tree pass follows
     a.has_claim = claim ? 1u : 0u;
     if (claim) a.claim = *claim;
     e = launch_finish(g, tn, rows, a, s);
     if (e != hipSuccess || !claim) return e;
-    return launch_tree_k<LOGK>(g, tn, claim->B, s);
+    return launch_tree_k<LOGK>(g, tn, *claim, s);
   }
   if (!finish_weights) return e;
   PER_LAUNCH(KID_WEIGHTS, k_weights, dim3((B + 255) / 256, g.T), dim3(256), 0, s, g, B, size, beta, out_w, parity);

@@ -12,16 +12,21 @@ struct SubLevels {
   uint32_t n[kSubSlots];          // real nodes of that height
   uint32_t lds_off[kSubSlots];    // where the workgroup keeps its part of that height (floats)
   uint32_t lds_floats;            // total
+  uint32_t list_cap;              // height-1 nodes under one workgroup root: entries of the workgroup's node list
   uint32_t hb;
+  uint32_t stamp_floor;           // group entries with a stamp at or above this one belong to the batch (kNoGroupStamp: none)
 };
 
 // Tree pass.  Workgroup b of tree t owns the subtree under node b of height hb and keeps the
 // subtree's nodes of heights 1 .. hb in LDS.
-//  0. In one trip it fetches its height-1 nodes and the dirty bits of the leaves below them.
-//  1. Each height-1 node with a dirty leaf is rebuilt by LPS lanes: they read its K leaves and,
-//     for the dirty ones only, the stamp entry, whose lower word is the value of the batch
-//     element that won that leaf; it replaces the leaf (and is stored); the K values are
-//     summed pairwise.  The dirty bits are cleared at the end.
+//  0. In one trip it fetches its height-1 nodes, the dirty bits of the leaves below them and the
+//     entries of their claim groups.
+//  1. Each height-1 node with a claimed leaf (a dirty bit, or the leaf of a group entry written by
+//     this batch) is rebuilt by LPS lanes: they read its K leaves and, for the dirty ones only,
+//     the stamp entry, whose lower word is the value of the batch element that won that leaf; it
+//     replaces the leaf (and is stored), and so does the value of the group entry, which wins
+//     against a dirty bit of the same leaf (it is the latest element of its group); the K values
+//     are summed pairwise.  The dirty bits are cleared at the end.
 //  2. Heights 2 .. hb of the subtree are recomputed from LDS and stored.
 //  3. Above hb every node counts the arrivals of its children's workgroups; the last one to
 //     arrive recomputes it and carries on upwards, so the root is written by whichever
@@ -36,10 +41,12 @@ template <int LOGK>
 __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uint32_t t, uint32_t b, uint32_t chain) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
+  // dynamic LDS: the subtree's nodes, then the list of claimed height-1 nodes (see tree_lds_bytes)
   extern __shared__ __attribute__((aligned(16))) float sub[];   // 16-byte LDS accesses need the alignment
-  __shared__ uint32_t s_list[kDirtyListCap];
-  __shared__ uint32_t s_bits[kDirtyListCap];
-  __shared__ uint32_t s_bits_hi[LOGK == 6 ? kDirtyListCap : 1];
+  uint2* s_entry = reinterpret_cast<uint2*>(sub + (sl.lds_floats + 3u) / 4u * 4u);
+  uint32_t* s_list = reinterpret_cast<uint32_t*>(s_entry + sl.list_cap);
+  uint32_t* s_bits = s_list + sl.list_cap;
+  [[maybe_unused]] uint32_t* s_bits_hi = s_bits + sl.list_cap;   // K = 64 only
   __shared__ uint32_t s_wave[16];
   __shared__ uint32_t s_last;
   const uint32_t hb = sl.hb;
@@ -73,23 +80,45 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
       return (dirty[bit0 >> 5] >> (bit0 & 31u)) & ((1u << K) - 1u);
     }
   };
+  // the claim group entry of a height-1 node if this batch wrote it for a leaf of that node:
+  // (value bits, 0x80000000 | leaf within the node), else y = 0
+  const uint2* groups = g.nclaim + (size_t)t * g.nclaim_stride;
+  const uint32_t floor = sl.stamp_floor;
+  auto node_entry = [&](uint32_t node) -> uint2 {
+    uint2 e = groups[LOGK >= 5 ? node : (node << LOGK) >> 5];
+    bool mine = (e.y >> 6) >= floor;
+    if constexpr (LOGK < 5) mine = mine && ((e.y & 31u) >> LOGK) == (node & ((32u >> LOGK) - 1u));
+    e.y = mine ? 0x80000000u | (e.y & (uint32_t)(K - 1)) : 0u;
+    return e;
+  };
   // one node per thread and sweep; the first sweep's bits are fetched together with the height-1 nodes
   const uint32_t f_first = lo1 + threadIdx.x;
   unsigned long long bits_first = 0;
-  if (f_first < hi1) bits_first = node_bits(f_first);
+  uint2 entry_first = make_uint2(0, 0);
+  if (f_first < hi1) {
+    bits_first = node_bits(f_first);
+    entry_first = node_entry(f_first);
+  }
   for (uint32_t i = threadIdx.x; i < sl.lds_floats; i += blockDim.x) {
     const uint32_t gi = lo1 + i;
     sub[i] = (i < sl.lds_off[1] || hb == 1) && gi < n1_pad ? lvl1[gi] : 0.0f;   // slot 0 from memory, the rest zero
   }
-  // compact the dirty nodes into s_list / s_bits: ballot within the wave, wave totals through LDS
+  // compact the claimed nodes into s_list / s_bits / s_entry: ballot within the wave, wave totals through LDS
   const uint32_t nwaves = blockDim.x >> 6;
   uint32_t nd = 0;
   for (uint32_t f0 = lo1; f0 < hi1; f0 += blockDim.x) {
     const uint32_t f = f0 + threadIdx.x;
     unsigned long long bits = 0;
-    if (f0 == lo1) bits = bits_first;
-    else if (f < hi1) bits = node_bits(f);
-    const unsigned long long m = __ballot(bits != 0);
+    uint2 entry = make_uint2(0, 0);
+    if (f0 == lo1) {
+      bits = bits_first;
+      entry = entry_first;
+    } else if (f < hi1) {
+      bits = node_bits(f);
+      entry = node_entry(f);
+    }
+    const bool listed = bits != 0 || entry.y != 0;
+    const unsigned long long m = __ballot(listed);
     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
     if (lane == 0) s_wave[threadIdx.x >> 6] = (uint32_t)__popcll(m);
     __syncthreads();
@@ -99,9 +128,10 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
       if (wv < (threadIdx.x >> 6)) before += c;
       total += c;
     }
-    if (bits != 0) {
+    if (listed) {
       s_list[before + rank] = f;
       s_bits[before + rank] = (uint32_t)bits;
+      s_entry[before + rank] = entry;
       if constexpr (LOGK == 6) s_bits_hi[before + rank] = (uint32_t)(bits >> 32);
     }
     nd = total;
@@ -120,8 +150,9 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
       size_t at;
       LeafVec c;
       uint2 s[4];
+      uint2 e;
     };
-    // A set bit means the leaf was claimed in this batch: its stamp entry holds the winner's value.
+    // A set bit means the leaf was claimed leaf by leaf in this batch: its stamp entry holds the winner's value.
     auto fetch = [&](uint32_t item) -> Item {
       Item it;
       it.ok = item < nd;
@@ -137,6 +168,7 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
         it.at = (size_t)it.node * K + 4 * q;
       }
       it.c = *reinterpret_cast<const LeafVec*>(leaves + it.at);
+      it.e = s_entry[li];
 #pragma unroll
       for (int k = 0; k < (LOGK == 1 ? 2 : 4); ++k) {
         it.s[k] = make_uint2(0, 0);
@@ -146,15 +178,28 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
     };
     auto finish = [&](Item& it) {
       float sum;
+      // the group entry's leaf, if it is one of this lane's
+      const uint32_t el = it.e.y & 63u;
+      const bool here = it.e.y != 0 && (LOGK == 1 || (el >> 2) == q);
+      const uint32_t sel = here ? 1u << (el & (LOGK == 1 ? 1u : 3u)) : 0u;
+      const float ev = __uint_as_float(it.e.x);
       if constexpr (LOGK == 1) {
         if (it.my & 1u) it.c.x = __uint_as_float(it.s[0].x);
         if (it.my & 2u) it.c.y = __uint_as_float(it.s[1].x);
+        if (sel & 1u) it.c.x = ev;
+        if (sel & 2u) it.c.y = ev;
+        it.my |= sel;
         sum = it.c.x + it.c.y;
       } else {
         if (it.my & 1u) it.c.x = __uint_as_float(it.s[0].x);
         if (it.my & 2u) it.c.y = __uint_as_float(it.s[1].x);
         if (it.my & 4u) it.c.z = __uint_as_float(it.s[2].x);
         if (it.my & 8u) it.c.w = __uint_as_float(it.s[3].x);
+        if (sel & 1u) it.c.x = ev;
+        if (sel & 2u) it.c.y = ev;
+        if (sel & 4u) it.c.z = ev;
+        if (sel & 8u) it.c.w = ev;
+        it.my |= sel;
         sum = (it.c.x + it.c.y) + (it.c.z + it.c.w);
 #pragma unroll
         for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) sum = sum + __shfl_xor(sum, 1 << k);
@@ -215,10 +260,12 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   for (uint32_t i = threadIdx.x; i < nd; i += blockDim.x) {
     const uint32_t node = s_list[i];
     if constexpr (LOGK == 6) {
-      dirty[2 * (size_t)node] = 0;
-      dirty[2 * (size_t)node + 1] = 0;
+      if (s_bits[i] | s_bits_hi[i]) {
+        dirty[2 * (size_t)node] = 0;
+        dirty[2 * (size_t)node + 1] = 0;
+      }
     } else {
-      dirty[(node << LOGK) >> 5] = 0;   // for K < 32 the word is shared with neighbours of the same subtree
+      if (s_bits[i]) dirty[(node << LOGK) >> 5] = 0;   // for K < 32 the word is shared with neighbours of the same subtree
     }
   }
   // ---- 3. above the subtree: the last child to arrive recomputes the parent
@@ -298,14 +345,24 @@ uint32_t lazy_top_height(const Geom& g, const Tuning& tn) {
   return tn.lazy_top && hb < g.H && g.n[hb] <= kLazyTopNodes ? hb : 0u;
 }
 
-// Sub-level descriptors, workgroup size and LDS floats of the tree pass for update batches of B.
+// Dynamic LDS of a tree-pass workgroup: its subtree's nodes (padded to 16 bytes), then per listed
+// height-1 node the group entry (8 bytes), the node number and the dirty bits (4 bytes each; 8 for K = 64).
 template <int LOGK>
-static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, uint32_t B, SubLevels* out, uint32_t* tblock_out) {
+static size_t tree_lds_bytes(const SubLevels& sl) {
+  return ((size_t)(sl.lds_floats + 3u) / 4u * 4u + (size_t)sl.list_cap * (LOGK == 6 ? 5u : 4u)) * 4u;
+}
+
+// Sub-level descriptors and workgroup size of the tree pass for the update batch claimed with `c`.
+template <int LOGK>
+static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, const ClaimArgs& c, SubLevels* out,
+                                  uint32_t* tblock_out) {
   constexpr int K = Fan<LOGK>::K;
+  const uint32_t B = c.B;
   const uint32_t hb = tree_pass_height(g);
   if (hb > (uint32_t)kSubSlots) return hipErrorInvalidValue;   // cannot happen for fanouts and capacities accepted at create
   SubLevels sl{};
   sl.hb = hb;
+  sl.stamp_floor = c.group_mode ? c.stamp_base & kGroupStampMask : kNoGroupStamp;
   uint32_t off = 0;
   for (uint32_t h = 1; h <= hb; ++h) {
     const uint32_t j = h - 1;
@@ -319,6 +376,7 @@ static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, uint32_t B, S
     off += (uint32_t)(full < padded ? full : padded);
   }
   sl.lds_floats = off;
+  sl.list_cap = hb > 1 ? sl.lds_off[1] : 1u;
   // Unless told otherwise: enough lane groups to rebuild in one sweep twice the dirty height-1 nodes a
   // subtree gets on average (never more than it has), so that small batches do not launch idle waves.
   uint32_t tblock = tn.tree_block;
@@ -340,23 +398,23 @@ static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, uint32_t B, S
 }
 
 template <int LOGK>
-static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, uint32_t B, hipStream_t s) {
+static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s) {
   SubLevels sl;
   uint32_t tblock;
-  hipError_t e = tree_pass_shape<LOGK>(g, tn, B, &sl, &tblock);
+  hipError_t e = tree_pass_shape<LOGK>(g, tn, c, &sl, &tblock);
   if (e != hipSuccess) return e;
-  PER_LAUNCH(KID_UPDATE_TREE, k_update_tree<LOGK>, dim3(g.n[sl.hb], g.T), dim3(tblock), (size_t)sl.lds_floats * 4, s, g,
+  PER_LAUNCH(KID_UPDATE_TREE, k_update_tree<LOGK>, dim3(g.n[sl.hb], g.T), dim3(tblock), tree_lds_bytes<LOGK>(sl), s, g,
              sl, lazy_top_height(g, tn) ? 0u : 1u);
   return hipGetLastError();
 }
 
-// The tree pass of an update batch of B together with the weights and row jobs in `a` / `rows`.
+// The tree pass of the update batch claimed with `c` together with the weights and row jobs in `a` / `rows`.
 template <int LOGK>
-static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, uint32_t B, const FieldTable* rows,
+static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, const FieldTable* rows,
                                        const FinishArgs& a, hipStream_t s) {
   SubLevels sl;
   uint32_t tblock;
-  hipError_t e = tree_pass_shape<LOGK>(g, tn, B, &sl, &tblock);
+  hipError_t e = tree_pass_shape<LOGK>(g, tn, c, &sl, &tblock);
   if (e != hipSuccess) return e;
   if (tblock > 512) tblock = 512;   // half the lanes of a compute unit are left to the other jobs
   FieldTable ft{};
@@ -364,7 +422,7 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, uint32_t
   const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u);
   const uint32_t tree_blocks = g.n[sl.hb];
   PER_LAUNCH(KID_TREE_FINISH, k_tree_finish<LOGK>, dim3(tree_blocks + jr.first[2 + kMaxFields], g.T), dim3(tblock),
-             (size_t)sl.lds_floats * 4, s, g, sl, lazy_top_height(g, tn) ? 0u : 1u, tree_blocks, ft, jr, a);
+             tree_lds_bytes<LOGK>(sl), s, g, sl, lazy_top_height(g, tn) ? 0u : 1u, tree_blocks, ft, jr, a);
   return hipGetLastError();
 }
 
@@ -374,7 +432,7 @@ static hipError_t launch_update_k(const Geom& g, const Tuning& tn, const ClaimAr
   PER_LAUNCH(KID_UPDATE_CLAIM, k_update_claim, dim3((c.B + block - 1) / block, g.T), dim3(block), 0, s, g, c);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return launch_tree_k<LOGK>(g, tn, c.B, s);
+  return launch_tree_k<LOGK>(g, tn, c, s);
 }
 
 hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s) {

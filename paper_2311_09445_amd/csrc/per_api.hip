@@ -20,6 +20,8 @@ struct per_buffer {
   uint64_t col_stride[kMaxFields];
   uint64_t cursor, size;
   uint64_t stamp_next;       // next unused last-writer stamp (stamps 1 .. 2^32-1)
+  bool groups_stale;         // the claim group entries are to be cleared before their next use
+  bool leaves_stale;         // and so are the per-leaf stamps (an arena copied back may hold stamps of another counter)
   uint32_t weight_calls;     // number of per_sample calls that used the partial-minimum buffers
   uint32_t stale_hb;         // != 0: the last update left the heights above this one to their next reader
   bool rng_on;               // per_set_rng was called: sampling calls without uniforms draw their own
@@ -39,10 +41,10 @@ struct Layout {
   uint32_t n[kMaxHeight + 1];
   uint32_t stride[kMaxHeight + 1];
   size_t level_off[kMaxHeight + 1];
-  size_t scalars_off, owner_off, dirty_off, arrive_off, col_off[kMaxFields];
+  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, col_off[kMaxFields];
   uint32_t dirty_stride, arrive_stride, arrive_level_off[kMaxHeight + 1];
   uint64_t col_stride[kMaxFields];
-  uint32_t owner_stride;
+  uint32_t owner_stride, nclaim_stride;
   size_t tree_end;            // bytes up to here are zero-filled as 32-bit words at create
   size_t total;
 };
@@ -84,6 +86,10 @@ void make_layout(const per_config* c, Layout* L) {
   L->owner_stride = (uint32_t)round_up(c->capacity, 64);
   L->owner_off = off;
   off = round_up(off + (size_t)L->owner_stride * T * 8, kAlign);
+  // one claim entry per 32 (padded) leaves, per 64 for K = 64
+  L->nclaim_stride = (uint32_t)round_up(((size_t)L->n[1] * K + (K == 64 ? 63 : 31)) / (K == 64 ? 64 : 32), 64);
+  L->nclaim_off = off;
+  off = round_up(off + (size_t)L->nclaim_stride * T * 8, kAlign);
   L->dirty_stride = (uint32_t)round_up(((size_t)L->n[1] * K + 31) / 32, 64);   // one bit per (padded) leaf
   L->dirty_off = off;
   off = round_up(off + (size_t)L->dirty_stride * T * 4, kAlign);
@@ -181,6 +187,8 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.root_stride = g.stride[L.H];
   g.owner = reinterpret_cast<uint64_t*>(p->arena + L.owner_off);
   g.owner_stride = L.owner_stride;
+  g.nclaim = reinterpret_cast<uint2*>(p->arena + L.nclaim_off);
+  g.nclaim_stride = L.nclaim_stride;
   g.dirty = reinterpret_cast<uint32_t*>(p->arena + L.dirty_off);
   g.dirty_stride = L.dirty_stride;
   g.arrive = reinterpret_cast<uint32_t*>(p->arena + L.arrive_off);
@@ -201,9 +209,11 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.lazy_top = 1;
   p->tn.claim_in_sample = 1;
   p->tn.insert_small = 1;
+  p->tn.group_claim = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->stamp_next = 1;
+  p->groups_stale = p->leaves_stale = false;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -273,16 +283,40 @@ int per_insert_protected(per_t* p, uint32_t n, const void* const* d_field_src, c
   return insert_impl(p, n, d_field_src, d_prio, d_out_idx, n_protect, d_protect_idx, stream);
 }
 
-// Takes the stamps of one update batch from the host counter (clearing the stamp array when the
-// 32-bit stamps run out).
-static int reserve_stamps(per_t* p, uint32_t B, hipStream_t s, uint32_t* base) {
-  if (p->stamp_next + B > 0xFFFFFFFFull) {
-    hipError_t e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(p->g.owner), 2ull * p->g.owner_stride * p->g.T, 0u, s);
-    if (e != hipSuccess) return PER_EHIP;
-    p->stamp_next = 1;
+// Takes the stamps of one update batch from the host counter and decides how the batch claims its leaves.
+// The group entries keep the low kGroupStampBits bits of a stamp, so no batch that could use them crosses
+// a multiple of 2^kGroupStampBits (a span): it moves to the start of the next span instead, and the
+// entries, whose stamps would otherwise look recent there, are cleared.  The leaf stamps are cleared when
+// the 32-bit stamps run out.  Stamp 0 (and low bits 0) is never handed out: it marks a cleared entry.
+static int reserve_stamps(per_t* p, uint32_t B, hipStream_t s, ClaimArgs* c) {
+  const Geom& g = p->g;
+  const bool fits_span = B <= kGroupStampMask - 1;
+  uint64_t next = p->stamp_next;
+  bool clear_groups = p->groups_stale, clear_leaves = p->leaves_stale;
+  if (fits_span) {
+    if ((next & kGroupStampMask) == 0) ++next;
+    if ((next & kGroupStampMask) + B > kGroupStampMask) {
+      next = (next | kGroupStampMask) + 2;
+      clear_groups = true;
+    }
+  } else {
+    clear_groups = true;   // this batch runs through spans; the next one starts a fresh span (below)
   }
-  *base = (uint32_t)p->stamp_next;
-  p->stamp_next += B;
+  if (next + B > 0xFFFFFFFFull) {
+    next = 1;
+    clear_groups = clear_leaves = true;
+  }
+  hipError_t e = hipSuccess;
+  if (clear_leaves) e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(g.owner), 2ull * g.owner_stride * g.T, 0u, s);
+  if (e == hipSuccess && clear_groups)
+    e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(g.nclaim), 2ull * g.nclaim_stride * g.T, 0u, s);
+  if (e != hipSuccess) return PER_EHIP;
+  p->groups_stale = p->leaves_stale = false;
+  c->stamp_base = (uint32_t)next;
+  c->group_mode = fits_span && p->tn.group_claim ? 1u : 0u;
+  next += B;
+  if (!fits_span) next = ((next - 1) | kGroupStampMask) + 2;
+  p->stamp_next = next;
   return PER_OK;
 }
 
@@ -322,7 +356,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
     claim.size = (uint32_t)p->size;
     claim.idx = d_upd_idx;
     claim.prio = d_upd_prio;
-    int rc = reserve_stamps(p, upd_B, s, &claim.stamp_base);
+    int rc = reserve_stamps(p, upd_B, s, &claim);
     if (rc != PER_OK) return rc;
     // The claim phase reads the update batch.  It may run inside the sampling kernel when that
     // kernel does not write what it reads: the batch is either the sampled batch itself (same
@@ -397,7 +431,7 @@ int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio,
   claim.size = (uint32_t)p->size;
   claim.idx = d_idx;
   claim.prio = d_prio;
-  rc = reserve_stamps(p, B, s, &claim.stamp_base);
+  rc = reserve_stamps(p, B, s, &claim);
   if (rc != PER_OK) return rc;
   hipError_t e = launch_update(p->g, p->tn, claim, s);
   if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
@@ -418,7 +452,7 @@ int per_update_td(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_td
   claim.from_td = 1;
   claim.td_eps = eps;
   claim.td_alpha = alpha;
-  rc = reserve_stamps(p, B, s, &claim.stamp_base);
+  rc = reserve_stamps(p, B, s, &claim);
   if (rc != PER_OK) return rc;
   hipError_t e = launch_update(p->g, p->tn, claim, s);
   if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
@@ -533,6 +567,7 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size) {
   p->cursor = cursor;
   p->size = size;
   p->stale_hb = lazy_top_height(p->g, p->tn);   // a saved arena may predate the rebuild of its top heights
+  p->groups_stale = p->leaves_stale = true;     // and its last-writer stamps belong to the counter it was saved under
   return PER_OK;
 }
 
@@ -555,6 +590,7 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   }
   if (!strcmp(name, "stamp_next")) {   // test hook: move the last-writer stamp counter (e.g. close to its wrap)
     if (value < (int64_t)p->stamp_next || value > 0xFFFFFFFFll) return PER_EINVAL;
+    if ((uint64_t)value >> kGroupStampBits != p->stamp_next >> kGroupStampBits) p->groups_stale = true;
     p->stamp_next = (uint64_t)value;
     return PER_OK;
   }
@@ -571,6 +607,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "insert_small")) {
     if (value != 0 && value != 1) return PER_EINVAL;
     p->tn.insert_small = (uint32_t)value;
+    return PER_OK;
+  }
+  if (!strcmp(name, "group_claim")) {
+    if (value != 0 && value != 1) return PER_EINVAL;
+    p->tn.group_claim = (uint32_t)value;
     return PER_OK;
   }
   if (!strcmp(name, "claim_in_sample")) {

@@ -27,6 +27,8 @@ struct Geom {
   uint32_t root_stride;             // == stride[H]
   uint64_t* owner;                  // [T][owner_stride] last-writer stamps: (stamp << 32) | fp32 bits of the value
   uint32_t owner_stride;
+  uint2*   nclaim;                  // [T][nclaim_stride] group entries of the claim phase: (value bits, stamp << 6 | slot)
+  uint32_t nclaim_stride;
   uint32_t* dirty;                  // [T][dirty_stride] words of one bit per leaf: the leaf was claimed by the current update
   uint32_t dirty_stride;
   uint32_t* arrive;                 // [T][arrive_stride] arrival counters of the nodes of heights >= 2
@@ -46,9 +48,16 @@ struct FieldTable {
   uint32_t n_fields;
 };
 
+// Stamps of the claim phase.  A batch takes consecutive 32-bit stamps; the group entries keep the low
+// kGroupStampBits bits only, so a batch that uses them never crosses a multiple of 2^kGroupStampBits.
+constexpr uint32_t kGroupStampBits = 26;
+constexpr uint32_t kGroupStampMask = (1u << kGroupStampBits) - 1u;
+constexpr uint32_t kNoGroupStamp = 0xFFFFFFFFu;   // floor above every group stamp: no group entry counts
+
 // Claim phase of a priority update (first half of per_update).
 struct ClaimArgs {
   uint32_t B, size, stamp_base;
+  uint32_t group_mode;     // the batch claims through the group entries (else leaf by leaf)
   const uint32_t* idx;     // [T][B]
   const float* prio;       // [T][B] tree values, or temporal-difference errors when from_td is set
   uint32_t from_td;        // value = (|prio| + td_eps)^td_alpha, fp64, rounded once
@@ -133,6 +142,7 @@ struct Tuning {
   uint32_t lazy_top;   // updates may leave the few topmost heights to their next reader
   uint32_t insert_small;      // small inserts run as one kernel (one workgroup per tree)
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
+  uint32_t group_claim;       // update batches claim through the group entries whenever their stamps fit one span
   Profiler* prof;
 };
 

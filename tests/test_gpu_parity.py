@@ -26,6 +26,21 @@ def log(msg):
     print(msg, flush=True)
 
 
+@pytest.fixture(autouse=True, params=["group", "leaf"])
+def claim_form(request, monkeypatch):
+    """Every test runs twice: update batches claim their leaves through the group entries (the default)
+    or leaf by leaf."""
+    if request.param == "leaf":
+        created = PrioritizedReplay.__init__
+
+        def create_then_set(self, *a, **kw):
+            created(self, *a, **kw)
+            self.set_tuning("group_claim", 0)
+
+        monkeypatch.setattr(PrioritizedReplay, "__init__", create_then_set)
+    return request.param
+
+
 # ------------------------------------------------------------------ small, every fanout
 @pytest.mark.parametrize("K", [2, 4, 8, 16, 32, 64])
 @pytest.mark.parametrize("N,T", [(1, 1), (5, 2), (1000, 1), (4097, 3), (70000, 1)])
@@ -113,6 +128,68 @@ def test_last_writer_stamps_wrap_around():
     for it in range(4):        # the third call no longer fits below 2^32
         m.update(rng.integers(0, 200, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
         m.compare_tree()
+    m.compare_status()
+
+
+def test_group_stamps_cross_their_span():
+    """The group entries keep 26 bits of a stamp: a batch that would cross a multiple of 2^26 moves to the next
+    span and the entries are cleared; entries left by earlier batches must never count for a later one."""
+    rng = np.random.default_rng(11)
+    N, T, B = 20000, 2, 3000
+    for K in (4, 32, 64):
+        m = Mirror(K, N, T, ())
+        m.insert(N, prio=rng.random((T, N)).astype(np.float32), with_rows=False)
+        m.gpu.set_tuning("stamp_next", (1 << 26) - 2 * B - 5)
+        for it in range(5):        # the third call no longer fits below 2^26
+            idx = rng.integers(0, 200 if it % 2 else N, (T, B)).astype(np.uint32)
+            m.update(idx, rng.random((T, B)).astype(np.float32))
+            m.compare_tree()
+        m.gpu.set_tuning("stamp_next", 3 << 26)   # low bits zero: not a stamp
+        m.update(rng.integers(0, 200, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
+        m.compare_tree()
+        m.compare_status()
+
+
+@pytest.mark.parametrize("K", [2, 16, 32, 64])
+def test_claim_forms_alternate_on_one_buffer(K):
+    """Batches that claim leaf by leaf and batches that claim through group entries follow one another on
+    the same few groups: what one form leaves behind must not count for the other."""
+    log(f"alternating claim forms K={K}")
+    rng = np.random.default_rng(K + 100)
+    N, T, B = 3000, 2, 700
+    m = Mirror(K, N, T, ())
+    m.insert(N, prio=np.ones((T, N), np.float32), with_rows=False)
+    for it in range(12):
+        m.gpu.set_tuning("group_claim", 1 if it % 3 else 0)
+        hi = [N, 70, 33, 130][it % 4]
+        idx = rng.integers(0, hi, (T, B)).astype(np.uint32)
+        if it % 5 == 4:
+            idx[:, ::2] = idx[:, 0:1]          # half the batch on one leaf
+        m.update(idx, rng.random((T, B)).astype(np.float32))
+        m.compare_tree()
+    m.compare_status()
+
+
+def test_resume_in_a_fresh_buffer():
+    """A byte copy of the arena plus (cursor, size) is the whole state: copied into a buffer created
+    afterwards (whose stamp counter starts over) the next updates must still find the last writers."""
+    rng = np.random.default_rng(21)
+    K, N, T, B = 16, 6000, 2, 900
+    m = Mirror(K, N, T, FIELDS)
+    m.insert(5000, prio=rng.random((T, 5000)).astype(np.float32))
+    for it in range(3):
+        m.update(rng.integers(0, 300, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
+    saved, cursor, size = m.gpu.arena.clone(), m.gpu.cursor, m.gpu.size
+    fresh = PrioritizedReplay(K, N, T, FIELDS)
+    fresh.arena.copy_(saved)
+    fresh.set_ring(cursor, size)
+    m.gpu = fresh
+    for it in range(3):
+        m.update(rng.integers(0, 300, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
+        m.compare_tree()
+    gi, ci = m.sample(wl.uniform01(rng, (T, 257)), beta=0.5, fused_rows=True)
+    m.insert(2000)
+    m.compare_tree()
     m.compare_status()
 
 
