@@ -384,7 +384,36 @@ def main():
         step_stream = {"ms_per_step": round(ms_stream, 5), "value": round(T * B / (ms_stream * 1e-3), 1),
                        "unit": "transitions/s", "launches": 1, "steps_per_launch": steps,
                        "call": "per_run_steps (tree held in LDS, one workgroup per tree)"}
-        del o_idx, o_w, o_v, o_rows
+
+        # the same steps once more as a queue of op-coded requests (insert, sample, update per step)
+        from paper_2311_09445_amd.per import OP_INSERT, OP_SAMPLE, OP_UPDATE
+
+        def queue(lo, hi):
+            q = []
+            for s in range(lo, hi):
+                if w.n_insert:
+                    q.append({"op": OP_INSERT, "n": w.n_insert, "rows": None if i_rows is None else [r[s] for r in i_rows]})
+                q.append({"op": OP_SAMPLE, "u": d_u[s], "beta": float(inputs[s]["beta"]), "idx": o_idx[s],
+                          "out_weight": None if o_w is None else o_w[s], "out_prio": o_v[s], "rows": [r[s] for r in o_rows]})
+                q.append({"op": OP_UPDATE, "idx": d_upd_idx[s], "prio": d_prio[s]})
+            return q
+
+        restore()
+        o_idx.zero_()
+        keep = [buf.run_requests(queue(0, warmup))]
+        timed_queue = buf.prepare_requests(queue(warmup, total_steps))   # encoded and copied to the device beforehand
+        torch.cuda.synchronize()
+        s0.record(stream)
+        keep.append(buf.run_requests(timed_queue))
+        s1.record(stream)
+        torch.cuda.synchronize()
+        ms_queue = s0.elapsed_time(s1) / steps
+        assert np.array_equal(o_idx.cpu().numpy().view(np.uint32), rec_idx), "request queue diverged from the separate calls"
+        assert buf.total().cpu().numpy().tobytes() == final_root.tobytes(), "request queue ended in a different state"
+        step_stream["request_queue"] = {
+            "ms_per_step": round(ms_queue, 5), "requests": timed_queue[0],
+            "call": "per_run_requests (the same steps as a queue of op-coded requests, one launch)"}
+        del o_idx, o_w, o_v, o_rows, keep
 
     # what a plain streaming device copy reaches on this GPU in this run (read + written bytes per second)
     src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")

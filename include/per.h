@@ -207,6 +207,46 @@ typedef struct {
 int per_run_steps(per_t* p, uint32_t n_steps, uint32_t n_insert, uint32_t B, const per_stream_io* io, void* stream);
 int per_run_steps_fits(const per_t* p);   /* 1: the trees of this buffer fit, 0: they do not */
 
+/* A queue of op-coded requests in one launch (Section V-A, "RM on FPGA": the requests fed to the Replay
+ * Manager carry a unified operation code and are decoded and executed as they stream in, by kernels
+ * that are started once).  As per_run_steps: for buffers whose trees fit the LDS of a compute unit, one
+ * workgroup per tree loads the tree, works through the queue in order against the LDS copy and stores
+ * the tree back.  Request r is one of
+ *   PER_OP_INSERT : per_insert of n rows (per_insert_protected when protect is given): field[f] are the
+ *                   sources [T][n][bytes] (NULL entries skipped), prio [T][n] or NULL (running maximum),
+ *                   idx receives the slots [T][n] (or NULL), protect [T][n_protect] or NULL
+ *   PER_OP_SAMPLE : per_sample_gather of n samples: u [T][n] uniforms, beta, idx receives the indices
+ *                   [T][n], out_weight / out_prio [T][n] or NULL, field[f] the destinations
+ *                   [T][n][bytes] of the gathered rows (NULL entries skipped)
+ *   PER_OP_UPDATE : per_update of n elements: idx [T][n] (NULL: the indices sampled by the latest SAMPLE
+ *                   request of this queue, whose n must be the same), prio [T][n]
+ * with the results of those calls issued one after the other.  1 <= n <= 1024.  All pointers are
+ * device pointers; a field pointer must be aligned to the largest power of two (at most 16) that
+ * divides the field's row size.
+ *   h_requests : HOST array of n_requests requests: the call checks the arguments on it and derives the
+ *                ring state (cursor, size) from it; read during the call only
+ *   d_requests : the same queue in DEVICE memory (8-byte aligned), placed there by the caller: this is
+ *                what the kernel decodes; it stays untouched until the work on `stream` is done
+ * PER_ERANGE: a tree does not fit (per_run_steps_fits) or a count is out of range; PER_EINVAL:
+ * unknown operation code, missing or misaligned pointer; PER_EEMPTY: a SAMPLE request would meet an
+ * empty buffer.  Nothing is enqueued on an error. */
+enum { PER_OP_INSERT = 1, PER_OP_SAMPLE = 2, PER_OP_UPDATE = 3 };
+typedef struct per_request {
+  uint32_t op;                   /* PER_OP_*                                                    */
+  uint32_t n;                    /* rows, samples or elements per tree                          */
+  float beta;                    /* SAMPLE: exponent of the importance weights                  */
+  uint32_t n_protect;            /* INSERT: entries per tree of protect                         */
+  const float* prio;             /* INSERT: values or NULL; UPDATE: new values                  */
+  const float* u;                /* SAMPLE: uniforms in [0,1)                                   */
+  uint32_t* idx;                 /* INSERT: slots out; SAMPLE: indices out; UPDATE: indices in  */
+  float* out_weight;             /* SAMPLE, or NULL                                             */
+  float* out_prio;               /* SAMPLE, or NULL                                             */
+  const uint32_t* protect;       /* INSERT: slots not to be overwritten, or NULL                */
+  void* field[PER_MAX_FIELDS];   /* INSERT: row sources; SAMPLE: row destinations               */
+} per_request;
+int per_run_requests(per_t* p, uint32_t n_requests, const per_request* h_requests, const per_request* d_requests,
+                     void* stream);
+
 /* Priority retrieval (Section V-A): d_out[t][i] = leaf d_idx[t][i]. */
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream);
 

@@ -55,10 +55,162 @@ __device__ __forceinline__ void resum_paths_lds(float* tree, const uint32_t* off
   }
 }
 
+// One tree in the LDS of its workgroup, and the few words the operations below share.
+struct LdsTree {
+  float* tree;              // heights 0 .. H back to back, zero padding included
+  const uint32_t* off;      // off[h]: where height h starts (floats); off[H + 1]: all floats
+  uint32_t* sampled;        // [1024] indices of the latest sampling operation
+  uint32_t* max_bits;       // running maximum priority (fp32 bits)
+  uint32_t* vmin_bits;      // minimum of the batch being sampled (fp32 bits)
+  uint32_t* skip;           // [32] bit j: row j of the insertion under way is deferred
+  uint32_t H, N;
+};
+
+// The three operations are called by all 1024 lanes of the workgroup.  Each leaves the tree
+// consistent, but its last phase may still be under way in other waves when it returns: the next
+// operation starts with a barrier of its own (lds_sample), or the caller places one.
+
+// Insertion of n <= 1024 rows: rows, leaves (given value, or the running maximum on entry), ancestors.
+// prio, out_idx and protect point at this tree's part (or are null).
+template <int LOGK>
+__device__ __forceinline__ void lds_insert(const LdsTree& lt, const FieldTable& rows, uint32_t t, uint64_t dense_row0,
+                                           uint32_t n, const float* prio, uint32_t* out_idx, const uint32_t* protect,
+                                           uint32_t n_protect, uint32_t& cursor, uint32_t& size, uint32_t& flags) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t N = lt.N;
+  if (protect) {   // collision-free insertion: rows aimed at a protected slot are deferred (see k_insert_small)
+    if (tid < 32) lt.skip[tid] = 0;
+    __syncthreads();
+    for (uint32_t k = tid; k < n_protect; k += blockDim.x) {
+      const uint32_t i = protect[k];
+      if (i < N) {
+        const uint32_t j = i >= cursor ? i - cursor : i + (N - cursor);   // position in the ring window
+        if (j < n) atomicOr(&lt.skip[j >> 5], 1u << (j & 31u));
+      }
+    }
+    __syncthreads();
+  }
+  (void)move_rows_one_workgroup<false>(rows, t, dense_row0, n, cursor, N, nullptr, protect ? lt.skip : nullptr);
+  __syncthreads();   // (also: the tree is loaded, the operation before this one is complete)
+  const float max_on_entry = __uint_as_float(*lt.max_bits);
+  __syncthreads();
+  bool ok = false;
+  uint32_t slot = 0;
+  if (tid < n) {
+    uint64_t sl = (uint64_t)cursor + tid;
+    if (sl >= N) sl -= N;
+    slot = (uint32_t)sl;
+    const bool deferred = protect && ((lt.skip[tid >> 5] >> (tid & 31u)) & 1u);
+    if (out_idx) out_idx[tid] = deferred ? 0xFFFFFFFFu : slot;
+    if (!deferred) {
+      float v = max_on_entry;
+      ok = true;
+      if (prio) {
+        v = prio[tid];
+        ok = valid_priority(v);
+        if (ok && v > 0.0f) atomicMax(lt.max_bits, __float_as_uint(v));
+        if (!ok) flags |= 2u;
+      }
+      if (ok) lt.tree[lt.off[0] + slot] = v;
+    }
+  }
+  resum_paths_lds<LOGK>(lt.tree, lt.off, lt.H, ok, slot);
+  const uint64_t end = (uint64_t)cursor + n;
+  cursor = (uint32_t)(end >= N ? end - N : end);
+  size = size + n > N ? N : size + n;
+}
+
+// Priority sampling of B <= 1024 indices with importance weights, and the rows of the sampled
+// indices.  u_i: this lane's uniform (lanes >= B: any value).  out_idx (never null), out_w, out_prio
+// point at this tree's part.  Returns this lane's index.
+template <int LOGK>
+__device__ __forceinline__ uint32_t lds_sample(const LdsTree& lt, const FieldTable& rows, uint32_t t, uint64_t dense_row0,
+                                               uint32_t B, float u_i, float beta, uint32_t* out_idx, float* out_w,
+                                               float* out_prio, uint32_t& flags) {
+  constexpr int K = Fan<LOGK>::K;
+  const uint32_t tid = threadIdx.x;
+  if (tid == 0) *lt.vmin_bits = 0x7F800000u;
+  __syncthreads();
+  const float total = lt.tree[lt.off[lt.H]];
+  uint32_t node = 0xFFFFFFFFu;
+  float val = 0.0f;
+  if (total > 0.0f) {
+    const uint32_t si = tid < B ? tid : B - 1;
+    float r = ((float)si + u_i) * (total / (float)B);
+    node = 0;
+    val = total;
+    for (uint32_t h = lt.H; h-- > 0;) {
+      unsigned child;
+      descend_lane<LOGK>(lt.tree + lt.off[h] + (size_t)node * K, r, child, val);
+      node = node * K + child;
+    }
+    if (out_w && tid < B) atomicMin(lt.vmin_bits, __float_as_uint(val));
+  } else if (tid == 0) {
+    flags |= 4u;
+  }
+  if (tid < B) {
+    lt.sampled[tid] = node;
+    out_idx[tid] = node;
+    if (out_prio) out_prio[tid] = val;
+  }
+  __syncthreads();
+  // (the weights, a power per sample, are computed while the rows are on their way: every lane that
+  // owns a sample also owns a row element of the first sweep, so no wave runs the power twice)
+  auto weights = [&]() {
+    if (out_w && tid < B) out_w[tid] = total > 0.0f ? importance_weight(val, __uint_as_float(*lt.vmin_bits), beta) : 0.0f;
+  };
+  if (move_rows_one_workgroup<true>(rows, t, dense_row0, B, 0, lt.N, lt.sampled, nullptr, weights)) flags |= 1u;
+  return node;
+}
+
+// Priority update of B <= 1024 elements: lane tid < B sets leaf i to v.  Last writer by LDS
+// atomics (see the head of this file), then the ancestors.
+template <int LOGK>
+__device__ __forceinline__ void lds_update(const LdsTree& lt, uint32_t B, uint32_t i, float v, uint32_t size,
+                                           uint32_t& flags) {
+  const uint32_t tid = threadIdx.x;
+  uint32_t* leaf_bits = reinterpret_cast<uint32_t*>(lt.tree + lt.off[0]);
+  bool valid = false;
+  if (tid < B) {
+    if (!(i < size)) flags |= 1u;
+    else if (!valid_priority(v)) flags |= 2u;
+    else valid = true;
+  }
+  const uint32_t mark = 0x80000001u + tid;
+  if (valid) atomicMax(&leaf_bits[i], mark);
+  __syncthreads();
+  const bool won = valid && leaf_bits[i] == mark;
+  __syncthreads();
+  if (won) lt.tree[lt.off[0] + i] = v;
+  if (valid && v > 0.0f) atomicMax(lt.max_bits, __float_as_uint(v));
+  resum_paths_lds<LOGK>(lt.tree, lt.off, lt.H, valid, i);
+}
+
+// Loads every height of tree t into LDS (lanes 64 .. 64 + H + 1 have filled s_off, lane 0 the maximum).
+__device__ __forceinline__ void lds_tree_load(const LevelTable& tab, const LdsTree& lt) {
+  for (uint32_t h = 0; h <= lt.H; ++h) {   // the whole tree, zero padding included
+    const float* lvl = tab.lvl[h];
+    float* dst = lt.tree + lt.off[h];
+    for (uint32_t e = threadIdx.x; e < lt.off[h + 1] - lt.off[h]; e += blockDim.x) dst[e] = lvl[e];
+  }
+}
+// ... and back to memory, with the running maximum and the flags the lanes have collected.
+__device__ __forceinline__ void lds_tree_store(const Geom& g, uint32_t t, const LevelTable& tab, const LdsTree& lt,
+                                               uint32_t flags, uint32_t* s_flags) {
+  for (uint32_t h = 0; h <= lt.H; ++h) {
+    float* lvl = tab.lvl[h];
+    const float* src = lt.tree + lt.off[h];
+    for (uint32_t e = threadIdx.x; e < tab.n[h]; e += blockDim.x) lvl[e] = src[e];
+  }
+  if (threadIdx.x == 0) g.max_v[t] = __uint_as_float(*lt.max_bits);
+  if (flags) atomicOr(s_flags, flags);
+  __syncthreads();
+  if (threadIdx.x == 0 && *s_flags) atomicOr(&g.status[t], *s_flags);
+}
+
 template <int LOGK>
 __global__ void __launch_bounds__(1024)
 k_run_steps(StreamKernelArgs ka) {
-  constexpr int K = Fan<LOGK>::K;
   const Geom& g = ka.g;
   const StreamArgs& a = ka.a;
   extern __shared__ __attribute__((aligned(16))) float tree[];
@@ -67,7 +219,7 @@ k_run_steps(StreamKernelArgs ka) {
   __shared__ uint32_t s_max, s_vmin, s_flags;
   const uint32_t t = blockIdx.x;
   const uint32_t tid = threadIdx.x;
-  const uint32_t H = g.H, N = g.N, T = g.T, B = a.B, n_ins = a.n_insert;
+  const uint32_t H = g.H, T = g.T, B = a.B, n_ins = a.n_insert;
   fill_level_table(H, t, &tab);
   if (tid >= 64 && tid <= 64 + H + 1)
     s_off[tid - 64] = kernarg_at<StreamArgs>(offsetof(StreamKernelArgs, a))->off[tid - 64];
@@ -76,132 +228,120 @@ k_run_steps(StreamKernelArgs ka) {
     s_flags = 0;
   }
   __syncthreads();
-  for (uint32_t h = 0; h <= H; ++h) {   // the whole tree, zero padding included
-    const float* lvl = tab.lvl[h];
-    float* dst = tree + s_off[h];
-    for (uint32_t e = tid; e < s_off[h + 1] - s_off[h]; e += blockDim.x) dst[e] = lvl[e];
-  }
-  uint32_t* s_idx = reinterpret_cast<uint32_t*>(tree + s_off[H + 1]);   // indices sampled in the current step
-  uint32_t* leaf_bits = reinterpret_cast<uint32_t*>(tree + s_off[0]);
+  LdsTree lt;
+  lt.tree = tree;
+  lt.off = s_off;
+  lt.sampled = reinterpret_cast<uint32_t*>(tree + s_off[H + 1]);
+  lt.max_bits = &s_max;
+  lt.vmin_bits = &s_vmin;
+  lt.skip = nullptr;
+  lt.H = H;
+  lt.N = g.N;
+  lds_tree_load(tab, lt);
   uint32_t cursor = a.cursor, size = a.size;
   uint32_t flags = 0;
-  PER_TRACE_DECL;
 
   for (uint32_t s = 0; s < a.n_steps; ++s) {
-    PER_MARK(0);
-    const size_t bo = ((size_t)s * T + t) * B + tid;
+    const size_t bo = ((size_t)s * T + t) * B;
     // inputs of this step, fetched before the tree work
     float u_i = 0.0f, up_v = 0.0f;
     uint32_t up_i = 0;
     if (tid < B) {
-      u_i = a.u[bo];
+      u_i = a.u[bo + tid];
       if (a.upd_prio) {
-        up_v = a.upd_prio[bo];
-        if (!a.upd_is_sampled) up_i = a.upd_idx[bo];
+        up_v = a.upd_prio[bo + tid];
+        if (!a.upd_is_sampled) up_i = a.upd_idx[bo + tid];
       }
     }
     const float beta = a.beta[s];
-
-    // ---- insertion: rows, leaves (given value or the running maximum on entry), ancestors
     if (n_ins) {
-      (void)move_rows_one_workgroup<false>(a.ins, t, ((uint64_t)s * T + t) * n_ins, n_ins, cursor, N, nullptr);
-      __syncthreads();   // (also: the tree is loaded, the last step's update is complete)
-      const float max_on_entry = __uint_as_float(s_max);
-      __syncthreads();
-      bool ok = false;
-      uint32_t slot = 0;
-      if (tid < n_ins) {
-        uint64_t sl = (uint64_t)cursor + tid;
-        if (sl >= N) sl -= N;
-        slot = (uint32_t)sl;
-        float v = max_on_entry;
-        ok = true;
-        if (a.ins_prio) {
-          v = a.ins_prio[((size_t)s * T + t) * n_ins + tid];
-          ok = valid_priority(v);
-          if (ok && v > 0.0f) atomicMax(&s_max, __float_as_uint(v));
-          if (!ok) flags |= 2u;
-        }
-        if (ok) tree[s_off[0] + slot] = v;
-      }
-      resum_paths_lds<LOGK>(tree, s_off, H, ok, slot);
-      const uint64_t end = (uint64_t)cursor + n_ins;
-      cursor = (uint32_t)(end >= N ? end - N : end);
-      size = size + n_ins > N ? N : size + n_ins;
+      const uint64_t io = ((uint64_t)s * T + t) * n_ins;
+      lds_insert<LOGK>(lt, a.ins, t, io, n_ins, a.ins_prio ? a.ins_prio + io : nullptr, nullptr, nullptr, 0, cursor, size,
+                       flags);
     }
-    if (tid == 0) s_vmin = 0x7F800000u;
+    const uint32_t node = lds_sample<LOGK>(lt, a.rows, t, ((uint64_t)s * T + t) * B, B, u_i, beta, a.out_idx + bo,
+                                           a.out_w ? a.out_w + bo : nullptr, a.out_prio ? a.out_prio + bo : nullptr, flags);
+    if (a.upd_prio) lds_update<LOGK>(lt, B, a.upd_is_sampled ? node : up_i, up_v, size, flags);
     __syncthreads();
-    PER_MARK(1);
-
-    // ---- priority sampling and importance weights
-    const float total = tree[s_off[H]];
-    uint32_t node = 0xFFFFFFFFu;
-    float val = 0.0f;
-    if (total > 0.0f) {
-      const uint32_t si = tid < B ? tid : B - 1;
-      float r = ((float)si + u_i) * (total / (float)B);
-      node = 0;
-      val = total;
-      for (uint32_t h = H; h-- > 0;) {
-        unsigned child;
-        descend_lane<LOGK>(tree + s_off[h] + (size_t)node * K, r, child, val);
-        node = node * K + child;
-      }
-      if (a.out_w && tid < B) atomicMin(&s_vmin, __float_as_uint(val));
-    } else if (tid == 0) {
-      flags |= 4u;
-    }
-    if (tid < B) {
-      s_idx[tid] = node;
-      a.out_idx[bo] = node;
-      if (a.out_prio) a.out_prio[bo] = val;
-    }
-    __syncthreads();
-
-    PER_MARK(2);
-    // ---- rows of the sampled indices
-    // (the weights, a power per sample, are computed while the rows are on their way: every lane that
-    // owns a sample also owns a row element of the first sweep, so no wave runs the power twice)
-    auto weights = [&]() {
-      if (a.out_w && tid < B)
-        a.out_w[bo] = total > 0.0f ? importance_weight(val, __uint_as_float(s_vmin), beta) : 0.0f;
-    };
-    if (move_rows_one_workgroup<true>(a.rows, t, ((uint64_t)s * T + t) * B, B, 0, N, s_idx, nullptr, weights)) flags |= 1u;
-
-    PER_MARK(3);
-    // ---- priority update: last writer by LDS atomics, then the ancestors
-    if (a.upd_prio) {
-      const uint32_t i = a.upd_is_sampled ? node : up_i;
-      bool valid = false;
-      if (tid < B) {
-        if (!(i < size)) flags |= 1u;
-        else if (!valid_priority(up_v)) flags |= 2u;
-        else valid = true;
-      }
-      const uint32_t mark = 0x80000001u + tid;
-      if (valid) atomicMax(&leaf_bits[i], mark);
-      __syncthreads();
-      const bool won = valid && leaf_bits[i] == mark;
-      __syncthreads();
-      if (won) tree[s_off[0] + i] = up_v;
-      if (valid && up_v > 0.0f) atomicMax(&s_max, __float_as_uint(up_v));
-      resum_paths_lds<LOGK>(tree, s_off, H, valid, i);
-    }
-    __syncthreads();
-    PER_MARK(4);
   }
-  PER_FLUSH();
+  lds_tree_store(g, t, tab, lt, flags, &s_flags);
+}
 
-  // ---- the tree goes back to memory
-  for (uint32_t h = 0; h <= H; ++h) {
-    float* lvl = tab.lvl[h];
-    const float* src = tree + s_off[h];
-    for (uint32_t e = tid; e < tab.n[h]; e += blockDim.x) lvl[e] = src[e];
+// ---------------------------------------------------------------------------------
+// a queue of op-coded requests on an LDS-resident tree
+// ---------------------------------------------------------------------------------
+// The same workgroup-per-tree arrangement, driven by a queue of requests in memory instead of a
+// fixed step: each request names its operation (the paper's unified operation code, Section V-A)
+// and is decoded when its turn comes.  The queue's length is fixed at launch; the kernel ends after
+// its last request.
+struct QueueKernelArgs {            // one kernel argument (Geom first: see fill_level_table)
+  Geom g;
+  QueueArgs a;
+};
+
+template <int LOGK>
+__global__ void __launch_bounds__(1024)
+k_run_requests(QueueKernelArgs ka) {
+  const Geom& g = ka.g;
+  const QueueArgs& a = ka.a;
+  extern __shared__ __attribute__((aligned(16))) float tree[];
+  __shared__ LevelTable tab;
+  __shared__ FieldTable s_ft;        // the buffer's columns with the current request's row arrays
+  __shared__ uint32_t s_off[kMaxHeight + 2];
+  __shared__ uint32_t s_skip[32];
+  __shared__ uint32_t s_max, s_vmin, s_flags;
+  const uint32_t t = blockIdx.x;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t H = g.H;
+  fill_level_table(H, t, &tab);
+  if (tid >= 64 && tid <= 64 + H + 1)
+    s_off[tid - 64] = kernarg_at<QueueArgs>(offsetof(QueueKernelArgs, a))->off[tid - 64];
+  if (tid == 0) {
+    s_max = read_max_bits(g, t);
+    s_flags = 0;
+    s_ft = a.fields;
   }
-  if (tid == 0) g.max_v[t] = __uint_as_float(s_max);
-  if (flags) atomicOr(&s_flags, flags);
   __syncthreads();
-  if (tid == 0 && s_flags) atomicOr(&g.status[t], s_flags);
+  LdsTree lt;
+  lt.tree = tree;
+  lt.off = s_off;
+  lt.sampled = reinterpret_cast<uint32_t*>(tree + s_off[H + 1]);
+  lt.max_bits = &s_max;
+  lt.vmin_bits = &s_vmin;
+  lt.skip = s_skip;
+  lt.H = H;
+  lt.N = g.N;
+  lds_tree_load(tab, lt);
+  uint32_t cursor = a.cursor, size = a.size;
+  uint32_t flags = 0;
+  uint32_t last_node = 0xFFFFFFFFu;   // this lane's index from the latest sampling request
+
+  for (uint32_t r = 0; r < a.n_requests; ++r) {
+    const per_request& q = a.queue[r];
+    const uint32_t n = q.n;
+    const size_t to = (size_t)t * n;
+    __syncthreads();   // the request before this one is complete (and has finished with s_ft)
+    if (tid < (uint32_t)kMaxFields) s_ft.io[tid] = static_cast<uint8_t*>(q.field[tid]);
+    __syncthreads();
+    if (q.op == PER_OP_INSERT) {
+      lds_insert<LOGK>(lt, s_ft, t, to, n, q.prio ? q.prio + to : nullptr, q.idx ? q.idx + to : nullptr,
+                       q.protect ? q.protect + (size_t)t * q.n_protect : nullptr, q.n_protect, cursor, size, flags);
+    } else if (q.op == PER_OP_SAMPLE) {
+      const float u_i = tid < n ? q.u[to + tid] : 0.0f;
+      last_node = lds_sample<LOGK>(lt, s_ft, t, to, n, u_i, q.beta, q.idx + to, q.out_weight ? q.out_weight + to : nullptr,
+                                   q.out_prio ? q.out_prio + to : nullptr, flags);
+    } else if (q.op == PER_OP_UPDATE) {
+      float v = 0.0f;
+      uint32_t i = last_node;
+      if (tid < n) {
+        v = q.prio[to + tid];
+        if (q.idx) i = q.idx[to + tid];
+      }
+      lds_update<LOGK>(lt, n, i, v, size, flags);
+    }
+  }
+  __syncthreads();
+  lds_tree_store(g, t, tab, lt, flags, &s_flags);
 }
 
 // LDS floats of a whole tree (every height padded to whole child groups), or 0 if it cannot be
@@ -239,6 +379,29 @@ static hipError_t launch_run_steps_k(const Geom& g, const Tuning& tn, StreamArgs
 
 hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s) {
 #define CALL(L) launch_run_steps_k<L>(g, tn, a, s)
+  PER_DISPATCH_LOGK(g.logK, CALL)
+#undef CALL
+}
+
+template <int LOGK>
+static hipError_t launch_run_requests_k(const Geom& g, const Tuning& tn, const QueueArgs& a, hipStream_t s) {
+  QueueKernelArgs ka{};
+  ka.g = g;
+  ka.a = a;
+  const uint32_t floats = stream_tree_floats(g, ka.a.off);
+  if (!floats) return hipErrorInvalidValue;
+  const size_t bytes = ((size_t)floats + 1024) * 4;   // the tree and the indices of the latest sampling request
+  if (bytes > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_run_requests<LOGK>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+  }
+  PER_LAUNCH(KID_RUN_REQUESTS, k_run_requests<LOGK>, dim3(g.T), dim3(1024), bytes, s, ka);
+  return hipGetLastError();
+}
+
+hipError_t launch_run_requests(const Geom& g, const Tuning& tn, const QueueArgs& a, hipStream_t s) {
+#define CALL(L) launch_run_requests_k<L>(g, tn, a, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

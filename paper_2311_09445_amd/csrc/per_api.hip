@@ -507,6 +507,53 @@ int per_run_steps(per_t* p, uint32_t n_steps, uint32_t n_insert, uint32_t B, con
   return hip_rc(e);
 }
 
+int per_run_requests(per_t* p, uint32_t n_requests, const per_request* h_requests, const per_request* d_requests,
+                     void* stream) {
+  if (!p) return PER_EINVAL;
+  if (n_requests == 0) return PER_OK;
+  if (!h_requests || !d_requests || misaligned(d_requests, 8)) return PER_EINVAL;
+  if (!stream_tree_floats(p->g, nullptr)) return PER_ERANGE;   // the tree does not fit the LDS of a compute unit
+  QueueArgs a{};
+  (void)fill_fields(p, nullptr, &a.fields);
+  for (uint32_t f = 0; f < a.fields.n_fields; ++f) a.fields.vec[f] = vec_width(a.fields.bytes[f], nullptr);
+  // a dry run over the host copy: argument checks and the ring state after every request
+  const uint64_t N = p->cfg.capacity;
+  uint64_t cursor = p->cursor, size = p->size;
+  uint32_t sampled_n = 0;   // batch of the latest SAMPLE request (0: none yet)
+  for (uint32_t r = 0; r < n_requests; ++r) {
+    const per_request& q = h_requests[r];
+    if (q.op != PER_OP_INSERT && q.op != PER_OP_SAMPLE && q.op != PER_OP_UPDATE) return PER_EINVAL;
+    if (q.n == 0 || q.n > 1024) return PER_ERANGE;
+    if (misaligned(q.prio, 4) || misaligned(q.u, 4) || misaligned(q.idx, 4) || misaligned(q.out_weight, 4) ||
+        misaligned(q.out_prio, 4) || misaligned(q.protect, 4))
+      return PER_EINVAL;
+    if (q.op != PER_OP_UPDATE)
+      for (uint32_t f = 0; f < a.fields.n_fields; ++f)
+        if (misaligned(q.field[f], a.fields.vec[f])) return PER_EINVAL;
+    if (q.op == PER_OP_INSERT) {
+      if (q.n > N) return PER_ERANGE;
+      cursor = (cursor + q.n) % N;
+      size = size + q.n > N ? N : size + q.n;
+    } else if (q.op == PER_OP_SAMPLE) {
+      if (!q.u || !q.idx || !isfinite(q.beta) || q.beta < 0.0f) return PER_EINVAL;
+      if (size == 0) return PER_EEMPTY;
+      sampled_n = q.n;
+    } else {
+      if (!q.prio || (!q.idx && sampled_n != q.n)) return PER_EINVAL;
+    }
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  a.n_requests = n_requests;
+  a.cursor = (uint32_t)p->cursor;
+  a.size = (uint32_t)p->size;
+  a.queue = d_requests;
+  hipError_t e = ensure_top(p, s);   // the kernel loads whole heights from memory
+  if (e == hipSuccess) e = launch_run_requests(p->g, p->tn, a, s);
+  p->cursor = cursor;
+  p->size = size;
+  return hip_rc(e);
+}
+
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream) {
   if (!p) return PER_EINVAL;
   if (n == 0) return PER_OK;

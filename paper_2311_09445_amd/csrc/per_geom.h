@@ -11,6 +11,8 @@
 
 #include <vector>
 
+#include "../../include/per.h"
+
 namespace per {
 
 constexpr int kMaxHeight = 32;   // K = 2, N = 2^31 gives H = 31
@@ -108,6 +110,15 @@ struct StreamArgs {
   uint32_t off[kMaxHeight + 2];     // where height h starts in LDS (floats); off[H + 1] = all floats
 };
 
+// A queue of op-coded requests run by one workgroup per tree on an LDS copy of the tree (see k_run_requests).
+struct QueueArgs {
+  uint32_t n_requests;
+  uint32_t cursor, size;            // ring state before the first request
+  const per_request* queue;         // device copy of the requests
+  FieldTable fields;                // columns, row sizes and access widths; the io pointers come from the requests
+  uint32_t off[kMaxHeight + 2];     // as in StreamArgs
+};
+
 // Workgroup ranges of the jobs sharing one launch: [first[j], first[j+1]) for job j, where job 0 is the
 // weights, job 1 the claim and job 2 + f the rows of payload field f.
 struct JobRanges {
@@ -120,7 +131,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_UPDATE_DELTA, KID_GET_PRIORITY,
-  KID_INSERT_SMALL, KID_RUN_STEPS, KID_COUNT
+  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -171,6 +182,7 @@ hipError_t launch_update_delta(const Geom& g, const Tuning& tn, uint32_t B, uint
                                const float* delta, hipStream_t s);
 uint32_t stream_tree_floats(const Geom& g, uint32_t* off);
 hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s);
+hipError_t launch_run_requests(const Geom& g, const Tuning& tn, const QueueArgs& a, hipStream_t s);
 hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
 hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s);
 hipError_t launch_clear_status(const Geom& g, hipStream_t s);

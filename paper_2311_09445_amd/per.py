@@ -22,7 +22,7 @@ EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_insert_protected", "per_sample", "per_sample_gather",
     "per_sample_gather_update", "per_gather",
     "per_update", "per_update_td", "per_update_delta", "per_set_rng", "per_rng_calls", "per_run_steps",
-    "per_run_steps_fits", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
+    "per_run_steps_fits", "per_run_requests", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
 ]
@@ -53,6 +53,25 @@ class PerStreamIO(C.Structure):
         ("d_rows_out", C.c_void_p),
         ("d_upd_idx", C.c_void_p),
         ("d_upd_prio", C.c_void_p),
+    ]
+
+
+OP_INSERT, OP_SAMPLE, OP_UPDATE = 1, 2, 3
+
+
+class PerRequest(C.Structure):
+    _fields_ = [
+        ("op", C.c_uint32),
+        ("n", C.c_uint32),
+        ("beta", C.c_float),
+        ("n_protect", C.c_uint32),
+        ("prio", C.c_void_p),
+        ("u", C.c_void_p),
+        ("idx", C.c_void_p),
+        ("out_weight", C.c_void_p),
+        ("out_prio", C.c_void_p),
+        ("protect", C.c_void_p),
+        ("field", C.c_void_p * MAX_FIELDS),
     ]
 
 
@@ -92,6 +111,7 @@ def _lib():
         "per_rng_calls": (C.c_uint64, [vp]),
         "per_run_steps": (C.c_int, [vp, u32, u32, u32, C.POINTER(PerStreamIO), vp]),
         "per_run_steps_fits": (C.c_int, [vp]),
+        "per_run_requests": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update_td": (C.c_int, [vp, u32, vp, vp, C.c_double, C.c_double, vp]),
         "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_read_level": (C.c_int, [vp, u32, u32, vp, C.POINTER(u64), vp]),
@@ -320,6 +340,57 @@ class PrioritizedReplay:
         io.d_upd_prio = ptr(upd_prio, torch.float32)
         rc = self.lib.per_run_steps(self._h, steps, int(n_insert), B, C.byref(io), self._stream())
         self._check(rc, "per_run_steps")
+
+    def prepare_requests(self, requests):
+        """Encodes a list of requests for run_requests: a host array of per_request and its device copy.
+        ``requests``: a list of dicts, each with ``op`` (OP_INSERT / OP_SAMPLE / OP_UPDATE) and device tensors
+        under the names of per.h's per_request (``prio``, ``u``, ``idx``, ``out_weight``, ``out_prio``,
+        ``protect``, ``beta``, ``rows``: one tensor or None per payload field).  The batch of a request is
+        taken from ``u`` (SAMPLE), ``prio`` (UPDATE), or ``n`` (INSERT)."""
+        torch = self._torch
+        arr = (PerRequest * max(1, len(requests)))()
+        for r, q in enumerate(requests):
+            op = int(q["op"])
+            if op == OP_SAMPLE:
+                n = q["u"].numel() // self.T
+            elif op == OP_UPDATE:
+                n = q["prio"].numel() // self.T
+            else:
+                n = int(q["n"])
+            a = arr[r]
+            a.op, a.n, a.beta = op, n, float(q.get("beta", 0.0))
+            for name, dtype in (("prio", torch.float32), ("u", torch.float32), ("idx", torch.int32),
+                                ("out_weight", torch.float32), ("out_prio", torch.float32), ("protect", torch.int32)):
+                x = q.get(name)
+                if x is not None and name != "protect" and x.numel() != self.T * n:
+                    raise ValueError(f"request {r}: {name} must hold T*n values")
+                ptr = _dptr(x, dtype)
+                setattr(a, name, None if ptr is None else ptr.value)
+            if q.get("protect") is not None:
+                a.n_protect = q["protect"].numel() // self.T
+            rows = q.get("rows")
+            if rows is not None:
+                if len(rows) != len(self.field_bytes):
+                    raise ValueError("one tensor (or None) per payload field is required")
+                for f, x in enumerate(rows):
+                    if x is None:
+                        continue
+                    if x.numel() * x.element_size() != self.T * n * self.field_bytes[f]:
+                        raise ValueError(f"request {r}, field {f}: expected T*n*{self.field_bytes[f]} bytes")
+                    a.field[f] = _dptr(x).value
+        nbytes = C.sizeof(PerRequest) * len(requests)
+        host = torch.frombuffer(bytearray(bytes(arr)[:max(nbytes, 1)]), dtype=torch.uint8)
+        return len(requests), arr, host.to(self.device)
+
+    def run_requests(self, requests):
+        """A queue of op-coded requests in one launch on an LDS copy of the tree.  ``requests``: what
+        prepare_requests returned, or a list of request dicts (encoded here).  Returns the encoded queue,
+        which must stay alive until the stream's work is done."""
+        prepared = requests if isinstance(requests, tuple) else self.prepare_requests(requests)
+        n, arr, d_queue = prepared
+        rc = self.lib.per_run_requests(self._h, n, C.cast(arr, C.c_void_p), C.c_void_p(d_queue.data_ptr()), self._stream())
+        self._check(rc, "per_run_requests")
+        return prepared
 
     def set_rng(self, seed: int, next_call: int = 0):
         """Sampling calls without uniforms draw them from a counter-based generator keyed by ``seed``."""

@@ -666,6 +666,124 @@ def test_run_steps_limits_and_empty_tree():
     assert q.status() == FLAG_ZERO_TOTAL
 
 
+# ---------------------------------------------------------------------------------------------
+# per_run_requests: a queue of op-coded requests in one launch.  Same results as the calls, in queue order.
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K,N,T,fb,seed", [(2, 4096, 1, (16, 4, 4, 16, 1), 1), (16, 30000, 2, (12,), 2),
+                                           (32, 32768, 1, (128,), 3), (4, 1000, 3, (), 4), (64, 20000, 1, (5, 68), 5)])
+def test_run_requests_equals_the_separate_calls(K, N, T, fb, seed):
+    """A random queue of insert (plain and collision-free), sample (+ weights, + rows) and update requests
+    (given indices, or the batch sampled last).  The oracle gets every request as it is drawn, so later
+    requests can refer to what earlier ones returned; the library gets the whole queue in one call."""
+    from paper_2311_09445_amd.per import OP_INSERT, OP_SAMPLE, OP_UPDATE
+    log(f"run_requests K={K} N={N} T={T} fb={fb}")
+    rng = np.random.default_rng(seed)
+    m = Mirror(K, N, T, fb)
+    first = N - 300
+    m.insert(first, prio=wl._draw_priorities("exponential_1", rng, (T, first)), chunk=5000)   # the ring wraps below
+    queue, checks = [], []
+    sampled = None                  # indices of the latest sampling request (from the oracle)
+    for r in range(40):
+        kind = rng.choice(["insert", "protected", "sample", "update", "update_sampled"])
+        if kind == "update_sampled" and sampled is None:
+            kind = "sample"
+        if kind in ("insert", "protected"):
+            n = min(int(rng.choice([1, 7, 64, 333, 1024])), N)
+            counters = m.counter + np.arange(n)
+            m.counter += n
+            rows = [np.stack([wl.row_bytes(t, counters, f, b) for t in range(T)]) for f, b in enumerate(fb)] \
+                if fb and r % 5 else None
+            prio = None
+            if rng.random() < 0.5:
+                prio = (rng.random((T, n)) * 5).astype(np.float32)
+                if r % 3 == 0:
+                    prio[:, 0] = np.float32("nan")
+            protect = None
+            if kind == "protected":   # the batch sampled last, or slots around the cursor
+                protect = sampled if sampled is not None else \
+                    ((m.cpu.trees[0].cursor + rng.integers(0, 2 * n, (T, 50))) % N).astype(np.uint32)
+            out = torch.full((T, n), -7, dtype=torch.int32, device="cuda")
+            queue.append({"op": OP_INSERT, "n": n, "prio": None if prio is None else dev(prio), "idx": out,
+                          "rows": None if rows is None else [dev(x) for x in rows],
+                          "protect": None if protect is None else idx_to_dev(protect)})
+            checks.append(("slots", out, m.cpu.insert(n, rows, prio, protect=protect)))
+        elif kind == "sample":
+            B = int(rng.choice([1, 33, 256, 1000, 1024]))
+            u = wl.uniform01(rng, (T, B))
+            beta = float(rng.choice([0.0, 0.4, 1.0]))
+            want_w = bool(r % 4)
+            oi = torch.empty((T, B), dtype=torch.int32, device="cuda")
+            ow = torch.empty((T, B), dtype=torch.float32, device="cuda") if want_w else None
+            ov = torch.empty((T, B), dtype=torch.float32, device="cuda")
+            rows_out = [torch.empty((T, B, b), dtype=torch.uint8, device="cuda") for b in fb] if fb and r % 3 else None
+            queue.append({"op": OP_SAMPLE, "u": dev(u), "beta": beta, "idx": oi, "out_weight": ow, "out_prio": ov,
+                          "rows": rows_out})
+            ci, cw, cv = m.cpu.sample(u, beta, want_w)
+            checks.append(("sample", oi, ow, ov, rows_out, ci, cw, cv, m.cpu.gather(ci) if rows_out else None))
+            sampled = ci
+        else:
+            B = sampled.shape[1] if kind == "update_sampled" else int(rng.choice([1, 50, 700, 1024]))
+            prio = (rng.random((T, B)) * 3).astype(np.float32)
+            if r % 2:
+                prio[:, ::11] = -1.0
+            idx = None
+            if kind == "update":
+                idx = rng.integers(0, N, (T, B)).astype(np.uint32)
+                idx[:, 1::2] = idx[:, 0::2][:, :idx[:, 1::2].shape[1]]     # every other element repeats its neighbour
+                idx[:, 0] = N + 1                                          # out of range
+            queue.append({"op": OP_UPDATE, "prio": dev(prio), "idx": None if idx is None else idx_to_dev(idx)})
+            m.cpu.update(sampled if idx is None else idx, prio)
+    keep = m.gpu.run_requests(queue)
+    torch.cuda.synchronize()
+    del keep
+    for r, c in enumerate(checks):
+        if c[0] == "slots":
+            assert np.array_equal(idx_to_host(c[1]), c[2]), f"check {r}: slots reported by an insert request"
+        else:
+            _, oi, ow, ov, rows_out, ci, cw, cv, crow = c
+            assert np.array_equal(idx_to_host(oi), ci), f"check {r}: sampled indices"
+            assert ov.cpu().numpy().tobytes() == cv.tobytes(), f"check {r}: sampled values"
+            if ow is not None:
+                np.testing.assert_allclose(ow.cpu().numpy(), cw, rtol=1e-6, atol=0)
+            if rows_out:
+                for f, want in enumerate(crow):
+                    assert np.array_equal(rows_out[f].cpu().numpy(), want), f"check {r}: rows of field {f}"
+    m.compare_tree()
+    m.compare_status()
+    assert m.gpu.cursor == m.cpu.trees[0].cursor and m.gpu.size == m.cpu.trees[0].size
+    # the separate calls carry on from the state the queue left
+    m.update(rng.integers(0, N, (T, 50)).astype(np.uint32), rng.random((T, 50)).astype(np.float32))
+    m.sample(wl.uniform01(rng, (T, 64)), 0.4)
+    m.compare_tree()
+
+
+def test_run_requests_argument_checks():
+    from paper_2311_09445_amd.per import OP_SAMPLE, OP_UPDATE
+    big = PrioritizedReplay(16, 1 << 20)
+    z = torch.zeros((1, 8), device="cuda")
+    zi = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(PerError) as e:
+        big.run_requests([{"op": OP_SAMPLE, "u": z, "idx": zi}])
+    assert e.value.code == ERANGE                                  # the tree does not fit
+    p = PrioritizedReplay(4, 256)
+    with pytest.raises(PerError) as e:
+        p.run_requests([{"op": OP_SAMPLE, "u": z, "idx": zi}])
+    assert e.value.code == EEMPTY
+    p.insert(10, None, torch.ones((1, 10), device="cuda"))
+    for bad in ([{"op": 9, "n": 1}], [{"op": OP_SAMPLE, "u": z, "idx": None}],
+                [{"op": OP_UPDATE, "prio": z, "idx": None}],                       # no sampling request before it
+                [{"op": OP_SAMPLE, "u": z, "idx": zi}, {"op": OP_UPDATE, "prio": torch.zeros((1, 4), device="cuda")}]):
+        with pytest.raises(PerError) as e:
+            p.run_requests(bad)
+        assert e.value.code == EINVAL, bad
+    with pytest.raises(PerError) as e:
+        p.run_requests([{"op": OP_SAMPLE, "u": torch.zeros((1, 2000), device="cuda"),
+                         "idx": torch.zeros((1, 2000), dtype=torch.int32, device="cuda")}])
+    assert e.value.code == ERANGE
+    assert p.size == 10 and p.cursor == 10                          # nothing was enqueued
+    p.run_requests([])
+
+
 @pytest.mark.parametrize("K,N,T,seed", [(16, 20000, 2, 1), (2, 3000, 1, 2), (32, 32768, 1, 3), (4, 25000, 3, 4)])
 def test_interleaved_operations(K, N, T, seed):
     """Every entry point in random order on one buffer, the tree compared with the oracle after each call.  All
