@@ -29,7 +29,9 @@
  *     writer of a duplicated index wins (the paper's delta propagation is a
  *     separate operation, oracle_update_delta);
  *   - new rows get the running maximum of all values ever written;
- *   - importance weights are normalised by the batch maximum, in fp64.
+ *   - importance weights are normalised by the batch maximum, in fp64; on request
+ *     (oracle_set_weight_norm) by the maximum over the whole buffer instead, i.e. over
+ *     every stored row that can be sampled at all (priority > 0).
  *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC.
  */
@@ -53,6 +55,7 @@ typedef struct {
   uint64_t cursor, size;
   float    max_v;
   uint32_t status;
+  int      weight_norm;      /* 0: weights relative to the batch maximum, 1: to the buffer-wide one */
 } oracle_t;
 
 static int valid_priority(float v) { return isfinite(v) && v >= 0.0f; }
@@ -244,10 +247,30 @@ int oracle_sample(oracle_t* o, uint32_t B, float beta, const float* u, uint32_t*
       if (wt[i] > wmax) wmax = wt[i];
     }
   }
+  if (wt && o->weight_norm == 1) {
+    /* the largest weight any stored row could get: rows that cannot be sampled (priority 0) have none */
+    wmax = 0.0;
+    for (uint64_t j = 0; j < o->size; ++j) {
+      const float v = t[o->P + j];
+      if (v > 0.0f) {
+        const double w = pow((double)o->size * (double)v / (double)total, -(double)beta);
+        if (w > wmax) wmax = w;
+      }
+    }
+  }
   if (wt) {
     for (uint32_t i = 0; i < B; ++i) out_weight_or_null[i] = (float)(wt[i] / wmax);
     free(wt);
   }
+  return 0;
+}
+
+/* Importance weights w_i = (size * P(i) / total)^-beta are scaled by 1 / max w "for stability" (prioritized
+ * experience replay, the method cited in Section II-A); mode 0 takes the maximum over the sampled
+ * batch, mode 1 over all stored rows with a positive priority. */
+int oracle_set_weight_norm(oracle_t* o, int mode) {
+  if (mode != 0 && mode != 1) return -1;
+  o->weight_norm = mode;
   return 0;
 }
 

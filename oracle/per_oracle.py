@@ -49,6 +49,8 @@ def _load():
     lib.oracle_insert.argtypes = [vp, u32, vp, vp, vp]
     lib.oracle_insert_protected.restype = C.c_int
     lib.oracle_insert_protected.argtypes = [vp, u32, vp, vp, vp, u32, vp]
+    lib.oracle_set_weight_norm.restype = C.c_int
+    lib.oracle_set_weight_norm.argtypes = [vp, C.c_int]
     lib.oracle_sample.restype = C.c_int
     lib.oracle_sample.argtypes = [vp, u32, f32, vp, vp, vp, vp]
     lib.oracle_gather.argtypes = [vp, u32, vp, vp]
@@ -214,6 +216,11 @@ class Oracle:
     def cursor(self) -> int:
         return int(self._lib.oracle_cursor(self._h))
 
+    def set_weight_norm(self, mode: str) -> None:
+        """'batch': weights relative to the largest weight of the sampled batch; 'buffer': of all stored rows."""
+        if self._lib.oracle_set_weight_norm(self._h, {"batch": 0, "buffer": 1}[mode]) != 0:
+            raise ValueError(mode)
+
     @property
     def status(self) -> int:
         return int(self._lib.oracle_status(self._h))
@@ -270,6 +277,10 @@ class MultiOracle:
     @property
     def total(self):
         return np.array([o.total for o in self.trees], dtype=np.float32)
+
+    def set_weight_norm(self, mode):
+        for o in self.trees:
+            o.set_weight_norm(mode)
 
     @property
     def status(self):

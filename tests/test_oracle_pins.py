@@ -346,6 +346,53 @@ def test_importance_weights():
     assert np.all(o2.sample(u[:32], beta=0.9)[1] == 1.0)
 
 
+def test_importance_weights_relative_to_the_whole_buffer():
+    """Closed forms: with beta = 1 the weight of a row is (smallest positive priority of the buffer) / (its own),
+    whatever else was sampled; rows with priority 0 and unfilled slots do not count; a batch that happens to
+    hold the smallest row gets the batch-relative weights; equal priorities give weights of one."""
+    o = Oracle(2, 16)
+    o.insert(6, None, np.array([4.0, 0.0, 1.0, 8.0, 2.0, 16.0], np.float32))    # total 31, smallest positive 1
+    o.set_weight_norm("buffer")
+    B = 31                                                                       # one target per unit of priority
+    idx, w, v = o.sample(np.full(B, 0.5, np.float32), beta=1.0)
+    assert sorted(set(idx.tolist())) == [0, 2, 3, 4, 5]
+    np.testing.assert_allclose(w, 1.0 / v, rtol=2e-7)
+    upper = np.array([0.99], np.float32)                                         # a batch of one: the last row only
+    idx, w, v = o.sample(upper, beta=1.0)
+    assert idx.tolist() == [5] and abs(float(w[0]) - 1.0 / 16.0) < 1e-8
+    idx, w, v = o.sample(upper, beta=0.5)
+    assert abs(float(w[0]) - 0.25) < 1e-7
+    o.set_weight_norm("batch")
+    assert o.sample(upper, beta=1.0)[1].tolist() == [1.0]
+    # against the definition written out with numpy: every stored row's weight, then the maximum
+    rng = np.random.default_rng(18)
+    N = 3000
+    leaves = wl._draw_priorities("pareto_1.5", rng, (N,))
+    leaves[rng.integers(0, N, 30)] = 0.0
+    o = Oracle(16, 5000)
+    o.insert(N, None, leaves)
+    o.set_weight_norm("buffer")
+    u = wl.uniform01(rng, (300,))
+    for beta in (0.0, 0.4, 1.0):
+        idx, w, v = o.sample(u, beta=beta)
+        total = float(np.float32(o.total))
+        every = (N * leaves[leaves > 0].astype(np.float64) / total) ** (-beta)
+        np.testing.assert_allclose(w, (N * v.astype(np.float64) / total) ** (-beta) / every.max(), rtol=2e-7)
+        assert np.all(w <= 1.0) and np.all(w > 0)
+        o.set_weight_norm("batch")
+        wb = o.sample(u, beta=beta)[1]
+        o.set_weight_norm("buffer")
+        ratio = (float(leaves[leaves > 0].min()) / float(v.min())) ** beta       # buffer-wide = batch-relative * this
+        np.testing.assert_allclose(w, wb * ratio, rtol=3e-7)
+    # updates move the minimum
+    o.update(np.array([int(np.argmin(np.where(leaves > 0, leaves, np.inf)))], np.uint32), np.array([1e-3], np.float32))
+    idx, w, v = o.sample(u, beta=1.0)
+    np.testing.assert_allclose(w, 1e-3 / v.astype(np.float64), rtol=2e-7)
+    o2 = filled(4, np.full(64, 0.25, np.float32))
+    o2.set_weight_norm("buffer")
+    assert np.all(o2.sample(u[:32], beta=0.9)[1] == 1.0)
+
+
 # ----------------------------------------------------------- insert / ring / gather
 def test_ring_insert_gather_and_max_priority():
     w = wl.WORKLOADS["c1_binary_small"]
