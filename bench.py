@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-delta-form", action="store_true",
                     help="skip the extra timing of the step with the paper's delta-propagation update")
     ap.add_argument("--tune", action="append", default=[], help="name=value passed to per_set_tuning")
+    ap.add_argument("--weight-norm", choices=["batch", "buffer"], default="batch",
+                    help="importance weights relative to the sampled batch (the metric's form) or to the whole buffer")
     return ap.parse_args()
 
 
@@ -126,6 +128,7 @@ def main():
     for kv in args.tune:
         k, v = kv.split("=")
         buf.set_tuning(k, int(v))
+    buf.set_weight_norm(args.weight_norm)
     prio0 = wl.initial_priorities(w, args.seed)
     chunk = 1 << 20
     for lo in range(0, N, chunk):
@@ -437,6 +440,7 @@ def main():
     if args.cpu_seconds > 0:
         from oracle.per_oracle import MultiOracle
         orc = MultiOracle(T, K, N, w.field_bytes, with_payload=True)
+        orc.set_weight_norm(args.weight_norm)
         for lo in range(0, N, chunk):
             m = min(chunk, N - lo)
             cnt = np.arange(lo, lo + m)
@@ -516,7 +520,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "K": K, "N": N, "T": T, "B": B, "row_bytes": w.row_bytes,
                    "insert_per_step": w.n_insert, "launch": "hip_graph" if graph is not None else "eager",
-                   "streams": 2 if overlap else 1, "calls_per_step": "per_sample_gather_update" if fused_step else
+                   "streams": 2 if overlap else 1, "weight_norm": args.weight_norm, "calls_per_step": "per_sample_gather_update" if fused_step else
                    ("per_sample_gather, per_update" if fused else "per_sample, per_gather, per_update")},
         "roofline": roofline,
         "cpu_baseline": cpu,

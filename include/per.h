@@ -277,6 +277,23 @@ uint64_t per_cursor(const per_t* p);     /* next ring slot                      
  * the stamp arrays first.) */
 int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
 
+/* What the importance weights of the sampling calls are relative to.  w_i = (size * P(i) / total)^-beta is
+ * scaled by 1 / max w (prioritized experience replay, the method cited in Section II-A).
+ *   PER_NORM_BATCH  (default): the maximum over the sampled batch, so the largest weight returned is 1;
+ *   PER_NORM_BUFFER : the maximum over every stored row that can be sampled (priority > 0), the form
+ *                     that implementations back with a min tree beside the sum tree.
+ * Here the companion structure is the smallest positive leaf under every height-1 node, renewed by
+ * per_update, the fused step and small inserts for the nodes they touch while this mode is on, rebuilt
+ * from the leaves after calls that cannot (large inserts, per_update_delta, per_run_steps,
+ * per_run_requests, per_set_ring), and reduced to one value per tree by a kernel in front of every
+ * sampling call that returns weights.  per_run_steps and per_run_requests sweep their LDS copy of the
+ * leaves instead.  The mode applies to the calls made after it is set.
+ * per_min_priority: d_out[t] = smallest positive leaf of tree t (+infinity if there is none). */
+#define PER_NORM_BATCH  0
+#define PER_NORM_BUFFER 1
+int per_set_weight_norm(per_t* p, int mode);
+int per_min_priority(per_t* p, float* d_out, void* stream);
+
 /* Uniforms drawn on the device ("uniformly generated random", Section II-A), for sampling calls that
  * pass d_u == NULL.  The generator is counter-based (Philox4x32-10), so the uniforms are a pure
  * function of (seed, number of the sampling call, tree, sample): sample i of tree t in call number c

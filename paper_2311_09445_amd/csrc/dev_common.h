@@ -39,6 +39,27 @@ __device__ __forceinline__ float group_sum(const float* grp, unsigned q) {
   }
 }
 
+// Companion minimum of the sum tree (for importance weights relative to the whole buffer): the
+// smallest POSITIVE value, since a priority of zero is never sampled and has no weight.  Positive
+// fp32 values order like their bit patterns; kNoMin (+inf) stands for "none".
+__device__ __forceinline__ uint32_t positive_bits(float v) { return v > 0.0f ? __float_as_uint(v) : kNoMin; }
+__device__ __forceinline__ uint32_t min_u32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+// Smallest positive value among the K children starting at grp, as bits; lane layout as group_sum.
+template <int LOGK>
+__device__ __forceinline__ uint32_t group_min_positive(const float* grp, unsigned q) {
+  if constexpr (LOGK == 1) {
+    const float2 c = *reinterpret_cast<const float2*>(grp);
+    return min_u32(positive_bits(c.x), positive_bits(c.y));
+  } else {
+    const float4 c = *reinterpret_cast<const float4*>(grp + 4 * q);
+    uint32_t m = min_u32(min_u32(positive_bits(c.x), positive_bits(c.y)), min_u32(positive_bits(c.z), positive_bits(c.w)));
+#pragma unroll
+    for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) m = min_u32(m, (uint32_t)__shfl_xor((int)m, 1 << k));
+    return m;
+  }
+}
+
 // Per-height facts of one tree, kept in LDS by kernels that loop over heights: indexing the
 // kernel arguments by a run-time height costs a dependent scalar load from memory per use.  The
 // kernel-argument segment is ordinary read-only memory, so lane h fetches the entries of height h
@@ -139,6 +160,13 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
     x = y > x ? y : x;
   }
   return x;
+}
+
+// Smallest positive leaf of tree t as left by k_min_reduce in the entry named by the weight mode:
+// the kMinSlots partial minima, one per lane, folded by a wave reduction.  Called by whole waves.
+__device__ __forceinline__ uint32_t buffer_min_bits(const Geom& g, uint32_t t, uint32_t mode) {
+  const uint32_t parity = (mode >> kWeightBufferParityShift) & 1u;
+  return wave_min_u32(g.vmin_buf[((size_t)parity * g.T + t) * kMinSlots + (threadIdx.x & 63u)]);
 }
 
 // Running maximum priority: mx = fp32 bits of this lane's valid positive value (0: none).  One

@@ -56,6 +56,7 @@ struct InsertPlan {
 struct InsertArgs {                // one kernel argument, so that both parts sit at known offsets of the segment
   Geom g;
   InsertPlan plan;
+  uint32_t track_min;              // also renew min1 (smallest positive leaf) of the touched height-1 nodes
 };
 
 // position of node among the touched nodes of its height (the two ranges back to back)
@@ -159,9 +160,13 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
       const uint32_t pos = base + grp;
       const bool ok = pos < cnt;
       const float sum = group_sum<LOGK>(staged + s_off[h - 1] + (size_t)(ok ? pos : 0u) * K, q);
+      uint32_t mn = kNoMin;
+      if (a.track_min && h == 1)   // the staged groups of height 0 hold the leaves of every touched height-1 node
+        mn = group_min_positive<LOGK>(staged + s_off[0] + (size_t)(ok ? pos : 0u) * K, q);
       if (ok && q == 0) {
         const uint32_t node = pos < c0 ? r.a0 + pos : r.a1 + (pos - c0);
         par[node] = sum;
+        if (a.track_min && h == 1) g.min1[(size_t)t * g.min1_stride + node] = mn;
         if (h < H) staged[s_off[h] + plan_pos(s_r[h], node >> LOGK) * K + (node & (K - 1))] = sum;
       }
     }
@@ -191,12 +196,13 @@ bool insert_fits_one_workgroup(const Geom& g, const FieldTable* ft, uint32_t n) 
 template <int LOGK>
 static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n,
                                         uint32_t cursor, const float* prio, uint32_t* out_idx, uint32_t stale_hb,
-                                        const uint32_t* protect, uint32_t n_protect, hipStream_t s) {
+                                        const uint32_t* protect, uint32_t n_protect, bool track_min, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
   FieldTable f{};
   if (ft) f = *ft;
   InsertArgs a{};
   a.g = g;
+  a.track_min = track_min ? 1u : 0u;
   InsertPlan& plan = a.plan;
   const uint64_t end = (uint64_t)cursor + n;
   Range2 r;
@@ -224,8 +230,8 @@ static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const F
 
 hipError_t launch_insert_small(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n, uint32_t cursor,
                                const float* prio, uint32_t* out_idx, uint32_t stale_hb, const uint32_t* protect,
-                               uint32_t n_protect, hipStream_t s) {
-#define CALL(L) launch_insert_small_k<L>(g, tn, ft, n, cursor, prio, out_idx, stale_hb, protect, n_protect, s)
+                               uint32_t n_protect, bool track_min, hipStream_t s) {
+#define CALL(L) launch_insert_small_k<L>(g, tn, ft, n, cursor, prio, out_idx, stale_hb, protect, n_protect, track_min, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

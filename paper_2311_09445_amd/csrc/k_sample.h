@@ -242,11 +242,12 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
       __syncthreads();
       uint32_t mm = 0x7F800000u;
       for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_min[wv] < mm ? s_min[wv] : mm;
+      if (parity & kWeightBufferNorm) mm = buffer_min_bits(g, t, parity);   // (uniform over the launch)
       if (active) out_w[o] = importance_weight(val, __uint_as_float(mm), beta);
     } else {                // partial minima, spread over kVminSlots addresses; the weights job finishes
       if (active) out_w[o] = val;
       if (lane == 0)
-        atomicMin(&g.vmin[((size_t)parity * g.T + t) * kVminSlots + ((bx * (blockDim.x >> 6) + wave) % kVminSlots)], m);
+        atomicMin(&g.vmin[((size_t)(parity & 1u) * g.T + t) * kVminSlots + ((bx * (blockDim.x >> 6) + wave) % kVminSlots)], m);
     }
   }
   if (claim_mode == 1) {   // element s of the update batch is this lane's own sample
@@ -260,10 +261,12 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
 // Finishes the importance weights of tree t: folds the partial minima of this call, re-arms
 // the other buffer for the next call, and turns the sampled values left in w into weights.
 // Called by whole workgroups of any size; `first` marks the one that re-arms.
+// `mode`: see kWeightBufferNorm.
 __device__ __forceinline__ void weights_job(const Geom& g, uint32_t t, uint32_t B, uint32_t size, float beta,
-                                            float* __restrict__ w, uint32_t parity, uint32_t job_block,
+                                            float* __restrict__ w, uint32_t mode, uint32_t job_block,
                                             uint32_t job_blocks) {
   __shared__ uint32_t s_wmin[16];
+  const uint32_t parity = mode & 1u;
   if (job_block != 0 && job_block * blockDim.x >= B) return;   // nothing to do for this workgroup
   const uint32_t* part = g.vmin + ((size_t)parity * g.T + t) * kVminSlots;
   uint32_t m = 0x7F800000u;
@@ -279,6 +282,7 @@ __device__ __forceinline__ void weights_job(const Geom& g, uint32_t t, uint32_t 
   // No minimum at all means that nothing could be sampled (the tree's total was zero): weights 0.  (The root
   // itself must not be consulted here: a tree pass running beside this job may already have rewritten it.)
   const bool nothing_sampled = mm == 0x7F800000u;
+  if (mode & kWeightBufferNorm) mm = buffer_min_bits(g, t, mode);   // (uniform over the launch)
   for (uint32_t i = job_block * blockDim.x + threadIdx.x; i < B; i += job_blocks * blockDim.x) {
     const size_t o = (size_t)t * B + i;
     w[o] = nothing_sampled ? 0.0f : importance_weight(w[o], __uint_as_float(mm), beta);
@@ -306,8 +310,8 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const Cl
 template <int LOGK>
 static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
                                   const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w,
-                                  float* out_prio, uint32_t* weight_calls, uint32_t stale_hb, const FieldTable* rows,
-                                  const ClaimArgs* claim, int claim_mode, hipStream_t s) {
+                                  float* out_prio, uint32_t* weight_calls, uint32_t weight_mode, uint32_t stale_hb,
+                                  const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
   constexpr uint32_t kLdsCap = 128 * 1024;
   const uint32_t wave_bytes = LOGK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
@@ -345,7 +349,7 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   if (bytes < tn.sample_min_lds) bytes = tn.sample_min_lds;   // asking for more LDS than needed spreads workgroups over more CUs
   // The two buffers of partial minima alternate between the calls that use them (k_weights of
   // one call re-arms the buffer of the next).
-  const uint32_t parity = *weight_calls & 1u;
+  const uint32_t parity = (*weight_calls & 1u) | weight_mode;   // (weight_mode: the bits above bit 0)
   if (out_w && gx > 1) ++*weight_calls;
   hipError_t e;
   int stale = -1;
@@ -413,9 +417,10 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   }
 
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
-                         const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
-                         const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s) {
-#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, rng, out_idx, out_w, out_prio, weight_calls, stale_hb, rows, claim, claim_mode, s)
+                         const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls,
+                         uint32_t weight_mode, uint32_t stale_hb, const FieldTable* rows, const ClaimArgs* claim,
+                         int claim_mode, hipStream_t s) {
+#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, rng, out_idx, out_w, out_prio, weight_calls, weight_mode, stale_hb, rows, claim, claim_mode, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

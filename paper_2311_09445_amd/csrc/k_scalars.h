@@ -28,7 +28,8 @@ __global__ void k_init_scalars(Geom g, float init_max) {
   if (t >= g.T) return;
   g.max_v[t] = init_max;
   g.status[t] = 0;
-  for (uint32_t k = 0; k < 2 * kVminSlots; ++k) g.vmin[(size_t)k * g.T + t] = 0x7F800000u;
+  for (uint32_t k = 0; k < 2 * kVminSlots; ++k) g.vmin[(size_t)k * g.T + t] = kNoMin;
+  for (uint32_t k = 0; k < 2 * kMinSlots; ++k) g.vmin_buf[(size_t)(k / kMinSlots) * g.T * kMinSlots + (size_t)t * kMinSlots + k % kMinSlots] = kNoMin;
 }
 
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s) {
@@ -36,10 +37,20 @@ hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s) {
   return hipGetLastError();
 }
 
-// which: 0 = root of every tree, 1 = running max priority
+// which: 0 = root of every tree, 1 = running max priority, 2 / 3 = smallest positive leaf as reduced into
+// entry 0 / 1 of vmin_buf
 __global__ void k_read_scalars(Geom g, int which, float* out) {
   const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= g.T) return;
+  if (which >= 2) {
+    uint32_t m = kNoMin;
+    for (uint32_t k = 0; k < kMinSlots; ++k) {
+      const uint32_t v = g.vmin_buf[((size_t)(which - 2) * g.T + t) * kMinSlots + k];
+      m = v < m ? v : m;
+    }
+    out[t] = __uint_as_float(m);
+    return;
+  }
   out[t] = which == 0 ? g.root[(size_t)t * g.root_stride] : g.max_v[t];
 }
 

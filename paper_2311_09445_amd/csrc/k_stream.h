@@ -62,6 +62,7 @@ struct LdsTree {
   uint32_t* sampled;        // [1024] indices of the latest sampling operation
   uint32_t* max_bits;       // running maximum priority (fp32 bits)
   uint32_t* vmin_bits;      // minimum of the batch being sampled (fp32 bits)
+  uint32_t* bmin_bits;      // smallest positive leaf of the tree (fp32 bits), when the weights are relative to it
   uint32_t* skip;           // [32] bit j: row j of the insertion under way is deferred
   uint32_t H, N;
 };
@@ -126,12 +127,21 @@ __device__ __forceinline__ void lds_insert(const LdsTree& lt, const FieldTable& 
 template <int LOGK>
 __device__ __forceinline__ uint32_t lds_sample(const LdsTree& lt, const FieldTable& rows, uint32_t t, uint64_t dense_row0,
                                                uint32_t B, float u_i, float beta, uint32_t* out_idx, float* out_w,
-                                               float* out_prio, uint32_t& flags) {
+                                               float* out_prio, bool buffer_norm, uint32_t& flags) {
   constexpr int K = Fan<LOGK>::K;
   const uint32_t tid = threadIdx.x;
-  if (tid == 0) *lt.vmin_bits = 0x7F800000u;
+  if (tid == 0) {
+    *lt.vmin_bits = kNoMin;
+    *lt.bmin_bits = kNoMin;
+  }
   __syncthreads();
   const float total = lt.tree[lt.off[lt.H]];
+  if (buffer_norm && out_w) {   // weights relative to the whole tree: its smallest positive leaf, by a sweep over the LDS copy
+    uint32_t m = kNoMin;
+    for (uint32_t e = tid; e < lt.N; e += blockDim.x) m = min_u32(m, positive_bits(lt.tree[lt.off[0] + e]));
+    m = wave_min_u32(m);
+    if ((tid & 63u) == 0 && m != kNoMin) atomicMin(lt.bmin_bits, m);
+  }
   uint32_t node = 0xFFFFFFFFu;
   float val = 0.0f;
   if (total > 0.0f) {
@@ -157,7 +167,9 @@ __device__ __forceinline__ uint32_t lds_sample(const LdsTree& lt, const FieldTab
   // (the weights, a power per sample, are computed while the rows are on their way: every lane that
   // owns a sample also owns a row element of the first sweep, so no wave runs the power twice)
   auto weights = [&]() {
-    if (out_w && tid < B) out_w[tid] = total > 0.0f ? importance_weight(val, __uint_as_float(*lt.vmin_bits), beta) : 0.0f;
+    if (out_w && tid < B)
+      out_w[tid] = total > 0.0f ? importance_weight(val, __uint_as_float(buffer_norm ? *lt.bmin_bits : *lt.vmin_bits), beta)
+                                : 0.0f;
   };
   if (move_rows_one_workgroup<true>(rows, t, dense_row0, B, 0, lt.N, lt.sampled, nullptr, weights)) flags |= 1u;
   return node;
@@ -216,7 +228,7 @@ k_run_steps(StreamKernelArgs ka) {
   extern __shared__ __attribute__((aligned(16))) float tree[];
   __shared__ LevelTable tab;
   __shared__ uint32_t s_off[kMaxHeight + 2];
-  __shared__ uint32_t s_max, s_vmin, s_flags;
+  __shared__ uint32_t s_max, s_vmin, s_bmin, s_flags;
   const uint32_t t = blockIdx.x;
   const uint32_t tid = threadIdx.x;
   const uint32_t H = g.H, T = g.T, B = a.B, n_ins = a.n_insert;
@@ -234,6 +246,7 @@ k_run_steps(StreamKernelArgs ka) {
   lt.sampled = reinterpret_cast<uint32_t*>(tree + s_off[H + 1]);
   lt.max_bits = &s_max;
   lt.vmin_bits = &s_vmin;
+  lt.bmin_bits = &s_bmin;
   lt.skip = nullptr;
   lt.H = H;
   lt.N = g.N;
@@ -260,7 +273,8 @@ k_run_steps(StreamKernelArgs ka) {
                        flags);
     }
     const uint32_t node = lds_sample<LOGK>(lt, a.rows, t, ((uint64_t)s * T + t) * B, B, u_i, beta, a.out_idx + bo,
-                                           a.out_w ? a.out_w + bo : nullptr, a.out_prio ? a.out_prio + bo : nullptr, flags);
+                                           a.out_w ? a.out_w + bo : nullptr, a.out_prio ? a.out_prio + bo : nullptr,
+                                           a.buffer_norm != 0, flags);
     if (a.upd_prio) lds_update<LOGK>(lt, B, a.upd_is_sampled ? node : up_i, up_v, size, flags);
     __syncthreads();
   }
@@ -289,7 +303,7 @@ k_run_requests(QueueKernelArgs ka) {
   __shared__ FieldTable s_ft;        // the buffer's columns with the current request's row arrays
   __shared__ uint32_t s_off[kMaxHeight + 2];
   __shared__ uint32_t s_skip[32];
-  __shared__ uint32_t s_max, s_vmin, s_flags;
+  __shared__ uint32_t s_max, s_vmin, s_bmin, s_flags;
   const uint32_t t = blockIdx.x;
   const uint32_t tid = threadIdx.x;
   const uint32_t H = g.H;
@@ -308,6 +322,7 @@ k_run_requests(QueueKernelArgs ka) {
   lt.sampled = reinterpret_cast<uint32_t*>(tree + s_off[H + 1]);
   lt.max_bits = &s_max;
   lt.vmin_bits = &s_vmin;
+  lt.bmin_bits = &s_bmin;
   lt.skip = s_skip;
   lt.H = H;
   lt.N = g.N;
@@ -329,7 +344,7 @@ k_run_requests(QueueKernelArgs ka) {
     } else if (q.op == PER_OP_SAMPLE) {
       const float u_i = tid < n ? q.u[to + tid] : 0.0f;
       last_node = lds_sample<LOGK>(lt, s_ft, t, to, n, u_i, q.beta, q.idx + to, q.out_weight ? q.out_weight + to : nullptr,
-                                   q.out_prio ? q.out_prio + to : nullptr, flags);
+                                   q.out_prio ? q.out_prio + to : nullptr, a.buffer_norm != 0, flags);
     } else if (q.op == PER_OP_UPDATE) {
       float v = 0.0f;
       uint32_t i = last_node;

@@ -36,8 +36,10 @@ struct SubLevels {
 constexpr uint32_t kDirtyListCap = 2048;
 constexpr uint32_t kLazyTopNodes = 4096;
 
-// The work of workgroup b of tree t (b = its subtree's root at height hb).
-template <int LOGK>
+// The work of workgroup b of tree t (b = its subtree's root at height hb).  TRACK_MIN: also renew min1
+// (smallest positive leaf) of every rebuilt height-1 node; a compile-time choice, because even as a
+// never-taken branch that code cost the pass half a microsecond.
+template <int LOGK, bool TRACK_MIN>
 __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uint32_t t, uint32_t b, uint32_t chain) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
@@ -151,6 +153,7 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
       LeafVec c;
       uint2 s[4];
       uint2 e;
+      uint32_t mn;   // (TRACK_MIN only)
     };
     // A set bit means the leaf was claimed leaf by leaf in this batch: its stamp entry holds the winner's value.
     auto fetch = [&](uint32_t item) -> Item {
@@ -190,6 +193,7 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
         if (sel & 2u) it.c.y = ev;
         it.my |= sel;
         sum = it.c.x + it.c.y;
+        if constexpr (TRACK_MIN) it.mn = min_u32(positive_bits(it.c.x), positive_bits(it.c.y));
       } else {
         if (it.my & 1u) it.c.x = __uint_as_float(it.s[0].x);
         if (it.my & 2u) it.c.y = __uint_as_float(it.s[1].x);
@@ -203,6 +207,13 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
         sum = (it.c.x + it.c.y) + (it.c.z + it.c.w);
 #pragma unroll
         for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) sum = sum + __shfl_xor(sum, 1 << k);
+        if constexpr (TRACK_MIN) {
+          uint32_t m = min_u32(min_u32(positive_bits(it.c.x), positive_bits(it.c.y)),
+                               min_u32(positive_bits(it.c.z), positive_bits(it.c.w)));
+#pragma unroll
+          for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) m = min_u32(m, (uint32_t)__shfl_xor((int)m, 1 << k));
+          it.mn = m;
+        }
       }
       return sum;
     };
@@ -211,6 +222,7 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
       if (it.ok && q == 0) {
         lvl1[it.node] = sum;
         sub[it.node - lo1] = sum;
+        if constexpr (TRACK_MIN) g.min1[(size_t)t * g.min1_stride + it.node] = it.mn;
       }
     };
     for (uint32_t base = 0; base < nd; base += 2 * ngrp) {
@@ -297,10 +309,10 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
 // Two 1024-lane workgroups share a compute unit only while a wave stays within an eighth of the
 // SIMD's scalar and vector registers; with one more scalar register than that the second workgroup
 // waits for the first to end and the kernel takes half as long again.
-template <int LOGK>
+template <int LOGK, bool TRACK_MIN>
 __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8)))
 k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
-  tree_job<LOGK>(g, sl, blockIdx.y, blockIdx.x, chain);
+  tree_job<LOGK, TRACK_MIN>(g, sl, blockIdx.y, blockIdx.x, chain);
 }
 
 // Second kernel of a fused step whose claim phase rode in the sampling kernel: the tree pass
@@ -308,12 +320,12 @@ k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
 // importance weights and the rows of the sampled indices (JobRanges, offset by tree_blocks).  The
 // tree pass is a chain of dependent memory trips and the row traffic fills the gaps; launched with
 // workgroups of at most 512 lanes so that the two kinds share the compute units.
-template <int LOGK>
+template <int LOGK, bool TRACK_MIN>
 __global__ void __launch_bounds__(512)
 k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldTable ft, JobRanges jr, FinishArgs a) {
   const uint32_t t = blockIdx.y;
   if (blockIdx.x < tree_blocks) {
-    tree_job<LOGK>(g, sl, t, blockIdx.x, chain);
+    tree_job<LOGK, TRACK_MIN>(g, sl, t, blockIdx.x, chain);
     return;
   }
   const uint32_t b = blockIdx.x - tree_blocks;
@@ -403,8 +415,14 @@ static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, const ClaimArgs
   uint32_t tblock;
   hipError_t e = tree_pass_shape<LOGK>(g, tn, c, &sl, &tblock);
   if (e != hipSuccess) return e;
-  PER_LAUNCH(KID_UPDATE_TREE, k_update_tree<LOGK>, dim3(g.n[sl.hb], g.T), dim3(tblock), tree_lds_bytes<LOGK>(sl), s, g,
-             sl, lazy_top_height(g, tn) ? 0u : 1u);
+  const uint32_t chain = lazy_top_height(g, tn) ? 0u : 1u;
+  if (c.track_min) {
+    PER_LAUNCH(KID_UPDATE_TREE, (k_update_tree<LOGK, true>), dim3(g.n[sl.hb], g.T), dim3(tblock), tree_lds_bytes<LOGK>(sl),
+               s, g, sl, chain);
+  } else {
+    PER_LAUNCH(KID_UPDATE_TREE, (k_update_tree<LOGK, false>), dim3(g.n[sl.hb], g.T), dim3(tblock), tree_lds_bytes<LOGK>(sl),
+               s, g, sl, chain);
+  }
   return hipGetLastError();
 }
 
@@ -421,8 +439,15 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const Cl
   if (rows) ft = *rows;
   const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u);
   const uint32_t tree_blocks = g.n[sl.hb];
-  PER_LAUNCH(KID_TREE_FINISH, k_tree_finish<LOGK>, dim3(tree_blocks + jr.first[2 + kMaxFields], g.T), dim3(tblock),
-             tree_lds_bytes<LOGK>(sl), s, g, sl, lazy_top_height(g, tn) ? 0u : 1u, tree_blocks, ft, jr, a);
+  const uint32_t chain = lazy_top_height(g, tn) ? 0u : 1u;
+  const dim3 grid(tree_blocks + jr.first[2 + kMaxFields], g.T);
+  if (c.track_min) {
+    PER_LAUNCH(KID_TREE_FINISH, (k_tree_finish<LOGK, true>), grid, dim3(tblock), tree_lds_bytes<LOGK>(sl), s, g, sl, chain,
+               tree_blocks, ft, jr, a);
+  } else {
+    PER_LAUNCH(KID_TREE_FINISH, (k_tree_finish<LOGK, false>), grid, dim3(tblock), tree_lds_bytes<LOGK>(sl), s, g, sl, chain,
+               tree_blocks, ft, jr, a);
+  }
   return hipGetLastError();
 }
 

@@ -23,6 +23,9 @@ struct per_buffer {
   bool groups_stale;         // the claim group entries are to be cleared before their next use
   bool leaves_stale;         // and so are the per-leaf stamps (an arena copied back may hold stamps of another counter)
   uint32_t weight_calls;     // number of per_sample calls that used the partial-minimum buffers
+  int weight_norm;           // PER_NORM_BATCH or PER_NORM_BUFFER
+  bool min_stale;            // min1 does not describe the leaves (it is rebuilt when next needed)
+  uint32_t min_calls;        // number of reductions of min1 so far (their results alternate between two entries)
   uint32_t stale_hb;         // != 0: the last update left the heights above this one to their next reader
   bool rng_on;               // per_set_rng was called: sampling calls without uniforms draw their own
   uint64_t rng_seed, rng_calls;   // key of the generator; number of sampling calls that drew from it
@@ -41,10 +44,10 @@ struct Layout {
   uint32_t n[kMaxHeight + 1];
   uint32_t stride[kMaxHeight + 1];
   size_t level_off[kMaxHeight + 1];
-  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, col_off[kMaxFields];
+  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, min1_off, col_off[kMaxFields];
   uint32_t dirty_stride, arrive_stride, arrive_level_off[kMaxHeight + 1];
   uint64_t col_stride[kMaxFields];
-  uint32_t owner_stride, nclaim_stride;
+  uint32_t owner_stride, nclaim_stride, min1_stride;
   size_t tree_end;            // bytes up to here are zero-filled as 32-bit words at create
   size_t total;
 };
@@ -75,8 +78,8 @@ void make_layout(const per_config* c, Layout* L) {
   } while (n > 1);
   L->H = h;
   size_t off = 0;
-  L->scalars_off = off;                         // max_v[T], status[T], vmin[2][T][kVminSlots]
-  off = round_up(off + (size_t)(2 + 2 * kVminSlots) * T * 4, kAlign);
+  L->scalars_off = off;                         // max_v[T], status[T], vmin[2][T][kVminSlots], vmin_buf[2][T][kMinSlots]
+  off = round_up(off + (size_t)(2 + 2 * kVminSlots + 2 * kMinSlots) * T * 4, kAlign);
   for (uint32_t l = 0; l <= L->H; ++l) {
     const uint64_t padded = ((uint64_t)L->n[l] + K - 1) / K * K;
     L->stride[l] = (uint32_t)round_up(padded, 64);
@@ -101,6 +104,9 @@ void make_layout(const per_config* c, Layout* L) {
   L->arrive_stride = (uint32_t)round_up((size_t)counters + 1, 64);
   L->arrive_off = off;
   off = round_up(off + (size_t)L->arrive_stride * T * 4, kAlign);
+  L->min1_stride = (uint32_t)round_up(L->n[1], 64);
+  L->min1_off = off;
+  off = round_up(off + (size_t)L->min1_stride * T * 4, kAlign);
   L->tree_end = off;
   for (uint32_t f = 0; f < c->n_fields; ++f) {
     L->col_stride[f] = round_up((size_t)c->capacity * c->field_bytes[f], kAlign);
@@ -135,6 +141,27 @@ int fill_fields(per_t* p, void* const* io, FieldTable* ft) {
 }
 
 int hip_rc(hipError_t e) { return e == hipSuccess ? PER_OK : PER_EHIP; }
+
+// True when min1 is being kept current, so that kernels rewriting leaves must renew it; a caller whose
+// kernels cannot do that marks it stale instead.
+bool tracks_min(const per_t* p) { return p->weight_norm == PER_NORM_BUFFER && !p->min_stale; }
+
+// Brings vmin_buf up to date for a reader: min1 from the leaves if it is stale, then its reduction.  Returns the
+// weight-mode bits naming the entry that holds the result.
+hipError_t reduce_min(per_t* p, hipStream_t s, uint32_t* mode_bits) {
+  hipError_t e = hipSuccess;
+  if (p->min_stale) {
+    e = launch_min_rebuild(p->g, p->tn, s);
+    if (e != hipSuccess) return e;
+    p->min_stale = false;
+  }
+  const uint32_t parity = p->min_calls & 1u;
+  e = launch_min_reduce(p->g, p->tn, parity, s);
+  if (e != hipSuccess) return e;
+  ++p->min_calls;
+  *mode_bits = kWeightBufferNorm | (parity << kWeightBufferParityShift);
+  return hipSuccess;
+}
 
 // Rebuilds the heights an update left stale, for readers that take them from memory.
 hipError_t ensure_top(per_t* p, hipStream_t s) {
@@ -197,6 +224,9 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.max_v = reinterpret_cast<float*>(p->arena + L.scalars_off);
   g.status = reinterpret_cast<uint32_t*>(g.max_v + g.T);
   g.vmin = g.status + g.T;
+  g.vmin_buf = g.vmin + (size_t)2 * kVminSlots * g.T;
+  g.min1 = reinterpret_cast<uint32_t*>(p->arena + L.min1_off);
+  g.min1_stride = L.min1_stride;
   for (uint32_t f = 0; f < cfg->n_fields; ++f) {
     p->col[f] = p->arena + L.col_off[f];
     p->col_stride[f] = L.col_stride[f];
@@ -214,6 +244,9 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.prof = &p->prof;
   p->stamp_next = 1;
   p->groups_stale = p->leaves_stale = false;
+  p->weight_norm = PER_NORM_BATCH;
+  p->min_stale = true;
+  p->min_calls = 0;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -249,12 +282,13 @@ static int insert_impl(per_t* p, uint32_t n, const void* const* d_field_src, con
   if ((p->tn.insert_small || n_protect) && one_workgroup) {
     // one kernel: rows, leaves, ancestors, and the heights an update may have left stale
     hipError_t e1 = launch_insert_small(p->g, p->tn, has_rows ? &ft : nullptr, n, cursor, d_prio, d_out_idx, p->stale_hb,
-                                        n_protect ? d_protect : nullptr, n_protect, s);
+                                        n_protect ? d_protect : nullptr, n_protect, tracks_min(p), s);
     if (e1 == hipSuccess) p->stale_hb = 0;
     p->cursor = (p->cursor + n) % N;
     p->size = p->size + n > N ? N : p->size + n;
     return hip_rc(e1);
   }
+  p->min_stale = true;   // (the kernels of a large insert do not renew min1)
   hipError_t e = ensure_top(p, s);
   if (e == hipSuccess && has_rows) e = launch_scatter(p->g, p->tn, ft, n, cursor, s);
   if (e == hipSuccess) e = launch_insert_leaves(p->g, p->tn, n, cursor, d_prio, d_out_idx, s);
@@ -314,6 +348,8 @@ static int reserve_stamps(per_t* p, uint32_t B, hipStream_t s, ClaimArgs* c) {
   p->groups_stale = p->leaves_stale = false;
   c->stamp_base = (uint32_t)next;
   c->group_mode = fits_span && p->tn.group_claim ? 1u : 0u;
+  c->track_min = tracks_min(p) ? 1u : 0u;   // (else min1 is, or now becomes, stale)
+  if (!c->track_min) p->min_stale = true;
   next += B;
   if (!fits_span) next = ((next - 1) | kGroupStampMask) + 2;
   p->stamp_next = next;
@@ -349,6 +385,10 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
   hipStream_t s = static_cast<hipStream_t>(stream);
   FieldTable ft;
   const bool fused = d_field_dst && fill_fields(p, d_field_dst, &ft);
+  uint32_t weight_mode = 0;
+  if (d_out_weight && p->weight_norm == PER_NORM_BUFFER &&   // the weights refer to the tree as it is before this call's update
+      reduce_min(p, s, &weight_mode) != hipSuccess)
+    return PER_EHIP;
   ClaimArgs claim{};
   int claim_mode = CLAIM_NONE;
   if (upd_B) {
@@ -386,7 +426,8 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
   const uint32_t stale = p->stale_hb;
   p->stale_hb = 0;   // the sampling kernel rebuilds and stores the stale heights
   hipError_t e = launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, rng, d_out_idx, d_out_weight, d_out_prio,
-                               &p->weight_calls, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr, claim_mode, s);
+                               &p->weight_calls, weight_mode, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr,
+                               claim_mode, s);
   if (e == hipSuccess && upd_B) p->stale_hb = lazy_top_height(p->g, p->tn);   // the tree pass ran
   return hip_rc(e);
 }
@@ -463,6 +504,7 @@ int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d
   int rc = check_update_args(p, B, d_idx, d_delta);
   if (rc != PER_OK || B == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  p->min_stale = true;               // (changes added by atomics: min1 cannot follow them)
   hipError_t e = ensure_top(p, s);   // changes are added to whole nodes: the top heights must be current
   if (e == hipSuccess) e = launch_update_delta(p->g, p->tn, B, (uint32_t)p->size, d_idx, d_delta, s);
   return hip_rc(e);
@@ -489,6 +531,8 @@ int per_run_steps(per_t* p, uint32_t n_steps, uint32_t n_insert, uint32_t B, con
   a.cursor = (uint32_t)p->cursor;
   a.size = (uint32_t)p->size;
   a.upd_is_sampled = io->d_upd_prio && !io->d_upd_idx ? 1u : 0u;
+  a.buffer_norm = p->weight_norm == PER_NORM_BUFFER ? 1u : 0u;
+  p->min_stale = true;   // (the kernel works on an LDS copy of the leaves and does not keep min1)
   a.u = io->d_u;
   a.beta = io->d_beta;
   a.out_idx = io->d_out_idx;
@@ -544,6 +588,8 @@ int per_run_requests(per_t* p, uint32_t n_requests, const per_request* h_request
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   a.n_requests = n_requests;
+  a.buffer_norm = p->weight_norm == PER_NORM_BUFFER ? 1u : 0u;
+  p->min_stale = true;   // (as per_run_steps)
   a.cursor = (uint32_t)p->cursor;
   a.size = (uint32_t)p->size;
   a.queue = d_requests;
@@ -615,7 +661,22 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size) {
   p->size = size;
   p->stale_hb = lazy_top_height(p->g, p->tn);   // a saved arena may predate the rebuild of its top heights
   p->groups_stale = p->leaves_stale = true;     // and its last-writer stamps belong to the counter it was saved under
+  p->min_stale = true;
   return PER_OK;
+}
+
+int per_set_weight_norm(per_t* p, int mode) {
+  if (!p || (mode != PER_NORM_BATCH && mode != PER_NORM_BUFFER)) return PER_EINVAL;
+  p->weight_norm = mode;
+  return PER_OK;
+}
+
+int per_min_priority(per_t* p, float* d_out, void* stream) {
+  if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint32_t mode = 0;
+  if (reduce_min(p, s, &mode) != hipSuccess) return PER_EHIP;
+  return hip_rc(launch_read_scalars(p->g, 2 + (int)((mode >> kWeightBufferParityShift) & 1u), d_out, s));
 }
 
 int per_set_rng(per_t* p, uint64_t seed, uint64_t next_call) {

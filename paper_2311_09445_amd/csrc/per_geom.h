@@ -39,7 +39,19 @@ struct Geom {
   float*    max_v;                  // [T] running max priority
   uint32_t* status;                 // [T] sticky flags
   uint32_t* vmin;                   // [2][T][kVminSlots] partial batch minima of sampled values (fp32 bits)
+  uint32_t* min1;                   // [T][min1_stride] smallest positive leaf under each height-1 node (fp32 bits; kNoMin: none)
+  uint32_t min1_stride;
+  uint32_t* vmin_buf;               // [2][T][kMinSlots] partial minima of min1 (fp32 bits), as reduced for a sampling call
 };
+constexpr uint32_t kMinSlots = 64;       // one per lane of a wave: a reader folds them with one wave reduction
+
+constexpr uint32_t kNoMin = 0x7F800000u;   // fp32 bits of +inf: above every valid priority
+
+// How a sampling call scales its importance weights, packed into one kernel argument:
+// bit 0: which of the two buffers of partial batch minima the call uses; bit 1: scale by the smallest
+// positive leaf of the whole tree instead of the batch's; bit 2: which vmin_buf entry holds it.
+constexpr uint32_t kWeightBufferNorm = 2u;
+constexpr uint32_t kWeightBufferParityShift = 2u;
 
 struct FieldTable {
   uint8_t* col[kMaxFields];         // column f of tree 0
@@ -60,6 +72,7 @@ constexpr uint32_t kNoGroupStamp = 0xFFFFFFFFu;   // floor above every group sta
 struct ClaimArgs {
   uint32_t B, size, stamp_base;
   uint32_t group_mode;     // the batch claims through the group entries (else leaf by leaf)
+  uint32_t track_min;      // the tree pass also renews min1 of the height-1 nodes it rebuilds
   const uint32_t* idx;     // [T][B]
   const float* prio;       // [T][B] tree values, or temporal-difference errors when from_td is set
   uint32_t from_td;        // value = (|prio| + td_eps)^td_alpha, fp64, rounded once
@@ -98,6 +111,7 @@ struct StreamArgs {
   uint32_t n_steps, n_insert, B;
   uint32_t cursor, size;            // ring state before the first step
   uint32_t upd_is_sampled;          // a step updates the batch it has just sampled
+  uint32_t buffer_norm;             // importance weights relative to the whole tree (else to the batch)
   const float* u;                   // [steps][T][B]
   const float* beta;                // [steps]
   uint32_t* out_idx;                // [steps][T][B]
@@ -114,6 +128,7 @@ struct StreamArgs {
 struct QueueArgs {
   uint32_t n_requests;
   uint32_t cursor, size;            // ring state before the first request
+  uint32_t buffer_norm;             // importance weights relative to the whole tree (else to the batch)
   const per_request* queue;         // device copy of the requests
   FieldTable fields;                // columns, row sizes and access widths; the io pointers come from the requests
   uint32_t off[kMaxHeight + 2];     // as in StreamArgs
@@ -131,7 +146,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_UPDATE_DELTA, KID_GET_PRIORITY,
-  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_COUNT
+  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_MIN_REBUILD, KID_MIN_REDUCE, KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -160,9 +175,12 @@ struct Tuning {
 // Launchers (per_kernels.hip).  All enqueue on `s` and return hipGetLastError().
 hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32_t value, hipStream_t s);
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
+hipError_t launch_min_rebuild(const Geom& g, const Tuning& tn, hipStream_t s);
+hipError_t launch_min_reduce(const Geom& g, const Tuning& tn, uint32_t parity, hipStream_t s);
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          const RngArgs& rng,
-                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t stale_hb,
+                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t weight_mode,
+                         uint32_t stale_hb,
                          const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s);
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s);
@@ -173,7 +191,7 @@ hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uin
 bool insert_fits_one_workgroup(const Geom& g, const FieldTable* ft, uint32_t n);
 hipError_t launch_insert_small(const Geom& g, const Tuning& tn, const FieldTable* ft, uint32_t n, uint32_t cursor,
                                const float* prio, uint32_t* out_idx, uint32_t stale_hb, const uint32_t* protect,
-                               uint32_t n_protect, hipStream_t s);
+                               uint32_t n_protect, bool track_min, hipStream_t s);
 hipError_t launch_resum_ranges(const Geom& g, const Tuning& tn, Range2 r0, hipStream_t s);
 hipError_t launch_resum_top(const Geom& g, const Tuning& tn, uint32_t hb, hipStream_t s);
 uint32_t lazy_top_height(const Geom& g, const Tuning& tn);

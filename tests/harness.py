@@ -42,6 +42,19 @@ class Mirror:
         assert self.gpu.H == self.cpu.H
 
     # ---------------------------------------------------------------- operations
+    def set_weight_norm(self, mode):
+        self.gpu.set_weight_norm(mode)
+        self.cpu.set_weight_norm(mode)
+
+    def compare_min_priority(self):
+        """The companion minimum against its definition: the smallest positive leaf of each tree, bit for bit."""
+        got = self.gpu.min_priority().cpu().numpy()
+        for t in range(self.T):
+            leaves = self.cpu.read_level(t, 0)
+            pos = leaves[leaves > 0]
+            want = np.float32(pos.min()) if pos.size else np.float32(np.inf)
+            assert got[t].tobytes() == want.tobytes(), f"tree {t}: smallest positive leaf {got[t]} vs {want}"
+
     def insert(self, n, prio=None, with_rows=True, chunk=None):
         """Insert n rows per tree (row bytes = hash of tree / insert counter / field / offset)."""
         chunk = n if chunk is None else chunk

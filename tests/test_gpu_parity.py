@@ -667,6 +667,109 @@ def test_run_steps_limits_and_empty_tree():
 
 
 # ---------------------------------------------------------------------------------------------
+# importance weights relative to the whole buffer (companion minimum of the sum tree)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K", [2, 4, 8, 16, 32, 64])
+@pytest.mark.parametrize("N,T", [(5, 2), (1000, 1), (4097, 3), (70000, 1)])
+def test_buffer_wide_weights_through_an_operation_mix(K, N, T):
+    """As the random operation mix, with the weights relative to the smallest positive leaf of the tree: the
+    companion minimum has to follow large inserts (rebuilt), small inserts and updates (renewed in place),
+    the delta-form update (rebuilt), zeros and duplicates; it is compared with its definition after every
+    operation, and the weights with the oracle's."""
+    log(f"buffer-wide weights K={K} N={N} T={T}")
+    rng = np.random.default_rng(K * 7919 + N + T)
+    m = Mirror(K, N, T, (8,))
+    first = max(1, (2 * N) // 3)
+    prio = wl._draw_priorities("lognormal_0_1", rng, (T, first))
+    prio[:, ::5] = 0.0
+    m.insert(first, prio=prio)
+    m.set_weight_norm("buffer")
+    m.compare_min_priority()
+    for it in range(5):
+        B = int(rng.choice([1, 3, 64, 257, 1500]))
+        gi, ci = m.sample(wl.uniform01(rng, (T, B)), beta=float(rng.choice([0.4, 1.0])), fused_rows=(it % 2 == 0))
+        upd_idx = ci.copy()
+        if m.cpu.trees[0].size:
+            upd_idx[:, ::2] = rng.integers(0, m.cpu.trees[0].size, upd_idx[:, ::2].shape)
+        upd_prio = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B))
+        upd_prio[:, ::3] *= np.float32(1e-3)                       # new minima now and then
+        if B > 4:
+            upd_idx[:, B // 2:] = upd_idx[:, : B - B // 2]
+            upd_prio[:, 1] = np.nan
+            upd_prio[:, 2] = 0.0
+        if it == 3:                                                # the current minimum goes away
+            for t in range(T):
+                leaves = m.cpu.read_level(t, 0)
+                upd_idx[t, 0] = int(np.argmin(np.where(leaves > 0, leaves, np.inf)))
+                upd_prio[t, 0] = 5.0
+        m.update(upd_idx, upd_prio)
+        m.compare_tree()
+        m.compare_min_priority()
+        n_ins = int(rng.integers(1, max(2, N // 2))) if it % 2 else int(rng.integers(1, 9))
+        n_ins = min(n_ins, N)
+        ins = wl._draw_priorities("exponential_1", rng, (T, n_ins)) * np.float32(1e-2 if it == 2 else 1.0)
+        m.insert(n_ins, prio=None if it == 4 else ins)
+        m.compare_min_priority()
+        if it == 1:   # the delta form leaves the minimum to a rebuild (zeros: sums in any order stay bit-comparable)
+            didx = rng.integers(0, m.cpu.trees[0].size, (T, 20)).astype(np.uint32)
+            delta = np.zeros((T, 20), np.float32)
+            m.gpu.update_delta(idx_to_dev(didx), dev(delta))
+            m.cpu.update_delta(didx, delta)
+            m.compare_min_priority()
+    m.set_weight_norm("batch")                                     # and back: the largest weight is 1 again
+    gi, ci = m.sample(wl.uniform01(rng, (T, 64)), beta=0.7)
+    m.compare_status()
+
+
+@pytest.mark.parametrize("K,N,B", [(16, 65536, 4096), (32, 200000, 8192), (2, 3000, 300)])
+def test_buffer_wide_weights_in_the_fused_step_and_the_one_launch_forms(K, N, B):
+    log(f"buffer-wide weights, fused K={K} N={N} B={B}")
+    from paper_2311_09445_amd.per import OP_SAMPLE, OP_UPDATE
+    rng = np.random.default_rng(K + N)
+    T = 1
+    m = Mirror(K, N, T, (16,))
+    m.insert(N, prio=wl._draw_priorities("pareto_1.5", rng, (T, N)), chunk=50000)
+    m.set_weight_norm("buffer")
+    for it in range(4):                      # update batch = sampled batch (in place), apart, overlapping
+        upd = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B)) * np.float32(0.1 if it == 1 else 1.0)
+        if it == 3:
+            m.sample_gather_update(wl.uniform01(rng, (T, B)), 0.6, True, upd, tail=B // 3)
+        else:
+            m.sample_gather_update(wl.uniform01(rng, (T, B)), 0.6, True, upd, alias=(it % 2 == 0))
+        m.compare_tree()
+        m.compare_min_priority()
+    if m.gpu.run_steps_fits():
+        steps, Bs = 3, 64
+        u = wl.uniform01(rng, (steps, T, Bs))
+        beta = np.array([0.4, 0.7, 1.0], np.float32)
+        upd = (rng.random((steps, T, Bs)) * np.float32(0.01)).astype(np.float32)
+        oi = torch.empty((steps, T, Bs), dtype=torch.int32, device="cuda")
+        ow = torch.empty((steps, T, Bs), dtype=torch.float32, device="cuda")
+        m.gpu.run_steps(dev(u), dev(beta), oi, ow, upd_prio=dev(upd))
+        for s_ in range(steps):
+            ci, cw, cv = m.cpu.sample(u[s_], float(beta[s_]), True)
+            assert np.array_equal(idx_to_host(oi)[s_], ci)
+            np.testing.assert_allclose(ow.cpu().numpy()[s_], cw, rtol=1e-6, atol=0)
+            m.cpu.update(ci, upd[s_])
+        m.compare_min_priority()
+        u2 = wl.uniform01(rng, (T, Bs))
+        o2 = torch.empty((T, Bs), dtype=torch.int32, device="cuda")
+        w2 = torch.empty((T, Bs), dtype=torch.float32, device="cuda")
+        p2 = (rng.random((T, Bs)) * 2).astype(np.float32)
+        keep = m.gpu.run_requests([{"op": OP_SAMPLE, "u": dev(u2), "beta": 0.5, "idx": o2, "out_weight": w2},
+                                   {"op": OP_UPDATE, "prio": dev(p2)}])
+        ci, cw, cv = m.cpu.sample(u2, 0.5, True)
+        assert np.array_equal(idx_to_host(o2), ci)
+        np.testing.assert_allclose(w2.cpu().numpy(), cw, rtol=1e-6, atol=0)
+        m.cpu.update(ci, p2)
+        del keep
+        m.compare_tree()
+        m.compare_min_priority()
+    gi, ci = m.sample(wl.uniform01(rng, (T, 500)), beta=1.0)
+    m.compare_status()
+
+
+# ---------------------------------------------------------------------------------------------
 # per_run_requests: a queue of op-coded requests in one launch.  Same results as the calls, in queue order.
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("K,N,T,fb,seed", [(2, 4096, 1, (16, 4, 4, 16, 1), 1), (16, 30000, 2, (12,), 2),
