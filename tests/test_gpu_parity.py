@@ -150,6 +150,37 @@ def test_group_stamps_cross_their_span():
         m.compare_status()
 
 
+def test_update_batch_longer_than_a_group_stamp_span(claim_form):
+    """A batch of 2^26 + 3 elements cannot use the group entries (they keep 26 stamp bits): it claims leaf by
+    leaf, and the batches after it start a fresh span with the entries cleared."""
+    if claim_form != "group":
+        pytest.skip("the same path as the other form")
+    rng = np.random.default_rng(26)
+    K, N, T = 16, 1 << 16, 1
+    B = (1 << 26) + 3
+    m = Mirror(K, N, T, ())
+    m.insert(N, prio=rng.random((T, N)).astype(np.float32), with_rows=False)
+    m.update(rng.integers(0, N, (T, 5000)).astype(np.uint32), rng.random((T, 5000)).astype(np.float32))   # leaves entries behind
+    idx = rng.integers(0, N, (T, B), dtype=np.uint32)
+    prio = rng.random((T, B), dtype=np.float32)      # all below the initial running maximum of 1, which so stays put
+    log("long batch: device")
+    m.gpu.update(idx_to_dev(idx), dev(prio))
+    # expected leaves: the last writer of every index (the oracle's loop over 2^26 elements takes too long here)
+    last = np.full(N, -1, dtype=np.int64)
+    last[idx[0]] = np.arange(B)                 # later assignments win
+    leaves = m.cpu.read_level(0, 0).copy()
+    hit = last >= 0
+    leaves[hit] = prio[0, last[hit]]
+    log("long batch: oracle")
+    m.cpu.update(np.nonzero(hit)[0].astype(np.uint32)[None], leaves[hit][None])     # one element per written leaf
+    del idx, prio
+    m.compare_tree()
+    for it in range(2):
+        m.update(rng.integers(0, 300, (T, 4000)).astype(np.uint32), rng.random((T, 4000)).astype(np.float32))
+        m.compare_tree()
+    m.compare_status()
+
+
 @pytest.mark.parametrize("K", [2, 16, 32, 64])
 def test_claim_forms_alternate_on_one_buffer(K):
     """Batches that claim leaf by leaf and batches that claim through group entries follow one another on
