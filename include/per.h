@@ -28,8 +28,8 @@
  *    the host, in which case no work was enqueued.  Conditions only the device
  *    can see set sticky bits (PER_FLAG_*) read by per_status.
  *  - A batch of size 0 is valid and enqueues nothing.
- *  - The ring cursor, the filled size, the last-writer stamps of updates and a few similar
- *    counters are kept on the host (they are pure functions of the call sequence) and enter the
+ *  - The ring cursor, the filled size and a few similar counters (which of two buffers of partial
+ *    minima a sampling call uses, the call number of the generator of per_set_rng) are kept on the host (they are pure functions of the call sequence) and enter the
  *    kernels as arguments.  Calls may therefore be captured into a HIP graph, but the graph then
  *    stands for exactly the captured calls: launch it once, on the buffer state it was captured
  *    on, and capture again for the next stretch of calls.
@@ -272,9 +272,8 @@ uint64_t per_cursor(const per_t* p);     /* next ring slot                      
 
 /* Checkpoint / resume: a byte copy of the arena plus (cursor, size) is the whole state of a
  * buffer.  After the caller has copied a saved arena back, this sets the host mirrors to the
- * values saved with it.  cursor < N, size <= N.  (The last-writer stamps inside a saved arena were
- * taken from the counter of the buffer that wrote them: the next update after this call clears
- * the stamp arrays first.) */
+ * values saved with it.  cursor < N, size <= N.  Take the copy between calls (with the stream
+ * idle): the scratch arrays of an update are all zero then, which the next update relies on. */
 int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
 
 /* What the importance weights of the sampling calls are relative to.  w_i = (size * P(i) / total)^-beta is
@@ -308,10 +307,6 @@ uint64_t per_rng_calls(const per_t* p);
  *   "sample_block", "update_block", "gather_block" : workgroup sizes (multiples of 64, <= 1024)
  *   "tree_block" : workgroup size of the update's tree pass (multiple of 64, <= 1024; 0 = chosen per launch)
  *   "sample_min_lds" : lower bound in bytes of the sampling kernel's LDS request
- *   "stamp_next" : moves the last-writer stamp counter forward (never back); stamps are 32 bits and
- *                  the library clears the stamp array and starts over when they run out; the claim
- *                  group entries keep 26 of the bits and are cleared whenever a batch would cross a
- *                  multiple of 2^26
  *   "group_claim" : how per_update and the fused step find the last writer of a leaf.  0: every element
  *                  raises the 64-bit stamp of its leaf; 1 (default): every element raises the entry shared
  *                  by a group of 32 leaves (64 for K = 64), an array small enough to stay in cache, and

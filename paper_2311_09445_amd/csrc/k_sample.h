@@ -252,7 +252,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   }
   if (claim_mode == 1) {   // element s of the update batch is this lane's own sample
     uint32_t mx = 0, flags = 0;
-    if (active) claim_element(g, t, size, c.stamp_base, c.group_mode, s, node, upd_v, mx, flags);
+    if (active) claim_element(g, t, size, c.group_mode, s, node, upd_v, mx, flags);
     raise_max(g, t, mx, max_seen);
     if (flags) atomicOr(&g.status[t], flags);
   }

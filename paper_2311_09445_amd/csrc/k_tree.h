@@ -14,7 +14,6 @@ struct SubLevels {
   uint32_t lds_floats;            // total
   uint32_t list_cap;              // height-1 nodes under one workgroup root: entries of the workgroup's node list
   uint32_t hb;
-  uint32_t stamp_floor;           // group entries with a stamp at or above this one belong to the batch (kNoGroupStamp: none)
 };
 
 // Tree pass.  Workgroup b of tree t owns the subtree under node b of height hb and keeps the
@@ -26,7 +25,7 @@ struct SubLevels {
 //     the stamp entry, whose lower word is the value of the batch element that won that leaf; it
 //     replaces the leaf (and is stored), and so does the value of the group entry, which wins
 //     against a dirty bit of the same leaf (it is the latest element of its group); the K values
-//     are summed pairwise.  The dirty bits are cleared at the end.
+//     are summed pairwise.  Entries, dirty bits and used stamps are cleared at the end.
 //  2. Heights 2 .. hb of the subtree are recomputed from LDS and stored.
 //  3. Above hb every node counts the arrivals of its children's workgroups; the last one to
 //     arrive recomputes it and carries on upwards, so the root is written by whichever
@@ -34,6 +33,10 @@ struct SubLevels {
 //     few nodes at height hb this step is skipped (chain == 0): the agent-scope fences it
 //     needs cost more than recomputing those heights in the next kernel that reads them.
 constexpr uint32_t kDirtyListCap = 2048;
+// Largest hb that tree_pass_height can give a fanout: the whole tree when it has at most kDirtyListCap
+// height-1 nodes (H <= 1 + ceil(log_K 2048)), else the lowest height whose subtrees hold 64 of them.
+template <int LOGK>
+constexpr int kMaxPassHeight = LOGK == 1 ? 13 : LOGK == 2 ? 7 : LOGK == 3 ? 5 : LOGK <= 5 ? 4 : 3;
 constexpr uint32_t kLazyTopNodes = 4096;
 
 // The work of workgroup b of tree t (b = its subtree's root at height hb).  TRACK_MIN: also renew min1
@@ -69,7 +72,7 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   float* lvl1 = sl.ptr[0] + (size_t)t * sl.stride[0];
   uint32_t* dirty = g.dirty + (size_t)t * g.dirty_stride;
   float* leaves = g.level[0] + (size_t)t * g.stride[0];
-  const uint2* owner = reinterpret_cast<const uint2*>(g.owner) + (size_t)t * g.owner_stride;   // (value, stamp)
+  uint2* owner = reinterpret_cast<uint2*>(g.owner) + (size_t)t * g.owner_stride;   // (value, stamp)
   // the K dirty bits of one height-1 node
   auto node_bits = [&](uint32_t node) -> unsigned long long {
     if constexpr (LOGK == 6) {
@@ -84,11 +87,10 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   };
   // the claim group entry of a height-1 node if this batch wrote it for a leaf of that node:
   // (value bits, 0x80000000 | leaf within the node), else y = 0
-  const uint2* groups = g.nclaim + (size_t)t * g.nclaim_stride;
-  const uint32_t floor = sl.stamp_floor;
+  uint2* groups = g.nclaim + (size_t)t * g.nclaim_stride;
   auto node_entry = [&](uint32_t node) -> uint2 {
     uint2 e = groups[LOGK >= 5 ? node : (node << LOGK) >> 5];
-    bool mine = (e.y >> 6) >= floor;
+    bool mine = e.y != 0;
     if constexpr (LOGK < 5) mine = mine && ((e.y & 31u) >> LOGK) == (node & ((32u >> LOGK) - 1u));
     e.y = mine ? 0x80000000u | (e.y & (uint32_t)(K - 1)) : 0u;
     return e;
@@ -244,8 +246,10 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
     }
     PER_MARK(2);
     // ---- 2. heights 2 .. hb of this subtree, from LDS
+    // (unrolled over the slots, so that the per-height facts come out of the kernel arguments at fixed
+    // offsets; read through a table in LDS instead, they cost the pass 0.3 us)
 #pragma unroll
-    for (int j = 1; j < kSubSlots; ++j) {
+    for (int j = 1; j < kMaxPassHeight<LOGK>; ++j) {
       if ((uint32_t)j < hb) {
         __syncthreads();
         const uint32_t sh = (hb - 1 - (uint32_t)j) * LOGK;
@@ -267,17 +271,26 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
 
   PER_MARK(3);
   PER_FLUSH();
-  // The flags are cleared only now: a wait for loaded data also waits for every earlier store
-  // of the wave, so stores that nothing depends on go last.
+  // Everything the batch has set in the claim arrays is cleared again, so that they are all zero between
+  // batches: the group entry whose leaf lies under a listed node, the dirty bits, and the stamps of
+  // the dirty leaves.  Only now: a wait for loaded data also waits for every earlier store of the
+  // wave, so stores that nothing depends on go last.
   for (uint32_t i = threadIdx.x; i < nd; i += blockDim.x) {
     const uint32_t node = s_list[i];
-    if constexpr (LOGK == 6) {
-      if (s_bits[i] | s_bits_hi[i]) {
+    if (s_entry[i].y) groups[LOGK >= 5 ? node : (node << LOGK) >> 5] = make_uint2(0, 0);
+    unsigned long long bits = s_bits[i];
+    if constexpr (LOGK == 6) bits |= (unsigned long long)s_bits_hi[i] << 32;
+    if (bits) {
+      if constexpr (LOGK == 6) {
         dirty[2 * (size_t)node] = 0;
         dirty[2 * (size_t)node + 1] = 0;
+      } else {
+        dirty[(node << LOGK) >> 5] = 0;   // for K < 32 the word is shared with neighbours of the same subtree
       }
-    } else {
-      if (s_bits[i]) dirty[(node << LOGK) >> 5] = 0;   // for K < 32 the word is shared with neighbours of the same subtree
+      while (bits) {   // (few leaves: those that met another leaf of their group, or a batch claiming leaf by leaf)
+        owner[(size_t)node * K + (uint32_t)(__ffsll((long long)bits) - 1)] = make_uint2(0, 0);
+        bits &= bits - 1;
+      }
     }
   }
   // ---- 3. above the subtree: the last child to arrive recomputes the parent
@@ -306,11 +319,12 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   }
 }
 
-// Two 1024-lane workgroups share a compute unit only while a wave stays within an eighth of the
-// SIMD's scalar and vector registers; with one more scalar register than that the second workgroup
-// waits for the first to end and the kernel takes half as long again.
+// Workgroups of at most 512 lanes: two 1024-lane workgroups share a compute unit only while a wave
+// stays within an eighth of the SIMD's scalar and vector registers (with one scalar register more the
+// second workgroup waits for the first to end and the kernel takes half as long again), and holding
+// the compiler to that budget made it spill; 512 lanes run the pass just as fast.
 template <int LOGK, bool TRACK_MIN>
-__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8)))
+__global__ void __launch_bounds__(512)
 k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
   tree_job<LOGK, TRACK_MIN>(g, sl, blockIdx.y, blockIdx.x, chain);
 }
@@ -371,10 +385,10 @@ static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, const ClaimAr
   constexpr int K = Fan<LOGK>::K;
   const uint32_t B = c.B;
   const uint32_t hb = tree_pass_height(g);
-  if (hb > (uint32_t)kSubSlots) return hipErrorInvalidValue;   // cannot happen for fanouts and capacities accepted at create
+  if (hb > (uint32_t)kSubSlots || hb > (uint32_t)kMaxPassHeight<LOGK>)
+    return hipErrorInvalidValue;   // cannot happen for fanouts and capacities accepted at create
   SubLevels sl{};
   sl.hb = hb;
-  sl.stamp_floor = c.group_mode ? c.stamp_base & kGroupStampMask : kNoGroupStamp;
   uint32_t off = 0;
   for (uint32_t h = 1; h <= hb; ++h) {
     const uint32_t j = h - 1;
@@ -415,6 +429,7 @@ static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, const ClaimArgs
   uint32_t tblock;
   hipError_t e = tree_pass_shape<LOGK>(g, tn, c, &sl, &tblock);
   if (e != hipSuccess) return e;
+  if (tblock > 512) tblock = 512;
   const uint32_t chain = lazy_top_height(g, tn) ? 0u : 1u;
   if (c.track_min) {
     PER_LAUNCH(KID_UPDATE_TREE, (k_update_tree<LOGK, true>), dim3(g.n[sl.hb], g.T), dim3(tblock), tree_lds_bytes<LOGK>(sl),

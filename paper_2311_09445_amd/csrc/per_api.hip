@@ -1,5 +1,5 @@
 // C-ABI of the prioritized replay buffer: argument checks, arena layout and the host-side
-// mirrors (ring cursor, fill count, stamp counter).  All device work is in per_kernels.hip.
+// mirrors (ring cursor, fill count).  All device work is in per_kernels.hip.
 #include <math.h>
 #include <string.h>
 
@@ -19,9 +19,7 @@ struct per_buffer {
   uint8_t* col[kMaxFields];
   uint64_t col_stride[kMaxFields];
   uint64_t cursor, size;
-  uint64_t stamp_next;       // next unused last-writer stamp (stamps 1 .. 2^32-1)
-  bool groups_stale;         // the claim group entries are to be cleared before their next use
-  bool leaves_stale;         // and so are the per-leaf stamps (an arena copied back may hold stamps of another counter)
+  bool claims_left;          // a launch failed between a claim phase and its tree pass: the claim arrays are not all zero
   uint32_t weight_calls;     // number of per_sample calls that used the partial-minimum buffers
   int weight_norm;           // PER_NORM_BATCH or PER_NORM_BUFFER
   bool min_stale;            // min1 does not describe the leaves (it is rebuilt when next needed)
@@ -242,8 +240,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.group_claim = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
-  p->stamp_next = 1;
-  p->groups_stale = p->leaves_stale = false;
+  p->claims_left = false;
   p->weight_norm = PER_NORM_BATCH;
   p->min_stale = true;
   p->min_calls = 0;
@@ -317,42 +314,22 @@ int per_insert_protected(per_t* p, uint32_t n, const void* const* d_field_src, c
   return insert_impl(p, n, d_field_src, d_prio, d_out_idx, n_protect, d_protect_idx, stream);
 }
 
-// Takes the stamps of one update batch from the host counter and decides how the batch claims its leaves.
-// The group entries keep the low kGroupStampBits bits of a stamp, so no batch that could use them crosses
-// a multiple of 2^kGroupStampBits (a span): it moves to the start of the next span instead, and the
-// entries, whose stamps would otherwise look recent there, are cleared.  The leaf stamps are cleared when
-// the 32-bit stamps run out.  Stamp 0 (and low bits 0) is never handed out: it marks a cleared entry.
-static int reserve_stamps(per_t* p, uint32_t B, hipStream_t s, ClaimArgs* c) {
+// Decides how an update batch claims its leaves.  The claim arrays are all zero between batches (the
+// tree pass clears what its batch has set); should a launch have failed between a claim phase and its
+// tree pass, they are cleared here first.
+static int prepare_claim(per_t* p, uint32_t B, hipStream_t s, ClaimArgs* c) {
   const Geom& g = p->g;
-  const bool fits_span = B <= kGroupStampMask - 1;
-  uint64_t next = p->stamp_next;
-  bool clear_groups = p->groups_stale, clear_leaves = p->leaves_stale;
-  if (fits_span) {
-    if ((next & kGroupStampMask) == 0) ++next;
-    if ((next & kGroupStampMask) + B > kGroupStampMask) {
-      next = (next | kGroupStampMask) + 2;
-      clear_groups = true;
-    }
-  } else {
-    clear_groups = true;   // this batch runs through spans; the next one starts a fresh span (below)
+  if (p->claims_left) {
+    hipError_t e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(g.owner), 2ull * g.owner_stride * g.T, 0u, s);
+    if (e == hipSuccess)
+      e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(g.nclaim), 2ull * g.nclaim_stride * g.T, 0u, s);
+    if (e == hipSuccess) e = launch_fill_u32(p->tn, g.dirty, (uint64_t)g.dirty_stride * g.T, 0u, s);
+    if (e != hipSuccess) return PER_EHIP;
+    p->claims_left = false;
   }
-  if (next + B > 0xFFFFFFFFull) {
-    next = 1;
-    clear_groups = clear_leaves = true;
-  }
-  hipError_t e = hipSuccess;
-  if (clear_leaves) e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(g.owner), 2ull * g.owner_stride * g.T, 0u, s);
-  if (e == hipSuccess && clear_groups)
-    e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(g.nclaim), 2ull * g.nclaim_stride * g.T, 0u, s);
-  if (e != hipSuccess) return PER_EHIP;
-  p->groups_stale = p->leaves_stale = false;
-  c->stamp_base = (uint32_t)next;
-  c->group_mode = fits_span && p->tn.group_claim ? 1u : 0u;
+  c->group_mode = B <= kGroupClaimMaxBatch && p->tn.group_claim ? 1u : 0u;
   c->track_min = tracks_min(p) ? 1u : 0u;   // (else min1 is, or now becomes, stale)
   if (!c->track_min) p->min_stale = true;
-  next += B;
-  if (!fits_span) next = ((next - 1) | kGroupStampMask) + 2;
-  p->stamp_next = next;
   return PER_OK;
 }
 
@@ -396,7 +373,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
     claim.size = (uint32_t)p->size;
     claim.idx = d_upd_idx;
     claim.prio = d_upd_prio;
-    int rc = reserve_stamps(p, upd_B, s, &claim);
+    int rc = prepare_claim(p, upd_B, s, &claim);
     if (rc != PER_OK) return rc;
     // The claim phase reads the update batch.  It may run inside the sampling kernel when that
     // kernel does not write what it reads: the batch is either the sampled batch itself (same
@@ -429,6 +406,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
                                &p->weight_calls, weight_mode, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr,
                                claim_mode, s);
   if (e == hipSuccess && upd_B) p->stale_hb = lazy_top_height(p->g, p->tn);   // the tree pass ran
+  if (e != hipSuccess && upd_B) p->claims_left = true;   // (the claim phase may have run without its tree pass)
   return hip_rc(e);
 }
 
@@ -472,10 +450,11 @@ int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio,
   claim.size = (uint32_t)p->size;
   claim.idx = d_idx;
   claim.prio = d_prio;
-  rc = reserve_stamps(p, B, s, &claim);
+  rc = prepare_claim(p, B, s, &claim);
   if (rc != PER_OK) return rc;
   hipError_t e = launch_update(p->g, p->tn, claim, s);
   if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
+  else p->claims_left = true;   // (the claim phase may have run without its tree pass)
   return hip_rc(e);
 }
 
@@ -493,10 +472,11 @@ int per_update_td(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_td
   claim.from_td = 1;
   claim.td_eps = eps;
   claim.td_alpha = alpha;
-  rc = reserve_stamps(p, B, s, &claim);
+  rc = prepare_claim(p, B, s, &claim);
   if (rc != PER_OK) return rc;
   hipError_t e = launch_update(p->g, p->tn, claim, s);
   if (e == hipSuccess) p->stale_hb = lazy_top_height(p->g, p->tn);
+  else p->claims_left = true;   // (the claim phase may have run without its tree pass)
   return hip_rc(e);
 }
 
@@ -660,7 +640,6 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size) {
   p->cursor = cursor;
   p->size = size;
   p->stale_hb = lazy_top_height(p->g, p->tn);   // a saved arena may predate the rebuild of its top heights
-  p->groups_stale = p->leaves_stale = true;     // and its last-writer stamps belong to the counter it was saved under
   p->min_stale = true;
   return PER_OK;
 }
@@ -694,12 +673,6 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "lds_budget_bytes")) {
     if (value < 0 || value > 160 * 1024) return PER_EINVAL;
     p->tn.lds_budget_bytes = (uint32_t)value;
-    return PER_OK;
-  }
-  if (!strcmp(name, "stamp_next")) {   // test hook: move the last-writer stamp counter (e.g. close to its wrap)
-    if (value < (int64_t)p->stamp_next || value > 0xFFFFFFFFll) return PER_EINVAL;
-    if ((uint64_t)value >> kGroupStampBits != p->stamp_next >> kGroupStampBits) p->groups_stale = true;
-    p->stamp_next = (uint64_t)value;
     return PER_OK;
   }
   if (!strcmp(name, "sample_min_lds")) {

@@ -27,9 +27,9 @@ struct Geom {
   float*   level[kMaxHeight + 1];   // level h of tree 0
   float*   root;                    // == level[H]; at a fixed offset so kernels need no dependent load
   uint32_t root_stride;             // == stride[H]
-  uint64_t* owner;                  // [T][owner_stride] last-writer stamps: (stamp << 32) | fp32 bits of the value
+  uint64_t* owner;                  // [T][owner_stride] last-writer stamps: (stamp << 32) | fp32 bits of the value; zero between batches
   uint32_t owner_stride;
-  uint2*   nclaim;                  // [T][nclaim_stride] group entries of the claim phase: (value bits, stamp << 6 | slot)
+  uint2*   nclaim;                  // [T][nclaim_stride] group entries of the claim phase: (value bits, stamp << 6 | slot); zero between batches
   uint32_t nclaim_stride;
   uint32_t* dirty;                  // [T][dirty_stride] words of one bit per leaf: the leaf was claimed by the current update
   uint32_t dirty_stride;
@@ -62,15 +62,12 @@ struct FieldTable {
   uint32_t n_fields;
 };
 
-// Stamps of the claim phase.  A batch takes consecutive 32-bit stamps; the group entries keep the low
-// kGroupStampBits bits only, so a batch that uses them never crosses a multiple of 2^kGroupStampBits.
-constexpr uint32_t kGroupStampBits = 26;
-constexpr uint32_t kGroupStampMask = (1u << kGroupStampBits) - 1u;
-constexpr uint32_t kNoGroupStamp = 0xFFFFFFFFu;   // floor above every group stamp: no group entry counts
+// Largest batch that can claim through the group entries: their stamp (position in the batch + 1) has 26 bits.
+constexpr uint32_t kGroupClaimMaxBatch = (1u << 26) - 2u;
 
 // Claim phase of a priority update (first half of per_update).
 struct ClaimArgs {
-  uint32_t B, size, stamp_base;
+  uint32_t B, size;
   uint32_t group_mode;     // the batch claims through the group entries (else leaf by leaf)
   uint32_t track_min;      // the tree pass also renews min1 of the height-1 nodes it rebuilds
   const uint32_t* idx;     // [T][B]
@@ -168,7 +165,7 @@ struct Tuning {
   uint32_t lazy_top;   // updates may leave the few topmost heights to their next reader
   uint32_t insert_small;      // small inserts run as one kernel (one workgroup per tree)
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
-  uint32_t group_claim;       // update batches claim through the group entries whenever their stamps fit one span
+  uint32_t group_claim;       // update batches claim through the group entries whenever they are short enough
   Profiler* prof;
 };
 

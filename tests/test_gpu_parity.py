@@ -116,43 +116,9 @@ def test_last_writer_adversarial(K):
     m.compare_status()
 
 
-def test_last_writer_stamps_wrap_around():
-    """The 32-bit stamp counter is pushed to just below its end: the next updates must clear the stamp
-    array, start over, and still pick the last writer."""
-    rng = np.random.default_rng(5)
-    N, T, B = 20000, 2, 3000
-    m = Mirror(16, N, T, ())
-    m.insert(N, prio=rng.random((T, N)).astype(np.float32), with_rows=False)
-    m.update(rng.integers(0, 200, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
-    m.gpu.set_tuning("stamp_next", 0xFFFFFFFF - 2 * B - 5)
-    for it in range(4):        # the third call no longer fits below 2^32
-        m.update(rng.integers(0, 200, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
-        m.compare_tree()
-    m.compare_status()
-
-
-def test_group_stamps_cross_their_span():
-    """The group entries keep 26 bits of a stamp: a batch that would cross a multiple of 2^26 moves to the next
-    span and the entries are cleared; entries left by earlier batches must never count for a later one."""
-    rng = np.random.default_rng(11)
-    N, T, B = 20000, 2, 3000
-    for K in (4, 32, 64):
-        m = Mirror(K, N, T, ())
-        m.insert(N, prio=rng.random((T, N)).astype(np.float32), with_rows=False)
-        m.gpu.set_tuning("stamp_next", (1 << 26) - 2 * B - 5)
-        for it in range(5):        # the third call no longer fits below 2^26
-            idx = rng.integers(0, 200 if it % 2 else N, (T, B)).astype(np.uint32)
-            m.update(idx, rng.random((T, B)).astype(np.float32))
-            m.compare_tree()
-        m.gpu.set_tuning("stamp_next", 3 << 26)   # low bits zero: not a stamp
-        m.update(rng.integers(0, 200, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
-        m.compare_tree()
-        m.compare_status()
-
-
-def test_update_batch_longer_than_a_group_stamp_span(claim_form):
-    """A batch of 2^26 + 3 elements cannot use the group entries (they keep 26 stamp bits): it claims leaf by
-    leaf, and the batches after it start a fresh span with the entries cleared."""
+def test_update_batch_too_long_for_the_group_entries(claim_form):
+    """A batch of 2^26 + 3 elements cannot use the group entries (their stamp, the position in the batch, has 26
+    bits): it claims leaf by leaf, between batches that use the entries."""
     if claim_form != "group":
         pytest.skip("the same path as the other form")
     rng = np.random.default_rng(26)
