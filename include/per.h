@@ -293,6 +293,12 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
 int per_set_weight_norm(per_t* p, int mode);
 int per_min_priority(per_t* p, float* d_out, void* stream);
 
+/* To be called after a captured graph holding calls on this buffer has been replayed and before the next
+ * call made outside the graph: a replay changes the device without passing through the library, so
+ * what the host has noted about the device (are the topmost heights current, is the companion minimum
+ * current) is set to "no", and the next call rebuilds what it needs. */
+int per_note_replay(per_t* p);
+
 /* Uniforms drawn on the device ("uniformly generated random", Section II-A), for sampling calls that
  * pass d_u == NULL.  The generator is counter-based (Philox4x32-10), so the uniforms are a pure
  * function of (seed, number of the sampling call, tree, sample): sample i of tree t in call number c
@@ -307,11 +313,13 @@ uint64_t per_rng_calls(const per_t* p);
  *   "sample_block", "update_block", "gather_block" : workgroup sizes (multiples of 64, <= 1024)
  *   "tree_block" : workgroup size of the update's tree pass (multiple of 64, <= 1024; 0 = chosen per launch)
  *   "sample_min_lds" : lower bound in bytes of the sampling kernel's LDS request
+ *   "group_stamp_next" : moves the device-side stamp counter of the claim group entries (1 .. 2^25; enqueued on
+ *                  the default stream), e.g. close to the point where the entries are cleared and it starts over
  *   "group_claim" : how per_update and the fused step find the last writer of a leaf.  0: every element
  *                  raises the 64-bit stamp of its leaf; 1 (default): every element raises the entry shared
  *                  by a group of 32 leaves (64 for K = 64), an array small enough to stay in cache, and
  *                  goes to its leaf's own stamp only when two leaves of one group meet in a batch
- *                  (batches of 2^26 - 2 elements and more always use form 0)
+ *                  (batches of more than 2^25 elements always use form 0)
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
  *                  the next call that reads them; 0 makes per_update finish them itself
  *   "insert_small" : 1 (default) runs an insert of few rows as a single kernel, one workgroup per tree

@@ -162,11 +162,14 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
   return x;
 }
 
-// Smallest positive leaf of tree t as left by k_min_reduce in the entry named by the weight mode:
-// the kMinSlots partial minima, one per lane, folded by a wave reduction.  Called by whole waves.
+// Smallest positive leaf of tree t from the partial minima k_min_reduce has left (their number is part
+// of the weight mode), folded by every calling wave for itself.  Called by whole waves.
 __device__ __forceinline__ uint32_t buffer_min_bits(const Geom& g, uint32_t t, uint32_t mode) {
-  const uint32_t parity = (mode >> kWeightBufferParityShift) & 1u;
-  return wave_min_u32(g.vmin_buf[((size_t)parity * g.T + t) * kMinSlots + (threadIdx.x & 63u)]);
+  const uint32_t parts = mode >> kWeightPartsShift;
+  const uint32_t* part = g.vmin_buf + (size_t)t * kMinParts;
+  uint32_t m = kNoMin;
+  for (uint32_t i = threadIdx.x & 63u; i < parts; i += 64) m = min_u32(m, part[i]);
+  return wave_min_u32(m);
 }
 
 // Running maximum priority: mx = fp32 bits of this lane's valid positive value (0: none).  One

@@ -10,8 +10,8 @@
 // of its reduction, so the companion structure need not mirror the sum tree: min1 holds the
 // minimum under every height-1 node, kept current by the kernels that rewrite leaves of few nodes (the
 // update's tree pass, small inserts); everything else marks it stale on the host and k_min_rebuild
-// recomputes it from the leaves when it is next needed.  k_min_reduce folds min1 into one value per
-// tree before a sampling call that wants it.
+// recomputes it from the leaves when it is next needed.  k_min_reduce folds min1 into a few partial
+// minima per tree before a sampling call that wants it.
 
 // min1 of every height-1 node from its K leaves; LPS lanes per node.
 template <int LOGK>
@@ -31,11 +31,10 @@ k_min_rebuild(Geom g) {
   }
 }
 
-// vmin_buf[parity][t][slot] = partial minima of min1 of tree t (workgroup b folds into slot b mod
-// kMinSlots: atomics on one address would queue up); the entry of the other parity is re-armed
-// for the next call.  The entry of this parity was re-armed by the call before (or at creation).
+// vmin_buf[t][b] = minimum of the part of min1 of tree t that workgroup b has swept.  Plain stores, one
+// per workgroup, so nothing has to be armed beforehand; the readers fold the gridDim.x partial minima.
 __global__ void __launch_bounds__(256)
-k_min_reduce(Geom g, uint32_t parity) {
+k_min_reduce(Geom g) {
   __shared__ uint32_t s_m[4];
   const uint32_t t = blockIdx.y;
   const uint32_t* min1 = g.min1 + (size_t)t * g.min1_stride;
@@ -54,13 +53,8 @@ k_min_reduce(Geom g, uint32_t parity) {
   m = wave_min_u32(m);
   if ((threadIdx.x & 63u) == 0) s_m[threadIdx.x >> 6] = m;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    m = min_u32(min_u32(s_m[0], s_m[1]), min_u32(s_m[2], s_m[3]));
-    uint32_t* out = g.vmin_buf + ((size_t)parity * g.T + t) * kMinSlots + blockIdx.x % kMinSlots;
-    if (m < *reinterpret_cast<volatile uint32_t*>(out)) atomicMin(out, m);   // (a stale read only costs a redundant atomic)
-  }
-  if (blockIdx.x == 0 && threadIdx.x < kMinSlots)
-    g.vmin_buf[((size_t)(parity ^ 1u) * g.T + t) * kMinSlots + threadIdx.x] = kNoMin;
+  if (threadIdx.x == 0)
+    g.vmin_buf[(size_t)t * kMinParts + blockIdx.x] = min_u32(min_u32(s_m[0], s_m[1]), min_u32(s_m[2], s_m[3]));
 }
 
 template <int LOGK>
@@ -78,9 +72,10 @@ hipError_t launch_min_rebuild(const Geom& g, const Tuning& tn, hipStream_t s) {
 #undef CALL
 }
 
-hipError_t launch_min_reduce(const Geom& g, const Tuning& tn, uint32_t parity, hipStream_t s) {
+hipError_t launch_min_reduce(const Geom& g, const Tuning& tn, uint32_t* weight_mode, hipStream_t s) {
   uint64_t blocks = ((uint64_t)g.n[1] + 1023) / 1024;   // four entries per lane
-  if (blocks > 4096) blocks = 4096;
-  PER_LAUNCH(KID_MIN_REDUCE, k_min_reduce, dim3((unsigned)blocks, g.T), dim3(256), 0, s, g, parity);
+  if (blocks > kMinParts) blocks = kMinParts;
+  PER_LAUNCH(KID_MIN_REDUCE, k_min_reduce, dim3((unsigned)blocks, g.T), dim3(256), 0, s, g);
+  *weight_mode = kWeightBufferNorm | ((uint32_t)blocks << kWeightPartsShift);
   return hipGetLastError();
 }

@@ -156,7 +156,7 @@ __global__ void k_finish(FieldTable ft, JobRanges jr, Geom g, FinishArgs a) {
   const uint32_t t = blockIdx.y;
   const uint32_t b = blockIdx.x;
   if (b < jr.first[1]) {
-    weights_job(g, t, a.B, a.size, a.beta, a.w, a.parity, b, jr.first[1]);
+    weights_job(g, t, a.B, a.size, a.beta, a.w, a.weight_mode, b, jr.first[1]);
     return;
   }
   if (b < jr.first[2]) {

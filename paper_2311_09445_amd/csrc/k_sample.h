@@ -78,7 +78,7 @@ template <int LOGK>
 __global__ void __launch_bounds__(1024)
 k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float* __restrict__ u,
          uint32_t* __restrict__ out_idx, float* __restrict__ out_prio, float* __restrict__ out_w,
-         uint32_t parity, int stale, uint32_t claim_blocks, ClaimArgs c, int claim_mode, RngArgs rng) {
+         uint32_t weight_mode, int stale, uint32_t claim_blocks, ClaimArgs c, int claim_mode, RngArgs rng) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   constexpr int ROW = K + 4;                  // staging row, floats
@@ -108,12 +108,21 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   // the root, this lane's uniform and the top copy are all fetched in the same trip
   float total = tc.root[(size_t)t * tc.root_stride];
   const float u_s = rng.on ? counter_uniform(rng, s, t) : u[o];
-  // the new priority of this lane's sample and the running maximum, fetched in that same trip
+  // which buffer of partial batch minima this call fills (stable while this kernel runs: the weights job of
+  // the call before has written it), fetched in that same trip
+  uint32_t vbuf = 0;
+  if (out_w && sample_blocks > 1) {
+    vbuf = g.vnext[t] & 1u;
+    if (bx == 0 && threadIdx.x == 0) g.vcur[t] = vbuf;   // for the weights job of this call (also when nothing can be sampled)
+  }
+  // the new priority of this lane's sample and the running maximum, likewise
   float upd_v = 0.0f;
   uint32_t max_seen = 0;
+  uint32_t claim_first = 1;
   if (claim_mode == 1) {
     upd_v = c.prio[o];
     max_seen = read_max_bits(g, t);
+    claim_first = claim_base(g, t, c.group_mode, bx == 0 && threadIdx.x == 0);
   }
 
   uint32_t off[kTopSlots + 1];
@@ -242,40 +251,49 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
       __syncthreads();
       uint32_t mm = 0x7F800000u;
       for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_min[wv] < mm ? s_min[wv] : mm;
-      if (parity & kWeightBufferNorm) mm = buffer_min_bits(g, t, parity);   // (uniform over the launch)
+      if (weight_mode & kWeightBufferNorm) mm = buffer_min_bits(g, t, weight_mode);   // (uniform over the launch)
       if (active) out_w[o] = importance_weight(val, __uint_as_float(mm), beta);
     } else {                // partial minima, spread over kVminSlots addresses; the weights job finishes
       if (active) out_w[o] = val;
       if (lane == 0)
-        atomicMin(&g.vmin[((size_t)(parity & 1u) * g.T + t) * kVminSlots + ((bx * (blockDim.x >> 6) + wave) % kVminSlots)], m);
+        atomicMin(&g.vmin[((size_t)vbuf * g.T + t) * kVminSlots + ((bx * (blockDim.x >> 6) + wave) % kVminSlots)], m);
     }
   }
   if (claim_mode == 1) {   // element s of the update batch is this lane's own sample
     uint32_t mx = 0, flags = 0;
-    if (active) claim_element(g, t, size, c.group_mode, s, node, upd_v, mx, flags);
+    if (active) claim_element(g, t, size, c.group_mode, claim_first, s, node, upd_v, mx, flags);
     raise_max(g, t, mx, max_seen);
     if (flags) atomicOr(&g.status[t], flags);
   }
 }
 
-// Finishes the importance weights of tree t: folds the partial minima of this call, re-arms
-// the other buffer for the next call, and turns the sampled values left in w into weights.
-// Called by whole workgroups of any size; `first` marks the one that re-arms.
-// `mode`: see kWeightBufferNorm.
+// Finishes the importance weights of tree t: folds the partial minima that the sampling kernel of this
+// call has left in one of the two vmin buffers and turns the sampled values left in w into weights.
+// Called by whole workgroups of any size.  Which buffer: vcur, written by that sampling kernel.  The
+// first workgroup re-arms the other buffer and makes it the one the next sampling kernel fills (vnext;
+// only kernels of later calls read that word).  Nothing of this alternation lives on the host, so a
+// captured call can be replayed.  `mode`: see kWeightBufferNorm.
 __device__ __forceinline__ void weights_job(const Geom& g, uint32_t t, uint32_t B, uint32_t size, float beta,
                                             float* __restrict__ w, uint32_t mode, uint32_t job_block,
                                             uint32_t job_blocks) {
   __shared__ uint32_t s_wmin[16];
-  const uint32_t parity = mode & 1u;
   if (job_block != 0 && job_block * blockDim.x >= B) return;   // nothing to do for this workgroup
-  const uint32_t* part = g.vmin + ((size_t)parity * g.T + t) * kVminSlots;
-  uint32_t m = 0x7F800000u;
-  for (uint32_t j = threadIdx.x; j < kVminSlots; j += blockDim.x) m = part[j] < m ? part[j] : m;
-  m = wave_min_u32(m);
+  // (both buffers are fetched beside the word that says which one counts: one trip instead of two)
+  const uint32_t* part0 = g.vmin + (size_t)t * kVminSlots;
+  const uint32_t* part1 = g.vmin + ((size_t)g.T + t) * kVminSlots;
+  uint32_t m0 = 0x7F800000u, m1 = 0x7F800000u;
+  for (uint32_t j = threadIdx.x; j < kVminSlots; j += blockDim.x) {
+    m0 = part0[j] < m0 ? part0[j] : m0;
+    m1 = part1[j] < m1 ? part1[j] : m1;
+  }
+  const uint32_t vbuf = g.vcur[t] & 1u;
+  uint32_t m = wave_min_u32(vbuf ? m1 : m0);
   if ((threadIdx.x & 63u) == 0) s_wmin[threadIdx.x >> 6] = m;
-  if (job_block == 0)
+  if (job_block == 0) {
     for (uint32_t j = threadIdx.x; j < kVminSlots; j += blockDim.x)
-      g.vmin[((size_t)(parity ^ 1u) * g.T + t) * kVminSlots + j] = 0x7F800000u;
+      g.vmin[((size_t)(vbuf ^ 1u) * g.T + t) * kVminSlots + j] = 0x7F800000u;
+    if (threadIdx.x == 0) g.vnext[t] = vbuf ^ 1u;
+  }
   __syncthreads();
   uint32_t mm = 0x7F800000u;
   for (uint32_t wv = 0; wv < (blockDim.x >> 6); ++wv) mm = s_wmin[wv] < mm ? s_wmin[wv] : mm;
@@ -289,8 +307,8 @@ __device__ __forceinline__ void weights_job(const Geom& g, uint32_t t, uint32_t 
   }
 }
 
-__global__ void k_weights(Geom g, uint32_t B, uint32_t size, float beta, float* __restrict__ w, uint32_t parity) {
-  weights_job(g, blockIdx.y, B, size, beta, w, parity, blockIdx.x, gridDim.x);
+__global__ void k_weights(Geom g, uint32_t B, uint32_t size, float beta, float* __restrict__ w, uint32_t mode) {
+  weights_job(g, blockIdx.y, B, size, beta, w, mode, blockIdx.x, gridDim.x);
 }
 
 template <int LOGK>
@@ -310,8 +328,8 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const Cl
 template <int LOGK>
 static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
                                   const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w,
-                                  float* out_prio, uint32_t* weight_calls, uint32_t weight_mode, uint32_t stale_hb,
-                                  const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s) {
+                                  float* out_prio, uint32_t weight_mode, uint32_t stale_hb, const FieldTable* rows,
+                                  const ClaimArgs* claim, int claim_mode, hipStream_t s) {
   constexpr int K = Fan<LOGK>::K;
   constexpr uint32_t kLdsCap = 128 * 1024;
   const uint32_t wave_bytes = LOGK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
@@ -347,10 +365,6 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   tc.root_stride = g.root_stride;
   size_t bytes = (size_t)top + (size_t)waves * wave_bytes;
   if (bytes < tn.sample_min_lds) bytes = tn.sample_min_lds;   // asking for more LDS than needed spreads workgroups over more CUs
-  // The two buffers of partial minima alternate between the calls that use them (k_weights of
-  // one call re-arms the buffer of the next).
-  const uint32_t parity = (*weight_calls & 1u) | weight_mode;   // (weight_mode: the bits above bit 0)
-  if (out_w && gx > 1) ++*weight_calls;
   hipError_t e;
   int stale = -1;
   if (stale_hb) {
@@ -376,7 +390,7 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
     if (claim_blocks > 4096) claim_blocks = 4096;   // the claim job strides
   }
   PER_LAUNCH(KID_SAMPLE, k_sample<LOGK>, dim3(gx + claim_blocks, g.T), dim3(block), bytes, s, g, tc, B, size, beta, u,
-             out_idx, out_prio, out_w, parity, stale, claim_blocks, claim_here ? *claim : ClaimArgs{},
+             out_idx, out_prio, out_w, weight_mode, stale, claim_blocks, claim_here ? *claim : ClaimArgs{},
              claim_here ? claim_mode : (int)CLAIM_NONE, rng);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -388,7 +402,7 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
     a.w = finish_weights ? out_w : nullptr;
     a.size = size;
     a.beta = beta;
-    a.parity = parity;
+    a.weight_mode = weight_mode;
     if (claim_here) {   // second kernel: tree pass beside the weights and the rows
       if (rows || finish_weights) return launch_tree_finish_k<LOGK>(g, tn, *claim, rows, a, s);
       return launch_tree_k<LOGK>(g, tn, *claim, s);
@@ -401,7 +415,7 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
     return launch_tree_k<LOGK>(g, tn, *claim, s);
   }
   if (!finish_weights) return e;
-  PER_LAUNCH(KID_WEIGHTS, k_weights, dim3((B + 255) / 256, g.T), dim3(256), 0, s, g, B, size, beta, out_w, parity);
+  PER_LAUNCH(KID_WEIGHTS, k_weights, dim3((B + 255) / 256, g.T), dim3(256), 0, s, g, B, size, beta, out_w, weight_mode);
   return hipGetLastError();
 }
 
@@ -417,10 +431,10 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   }
 
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
-                         const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls,
-                         uint32_t weight_mode, uint32_t stale_hb, const FieldTable* rows, const ClaimArgs* claim,
-                         int claim_mode, hipStream_t s) {
-#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, rng, out_idx, out_w, out_prio, weight_calls, weight_mode, stale_hb, rows, claim, claim_mode, s)
+                         const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio, uint32_t weight_mode,
+                         uint32_t stale_hb, const FieldTable* rows, const ClaimArgs* claim, int claim_mode,
+                         hipStream_t s) {
+#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, rng, out_idx, out_w, out_prio, weight_mode, stale_hb, rows, claim, claim_mode, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

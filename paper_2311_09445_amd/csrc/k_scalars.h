@@ -28,8 +28,11 @@ __global__ void k_init_scalars(Geom g, float init_max) {
   if (t >= g.T) return;
   g.max_v[t] = init_max;
   g.status[t] = 0;
-  for (uint32_t k = 0; k < 2 * kVminSlots; ++k) g.vmin[(size_t)k * g.T + t] = kNoMin;
-  for (uint32_t k = 0; k < 2 * kMinSlots; ++k) g.vmin_buf[(size_t)(k / kMinSlots) * g.T * kMinSlots + (size_t)t * kMinSlots + k % kMinSlots] = kNoMin;
+  for (uint32_t k = 0; k < 2 * kVminSlots; ++k) g.vmin[((size_t)(k / kVminSlots) * g.T + t) * kVminSlots + k % kVminSlots] = kNoMin;
+  g.vnext[t] = 0;
+  g.vcur[t] = 0;
+  g.sbase[t] = 1;
+  g.sfloor[t] = 1;
 }
 
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s) {
@@ -37,15 +40,15 @@ hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s) {
   return hipGetLastError();
 }
 
-// which: 0 = root of every tree, 1 = running max priority, 2 / 3 = smallest positive leaf as reduced into
-// entry 0 / 1 of vmin_buf
-__global__ void k_read_scalars(Geom g, int which, float* out) {
+// which: 0 = root of every tree, 1 = running max priority, 2 = smallest positive leaf from the partial
+// minima of k_min_reduce (weight_mode tells how many there are)
+__global__ void k_read_scalars(Geom g, int which, uint32_t weight_mode, float* out) {
   const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= g.T) return;
-  if (which >= 2) {
+  if (which == 2) {
     uint32_t m = kNoMin;
-    for (uint32_t k = 0; k < kMinSlots; ++k) {
-      const uint32_t v = g.vmin_buf[((size_t)(which - 2) * g.T + t) * kMinSlots + k];
+    for (uint32_t k = 0; k < (weight_mode >> kWeightPartsShift); ++k) {
+      const uint32_t v = g.vmin_buf[(size_t)t * kMinParts + k];
       m = v < m ? v : m;
     }
     out[t] = __uint_as_float(m);
@@ -54,8 +57,8 @@ __global__ void k_read_scalars(Geom g, int which, float* out) {
   out[t] = which == 0 ? g.root[(size_t)t * g.root_stride] : g.max_v[t];
 }
 
-hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s) {
-  k_read_scalars<<<dim3((g.T + 63) / 64), dim3(64), 0, s>>>(g, which, out);
+hipError_t launch_read_scalars(const Geom& g, int which, uint32_t weight_mode, float* out, hipStream_t s) {
+  k_read_scalars<<<dim3((g.T + 63) / 64), dim3(64), 0, s>>>(g, which, weight_mode, out);
   return hipGetLastError();
 }
 

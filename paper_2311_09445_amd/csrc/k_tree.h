@@ -14,6 +14,7 @@ struct SubLevels {
   uint32_t lds_floats;            // total
   uint32_t list_cap;              // height-1 nodes under one workgroup root: entries of the workgroup's node list
   uint32_t hb;
+  uint32_t group_batch;           // size of the batch if it claimed through the group entries, else 0
 };
 
 // Tree pass.  Workgroup b of tree t owns the subtree under node b of height hb and keeps the
@@ -25,7 +26,7 @@ struct SubLevels {
 //     the stamp entry, whose lower word is the value of the batch element that won that leaf; it
 //     replaces the leaf (and is stored), and so does the value of the group entry, which wins
 //     against a dirty bit of the same leaf (it is the latest element of its group); the K values
-//     are summed pairwise.  Entries, dirty bits and used stamps are cleared at the end.
+//     are summed pairwise.  Dirty bits and used leaf stamps are cleared at the end.
 //  2. Heights 2 .. hb of the subtree are recomputed from LDS and stored.
 //  3. Above hb every node counts the arrivals of its children's workgroups; the last one to
 //     arrive recomputes it and carries on upwards, so the root is written by whichever
@@ -88,9 +89,11 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   // the claim group entry of a height-1 node if this batch wrote it for a leaf of that node:
   // (value bits, 0x80000000 | leaf within the node), else y = 0
   uint2* groups = g.nclaim + (size_t)t * g.nclaim_stride;
+  // first stamp of this batch, left by its claim phase (a batch that claimed leaf by leaf has no entries)
+  const uint32_t floor = sl.group_batch ? g.sfloor[t] : 0xFFFFFFFFu;
   auto node_entry = [&](uint32_t node) -> uint2 {
     uint2 e = groups[LOGK >= 5 ? node : (node << LOGK) >> 5];
-    bool mine = e.y != 0;
+    bool mine = (e.y >> 6) >= floor;
     if constexpr (LOGK < 5) mine = mine && ((e.y & 31u) >> LOGK) == (node & ((32u >> LOGK) - 1u));
     e.y = mine ? 0x80000000u | (e.y & (uint32_t)(K - 1)) : 0u;
     return e;
@@ -222,7 +225,10 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
     auto store = [&](const Item& it, float sum) {
       if (it.ok && it.my) *reinterpret_cast<LeafVec*>(leaves + it.at) = it.c;
       if (it.ok && q == 0) {
-        lvl1[it.node] = sum;
+        // (nontemporal: the scattered 4-byte stores then leave for memory while the pass goes on, instead
+        // of all being written back when the kernel ends; measured - 0.15 us per step.  The same for the
+        // upper heights, which the next kernel reads first, cost + 1.2 us.)
+        __builtin_nontemporal_store(sum, lvl1 + it.node);
         sub[it.node - lo1] = sum;
         if constexpr (TRACK_MIN) g.min1[(size_t)t * g.min1_stride + it.node] = it.mn;
       }
@@ -271,13 +277,11 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
 
   PER_MARK(3);
   PER_FLUSH();
-  // Everything the batch has set in the claim arrays is cleared again, so that they are all zero between
-  // batches: the group entry whose leaf lies under a listed node, the dirty bits, and the stamps of
-  // the dirty leaves.  Only now: a wait for loaded data also waits for every earlier store of the
-  // wave, so stores that nothing depends on go last.
+  // The dirty bits and the stamps of the dirty leaves are cleared again (both arrays are all zero between
+  // batches).  Only now: a wait for loaded data also waits for every earlier store of the wave, so
+  // stores that nothing depends on go last.
   for (uint32_t i = threadIdx.x; i < nd; i += blockDim.x) {
     const uint32_t node = s_list[i];
-    if (s_entry[i].y) groups[LOGK >= 5 ? node : (node << LOGK) >> 5] = make_uint2(0, 0);
     unsigned long long bits = s_bits[i];
     if constexpr (LOGK == 6) bits |= (unsigned long long)s_bits_hi[i] << 32;
     if (bits) {
@@ -292,6 +296,17 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
         bits &= bits - 1;
       }
     }
+  }
+  // The stamp counter of the group entries: the next batch starts after this one; when that is beyond the
+  // turning point, every workgroup clears the entries of its subtree instead and the counter starts over.
+  if (sl.group_batch) {
+    const bool turn = floor + sl.group_batch > kGroupStampTurn;   // (uniform over the launch)
+    if (turn) {
+      const uint32_t e_lo = LOGK >= 5 ? lo1 : (lo1 << LOGK) >> 5;
+      const uint32_t e_hi = LOGK >= 5 ? hi1 : (uint32_t)((((unsigned long long)hi1 << LOGK) + 31u) >> 5);
+      for (uint32_t e = e_lo + threadIdx.x; e < e_hi; e += blockDim.x) groups[e] = make_uint2(0, 0);
+    }
+    if (b == 0 && threadIdx.x == 0) g.sbase[t] = turn ? 1u : floor + sl.group_batch;
   }
   // ---- 3. above the subtree: the last child to arrive recomputes the parent
   if (!chain) return;   // the heights above hb are left to their next reader
@@ -344,7 +359,7 @@ k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldT
   }
   const uint32_t b = blockIdx.x - tree_blocks;
   if (b < jr.first[1]) {
-    weights_job(g, t, a.B, a.size, a.beta, a.w, a.parity, b, jr.first[1]);
+    weights_job(g, t, a.B, a.size, a.beta, a.w, a.weight_mode, b, jr.first[1]);
     return;
   }
 #pragma unroll
@@ -389,6 +404,7 @@ static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, const ClaimAr
     return hipErrorInvalidValue;   // cannot happen for fanouts and capacities accepted at create
   SubLevels sl{};
   sl.hb = hb;
+  sl.group_batch = c.group_mode ? c.B : 0u;
   uint32_t off = 0;
   for (uint32_t h = 1; h <= hb; ++h) {
     const uint32_t j = h - 1;

@@ -20,10 +20,8 @@ struct per_buffer {
   uint64_t col_stride[kMaxFields];
   uint64_t cursor, size;
   bool claims_left;          // a launch failed between a claim phase and its tree pass: the claim arrays are not all zero
-  uint32_t weight_calls;     // number of per_sample calls that used the partial-minimum buffers
   int weight_norm;           // PER_NORM_BATCH or PER_NORM_BUFFER
   bool min_stale;            // min1 does not describe the leaves (it is rebuilt when next needed)
-  uint32_t min_calls;        // number of reductions of min1 so far (their results alternate between two entries)
   uint32_t stale_hb;         // != 0: the last update left the heights above this one to their next reader
   bool rng_on;               // per_set_rng was called: sampling calls without uniforms draw their own
   uint64_t rng_seed, rng_calls;   // key of the generator; number of sampling calls that drew from it
@@ -76,8 +74,8 @@ void make_layout(const per_config* c, Layout* L) {
   } while (n > 1);
   L->H = h;
   size_t off = 0;
-  L->scalars_off = off;                         // max_v[T], status[T], vmin[2][T][kVminSlots], vmin_buf[2][T][kMinSlots]
-  off = round_up(off + (size_t)(2 + 2 * kVminSlots + 2 * kMinSlots) * T * 4, kAlign);
+  L->scalars_off = off;                         // max_v, status, vnext, vcur, sbase, sfloor [T] each; vmin[2][T][kVminSlots], vmin_buf[T][kMinParts]
+  off = round_up(off + (size_t)(6 + 2 * kVminSlots + kMinParts) * T * 4, kAlign);
   for (uint32_t l = 0; l <= L->H; ++l) {
     const uint64_t padded = ((uint64_t)L->n[l] + K - 1) / K * K;
     L->stride[l] = (uint32_t)round_up(padded, 64);
@@ -145,20 +143,14 @@ int hip_rc(hipError_t e) { return e == hipSuccess ? PER_OK : PER_EHIP; }
 bool tracks_min(const per_t* p) { return p->weight_norm == PER_NORM_BUFFER && !p->min_stale; }
 
 // Brings vmin_buf up to date for a reader: min1 from the leaves if it is stale, then its reduction.  Returns the
-// weight-mode bits naming the entry that holds the result.
-hipError_t reduce_min(per_t* p, hipStream_t s, uint32_t* mode_bits) {
-  hipError_t e = hipSuccess;
+// weight mode that tells the reader where the result is.
+hipError_t reduce_min(per_t* p, hipStream_t s, uint32_t* weight_mode) {
   if (p->min_stale) {
-    e = launch_min_rebuild(p->g, p->tn, s);
+    hipError_t e = launch_min_rebuild(p->g, p->tn, s);
     if (e != hipSuccess) return e;
     p->min_stale = false;
   }
-  const uint32_t parity = p->min_calls & 1u;
-  e = launch_min_reduce(p->g, p->tn, parity, s);
-  if (e != hipSuccess) return e;
-  ++p->min_calls;
-  *mode_bits = kWeightBufferNorm | (parity << kWeightBufferParityShift);
-  return hipSuccess;
+  return launch_min_reduce(p->g, p->tn, weight_mode, s);
 }
 
 // Rebuilds the heights an update left stale, for readers that take them from memory.
@@ -221,7 +213,11 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   for (uint32_t l = 0; l <= L.H; ++l) g.arrive_off[l] = L.arrive_level_off[l];
   g.max_v = reinterpret_cast<float*>(p->arena + L.scalars_off);
   g.status = reinterpret_cast<uint32_t*>(g.max_v + g.T);
-  g.vmin = g.status + g.T;
+  g.vnext = g.status + g.T;
+  g.vcur = g.vnext + g.T;
+  g.sbase = g.vcur + g.T;
+  g.sfloor = g.sbase + g.T;
+  g.vmin = g.sfloor + g.T;
   g.vmin_buf = g.vmin + (size_t)2 * kVminSlots * g.T;
   g.min1 = reinterpret_cast<uint32_t*>(p->arena + L.min1_off);
   g.min1_stride = L.min1_stride;
@@ -243,7 +239,6 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->claims_left = false;
   p->weight_norm = PER_NORM_BATCH;
   p->min_stale = true;
-  p->min_calls = 0;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -324,6 +319,7 @@ static int prepare_claim(per_t* p, uint32_t B, hipStream_t s, ClaimArgs* c) {
     if (e == hipSuccess)
       e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(g.nclaim), 2ull * g.nclaim_stride * g.T, 0u, s);
     if (e == hipSuccess) e = launch_fill_u32(p->tn, g.dirty, (uint64_t)g.dirty_stride * g.T, 0u, s);
+    if (e == hipSuccess) e = launch_fill_u32(p->tn, g.sbase, g.T, 1u, s);
     if (e != hipSuccess) return PER_EHIP;
     p->claims_left = false;
   }
@@ -403,7 +399,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
   const uint32_t stale = p->stale_hb;
   p->stale_hb = 0;   // the sampling kernel rebuilds and stores the stale heights
   hipError_t e = launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, rng, d_out_idx, d_out_weight, d_out_prio,
-                               &p->weight_calls, weight_mode, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr,
+                               weight_mode, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr,
                                claim_mode, s);
   if (e == hipSuccess && upd_B) p->stale_hb = lazy_top_height(p->g, p->tn);   // the tree pass ran
   if (e != hipSuccess && upd_B) p->claims_left = true;   // (the claim phase may have run without its tree pass)
@@ -603,12 +599,12 @@ int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint6
 int per_total(per_t* p, float* d_out, void* stream) {
   if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
   if (ensure_top(p, static_cast<hipStream_t>(stream)) != hipSuccess) return PER_EHIP;
-  return hip_rc(launch_read_scalars(p->g, 0, d_out, static_cast<hipStream_t>(stream)));
+  return hip_rc(launch_read_scalars(p->g, 0, 0, d_out, static_cast<hipStream_t>(stream)));
 }
 
 int per_max_priority(per_t* p, float* d_out, void* stream) {
   if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
-  return hip_rc(launch_read_scalars(p->g, 1, d_out, static_cast<hipStream_t>(stream)));
+  return hip_rc(launch_read_scalars(p->g, 1, 0, d_out, static_cast<hipStream_t>(stream)));
 }
 
 int per_status(per_t* p, void* stream, uint32_t* flags) {
@@ -655,7 +651,14 @@ int per_min_priority(per_t* p, float* d_out, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint32_t mode = 0;
   if (reduce_min(p, s, &mode) != hipSuccess) return PER_EHIP;
-  return hip_rc(launch_read_scalars(p->g, 2 + (int)((mode >> kWeightBufferParityShift) & 1u), d_out, s));
+  return hip_rc(launch_read_scalars(p->g, 2, mode, d_out, s));
+}
+
+int per_note_replay(per_t* p) {
+  if (!p) return PER_EINVAL;
+  p->stale_hb = lazy_top_height(p->g, p->tn);   // a replayed update has left the topmost heights to their next reader
+  p->min_stale = true;                          // and may not have renewed the companion minimum
+  return PER_OK;
 }
 
 int per_set_rng(per_t* p, uint64_t seed, uint64_t next_call) {
@@ -674,6 +677,10 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
     if (value < 0 || value > 160 * 1024) return PER_EINVAL;
     p->tn.lds_budget_bytes = (uint32_t)value;
     return PER_OK;
+  }
+  if (!strcmp(name, "group_stamp_next")) {   // test hook: move the device-side stamp counter of the group entries
+    if (value < 1 || value > (int64_t)kGroupStampTurn) return PER_EINVAL;
+    return hip_rc(launch_fill_u32(p->tn, p->g.sbase, p->g.T, (uint32_t)value, nullptr));
   }
   if (!strcmp(name, "sample_min_lds")) {
     if (value < 0 || value > 160 * 1024) return PER_EINVAL;

@@ -29,7 +29,9 @@ struct Geom {
   uint32_t root_stride;             // == stride[H]
   uint64_t* owner;                  // [T][owner_stride] last-writer stamps: (stamp << 32) | fp32 bits of the value; zero between batches
   uint32_t owner_stride;
-  uint2*   nclaim;                  // [T][nclaim_stride] group entries of the claim phase: (value bits, stamp << 6 | slot); zero between batches
+  uint2*   nclaim;                  // [T][nclaim_stride] group entries of the claim phase: (value bits, stamp << 6 | slot)
+  uint32_t* sbase;                  // [T] first stamp of the next batch that claims through the group entries (device-side counter)
+  uint32_t* sfloor;                 // [T] first stamp of the batch being processed (left by its claim phase for its tree pass)
   uint32_t nclaim_stride;
   uint32_t* dirty;                  // [T][dirty_stride] words of one bit per leaf: the leaf was claimed by the current update
   uint32_t dirty_stride;
@@ -38,20 +40,22 @@ struct Geom {
   uint32_t arrive_off[kMaxHeight + 1];   // offset of height h (>= 2) inside a tree's counters
   float*    max_v;                  // [T] running max priority
   uint32_t* status;                 // [T] sticky flags
-  uint32_t* vmin;                   // [2][T][kVminSlots] partial batch minima of sampled values (fp32 bits)
+  uint32_t* vmin;                   // [2][T][kVminSlots] partial batch minima of sampled values (fp32 bits), two buffers
+  uint32_t* vnext;                  // [T] which buffer the next sampling kernel fills (written by the weights job)
+  uint32_t* vcur;                   // [T] which buffer the current call uses (written by its sampling kernel for its weights job)
   uint32_t* min1;                   // [T][min1_stride] smallest positive leaf under each height-1 node (fp32 bits; kNoMin: none)
   uint32_t min1_stride;
-  uint32_t* vmin_buf;               // [2][T][kMinSlots] partial minima of min1 (fp32 bits), as reduced for a sampling call
+  uint32_t* vmin_buf;               // [T][kMinParts] partial minima of min1 (fp32 bits), one per workgroup of k_min_reduce
 };
-constexpr uint32_t kMinSlots = 64;       // one per lane of a wave: a reader folds them with one wave reduction
+constexpr uint32_t kMinParts = 1024;     // most workgroups k_min_reduce is launched with
 
 constexpr uint32_t kNoMin = 0x7F800000u;   // fp32 bits of +inf: above every valid priority
 
-// How a sampling call scales its importance weights, packed into one kernel argument:
-// bit 0: which of the two buffers of partial batch minima the call uses; bit 1: scale by the smallest
-// positive leaf of the whole tree instead of the batch's; bit 2: which vmin_buf entry holds it.
-constexpr uint32_t kWeightBufferNorm = 2u;
-constexpr uint32_t kWeightBufferParityShift = 2u;
+// How a sampling call scales its importance weights, packed into one kernel argument: 0 = by the batch's
+// smallest sampled value; else kWeightBufferNorm | (number of partial minima in vmin_buf << kWeightPartsShift) =
+// by the smallest positive leaf of the whole tree.
+constexpr uint32_t kWeightBufferNorm = 1u;
+constexpr uint32_t kWeightPartsShift = 8u;
 
 struct FieldTable {
   uint8_t* col[kMaxFields];         // column f of tree 0
@@ -62,8 +66,12 @@ struct FieldTable {
   uint32_t n_fields;
 };
 
-// Largest batch that can claim through the group entries: their stamp (position in the batch + 1) has 26 bits.
-constexpr uint32_t kGroupClaimMaxBatch = (1u << 26) - 2u;
+// Stamps of the group entries: 26 bits, taken from a counter in device memory that starts at 1 and
+// grows by the batch size; a batch starts at or below kGroupStampTurn and is no longer than that, so
+// its stamps fit; the tree pass of a batch that ends beyond it clears all entries and restarts the
+// counter (about every 500 steps of the headline workload).
+constexpr uint32_t kGroupStampTurn = 1u << 25;
+constexpr uint32_t kGroupClaimMaxBatch = kGroupStampTurn;
 
 // Claim phase of a priority update (first half of per_update).
 struct ClaimArgs {
@@ -98,7 +106,7 @@ struct FinishArgs {
   float* w;                // [T][B] sampled values in, weights out; nullptr: no weights job
   uint32_t size;
   float beta;
-  uint32_t parity;
+  uint32_t weight_mode;    // see kWeightBufferNorm
   uint32_t has_claim;
   ClaimArgs claim;
 };
@@ -173,11 +181,10 @@ struct Tuning {
 hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32_t value, hipStream_t s);
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
 hipError_t launch_min_rebuild(const Geom& g, const Tuning& tn, hipStream_t s);
-hipError_t launch_min_reduce(const Geom& g, const Tuning& tn, uint32_t parity, hipStream_t s);
+hipError_t launch_min_reduce(const Geom& g, const Tuning& tn, uint32_t* weight_mode, hipStream_t s);
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          const RngArgs& rng,
-                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t* weight_calls, uint32_t weight_mode,
-                         uint32_t stale_hb,
+                         uint32_t* out_idx, float* out_w, float* out_prio, uint32_t weight_mode, uint32_t stale_hb,
                          const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s);
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s);
@@ -199,7 +206,7 @@ uint32_t stream_tree_floats(const Geom& g, uint32_t* off);
 hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s);
 hipError_t launch_run_requests(const Geom& g, const Tuning& tn, const QueueArgs& a, hipStream_t s);
 hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);
-hipError_t launch_read_scalars(const Geom& g, int which, float* out, hipStream_t s);
+hipError_t launch_read_scalars(const Geom& g, int which, uint32_t weight_mode, float* out, hipStream_t s);
 hipError_t launch_clear_status(const Geom& g, hipStream_t s);
 
 }  // namespace per

@@ -22,7 +22,7 @@ EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_insert_protected", "per_sample", "per_sample_gather",
     "per_sample_gather_update", "per_gather",
     "per_update", "per_update_td", "per_update_delta", "per_set_rng", "per_rng_calls", "per_run_steps",
-    "per_run_steps_fits", "per_run_requests", "per_set_weight_norm", "per_min_priority", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
+    "per_run_steps_fits", "per_run_requests", "per_set_weight_norm", "per_min_priority", "per_note_replay", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
 ]
@@ -113,6 +113,7 @@ def _lib():
         "per_run_steps_fits": (C.c_int, [vp]),
         "per_run_requests": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_set_weight_norm": (C.c_int, [vp, C.c_int]),
+        "per_note_replay": (C.c_int, [vp]),
         "per_min_priority": (C.c_int, [vp, vp, vp]),
         "per_update_td": (C.c_int, [vp, u32, vp, vp, C.c_double, C.c_double, vp]),
         "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
@@ -393,6 +394,10 @@ class PrioritizedReplay:
         rc = self.lib.per_run_requests(self._h, n, C.cast(arr, C.c_void_p), C.c_void_p(d_queue.data_ptr()), self._stream())
         self._check(rc, "per_run_requests")
         return prepared
+
+    def note_replay(self):
+        """Call after replaying a captured graph of calls on this buffer, before the next call outside it."""
+        self._check(self.lib.per_note_replay(self._h), "per_note_replay")
 
     def set_weight_norm(self, mode: str):
         """'batch' (default): importance weights relative to the largest weight of the sampled batch;

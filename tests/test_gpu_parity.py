@@ -116,9 +116,28 @@ def test_last_writer_adversarial(K):
     m.compare_status()
 
 
+def test_group_stamp_counter_turns_over():
+    """The stamps of the group entries come from a counter in device memory; the tree pass of the batch that
+    takes it past 2^25 clears all entries and starts it over.  Entries of earlier batches must never count."""
+    rng = np.random.default_rng(11)
+    N, T, B = 20000, 2, 3000
+    for K in (4, 32, 64):
+        m = Mirror(K, N, T, ())
+        m.insert(N, prio=rng.random((T, N)).astype(np.float32), with_rows=False)
+        m.update(rng.integers(0, N, (T, B)).astype(np.uint32), rng.random((T, B)).astype(np.float32))
+        torch.cuda.synchronize()
+        m.gpu.set_tuning("group_stamp_next", (1 << 25) - 2 * B - 5)
+        torch.cuda.synchronize()
+        for it in range(5):        # the second call ends beyond the turning point
+            idx = rng.integers(0, 200 if it % 2 else N, (T, B)).astype(np.uint32)
+            m.update(idx, rng.random((T, B)).astype(np.float32))
+            m.compare_tree()
+        m.compare_status()
+
+
 def test_update_batch_too_long_for_the_group_entries(claim_form):
-    """A batch of 2^26 + 3 elements cannot use the group entries (their stamp, the position in the batch, has 26
-    bits): it claims leaf by leaf, between batches that use the entries."""
+    """A batch of 2^26 + 3 elements cannot use the group entries (at most 2^25 elements): it claims leaf by
+    leaf, between batches that use the entries."""
     if claim_form != "group":
         pytest.skip("the same path as the other form")
     rng = np.random.default_rng(26)
@@ -661,6 +680,87 @@ def test_run_steps_limits_and_empty_tree():
     q.run_steps(torch.zeros((2, 1, 8), device="cuda"), torch.zeros(2, device="cuda"), oi, ow)
     assert np.all(idx_to_host(oi) == 0xFFFFFFFF) and float(ow.abs().max()) == 0.0
     assert q.status() == FLAG_ZERO_TOTAL
+
+
+# ---------------------------------------------------------------------------------------------
+# a captured fused step can be replayed: nothing of a sampling + update call lives in host counters
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K,N,B", [(16, 50000, 4096), (32, 300000, 20000), (2, 4096, 64)])
+def test_captured_step_replays(K, N, B):
+    """One per_sample_gather_update call (uniforms given, weights, rows, update of the batch sampled before) is
+    captured into a HIP graph and replayed with fresh inputs in the same buffers; eager calls run between
+    the replays.  Every replay must give what the oracle gives for that step."""
+    log(f"graph replay K={K} N={N} B={B}")
+    rng = np.random.default_rng(K + B)
+    T, fb = 1, (32,)
+    m = Mirror(K, N, T, fb)
+    m.insert(N, prio=wl._draw_priorities("lognormal_0_1", rng, (T, N)), chunk=100000)
+    u_buf = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    upd_idx = torch.empty((T, B), dtype=torch.int32, device="cuda")
+    upd_prio = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    oi = torch.empty((T, B), dtype=torch.int32, device="cuda")
+    ow = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    ov = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    rows = [torch.empty((T, B, b), dtype=torch.uint8, device="cuda") for b in fb]
+
+    def call():
+        m.gpu.sample(u_buf, 0.5, out_idx=oi, out_weight=ow, out_prio=ov, rows_out=rows, update=(upd_idx, upd_prio))
+
+    def feed():
+        u = wl.uniform01(rng, (T, B))
+        idx = rng.integers(0, N, (T, B)).astype(np.uint32)
+        idx[:, 1::2] = idx[:, 0::2][:, :idx[:, 1::2].shape[1]]
+        pr = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B))
+        u_buf.copy_(dev(u)); upd_idx.copy_(idx_to_dev(idx)); upd_prio.copy_(dev(pr))
+        return u, idx, pr
+
+    def check(u, idx, pr, tree=True):
+        ci, cw, cv = m.cpu.sample(u, 0.5, True)
+        assert np.array_equal(idx_to_host(oi), ci), "sampled indices"
+        assert ov.cpu().numpy().tobytes() == cv.tobytes(), "sampled values"
+        np.testing.assert_allclose(ow.cpu().numpy(), cw, rtol=1e-6, atol=0)
+        for f, want in enumerate(m.cpu.gather(ci)):
+            assert np.array_equal(rows[f].cpu().numpy(), want)
+        m.cpu.update(idx, pr)
+        if tree:
+            m.compare_tree()
+
+    args = feed()
+    call()                                   # eager: leaves the buffer in the state every step starts from
+    check(*args)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    args = feed()
+    with torch.cuda.graph(graph):
+        call()                               # recorded, not run
+    for it in range(4):
+        if it:
+            args = feed()
+        graph.replay()
+        m.gpu.note_replay()
+        torch.cuda.synchronize()
+        check(*args)
+        if it == 1:                          # the program's own eager work between replays
+            m.update(rng.integers(0, N, (T, 100)).astype(np.uint32), rng.random((T, 100)).astype(np.float32))
+            m.compare_tree()
+    # the tight loop: captured right after a step, replayed back to back, the library not called in between
+    # (only the outputs are read, through torch)
+    args = feed()
+    call()
+    check(*args, tree=False)
+    loop = torch.cuda.CUDAGraph()
+    args = feed()
+    with torch.cuda.graph(loop):
+        call()
+    for it in range(4):
+        if it:
+            args = feed()
+        loop.replay()
+        torch.cuda.synchronize()
+        check(*args, tree=False)
+    m.gpu.note_replay()
+    m.compare_tree()
+    m.compare_status()
 
 
 # ---------------------------------------------------------------------------------------------
