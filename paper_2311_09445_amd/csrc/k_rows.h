@@ -4,49 +4,126 @@
 // ---------------------------------------------------------------------------------
 // Data Storage: row gather and row scatter
 // ---------------------------------------------------------------------------------
-// grid (x, n_fields, T).  A row of E bytes is moved by E/vec adjacent lanes, vec bytes each,
-// so the dense side is fully coalesced and the storage side is coalesced within a row.
+// A field of E bytes is moved by E/vec adjacent lanes, vec bytes each, so the dense side is fully
+// coalesced and the storage side is coalesced within a row.
+//
+// Elements a lane keeps in flight per sweep, about 32 bytes: narrow fields need more elements to cover
+// the same latency, and a launch over many trees must not need several rounds of workgroups.  Per
+// sweep all indices are fetched first, then all rows, then everything is stored (a wait for loaded
+// data also waits for earlier stores, so load -> store -> load would cost a memory trip per
+// element).  Elements beyond the end are clamped to the lane's first one, so that every load is
+// unconditional and the three phases stay straight-line code; only their stores are skipped.
+template <typename V>
+struct InFlight {
+  static constexpr int U = sizeof(V) >= 16 ? 2 : sizeof(V) == 8 ? 4 : 8;
+};
+static uint32_t max_in_flight(uint32_t vec) { return vec >= 16 ? 2u : vec == 8 ? 4u : 8u; }
+
+// A lane's values for the elements of a sweep: a nested struct reached through compile-time paths only
+// (an array written in unrolled loops was moved to LDS or scratch by the compiler).
+template <typename T, int N>
+struct Regs {
+  T head;
+  Regs<T, N - 1> tail;
+};
+template <typename T>
+struct Regs<T, 0> {};
+template <int K, typename T, int N>
+__device__ __forceinline__ T& reg(Regs<T, N>& r) {
+  if constexpr (K == 0) return r.head;
+  else return reg<K - 1>(r.tail);
+}
+
+struct RowMove {                 // what the elements of one field and tree have in common
+  uint8_t* col;                  // the field in row 0 of the tree
+  uint8_t* io;                   // the tree's dense rows: element e sits at byte e * sizeof(V)
+  const uint32_t* idx;           // the tree's indices (gather)
+  uint64_t total, stride;        // elements of the job; elements between two of a lane's
+  uint32_t RS, epr, cursor, N;
+};
+
+// Element K of the sweep that starts at e0 (clamped to e0 beyond the end, so that loads need no branch).
+template <int K>
+__device__ __forceinline__ uint64_t sweep_elem(const RowMove& m, uint64_t e0, bool& live) {
+  const uint64_t e = e0 + (uint64_t)K * m.stride;
+  live = e < m.total;
+  return live ? e : e0;
+}
+// The three phases of a sweep, each over elements K .. U-1: where the stored side of every element is
+// (for a gather that is a load of the index), the loads, the stores.
+template <typename V, bool GATHER, int K, int U>
+__device__ __forceinline__ void sweep_where(const RowMove& m, uint64_t e0, Regs<uint32_t, U>& at) {
+  if constexpr (K < U) {
+    bool live;
+    const uint32_t row = (uint32_t)(sweep_elem<K>(m, e0, live) / m.epr);
+    if constexpr (GATHER) {
+      reg<K>(at) = m.idx[row];
+    } else {
+      uint64_t slot = (uint64_t)m.cursor + row;
+      if (slot >= m.N) slot -= m.N;
+      reg<K>(at) = (uint32_t)slot;
+    }
+    sweep_where<V, GATHER, K + 1, U>(m, e0, at);
+  }
+}
+// (values narrower than a register are kept widened)
+template <typename V>
+using Held = typename std::conditional<sizeof(V) < 4, uint32_t, V>::type;
+template <typename V, bool GATHER, int K, int U>
+__device__ __forceinline__ void sweep_load(const RowMove& m, uint64_t e0, Regs<uint32_t, U>& at, Regs<Held<V>, U>& v,
+                                           bool& bad) {
+  if constexpr (K < U) {
+    bool live;
+    const uint64_t e = sweep_elem<K>(m, e0, live);
+    if constexpr (GATHER) {
+      const uint32_t within = (uint32_t)(e % m.epr);
+      const bool ok = reg<K>(at) < m.N;
+      bad |= !ok;
+      V got = *(reinterpret_cast<const V*>(m.col + (uint64_t)(ok ? reg<K>(at) : 0u) * m.RS) + within);
+      if (!ok) __builtin_memset(&got, 0, sizeof(V));
+      reg<K>(v) = (Held<V>)got;
+    } else {
+      reg<K>(v) = (Held<V>)*(reinterpret_cast<const V*>(m.io) + e);
+    }
+    sweep_load<V, GATHER, K + 1, U>(m, e0, at, v, bad);
+  }
+}
+template <typename V, bool GATHER, int K, int U>
+__device__ __forceinline__ void sweep_store(const RowMove& m, uint64_t e0, Regs<uint32_t, U>& at, Regs<Held<V>, U>& v) {
+  if constexpr (K < U) {
+    bool live;
+    const uint64_t e = sweep_elem<K>(m, e0, live);
+    if (live) {
+      if constexpr (GATHER) *(reinterpret_cast<V*>(m.io) + e) = (V)reg<K>(v);
+      else *(reinterpret_cast<V*>(m.col + (uint64_t)reg<K>(at) * m.RS) + (uint32_t)(e % m.epr)) = (V)reg<K>(v);
+    }
+    sweep_store<V, GATHER, K + 1, U>(m, e0, at, v);
+  }
+}
+
 template <typename V, bool GATHER>
 __device__ __forceinline__ void move_rows(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
                                           const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
                                           uint32_t* status, uint32_t job_block, uint32_t job_blocks) {
+  constexpr int U = InFlight<V>::U;
+  RowMove m;
   const uint32_t E = ft.bytes[f];
-  const uint32_t epr = E / (uint32_t)sizeof(V);
-  const uint64_t total = (uint64_t)B * epr;
-  uint8_t* col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
-  uint8_t* io = ft.io[f] + (uint64_t)t * B * E;
+  m.RS = ft.row_stride;
+  m.epr = E / (uint32_t)sizeof(V);
+  m.total = (uint64_t)B * m.epr;
+  m.col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
+  m.io = ft.io[f] + (uint64_t)t * B * E;
+  m.idx = idx ? idx + (size_t)t * B : nullptr;
+  m.stride = (uint64_t)job_blocks * blockDim.x;
+  m.cursor = cursor;
+  m.N = N;
   bool bad = false;
-  // Two elements per lane and sweep, both loads issued before the first store: a wait for loaded
-  // data also waits for earlier stores, so load -> store -> load would cost two memory trips.
-  const uint64_t stride = (uint64_t)job_blocks * blockDim.x;
-  for (uint64_t e0 = (uint64_t)job_block * blockDim.x + threadIdx.x; e0 < total; e0 += 2 * stride) {
-    const uint64_t e1 = e0 + stride;
-    const bool live1 = e1 < total;
-    const uint64_t e1c = live1 ? e1 : e0;
-    const uint32_t row0 = (uint32_t)(e0 / epr), row1 = (uint32_t)(e1c / epr);
-    const uint32_t k0 = (uint32_t)(e0 - (uint64_t)row0 * epr), k1 = (uint32_t)(e1c - (uint64_t)row1 * epr);
-    V* dense0 = reinterpret_cast<V*>(io + (uint64_t)row0 * E) + k0;
-    V* dense1 = reinterpret_cast<V*>(io + (uint64_t)row1 * E) + k1;
-    if constexpr (GATHER) {
-      const uint32_t i0 = idx[(size_t)t * B + row0];
-      const uint32_t i1 = idx[(size_t)t * B + row1];
-      const bool ok0 = i0 < N, ok1 = i1 < N;
-      V v0 = *(reinterpret_cast<const V*>(col + (uint64_t)(ok0 ? i0 : 0u) * E) + k0);
-      V v1 = *(reinterpret_cast<const V*>(col + (uint64_t)(ok1 ? i1 : 0u) * E) + k1);
-      if (!ok0) __builtin_memset(&v0, 0, sizeof(V));
-      if (!ok1) __builtin_memset(&v1, 0, sizeof(V));
-      bad |= !ok0 || (live1 && !ok1);
-      *dense0 = v0;
-      if (live1) *dense1 = v1;
-    } else {
-      uint64_t slot0 = (uint64_t)cursor + row0, slot1 = (uint64_t)cursor + row1;
-      if (slot0 >= N) slot0 -= N;
-      if (slot1 >= N) slot1 -= N;
-      const V v0 = *dense0;
-      const V v1 = *dense1;
-      *(reinterpret_cast<V*>(col + slot0 * E) + k0) = v0;
-      if (live1) *(reinterpret_cast<V*>(col + slot1 * E) + k1) = v1;
-    }
+  for (uint64_t e0 = (uint64_t)job_block * blockDim.x + threadIdx.x; e0 < m.total; e0 += U * m.stride) {
+    Regs<uint32_t, U> at;
+    Regs<Held<V>, U> v;
+    sweep_where<V, GATHER, 0, U>(m, e0, at);
+    sweep_load<V, GATHER, 0, U>(m, e0, at, v, bad);
+    sweep_store<V, GATHER, 0, U>(m, e0, at, v);
   }
   if (bad) atomicOr(&status[t], 1u);
 }
@@ -119,7 +196,7 @@ __device__ __forceinline__ bool move_rows_one_workgroup(const FieldTable& ft, ui
       if (skip_bits && ((skip_bits[row >> 5] >> (row & 31u)) & 1u)) continue;
     }
     uint8_t* dense = io + (dense_row0 + row) * E + (uint64_t)k * w;
-    uint8_t* stored = col + slot * E + (uint64_t)k * w;
+    uint8_t* stored = col + slot * ft.row_stride + (uint64_t)k * w;
     const uint8_t* src = GATHER ? stored : dense;
     uint8_t* dst = GATHER ? dense : stored;
     uint4 v = make_uint4(0, 0, 0, 0);
@@ -185,9 +262,12 @@ __global__ void k_rows(FieldTable ft, JobRanges jr, uint32_t B, const uint32_t* 
     }
 }
 
-// Workgroups per job: weights, claim, then each field with a destination (a field's count is what
-// one pass over its elements needs, capped; the movers stride when capped).
-static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block, uint32_t weights_B, uint32_t claim_B) {
+// Workgroups per job: weights, claim, then each field with a destination.  A field gets the workgroups one
+// pass over its elements needs with as few elements per lane (1, 2, 4 .. what its mover keeps in flight)
+// as keep the field's workgroups over all trees within about one round of the device; the movers
+// stride when that is not enough.
+static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block, uint32_t weights_B, uint32_t claim_B,
+                            uint32_t trees) {
   JobRanges jr{};
   uint32_t at = 0;
   jr.first[0] = at;
@@ -197,10 +277,13 @@ static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block,
   jr.first[2] = at;
   for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f) {
     if (ft && f < ft->n_fields && ft->io[f]) {
-      // two elements per lane once a field is large enough to matter, so that the whole launch stays resident
       const uint64_t elems = (uint64_t)rows * (ft->bytes[f] / ft->vec[f]);
-      uint64_t n = (elems + block - 1) / block;
-      if (n > 512) n = (elems + 2 * block - 1) / (2 * block);
+      const uint32_t most = max_in_flight(ft->vec[f]);
+      uint64_t n = 0;
+      for (uint32_t per_lane = 1; per_lane <= most; per_lane *= 2) {
+        n = (elems + (uint64_t)per_lane * block - 1) / ((uint64_t)per_lane * block);
+        if (n * trees <= 512) break;
+      }
       if (n > (1u << 20)) n = 1u << 20;
       at += (uint32_t)n;
     }
@@ -212,7 +295,7 @@ static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block,
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s) {
   const uint32_t block = tn.gather_block;
-  const JobRanges jr = job_ranges(&ft, B, block, 0, 0);
+  const JobRanges jr = job_ranges(&ft, B, block, 0, 0, g.T);
   const uint32_t gx = jr.first[2 + kMaxFields];
   if (gx == 0) return hipSuccess;
   PER_LAUNCH(KID_GATHER, k_rows<true>, dim3(gx, g.T), dim3(block), 0, s, ft, jr, B, idx, 0, g.N, g.status);
@@ -225,7 +308,7 @@ static hipError_t launch_finish(const Geom& g, const Tuning& tn, const FieldTabl
   if (rows) ft = *rows;
   if (!a.w && !a.has_claim) return rows ? launch_gather(g, tn, ft, a.B, a.idx, s) : hipSuccess;
   const uint32_t block = tn.gather_block;
-  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, block, a.w ? a.B : 0u, a.has_claim ? a.claim.B : 0u);
+  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, block, a.w ? a.B : 0u, a.has_claim ? a.claim.B : 0u, g.T);
   PER_LAUNCH(KID_FINISH, k_finish, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), 0, s, ft, jr, g, a);
   return hipGetLastError();
 }
@@ -233,7 +316,7 @@ static hipError_t launch_finish(const Geom& g, const Tuning& tn, const FieldTabl
 hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t n, uint32_t cursor,
                           hipStream_t s) {
   const uint32_t block = tn.gather_block;
-  const JobRanges jr = job_ranges(&ft, n, block, 0, 0);
+  const JobRanges jr = job_ranges(&ft, n, block, 0, 0, g.T);
   const uint32_t gx = jr.first[2 + kMaxFields];
   if (gx == 0) return hipSuccess;
   PER_LAUNCH(KID_SCATTER, k_rows<false>, dim3(gx, g.T), dim3(block), 0, s, ft, jr, n, nullptr, cursor, g.N, g.status);

@@ -468,7 +468,7 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const Cl
   if (tblock > 512) tblock = 512;   // half the lanes of a compute unit are left to the other jobs
   FieldTable ft{};
   if (rows) ft = *rows;
-  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u);
+  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u, g.T);
   const uint32_t tree_blocks = g.n[sl.hb];
   const uint32_t chain = lazy_top_height(g, tn) ? 0u : 1u;
   const dim3 grid(tree_blocks + jr.first[2 + kMaxFields], g.T);

@@ -18,6 +18,7 @@ struct per_buffer {
   size_t arena_bytes;
   uint8_t* col[kMaxFields];
   uint64_t col_stride[kMaxFields];
+  uint32_t row_stride;
   uint64_t cursor, size;
   bool claims_left;          // a launch failed between a claim phase and its tree pass: the claim arrays are not all zero
   int weight_norm;           // PER_NORM_BATCH or PER_NORM_BUFFER
@@ -43,6 +44,7 @@ struct Layout {
   size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, min1_off, col_off[kMaxFields];
   uint32_t dirty_stride, arrive_stride, arrive_level_off[kMaxHeight + 1];
   uint64_t col_stride[kMaxFields];
+  uint32_t row_stride;        // bytes between stored rows
   uint32_t owner_stride, nclaim_stride, min1_stride;
   size_t tree_end;            // bytes up to here are zero-filled as 32-bit words at create
   size_t total;
@@ -59,6 +61,15 @@ int check_config(const per_config* c) {
     if (c->field_bytes[f] == 0 || c->field_bytes[f] > (1u << 20)) return PER_EINVAL;
   if (!(c->init_max_priority > 0.0f) || !isfinite(c->init_max_priority)) return PER_EINVAL;
   return PER_OK;
+}
+
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+// widest power-of-two access (<= 16 bytes) that divides the row size and the pointer
+uint32_t vec_width(uint32_t bytes, const void* io) {
+  uint32_t v = 16;
+  while (v > 1 && (bytes % v != 0 || misaligned(io, v))) v >>= 1;
+  return v;
 }
 
 void make_layout(const per_config* c, Layout* L) {
@@ -104,26 +115,29 @@ void make_layout(const per_config* c, Layout* L) {
   L->min1_off = off;
   off = round_up(off + (size_t)L->min1_stride * T * 4, kAlign);
   L->tree_end = off;
+  // payload, row-major: every field at an offset aligned to the widest access its size allows, rows 16 bytes apart or a multiple
+  uint32_t row = 0;
+  uint32_t field_off[kMaxFields] = {};
   for (uint32_t f = 0; f < c->n_fields; ++f) {
-    L->col_stride[f] = round_up((size_t)c->capacity * c->field_bytes[f], kAlign);
-    L->col_off[f] = off;
-    off += (size_t)L->col_stride[f] * T;
+    const uint32_t a = vec_width(c->field_bytes[f], nullptr);
+    row = (uint32_t)round_up(row, a);
+    field_off[f] = row;
+    row += c->field_bytes[f];
   }
+  L->row_stride = (uint32_t)round_up(row, 16);
+  const size_t tree_rows = round_up((size_t)c->capacity * L->row_stride, kAlign);
+  for (uint32_t f = 0; f < c->n_fields; ++f) {
+    L->col_stride[f] = tree_rows;
+    L->col_off[f] = off + field_off[f];
+  }
+  off += tree_rows * T;
   L->total = round_up(off, kAlign);
-}
-
-bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
-
-// widest power-of-two access (<= 16 bytes) that divides the row size and the pointer
-uint32_t vec_width(uint32_t bytes, const void* io) {
-  uint32_t v = 16;
-  while (v > 1 && (bytes % v != 0 || misaligned(io, v))) v >>= 1;
-  return v;
 }
 
 int fill_fields(per_t* p, void* const* io, FieldTable* ft) {
   memset(ft, 0, sizeof(*ft));
   ft->n_fields = p->cfg.n_fields;
+  ft->row_stride = p->row_stride;
   bool any = false;
   for (uint32_t f = 0; f < ft->n_fields; ++f) {
     ft->col[f] = p->col[f];
@@ -225,6 +239,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
     p->col[f] = p->arena + L.col_off[f];
     p->col_stride[f] = L.col_stride[f];
   }
+  p->row_stride = L.row_stride;
   p->tn.lds_budget_bytes = 64 * 1024;
   p->tn.sample_block = 256;
   p->tn.update_block = 256;

@@ -57,13 +57,16 @@ constexpr uint32_t kNoMin = 0x7F800000u;   // fp32 bits of +inf: above every val
 constexpr uint32_t kWeightBufferNorm = 1u;
 constexpr uint32_t kWeightPartsShift = 8u;
 
+// Payload.  Stored row-major: the fields of a row lie side by side (a row of several fields is then one or
+// two cache lines to fetch, not one per field); the caller's arrays are dense per field.
 struct FieldTable {
-  uint8_t* col[kMaxFields];         // column f of tree 0
+  uint8_t* col[kMaxFields];         // field f of row 0 of tree 0
   uint8_t* io[kMaxFields];          // caller's dense [T][B][bytes] array (source or destination)
-  uint64_t col_stride[kMaxFields];  // bytes between trees of a column
-  uint32_t bytes[kMaxFields];       // bytes per row
+  uint64_t col_stride[kMaxFields];  // bytes between trees (the same for every field)
+  uint32_t bytes[kMaxFields];       // bytes of the field
   uint32_t vec[kMaxFields];         // bytes moved per lane: 16, 8, 4, 2 or 1
   uint32_t n_fields;
+  uint32_t row_stride;              // bytes between stored rows (multiple of 16)
 };
 
 // Stamps of the group entries: 26 bits, taken from a counter in device memory that starts at 1 and
