@@ -425,6 +425,7 @@ static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, const ClaimAr
   if (tblock == 0) {
     const uint64_t per_subtree = hb > 1 ? sl.lds_off[1] : 1;
     uint64_t expect = 2 * ((uint64_t)B + g.n[hb] - 1) / g.n[hb];
+    if ((uint64_t)g.n[hb] * g.T >= 2048) expect = (expect + 1) / 2;   // many small subtrees (many trees): more workgroups resident instead
     if (expect > per_subtree) expect = per_subtree;
     uint64_t want = expect * Fan<LOGK>::LPS;
     if (hb > 2) {   // the dense heights of the subtree want a lane group per height-2 node
