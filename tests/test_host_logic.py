@@ -77,6 +77,17 @@ def test_bad_configurations_are_rejected_on_the_host():
     assert lib.per_update(None, 1, None, None, None) == per.EINVAL
     assert lib.per_insert(None, 1, None, None, None, None) == per.EINVAL
     assert lib.per_gather(None, 1, None, None, None) == per.EINVAL
+    assert lib.per_update_td(None, 1, None, None, 1e-6, 0.6, None) == per.EINVAL
+    assert lib.per_update_delta(None, 1, None, None, None) == per.EINVAL
+    assert lib.per_run_requests(None, 1, None, None, None) == per.EINVAL
+    assert lib.per_run_steps(None, 1, 0, 1, None, None) == per.EINVAL
+    assert lib.per_set_weight_norm(None, 0) == per.EINVAL
+    assert lib.per_min_priority(None, None, None) == per.EINVAL
+    assert lib.per_note_replay(None) == per.EINVAL
+    assert lib.per_set_rng(None, 1, 0) == per.EINVAL
+    assert lib.per_set_ring(None, 0, 0) == per.EINVAL
+    assert lib.per_set_tuning(None, b"lazy_top", 1) == per.EINVAL
+    assert lib.per_run_steps_fits(None) == 0
     assert lib.per_size(None) == 0
     assert lib.per_strerror(per.ENOMEM) == b"arena too small"
 
