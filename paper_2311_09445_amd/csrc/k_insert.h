@@ -221,6 +221,11 @@ static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const F
     floats += ((r.b0 - r.a0) + (r.b1 - r.a1)) * K;
   }
   uint32_t block = (n * Fan<LOGK>::LPS + 63) / 64 * 64;
+  // (enough lanes to move all row elements in one sweep: a second sweep is a second trip to memory)
+  uint64_t row_elements = 0;
+  for (uint32_t i = 0; i < f.n_fields; ++i)
+    if (f.io[i]) row_elements += (uint64_t)n * (f.bytes[i] / f.vec[i]);
+  if (row_elements > block) block = (uint32_t)((row_elements > 1024 ? 1024 : row_elements) + 63) / 64 * 64;
   if (block < 256) block = 256;
   if (block > 1024) block = 1024;
   PER_LAUNCH(KID_INSERT_SMALL, k_insert_small<LOGK>, dim3(g.T), dim3(block), (size_t)floats * 4, s, a, f, n, cursor, prio,
