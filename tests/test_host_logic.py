@@ -124,3 +124,11 @@ def test_row_hash_matches_between_numpy_and_torch():
         a = wl.row_bytes(3, c, f, b)
         t = wl.row_bytes_torch(3, torch.from_numpy(c), f, b).numpy()
         assert np.array_equal(a, t)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
