@@ -1182,3 +1182,37 @@ def test_fused_step_on_an_empty_total_that_the_update_fills(K, N):
     m.compare_status()
     m.step(wl.WORKLOADS["c3_ddpg"], 2, B=700)                 # and the next step samples the filled tree
     m.compare_tree()
+
+
+# a seeded sweep of shapes beyond the hand-picked ones above
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("sweep_seed", [11, 12, 13])
+def test_seeded_sweep_of_shapes(sweep_seed):
+    """The operation-mix, interleaved, one-launch, placement and replay tests above at shapes drawn from a seeded
+    generator: fanout, capacity (ragged, powers of two and their neighbours), tree count, batch and row layout."""
+    r = np.random.default_rng(sweep_seed)
+    layouts = [(), (5,), (12,), (128,), FIELDS, (68, 24, 4, 68, 1), (5, 68), (3, 8)]
+    for case in range(24):
+        K = int(r.choice([2, 4, 8, 16, 32, 64]))
+        T = int(r.integers(1, 4))
+        fb = layouts[int(r.integers(0, len(layouts)))]
+        which = case % 6
+        if which == 0:
+            N = max(1, (1 << int(r.integers(1, 18))) + int(r.integers(-1, 2)))
+            test_random_operation_mix(K, N, T)
+        elif which == 1:
+            test_buffer_wide_weights_through_an_operation_mix(K, int(r.integers(1, 200000)), T)
+        elif which == 2:
+            test_interleaved_operations(K, int(r.integers(1100, 300000)), T, int(r.integers(0, 1 << 30)))
+        elif which == 3:
+            N = int(r.integers(1100, 30000))
+            if PrioritizedReplay(K, N, T, fb, 1.0).run_steps_fits():
+                test_run_steps_equals_the_separate_calls(K, N, T, int(r.integers(1, 1025)), int(r.choice([0, 1, 4, 40])),
+                                                         fb, bool(r.integers(0, 2)), bool(r.integers(0, 2)))
+                test_run_requests_equals_the_separate_calls(K, N, T, fb, int(r.integers(0, 1 << 30)))
+        elif which == 4:
+            N = int(r.integers(5000, 300000))
+            test_fused_step_wherever_the_update_batch_lies(K, N, min(N, int(r.integers(64, 20000))), fb)
+        else:
+            N = int(r.integers(4096, 300000))
+            test_captured_step_replays(K, N, min(N, int(r.integers(64, 20000))))
