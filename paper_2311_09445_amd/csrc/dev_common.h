@@ -73,6 +73,22 @@ template <typename T>
 __device__ __forceinline__ const T* kernarg_at(size_t offset) {
   return (const T*)((const char*)__builtin_amdgcn_kernarg_segment_ptr() + offset);
 }
+// Reads one word of each of the first LINES 64-byte lines of the kernel-argument segment, all in flight
+// together.  A kernel with many arguments otherwise meets those lines one after the other (its prologue
+// is a chain of scalar loads, each waited for before the next is issued), every first touch a miss of
+// the scalar cache.
+template <typename... Args>
+constexpr int kernarg_lines() {   // lines that hold arguments of these types (each rounded up to 8 bytes: a few bytes over, never under)
+  return (int)(((size_t)0 + ... + ((sizeof(Args) + 7) / 8 * 8)) + 63) / 64;
+}
+template <int LINES>
+__device__ __forceinline__ void touch_kernel_arguments() {
+  const uint32_t* ka = kernarg_at<uint32_t>(0);
+  uint32_t acc = 0;
+#pragma unroll
+  for (int i = 0; i < LINES; ++i) acc |= ka[i * 16];
+  asm volatile("" ::"s"(acc));
+}
 __device__ __forceinline__ void fill_level_table(uint32_t H, uint32_t t, LevelTable* tab) {
   const Geom* gk = kernarg_at<Geom>(0);
   const uint32_t h = threadIdx.x;
@@ -172,12 +188,30 @@ __device__ __forceinline__ uint32_t buffer_min_bits(const Geom& g, uint32_t t, u
   return wave_min_u32(m);
 }
 
+// A control word that every lane reads from one address, fetched with an ordinary vector load.  The compiler
+// would read a uniform address through the scalar cache (or move the loaded word to a scalar register) and
+// make the wave wait for it on the spot: a trip to memory of its own in front of the loads that follow.
+// With a lane offset it cannot see through (always zero) the word travels with those loads and is waited
+// for with them.
+__device__ __forceinline__ uint32_t read_word_with_the_loads(const uint32_t* p) {
+  uint32_t zero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
+  return p[zero];
+}
+// Pins what is computed from x to after this point.  (Arithmetic on a loaded word otherwise moves up to the
+// load, and the wait for the load with it.)
+__device__ __forceinline__ uint32_t not_before_here(uint32_t x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 // Running maximum priority: mx = fp32 bits of this lane's valid positive value (0: none).  One
 // atomic per wave, and only when the wave would actually raise the maximum; the plain read may
 // be stale, which can only cause a redundant atomic, never a missed one (the value only grows).
 // `seen` is the value read when the kernel started (so the read overlaps the other loads).
 __device__ __forceinline__ uint32_t read_max_bits(const Geom& g, uint32_t t) {
-  return *reinterpret_cast<volatile uint32_t*>(&g.max_v[t]);
+  // (a relaxed atomic load: a volatile one makes the wave wait for it on the spot; other workgroups raise the word meanwhile)
+  return __hip_atomic_load(reinterpret_cast<const uint32_t*>(&g.max_v[t]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void raise_max(const Geom& g, uint32_t t, uint32_t mx, uint32_t seen) {
   mx = wave_max_u32(mx);

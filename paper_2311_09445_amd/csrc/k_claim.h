@@ -65,11 +65,12 @@ __device__ __forceinline__ void claim_element(const Geom& g, uint32_t t, uint32_
 // First stamp of the batch being claimed.  Through group entries it is the device counter (stable while the
 // claim phase runs: only a tree pass writes it); one lane of the phase (`leader`) leaves it for the
 // batch's tree pass.
-__device__ __forceinline__ uint32_t claim_base(const Geom& g, uint32_t t, uint32_t group_mode, bool leader) {
-  if (!group_mode) return 1u;
-  const uint32_t base = g.sbase[t];
-  if (leader) g.sfloor[t] = base;
-  return base;
+__device__ __forceinline__ uint32_t claim_base(const Geom& g, uint32_t t, uint32_t group_mode) {
+  return group_mode ? read_word_with_the_loads(g.sbase + t) : 1u;
+}
+// (stores last: the leader's store would otherwise make its wave wait for `base` before it issues its loads)
+__device__ __forceinline__ void leave_claim_base(const Geom& g, uint32_t t, uint32_t group_mode, bool leader, uint32_t base) {
+  if (group_mode && leader) g.sfloor[t] = base;
 }
 
 // Claims elements of the batch, strided over the job's workgroups.  Called by whole workgroups.
@@ -79,7 +80,7 @@ template <bool TD = false>
 __device__ __forceinline__ void claim_job(const Geom& g, uint32_t t, const ClaimArgs& c, uint32_t job_block,
                                           uint32_t job_blocks) {
   if (job_block * blockDim.x >= c.B) return;   // nothing to do for this workgroup
-  const uint32_t first = claim_base(g, t, c.group_mode, job_block == 0 && threadIdx.x == 0);
+  const uint32_t first = claim_base(g, t, c.group_mode);
   const uint32_t max_seen = read_max_bits(g, t);
   uint32_t mx = 0;
   uint32_t flags = 0;
@@ -96,6 +97,9 @@ __device__ __forceinline__ void claim_job(const Geom& g, uint32_t t, const Claim
   }
   raise_max(g, t, mx, max_seen);
   if (flags) atomicOr(&g.status[t], flags);
+  leave_claim_base(g, t, c.group_mode, job_block == 0 && threadIdx.x == 0, first);
 }
 
-__global__ void k_update_claim(Geom g, ClaimArgs c) { claim_job<true>(g, blockIdx.y, c, blockIdx.x, gridDim.x); }
+__global__ void k_update_claim(Geom g, ClaimArgs c) {
+  claim_job<true>(g, blockIdx.y, c, blockIdx.x, gridDim.x);
+}

@@ -84,6 +84,8 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   constexpr int ROW = K + 4;                  // staging row, floats
   using Vec = typename std::conditional<LOGK == 1, float2, float4>::type;
   constexpr int VF = sizeof(Vec) / 4;
+  touch_kernel_arguments<kernarg_lines<Geom, TopCopy, uint32_t, uint32_t, float, const float*, uint32_t*, float*, float*, uint32_t,
+                                       int, uint32_t, ClaimArgs, int, RngArgs>()>();
   extern __shared__ __attribute__((aligned(16))) float lds[];   // 16-byte LDS accesses need the alignment
   __shared__ uint32_t s_min[16];
   __shared__ float s_total;
@@ -111,10 +113,8 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   // which buffer of partial batch minima this call fills (stable while this kernel runs: the weights job of
   // the call before has written it), fetched in that same trip
   uint32_t vbuf = 0;
-  if (out_w && sample_blocks > 1) {
-    vbuf = g.vnext[t] & 1u;
-    if (bx == 0 && threadIdx.x == 0) g.vcur[t] = vbuf;   // for the weights job of this call (also when nothing can be sampled)
-  }
+  const bool partial_minima = out_w && sample_blocks > 1;
+  if (partial_minima) vbuf = read_word_with_the_loads(g.vnext + t);   // (its low bit; taken where it is used, so that nothing waits for the word here)
   // the new priority of this lane's sample and the running maximum, likewise
   float upd_v = 0.0f;
   uint32_t max_seen = 0;
@@ -122,7 +122,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   if (claim_mode == 1) {
     upd_v = c.prio[o];
     max_seen = read_max_bits(g, t);
-    claim_first = claim_base(g, t, c.group_mode, bx == 0 && threadIdx.x == 0);
+    claim_first = claim_base(g, t, c.group_mode);
   }
 
   uint32_t off[kTopSlots + 1];
@@ -183,7 +183,11 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
       if (out_w) out_w[o] = 0.0f;
     }
     // (a fused update of these samples finds no valid index: every element is out of range)
-    if (bx == 0 && threadIdx.x == 0) atomicOr(&g.status[t], claim_mode == 1 ? 5u : 4u);
+    if (bx == 0 && threadIdx.x == 0) {
+      atomicOr(&g.status[t], claim_mode == 1 ? 5u : 4u);
+      if (partial_minima) g.vcur[t] = not_before_here(vbuf) & 1u;   // the weights job of this call runs all the same
+      if (claim_mode == 1) leave_claim_base(g, t, c.group_mode, true, claim_first);
+    }
     return;
   }
 
@@ -255,6 +259,8 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
       if (active) out_w[o] = importance_weight(val, __uint_as_float(mm), beta);
     } else {                // partial minima, spread over kVminSlots addresses; the weights job finishes
       if (active) out_w[o] = val;
+      vbuf = not_before_here(vbuf) & 1u;
+      if (bx == 0 && threadIdx.x == 0) g.vcur[t] = vbuf;   // tells the weights job of this call which buffer it is
       if (lane == 0)
         atomicMin(&g.vmin[((size_t)vbuf * g.T + t) * kVminSlots + ((bx * (blockDim.x >> 6) + wave) % kVminSlots)], m);
     }
@@ -264,6 +270,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
     if (active) claim_element(g, t, size, c.group_mode, claim_first, s, node, upd_v, mx, flags);
     raise_max(g, t, mx, max_seen);
     if (flags) atomicOr(&g.status[t], flags);
+    leave_claim_base(g, t, c.group_mode, bx == 0 && threadIdx.x == 0, claim_first);
   }
 }
 
@@ -282,11 +289,12 @@ __device__ __forceinline__ void weights_job(const Geom& g, uint32_t t, uint32_t 
   const uint32_t* part0 = g.vmin + (size_t)t * kVminSlots;
   const uint32_t* part1 = g.vmin + ((size_t)g.T + t) * kVminSlots;
   uint32_t m0 = 0x7F800000u, m1 = 0x7F800000u;
+  const uint32_t vword = read_word_with_the_loads(g.vcur + t);
   for (uint32_t j = threadIdx.x; j < kVminSlots; j += blockDim.x) {
     m0 = part0[j] < m0 ? part0[j] : m0;
     m1 = part1[j] < m1 ? part1[j] : m1;
   }
-  const uint32_t vbuf = g.vcur[t] & 1u;
+  const uint32_t vbuf = not_before_here(vword) & 1u;
   uint32_t m = wave_min_u32(vbuf ? m1 : m0);
   if ((threadIdx.x & 63u) == 0) s_wmin[threadIdx.x >> 6] = m;
   if (job_block == 0) {

@@ -90,9 +90,11 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   // (value bits, 0x80000000 | leaf within the node), else y = 0
   uint2* groups = g.nclaim + (size_t)t * g.nclaim_stride;
   // first stamp of this batch, left by its claim phase (a batch that claimed leaf by leaf has no entries)
-  const uint32_t floor = sl.group_batch ? g.sfloor[t] : 0xFFFFFFFFu;
-  auto node_entry = [&](uint32_t node) -> uint2 {
-    uint2 e = groups[LOGK >= 5 ? node : (node << LOGK) >> 5];
+  const uint32_t floor = sl.group_batch ? read_word_with_the_loads(g.sfloor + t) : 0xFFFFFFFFu;
+  // (fetched here, decoded there: the comparison would make the wave wait for the entry, and the floor, before it
+  // issues the loads that follow)
+  auto fetch_entry = [&](uint32_t node) -> uint2 { return groups[LOGK >= 5 ? node : (node << LOGK) >> 5]; };
+  auto decode_entry = [&](uint2 e, uint32_t node) -> uint2 {
     bool mine = (e.y >> 6) >= floor;
     if constexpr (LOGK < 5) mine = mine && ((e.y & 31u) >> LOGK) == (node & ((32u >> LOGK) - 1u));
     e.y = mine ? 0x80000000u | (e.y & (uint32_t)(K - 1)) : 0u;
@@ -104,7 +106,7 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   uint2 entry_first = make_uint2(0, 0);
   if (f_first < hi1) {
     bits_first = node_bits(f_first);
-    entry_first = node_entry(f_first);
+    entry_first = fetch_entry(f_first);
   }
   {
     // slot 0 from memory, the rest zero.  The first two sweeps' loads are issued together (a sweep that
@@ -131,8 +133,10 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
       entry = entry_first;
     } else if (f < hi1) {
       bits = node_bits(f);
-      entry = node_entry(f);
+      entry = fetch_entry(f);
     }
+    entry = decode_entry(entry, f);
+    if (!(f < hi1)) entry.y = 0;
     const bool listed = bits != 0 || entry.y != 0;
     const unsigned long long m = __ballot(listed);
     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
