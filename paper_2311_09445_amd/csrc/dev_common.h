@@ -221,7 +221,9 @@ __device__ __forceinline__ void raise_max(const Geom& g, uint32_t t, uint32_t mx
 // Importance weight (prioritized experience replay, cited in Section II-A):
 // w = (size * v / total)^-beta / max over the batch.  The maximum is reached at the batch minimum
 // of v, and size / total cancels in the quotient, which leaves (v / vmin)^-beta: one power instead
-// of two.  fp64, so that the result stays within 1e-6 of an fp64 evaluation of the two-power form.
+// of two.  fp64, so that the result stays within 1e-6 of an fp64 evaluation of the two-power form;
+// as exp(-beta log(.)), whose error (about beta |log| 2^-53) is far inside that and which costs less
+// than the library's power function.
 __device__ __forceinline__ float importance_weight(float v, float vmin, float beta) {
-  return (float)pow((double)v / (double)vmin, -(double)beta);
+  return (float)exp(-(double)beta * log((double)v / (double)vmin));
 }

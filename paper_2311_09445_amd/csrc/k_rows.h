@@ -128,6 +128,16 @@ __device__ __forceinline__ void move_rows(const FieldTable& ft, uint32_t f, uint
   if (bad) atomicOr(&status[t], 1u);
 }
 
+// The field whose row job workgroup b of the job grid belongs to (kMaxFields: none).  The ranges lie back to
+// back, so it is the number of ranges that end at or before b; written without an early exit so that the
+// range ends are read together, not one after the other.
+__device__ __forceinline__ uint32_t job_field(const JobRanges& jr, uint32_t b) {
+  uint32_t f = 0;
+#pragma unroll
+  for (uint32_t k = 0; k < (uint32_t)kMaxFields; ++k) f += b >= jr.first[3 + k] ? 1u : 0u;
+  return f;
+}
+
 // Moves the rows of one payload field; the workgroup is number job_block of job_blocks on that field.
 template <bool GATHER>
 __device__ __forceinline__ void rows_job(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
@@ -240,12 +250,9 @@ __global__ void k_finish(FieldTable ft, JobRanges jr, Geom g, FinishArgs a) {
     claim_job(g, t, a.claim, b - jr.first[1], jr.first[2] - jr.first[1]);
     return;
   }
-#pragma unroll
-  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
-    if (b >= jr.first[2 + f] && b < jr.first[3 + f]) {
-      rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
-      return;
-    }
+  const uint32_t f = job_field(jr, b);
+  if (f < (uint32_t)kMaxFields)
+    rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
 }
 
 // Stand-alone gather (GATHER) and insert scatter: one job per payload field.
@@ -254,12 +261,9 @@ __global__ void k_rows(FieldTable ft, JobRanges jr, uint32_t B, const uint32_t* 
                        uint32_t N, uint32_t* status) {
   const uint32_t t = blockIdx.y;
   const uint32_t b = blockIdx.x;
-#pragma unroll
-  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
-    if (b >= jr.first[2 + f] && b < jr.first[3 + f]) {
-      rows_job<GATHER>(ft, f, t, B, idx, cursor, N, status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
-      return;
-    }
+  const uint32_t f = job_field(jr, b);
+  if (f < (uint32_t)kMaxFields)
+    rows_job<GATHER>(ft, f, t, B, idx, cursor, N, status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
 }
 
 // Workgroups per job: weights, claim, then each field with a destination.  A field gets the workgroups one

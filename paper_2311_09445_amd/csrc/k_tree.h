@@ -371,16 +371,19 @@ k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldT
     return;
   }
   const uint32_t b = blockIdx.x - tree_blocks;
+  PER_TRACE_DECL;
+  PER_MARK(0);
   if (b < jr.first[1]) {
     weights_job(g, t, a.B, a.size, a.beta, a.w, a.weight_mode, b, jr.first[1]);
+    PER_MARK(3);
+    PER_FLUSH();
     return;
   }
-#pragma unroll
-  for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f)
-    if (b >= jr.first[2 + f] && b < jr.first[3 + f]) {
-      rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
-      return;
-    }
+  const uint32_t f = job_field(jr, b);
+  if (f < (uint32_t)kMaxFields)
+    rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+  PER_MARK(3);
+  PER_FLUSH();
 }
 
 // Height of the workgroup roots of the tree pass: the whole tree for small trees, else the
