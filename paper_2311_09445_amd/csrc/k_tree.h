@@ -361,9 +361,12 @@ k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
 // (workgroups 0 .. tree_blocks-1) and, beside it, what is left of the sampling call: the
 // importance weights and the rows of the sampled indices (JobRanges, offset by tree_blocks).  The
 // tree pass is a chain of dependent memory trips and the row traffic fills the gaps; launched with
-// workgroups of at most 512 lanes so that the two kinds share the compute units.
+// workgroups of at most 512 lanes so that the two kinds share the compute units.  Held to 96 scalar
+// registers (it needs no scratch memory for that; the row jobs' argument tables would take a few more):
+// with its 54 vector registers four workgroups then fit a compute unit instead of three, which the many
+// small trees of a multi-tree buffer gain from (one big tree neither gains nor loses).
 template <int LOGK, bool TRACK_MIN>
-__global__ void __launch_bounds__(512)
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_num_sgpr(96)))
 k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldTable ft, JobRanges jr, FinishArgs a) {
   const uint32_t t = blockIdx.y;
   if (blockIdx.x < tree_blocks) {
