@@ -362,9 +362,11 @@ k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
 // importance weights and the rows of the sampled indices (JobRanges, offset by tree_blocks).  The
 // tree pass is a chain of dependent memory trips and the row traffic fills the gaps; launched with
 // workgroups of at most 512 lanes so that the two kinds share the compute units.  Held to 96 scalar
-// registers (it needs no scratch memory for that; the row jobs' argument tables would take a few more):
-// with its 54 vector registers four workgroups then fit a compute unit instead of three, which the many
-// small trees of a multi-tree buffer gain from (one big tree neither gains nor loses).
+// registers (it needs no scratch memory for that; the row jobs' argument tables would take a few more),
+// which the many small trees of a multi-tree buffer gain from (one big tree neither gains nor loses).
+// Three such workgroups are resident per compute unit where the machine reserves 16 more scalar
+// registers per wave; a cap of 80 makes it four, measured slower: the jobs then slow each other down
+// in the memory system by more than the earlier start of the row jobs gives back.
 template <int LOGK, bool TRACK_MIN>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_num_sgpr(96)))
 k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldTable ft, JobRanges jr, FinishArgs a) {
@@ -376,6 +378,7 @@ k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldT
   const uint32_t b = blockIdx.x - tree_blocks;
   PER_TRACE_DECL;
   PER_MARK(0);
+  PER_MARK_HWID(15);
   if (b < jr.first[1]) {
     weights_job(g, t, a.B, a.size, a.beta, a.w, a.weight_mode, b, jr.first[1]);
     PER_MARK(3);
