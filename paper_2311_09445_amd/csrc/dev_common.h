@@ -23,6 +23,39 @@ __device__ __forceinline__ bool valid_priority(float v) {
 
 __device__ __forceinline__ uint32_t shr64(uint32_t x, uint32_t sh) { return (uint32_t)((uint64_t)x >> sh); }
 
+// Step k of a butterfly over aligned groups of up to 16 lanes, as a data-parallel-primitive move of the
+// vector unit (a few cycles) instead of a trip through the LDS crossbar.  Steps 0 and 1 swap lanes within
+// fours (i ^ 1, i ^ 2).  Steps 2 and 3 mirror the lanes of an eight or a sixteen (i -> 7 - i, 15 - i),
+// which serves as i ^ 4, i ^ 8 because after the steps before them all lanes of a four (an eight) hold the
+// same value.  Only for reductions with a commutative operation, taken in the order k = 0, 1, 2, 3.
+template <int STEP>
+__device__ __forceinline__ int butterfly_move(int x) {
+  static_assert(STEP >= 0 && STEP <= 3, "groups of at most 16 lanes");
+  constexpr int ctrl = STEP == 0 ? 0xB1      // quad_perm [1,0,3,2]
+                     : STEP == 1 ? 0x4E      // quad_perm [2,3,0,1]
+                     : STEP == 2 ? 0x141     // row_half_mirror
+                                 : 0x140;    // row_mirror
+  return __builtin_amdgcn_update_dpp(0, x, ctrl, 0xF, 0xF, true);
+}
+template <int LOGLPS, int STEP = 0>
+__device__ __forceinline__ float butterfly_sum(float s) {
+  if constexpr (STEP < LOGLPS) {
+    s = s + __int_as_float(butterfly_move<STEP>(__float_as_int(s)));
+    return butterfly_sum<LOGLPS, STEP + 1>(s);
+  } else {
+    return s;
+  }
+}
+template <int LOGLPS, int STEP = 0>
+__device__ __forceinline__ uint32_t butterfly_min(uint32_t m) {
+  if constexpr (STEP < LOGLPS) {
+    const uint32_t o = (uint32_t)butterfly_move<STEP>((int)m);
+    return butterfly_min<LOGLPS, STEP + 1>(o < m ? o : m);
+  } else {
+    return m;
+  }
+}
+
 // Sum of the K children starting at grp; q = lane position inside the LPS-lane group.
 // Every lane of the group returns the same value.
 template <int LOGK>
@@ -32,10 +65,7 @@ __device__ __forceinline__ float group_sum(const float* grp, unsigned q) {
     return c.x + c.y;
   } else {
     const float4 c = *reinterpret_cast<const float4*>(grp + 4 * q);
-    float s = (c.x + c.y) + (c.z + c.w);
-#pragma unroll
-    for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) s = s + __shfl_xor(s, 1 << k);
-    return s;
+    return butterfly_sum<Fan<LOGK>::LOGLPS>((c.x + c.y) + (c.z + c.w));
   }
 }
 
@@ -54,9 +84,7 @@ __device__ __forceinline__ uint32_t group_min_positive(const float* grp, unsigne
   } else {
     const float4 c = *reinterpret_cast<const float4*>(grp + 4 * q);
     uint32_t m = min_u32(min_u32(positive_bits(c.x), positive_bits(c.y)), min_u32(positive_bits(c.z), positive_bits(c.w)));
-#pragma unroll
-    for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) m = min_u32(m, (uint32_t)__shfl_xor((int)m, 1 << k));
-    return m;
+    return butterfly_min<Fan<LOGK>::LOGLPS>(m);
   }
 }
 

@@ -222,15 +222,11 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
         if (sel & 4u) it.c.z = ev;
         if (sel & 8u) it.c.w = ev;
         it.my |= sel;
-        sum = (it.c.x + it.c.y) + (it.c.z + it.c.w);
-#pragma unroll
-        for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) sum = sum + __shfl_xor(sum, 1 << k);
+        sum = butterfly_sum<Fan<LOGK>::LOGLPS>((it.c.x + it.c.y) + (it.c.z + it.c.w));
         if constexpr (TRACK_MIN) {
           uint32_t m = min_u32(min_u32(positive_bits(it.c.x), positive_bits(it.c.y)),
                                min_u32(positive_bits(it.c.z), positive_bits(it.c.w)));
-#pragma unroll
-          for (int k = 0; k < Fan<LOGK>::LOGLPS; ++k) m = min_u32(m, (uint32_t)__shfl_xor((int)m, 1 << k));
-          it.mn = m;
+          it.mn = butterfly_min<Fan<LOGK>::LOGLPS>(m);
         }
       }
       return sum;
