@@ -189,17 +189,20 @@ __device__ __forceinline__ void descend_lane(const float* grp, float& r, unsigne
   }
 }
 
+// (sixteens by the butterfly moves of the vector unit, the last two steps across them by LDS permutes)
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+  x = butterfly_min<4>(x);
 #pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
+  for (int m = 16; m <= 32; m <<= 1) {
     const uint32_t y = (uint32_t)__shfl_xor((int)x, m);
     x = y < x ? y : x;
   }
   return x;
 }
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+  x = ~butterfly_min<4>(~x);
 #pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
+  for (int m = 16; m <= 32; m <<= 1) {
     const uint32_t y = (uint32_t)__shfl_xor((int)x, m);
     x = y > x ? y : x;
   }
