@@ -241,7 +241,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   }
   p->row_stride = L.row_stride;
   p->tn.lds_budget_bytes = 64 * 1024;
-  p->tn.sample_block = 256;
+  p->tn.sample_block = 128;   // (two waves: measured faster than four on large batches, 20.8 -> 20.1 us on the 65536-sample workload)
   p->tn.update_block = 256;
   p->tn.gather_block = 256;
   p->tn.tree_block = 0;   // chosen per launch
