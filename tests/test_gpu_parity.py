@@ -1216,3 +1216,21 @@ def test_seeded_sweep_of_shapes(sweep_seed):
         else:
             N = int(r.integers(4096, 300000))
             test_captured_step_replays(K, N, min(N, int(r.integers(64, 20000))))
+
+
+@pytest.mark.parametrize("beta", [0.0, 0.01, 0.4, 1.0, 2.5, 3.0])
+def test_weights_over_a_wide_range_of_ratios_and_exponents(beta):
+    """Importance weights (Section II-A) where the ratio to the batch minimum spans twelve decades and beta goes
+    beyond 1: the kernels' own fp64 evaluation of the power against the oracle's, within 1e-6 relative, in the
+    separate call, in the one-workgroup form (small batch) and relative to the whole buffer."""
+    log(f"weights beta={beta}")
+    rng = np.random.default_rng(int(beta * 1000) + 5)
+    K, N, T = 16, 6000, 2
+    m = Mirror(K, N, T, ())
+    m.insert(N, prio=(10.0 ** rng.uniform(-6, 6, (T, N))).astype(np.float32))
+    for B in (3000, 40):
+        m.sample(wl.uniform01(rng, (T, B)), beta=beta)
+    m.set_weight_norm("buffer")
+    for B in (3000, 40):
+        m.sample(wl.uniform01(rng, (T, B)), beta=beta)
+    m.compare_status()
