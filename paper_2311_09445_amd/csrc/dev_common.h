@@ -241,8 +241,8 @@ __device__ __forceinline__ uint32_t not_before_here(uint32_t x) {
 // be stale, which can only cause a redundant atomic, never a missed one (the value only grows).
 // `seen` is the value read when the kernel started (so the read overlaps the other loads).
 __device__ __forceinline__ uint32_t read_max_bits(const Geom& g, uint32_t t) {
-  // (a relaxed atomic load: a volatile one makes the wave wait for it on the spot; other workgroups raise the word meanwhile)
-  return __hip_atomic_load(reinterpret_cast<const uint32_t*>(&g.max_v[t]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // (not a volatile read: that makes the wave wait for it on the spot)
+  return read_word_with_the_loads(reinterpret_cast<const uint32_t*>(g.max_v) + t);
 }
 __device__ __forceinline__ void raise_max(const Geom& g, uint32_t t, uint32_t mx, uint32_t seen) {
   mx = wave_max_u32(mx);
