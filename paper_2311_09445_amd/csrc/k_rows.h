@@ -19,6 +19,20 @@ struct InFlight {
 };
 static uint32_t max_in_flight(uint32_t vec) { return vec >= 16 ? 2u : vec == 8 ? 4u : 8u; }
 
+// A field whose size and addresses are multiples of 4 bytes only (17 floats, say) still moves in 16-byte
+// pieces when it is long enough: pieces on 4-byte boundaries, which the target's memory instructions allow,
+// the last one ending with the field and overlapping the one before it (the shared bytes are written twice
+// with the same values).  A row of 68 bytes is then 5 moves instead of 17.
+struct __attribute__((packed, aligned(4))) Wide16 {
+  uint32_t x, y, z, w;
+};
+__host__ __device__ __forceinline__ bool moves_wide(uint32_t bytes, uint32_t vec) { return vec == 4 && bytes >= 32; }
+// elements a row of the field is moved in, and elements a lane keeps in flight
+__host__ __device__ __forceinline__ uint32_t row_elements(uint32_t bytes, uint32_t vec) {
+  return moves_wide(bytes, vec) ? (bytes + 15u) / 16u : bytes / vec;
+}
+static uint32_t field_in_flight(uint32_t bytes, uint32_t vec) { return moves_wide(bytes, vec) ? 2u : max_in_flight(vec); }
+
 // A lane's values for the elements of a sweep: a nested struct reached through compile-time paths only
 // (an array written in unrolled loops was moved to LDS or scratch by the compiler).
 template <typename T, int N>
@@ -128,6 +142,87 @@ __device__ __forceinline__ void move_rows(const FieldTable& ft, uint32_t f, uint
   if (bad) atomicOr(&status[t], 1u);
 }
 
+// The same for a field that moves wide (see Wide16): element e of the job is piece e % epr of row e / epr,
+// at byte min(16 piece, E - 16) of the field on both sides.  Kept apart from the mover above so that the
+// code of that one stays as it is.  Held as plain vectors (a packed type among the held values would keep
+// them out of registers).
+struct WideMove {
+  RowMove m;
+  uint32_t E;   // bytes of the field in a row
+};
+__device__ __forceinline__ uint32_t wide_offset(const WideMove& w, uint64_t e) {
+  const uint32_t off = 16u * (uint32_t)(e % w.m.epr);
+  return off + 16u <= w.E ? off : w.E - 16u;
+}
+__device__ __forceinline__ uint4 load_wide(const uint8_t* p) {
+  const Wide16 x = *reinterpret_cast<const Wide16*>(p);
+  return make_uint4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ void store_wide(uint8_t* p, const uint4& h) {
+  Wide16 x;
+  x.x = h.x;
+  x.y = h.y;
+  x.z = h.z;
+  x.w = h.w;
+  *reinterpret_cast<Wide16*>(p) = x;
+}
+template <bool GATHER, int K, int U>
+__device__ __forceinline__ void wide_load(const WideMove& w, uint64_t e0, Regs<uint32_t, U>& at, Regs<uint4, U>& v, bool& bad) {
+  if constexpr (K < U) {
+    bool live;
+    const uint64_t e = sweep_elem<K>(w.m, e0, live);
+    if constexpr (GATHER) {
+      const bool ok = reg<K>(at) < w.m.N;
+      bad |= !ok;
+      uint4 got = load_wide(w.m.col + (uint64_t)(ok ? reg<K>(at) : 0u) * w.m.RS + wide_offset(w, e));
+      if (!ok) got = make_uint4(0, 0, 0, 0);
+      reg<K>(v) = got;
+    } else {
+      reg<K>(v) = load_wide(w.m.io + (e / w.m.epr) * w.E + wide_offset(w, e));
+    }
+    wide_load<GATHER, K + 1, U>(w, e0, at, v, bad);
+  }
+}
+template <bool GATHER, int K, int U>
+__device__ __forceinline__ void wide_store(const WideMove& w, uint64_t e0, Regs<uint32_t, U>& at, Regs<uint4, U>& v) {
+  if constexpr (K < U) {
+    bool live;
+    const uint64_t e = sweep_elem<K>(w.m, e0, live);
+    if (live) {
+      if constexpr (GATHER) store_wide(w.m.io + (e / w.m.epr) * w.E + wide_offset(w, e), reg<K>(v));
+      else store_wide(w.m.col + (uint64_t)reg<K>(at) * w.m.RS + wide_offset(w, e), reg<K>(v));
+    }
+    wide_store<GATHER, K + 1, U>(w, e0, at, v);
+  }
+}
+template <bool GATHER>
+__device__ __forceinline__ void move_rows_wide(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
+                                               const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
+                                               uint32_t* status, uint32_t job_block, uint32_t job_blocks) {
+  constexpr int U = 2;
+  WideMove w;
+  RowMove& m = w.m;
+  w.E = ft.bytes[f];
+  m.RS = ft.row_stride;
+  m.epr = (w.E + 15u) / 16u;
+  m.total = (uint64_t)B * m.epr;
+  m.col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
+  m.io = ft.io[f] + (uint64_t)t * B * w.E;
+  m.idx = idx ? idx + (size_t)t * B : nullptr;
+  m.stride = (uint64_t)job_blocks * blockDim.x;
+  m.cursor = cursor;
+  m.N = N;
+  bool bad = false;
+  for (uint64_t e0 = (uint64_t)job_block * blockDim.x + threadIdx.x; e0 < m.total; e0 += U * m.stride) {
+    Regs<uint32_t, U> at;
+    Regs<uint4, U> v;
+    sweep_where<uint4, GATHER, 0, U>(m, e0, at);
+    wide_load<GATHER, 0, U>(w, e0, at, v, bad);
+    wide_store<GATHER, 0, U>(w, e0, at, v);
+  }
+  if (bad) atomicOr(&status[t], 1u);
+}
+
 // The field whose row job workgroup b of the job grid belongs to (kMaxFields: none).  The ranges lie back to
 // back, so it is the number of ranges that end at or before b; written without an early exit so that the
 // range ends are read together, not one after the other.
@@ -139,14 +234,24 @@ __device__ __forceinline__ uint32_t job_field(const JobRanges& jr, uint32_t b) {
 }
 
 // Moves the rows of one payload field; the workgroup is number job_block of job_blocks on that field.
-template <bool GATHER>
+// WIDE: the kernel was built with the 16-byte moves on 4-byte boundaries (see Wide16); the launchers pick
+// that build only when a field of the call moves that way, so that calls without one run the smaller code.
+template <bool GATHER, bool WIDE>
 __device__ __forceinline__ void rows_job(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
                                          const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
                                          uint32_t* status, uint32_t job_block, uint32_t job_blocks) {
   switch (ft.vec[f]) {
     case 16: move_rows<uint4, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
     case 8: move_rows<uint2, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
-    case 4: move_rows<uint32_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
+    case 4:
+      if constexpr (WIDE) {
+        if (moves_wide(ft.bytes[f], 4)) {
+          move_rows_wide<GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks);
+          break;
+        }
+      }
+      move_rows<uint32_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks);
+      break;
     case 2: move_rows<uint16_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
     default: move_rows<uint8_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
   }
@@ -239,6 +344,7 @@ __device__ __forceinline__ bool move_rows_one_workgroup(const FieldTable& ft, ui
 // asked for), then the claim phase of a priority update (if one is fused in), then one job per
 // payload field of the sampled rows.  The small jobs come first, so their latency hides behind the
 // row traffic.
+template <bool WIDE>
 __global__ void k_finish(FieldTable ft, JobRanges jr, Geom g, FinishArgs a) {
   const uint32_t t = blockIdx.y;
   const uint32_t b = blockIdx.x;
@@ -252,18 +358,18 @@ __global__ void k_finish(FieldTable ft, JobRanges jr, Geom g, FinishArgs a) {
   }
   const uint32_t f = job_field(jr, b);
   if (f < (uint32_t)kMaxFields)
-    rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+    rows_job<true, WIDE>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
 }
 
 // Stand-alone gather (GATHER) and insert scatter: one job per payload field.
-template <bool GATHER>
+template <bool GATHER, bool WIDE>
 __global__ void k_rows(FieldTable ft, JobRanges jr, uint32_t B, const uint32_t* __restrict__ idx, uint32_t cursor,
                        uint32_t N, uint32_t* status) {
   const uint32_t t = blockIdx.y;
   const uint32_t b = blockIdx.x;
   const uint32_t f = job_field(jr, b);
   if (f < (uint32_t)kMaxFields)
-    rows_job<GATHER>(ft, f, t, B, idx, cursor, N, status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+    rows_job<GATHER, WIDE>(ft, f, t, B, idx, cursor, N, status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
 }
 
 // Workgroups per job: weights, claim, then each field with a destination.  A field gets the workgroups one
@@ -281,8 +387,8 @@ static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block,
   jr.first[2] = at;
   for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f) {
     if (ft && f < ft->n_fields && ft->io[f]) {
-      const uint64_t elems = (uint64_t)rows * (ft->bytes[f] / ft->vec[f]);
-      const uint32_t most = max_in_flight(ft->vec[f]);
+      const uint64_t elems = (uint64_t)rows * row_elements(ft->bytes[f], ft->vec[f]);
+      const uint32_t most = field_in_flight(ft->bytes[f], ft->vec[f]);
       uint64_t n = 0;
       for (uint32_t per_lane = 1; per_lane <= most; per_lane *= 2) {
         n = (elems + (uint64_t)per_lane * block - 1) / ((uint64_t)per_lane * block);
@@ -296,13 +402,24 @@ static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block,
   return jr;
 }
 
+// true when a field of the call moves in 16-byte pieces on 4-byte boundaries
+static bool any_field_moves_wide(const FieldTable* ft) {
+  for (uint32_t f = 0; ft && f < ft->n_fields; ++f)
+    if (ft->io[f] && moves_wide(ft->bytes[f], ft->vec[f])) return true;
+  return false;
+}
+
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s) {
   const uint32_t block = tn.gather_block;
   const JobRanges jr = job_ranges(&ft, B, block, 0, 0, g.T);
   const uint32_t gx = jr.first[2 + kMaxFields];
   if (gx == 0) return hipSuccess;
-  PER_LAUNCH(KID_GATHER, k_rows<true>, dim3(gx, g.T), dim3(block), 0, s, ft, jr, B, idx, 0, g.N, g.status);
+  if (any_field_moves_wide(&ft)) {
+    PER_LAUNCH(KID_GATHER, (k_rows<true, true>), dim3(gx, g.T), dim3(block), 0, s, ft, jr, B, idx, 0, g.N, g.status);
+  } else {
+    PER_LAUNCH(KID_GATHER, (k_rows<true, false>), dim3(gx, g.T), dim3(block), 0, s, ft, jr, B, idx, 0, g.N, g.status);
+  }
   return hipGetLastError();
 }
 
@@ -313,7 +430,11 @@ static hipError_t launch_finish(const Geom& g, const Tuning& tn, const FieldTabl
   if (!a.w && !a.has_claim) return rows ? launch_gather(g, tn, ft, a.B, a.idx, s) : hipSuccess;
   const uint32_t block = tn.gather_block;
   const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, block, a.w ? a.B : 0u, a.has_claim ? a.claim.B : 0u, g.T);
-  PER_LAUNCH(KID_FINISH, k_finish, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), 0, s, ft, jr, g, a);
+  if (any_field_moves_wide(rows ? &ft : nullptr)) {
+    PER_LAUNCH(KID_FINISH, k_finish<true>, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), 0, s, ft, jr, g, a);
+  } else {
+    PER_LAUNCH(KID_FINISH, k_finish<false>, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), 0, s, ft, jr, g, a);
+  }
   return hipGetLastError();
 }
 
@@ -323,6 +444,10 @@ hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft,
   const JobRanges jr = job_ranges(&ft, n, block, 0, 0, g.T);
   const uint32_t gx = jr.first[2 + kMaxFields];
   if (gx == 0) return hipSuccess;
-  PER_LAUNCH(KID_SCATTER, k_rows<false>, dim3(gx, g.T), dim3(block), 0, s, ft, jr, n, nullptr, cursor, g.N, g.status);
+  if (any_field_moves_wide(&ft)) {
+    PER_LAUNCH(KID_SCATTER, (k_rows<false, true>), dim3(gx, g.T), dim3(block), 0, s, ft, jr, n, nullptr, cursor, g.N, g.status);
+  } else {
+    PER_LAUNCH(KID_SCATTER, (k_rows<false, false>), dim3(gx, g.T), dim3(block), 0, s, ft, jr, n, nullptr, cursor, g.N, g.status);
+  }
   return hipGetLastError();
 }

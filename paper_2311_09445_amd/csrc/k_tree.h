@@ -363,7 +363,7 @@ k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
 // Three such workgroups are resident per compute unit where the machine reserves 16 more scalar
 // registers per wave; a cap of 80 makes it four, measured slower: the jobs then slow each other down
 // in the memory system by more than the earlier start of the row jobs gives back.
-template <int LOGK, bool TRACK_MIN>
+template <int LOGK, bool TRACK_MIN, bool WIDE>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_num_sgpr(96)))
 k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldTable ft, JobRanges jr, FinishArgs a) {
   const uint32_t t = blockIdx.y;
@@ -383,7 +383,7 @@ k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldT
   }
   const uint32_t f = job_field(jr, b);
   if (f < (uint32_t)kMaxFields)
-    rows_job<true>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+    rows_job<true, WIDE>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
   PER_MARK(3);
   PER_FLUSH();
 }
@@ -491,13 +491,16 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const Cl
   const uint32_t tree_blocks = g.n[sl.hb];
   const uint32_t chain = lazy_top_height(g, tn) ? 0u : 1u;
   const dim3 grid(tree_blocks + jr.first[2 + kMaxFields], g.T);
+  const bool wide = any_field_moves_wide(rows ? &ft : nullptr);
+#define PER_TREE_FINISH(TM, WD)                                                                                        \
+  PER_LAUNCH(KID_TREE_FINISH, (k_tree_finish<LOGK, TM, WD>), grid, dim3(tblock), tree_lds_bytes<LOGK>(sl), s, g, sl, \
+             chain, tree_blocks, ft, jr, a)
   if (c.track_min) {
-    PER_LAUNCH(KID_TREE_FINISH, (k_tree_finish<LOGK, true>), grid, dim3(tblock), tree_lds_bytes<LOGK>(sl), s, g, sl, chain,
-               tree_blocks, ft, jr, a);
+    if (wide) { PER_TREE_FINISH(true, true); } else { PER_TREE_FINISH(true, false); }
   } else {
-    PER_LAUNCH(KID_TREE_FINISH, (k_tree_finish<LOGK, false>), grid, dim3(tblock), tree_lds_bytes<LOGK>(sl), s, g, sl, chain,
-               tree_blocks, ft, jr, a);
+    if (wide) { PER_TREE_FINISH(false, true); } else { PER_TREE_FINISH(false, false); }
   }
+#undef PER_TREE_FINISH
   return hipGetLastError();
 }
 
