@@ -1234,3 +1234,59 @@ def test_weights_over_a_wide_range_of_ratios_and_exponents(beta):
     for B in (3000, 40):
         m.sample(wl.uniform01(rng, (T, B)), beta=beta)
     m.compare_status()
+
+
+@pytest.mark.parametrize("fb,shift", [((36, 100, 32), 4), ((68, 24, 4, 68, 1), 0), ((128,), 4), ((32, 20), 8), ((44,), 12)])
+def test_rows_in_16_byte_pieces_on_4_byte_boundaries(fb, shift):
+    """Fields whose size or address is a multiple of 4 bytes only are moved in 16-byte pieces, the last piece of
+    a row overlapping the one before it.  Dense arrays that start `shift` bytes into their allocation, sizes just
+    above and below the threshold, large and small batches (the scatter and gather kernels, the fused calls and
+    the one-workgroup insert), every byte compared with the oracle's rows."""
+    log(f"wide rows fb={fb} shift={shift}")
+    rng = np.random.default_rng(sum(fb) + shift)
+    K, N, T = 16, 20000, 2
+    gpu = PrioritizedReplay(K, N, T, fb)
+    cpu = MultiOracle(T, K, N, fb, 1.0)
+
+    def shifted(shape_bytes):   # a uint8 device array of that many bytes starting `shift` bytes into its allocation
+        return torch.empty(shape_bytes + shift, dtype=torch.uint8, device="cuda")[shift:]
+
+    def insert(n):
+        rows = [rng.integers(0, 256, (T, n, b), dtype=np.uint8) for b in fb]
+        src = []
+        for r in rows:
+            d = shifted(r.size)
+            d.copy_(torch.from_numpy(r.reshape(-1)).cuda())
+            src.append(d)
+        prio = (rng.random((T, n)) + 0.1).astype(np.float32)
+        gpu.insert(n, src, dev(prio))
+        cpu.insert(n, rows, prio)
+
+    def check(idx):
+        B = idx.shape[1]
+        out = [shifted(T * B * b) for b in fb]
+        for o in out:
+            o.fill_(0xEE)
+        gpu.gather(idx_to_dev(idx), out)
+        want = cpu.gather(idx)
+        for f, b in enumerate(fb):
+            assert np.array_equal(out[f].cpu().numpy().reshape(T, B, b), want[f]), f"field {f}"
+
+    insert(9000)                 # the scatter kernel
+    insert(7)                    # the one-workgroup insert
+    insert(N - 9007 + 300)       # wraps the ring
+    check(rng.integers(0, N, (T, 5000)).astype(np.uint32))
+    check(rng.integers(0, N, (T, 3)).astype(np.uint32))
+    bad = rng.integers(0, N, (T, 70)).astype(np.uint32)
+    bad[:, 5] = N + 1            # an index out of range gives a row of zeros
+    check(bad)
+    # fused sampling + gather into shifted arrays
+    B = 3000
+    u = wl.uniform01(rng, (T, B))
+    out = [shifted(T * B * b) for b in fb]
+    gi, _, _ = gpu.sample(dev(u), 0.4, rows_out=out)
+    ci, _, _ = cpu.sample(u, 0.4, True)
+    assert np.array_equal(idx_to_host(gi), ci)
+    want = cpu.gather(ci)
+    for f, b in enumerate(fb):
+        assert np.array_equal(out[f].cpu().numpy().reshape(T, B, b), want[f]), f"fused field {f}"
