@@ -16,8 +16,8 @@
  *    except per_status.  Calls on one buffer must be issued in order on one
  *    stream (or be ordered by the caller with events).
  *  - The library never allocates device memory: the caller provides one arena
- *    (per_arena_bytes tells how large) that holds tree levels, payload columns
- *    and all scratch.
+ *    (per_arena_bytes tells how large) that holds the tree levels, the payload
+ *    (stored row-major: the fields of a row side by side) and all scratch.
  *  - Arrays carry a leading tree dimension: "[T][B]" means T*B contiguous
  *    elements, tree-major.
  *  - Tree values are fp32.  The tree stores the value it is given (the caller
@@ -28,11 +28,15 @@
  *    the host, in which case no work was enqueued.  Conditions only the device
  *    can see set sticky bits (PER_FLAG_*) read by per_status.
  *  - A batch of size 0 is valid and enqueues nothing.
- *  - The ring cursor, the filled size and a few similar counters (which of two buffers of partial
- *    minima a sampling call uses, the call number of the generator of per_set_rng) are kept on the host (they are pure functions of the call sequence) and enter the
- *    kernels as arguments.  Calls may therefore be captured into a HIP graph, but the graph then
- *    stands for exactly the captured calls: launch it once, on the buffer state it was captured
- *    on, and capture again for the next stretch of calls.
+ *  - The ring cursor, the filled size and the call number of the generator of per_set_rng are kept
+ *    on the host (they are pure functions of the call sequence) and enter the kernels as arguments.
+ *    Calls may be captured into a HIP graph.  A captured insertion, or a captured sampling call that
+ *    draws its own uniforms, stands for exactly the captured call: launch such a graph once, on the
+ *    buffer state it was captured on.  Sampling with given uniforms, gather and the update forms carry
+ *    no host state: a graph of them may be replayed any number of times with the inputs refilled in
+ *    place, whatever ran on the buffer before the capture (what the host has noted about the device is
+ *    not relied on while a stream is being captured).  Call per_note_replay after a replay and before
+ *    the next call made outside the graph.
  */
 #ifndef PER_H_
 #define PER_H_
@@ -65,8 +69,9 @@ typedef struct per_config {
   uint32_t fanout;                      /* K in {2,4,8,16,32,64} (the paper's "fanout", Listing 1)    */
   uint64_t capacity;                    /* N leaves per tree, 1 <= N <= 2^31 (the paper's "size")     */
   uint32_t n_trees;                     /* T >= 1 independent buffers                                 */
-  uint32_t n_fields;                    /* payload columns per row, 0..PER_MAX_FIELDS, stored SoA     */
-  uint32_t field_bytes[PER_MAX_FIELDS]; /* bytes per row of each column, e.g. {68,24,4,68,1}          */
+  uint32_t n_fields;                    /* payload fields per row, 0..PER_MAX_FIELDS; the caller's    */
+                                        /* arrays are dense per field, the stored rows are row-major  */
+  uint32_t field_bytes[PER_MAX_FIELDS]; /* bytes per row of each field, e.g. {68,24,4,68,1}           */
   float    init_max_priority;           /* value given to the first inserted rows; finite and > 0     */
 } per_config;
 
@@ -145,6 +150,19 @@ int per_sample_gather_update(per_t* p, uint32_t B, float beta, const float* d_u,
                              float* d_out_weight, float* d_out_prio, void* const* d_field_dst,
                              uint32_t upd_B, const uint32_t* d_upd_idx, const float* d_upd_prio,
                              void* stream);
+
+/* One whole iteration of the loop of Listing 2 (Section IV-D) in one call: draw a batch, read its rows, and
+ * write back the priorities the Learner derived for that very batch.  Sampling, weights and rows as
+ * per_sample_gather; then, as per_update, element j of the update sets the leaf drawn by sample
+ * d_upd_pos[t][j] of this call to d_upd_prio[t][j] (d_upd_pos NULL: the leaf drawn by sample j), i.e. it is
+ *   per_sample_gather(...);  upd_idx[t][j] = d_out_idx[t][d_upd_pos[t][j]];  per_update(B, upd_idx, d_upd_prio)
+ * with the same results (last writer in order of j where several elements meet on a leaf).  A position
+ * >= B makes its element invalid (PER_FLAG_BAD_INDEX), as does a sample that found nothing
+ * (PER_FLAG_ZERO_TOTAL).  d_upd_prio and d_upd_pos are [T][B] and must not overlap the outputs
+ * (PER_EINVAL).  d_field_dst and d_out_weight may be NULL. */
+int per_step(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
+             float* d_out_prio, void* const* d_field_dst, const float* d_upd_prio, const uint32_t* d_upd_pos,
+             void* stream);
 
 /* Priority update (Section V-A), in the set-and-re-sum form: every valid element sets its
  * leaf; when an index occurs more than once the element latest in the batch wins;
@@ -247,6 +265,14 @@ typedef struct per_request {
 int per_run_requests(per_t* p, uint32_t n_requests, const per_request* h_requests, const per_request* d_requests,
                      void* stream);
 
+/* Full bottom-up rebuild: every stored node above the leaves is recomputed from its children, level by
+ * level, so that afterwards "a parent node stores the sum of priorities of its children" (Section V-A)
+ * holds exactly (balanced pairwise fp32 sums), whatever was done to the tree before.  Needed after
+ * per_update_delta, whose float atomics leave the upper levels equal to those sums only up to rounding;
+ * also usable after the leaves of a restored arena were edited.  Streaming and coalesced: reads every
+ * level once. */
+int per_rebuild(per_t* p, void* stream);
+
 /* Priority retrieval (Section V-A): d_out[t][i] = leaf d_idx[t][i]. */
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream);
 
@@ -261,7 +287,8 @@ int per_total(per_t* p, float* d_out, void* stream);
 /* d_out[t] = running maximum priority of tree t. */
 int per_max_priority(per_t* p, float* d_out, void* stream);
 
-/* Synchronises `stream`, then ORs the sticky device flags of all trees into *flags. */
+/* Synchronises `stream` (the one the buffer's calls were issued on), then ORs the sticky device flags of all
+ * trees into *flags.  The only call that waits for the device. */
 int per_status(per_t* p, void* stream, uint32_t* flags);
 int per_clear_status(per_t* p, void* stream);
 

@@ -92,7 +92,10 @@ __device__ __forceinline__ void claim_job(const Geom& g, uint32_t t, const Claim
         if (c.from_td)   // priority of a temporal-difference error; a non-finite error stays non-finite and is rejected
           v = (float)pow(fabs((double)v) + c.td_eps, c.td_alpha);
       }
-      claim_element(g, t, c.size, c.group_mode, first, j, c.idx[(size_t)t * c.B + j], v, mx, flags);
+      uint32_t at = j;
+      if (c.pos) at = c.pos[(size_t)t * c.B + j];
+      const uint32_t i = at < c.B ? c.idx[(size_t)t * c.B + at] : 0xFFFFFFFFu;
+      claim_element(g, t, c.size, c.group_mode, first, j, i, v, mx, flags);
     }
   }
   raise_max(g, t, mx, max_seen);

@@ -185,12 +185,25 @@ hipError_t launch_insert_leaves(const Geom& g, const Tuning& tn, uint32_t n, uin
 
 // True when an insert of n rows is small enough for k_insert_small: few bytes to move and few
 // nodes per height for one workgroup.
+static uint32_t tree_pass_height(const Geom& g);
 bool insert_fits_one_workgroup(const Geom& g, const FieldTable* ft, uint32_t n) {
   uint64_t bytes = 0;
   if (ft)
     for (uint32_t f = 0; f < ft->n_fields; ++f)
       if (ft->io[f]) bytes += (uint64_t)n * ft->bytes[f];
-  return n <= kInsertSmallRows && bytes <= 256 * 1024;
+  if (n > kInsertSmallRows || bytes > 256 * 1024) return false;
+  // the staged child groups must fit the dynamic LDS a kernel gets without asking for more (64 KB, of which
+  // the kernel's tables take about 2 KB): an upper bound over every ring position, with the heights an
+  // update may have left stale taken whole
+  const uint32_t hb = tree_pass_height(g);
+  const bool lazy = hb < g.H && g.n[hb] <= kLazyTopNodes;
+  uint64_t floats = 0;
+  for (uint32_t h = 1; h <= g.H; ++h) {
+    uint64_t nodes = (((uint64_t)n - 1) >> (h * g.logK < 63 ? h * g.logK : 63)) + 3;   // two ranges, each may straddle a node
+    if (nodes > g.n[h] || (lazy && h > hb)) nodes = g.n[h];
+    floats += nodes * g.K;
+  }
+  return floats * 4 <= 60 * 1024;
 }
 
 template <int LOGK>

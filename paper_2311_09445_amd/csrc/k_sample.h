@@ -176,7 +176,22 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
     }
   }
 
+  // The first workgroup of each tree puts the heights rebuilt above back into memory (also when nothing can be
+  // sampled: the host has noted that this kernel makes them current).
+  auto store_rebuilt_top = [&]() {
+    if (stale >= 0 && bx == 0) {
+#pragma unroll
+      for (int i = 0; i < kTopSlots; ++i)
+        if (i < stale) {
+          float* dst = g.level[H - 1 - (uint32_t)i] + (size_t)t * g.stride[H - 1 - (uint32_t)i];
+          for (uint32_t j = threadIdx.x; j < tc.nreal[i]; j += blockDim.x) dst[j] = lds[off[i] + j];
+        }
+      if (threadIdx.x == 0) g.root[(size_t)t * g.root_stride] = total;
+    }
+  };
+
   if (!(total > 0.0f)) {   // nothing can be sampled from this tree (uniform over the block)
+    store_rebuilt_top();
     if (active) {
       out_idx[o] = 0xFFFFFFFFu;
       if (out_prio) out_prio[o] = 0.0f;
@@ -235,16 +250,8 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
     if (out_prio) out_prio[o] = val;
   }
   // Stores come last on purpose: on this hardware a wait for loaded data also waits for every
-  // earlier store of the wave.  The first workgroup of each tree puts the rebuilt heights back.
-  if (stale >= 0 && bx == 0) {
-#pragma unroll
-    for (int i = 0; i < kTopSlots; ++i)
-      if (i < stale) {
-        float* dst = g.level[H - 1 - (uint32_t)i] + (size_t)t * g.stride[H - 1 - (uint32_t)i];
-        for (uint32_t j = threadIdx.x; j < tc.nreal[i]; j += blockDim.x) dst[j] = lds[off[i] + j];
-      }
-    if (threadIdx.x == 0) g.root[(size_t)t * g.root_stride] = total;
-  }
+  // earlier store of the wave.
+  store_rebuilt_top();
   PER_MARK(12);
   PER_FLUSH();
   if (out_w) {
@@ -385,11 +392,8 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
       if (e != hipSuccess) return e;
     }
   }
-  if (bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be requested per kernel
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sample<LOGK>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e != hipSuccess) return e;
-  }
+  e = grant_lds<&k_sample<LOGK>>(tn, bytes);
+  if (e != hipSuccess) return e;
   if (!claim) claim_mode = CLAIM_NONE;
   const bool claim_here = claim_mode == CLAIM_INLINE || claim_mode == CLAIM_BLOCKS;
   uint32_t claim_blocks = 0;

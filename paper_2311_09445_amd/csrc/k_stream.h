@@ -381,11 +381,8 @@ static hipError_t launch_run_steps_k(const Geom& g, const Tuning& tn, StreamArgs
   const uint32_t floats = stream_tree_floats(g, ka.a.off);
   if (!floats) return hipErrorInvalidValue;
   const size_t bytes = ((size_t)floats + 1024) * 4;   // the tree and the sampled indices of one step
-  if (bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be requested per kernel
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_run_steps<LOGK>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e != hipSuccess) return e;
-  }
+  hipError_t e = grant_lds<&k_run_steps<LOGK>>(tn, bytes);
+  if (e != hipSuccess) return e;
   // always the largest workgroup, also for small batches: measured faster than a workgroup of the batch's
   // size (the tree copy and the row movers use all lanes)
   PER_LAUNCH(KID_RUN_STEPS, k_run_steps<LOGK>, dim3(g.T), dim3(1024), bytes, s, ka);
@@ -406,11 +403,8 @@ static hipError_t launch_run_requests_k(const Geom& g, const Tuning& tn, const Q
   const uint32_t floats = stream_tree_floats(g, ka.a.off);
   if (!floats) return hipErrorInvalidValue;
   const size_t bytes = ((size_t)floats + 1024) * 4;   // the tree and the indices of the latest sampling request
-  if (bytes > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_run_requests<LOGK>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e != hipSuccess) return e;
-  }
+  hipError_t e = grant_lds<&k_run_requests<LOGK>>(tn, bytes);
+  if (e != hipSuccess) return e;
   PER_LAUNCH(KID_RUN_REQUESTS, k_run_requests<LOGK>, dim3(g.T), dim3(1024), bytes, s, ka);
   return hipGetLastError();
 }

@@ -38,7 +38,6 @@ constexpr uint32_t kDirtyListCap = 2048;
 // height-1 nodes (H <= 1 + ceil(log_K 2048)), else the lowest height whose subtrees hold 64 of them.
 template <int LOGK>
 constexpr int kMaxPassHeight = LOGK == 1 ? 13 : LOGK == 2 ? 7 : LOGK == 3 ? 5 : LOGK <= 5 ? 4 : 3;
-constexpr uint32_t kLazyTopNodes = 4096;
 
 // The work of workgroup b of tree t (b = its subtree's root at height hb).  TRACK_MIN: also renew min1
 // (smallest positive leaf) of every rebuilt height-1 node; a compile-time choice, because even as a

@@ -175,6 +175,31 @@ hipError_t ensure_top(per_t* p, hipStream_t s) {
   return e;
 }
 
+// A call made while its stream is being captured into a HIP graph does not run now and may run many times
+// later, in between other work on the buffer.  What the host has noted about the device (are the topmost
+// heights current, is the companion minimum current) therefore holds neither for the captured kernels nor
+// after the call: both are taken as "not current" on entry and left so on exit.  Rebuilding heights that
+// are current is harmless, so a captured call is correct on every replay whatever ran before it.
+bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  return hipStreamIsCapturing(s, &st) == hipSuccess && st == hipStreamCaptureStatusActive;
+}
+void forget_device_notes(per_t* p) {
+  const uint32_t hb = lazy_top_height(p->g, p->tn);
+  if (hb) p->stale_hb = hb;
+  p->min_stale = true;
+}
+struct CaptureGuard {
+  per_t* p;
+  bool on;
+  CaptureGuard(per_t* p_, hipStream_t s) : p(p_), on(p_ && stream_is_capturing(s)) {
+    if (on) forget_device_notes(p);
+  }
+  ~CaptureGuard() {
+    if (on) forget_device_notes(p);
+  }
+};
+
 }  // namespace
 
 extern "C" {
@@ -255,6 +280,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->weight_norm = PER_NORM_BATCH;
   p->min_stale = true;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
+  p->tn.device = p->device;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   // zero everything (tree levels, stamps and payload), then the scalars
@@ -280,6 +306,7 @@ static int insert_impl(per_t* p, uint32_t n, const void* const* d_field_src, con
   if (n == 0) return PER_OK;
   if (!d_protect) n_protect = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
   const uint64_t N = p->cfg.capacity;
   const uint32_t cursor = (uint32_t)p->cursor;
   FieldTable ft;
@@ -290,10 +317,11 @@ static int insert_impl(per_t* p, uint32_t n, const void* const* d_field_src, con
     // one kernel: rows, leaves, ancestors, and the heights an update may have left stale
     hipError_t e1 = launch_insert_small(p->g, p->tn, has_rows ? &ft : nullptr, n, cursor, d_prio, d_out_idx, p->stale_hb,
                                         n_protect ? d_protect : nullptr, n_protect, tracks_min(p), s);
-    if (e1 == hipSuccess) p->stale_hb = 0;
+    if (e1 != hipSuccess) return PER_EHIP;   // nothing was enqueued: the mirrors stay
+    p->stale_hb = 0;
     p->cursor = (p->cursor + n) % N;
     p->size = p->size + n > N ? N : p->size + n;
-    return hip_rc(e1);
+    return PER_OK;
   }
   p->min_stale = true;   // (the kernels of a large insert do not renew min1)
   hipError_t e = ensure_top(p, s);
@@ -361,7 +389,7 @@ static bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
 
 static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
                        float* d_out_prio, void* const* d_field_dst, uint32_t upd_B, const uint32_t* d_upd_idx,
-                       const float* d_upd_prio, void* stream) {
+                       const float* d_upd_prio, void* stream, const uint32_t* d_upd_pos = nullptr) {
   if (!p) return PER_EINVAL;
   if (B == 0) return PER_OK;
   if ((!d_u && !p->rng_on) || !d_out_idx || misaligned(d_u, 4) || misaligned(d_out_idx, 4) ||
@@ -371,6 +399,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
   if ((uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
   if (p->size == 0) return PER_EEMPTY;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
   FieldTable ft;
   const bool fused = d_field_dst && fill_fields(p, d_field_dst, &ft);
   uint32_t weight_mode = 0;
@@ -383,6 +412,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
     claim.B = upd_B;
     claim.size = (uint32_t)p->size;
     claim.idx = d_upd_idx;
+    claim.pos = d_upd_pos;
     claim.prio = d_upd_prio;
     int rc = prepare_claim(p, upd_B, s, &claim);
     if (rc != PER_OK) return rc;
@@ -397,7 +427,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
       idx_apart = idx_apart && !ranges_overlap(d_upd_idx, n_upd, o, n_out);
     }
     claim_mode = CLAIM_FINISH;
-    if (p->tn.claim_in_sample && prio_apart) {
+    if (p->tn.claim_in_sample && prio_apart && !d_upd_pos) {   // (through a position map an element needs another lane's sample)
       if (d_upd_idx == d_out_idx && upd_B == B) claim_mode = CLAIM_INLINE;
       else if (idx_apart) claim_mode = CLAIM_BLOCKS;
     }
@@ -443,6 +473,20 @@ int per_sample_gather_update(per_t* p, uint32_t B, float beta, const float* d_u,
                      stream);
 }
 
+int per_step(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
+             float* d_out_prio, void* const* d_field_dst, const float* d_upd_prio, const uint32_t* d_upd_pos,
+             void* stream) {
+  if (!p) return PER_EINVAL;
+  if (B == 0) return PER_OK;
+  if (!d_upd_prio || misaligned(d_upd_prio, 4) || misaligned(d_upd_pos, 4)) return PER_EINVAL;
+  const size_t n = (size_t)p->g.T * B * 4;
+  const void* outs[3] = {d_out_idx, d_out_weight, d_out_prio};
+  for (const void* o : outs)   // the update's inputs are read after (and while) the outputs are written
+    if (ranges_overlap(d_upd_prio, n, o, n) || ranges_overlap(d_upd_pos, n, o, n)) return PER_EINVAL;
+  return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, B, d_out_idx, d_upd_prio, stream,
+                     d_upd_pos);
+}
+
 int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field_dst, void* stream) {
   if (!p) return PER_EINVAL;
   if (B == 0) return PER_OK;
@@ -456,6 +500,7 @@ int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio,
   int rc = check_update_args(p, B, d_idx, d_prio);
   if (rc != PER_OK || B == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
   ClaimArgs claim{};
   claim.B = B;
   claim.size = (uint32_t)p->size;
@@ -475,6 +520,7 @@ int per_update_td(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_td
   if (rc != PER_OK || B == 0) return rc;
   if (!(eps >= 0.0) || !isfinite(eps) || !(alpha >= 0.0) || !isfinite(alpha)) return PER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
   ClaimArgs claim{};
   claim.B = B;
   claim.size = (uint32_t)p->size;
@@ -495,6 +541,7 @@ int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d
   int rc = check_update_args(p, B, d_idx, d_delta);
   if (rc != PER_OK || B == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
   p->min_stale = true;               // (changes added by atomics: min1 cannot follow them)
   hipError_t e = ensure_top(p, s);   // changes are added to whole nodes: the top heights must be current
   if (e == hipSuccess) e = launch_update_delta(p->g, p->tn, B, (uint32_t)p->size, d_idx, d_delta, s);
@@ -515,6 +562,7 @@ int per_run_steps(per_t* p, uint32_t n_steps, uint32_t n_insert, uint32_t B, con
   if (io->d_upd_idx && !io->d_upd_prio) return PER_EINVAL;
   if (p->size == 0 && n_insert == 0) return PER_EEMPTY;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
   StreamArgs a{};
   a.n_steps = n_steps;
   a.n_insert = n_insert;
@@ -578,6 +626,7 @@ int per_run_requests(per_t* p, uint32_t n_requests, const per_request* h_request
     }
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
   a.n_requests = n_requests;
   a.buffer_norm = p->weight_norm == PER_NORM_BUFFER ? 1u : 0u;
   p->min_stale = true;   // (as per_run_steps)
@@ -589,6 +638,17 @@ int per_run_requests(per_t* p, uint32_t n_requests, const per_request* h_request
   p->cursor = cursor;
   p->size = size;
   return hip_rc(e);
+}
+
+int per_rebuild(per_t* p, void* stream) {
+  if (!p) return PER_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
+  // all leaves count as touched: every height is recomputed in full, bottom-up
+  hipError_t e = launch_resum_ranges(p->g, p->tn, Range2{0, p->g.N, 0, 0}, s);
+  if (e != hipSuccess) return PER_EHIP;
+  p->stale_hb = 0;
+  return PER_OK;
 }
 
 int per_get_priority(per_t* p, uint32_t n, const uint32_t* d_idx, float* d_out, void* stream) {
@@ -604,6 +664,7 @@ int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint6
   if (count) *count = p->g.n[height];
   if (!d_out) return PER_OK;
   if (misaligned(d_out, 4)) return PER_EINVAL;
+  CaptureGuard capture(p, static_cast<hipStream_t>(stream));
   if (p->stale_hb && height > p->stale_hb && ensure_top(p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return PER_EHIP;
   const float* src = p->g.level[height] + (size_t)tree * p->g.stride[height];
@@ -613,6 +674,7 @@ int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint6
 
 int per_total(per_t* p, float* d_out, void* stream) {
   if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
+  CaptureGuard capture(p, static_cast<hipStream_t>(stream));
   if (ensure_top(p, static_cast<hipStream_t>(stream)) != hipSuccess) return PER_EHIP;
   return hip_rc(launch_read_scalars(p->g, 0, 0, d_out, static_cast<hipStream_t>(stream)));
 }
@@ -664,6 +726,7 @@ int per_set_weight_norm(per_t* p, int mode) {
 int per_min_priority(per_t* p, float* d_out, void* stream) {
   if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
   uint32_t mode = 0;
   if (reduce_min(p, s, &mode) != hipSuccess) return PER_EHIP;
   return hip_rc(launch_read_scalars(p->g, 2, mode, d_out, s));

@@ -74,6 +74,10 @@ struct FieldTable {
 // its stamps fit; the tree pass of a batch that ends beyond it clears all entries and restarts the
 // counter (about every 500 steps of the headline workload).
 constexpr uint32_t kGroupStampTurn = 1u << 25;
+
+// An update may leave the heights above its tree pass's workgroup roots to their next reader while that
+// height has at most this many nodes.
+constexpr uint32_t kLazyTopNodes = 4096;
 constexpr uint32_t kGroupClaimMaxBatch = kGroupStampTurn;
 
 // Claim phase of a priority update (first half of per_update).
@@ -82,6 +86,8 @@ struct ClaimArgs {
   uint32_t group_mode;     // the batch claims through the group entries (else leaf by leaf)
   uint32_t track_min;      // the tree pass also renews min1 of the height-1 nodes it rebuilds
   const uint32_t* idx;     // [T][B]
+  const uint32_t* pos;     // null, or [T][B] positions: element j targets idx[pos[j]] (the leaf drawn by sample pos[j] of the
+                           // sampling call the update is fused with); a position >= B makes the element invalid
   const float* prio;       // [T][B] tree values, or temporal-difference errors when from_td is set
   uint32_t from_td;        // value = (|prio| + td_eps)^td_alpha, fp64, rounded once
   double td_eps, td_alpha;
@@ -178,6 +184,7 @@ struct Tuning {
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   uint32_t group_claim;       // update batches claim through the group entries whenever they are short enough
   Profiler* prof;
+  int device;                 // the device the buffer lives on
 };
 
 // Launchers (per_kernels.hip).  All enqueue on `s` and return hipGetLastError().

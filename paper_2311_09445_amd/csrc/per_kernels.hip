@@ -12,6 +12,7 @@
 
 #include <hip/hip_ext.h>
 
+#include <atomic>
 #include <type_traits>
 
 namespace per {
@@ -71,6 +72,22 @@ bool Profiler::begin(int kid, hipEvent_t* start, hipEvent_t* stop) {
     else                                                                                           \
       KERNEL<<<GRID, BLOCK, LDS, STREAM>>>(__VA_ARGS__);                                           \
   } while (0)
+
+// Dynamic LDS beyond the default limit of 64 KB has to be granted per kernel and device by a host call.  The
+// largest grant made so far is remembered per kernel (process-wide: the grant belongs to the kernel, not to a
+// buffer), so the call is made when a kernel first needs a size, not once per launch.
+constexpr int kMaxDevices = 64;
+template <auto Kern>
+static hipError_t grant_lds(const Tuning& tn, size_t bytes) {
+  static std::atomic<uint32_t> granted[kMaxDevices];
+  if (bytes <= 64 * 1024) return hipSuccess;
+  const bool tracked = tn.device >= 0 && tn.device < kMaxDevices;
+  if (tracked && granted[tn.device].load(std::memory_order_relaxed) >= bytes) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)bytes);
+  if (e == hipSuccess && tracked) granted[tn.device].store((uint32_t)bytes, std::memory_order_relaxed);
+  return e;
+}
 
 #include "dev_trace.h"
 #include "dev_common.h"

@@ -20,8 +20,8 @@ FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 
 EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_insert_protected", "per_sample", "per_sample_gather",
-    "per_sample_gather_update", "per_gather",
-    "per_update", "per_update_td", "per_update_delta", "per_set_rng", "per_rng_calls", "per_run_steps",
+    "per_sample_gather_update", "per_step", "per_gather",
+    "per_update", "per_update_td", "per_update_delta", "per_rebuild", "per_set_rng", "per_rng_calls", "per_run_steps",
     "per_run_steps_fits", "per_run_requests", "per_set_weight_norm", "per_min_priority", "per_note_replay", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
@@ -104,9 +104,11 @@ def _lib():
         "per_sample": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp]),
         "per_sample_gather": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, vp]),
         "per_sample_gather_update": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, u32, vp, vp, vp]),
+        "per_step": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, vp, vp, vp]),
         "per_gather": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update_delta": (C.c_int, [vp, u32, vp, vp, vp]),
+        "per_rebuild": (C.c_int, [vp, vp]),
         "per_set_rng": (C.c_int, [vp, C.c_uint64, C.c_uint64]),
         "per_rng_calls": (C.c_uint64, [vp]),
         "per_run_steps": (C.c_int, [vp, u32, u32, u32, C.POINTER(PerStreamIO), vp]),
@@ -289,6 +291,35 @@ class PrioritizedReplay:
         self._check(rc, "per_sample")
         return out_idx, (out_weight if want_weights else None), (out_prio if want_prio else None)
 
+    def step(self, u, beta, upd_prio, upd_pos=None, want_weights: bool = True, want_prio: bool = True,
+             out_idx=None, out_weight=None, out_prio=None, rows_out=None, B=None):
+        """per_step: sample, gather and update the batch just drawn; element j of ``upd_prio`` goes to the leaf
+        drawn by sample ``upd_pos[j]`` (``None``: sample j).  Returns (idx, weights or None, prio or None)."""
+        torch = self._torch
+        if u is None:
+            if B is None:
+                raise ValueError("without uniforms the batch size B must be given")
+        else:
+            B = u.numel() // self.T
+        shape = (self.T, B)
+        if upd_prio.numel() != self.T * B or (upd_pos is not None and upd_pos.numel() != self.T * B):
+            raise ValueError("upd_prio and upd_pos must hold T*B values")
+        if out_idx is None:
+            out_idx = torch.empty(shape, dtype=torch.int32, device=self.device)
+        if want_weights and out_weight is None:
+            out_weight = torch.empty(shape, dtype=torch.float32, device=self.device)
+        if want_prio and out_prio is None:
+            out_prio = torch.empty(shape, dtype=torch.float32, device=self.device)
+        dst = None
+        if rows_out is not None:
+            _keep, dst = self._ptr_array(rows_out, B)
+        rc = self.lib.per_step(self._h, B, float(beta), _dptr(u, torch.float32), _dptr(out_idx, torch.int32),
+                               _dptr(out_weight, torch.float32) if want_weights else None,
+                               _dptr(out_prio, torch.float32) if want_prio else None, dst,
+                               _dptr(upd_prio, torch.float32), _dptr(upd_pos, torch.int32), self._stream())
+        self._check(rc, "per_step")
+        return out_idx, (out_weight if want_weights else None), (out_prio if want_prio else None)
+
     def run_steps_fits(self) -> bool:
         return bool(self.lib.per_run_steps_fits(self._h))
 
@@ -453,6 +484,10 @@ class PrioritizedReplay:
             raise ValueError("idx and delta must have the same number of elements")
         rc = self.lib.per_update_delta(self._h, B, _dptr(idx, torch.int32), _dptr(delta, torch.float32), self._stream())
         self._check(rc, "per_update_delta")
+
+    def rebuild(self):
+        """Recomputes every node above the leaves from its children (full bottom-up rebuild)."""
+        self._check(self.lib.per_rebuild(self._h, self._stream()), "per_rebuild")
 
     def get_priority(self, idx, out=None):
         torch = self._torch

@@ -175,6 +175,17 @@ def apply_dup_map(idx: np.ndarray, inp: dict) -> np.ndarray:
     return out
 
 
+def dup_positions(inp: dict, T: int, B: int) -> np.ndarray | None:
+    """The step's duplicate map as a position map [T, B]: update element j targets the index sampled at position
+    pos[j] (pos[j] = j except pos[dup_dst] = dup_src); None when the step has no duplicate map."""
+    if "dup_dst" not in inp:
+        return None
+    pos = np.tile(np.arange(B, dtype=np.uint32), (T, 1))
+    for t in range(T):
+        pos[t, inp["dup_dst"][t]] = inp["dup_src"][t].astype(np.uint32)
+    return pos
+
+
 # ----------------------------------------------------------------------------
 # Row payloads: every byte is a hash of (tree, insert counter, field, offset),
 # so a misplaced or stale byte anywhere in storage shows up in a comparison.

@@ -144,6 +144,30 @@ class Mirror:
         self.cpu.update(np.ascontiguousarray(upd_idx, dtype=np.uint32), upd_prio)
         return gi, ci
 
+    def step_call(self, u, beta, want_weights, upd_prio, pos=None):
+        """per_step against oracle sample -> gather -> update of the sampled indices taken through the position map
+        (element j targets the index drawn by sample pos[j]; positions >= B give an invalid index)."""
+        B = u.shape[-1]
+        ci, cw, cv = self.cpu.sample(u, beta, want_weights)
+        if pos is None:
+            upd_idx = ci
+        else:
+            ok = pos < B
+            upd_idx = np.where(ok, np.take_along_axis(ci, np.where(ok, pos, 0).astype(np.int64), axis=1),
+                               np.uint32(0xFFFFFFFF)).astype(np.uint32)
+        rows = [torch.empty((self.T, B, b), dtype=torch.uint8, device="cuda") for b in self.fb]
+        gi, gw, gv = self.gpu.step(dev(u), beta, dev(upd_prio),
+                                   None if pos is None else idx_to_dev(pos), want_weights=want_weights,
+                                   rows_out=rows if self.fb else None)
+        assert np.array_equal(idx_to_host(gi), ci), "sampled indices (per_step)"
+        assert gv.cpu().numpy().tobytes() == cv.tobytes(), "sampled leaf values (per_step)"
+        if want_weights:
+            np.testing.assert_allclose(gw.cpu().numpy(), cw, rtol=WEIGHT_RTOL, atol=0)
+        if self.fb:
+            self.gather(gi, ci, got=rows)
+        self.cpu.update(np.ascontiguousarray(upd_idx, dtype=np.uint32), upd_prio)
+        return gi, ci
+
     def update(self, idx_host, prio):
         self.gpu.update(idx_to_dev(idx_host), dev(prio))
         self.cpu.update(np.ascontiguousarray(idx_host, dtype=np.uint32), prio)
@@ -170,10 +194,12 @@ class Mirror:
         inp = wl.step_inputs(w, step, seed, B)
         if w.n_insert:
             self.insert(w.n_insert)
-        mode = step % 3           # rotate: separate calls, sample+gather fused, whole step fused
-        if mode == 2:
+        mode = step % 4           # rotate: separate calls, sample+gather fused, whole step fused (two call forms)
+        if mode == 3:
+            self.step_call(inp["u"], inp["beta"], w.weights, inp["upd_prio"], wl.dup_positions(inp, self.T, inp["u"].shape[-1]))
+        elif mode == 2:
             self.sample_gather_update(inp["u"], inp["beta"], w.weights, inp["upd_prio"], dup=inp,
-                                      alias=("dup_dst" not in inp and step % 2 == 0))
+                                      alias=("dup_dst" not in inp and step % 8 == 2))
         else:
             gi, ci = self.sample(inp["u"], inp["beta"], w.weights, fused_rows=(mode == 1))
             if mode == 0:

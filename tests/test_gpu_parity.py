@@ -763,6 +763,152 @@ def test_captured_step_replays(K, N, B):
     m.compare_status()
 
 
+@pytest.mark.parametrize("K,N,T,B,fb", [(32, 1 << 20, 1, 30000, (128,)), (16, 1 << 18, 3, 1024, (68, 24, 4, 68, 1)),
+                                        (2, 5000, 1, 64, ()), (4, 70001, 2, 3000, (12,)), (64, 300001, 1, 5000, (8,)),
+                                        (8, 1 << 21, 1, 9000, ())])
+def test_step_call_updates_the_batch_it_draws(K, N, T, B, fb):
+    """per_step: the update targets the leaves drawn by this very call, directly or through a position map
+    (the duplicate map of the stress workload; maps with many elements on one sample; invalid positions)."""
+    log(f"per_step K={K} N={N} T={T} B={B}")
+    rng = np.random.default_rng(K * 31 + B)
+    m = Mirror(K, N, T, fb)
+    prio = wl._draw_priorities("pareto_1.5", rng, (T, N))
+    prio[rng.random((T, N)) < 0.01] = 0.0
+    m.insert(N, prio=prio, chunk=1 << 18)
+    for it in range(8):
+        u = wl.uniform01(rng, (T, B))
+        pr = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B))
+        if it % 4 == 0:
+            pos = None
+        elif it % 4 == 1:                      # a tenth of the elements redirected to another sample's leaf
+            pos = np.tile(np.arange(B, dtype=np.uint32), (T, 1))
+            for t in range(T):
+                dst = rng.choice(B, size=B // 10, replace=False)
+                pos[t, dst] = rng.integers(0, B, B // 10)
+        elif it % 4 == 2:                      # everything onto a handful of samples; some elements invalid
+            pos = rng.integers(0, 7, (T, B)).astype(np.uint32)
+            pos[:, ::5] = B + 3
+            pr[:, 1::7] = np.float32(-1.0)
+        else:                                   # a random permutation
+            pos = np.stack([rng.permutation(B) for _ in range(T)]).astype(np.uint32)
+        m.step_call(u, 0.4 + 0.05 * it, it % 2 == 0, pr, pos)
+        m.compare_tree()
+        if it % 4 == 2:
+            assert m.gpu.status() & (FLAG_BAD_INDEX | FLAG_BAD_PRIORITY) == (FLAG_BAD_INDEX | FLAG_BAD_PRIORITY)
+    m.compare_status()
+
+
+@pytest.mark.parametrize("K,N,B", [(16, 1 << 20, 4096), (32, 300000, 20000)])
+def test_step_captured_on_a_fresh_top_replays(K, N, B):
+    """The capture happens right after an insert, when the topmost heights in memory are current and the host
+    knows it.  From the second replay on they are stale (the replayed update leaves them to the next
+    reader), so the captured sampling kernel must rebuild them whatever the host believed at capture time.
+    Also: a sampling call captured alone, and per_total captured alone, replayed after eager updates."""
+    log(f"graph captured on a fresh top K={K} N={N} B={B}")
+    rng = np.random.default_rng(K * 7 + B)
+    T = 1
+    m = Mirror(K, N, T, ())
+    m.insert(N, prio=wl._draw_priorities("exponential_1", rng, (T, N)), chunk=1 << 18, with_rows=False)
+    u_buf = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    upd_prio = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    oi = torch.empty((T, B), dtype=torch.int32, device="cuda")
+    ov = torch.empty((T, B), dtype=torch.float32, device="cuda")
+    tot = torch.empty(T, dtype=torch.float32, device="cuda")
+    m.insert(3, prio=np.full((T, 3), 2.0, dtype=np.float32), with_rows=False)   # leaves the top fresh
+    torch.cuda.synchronize()
+    step = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(step):       # sample, then update the batch just sampled
+        m.gpu.sample(u_buf, 0.4, want_weights=False, out_idx=oi, out_prio=ov, update=(oi, upd_prio))
+    only_sample = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(only_sample):
+        m.gpu.sample(u_buf, 0.4, want_weights=False, out_idx=oi, out_prio=ov)
+    only_total = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(only_total):
+        m.gpu.lib.per_total(m.gpu._h, tot.data_ptr(), m.gpu._stream())
+    for it in range(4):
+        u = wl.uniform01(rng, (T, B))
+        pr = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B))
+        u_buf.copy_(dev(u)); upd_prio.copy_(dev(pr))
+        step.replay()
+        torch.cuda.synchronize()
+        ci, _, cv = m.cpu.sample(u, 0.4, False)
+        assert np.array_equal(idx_to_host(oi), ci), f"replay {it}: sampled indices"
+        assert ov.cpu().numpy().tobytes() == cv.tobytes()
+        m.cpu.update(ci, pr)
+        only_total.replay()            # the root must be rebuilt by the captured call itself
+        torch.cuda.synchronize()
+        assert tot.cpu().numpy().tobytes() == m.cpu.total.tobytes(), f"replay {it}: captured per_total"
+        only_sample.replay()
+        torch.cuda.synchronize()
+        ci2, _, _ = m.cpu.sample(u, 0.4, False)
+        assert np.array_equal(idx_to_host(oi), ci2), f"replay {it}: captured plain sampling"
+    m.gpu.note_replay()
+    m.compare_tree()
+    m.compare_status()
+
+
+@pytest.mark.parametrize("K,N", [(16, 1 << 20), (32, 1 << 22)])
+def test_update_to_all_zero_on_a_tree_whose_top_is_rebuilt_lazily(K, N):
+    """A tree large enough for the update to leave its topmost heights to the next reader: every stored row is
+    updated to priority 0, then a plain sampling call finds the total 0.  That call has told the host that the
+    top is current again, so it must have stored the rebuilt heights: total, a second sampling call and a small
+    insert afterwards all agree with the oracle."""
+    log(f"all-zero update, lazy top K={K} N={N}")
+    rng = np.random.default_rng(K)
+    T, n = 1, 64
+    m = Mirror(K, N, T, ())
+    m.insert(n, prio=(rng.random((T, n)).astype(np.float32) + 0.5), with_rows=False)
+    idx = np.arange(n, dtype=np.uint32)[None, :]
+    m.update(idx, np.zeros((T, n), dtype=np.float32))
+    u = wl.uniform01(rng, (T, 256))
+    m.sample(u, 0.4)                                   # total 0: indices 0xFFFFFFFF, flag ZERO_TOTAL
+    assert m.gpu.status() & FLAG_ZERO_TOTAL
+    assert m.gpu.total().cpu().numpy().tobytes() == m.cpu.total.tobytes(), "root after the all-zero update"
+    m.sample(u, 0.4)
+    m.compare_tree()
+    m.insert(5, prio=np.full((T, 5), 0.25, dtype=np.float32), with_rows=False)
+    m.compare_tree()
+    m.sample(u, 0.4)
+    m.compare_status()
+
+
+def test_small_insert_that_would_overflow_the_default_lds_takes_the_general_path():
+    """K = 2 near N = 2^19 with a few thousand rows: the single-workgroup insert would need more than 64 KB of
+    staged child groups once an update has left the top stale; the insert must still succeed and match."""
+    log("small insert, K=2, many staged groups")
+    rng = np.random.default_rng(5)
+    K, N, T, n = 2, (1 << 19) - 3, 1, 4000
+    m = Mirror(K, N, T, ())
+    m.insert(N, prio=wl._draw_priorities("uniform_1e-3_1", rng, (T, N)), chunk=1 << 17, with_rows=False)
+    m.update(rng.integers(0, N, (T, 3000)).astype(np.uint32), rng.random((T, 3000)).astype(np.float32))
+    m.insert(n, prio=rng.random((T, n)).astype(np.float32), with_rows=False)
+    m.compare_tree()
+    assert m.gpu.cursor == m.cpu.trees[0].cursor and m.gpu.size == m.cpu.trees[0].size
+    m.compare_status()
+
+
+@pytest.mark.parametrize("K,N,T,B", [(32, 1 << 18, 1, 30000), (16, 70001, 2, 5000), (2, 5000, 1, 300)])
+def test_rebuild_restores_the_invariant_after_the_delta_form(K, N, T, B):
+    """per_update_delta on arbitrary floats leaves the upper levels equal to the sums of their children only up
+    to rounding; per_rebuild must make every level bit-equal to the oracle's set-form tree of the same leaves."""
+    log(f"rebuild after delta K={K} N={N} T={T}")
+    rng = np.random.default_rng(K + N)
+    m = Mirror(K, N, T, ())
+    m.insert(N, prio=wl._draw_priorities("lognormal_0_1", rng, (T, N)), chunk=1 << 17, with_rows=False)
+    idx = rng.integers(0, N, (T, B)).astype(np.uint32)
+    delta = (rng.random((T, B)).astype(np.float32) * 0.37).astype(np.float32)
+    m.gpu.update_delta(idx_to_dev(idx), dev(delta))
+    leaves = np.stack([m.gpu.read_level(t, 0).cpu().numpy() for t in range(T)])
+    m.gpu.rebuild()
+    # the oracle's set form fed with the device's leaves (every leaf set once: the invariant tree of those leaves)
+    ref = MultiOracle(T, K, N, ())
+    ref.insert(N, None, np.ascontiguousarray(leaves))
+    for t in range(T):
+        for h in range(m.gpu.H + 1):
+            assert m.gpu.read_level(t, h).cpu().numpy().tobytes() == ref.read_level(t, h).tobytes(), (t, h)
+    assert m.gpu.total().cpu().numpy().tobytes() == ref.total.tobytes()
+
+
 # ---------------------------------------------------------------------------------------------
 # importance weights relative to the whole buffer (companion minimum of the sum tree)
 # ---------------------------------------------------------------------------------------------
