@@ -8,11 +8,13 @@ update indices).  Prints ONE JSON line: transitions/s, the roofline figure of th
 dominant kernel (HIP-event timed inside this run) and the CPU oracle's rate on a
 bounded sample of the same steps.
 
-All inputs are resident in HBM before the timed region.  The update indices of
-step s are the indices sampled in step s with the workload's duplicate map
-applied; they are produced by an untimed recording pass from the same initial
-state (the arena is snapshotted and restored), so that the timed region contains
-only the library's own kernels.
+All inputs are resident in HBM before the timed region.  The headline form is the
+loop of Listing 2 as it is: the update of step s targets the indices sampled in
+step s, taken through the workload's duplicate position map inside the step
+(`per_step`), so the sample -> update dependency is inside the timed region.
+Beside it the line reports the relaxed form in which the update batch is a
+separate array that exists before the step starts ("earlier_batch_form": the
+priorities of an earlier batch; the array is filled from a first pass).
 """
 from __future__ import annotations
 
@@ -54,19 +56,24 @@ def parse():
     return ap.parse_args()
 
 
-def algorithmic_bytes(w, idx, upd_idx, K, H, h_mem, weights):
+def algorithmic_bytes(w, idx, upd_idx, K, H, h_lds, weights):
     """Bytes the method itself must move in one step, per part of the step, each distinct K-group counted
     once per phase (what a perfect cache would move).  idx / upd_idx: [T, B] uint32 of one step.
-    h_mem: heights below it are read from memory by the descent (the ones above sit in LDS)."""
+    h_lds: lowest height taken to be on chip; only the child groups below it count as memory traffic.
+      sample : 4B (u) + sum_{h < h_lds} 4K G_h + 4B (idx) + 4B (weight) + 4B (sampled priority, requested here)
+      gather : 4B (idx) + E R (distinct rows) + E B (dense rows)
+      update : 8B (idx, prio) + 4U (leaf writes) + sum_{h=1..H} (4K Q_h + 4 Q_h)
+    Values that only pass between two kernels of the step (the sampled value on its way to becoming a weight)
+    are not counted."""
     logK = K.bit_length() - 1
     T, B = idx.shape
     E = w.row_bytes
     out = {"k_sample": 0, "k_weights": 0, "k_rows_gather": 0, "k_update_claim": 0, "k_update_tree": 0}
     for t in range(T):
         i64 = idx[t].astype(np.int64)
-        groups = sum(len(np.unique(i64 >> ((h + 1) * logK))) * 4 * K for h in range(0, min(h_mem, H)))
-        out["k_sample"] += 4 * B + groups + 4 * B + 4 * B + (4 * B if weights else 0)   # u, groups, idx, prio, value
-        out["k_weights"] += 8 * B if weights else 0                                       # value in, weight out
+        groups = sum(len(np.unique(i64 >> ((h + 1) * logK))) * 4 * K for h in range(0, min(h_lds, H)))
+        out["k_sample"] += 4 * B + groups + 4 * B + 4 * B                                 # u, groups, idx, sampled priority
+        out["k_weights"] += 4 * B if weights else 0                                       # weight out
         out["k_rows_gather"] += 4 * B + E * len(np.unique(i64)) + E * B                   # idx, distinct rows, dense rows
         u64 = upd_idx[t].astype(np.int64)
         out["k_update_claim"] += 8 * B                                                    # idx, prio
@@ -80,7 +87,13 @@ def algorithmic_bytes(w, idx, upd_idx, K, H, h_mem, weights):
 def per_launched_kernel(parts, launched):
     """Algorithmic bytes of the kernels that were launched, from the parts of the step each one carries."""
     alg = dict(parts)
-    if "k_tree_finish" in launched:     # two-kernel step: claim in the sampling kernel, tree pass beside rows and weights
+    if "k_step" in launched:            # sampling and the update of the sampled batch in one kernel
+        alg["k_step"] = parts["k_sample"] + parts["k_update_claim"] + parts["k_update_tree"]
+        if "k_finish" in launched:
+            alg["k_finish"] = parts["k_rows_gather"] + parts["k_weights"]
+        else:
+            alg["k_step"] += parts["k_rows_gather"] + parts["k_weights"]
+    elif "k_tree_finish" in launched:   # two-kernel step: claim in the sampling kernel, tree pass beside rows and weights
         alg["k_sample"] = parts["k_sample"] + parts["k_update_claim"]
         alg["k_tree_finish"] = parts["k_update_tree"] + parts["k_rows_gather"] + parts["k_weights"]
     elif "k_finish" in launched:        # second kernel: rows and weights, plus the claim when no claim kernel ran
@@ -156,29 +169,36 @@ def main():
             ins_rows.append([torch.stack([wl.row_bytes_torch(t, cnt, f, b) for t in range(T)])
                              for f, b in enumerate(w.field_bytes)])
     has_dup = "dup_dst" in inputs[0]
-    if has_dup:
-        d_dst = torch.from_numpy(np.stack([i["dup_dst"] for i in inputs])).cuda()
-        d_src = torch.from_numpy(np.stack([i["dup_src"] for i in inputs])).cuda()
+    d_pos = None
+    if has_dup:   # the duplicate map as a position map: update element j targets the index sampled at position pos[j]
+        d_pos = torch.from_numpy(np.stack([wl.dup_positions(i, T, B) for i in inputs]).view(np.int32)).cuda()
 
     side = torch.cuda.Stream()
     gather_done = [None]
     fused = not args.separate_gather
     fused_step = fused and not args.separate_update
 
-    def step(s, recording=False, overlap=False):
-        """insert -> sample -> gather -> update.  With overlap the row gather (which only reads the
-        sampled indices and the payload) runs on a second stream beside the update, as the paper's
-        runtime overlaps data movement with the replay operations; the tree work stays in order."""
+    def step_in(s):
+        """The loop of Listing 2 as it is: insert -> sample -> gather -> update of the batch just sampled (through the
+        duplicate position map where the workload has one), one per_step call."""
+        if w.n_insert:
+            buf.insert(w.n_insert, ins_rows[s])
+        buf.step(d_u[s], inputs[s]["beta"], d_prio[s], None if d_pos is None else d_pos[s], want_weights=w.weights,
+                 want_prio=True, out_idx=d_idx[s], out_weight=d_w, out_prio=d_v, rows_out=d_rows)
+
+    def step(s, overlap=False):
+        """The relaxed form: the update batch of step s is a separate array that exists before the step starts.
+        With overlap the row gather (which only reads the sampled indices and the payload) runs on a second
+        stream beside the update, as the paper's runtime overlaps data movement with the replay operations."""
         main = torch.cuda.current_stream()
         if w.n_insert:
             if overlap and gather_done[0] is not None:
                 main.wait_event(gather_done[0])      # an insert may overwrite a row the last gather reads
             buf.insert(w.n_insert, ins_rows[s])
-        whole = fused_step and not recording     # the recording pass has to build the update indices in between
         buf.sample(d_u[s], inputs[s]["beta"], want_weights=w.weights, want_prio=True,
                    out_idx=d_idx[s], out_weight=d_w, out_prio=d_v, rows_out=d_rows if fused else None,
-                   update=(d_upd_idx[s], d_prio[s]) if whole else None)
-        if whole:
+                   update=(d_upd_idx[s], d_prio[s]) if fused_step else None)
+        if fused_step:
             return
         if fused:
             pass
@@ -192,113 +212,128 @@ def main():
                 gather_done[0].record(side)
         else:
             buf.gather(d_idx[s], d_rows)
-        if recording:     # synthesise this step's update indices (input generation, untimed pass only)
-            d_upd_idx[s].copy_(d_idx[s])
-            if has_dup:
-                for t in range(T):
-                    d_upd_idx[s, t, d_dst[s, t]] = d_idx[s, t, d_src[s, t]]
         buf.update(d_upd_idx[s], d_prio[s])
 
-    # ---------------------------------------------------------------- recording pass (untimed)
     torch.cuda.synchronize()
     snapshot = buf.arena.clone()
     cursor0 = (buf.cursor, buf.size)
-    for s in range(total_steps):
-        step(s, recording=True)
-    torch.cuda.synchronize()
-    status_record = buf.status()
-    rec_idx = d_idx.cpu().numpy().view(np.uint32)
-    rec_upd = d_upd_idx.cpu().numpy().view(np.uint32)
-    final_root = buf.total().cpu().numpy().copy()
 
     def restore():
         buf.arena.copy_(snapshot)
         buf.set_ring(*cursor0)
         torch.cuda.synchronize()
 
-    # per-kernel durations with HIP events (separate pass: events add gaps between kernels)
-    restore_ok = True
-    restore()
-    for s in range(warmup):
-        step(s)
-    buf.profile(True)
-    for s in range(warmup, total_steps):
-        step(s)
-    torch.cuda.synchronize()
-    kernels = buf.profile_read()
-    buf.profile(False)
-
-    # ---------------------------------------------------------------- timed run
-    if restore_ok:
-        restore()
     stream = torch.cuda.current_stream()
-    overlap = args.overlap and not fused
-    gather_done[0] = None
-    for s in range(warmup):
-        step(s)
-    torch.cuda.synchronize()
-    graph = None
-    if not args.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for s in range(warmup, total_steps):
-                step(s, overlap=overlap)
-            if overlap:
-                torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    ev0.record(stream)
-    if graph is not None:
-        graph.replay()
-    else:
+
+    def time_form(one_step, overlap=False):
+        """Per-kernel durations with HIP events attached to each launch (a pass of its own: the events add gaps
+        between kernels), then the timed run: warm-up steps eagerly, the timed steps as one HIP graph."""
+        restore()
+        for s in range(warmup):
+            one_step(s)
+        buf.profile(True)
         for s in range(warmup, total_steps):
-            step(s, overlap=overlap)
-        if overlap:
-            stream.wait_stream(side)
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    ms_total = ev0.elapsed_time(ev1)
-    ms_per_step = ms_total / steps
-    if restore_ok:   # the timed run must have reproduced the recorded trajectory
-        assert np.array_equal(d_idx.cpu().numpy().view(np.uint32)[warmup:], rec_idx[warmup:]), "timed run diverged"
-        assert buf.total().cpu().numpy().tobytes() == final_root.tobytes(), "timed run ended in a different state"
+            one_step(s)
+        torch.cuda.synchronize()
+        kern = buf.profile_read()
+        buf.profile(False)
+        idx_seen = d_idx.cpu().numpy().view(np.uint32).copy()
+        root_seen = buf.total().cpu().numpy().copy()
+        status_seen = buf.status()
+        restore()
+        gather_done[0] = None
+        for s in range(warmup):
+            one_step(s)
+        torch.cuda.synchronize()
+        graph = None
+        if not args.no_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for s in range(warmup, total_steps):
+                    one_step(s, overlap=overlap) if overlap else one_step(s)
+                if overlap:
+                    torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        if graph is not None:
+            graph.replay()
+        else:
+            for s in range(warmup, total_steps):
+                one_step(s, overlap=overlap) if overlap else one_step(s)
+            if overlap:
+                stream.wait_stream(side)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1) / steps
+        buf.note_replay()
+        # the timed run must have reproduced the trajectory of the pass before it
+        assert np.array_equal(d_idx.cpu().numpy().view(np.uint32)[warmup:], idx_seen[warmup:]), "timed run diverged"
+        assert buf.total().cpu().numpy().tobytes() == root_seen.tobytes(), "timed run ended in a different state"
+        return ms, kern, idx_seen, root_seen, status_seen, graph is not None
+
+    # ---------------------------------------------------------------- headline: the update targets this step's sample
+    ms_per_step, kernels, rec_idx, final_root, status_record, graphed = time_form(step_in)
+    rec_upd = np.stack([wl.apply_dup_map(rec_idx[s], inputs[s]) for s in range(total_steps)])
+
+    # ---------------------------------------------------------------- beside it: the update batch known before the step
+    # (same trajectory: the array holds what the headline form derives inside the step)
+    d_upd_idx.copy_(torch.from_numpy(rec_upd.view(np.int32)).cuda())
+    overlap = args.overlap and not fused
+    ms_early, kernels_early, idx_early, root_early, _, _ = time_form(step, overlap=overlap)
+    assert np.array_equal(idx_early, rec_idx) and root_early.tobytes() == final_root.tobytes(), "the two forms disagree"
+    restore_ok = True
 
     # ---------------------------------------------------------------- algorithmic bytes and roofline
     H = buf.H
     lvl_n = [buf.level_count(h) for h in range(H + 1)]
-    lds_budget = 64 * 1024
-    for kv in args.tune:
-        if kv.startswith("lds_budget_bytes="):
-            lds_budget = int(kv.split("=")[1])
-    h_mem, acc, slots = H, 0, 0     # mirrors the library's choice of the heights it copies to LDS
+    # h_lds: the lowest height such that it and everything above it fit the LDS of one compute unit beside the
+    # sampling kernel's staging rows (c4: height 2, 64 KiB + 2.2 KiB); child groups below it count as traffic
+    h_lds, acc = H, 0
     for l in range(H - 1, -1, -1):
         add = lvl_n[l + 1] * K * 4
-        if acc + add > lds_budget or slots == 4:
+        if acc + add > 96 * 1024:
             break
         acc += add
-        slots += 1
-        h_mem = l
+        h_lds = l
     sel = list(range(warmup, total_steps, max(1, steps // 16)))
-    per_step = [algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, h_mem, w.weights) for s in sel]
+    per_step = [algorithmic_bytes(w, rec_idx[s], rec_upd[s], K, H, h_lds, w.weights) for s in sel]
     parts = {k: float(np.mean([p[k] for p in per_step])) for k in per_step[0]}
     a_sample = parts["k_sample"]
     a_gather = parts["k_rows_gather"] + parts["k_weights"]
     a_update = parts["k_update_claim"] + parts["k_update_tree"]
     a_step = a_sample + a_gather + a_update
-    alg = per_launched_kernel(parts, set(kernels))
-    kern_ms = {k: v[0] / max(1, v[1]) for k, v in kernels.items()}
-    kern_per_step = {k: v[1] / steps for k, v in kernels.items()}
-    step_kernels = [k for k in kernels if k in alg]
+
+    def kernel_view(kern):
+        alg = per_launched_kernel(parts, set(kern))
+        kern_ms = {k: v[0] / max(1, v[1]) for k, v in kern.items()}
+        per = {k: v[1] / steps for k, v in kern.items()}
+        return alg, kern_ms, per, [k for k in kern if k in alg]
+
+    alg, kern_ms, kern_per_step, step_kernels = kernel_view(kernels)
     dominant = max(step_kernels, key=lambda k: kernels[k][0])
     dom_bytes = alg[dominant] / max(1e-9, kern_per_step[dominant])
     dom_gbs = dom_bytes / (kern_ms[dominant] * 1e-3) / 1e9
     roofline = {
         "kernel": dominant, "bound": "hbm", "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(w.name, dominant),
+        "traffic_source": f"profiles/{w.name}_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command)",
         "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(kern_ms[dominant] * 1e3, 2),
     }
     step_gbs = a_step / (ms_per_step * 1e-3) / 1e9
+    alg_e, kern_ms_e, kern_per_e, step_kernels_e = kernel_view(kernels_early)
+    early_form = {
+        "update_indices": "a separate array filled before the step (the priorities of an earlier batch); here it holds "
+                          "what the headline form derives in-step, so both forms walk the same trajectory",
+        "calls_per_step": "per_sample_gather_update" if fused_step else
+                          ("per_sample_gather, per_update" if fused else "per_sample, per_gather, per_update"),
+        "ms_per_step": round(ms_early, 5), "value": round(T * B / (ms_early * 1e-3), 1), "unit": "transitions/s",
+        "step_hbm_frac": round(a_step / (ms_early * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "streams": 2 if overlap else 1,
+        "kernels_us": {k: round(v * 1e3, 2) for k, v in sorted(kern_ms_e.items())},
+        "kernel_algorithmic_bytes": {k: int(alg_e[k]) for k in sorted(step_kernels_e)},
+    }
 
     # ---------------------------------------------------------------- the paper's own update form, for comparison
     # Same step with the update done as the paper does it (Section V-A): retrieve the old priorities, form
@@ -519,15 +554,18 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "K": K, "N": N, "T": T, "B": B, "row_bytes": w.row_bytes,
-                   "insert_per_step": w.n_insert, "launch": "hip_graph" if graph is not None else "eager",
-                   "streams": 2 if overlap else 1, "weight_norm": args.weight_norm, "calls_per_step": "per_sample_gather_update" if fused_step else
-                   ("per_sample_gather, per_update" if fused else "per_sample, per_gather, per_update")},
+                   "insert_per_step": w.n_insert, "launch": "hip_graph" if graphed else "eager",
+                   "streams": 1, "weight_norm": args.weight_norm, "calls_per_step": "per_step",
+                   "update_indices": "this step's sampled indices" +
+                                     (" through the duplicate position map, applied inside the step" if has_dup else "")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "cpu_workers_baseline": cpu_workers,
+        "earlier_batch_form": early_form,
         "paper_update_form": delta_form,
         "step_stream": step_stream,
         "step_algorithmic_bytes": int(a_step),
+        "h_lds": h_lds,
         "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
         "phase_algorithmic_bytes": {"sample": int(a_sample), "gather_and_weights": int(a_gather), "update": int(a_update)},
         "kernel_algorithmic_bytes": {k: int(alg[k]) for k in sorted(step_kernels)},
