@@ -320,6 +320,16 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
 int per_set_weight_norm(per_t* p, int mode);
 int per_min_priority(per_t* p, float* d_out, void* stream);
 
+/* per_min_priority for callers that must not allocate and cannot set memory aside for scratch (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the partial minima of the
+ * reduction live in a static device array of the library (256 KiB on every GPU the library runs on, held
+ * until the process ends) instead of the arena; no allocating call is made.  Same result as
+ * per_min_priority.  At most 64 trees (PER_ERANGE beyond).  PER_EHIP if the array's device address could not
+ * be obtained when the buffer was created.  All buffers on one GPU share the array, which keeps the last
+ * call's contents (nothing in it has to start at zero: every word read is written by the call first):
+ * calls that overlap in time on one GPU (different streams) race; issue them on one stream or order them. */
+int per_min_priority_static(per_t* p, float* d_out, void* stream);
+
 /* To be called after a captured graph holding calls on this buffer has been replayed and before the next
  * call made outside the graph: a replay changes the device without passing through the library, so
  * what the host has noted about the device (are the topmost heights current, is the companion minimum

@@ -79,3 +79,32 @@ hipError_t launch_min_reduce(const Geom& g, const Tuning& tn, uint32_t* weight_m
   *weight_mode = kWeightBufferNorm | ((uint32_t)blocks << kWeightPartsShift);
   return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------------
+// the same reduction with its partial minima in a static device array
+// ---------------------------------------------------------------------------------
+// For callers that may not hand over or allocate scratch memory at all.  The partial minima of k_min_reduce
+// ([tree][kMinParts] words) live in this array instead of the caller's arena; every GPU the library runs on
+// holds its own copy until the process ends.  In host code the array's name is only a stand-in: its address
+// on a device comes from hipGetSymbolAddress, asked once per device with that device current (at per_create)
+// and kept; the kernels take that address as an argument, as they take the arena's buffer.
+static __device__ __align__(256) uint32_t scratch[kStaticMinTrees * kMinParts];
+static uint32_t* g_scratch_addr[kMaxDevices];
+
+hipError_t static_scratch_address(int device, uint32_t** out) {
+  *out = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_addr[device]) {
+    int current = -1;
+    hipError_t e = hipGetDevice(&current);
+    if (e != hipSuccess) return e;
+    if (current != device) return hipErrorInvalidDevice;   // the symbol's address belongs to the current device
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_addr[device] = static_cast<uint32_t*>(ptr);
+  }
+  *out = g_scratch_addr[device];
+  return hipSuccess;
+}

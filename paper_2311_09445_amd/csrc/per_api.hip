@@ -27,6 +27,7 @@ struct per_buffer {
   bool rng_on;               // per_set_rng was called: sampling calls without uniforms draw their own
   uint64_t rng_seed, rng_calls;   // key of the generator; number of sampling calls that drew from it
   int device;
+  uint32_t* static_scratch;   // this device's copy of the static array of per_min_priority_static (null: its address could not be had)
   Profiler prof;
 };
 
@@ -281,6 +282,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->min_stale = true;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
   p->tn.device = p->device;
+  if (static_scratch_address(p->device, &p->static_scratch) != hipSuccess) p->static_scratch = nullptr;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   // zero everything (tree levels, stamps and payload), then the scalars
@@ -730,6 +732,25 @@ int per_min_priority(per_t* p, float* d_out, void* stream) {
   uint32_t mode = 0;
   if (reduce_min(p, s, &mode) != hipSuccess) return PER_EHIP;
   return hip_rc(launch_read_scalars(p->g, 2, mode, d_out, s));
+}
+
+int per_min_priority_static(per_t* p, float* d_out, void* stream) {
+  if (!p || !d_out || misaligned(d_out, 4)) return PER_EINVAL;
+  if (p->g.T > kStaticMinTrees) return PER_ERANGE;   // more trees than the static array has room for
+  if (!p->static_scratch) return PER_EHIP;           // the array's address on this device could not be had at create
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  CaptureGuard capture(p, s);
+  if (p->min_stale) {
+    if (launch_min_rebuild(p->g, p->tn, s) != hipSuccess) return PER_EHIP;
+    p->min_stale = false;
+  }
+  // the kernels of per_min_priority, with their partial minima in the static array instead of the arena; every
+  // word the reader folds is written by the reduction first (plain stores), so nothing has to start at zero
+  Geom g = p->g;
+  g.vmin_buf = p->static_scratch;
+  uint32_t mode = 0;
+  if (launch_min_reduce(g, p->tn, &mode, s) != hipSuccess) return PER_EHIP;
+  return hip_rc(launch_read_scalars(g, 2, mode, d_out, s));
 }
 
 int per_note_replay(per_t* p) {

@@ -48,6 +48,7 @@ struct Geom {
   uint32_t* vmin_buf;               // [T][kMinParts] partial minima of min1 (fp32 bits), one per workgroup of k_min_reduce
 };
 constexpr uint32_t kMinParts = 1024;     // most workgroups k_min_reduce is launched with
+constexpr uint32_t kStaticMinTrees = 64; // most trees per_min_priority_static serves (its static array: 64 x 1024 words = 256 KiB per GPU)
 
 constexpr uint32_t kNoMin = 0x7F800000u;   // fp32 bits of +inf: above every valid priority
 
@@ -192,6 +193,7 @@ hipError_t launch_fill_u32(const Tuning& tn, uint32_t* p, uint64_t count, uint32
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s);
 hipError_t launch_min_rebuild(const Geom& g, const Tuning& tn, hipStream_t s);
 hipError_t launch_min_reduce(const Geom& g, const Tuning& tn, uint32_t* weight_mode, hipStream_t s);
+hipError_t static_scratch_address(int device, uint32_t** out);   // the static array of per_min_priority_static on `device` (which must be current)
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          const RngArgs& rng,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t weight_mode, uint32_t stale_hb,

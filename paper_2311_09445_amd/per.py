@@ -22,7 +22,7 @@ EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_insert_protected", "per_sample", "per_sample_gather",
     "per_sample_gather_update", "per_step", "per_gather",
     "per_update", "per_update_td", "per_update_delta", "per_rebuild", "per_set_rng", "per_rng_calls", "per_run_steps",
-    "per_run_steps_fits", "per_run_requests", "per_set_weight_norm", "per_min_priority", "per_note_replay", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
+    "per_run_steps_fits", "per_run_requests", "per_set_weight_norm", "per_min_priority", "per_min_priority_static", "per_note_replay", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
     "per_profile", "per_profile_read", "per_strerror",
 ]
@@ -117,6 +117,7 @@ def _lib():
         "per_set_weight_norm": (C.c_int, [vp, C.c_int]),
         "per_note_replay": (C.c_int, [vp]),
         "per_min_priority": (C.c_int, [vp, vp, vp]),
+        "per_min_priority_static": (C.c_int, [vp, vp, vp]),
         "per_update_td": (C.c_int, [vp, u32, vp, vp, C.c_double, C.c_double, vp]),
         "per_get_priority": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_read_level": (C.c_int, [vp, u32, u32, vp, C.POINTER(u64), vp]),
@@ -439,6 +440,14 @@ class PrioritizedReplay:
         """Smallest positive leaf of every tree (+inf where there is none)."""
         out = self._torch.empty(self.T, dtype=self._torch.float32, device=self.device)
         self._check(self.lib.per_min_priority(self._h, _dptr(out), self._stream()), "per_min_priority")
+        return out
+
+    def min_priority_static(self, out=None):
+        """per_min_priority with the reduction's scratch in the library's static device array (no allocation when
+        ``out`` is given)."""
+        if out is None:
+            out = self._torch.empty(self.T, dtype=self._torch.float32, device=self.device)
+        self._check(self.lib.per_min_priority_static(self._h, _dptr(out), self._stream()), "per_min_priority_static")
         return out
 
     def set_rng(self, seed: int, next_call: int = 0):
