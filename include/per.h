@@ -61,6 +61,8 @@ extern "C" {
                                      gather and get_priority write zeros for it                                   */
 #define PER_FLAG_BAD_PRIORITY 2u  /* NaN, infinite or negative value: leaf write skipped                          */
 #define PER_FLAG_ZERO_TOTAL   4u  /* sample on a tree whose root is not > 0: indices 0xFFFFFFFF, weights 0        */
+#define PER_FLAG_GAVE_UP      8u  /* a bounded wait inside a kernel ran out (never seen; the call's update is then
+                                     incomplete: rebuild the buffer from a saved state)                           */
 
 typedef struct per_buffer per_t;   /* opaque host object */
 
@@ -360,6 +362,9 @@ uint64_t per_rng_calls(const per_t* p);
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
  *                  the next call that reads them; 0 makes per_update finish them itself
  *   "insert_small" : 1 (default) runs an insert of few rows as a single kernel, one workgroup per tree
+ *   "step_kernel" : 1 (default) lets per_step (and per_sample_gather_update called with the sampled batch as
+ *                  its update batch) run sampling and update as one kernel, one workgroup per subtree, where
+ *                  the tree and the batch fit that kernel; 0: always the separate kernels
  *   "claim_in_sample" : 1 (default) lets per_sample_gather_update run the first phase of its update
  *                  inside the sampling kernel (two kernels per step) whenever the update batch is the
  *                  sampled batch itself or lies apart from the sampling outputs; 0: always three kernels */

@@ -24,6 +24,7 @@ struct per_buffer {
   int weight_norm;           // PER_NORM_BATCH or PER_NORM_BUFFER
   bool min_stale;            // min1 does not describe the leaves (it is rebuilt when next needed)
   uint32_t stale_hb;         // != 0: the last update left the heights above this one to their next reader
+  bool side_maybe;           // the one-kernel step may have left the nodes of its owner height in the side array
   bool rng_on;               // per_set_rng was called: sampling calls without uniforms draw their own
   uint64_t rng_seed, rng_calls;   // key of the generator; number of sampling calls that drew from it
   int device;
@@ -42,7 +43,7 @@ struct Layout {
   uint32_t n[kMaxHeight + 1];
   uint32_t stride[kMaxHeight + 1];
   size_t level_off[kMaxHeight + 1];
-  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, min1_off, col_off[kMaxFields];
+  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, min1_off, side_off, col_off[kMaxFields];
   uint32_t dirty_stride, arrive_stride, arrive_level_off[kMaxHeight + 1];
   uint64_t col_stride[kMaxFields];
   uint32_t row_stride;        // bytes between stored rows
@@ -86,8 +87,8 @@ void make_layout(const per_config* c, Layout* L) {
   } while (n > 1);
   L->H = h;
   size_t off = 0;
-  L->scalars_off = off;                         // max_v, status, vnext, vcur, sbase, sfloor [T] each; vmin[2][T][kVminSlots], vmin_buf[T][kMinParts]
-  off = round_up(off + (size_t)(6 + 2 * kVminSlots + kMinParts) * T * 4, kAlign);
+  L->scalars_off = off;                         // max_v, status, vnext, vcur, sbase, sfloor [T] each; step_ctl[T][4]; vmin[2][T][kVminSlots], vmin_buf[T][kMinParts]
+  off = round_up(off + (size_t)(6 + 4 + 2 * kVminSlots + kMinParts) * T * 4, kAlign);
   for (uint32_t l = 0; l <= L->H; ++l) {
     const uint64_t padded = ((uint64_t)L->n[l] + K - 1) / K * K;
     L->stride[l] = (uint32_t)round_up(padded, 64);
@@ -115,6 +116,8 @@ void make_layout(const per_config* c, Layout* L) {
   L->min1_stride = (uint32_t)round_up(L->n[1], 64);
   L->min1_off = off;
   off = round_up(off + (size_t)L->min1_stride * T * 4, kAlign);
+  L->side_off = off;                            // second array for the nodes of the one-kernel step's owner height
+  off = round_up(off + (size_t)kStepSideStride * T * 4, kAlign);
   L->tree_end = off;
   // payload, row-major: every field at an offset aligned to the widest access its size allows, rows 16 bytes apart or a multiple
   uint32_t row = 0;
@@ -168,8 +171,19 @@ hipError_t reduce_min(per_t* p, hipStream_t s, uint32_t* weight_mode) {
   return launch_min_reduce(p->g, p->tn, weight_mode, s);
 }
 
+// After one-kernel steps the nodes of their owner height may live in the side array; every other kernel reads
+// the level array, so they are moved back first (a small kernel that looks at the device-side word itself).
+hipError_t settle_side(per_t* p, hipStream_t s) {
+  if (!p->side_maybe) return hipSuccess;
+  hipError_t e = launch_step_settle(p->g, p->tn, s);
+  if (e == hipSuccess) p->side_maybe = false;
+  return e;
+}
+
 // Rebuilds the heights an update left stale, for readers that take them from memory.
 hipError_t ensure_top(per_t* p, hipStream_t s) {
+  hipError_t e0 = settle_side(p, s);
+  if (e0 != hipSuccess) return e0;
   if (!p->stale_hb) return hipSuccess;
   hipError_t e = launch_resum_top(p->g, p->tn, p->stale_hb, s);
   if (e == hipSuccess) p->stale_hb = 0;
@@ -189,7 +203,16 @@ void forget_device_notes(per_t* p) {
   const uint32_t hb = lazy_top_height(p->g, p->tn);
   if (hb) p->stale_hb = hb;
   p->min_stale = true;
+  if (p->g.step_ho) p->side_maybe = true;
 }
+// Before a tree pass: the level array of every height it writes must be the current one, and the heights it
+// does not rewrite in full (up to its workgroup roots) must not be stale below those roots.
+hipError_t prepare_tree_pass(per_t* p, hipStream_t s) {
+  const uint32_t hb = lazy_top_height(p->g, p->tn);
+  if (p->stale_hb && (!hb || p->stale_hb < hb)) return ensure_top(p, s);
+  return settle_side(p, s);
+}
+
 struct CaptureGuard {
   per_t* p;
   bool on;
@@ -257,8 +280,12 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.vcur = g.vnext + g.T;
   g.sbase = g.vcur + g.T;
   g.sfloor = g.sbase + g.T;
-  g.vmin = g.sfloor + g.T;
+  g.step_ctl = g.sfloor + g.T;
+  g.vmin = g.step_ctl + (size_t)4 * g.T;
   g.vmin_buf = g.vmin + (size_t)2 * kVminSlots * g.T;
+  g.step_side = reinterpret_cast<float*>(p->arena + L.side_off);
+  g.step_side_stride = kStepSideStride;
+  g.step_ho = step_owner_height(g);
   g.min1 = reinterpret_cast<uint32_t*>(p->arena + L.min1_off);
   g.min1_stride = L.min1_stride;
   for (uint32_t f = 0; f < cfg->n_fields; ++f) {
@@ -275,9 +302,11 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.claim_in_sample = 1;
   p->tn.insert_small = 1;
   p->tn.group_claim = 1;
+  p->tn.step_kernel = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->claims_left = false;
+  p->side_maybe = false;
   p->weight_norm = PER_NORM_BATCH;
   p->min_stale = true;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
@@ -309,6 +338,7 @@ static int insert_impl(per_t* p, uint32_t n, const void* const* d_field_src, con
   if (!d_protect) n_protect = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   CaptureGuard capture(p, s);
+  if (settle_side(p, s) != hipSuccess) return PER_EHIP;
   const uint64_t N = p->cfg.capacity;
   const uint32_t cursor = (uint32_t)p->cursor;
   FieldTable ft;
@@ -404,10 +434,49 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
   CaptureGuard capture(p, s);
   FieldTable ft;
   const bool fused = d_field_dst && fill_fields(p, d_field_dst, &ft);
+  // An update of exactly the batch drawn here (element for element, or through a position map), its values apart
+  // from the outputs: sampling and update run as one kernel where that kernel fits the tree and the batch.
+  uint32_t step_block = 0;
+  if (upd_B == B && d_upd_idx == d_out_idx && p->tn.step_kernel && p->tn.lazy_top) {
+    const size_t n_out = (size_t)p->g.T * B * 4;
+    if (!ranges_overlap(d_upd_prio, n_out, d_out_idx, n_out) && !ranges_overlap(d_upd_prio, n_out, d_out_weight, n_out) &&
+        !ranges_overlap(d_upd_prio, n_out, d_out_prio, n_out) && !ranges_overlap(d_upd_pos, n_out, d_out_idx, n_out) &&
+        !ranges_overlap(d_upd_pos, n_out, d_out_weight, n_out) && !ranges_overlap(d_upd_pos, n_out, d_out_prio, n_out))
+      step_block = step_fits(p->g, B);
+  }
+  if (step_block) {
+    // the kernel reads the heights up to its owner height from memory: none of them may be stale
+    if (p->stale_hb && p->stale_hb < p->g.step_ho && ensure_top(p, s) != hipSuccess) return PER_EHIP;
+    if (p->claims_left) {   // (its scratch words alias the leaf stamps, which must be zero)
+      ClaimArgs none{};
+      int rc = prepare_claim(p, B, s, &none);
+      if (rc != PER_OK) return rc;
+    }
+  } else if ((upd_B ? prepare_tree_pass(p, s) : settle_side(p, s)) != hipSuccess) {
+    return PER_EHIP;
+  }
   uint32_t weight_mode = 0;
   if (d_out_weight && p->weight_norm == PER_NORM_BUFFER &&   // the weights refer to the tree as it is before this call's update
       reduce_min(p, s, &weight_mode) != hipSuccess)
     return PER_EHIP;
+  if (step_block) {
+    RngArgs rng{};
+    if (!d_u) {
+      rng.on = 1;
+      rng.seed_lo = (uint32_t)p->rng_seed;
+      rng.seed_hi = (uint32_t)(p->rng_seed >> 32);
+      rng.call_lo = (uint32_t)p->rng_calls;
+      rng.call_hi = (uint32_t)(p->rng_calls >> 32);
+      ++p->rng_calls;
+    }
+    p->min_stale = true;   // (the kernel does not renew the companion minimum)
+    hipError_t e = launch_step(p->g, p->tn, step_block, B, (uint32_t)p->size, beta, d_u, rng, d_out_idx, d_out_weight,
+                               d_out_prio, weight_mode, fused ? &ft : nullptr, d_upd_prio, d_upd_pos, s);
+    p->stale_hb = p->g.step_ho;   // the heights above the owner height are left to their next reader,
+    p->side_maybe = true;         // and the nodes of that height may be in the side array
+    if (e != hipSuccess) p->claims_left = true;
+    return hip_rc(e);
+  }
   ClaimArgs claim{};
   int claim_mode = CLAIM_NONE;
   if (upd_B) {
@@ -503,6 +572,7 @@ int per_update(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_prio,
   if (rc != PER_OK || B == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   CaptureGuard capture(p, s);
+  if (prepare_tree_pass(p, s) != hipSuccess) return PER_EHIP;
   ClaimArgs claim{};
   claim.B = B;
   claim.size = (uint32_t)p->size;
@@ -523,6 +593,7 @@ int per_update_td(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d_td
   if (!(eps >= 0.0) || !isfinite(eps) || !(alpha >= 0.0) || !isfinite(alpha)) return PER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   CaptureGuard capture(p, s);
+  if (prepare_tree_pass(p, s) != hipSuccess) return PER_EHIP;
   ClaimArgs claim{};
   claim.B = B;
   claim.size = (uint32_t)p->size;
@@ -646,6 +717,7 @@ int per_rebuild(per_t* p, void* stream) {
   if (!p) return PER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   CaptureGuard capture(p, s);
+  if (settle_side(p, s) != hipSuccess) return PER_EHIP;   // (the word that names the side array goes back to "level array")
   // all leaves count as touched: every height is recomputed in full, bottom-up
   hipError_t e = launch_resum_ranges(p->g, p->tn, Range2{0, p->g.N, 0, 0}, s);
   if (e != hipSuccess) return PER_EHIP;
@@ -667,6 +739,7 @@ int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint6
   if (!d_out) return PER_OK;
   if (misaligned(d_out, 4)) return PER_EINVAL;
   CaptureGuard capture(p, static_cast<hipStream_t>(stream));
+  if (height == p->g.step_ho && settle_side(p, static_cast<hipStream_t>(stream)) != hipSuccess) return PER_EHIP;
   if (p->stale_hb && height > p->stale_hb && ensure_top(p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return PER_EHIP;
   const float* src = p->g.level[height] + (size_t)tree * p->g.stride[height];
@@ -799,6 +872,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "group_claim")) {
     if (value != 0 && value != 1) return PER_EINVAL;
     p->tn.group_claim = (uint32_t)value;
+    return PER_OK;
+  }
+  if (!strcmp(name, "step_kernel")) {
+    if (value != 0 && value != 1) return PER_EINVAL;
+    p->tn.step_kernel = (uint32_t)value;
     return PER_OK;
   }
   if (!strcmp(name, "claim_in_sample")) {

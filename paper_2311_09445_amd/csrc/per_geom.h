@@ -46,7 +46,12 @@ struct Geom {
   uint32_t* min1;                   // [T][min1_stride] smallest positive leaf under each height-1 node (fp32 bits; kNoMin: none)
   uint32_t min1_stride;
   uint32_t* vmin_buf;               // [T][kMinParts] partial minima of min1 (fp32 bits), one per workgroup of k_min_reduce
+  uint32_t step_ho;                 // owner height of the one-kernel step (0: that kernel does not fit this tree)
+  float*   step_side;               // [T][step_side_stride] second array for the nodes of height step_ho
+  uint32_t step_side_stride;
+  uint32_t* step_ctl;               // [T][4] control words of the one-kernel step
 };
+uint32_t step_owner_height(const Geom& g);   // (needs K, logK, H, T, n[])
 constexpr uint32_t kMinParts = 1024;     // most workgroups k_min_reduce is launched with
 constexpr uint32_t kStaticMinTrees = 64; // most trees per_min_priority_static serves (its static array: 64 x 1024 words = 256 KiB per GPU)
 
@@ -79,6 +84,7 @@ constexpr uint32_t kGroupStampTurn = 1u << 25;
 // An update may leave the heights above its tree pass's workgroup roots to their next reader while that
 // height has at most this many nodes.
 constexpr uint32_t kLazyTopNodes = 4096;
+constexpr uint32_t kStepSideStride = kLazyTopNodes + 64;   // floats per tree of the one-kernel step's side array
 constexpr uint32_t kGroupClaimMaxBatch = kGroupStampTurn;
 
 // Claim phase of a priority update (first half of per_update).
@@ -161,7 +167,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_UPDATE_DELTA, KID_GET_PRIORITY,
-  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_MIN_REBUILD, KID_MIN_REDUCE, KID_COUNT
+  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_MIN_REBUILD, KID_MIN_REDUCE, KID_STEP, KID_STEP_SETTLE, KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -184,6 +190,7 @@ struct Tuning {
   uint32_t insert_small;      // small inserts run as one kernel (one workgroup per tree)
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   uint32_t group_claim;       // update batches claim through the group entries whenever they are short enough
+  uint32_t step_kernel;       // per_step runs sampling and update as one kernel where that kernel fits
   Profiler* prof;
   int device;                 // the device the buffer lives on
 };
@@ -214,6 +221,12 @@ uint32_t lazy_top_height(const Geom& g, const Tuning& tn);
 hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s);
 hipError_t launch_update_delta(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
                                const float* delta, hipStream_t s);
+uint32_t step_fits(const Geom& g, uint32_t B);
+hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, uint32_t B, uint32_t size, float beta,
+                       const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio,
+                       uint32_t weight_mode, const FieldTable* rows, const float* upd_prio, const uint32_t* upd_pos,
+                       hipStream_t s);
+hipError_t launch_step_settle(const Geom& g, const Tuning& tn, hipStream_t s);
 uint32_t stream_tree_floats(const Geom& g, uint32_t* off);
 hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s);
 hipError_t launch_run_requests(const Geom& g, const Tuning& tn, const QueueArgs& a, hipStream_t s);

@@ -24,7 +24,8 @@ const char* kernel_name(int kid) {
   static const char* const names[KID_COUNT] = {
       "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_finish", "k_rows_scatter", "k_insert_leaves",
       "k_resum_dense", "k_resum_tail", "k_update_claim", "k_update_tree", "k_tree_finish", "k_update_delta",
-      "k_get_priority", "k_insert_small", "k_run_steps", "k_run_requests", "k_min_rebuild", "k_min_reduce"};
+      "k_get_priority", "k_insert_small", "k_run_steps", "k_run_requests", "k_min_rebuild", "k_min_reduce", "k_step",
+      "k_step_settle"};
   return kid >= 0 && kid < KID_COUNT ? names[kid] : "?";
 }
 
@@ -98,6 +99,7 @@ static hipError_t grant_lds(const Tuning& tn, size_t bytes) {
 #include "k_resum.h"
 #include "k_insert.h"
 #include "k_tree.h"
+#include "k_step.h"
 #include "k_delta.h"
 #include "k_stream.h"
 #include "k_retrieve.h"

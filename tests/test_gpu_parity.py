@@ -766,12 +766,15 @@ def test_captured_step_replays(K, N, B):
 @pytest.mark.parametrize("K,N,T,B,fb", [(32, 1 << 20, 1, 30000, (128,)), (16, 1 << 18, 3, 1024, (68, 24, 4, 68, 1)),
                                         (2, 5000, 1, 64, ()), (4, 70001, 2, 3000, (12,)), (64, 300001, 1, 5000, (8,)),
                                         (8, 1 << 21, 1, 9000, ())])
-def test_step_call_updates_the_batch_it_draws(K, N, T, B, fb):
+@pytest.mark.parametrize("one_kernel", [1, 0])
+def test_step_call_updates_the_batch_it_draws(K, N, T, B, fb, one_kernel):
     """per_step: the update targets the leaves drawn by this very call, directly or through a position map
-    (the duplicate map of the stress workload; maps with many elements on one sample; invalid positions)."""
-    log(f"per_step K={K} N={N} T={T} B={B}")
+    (the duplicate map of the stress workload; maps with many elements on one sample; invalid positions).
+    Run with sampling and update as one kernel (where the tree takes it) and as separate kernels."""
+    log(f"per_step K={K} N={N} T={T} B={B} one_kernel={one_kernel}")
     rng = np.random.default_rng(K * 31 + B)
     m = Mirror(K, N, T, fb)
+    m.gpu.set_tuning("step_kernel", one_kernel)
     prio = wl._draw_priorities("pareto_1.5", rng, (T, N))
     prio[rng.random((T, N)) < 0.01] = 0.0
     m.insert(N, prio=prio, chunk=1 << 18)
@@ -795,6 +798,56 @@ def test_step_call_updates_the_batch_it_draws(K, N, T, B, fb):
         m.compare_tree()
         if it % 4 == 2:
             assert m.gpu.status() & (FLAG_BAD_INDEX | FLAG_BAD_PRIORITY) == (FLAG_BAD_INDEX | FLAG_BAD_PRIORITY)
+    m.compare_status()
+
+
+@pytest.mark.parametrize("K,N,T,B", [(32, 1 << 20, 1, 8192), (16, 1 << 18, 2, 2048), (8, 1 << 18, 1, 4096), (64, 1 << 19, 1, 3000)])
+def test_step_call_when_the_mass_sits_in_few_places(K, N, T, B):
+    """The samples of one subtree are one workgroup's work in the one-kernel step.  Here nearly all mass sits in one
+    leaf (a run of several thousand equal samples), then in one subtree spread over many leaves, then at the two
+    ends of the tree, then nowhere but one leaf; runs far longer than a workgroup go through the chunked path."""
+    log(f"per_step, concentrated mass K={K} N={N} T={T} B={B}")
+    rng = np.random.default_rng(K + B)
+    m = Mirror(K, N, T, ())
+    base = (rng.random((T, N)).astype(np.float32) * 0.5 + 0.25).astype(np.float32)
+    m.insert(N, prio=base, chunk=1 << 18, with_rows=False)
+    hot = N // 3 + 5
+    span = np.arange(hot, hot + 3000, dtype=np.uint32)
+    stages = [
+        (np.array([hot], dtype=np.uint32), np.float32(3e6)),                       # one leaf holds most of the mass
+        (span, np.float32(2e3)),                                                  # one stretch of leaves does
+        (np.array([0, 1, N - 2, N - 1], dtype=np.uint32), np.float32(5e6)),       # the two ends of the tree
+    ]
+    for idx, value in stages:
+        ii = np.tile(idx, (T, 1))
+        m.update(ii, np.full(ii.shape, value, dtype=np.float32))
+        for rep in range(2):
+            u = wl.uniform01(rng, (T, B))
+            pr = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B))
+            pos = None
+            if rep == 1:
+                pos = np.stack([rng.permutation(B) for _ in range(T)]).astype(np.uint32)
+                nn = min(pos[:, ::9].shape[1], pos[:, 1::9].shape[1])
+                pos[:, 0:9 * nn:9] = pos[:, 1::9][:, :nn]
+            m.step_call(u, 0.5, True, pr, pos)
+            m.compare_tree()
+    # everything to zero but one leaf
+    every = np.tile(np.arange(N, dtype=np.uint32), (T, 1))
+    zeros = np.zeros((T, N), dtype=np.float32)
+    zeros[:, N // 2] = 0.75
+    m.update(every, zeros)
+    u = wl.uniform01(rng, (T, B))
+    m.step_call(u, 0.5, True, wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B)), None)
+    m.compare_tree()
+    # and an empty total: nothing sampled, every element invalid
+    m.update(np.full((T, 1), N // 2, dtype=np.uint32), np.zeros((T, 1), dtype=np.float32))
+    for pos in (None, np.tile(np.arange(B, dtype=np.uint32)[::-1].copy(), (T, 1))):
+        m.step_call(u, 0.5, True, wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B)), pos)
+        assert m.gpu.status() & FLAG_ZERO_TOTAL
+        m.compare_tree()
+    m.insert(3, prio=np.full((T, 3), 0.5, dtype=np.float32), with_rows=False)
+    m.step_call(u, 0.5, True, wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B)), None)
+    m.compare_tree()
     m.compare_status()
 
 
