@@ -33,6 +33,11 @@ __global__ void k_init_scalars(Geom g, float init_max) {
   g.vcur[t] = 0;
   g.sbase[t] = 1;
   g.sfloor[t] = 1;
+  if (g.step_ho) {
+    for (uint32_t k = 0; k < kStepGroups; ++k) g.step_cnt[(size_t)t * kStepGroups + k] = 0ull;
+    for (uint32_t k = 0; k < 2 * kStepDoneSlots; ++k) g.step_done[(size_t)t * 2 * kStepDoneSlots + k] = 0u;
+    for (uint32_t k = 0; k < 2 * kVminSlots; ++k) g.step_vmin[(size_t)t * 2 * kVminSlots + k] = kNoMin;
+  }
 }
 
 hipError_t launch_init_scalars(const Geom& g, float init_max, hipStream_t s) {

@@ -1,20 +1,29 @@
-// One iteration of Listing 2 whose update targets the batch it draws, with sampling and update in one kernel.
+// One iteration of Listing 2 whose update targets the batch it draws: sampling, rows and update as one kernel.
 // Part of per_kernels.hip (included inside namespace per, in the order given there); not a stand-alone header.
 
 // ---------------------------------------------------------------------------------
-// sampling and the update of the sampled batch, one workgroup per subtree
+// the whole step, one workgroup per subtree
 // ---------------------------------------------------------------------------------
 // Stratified targets grow with the sample number and the walk is monotone in the target, so the samples
 // that end under one node of the tree are a contiguous run of sample numbers.  Workgroup b of tree t owns
 // the subtree under node b of height ho ("owner height").  It finds its run of samples, walks them down
-// (the heights ho .. H-1 of the whole tree and the heights 1 .. ho-1 of its own subtree from LDS copies, the
-// leaf groups from memory), and then applies the update of exactly those samples to its own subtree:
-// every leaf, every height-1 node and every higher node of the subtree is read and written by this
-// workgroup only, so the update needs no claim phase, no atomics and no second pass over the leaf groups
-// (they are still in LDS from the walk).  Sampling sees the tree as it was before the call because a
-// workgroup finishes all its walks before it changes anything, and what all workgroups read, the nodes of
-// height ho, is never written in place: the new value of node b goes to the other one of two arrays (the
-// level array itself and a side array), and the workgroup that finishes last makes that one current.
+// (the way from the root to node b is the same for all of them, so it is tabulated once; the heights
+// 1 .. ho-1 of its own subtree come from an LDS copy, the leaf groups from memory), moves their rows, and
+// then applies the update of exactly those samples to its own subtree: every leaf, every height-1 node and
+// every higher node of the subtree is read and written by this workgroup only, so the update needs no claim
+// phase, no atomics and no second pass over the leaf groups (they are still in LDS from the walk).
+// Sampling sees the tree as it was before the call because a workgroup finishes all its walks before it
+// changes anything, and what all workgroups read, the nodes of height ho, is never written in place: the
+// new value of node b goes to the other one of two arrays (the level array itself and a side array).
+// Which one is current follows from how many calls have run, and that is counted on the device: every
+// owner adds one to a counter when it is done (the owners are spread over kStepGroups counters, because
+// atomics on one address queue up), so counter i holds calls * (owners of group i) between calls, and a
+// workgroup that reads its own group's counter when it starts gets the number of finished calls whatever
+// the others have already added.  The importance weights are relative to the batch minimum of the sampled
+// values, which is known only when every owner is done: the owners leave their values and, in slots, their
+// minima, and a small second kernel (k_step_weights) turns the values into weights.  (Owners that wait for
+// each other inside the kernel were tried: 512 workgroups polling the counters slowed the very atomics
+// they waited for, + 9 us.)
 // The heights above ho are rebuilt in LDS from height ho by every workgroup (a few child groups) and are
 // left stale in memory, as after any update.
 //
@@ -28,7 +37,8 @@ constexpr int kStepTop = 4;          // most heights ho .. H-1
 constexpr int kStepSub = 4;          // most heights 1 .. ho-1
 constexpr uint32_t kStepPad = 4;     // sample numbers looked at in front of the estimated start of the run
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
-constexpr uint32_t kStepSpinLimit = 1u << 20;   // polls of the builders' counter before an owner gives up
+constexpr uint32_t kStepSpinLimit = 1u << 20;   // polls of a counter before a workgroup gives up
+constexpr int kStepPathMax = kStepTop * 6;      // binary steps from the root to a node of the owner height
 
 struct StepShape {
   float* top_ptr[kStepTop];        // height ho + i of tree 0 (i = 0: the level array of height ho)
@@ -42,16 +52,50 @@ struct StepShape {
   uint32_t sub_pad[kStepSub];      // nodes of that height in memory, padded to whole groups
   uint32_t sub_off[kStepSub];      // where in LDS (floats)
   uint32_t n_top, n_sub;           // H - ho, ho - 1
+  uint32_t path_off;               // LDS: the way from the root to node b: kStepPathMax entries of (left sum, flags)
   uint32_t rows_off;               // LDS: (block + 1) staging rows of K + 4 floats (16-byte aligned)
   uint32_t key_off;                // LDS: key[block + 2], wpos[block + 1], wval[block + 1], touch[block + 1]
   uint32_t owners;                 // n[ho]: owner workgroups per tree
   uint32_t builders;               // builder workgroups per tree in front of them (0: no position map)
   float* side;                     // [T][side_stride] second array for the nodes of height ho
   uint32_t side_stride;
-  uint32_t* ctl;                   // [T][4]: which array is current (0: the level array), builders done, owners done, spare
+  unsigned long long* cnt;         // [T][kStepGroups] finished owners of group i, over all calls
+  uint32_t* done;                  // [T][2][kStepDoneSlots] finished builders of this call (by parity of the call number)
+  uint32_t* vmin;                  // [T][2][kVminSlots] smallest sampled values of this call (fp32 bits; by parity)
   uint32_t* inv;                   // [T][inv_stride] per sample: 1 + the largest update element aimed at it (zero between calls)
   uint32_t inv_stride;
 };
+
+__device__ __forceinline__ uint32_t owners_of_group(uint32_t owners, uint32_t i) {
+  return i < owners ? (owners - i + kStepGroups - 1u) / kStepGroups : 0u;
+}
+__device__ __forceinline__ unsigned long long load_counter(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Balanced pairwise sum of the 2^m floats at p (half a child group at most: m < LOGK), in the order of group_sum and
+// of the walk inside a group.
+template <int LOGK>
+__device__ __forceinline__ float block_sum(const float* p, uint32_t m) {
+  if (m == 0) return p[0];
+  if (m == 1) return p[0] + p[1];
+  constexpr int MAXC = (1 << LOGK) / 8 > 1 ? (1 << LOGK) / 8 : 1;   // most chunks of four in half a group
+  const uint32_t nc = 1u << (m - 2);
+  float s[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    const float4 x = *reinterpret_cast<const float4*>(p + 4 * ((uint32_t)c < nc ? c : 0));
+    s[c] = (x.x + x.y) + (x.z + x.w);
+  }
+#pragma unroll
+  for (int w = MAXC; w > 1; w >>= 1) {
+    if ((uint32_t)w <= nc) {
+#pragma unroll
+      for (int c = 0; c < w / 2; ++c) s[c] = s[2 * c] + s[2 * c + 1];
+    }
+  }
+  return s[0];
+}
 
 // Pairwise sum of the K floats of a staged row, in the order of group_sum.
 template <int LOGK>
@@ -129,7 +173,7 @@ __device__ __forceinline__ void chunk_leaves(const ChunkLds& c, uint32_t slot, u
     const uint32_t h = group_head<LOGK>(c, j);
     c.rows[(size_t)h * ROW + (k & (uint32_t)(K - 1))] = bv;
     c.touch[h] = 1u;
-    leaves[k] = bv;
+    __builtin_nontemporal_store(bv, leaves + k);   // (leaves the cache while the kernel goes on, not when it ends)
   }
 }
 // Phase B: the slot that ends a group's run recomputes the height-1 node from the head's row.  Returns the head
@@ -148,41 +192,92 @@ __device__ __forceinline__ uint32_t chunk_groups(const ChunkLds& c, uint32_t slo
   if (open) return h;
   if (c.touch[h]) {
     const float sum = row_sum<LOGK>(c.rows + (size_t)h * ROW);
-    lvl1[g] = sum;
+    __builtin_nontemporal_store(sum, lvl1 + g);
     sub1[g - lo1] = sum;
   }
   return kNoKey;
 }
 
-template <int LOGK>
+
+// The rows of samples [first, first + count) of tree t, moved by the calling workgroup alone (field f; V: access width).
+template <typename V>
+__device__ __forceinline__ void step_rows(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B, uint32_t first, uint32_t count,
+                                          const uint32_t* idx, uint32_t N, bool& bad) {
+  constexpr int U = InFlight<V>::U;
+  RowMove m;
+  const uint32_t E = ft.bytes[f];
+  m.RS = ft.row_stride;
+  m.epr = E / (uint32_t)sizeof(V);
+  m.total = (uint64_t)count * m.epr;
+  m.col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
+  m.io = ft.io[f] + ((uint64_t)t * B + first) * E;
+  m.idx = idx + (size_t)t * B + first;
+  m.stride = blockDim.x;
+  m.cursor = 0;
+  m.N = N;
+  for (uint64_t e0 = threadIdx.x; e0 < m.total; e0 += U * m.stride) {
+    Regs<uint32_t, U> at;
+    Regs<Held<V>, U> v;
+    sweep_where<V, true, 0, U>(m, e0, at);
+    sweep_load<V, true, 0, U>(m, e0, at, v, bad);
+    sweep_store<V, true, 0, U>(m, e0, at, v);
+  }
+}
+__device__ __forceinline__ void step_rows_wide(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B, uint32_t first,
+                                               uint32_t count, const uint32_t* idx, uint32_t N, bool& bad) {
+  constexpr int U = 2;
+  WideMove w;
+  RowMove& m = w.m;
+  w.E = ft.bytes[f];
+  m.RS = ft.row_stride;
+  m.epr = (w.E + 15u) / 16u;
+  m.total = (uint64_t)count * m.epr;
+  m.col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
+  m.io = ft.io[f] + ((uint64_t)t * B + first) * w.E;
+  m.idx = idx + (size_t)t * B + first;
+  m.stride = blockDim.x;
+  m.cursor = 0;
+  m.N = N;
+  for (uint64_t e0 = threadIdx.x; e0 < m.total; e0 += U * m.stride) {
+    Regs<uint32_t, U> at;
+    Regs<uint4, U> v;
+    sweep_where<uint4, true, 0, U>(m, e0, at);
+    wide_load<true, 0, U>(w, e0, at, v, bad);
+    wide_store<true, 0, U>(w, e0, at, v);
+  }
+}
+
+template <int LOGK, bool WIDE>
 __global__ void __launch_bounds__(512)
-k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict__ u, RngArgs rng,
-       uint32_t* __restrict__ out_idx, float* __restrict__ out_prio, float* __restrict__ out_w,
-       const float* __restrict__ upd_prio, const uint32_t* __restrict__ upd_pos) {
+k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t weight_mode, const float* __restrict__ u,
+       RngArgs rng, uint32_t* out_idx, float* __restrict__ out_prio, float* out_w,
+       const float* __restrict__ upd_prio, const uint32_t* __restrict__ upd_pos, FieldTable ft, uint32_t has_rows,
+       uint32_t early_field) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   constexpr int ROW = K + 4;
   static_assert(LOGK >= 3, "the staged walk needs K >= 8");
+  touch_kernel_arguments<kernarg_lines<Geom, StepShape, uint32_t, uint32_t, float, uint32_t, const float*, RngArgs, uint32_t*,
+                                       float*, float*, const float*, const uint32_t*>()>();
   extern __shared__ __attribute__((aligned(16))) float lds[];
   __shared__ uint32_t s_u32[8];
-  __shared__ double s_est;
   const uint32_t t = blockIdx.y;
   const uint32_t tid = threadIdx.x;
   const uint32_t BD = blockDim.x;
   const unsigned lane = tid & 63u;
   const unsigned wave = tid >> 6;
-  uint32_t* ctl = sh.ctl + (size_t)t * 4;
+  const unsigned long long* cnt = sh.cnt + (size_t)t * kStepGroups;
   uint32_t* inv = sh.inv + (size_t)t * sh.inv_stride;
   const int n_top = (int)sh.n_top, n_sub = (int)sh.n_sub;
-
-  // which of the two arrays holds the nodes of height ho (stable while this kernel runs: the workgroup that
-  // finishes last flips it)
-  const uint32_t sel = read_word_with_the_loads(ctl) & 1u;
-  const float* cur_ho = sel ? sh.side + (size_t)t * sh.side_stride : sh.top_ptr[0] + (size_t)t * sh.top_stride[0];
-  float* new_ho = sel ? sh.top_ptr[0] + (size_t)t * sh.top_stride[0] : sh.side + (size_t)t * sh.side_stride;
+  float* lvl_ho = sh.top_ptr[0] + (size_t)t * sh.top_stride[0];
+  float* side_ho = sh.side + (size_t)t * sh.side_stride;
 
   // ------------------------------------------------------------------ builder workgroups (position map only)
   if (blockIdx.x < sh.builders) {
+    // (the owners of this call cannot finish before every builder has, so the count of group 0 is still that of the calls before)
+    const unsigned long long calls = load_counter(cnt) / owners_of_group(sh.owners, 0);
+    const uint32_t par = (uint32_t)calls & 1u;
+    const float* cur_ho = par ? side_ho : lvl_ho;
     const uint32_t max_seen = read_max_bits(g, t);
     uint32_t mx = 0, f_idx = 0, f_prio = 0, acc = 0;
     for (uint32_t j = blockIdx.x * BD + tid; j < B; j += sh.builders * BD) {
@@ -208,14 +303,17 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
     }
     asm volatile("" ::"v"(acc));
     __syncthreads();   // every lane's atomics have returned
-    if (tid == 0) atomicAdd(ctl + 1, 1u);
+    if (tid == 0) atomicAdd(sh.done + ((size_t)t * 2 + par) * kStepDoneSlots + blockIdx.x % kStepDoneSlots, 1u);
     return;
   }
 
   // ------------------------------------------------------------------ owner workgroup b
   const uint32_t b = blockIdx.x - sh.builders;
+  const uint32_t my_group = b % kStepGroups;
   float* top = lds;                                   // heights ho .. H-1, at top_off[i]
   float* sub = lds;                                   // heights 1 .. ho-1 of the own subtree, at sub_off[i]
+  // per binary step from the root to b: the sum of the left block; bit 0: b lies to the right, bit 1: the right block is not zero
+  float2* path = reinterpret_cast<float2*>(lds + sh.path_off);
   ChunkLds c;
   c.rows = lds + sh.rows_off;
   c.key = reinterpret_cast<uint32_t*>(lds + sh.key_off);
@@ -225,11 +323,23 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
 
   PER_TRACE_DECL;
   PER_MARK(0);
-  // ---- trip 1: height ho of the whole tree, the own subtree's heights, control words
-  uint32_t vbuf = 0;
-  if (out_w) vbuf = read_word_with_the_loads(g.vnext + t);
+  PER_MARK_HWID(15);
+  // ---- trip 1: the number of finished calls, both arrays of height ho, the own subtree's heights, the running maximum
+  unsigned long long count0 = 0;
+  {
+    uint32_t zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));   // (a lane offset the compiler cannot see through: the word travels with the loads below)
+    count0 = __hip_atomic_load(cnt + my_group + zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   const uint32_t max_seen = read_max_bits(g, t);
-  for (uint32_t i = tid; i < sh.top_cnt[0]; i += BD) top[sh.top_off[0] + i] = i < sh.top_n[0] ? cur_ho[i] : 0.0f;
+  float ho_a[4], ho_b[4];   // up to four nodes per lane of either array (more: a loop below)
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t i = tid + (uint32_t)k * BD;
+    const bool real = i < sh.top_n[0];
+    ho_a[k] = real ? lvl_ho[i] : 0.0f;
+    ho_b[k] = real ? side_ho[i] : 0.0f;
+  }
 #pragma unroll
   for (int i = 0; i < kStepSub; ++i) {
     if (i < n_sub) {
@@ -239,9 +349,19 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
         sub[sh.sub_off[i] + e] = first + e < sh.sub_pad[i] ? src[first + e] : 0.0f;
     }
   }
+  const unsigned long long calls = count0 / owners_of_group(sh.owners, my_group);
+  const uint32_t par = (uint32_t)calls & 1u;          // odd: the side array is the current one
+  const float* cur_ho = par ? side_ho : lvl_ho;
+  float* new_ho = par ? lvl_ho : side_ho;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t i = tid + (uint32_t)k * BD;
+    if (i < sh.top_cnt[0]) top[sh.top_off[0] + i] = par ? ho_b[k] : ho_a[k];
+  }
+  for (uint32_t i = tid + 4u * BD; i < sh.top_cnt[0]; i += BD) top[sh.top_off[0] + i] = i < sh.top_n[0] ? cur_ho[i] : 0.0f;
   __syncthreads();
-  // the heights above ho, from LDS (in memory they may be stale)
   PER_MARK(1);
+  // the heights above ho, from LDS (in memory they may be stale)
   {
     const unsigned q = tid % LPS;
     const uint32_t grp = tid / LPS, ngrp = BD / LPS;
@@ -258,6 +378,29 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
       }
     }
   }
+  // the way from the root to node b, one binary step per lane: step k halves the block of the child group of
+  // height ho + i that holds b's ancestor (i = n_top-1 first), and notes the sums of the two halves
+  const uint32_t n_steps = (uint32_t)n_top * LOGK;
+  double mass = 0.0;
+  if (tid < n_steps) {
+    const uint32_t i = (uint32_t)n_top - 1u - tid / LOGK, m = LOGK - 1u - tid % LOGK;   // height ho + i; halves of 2^m nodes
+    uint32_t off_i = sh.top_off[0];
+#pragma unroll
+    for (int k = 1; k < kStepTop; ++k)
+      if ((uint32_t)k == i) off_i = sh.top_off[k];
+    const uint32_t anc = shr64(b, i * LOGK);                 // b's ancestor at height ho + i
+    const uint32_t pos = anc & (uint32_t)(K - 1);
+    const float* blk = top + off_i + (size_t)(anc - pos) + ((pos >> (m + 1)) << (m + 1));
+    const float left = block_sum<LOGK>(blk, m), right = block_sum<LOGK>(blk + (1u << m), m);
+    const uint32_t turn = (pos >> m) & 1u;
+    path[tid] = make_float2(left, __uint_as_float(turn | (right != 0.0f ? 2u : 0u)));
+    if (turn) mass = (double)left;
+  }
+  // (b) where this workgroup's run of samples starts, to within a few: the mass in front of node b over seg
+  if (wave == 0) {
+#pragma unroll
+    for (int mm = 1; mm < 32; mm <<= 1) mass += __shfl_xor(mass, mm);
+  }
   float total;
   {
     const float* rootgrp = top;   // group 0 of height H-1
@@ -266,45 +409,54 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
       if (i == n_top - 1) rootgrp = top + sh.top_off[i];
     total = row_sum<LOGK>(rootgrp);
   }
-  const bool leader = b == 0 && tid == 0;
+  if (tid == 0) {
+    const double est = mass / ((double)total / (double)B);
+    const uint32_t s_guess = est >= (double)B ? B : (est > 0.0 ? (uint32_t)est : 0u);   // (not a number: 0)
+    s_u32[5] = s_guess > kStepPad ? s_guess - kStepPad : 0u;
+  }
+  __syncthreads();
   PER_MARK(2);
+  const bool leader = b == 0 && tid == 0;
 
-  // The end of every owner: the last one to finish makes the other array of height ho current (if the tree was
-  // changed) and puts the counters back to zero for the next call.
-  auto finish_owner = [&](bool changed) {
-    if (leader && out_w) g.vcur[t] = not_before_here(vbuf) & 1u;
-    __syncthreads();   // this workgroup's lanes have issued all their stores
-    if (tid == 0) {
-      const uint32_t old = atomicAdd(ctl + 2, 1u);
-      if (old == sh.owners - 1u) {
-        if (changed) ctl[0] = sel ^ 1u;
-        ctl[1] = 0u;
-        ctl[2] = 0u;
-      }
-    }
+  // This owner is done: one more in its group's counter (no answer is waited for).
+  auto count_me_in = [&]() {
+    __syncthreads();   // every lane of the workgroup has issued its stores
+    if (tid == 0) atomicAdd(sh.cnt + (size_t)t * kStepGroups + my_group, 1ull);
   };
-  // Waits until every builder workgroup has recorded its elements.  The builders come first in the grid and wait
-  // for nothing, so the wait ends; it is bounded all the same, and a workgroup that gives up says so.
+  // The words of the next call's parity start empty (nothing of this call touches them).
+  auto arm_next_call = [&]() {
+    if (b != 0) return;
+    for (uint32_t i = tid; i < kVminSlots; i += BD) sh.vmin[((size_t)t * 2 + (par ^ 1u)) * kVminSlots + i] = 0x7F800000u;
+    if (tid < kStepDoneSlots) sh.done[((size_t)t * 2 + (par ^ 1u)) * kStepDoneSlots + tid] = 0u;
+  };
+  // Waits (bounded) until every builder workgroup has recorded its elements.  The builders come first in the grid
+  // and wait for nothing, so the wait ends; a workgroup that gives up says so in the status word.
   auto wait_for_builders = [&]() -> bool {
     if (!sh.builders) return true;
-    if (tid == 0) {
+    if (wave == 0) {
       uint32_t spins = 0, ok = 1;
-      while (__hip_atomic_load(ctl + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < sh.builders) {
+      const uint32_t* slot = sh.done + ((size_t)t * 2 + par) * kStepDoneSlots;
+      for (;;) {
+        uint32_t d = lane < kStepDoneSlots ? __hip_atomic_load(slot + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+#pragma unroll
+        for (int m = 1; m < (int)kStepDoneSlots; m <<= 1) d += (uint32_t)__shfl_xor((int)d, m);
+        if (__shfl((int)d, 0) >= (int)sh.builders) break;
         if (++spins > kStepSpinLimit) {
           ok = 0;
           break;
         }
-        __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_s_sleep(4);
       }
-      s_u32[0] = ok;
-      if (!ok) atomicOr(&g.status[t], 8u);
+      if (lane == 0) {
+        s_u32[0] = ok;
+        if (!ok) atomicOr(&g.status[t], 8u);
+      }
     }
     __syncthreads();
     const bool ok = s_u32[0] != 0;
     __syncthreads();
     return ok;
   };
-
   if (!(total > 0.0f)) {   // nothing can be sampled from this tree; workgroup b reports a slice of the batch
     const bool waited = wait_for_builders();
     for (uint32_t s = b * BD + tid; s < B; s += sh.owners * BD) {
@@ -312,65 +464,50 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
       out_idx[o] = 0xFFFFFFFFu;
       if (out_prio) out_prio[o] = 0.0f;
       if (out_w) out_w[o] = 0.0f;
-      if (sh.builders && waited) inv[s] = 0u;   // (the builders have recorded nothing: no element is valid)
+      if (sh.builders && waited) inv[s] = 0u;   // (what the builders have recorded goes unused: no element is valid)
     }
     // (without a map every element is out of range too; with one the builders have said so)
     if (leader) atomicOr(&g.status[t], sh.builders ? 4u : 5u);
-    finish_owner(false);
+    if (tid == 0) new_ho[b] = top[sh.top_off[0] + b];   // the call counts all the same, so the other array becomes current
+    arm_next_call();
+    count_me_in();
     return;
   }
   const float seg = total / (float)B;
 
-  // ---- where this workgroup's run of samples starts, to within a few: the mass in front of node b over seg
-  if (wave == 0) {
-    double p = 0.0;
-    for (uint32_t e = lane; e < (uint32_t)n_top * K; e += 64) {
-      const uint32_t i = e >> LOGK, j = e & (uint32_t)(K - 1);
-      const uint32_t node = shr64(b, i * LOGK), sib = node & (uint32_t)(K - 1);
-      uint32_t off_i = sh.top_off[0];
+  // where a target lands relative to node b: 0 in front of it, 1 in its subtree (r then holds what is left of the
+  // target inside it), 2 behind it.  The same comparisons and subtractions as the walk through the child groups.
+  auto landing = [&](float& r) -> uint32_t {
+    for (int lv = 0; lv < n_top; ++lv) {   // the steps inside one child group: their table entries are read together
+      float2 e[LOGK];
 #pragma unroll
-      for (int k = 1; k < kStepTop; ++k)
-        if ((uint32_t)k == i) off_i = sh.top_off[k];
-      if (j < sib) p += (double)top[off_i + (node - sib) + j];
-    }
+      for (int j = 0; j < LOGK; ++j) e[j] = path[lv * LOGK + j];
 #pragma unroll
-    for (int m = 1; m < 64; m <<= 1) p += __shfl_xor(p, m);
-    if (lane == 0) s_est = p / (double)seg;
-  }
-  __syncthreads();
-  const double est = s_est;
-  PER_MARK(3);
-  const uint32_t s_guess = est >= (double)B ? B : (est > 0.0 ? (uint32_t)est : 0u);   // (not a number: 0)
-  uint32_t s0 = s_guess > kStepPad ? s_guess - kStepPad : 0u;
-
-  // walks a target down the heights H-1 .. ho in LDS; returns the node of height ho it lands in
-  auto walk_top = [&](float& r, float& val) -> uint32_t {
-    uint32_t node = 0;
-#pragma unroll
-    for (int i = kStepTop - 1; i >= 0; --i) {
-      if (i < n_top) {
-        unsigned child;
-        descend_lane<LOGK>(top + sh.top_off[i] + (size_t)node * K, r, child, val);
-        node = node * K + child;
+      for (int j = 0; j < LOGK; ++j) {
+        const float L = e[j].x;
+        const uint32_t fl = __float_as_uint(e[j].y);
+        const bool right = (fl & 2u) && !(r < L);
+        const bool want = (fl & 1u) != 0u;
+        if (right != want) return want ? 0u : 2u;
+        if (right) r = r - L;
       }
     }
-    return node;
+    return 1u;
   };
   auto uniform_of = [&](uint32_t s) -> float { return rng.on ? counter_uniform(rng, s, t) : u[(size_t)t * B + s]; };
-  // the node of height ho that sample s lands in (samples beyond the batch: beyond every node)
-  auto landing = [&](uint32_t s) -> uint32_t {
-    if (!(s < B)) return 0xFFFFFFFFu;
-    float r = ((float)s + uniform_of(s)) * seg, val = total;
-    return walk_top(r, val);
+  auto landing_of = [&](uint32_t s) -> uint32_t {   // (samples beyond the batch: behind every node)
+    if (!(s < B)) return 2u;
+    float r = ((float)s + uniform_of(s)) * seg;
+    return landing(r);
   };
-  // smallest s in [0, B] whose sample lands in a node >= bound; by one wave, 64 probes per round
-  auto first_at_or_after = [&](uint32_t bound) -> uint32_t {
+  // smallest s in [0, B] whose sample lands at or behind b (level 1) or behind it (level 2); one wave, 64 probes per round
+  auto first_at = [&](uint32_t level) -> uint32_t {
     uint32_t lo = 0, hi = B;
     while (lo < hi) {
       const uint32_t span = hi - lo, stride = (span + 63u) / 64u;
       const uint64_t s64 = (uint64_t)lo + (uint64_t)lane * stride;
       const bool probe = s64 < hi;
-      const bool ge = !probe || landing((uint32_t)s64) >= bound;
+      const bool ge = !probe || landing_of((uint32_t)s64) >= level;
       const unsigned long long m = __ballot(ge);
       if (m == 0ull) {
         lo = lo + 63u * stride + 1u;
@@ -384,52 +521,68 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
     return lo;
   };
 
+  const uint32_t s0 = s_u32[5];
+  PER_MARK(3);
+
   // ---- trip 2: the samples of the window [s0, s0 + BD): uniforms, their own new priorities
   uint32_t s = s0 + tid;
-  bool in = s < B;
+  const bool in = s < B;
   float u_s = in ? uniform_of(s) : 0.0f;
   float prio_s = in ? upd_prio[(size_t)t * B + s] : 0.0f;
   float r = ((float)s + u_s) * seg, val = total;
-  uint32_t node_ho = in ? walk_top(r, val) : 0xFFFFFFFFu;
+  const uint32_t where = in ? landing(r) : 2u;
   // does the window hold the whole run?  its first sample must land in front of b (or be sample 0), and a sample
   // of it must land behind b (or the batch must end in it)
+  uint32_t run_lo, run_n, n_front_lanes;
+  bool searched;   // (uniform over the workgroup)
   {
-    const int starts = tid == 0 && (s0 == 0 || node_ho < b) ? 1 : 0;
-    const int ends = (in && node_ho > b) || (tid == 0 && s0 + BD >= B) ? 1 : 0;
-    if (tid == 0) s_u32[1] = 0;
-    const int both = __syncthreads_or(starts) + 2 * __syncthreads_or(ends);
-    if (both != 3) {
-      // rare: the exact ends of the run by search, then chunks of it
+    if (tid == 0) s_u32[1] = (s0 == 0 || where == 0u) ? 1u : 0u;
+    const uint32_t n_front = (uint32_t)__syncthreads_count(in && where == 0u);
+    const uint32_t n_mine = (uint32_t)__syncthreads_count(in && where == 1u);
+    const bool complete = s_u32[1] != 0 && (n_front + n_mine < BD || s0 + BD >= B);
+    run_lo = s0 + n_front;
+    n_front_lanes = n_front;
+    run_n = n_mine;
+    if (!complete) {   // rare: the exact ends of the run by search, then chunks of it (uniform over the workgroup)
       if (wave == 0) {
-        const uint32_t lo = first_at_or_after(b), hi = first_at_or_after(b + 1u);
+        const uint32_t lo = first_at(1u), hi = first_at(2u);
         if (lane == 0) {
-          s_u32[1] = 1;
           s_u32[2] = lo;
           s_u32[3] = hi;
         }
       }
+      __syncthreads();
+      run_lo = s_u32[2];
+      run_n = s_u32[3] - s_u32[2];
     }
-    __syncthreads();
+    searched = !complete;
   }
-  PER_MARK(4);
-  const bool searched = s_u32[1] != 0;
-  const uint32_t run_lo = searched ? s_u32[2] : s0, run_hi = searched ? s_u32[3] : 0u;
-  const uint32_t n_chunks = searched ? (run_hi - run_lo + BD - 1u) / BD : 1u;
+  const uint32_t n_chunks = searched ? (run_n + BD - 1u) / BD : 1u;
   const bool two_phase = n_chunks > 1;
-  __syncthreads();
+  PER_MARK(4);
 
   const uint32_t lo1 = b * sh.sub_cnt[0];                                   // first height-1 node of the subtree
   float* leaves = g.level[0] + (size_t)t * g.stride[0];
   float* lvl1 = sh.sub_ptr[0] + (size_t)t * sh.sub_stride[0];
   float* stage = c.rows + (size_t)(1u + wave * 64u) * ROW;                  // this wave's rows: slots 1 + tid
   uint32_t mx = 0, flags = 0, vmin_bits = 0x7F800000u;
-  bool builders_ok = true, waited = false;
+  bool builders_ok = true, waited = false, bad_row = false;
   if (tid == 0) {
     c.key[0] = kNoKey;
     c.wpos[0] = 0;
     c.touch[0] = 0;
   }
   if (tid < 2) c.key[BD + tid] = kNoKey;   // (key[BD] is written again by the last lane; key[BD + 1] stays)
+
+  // Rows of a single 16-byte-wide field: the loads of the first kEarly pieces per lane are issued as soon as the
+  // indices are known and their stores wait until the update is through, so that trip to memory runs under it
+  // (the pieces beyond, if the run is long, move at the end).
+  const uint32_t early_epr = early_field < (uint32_t)kMaxFields ? ft.bytes[early_field < (uint32_t)kMaxFields ? early_field : 0u] / 16u : 0u;
+  constexpr int kEarly = 4;
+  const bool early_rows = has_rows && early_epr != 0u && !searched;
+  uint4 rv[kEarly];
+#pragma unroll
+  for (int k = 0; k < kEarly; ++k) rv[k] = make_uint4(0, 0, 0, 0);
 
   for (uint32_t pass = 0; pass < (two_phase ? 2u : 1u); ++pass) {
     // pass 0 walks (and, when one chunk holds the run, updates); pass 1 of a long run updates chunk by chunk
@@ -438,16 +591,16 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
       uint32_t idx = kNoKey;
       if (searched) {
         s = run_lo + ch * BD + tid;
-        member = s < run_hi;
-        if (pass == 0 || !two_phase) {
+        member = s < run_lo + run_n;
+        if (pass == 0) {
           u_s = member ? uniform_of(s) : 0.0f;
           r = ((float)s + u_s) * seg;
           val = total;
-          (void)walk_top(r, val);
+          (void)landing(r);
         }
         prio_s = member ? upd_prio[(size_t)t * B + s] : 0.0f;
       } else {
-        member = in && node_ho == b;
+        member = in && where == 1u;
       }
       const size_t o = (size_t)t * B + (member ? s : 0u);
       uint32_t x = b;   // node of height ho
@@ -479,12 +632,25 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
         idx = x * K + child;
         if (member) {
           out_idx[o] = idx;
-          if (out_prio) out_prio[o] = val;
-          if (out_w) out_w[o] = val;
+          if (out_prio) __builtin_nontemporal_store(val, out_prio + o);
+          if (out_w) __builtin_nontemporal_store(val, out_w + o);
           const uint32_t vb = __float_as_uint(val);
           vmin_bits = vb < vmin_bits ? vb : vmin_bits;
         }
         if (two_phase) continue;
+        if (early_rows) {
+          c.key[1 + tid] = member ? idx : kNoKey;
+          __syncthreads();
+          const uint8_t* col = ft.col[early_field] + (uint64_t)t * ft.col_stride[early_field];
+#pragma unroll
+          for (int k = 0; k < kEarly; ++k) {
+            const uint32_t e = tid + (uint32_t)k * BD;
+            const bool live = e < run_n * early_epr;
+            const uint32_t row = live ? e / early_epr : 0u;
+            const uint32_t leaf = live ? c.key[1u + n_front_lanes + row] : 0u;
+            rv[k] = *reinterpret_cast<const uint4*>(col + (uint64_t)leaf * ft.row_stride + (size_t)(e - row * early_epr) * 16u * (live ? 1u : 0u));
+          }
+        }
       }
       PER_MARK(5);
       // ---- the update of this chunk
@@ -589,29 +755,100 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, const float* __restrict_
     }
   }
   PER_MARK(8);
-  // ---- what is left: batch minimum for the weights, running maximum, flags
-  if (out_w) {
-    const uint32_t m = wave_min_u32(vmin_bits);
-    if (lane == 0 && m != 0x7F800000u)
-      atomicMin(&g.vmin[((size_t)(not_before_here(vbuf) & 1u) * g.T + t) * kVminSlots + ((b * (BD >> 6) + wave) % kVminSlots)], m);
+  // ---- the rows of this workgroup's samples (their indices, written above, are read back: a barrier lies between)
+  if (early_rows) {
+    uint8_t* io = ft.io[early_field] + ((uint64_t)t * B + run_lo) * ft.bytes[early_field];
+    const uint8_t* col = ft.col[early_field] + (uint64_t)t * ft.col_stride[early_field];
+    const uint32_t pieces = run_n * early_epr;
+#pragma unroll
+    for (int k = 0; k < kEarly; ++k) {
+      const uint32_t e = tid + (uint32_t)k * BD;
+      if (e < pieces) {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 x = {rv[k].x, rv[k].y, rv[k].z, rv[k].w};
+        __builtin_nontemporal_store(x, reinterpret_cast<u32x4*>(io + (size_t)e * 16u));
+      }
+    }
+    for (uint32_t e = tid + (uint32_t)kEarly * BD; e < pieces; e += BD) {   // (the slots of this chunk still hold its indices)
+      const uint32_t row = e / early_epr;
+      const uint32_t leaf = c.key[1u + n_front_lanes + row];
+      *reinterpret_cast<uint4*>(io + (size_t)e * 16u) =
+          *reinterpret_cast<const uint4*>(col + (uint64_t)leaf * ft.row_stride + (size_t)(e - row * early_epr) * 16u);
+    }
+  } else if (has_rows && run_n) {
+#pragma unroll 1
+    for (uint32_t f = 0; f < ft.n_fields; ++f) {
+      if (!ft.io[f]) continue;
+      switch (ft.vec[f]) {
+        case 16: step_rows<uint4>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row); break;
+        case 8: step_rows<uint2>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row); break;
+        case 4:
+          if constexpr (WIDE) {
+            if (moves_wide(ft.bytes[f], 4)) {
+              step_rows_wide(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row);
+              break;
+            }
+          }
+          step_rows<uint32_t>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row);
+          break;
+        case 2: step_rows<uint16_t>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row); break;
+        default: step_rows<uint8_t>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row); break;
+      }
+    }
   }
+  // ---- running maximum, flags, the smallest sampled value of this workgroup
   if (!sh.builders) raise_max(g, t, mx, max_seen);
+  if (bad_row) flags |= 1u;
   if (flags) atomicOr(&g.status[t], flags);
+  arm_next_call();
   PER_MARK(9);
   PER_FLUSH();
-  finish_owner(true);
+  if (out_w) {   // the smallest value this workgroup has sampled, for the kernel that turns the values into weights
+    const uint32_t m = wave_min_u32(vmin_bits);
+    if (lane == 0 && m != 0x7F800000u)
+      atomicMin(sh.vmin + ((size_t)t * 2 + par) * kVminSlots + (b * (BD >> 6) + wave) % kVminSlots, m);
+  }
+  count_me_in();
 }
 
-// The side array's values become the level array's (for kernels that read height ho from the level array).
+// Importance weights of the batch the one-kernel step has just drawn: the owners have left their sampled values in
+// w and the smallest of them in the slots of the call's parity; this kernel folds the slots and turns the
+// values into weights.  The call that has just finished is number (finished calls - 1).
+__global__ void __launch_bounds__(256)
+k_step_weights(Geom g, StepShape sh, uint32_t B, float beta, uint32_t weight_mode, float* __restrict__ w) {
+  __shared__ uint32_t s_m[4];
+  const uint32_t t = blockIdx.y;
+  const unsigned long long calls = sh.cnt[(size_t)t * kStepGroups] / owners_of_group(sh.owners, 0);
+  const uint32_t par = (uint32_t)(calls - 1ull) & 1u;
+  const uint32_t* slots = sh.vmin + ((size_t)t * 2 + par) * kVminSlots;
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t o = (size_t)t * B + (i < B ? i : 0u);
+  const float v = w[o];
+  uint32_t m = wave_min_u32(slots[threadIdx.x % kVminSlots]);   // (256 lanes: every slot once)
+  if ((threadIdx.x & 63u) == 0) s_m[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = min_u32(min_u32(s_m[0], s_m[1]), min_u32(s_m[2], s_m[3]));
+  const bool nothing_sampled = m == 0x7F800000u;   // (the tree's total was zero: the values are zeros already)
+  if (weight_mode & kWeightBufferNorm) m = buffer_min_bits(g, t, weight_mode);
+  if (i < B) w[o] = nothing_sampled ? 0.0f : importance_weight(v, __uint_as_float(m), beta);
+}
+
+// The side array's values become the level array's (for kernels that read height ho from the level array): when
+// an odd number of calls has run, one more is counted.  One workgroup per tree; nothing else runs on the buffer.
 __global__ void k_step_settle(StepShape sh) {
   const uint32_t t = blockIdx.x;
-  uint32_t* ctl = sh.ctl + (size_t)t * 4;
-  if (!(ctl[0] & 1u)) return;   // (uniform over the workgroup)
+  unsigned long long* cnt = sh.cnt + (size_t)t * kStepGroups;
+  const unsigned long long calls = cnt[0] / owners_of_group(sh.owners, 0);
+  if (!(calls & 1ull)) return;   // (uniform over the workgroup)
   const float* side = sh.side + (size_t)t * sh.side_stride;
   float* lvl = sh.top_ptr[0] + (size_t)t * sh.top_stride[0];
   for (uint32_t i = threadIdx.x; i < sh.top_n[0]; i += blockDim.x) lvl[i] = side[i];
+  // the words of the next parity start empty, as after a call
+  const uint32_t par = 1u;
+  for (uint32_t i = threadIdx.x; i < kVminSlots; i += blockDim.x) sh.vmin[((size_t)t * 2 + (par ^ 1u)) * kVminSlots + i] = 0x7F800000u;
+  if (threadIdx.x < kStepDoneSlots) sh.done[((size_t)t * 2 + (par ^ 1u)) * kStepDoneSlots + threadIdx.x] = 0u;
   __syncthreads();
-  if (threadIdx.x == 0) ctl[0] = 0u;
+  if (threadIdx.x < kStepGroups) cnt[threadIdx.x] += owners_of_group(sh.owners, threadIdx.x);
 }
 
 // The owner height of a tree for k_step, or 0 when the kernel does not fit it: the lowest height, not below the
@@ -645,9 +882,7 @@ static uint32_t step_block(const Geom& g, uint32_t ho, uint32_t B) {
 }
 
 template <int LOGK>
-static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block, uint32_t B, uint32_t size, const float* u,
-                                const RngArgs& rng, uint32_t* out_idx, float* out_prio, float* out_w,
-                                const float* upd_prio, const uint32_t* upd_pos, hipStream_t s) {
+static void step_shape(const Geom& g, uint32_t block, uint32_t B, bool with_map, StepShape* out, size_t* lds_bytes) {
   constexpr int K = Fan<LOGK>::K;
   const uint32_t ho = g.step_ho;
   StepShape sh{};
@@ -672,6 +907,9 @@ static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block,
     sh.sub_off[i] = off;
     off += sh.sub_cnt[i];
   }
+  off = (off + 1u) / 2u * 2u;
+  sh.path_off = off;
+  off += 2u * kStepPathMax;
   off = (off + 3u) / 4u * 4u;
   sh.rows_off = off;
   off += (block + 1u) * (K + 4);
@@ -679,20 +917,52 @@ static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block,
   off += (block + 2u) + 3u * (block + 1u);
   sh.owners = g.n[ho];
   sh.builders = 0;
-  if (upd_pos) {
+  if (with_map) {
     sh.builders = (B + 4u * block - 1u) / (4u * block);   // about four elements per builder lane
     if (sh.builders > 64) sh.builders = 64;
   }
   sh.side = g.step_side;
   sh.side_stride = g.step_side_stride;
-  sh.ctl = g.step_ctl;
+  sh.cnt = g.step_cnt;
+  sh.done = g.step_done;
+  sh.vmin = g.step_vmin;
   sh.inv = reinterpret_cast<uint32_t*>(g.owner);
   sh.inv_stride = 2u * g.owner_stride;
-  const size_t bytes = (size_t)off * 4;
-  hipError_t e = grant_lds<&k_step<LOGK>>(tn, bytes);
+  *out = sh;
+  *lds_bytes = (size_t)off * 4;
+}
+
+template <int LOGK>
+static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block, uint32_t B, uint32_t size, float beta,
+                                uint32_t weight_mode, const float* u, const RngArgs& rng, uint32_t* out_idx,
+                                float* out_prio, float* out_w, const float* upd_prio, const uint32_t* upd_pos,
+                                const FieldTable* rows, bool* refused, hipStream_t s) {
+  StepShape sh;
+  size_t bytes;
+  step_shape<LOGK>(g, block, B, upd_pos != nullptr, &sh, &bytes);
+  FieldTable ft{};
+  if (rows) ft = *rows;
+  const bool wide = any_field_moves_wide(rows ? &ft : nullptr);
+  hipError_t e = wide ? grant_lds<&k_step<LOGK, true>>(tn, bytes) : grant_lds<&k_step<LOGK, false>>(tn, bytes);
   if (e != hipSuccess) return e;
-  PER_LAUNCH(KID_STEP, k_step<LOGK>, dim3(sh.builders + sh.owners, g.T), dim3(block), bytes, s, g, sh, B, size, u, rng,
-             out_idx, out_prio, out_w, upd_prio, upd_pos);
+  const dim3 grid(sh.builders + sh.owners, g.T);
+  uint32_t early_field = 0xFFFFFFFFu, moved = 0;   // the single field that moves, if it moves 16 bytes at a time in at most 16 pieces
+  for (uint32_t f = 0; rows && f < ft.n_fields; ++f)
+    if (ft.io[f]) {
+      ++moved;
+      early_field = f;
+    }
+  if (moved != 1 || ft.vec[early_field] != 16 || ft.bytes[early_field] / 16u > 16u) early_field = 0xFFFFFFFFu;
+  if (wide) {
+    PER_LAUNCH(KID_STEP, (k_step<LOGK, true>), grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx,
+               out_prio, out_w, upd_prio, upd_pos, ft, rows ? 1u : 0u, early_field);
+  } else {
+    PER_LAUNCH(KID_STEP, (k_step<LOGK, false>), grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx,
+               out_prio, out_w, upd_prio, upd_pos, ft, rows ? 1u : 0u, early_field);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess || !out_w) return e;
+  PER_LAUNCH(KID_STEP_WEIGHTS, k_step_weights, dim3((B + 255u) / 256u, g.T), dim3(256), 0, s, g, sh, B, beta, weight_mode, out_w);
   return hipGetLastError();
 }
 
@@ -708,28 +978,22 @@ uint32_t step_fits(const Geom& g, uint32_t B) {
   }
 }
 
-// Sampling and the update of the sampled batch in one kernel, then the rows and the weights in a second.
+// The whole step as one kernel.  *refused: the kernel was not launched because its workgroups would not all be
+// resident at once (nothing was enqueued).
 hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, uint32_t B, uint32_t size, float beta,
                        const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio,
                        uint32_t weight_mode, const FieldTable* rows, const float* upd_prio, const uint32_t* upd_pos,
-                       hipStream_t s) {
-  hipError_t e;
+                       bool* refused, hipStream_t s) {
+  *refused = false;
+#define CALL(L) launch_step_k<L>(g, tn, block, B, size, beta, weight_mode, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, rows, refused, s)
   switch (g.logK) {
-    case 3: e = launch_step_k<3>(g, tn, block, B, size, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, s); break;
-    case 4: e = launch_step_k<4>(g, tn, block, B, size, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, s); break;
-    case 5: e = launch_step_k<5>(g, tn, block, B, size, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, s); break;
-    case 6: e = launch_step_k<6>(g, tn, block, B, size, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, s); break;
+    case 3: return CALL(3);
+    case 4: return CALL(4);
+    case 5: return CALL(5);
+    case 6: return CALL(6);
     default: return hipErrorInvalidValue;
   }
-  if (e != hipSuccess || (!rows && !out_w)) return e;
-  FinishArgs a{};
-  a.B = B;
-  a.idx = out_idx;
-  a.w = out_w;
-  a.size = size;
-  a.beta = beta;
-  a.weight_mode = weight_mode;
-  return launch_finish(g, tn, rows, a, s);
+#undef CALL
 }
 
 // Makes the level array of the owner height current again after k_step calls (see k_step_settle).
@@ -739,9 +1003,12 @@ hipError_t launch_step_settle(const Geom& g, const Tuning& tn, hipStream_t s) {
   sh.top_ptr[0] = g.level[g.step_ho];
   sh.top_stride[0] = g.stride[g.step_ho];
   sh.top_n[0] = g.n[g.step_ho];
+  sh.owners = g.n[g.step_ho];
   sh.side = g.step_side;
   sh.side_stride = g.step_side_stride;
-  sh.ctl = g.step_ctl;
+  sh.cnt = g.step_cnt;
+  sh.done = g.step_done;
+  sh.vmin = g.step_vmin;
   PER_LAUNCH(KID_STEP_SETTLE, k_step_settle, dim3(g.T), dim3(256), 0, s, sh);
   return hipGetLastError();
 }

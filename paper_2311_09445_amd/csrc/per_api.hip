@@ -43,7 +43,7 @@ struct Layout {
   uint32_t n[kMaxHeight + 1];
   uint32_t stride[kMaxHeight + 1];
   size_t level_off[kMaxHeight + 1];
-  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, min1_off, side_off, col_off[kMaxFields];
+  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, min1_off, side_off, step_off, col_off[kMaxFields];
   uint32_t dirty_stride, arrive_stride, arrive_level_off[kMaxHeight + 1];
   uint64_t col_stride[kMaxFields];
   uint32_t row_stride;        // bytes between stored rows
@@ -87,8 +87,10 @@ void make_layout(const per_config* c, Layout* L) {
   } while (n > 1);
   L->H = h;
   size_t off = 0;
-  L->scalars_off = off;                         // max_v, status, vnext, vcur, sbase, sfloor [T] each; step_ctl[T][4]; vmin[2][T][kVminSlots], vmin_buf[T][kMinParts]
-  off = round_up(off + (size_t)(6 + 4 + 2 * kVminSlots + kMinParts) * T * 4, kAlign);
+  L->scalars_off = off;                         // max_v, status, vnext, vcur, sbase, sfloor [T] each; vmin[2][T][kVminSlots], vmin_buf[T][kMinParts]
+  off = round_up(off + (size_t)(6 + 2 * kVminSlots + kMinParts) * T * 4, kAlign);
+  L->step_off = off;                            // the one-kernel step's words: cnt[T][kStepGroups] (64-bit), done[T][2][kStepDoneSlots], vmin[T][2][kVminSlots]
+  off = round_up(off + (size_t)(2 * kStepGroups + 2 * kStepDoneSlots + 2 * kVminSlots) * T * 4, kAlign);
   for (uint32_t l = 0; l <= L->H; ++l) {
     const uint64_t padded = ((uint64_t)L->n[l] + K - 1) / K * K;
     L->stride[l] = (uint32_t)round_up(padded, 64);
@@ -280,8 +282,10 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.vcur = g.vnext + g.T;
   g.sbase = g.vcur + g.T;
   g.sfloor = g.sbase + g.T;
-  g.step_ctl = g.sfloor + g.T;
-  g.vmin = g.step_ctl + (size_t)4 * g.T;
+  g.vmin = g.sfloor + g.T;
+  g.step_cnt = reinterpret_cast<unsigned long long*>(p->arena + L.step_off);
+  g.step_done = reinterpret_cast<uint32_t*>(g.step_cnt + (size_t)kStepGroups * g.T);
+  g.step_vmin = g.step_done + (size_t)2 * kStepDoneSlots * g.T;
   g.vmin_buf = g.vmin + (size_t)2 * kVminSlots * g.T;
   g.step_side = reinterpret_cast<float*>(p->arena + L.side_off);
   g.step_side_stride = kStepSideStride;
@@ -467,15 +471,20 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
       rng.seed_hi = (uint32_t)(p->rng_seed >> 32);
       rng.call_lo = (uint32_t)p->rng_calls;
       rng.call_hi = (uint32_t)(p->rng_calls >> 32);
-      ++p->rng_calls;
     }
-    p->min_stale = true;   // (the kernel does not renew the companion minimum)
+    bool refused = false;
     hipError_t e = launch_step(p->g, p->tn, step_block, B, (uint32_t)p->size, beta, d_u, rng, d_out_idx, d_out_weight,
-                               d_out_prio, weight_mode, fused ? &ft : nullptr, d_upd_prio, d_upd_pos, s);
-    p->stale_hb = p->g.step_ho;   // the heights above the owner height are left to their next reader,
-    p->side_maybe = true;         // and the nodes of that height may be in the side array
-    if (e != hipSuccess) p->claims_left = true;
-    return hip_rc(e);
+                               d_out_prio, weight_mode, fused ? &ft : nullptr, d_upd_prio, d_upd_pos, &refused, s);
+    if (!refused) {
+      if (!d_u) ++p->rng_calls;
+      p->min_stale = true;          // (the kernel does not renew the companion minimum)
+      p->stale_hb = p->g.step_ho;   // the heights above the owner height are left to their next reader,
+      p->side_maybe = true;         // and the nodes of that height may be in the side array
+      if (e != hipSuccess) p->claims_left = true;
+      return hip_rc(e);
+    }
+    // (nothing was enqueued: the separate kernels take over)
+    if (prepare_tree_pass(p, s) != hipSuccess) return PER_EHIP;
   }
   ClaimArgs claim{};
   int claim_mode = CLAIM_NONE;

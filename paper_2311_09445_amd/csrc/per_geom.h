@@ -18,6 +18,8 @@ namespace per {
 constexpr int kMaxHeight = 32;   // K = 2, N = 2^31 gives H = 31
 constexpr int kMaxFields = 8;
 constexpr uint32_t kVminSlots = 256;   // partial batch minima per tree and buffer
+constexpr uint32_t kStepGroups = 64;   // counters the owners of the one-kernel step are spread over (one wave reads them all)
+constexpr uint32_t kStepDoneSlots = 8; // counters its builders are spread over
 
 struct Geom {
   uint32_t K, logK, H, T;
@@ -49,7 +51,9 @@ struct Geom {
   uint32_t step_ho;                 // owner height of the one-kernel step (0: that kernel does not fit this tree)
   float*   step_side;               // [T][step_side_stride] second array for the nodes of height step_ho
   uint32_t step_side_stride;
-  uint32_t* step_ctl;               // [T][4] control words of the one-kernel step
+  unsigned long long* step_cnt;     // [T][kStepGroups] owners of the one-kernel step that have finished, over all calls
+  uint32_t* step_done;              // [T][2][kStepDoneSlots] its builders that have finished (by parity of the call)
+  uint32_t* step_vmin;              // [T][2][kVminSlots] smallest sampled values of its call (by parity)
 };
 uint32_t step_owner_height(const Geom& g);   // (needs K, logK, H, T, n[])
 constexpr uint32_t kMinParts = 1024;     // most workgroups k_min_reduce is launched with
@@ -167,7 +171,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_UPDATE_DELTA, KID_GET_PRIORITY,
-  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_MIN_REBUILD, KID_MIN_REDUCE, KID_STEP, KID_STEP_SETTLE, KID_COUNT
+  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_MIN_REBUILD, KID_MIN_REDUCE, KID_STEP, KID_STEP_SETTLE, KID_STEP_WEIGHTS, KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -225,7 +229,7 @@ uint32_t step_fits(const Geom& g, uint32_t B);
 hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, uint32_t B, uint32_t size, float beta,
                        const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio,
                        uint32_t weight_mode, const FieldTable* rows, const float* upd_prio, const uint32_t* upd_pos,
-                       hipStream_t s);
+                       bool* refused, hipStream_t s);
 hipError_t launch_step_settle(const Geom& g, const Tuning& tn, hipStream_t s);
 uint32_t stream_tree_floats(const Geom& g, uint32_t* off);
 hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s);
