@@ -87,12 +87,9 @@ def algorithmic_bytes(w, idx, upd_idx, K, H, h_lds, weights):
 def per_launched_kernel(parts, launched):
     """Algorithmic bytes of the kernels that were launched, from the parts of the step each one carries."""
     alg = dict(parts)
-    if "k_step" in launched:            # sampling and the update of the sampled batch in one kernel
+    if "k_step" in launched:            # sampling and the update of the sampled batch in one kernel; rows and weights in its epilogue
         alg["k_step"] = parts["k_sample"] + parts["k_update_claim"] + parts["k_update_tree"]
-        if "k_finish" in launched:
-            alg["k_finish"] = parts["k_rows_gather"] + parts["k_weights"]
-        else:
-            alg["k_step"] += parts["k_rows_gather"] + parts["k_weights"]
+        alg["k_step_epilogue"] = parts["k_rows_gather"] + parts["k_weights"]
     elif "k_tree_finish" in launched:   # two-kernel step: claim in the sampling kernel, tree pass beside rows and weights
         alg["k_sample"] = parts["k_sample"] + parts["k_update_claim"]
         alg["k_tree_finish"] = parts["k_update_tree"] + parts["k_rows_gather"] + parts["k_weights"]

@@ -362,9 +362,11 @@ uint64_t per_rng_calls(const per_t* p);
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
  *                  the next call that reads them; 0 makes per_update finish them itself
  *   "insert_small" : 1 (default) runs an insert of few rows as a single kernel, one workgroup per tree
- *   "step_kernel" : 1 (default) lets per_step (and per_sample_gather_update called with the sampled batch as
- *                  its update batch) run sampling and update as one kernel, one workgroup per subtree, where
- *                  the tree and the batch fit that kernel; 0: always the separate kernels
+ *   "step_kernel" : how per_step (and per_sample_gather_update called with the sampled batch as its update batch)
+ *                  runs.  1 (default): sampling and update as one kernel, one workgroup per subtree, with rows and
+ *                  weights in a second, where the tree fits that kernel and the batch is large enough for it
+ *                  to pay off (long runs of samples per subtree, few trees); 2: wherever the tree fits (tests);
+ *                  0: always the separate kernels
  *   "claim_in_sample" : 1 (default) lets per_sample_gather_update run the first phase of its update
  *                  inside the sampling kernel (two kernels per step) whenever the update batch is the
  *                  sampled batch itself or lies apart from the sampling outputs; 0: always three kernels */

@@ -1,4 +1,4 @@
-// One iteration of Listing 2 whose update targets the batch it draws: sampling, rows and update as one kernel.
+// One iteration of Listing 2 whose update targets the batch it draws: sampling and update as one kernel, rows and weights in a second.
 // Part of per_kernels.hip (included inside namespace per, in the order given there); not a stand-alone header.
 
 // ---------------------------------------------------------------------------------
@@ -8,24 +8,26 @@
 // that end under one node of the tree are a contiguous run of sample numbers.  Workgroup b of tree t owns
 // the subtree under node b of height ho ("owner height").  It finds its run of samples, walks them down
 // (the way from the root to node b is the same for all of them, so it is tabulated once; the heights
-// 1 .. ho-1 of its own subtree come from an LDS copy, the leaf groups from memory), moves their rows, and
+// 1 .. ho-1 of its own subtree come from an LDS copy, the leaf groups from memory), and
 // then applies the update of exactly those samples to its own subtree: every leaf, every height-1 node and
 // every higher node of the subtree is read and written by this workgroup only, so the update needs no claim
 // phase, no atomics and no second pass over the leaf groups (they are still in LDS from the walk).
 // Sampling sees the tree as it was before the call because a workgroup finishes all its walks before it
-// changes anything, and what all workgroups read, the nodes of height ho, is never written in place: the
-// new value of node b goes to the other one of two arrays (the level array itself and a side array).
-// Which one is current follows from how many calls have run, and that is counted on the device: every
-// owner adds one to a counter when it is done (the owners are spread over kStepGroups counters, because
-// atomics on one address queue up), so counter i holds calls * (owners of group i) between calls, and a
-// workgroup that reads its own group's counter when it starts gets the number of finished calls whatever
-// the others have already added.  The importance weights are relative to the batch minimum of the sampled
-// values, which is known only when every owner is done: the owners leave their values and, in slots, their
-// minima, and a small second kernel (k_step_weights) turns the values into weights.  (Owners that wait for
-// each other inside the kernel were tried: 512 workgroups polling the counters slowed the very atomics
-// they waited for, + 9 us.)
-// The heights above ho are rebuilt in LDS from height ho by every workgroup (a few child groups) and are
-// left stale in memory, as after any update.
+// changes anything, and what all workgroups read is not written by this kernel at all: the way from the
+// root to every owner's node (the left and right block sums of each binary step, in the walk's own
+// arithmetic), the mass in front of the node and the tree's total sit in a table built from the nodes
+// of height ho and above by the kernel that ends the call before (k_step_epilogue), or by a small
+// kernel in front when another call has changed the tree since (k_step_tables).  The new value of node b
+// goes to a side array; the epilogue moves the side array into the level array, recomputes the heights
+// above (so nothing is left stale), builds the tables of the next call, and turns the sampled values
+// into importance weights (they are relative to the batch minimum, which is known only when every owner
+// is done: the owners leave their values and, in slots, their minima).  The slots and the builders'
+// counters alternate between two sets by the number of finished calls, which is counted on the device:
+// every owner adds one to a counter when it is done (spread over kStepGroups counters, because atomics on
+// one address queue up), and a workgroup that reads its own group's counter when it starts gets the
+// number of finished calls whatever the others have already added.  (Owners that wait for each other
+// inside the kernel to finish the weights themselves were tried: 512 workgroups polling the counters
+// slowed the very atomics they waited for, + 9 us.)
 //
 // Last writer: element j of the update targets the leaf drawn by sample pos[j] (no map: by sample j).  The
 // samples of one leaf are neighbours in a workgroup's run, so the winner of a leaf is the largest j among
@@ -40,6 +42,15 @@ constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 constexpr uint32_t kStepSpinLimit = 1u << 20;   // polls of a counter before a workgroup gives up
 constexpr int kStepPathMax = kStepTop * 6;      // binary steps from the root to a node of the owner height
 
+// What an owner needs of the tree above it (one entry per owner, rebuilt whenever the heights ho .. H change).
+struct StepTable {
+  float2 path[kStepPathMax];   // per binary step from the root to the node: (sum of the left block, flags); bit 0 of the flags:
+                               // the node lies to the right; bit 1: the right block is not zero
+  double mass;                 // sum of the nodes of height ho in front of it
+  float total;                 // the root
+  float node;                  // its own value
+};
+
 struct StepShape {
   float* top_ptr[kStepTop];        // height ho + i of tree 0 (i = 0: the level array of height ho)
   uint32_t top_stride[kStepTop];   // floats between trees
@@ -52,12 +63,15 @@ struct StepShape {
   uint32_t sub_pad[kStepSub];      // nodes of that height in memory, padded to whole groups
   uint32_t sub_off[kStepSub];      // where in LDS (floats)
   uint32_t n_top, n_sub;           // H - ho, ho - 1
-  uint32_t path_off;               // LDS: the way from the root to node b: kStepPathMax entries of (left sum, flags)
+  uint32_t path_off;               // LDS: this owner's table entries (kStepPathMax float2)
   uint32_t rows_off;               // LDS: (block + 1) staging rows of K + 4 floats (16-byte aligned)
   uint32_t key_off;                // LDS: key[block + 2], wpos[block + 1], wval[block + 1], touch[block + 1]
   uint32_t owners;                 // n[ho]: owner workgroups per tree
   uint32_t builders;               // builder workgroups per tree in front of them (0: no position map)
-  float* side;                     // [T][side_stride] second array for the nodes of height ho
+  float* root;                     // root of tree 0
+  uint32_t root_stride;
+  float* side;                     // [T][side_stride] where the owners leave the new values of their nodes of height ho
+  StepTable* tab;                  // [T][owners]
   uint32_t side_stride;
   unsigned long long* cnt;         // [T][kStepGroups] finished owners of group i, over all calls
   uint32_t* done;                  // [T][2][kStepDoneSlots] finished builders of this call (by parity of the call number)
@@ -199,60 +213,11 @@ __device__ __forceinline__ uint32_t chunk_groups(const ChunkLds& c, uint32_t slo
 }
 
 
-// The rows of samples [first, first + count) of tree t, moved by the calling workgroup alone (field f; V: access width).
-template <typename V>
-__device__ __forceinline__ void step_rows(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B, uint32_t first, uint32_t count,
-                                          const uint32_t* idx, uint32_t N, bool& bad) {
-  constexpr int U = InFlight<V>::U;
-  RowMove m;
-  const uint32_t E = ft.bytes[f];
-  m.RS = ft.row_stride;
-  m.epr = E / (uint32_t)sizeof(V);
-  m.total = (uint64_t)count * m.epr;
-  m.col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
-  m.io = ft.io[f] + ((uint64_t)t * B + first) * E;
-  m.idx = idx + (size_t)t * B + first;
-  m.stride = blockDim.x;
-  m.cursor = 0;
-  m.N = N;
-  for (uint64_t e0 = threadIdx.x; e0 < m.total; e0 += U * m.stride) {
-    Regs<uint32_t, U> at;
-    Regs<Held<V>, U> v;
-    sweep_where<V, true, 0, U>(m, e0, at);
-    sweep_load<V, true, 0, U>(m, e0, at, v, bad);
-    sweep_store<V, true, 0, U>(m, e0, at, v);
-  }
-}
-__device__ __forceinline__ void step_rows_wide(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B, uint32_t first,
-                                               uint32_t count, const uint32_t* idx, uint32_t N, bool& bad) {
-  constexpr int U = 2;
-  WideMove w;
-  RowMove& m = w.m;
-  w.E = ft.bytes[f];
-  m.RS = ft.row_stride;
-  m.epr = (w.E + 15u) / 16u;
-  m.total = (uint64_t)count * m.epr;
-  m.col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
-  m.io = ft.io[f] + ((uint64_t)t * B + first) * w.E;
-  m.idx = idx + (size_t)t * B + first;
-  m.stride = blockDim.x;
-  m.cursor = 0;
-  m.N = N;
-  for (uint64_t e0 = threadIdx.x; e0 < m.total; e0 += U * m.stride) {
-    Regs<uint32_t, U> at;
-    Regs<uint4, U> v;
-    sweep_where<uint4, true, 0, U>(m, e0, at);
-    wide_load<true, 0, U>(w, e0, at, v, bad);
-    wide_store<true, 0, U>(w, e0, at, v);
-  }
-}
-
-template <int LOGK, bool WIDE>
+template <int LOGK>
 __global__ void __launch_bounds__(512)
 k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t weight_mode, const float* __restrict__ u,
        RngArgs rng, uint32_t* out_idx, float* __restrict__ out_prio, float* out_w,
-       const float* __restrict__ upd_prio, const uint32_t* __restrict__ upd_pos, FieldTable ft, uint32_t has_rows,
-       uint32_t early_field) {
+       const float* __restrict__ upd_prio, const uint32_t* __restrict__ upd_pos) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   constexpr int ROW = K + 4;
@@ -269,15 +234,15 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   const unsigned long long* cnt = sh.cnt + (size_t)t * kStepGroups;
   uint32_t* inv = sh.inv + (size_t)t * sh.inv_stride;
   const int n_top = (int)sh.n_top, n_sub = (int)sh.n_sub;
-  float* lvl_ho = sh.top_ptr[0] + (size_t)t * sh.top_stride[0];
+  const uint32_t n_steps = (uint32_t)n_top * LOGK;
   float* side_ho = sh.side + (size_t)t * sh.side_stride;
+  const StepTable* tab = sh.tab + (size_t)t * sh.owners;
 
   // ------------------------------------------------------------------ builder workgroups (position map only)
   if (blockIdx.x < sh.builders) {
     // (the owners of this call cannot finish before every builder has, so the count of group 0 is still that of the calls before)
     const unsigned long long calls = load_counter(cnt) / owners_of_group(sh.owners, 0);
     const uint32_t par = (uint32_t)calls & 1u;
-    const float* cur_ho = par ? side_ho : lvl_ho;
     const uint32_t max_seen = read_max_bits(g, t);
     uint32_t mx = 0, f_idx = 0, f_prio = 0, acc = 0;
     for (uint32_t j = blockIdx.x * BD + tid; j < B; j += sh.builders * BD) {
@@ -291,10 +256,8 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
         mx = vb > mx ? vb : mx;
       }
     }
-    // nothing can be sampled (and no element is valid) exactly when no node of height ho is positive
-    int positive = 0;
-    for (uint32_t i = tid; i < sh.top_n[0]; i += BD) positive |= cur_ho[i] > 0.0f ? 1 : 0;
-    positive = __syncthreads_or(positive);
+    // nothing can be sampled (and no element is valid) when the tree's total is not positive
+    const bool positive = tab[0].total > 0.0f;
     if (positive) {
       raise_max(g, t, mx, max_seen);
       if (f_idx | f_prio) atomicOr(&g.status[t], f_idx | f_prio);
@@ -310,7 +273,6 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   // ------------------------------------------------------------------ owner workgroup b
   const uint32_t b = blockIdx.x - sh.builders;
   const uint32_t my_group = b % kStepGroups;
-  float* top = lds;                                   // heights ho .. H-1, at top_off[i]
   float* sub = lds;                                   // heights 1 .. ho-1 of the own subtree, at sub_off[i]
   // per binary step from the root to b: the sum of the left block; bit 0: b lies to the right, bit 1: the right block is not zero
   float2* path = reinterpret_cast<float2*>(lds + sh.path_off);
@@ -324,7 +286,7 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   PER_TRACE_DECL;
   PER_MARK(0);
   PER_MARK_HWID(15);
-  // ---- trip 1: the number of finished calls, both arrays of height ho, the own subtree's heights, the running maximum
+  // ---- trip 1: the number of finished calls, this owner's table, the own subtree's heights, the running maximum
   unsigned long long count0 = 0;
   {
     uint32_t zero;
@@ -332,14 +294,10 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     count0 = __hip_atomic_load(cnt + my_group + zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   const uint32_t max_seen = read_max_bits(g, t);
-  float ho_a[4], ho_b[4];   // up to four nodes per lane of either array (more: a loop below)
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const uint32_t i = tid + (uint32_t)k * BD;
-    const bool real = i < sh.top_n[0];
-    ho_a[k] = real ? lvl_ho[i] : 0.0f;
-    ho_b[k] = real ? side_ho[i] : 0.0f;
-  }
+  const StepTable* mine = tab + b;
+  const float total = mine->total;
+  const double mass = mine->mass;
+  if (tid < n_steps) path[tid] = mine->path[tid];
 #pragma unroll
   for (int i = 0; i < kStepSub; ++i) {
     if (i < n_sub) {
@@ -350,71 +308,9 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     }
   }
   const unsigned long long calls = count0 / owners_of_group(sh.owners, my_group);
-  const uint32_t par = (uint32_t)calls & 1u;          // odd: the side array is the current one
-  const float* cur_ho = par ? side_ho : lvl_ho;
-  float* new_ho = par ? lvl_ho : side_ho;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const uint32_t i = tid + (uint32_t)k * BD;
-    if (i < sh.top_cnt[0]) top[sh.top_off[0] + i] = par ? ho_b[k] : ho_a[k];
-  }
-  for (uint32_t i = tid + 4u * BD; i < sh.top_cnt[0]; i += BD) top[sh.top_off[0] + i] = i < sh.top_n[0] ? cur_ho[i] : 0.0f;
+  const uint32_t par = (uint32_t)calls & 1u;          // which set of slots and builder counters this call uses
   __syncthreads();
   PER_MARK(1);
-  // the heights above ho, from LDS (in memory they may be stale)
-  {
-    const unsigned q = tid % LPS;
-    const uint32_t grp = tid / LPS, ngrp = BD / LPS;
-#pragma unroll
-    for (int i = 1; i < kStepTop; ++i) {
-      if (i < n_top) {
-        for (uint32_t base = 0; base < sh.top_cnt[i]; base += ngrp) {
-          const uint32_t j = base + grp;
-          const bool real = j < sh.top_n[i];
-          const float sum = group_sum<LOGK>(top + sh.top_off[i - 1] + (size_t)(real ? j : 0u) * K, q);
-          if (q == 0 && j < sh.top_cnt[i]) top[sh.top_off[i] + j] = real ? sum : 0.0f;
-        }
-        __syncthreads();
-      }
-    }
-  }
-  // the way from the root to node b, one binary step per lane: step k halves the block of the child group of
-  // height ho + i that holds b's ancestor (i = n_top-1 first), and notes the sums of the two halves
-  const uint32_t n_steps = (uint32_t)n_top * LOGK;
-  double mass = 0.0;
-  if (tid < n_steps) {
-    const uint32_t i = (uint32_t)n_top - 1u - tid / LOGK, m = LOGK - 1u - tid % LOGK;   // height ho + i; halves of 2^m nodes
-    uint32_t off_i = sh.top_off[0];
-#pragma unroll
-    for (int k = 1; k < kStepTop; ++k)
-      if ((uint32_t)k == i) off_i = sh.top_off[k];
-    const uint32_t anc = shr64(b, i * LOGK);                 // b's ancestor at height ho + i
-    const uint32_t pos = anc & (uint32_t)(K - 1);
-    const float* blk = top + off_i + (size_t)(anc - pos) + ((pos >> (m + 1)) << (m + 1));
-    const float left = block_sum<LOGK>(blk, m), right = block_sum<LOGK>(blk + (1u << m), m);
-    const uint32_t turn = (pos >> m) & 1u;
-    path[tid] = make_float2(left, __uint_as_float(turn | (right != 0.0f ? 2u : 0u)));
-    if (turn) mass = (double)left;
-  }
-  // (b) where this workgroup's run of samples starts, to within a few: the mass in front of node b over seg
-  if (wave == 0) {
-#pragma unroll
-    for (int mm = 1; mm < 32; mm <<= 1) mass += __shfl_xor(mass, mm);
-  }
-  float total;
-  {
-    const float* rootgrp = top;   // group 0 of height H-1
-#pragma unroll
-    for (int i = 0; i < kStepTop; ++i)
-      if (i == n_top - 1) rootgrp = top + sh.top_off[i];
-    total = row_sum<LOGK>(rootgrp);
-  }
-  if (tid == 0) {
-    const double est = mass / ((double)total / (double)B);
-    const uint32_t s_guess = est >= (double)B ? B : (est > 0.0 ? (uint32_t)est : 0u);   // (not a number: 0)
-    s_u32[5] = s_guess > kStepPad ? s_guess - kStepPad : 0u;
-  }
-  __syncthreads();
   PER_MARK(2);
   const bool leader = b == 0 && tid == 0;
 
@@ -468,7 +364,7 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     }
     // (without a map every element is out of range too; with one the builders have said so)
     if (leader) atomicOr(&g.status[t], sh.builders ? 4u : 5u);
-    if (tid == 0) new_ho[b] = top[sh.top_off[0] + b];   // the call counts all the same, so the other array becomes current
+    if (tid == 0) side_ho[b] = mine->node;   // (every owner leaves its node's value: the epilogue takes all of them)
     arm_next_call();
     count_me_in();
     return;
@@ -521,7 +417,13 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     return lo;
   };
 
-  const uint32_t s0 = s_u32[5];
+  // where this workgroup's run of samples starts, to within a few: the mass in front of node b over seg
+  uint32_t s0;
+  {
+    const double est = mass / ((double)total / (double)B);
+    const uint32_t s_guess = est >= (double)B ? B : (est > 0.0 ? (uint32_t)est : 0u);   // (not a number: 0)
+    s0 = s_guess > kStepPad ? s_guess - kStepPad : 0u;
+  }
   PER_MARK(3);
 
   // ---- trip 2: the samples of the window [s0, s0 + BD): uniforms, their own new priorities
@@ -533,7 +435,7 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   const uint32_t where = in ? landing(r) : 2u;
   // does the window hold the whole run?  its first sample must land in front of b (or be sample 0), and a sample
   // of it must land behind b (or the batch must end in it)
-  uint32_t run_lo, run_n, n_front_lanes;
+  uint32_t run_lo, run_n;
   bool searched;   // (uniform over the workgroup)
   {
     if (tid == 0) s_u32[1] = (s0 == 0 || where == 0u) ? 1u : 0u;
@@ -541,7 +443,6 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     const uint32_t n_mine = (uint32_t)__syncthreads_count(in && where == 1u);
     const bool complete = s_u32[1] != 0 && (n_front + n_mine < BD || s0 + BD >= B);
     run_lo = s0 + n_front;
-    n_front_lanes = n_front;
     run_n = n_mine;
     if (!complete) {   // rare: the exact ends of the run by search, then chunks of it (uniform over the workgroup)
       if (wave == 0) {
@@ -566,23 +467,13 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   float* lvl1 = sh.sub_ptr[0] + (size_t)t * sh.sub_stride[0];
   float* stage = c.rows + (size_t)(1u + wave * 64u) * ROW;                  // this wave's rows: slots 1 + tid
   uint32_t mx = 0, flags = 0, vmin_bits = 0x7F800000u;
-  bool builders_ok = true, waited = false, bad_row = false;
+  bool builders_ok = true, waited = false;
   if (tid == 0) {
     c.key[0] = kNoKey;
     c.wpos[0] = 0;
     c.touch[0] = 0;
   }
   if (tid < 2) c.key[BD + tid] = kNoKey;   // (key[BD] is written again by the last lane; key[BD + 1] stays)
-
-  // Rows of a single 16-byte-wide field: the loads of the first kEarly pieces per lane are issued as soon as the
-  // indices are known and their stores wait until the update is through, so that trip to memory runs under it
-  // (the pieces beyond, if the run is long, move at the end).
-  const uint32_t early_epr = early_field < (uint32_t)kMaxFields ? ft.bytes[early_field < (uint32_t)kMaxFields ? early_field : 0u] / 16u : 0u;
-  constexpr int kEarly = 4;
-  const bool early_rows = has_rows && early_epr != 0u && !searched;
-  uint4 rv[kEarly];
-#pragma unroll
-  for (int k = 0; k < kEarly; ++k) rv[k] = make_uint4(0, 0, 0, 0);
 
   for (uint32_t pass = 0; pass < (two_phase ? 2u : 1u); ++pass) {
     // pass 0 walks (and, when one chunk holds the run, updates); pass 1 of a long run updates chunk by chunk
@@ -632,25 +523,12 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
         idx = x * K + child;
         if (member) {
           out_idx[o] = idx;
-          if (out_prio) __builtin_nontemporal_store(val, out_prio + o);
-          if (out_w) __builtin_nontemporal_store(val, out_w + o);
+          if (out_prio) out_prio[o] = val;
+          if (out_w) out_w[o] = val;
           const uint32_t vb = __float_as_uint(val);
           vmin_bits = vb < vmin_bits ? vb : vmin_bits;
         }
         if (two_phase) continue;
-        if (early_rows) {
-          c.key[1 + tid] = member ? idx : kNoKey;
-          __syncthreads();
-          const uint8_t* col = ft.col[early_field] + (uint64_t)t * ft.col_stride[early_field];
-#pragma unroll
-          for (int k = 0; k < kEarly; ++k) {
-            const uint32_t e = tid + (uint32_t)k * BD;
-            const bool live = e < run_n * early_epr;
-            const uint32_t row = live ? e / early_epr : 0u;
-            const uint32_t leaf = live ? c.key[1u + n_front_lanes + row] : 0u;
-            rv[k] = *reinterpret_cast<const uint4*>(col + (uint64_t)leaf * ft.row_stride + (size_t)(e - row * early_epr) * 16u * (live ? 1u : 0u));
-          }
-        }
       }
       PER_MARK(5);
       // ---- the update of this chunk
@@ -751,54 +629,12 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
       if (i == n_sub - 1) off_last = sh.sub_off[i];
     if (tid < 64) {
       const float sum = group_sum<LOGK>(sub + off_last, lane % LPS);
-      if (lane == 0) new_ho[b] = sum;
+      if (lane == 0) side_ho[b] = sum;
     }
   }
   PER_MARK(8);
-  // ---- the rows of this workgroup's samples (their indices, written above, are read back: a barrier lies between)
-  if (early_rows) {
-    uint8_t* io = ft.io[early_field] + ((uint64_t)t * B + run_lo) * ft.bytes[early_field];
-    const uint8_t* col = ft.col[early_field] + (uint64_t)t * ft.col_stride[early_field];
-    const uint32_t pieces = run_n * early_epr;
-#pragma unroll
-    for (int k = 0; k < kEarly; ++k) {
-      const uint32_t e = tid + (uint32_t)k * BD;
-      if (e < pieces) {
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-        const u32x4 x = {rv[k].x, rv[k].y, rv[k].z, rv[k].w};
-        __builtin_nontemporal_store(x, reinterpret_cast<u32x4*>(io + (size_t)e * 16u));
-      }
-    }
-    for (uint32_t e = tid + (uint32_t)kEarly * BD; e < pieces; e += BD) {   // (the slots of this chunk still hold its indices)
-      const uint32_t row = e / early_epr;
-      const uint32_t leaf = c.key[1u + n_front_lanes + row];
-      *reinterpret_cast<uint4*>(io + (size_t)e * 16u) =
-          *reinterpret_cast<const uint4*>(col + (uint64_t)leaf * ft.row_stride + (size_t)(e - row * early_epr) * 16u);
-    }
-  } else if (has_rows && run_n) {
-#pragma unroll 1
-    for (uint32_t f = 0; f < ft.n_fields; ++f) {
-      if (!ft.io[f]) continue;
-      switch (ft.vec[f]) {
-        case 16: step_rows<uint4>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row); break;
-        case 8: step_rows<uint2>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row); break;
-        case 4:
-          if constexpr (WIDE) {
-            if (moves_wide(ft.bytes[f], 4)) {
-              step_rows_wide(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row);
-              break;
-            }
-          }
-          step_rows<uint32_t>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row);
-          break;
-        case 2: step_rows<uint16_t>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row); break;
-        default: step_rows<uint8_t>(ft, f, t, B, run_lo, run_n, out_idx, g.N, bad_row); break;
-      }
-    }
-  }
   // ---- running maximum, flags, the smallest sampled value of this workgroup
   if (!sh.builders) raise_max(g, t, mx, max_seen);
-  if (bad_row) flags |= 1u;
   if (flags) atomicOr(&g.status[t], flags);
   arm_next_call();
   PER_MARK(9);
@@ -811,17 +647,129 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   count_me_in();
 }
 
-// Importance weights of the batch the one-kernel step has just drawn: the owners have left their sampled values in
-// w and the smallest of them in the slots of the call's parity; this kernel folds the slots and turns the
-// values into weights.  The call that has just finished is number (finished calls - 1).
+// The tables of the owners [first, first + count) of tree t from the nodes of height ho at src (the level array, or
+// the side array the owners of a call have just filled), by one workgroup; dynamic LDS holds the heights ho .. H-1.
+// The workgroup with first == 0 also puts the tree's memory in order: the level array of height ho takes src's values
+// (if src is the side array) and the heights above are recomputed and stored, so that nothing is left stale.
+template <int LOGK>
+__device__ __forceinline__ void build_tables(const StepShape& sh, uint32_t t, const float* src, bool from_side, uint32_t first,
+                                             uint32_t count, float* top, float* skipped) {
+  constexpr int K = Fan<LOGK>::K;
+  constexpr int LPS = Fan<LOGK>::LPS;
+  const uint32_t tid = threadIdx.x, BD = blockDim.x;
+  const int n_top = (int)sh.n_top;
+  for (uint32_t i = tid; i < sh.top_cnt[0]; i += BD) top[sh.top_off[0] + i] = i < sh.top_n[0] ? src[i] : 0.0f;
+  __syncthreads();
+  {
+    const unsigned q = tid % LPS;
+    const uint32_t grp = tid / LPS, ngrp = BD / LPS;
+#pragma unroll
+    for (int i = 1; i < kStepTop; ++i) {
+      if (i < n_top) {
+        for (uint32_t base = 0; base < sh.top_cnt[i]; base += ngrp) {
+          const uint32_t j = base + grp;
+          const bool real = j < sh.top_n[i];
+          const float sum = group_sum<LOGK>(top + sh.top_off[i - 1] + (size_t)(real ? j : 0u) * K, q);
+          if (q == 0 && j < sh.top_cnt[i]) top[sh.top_off[i] + j] = real ? sum : 0.0f;
+        }
+        __syncthreads();
+      }
+    }
+  }
+  const float* rootgrp = top;   // group 0 of height H-1
+#pragma unroll
+  for (int i = 0; i < kStepTop; ++i)
+    if (i == n_top - 1) rootgrp = top + sh.top_off[i];
+  const float total = row_sum<LOGK>(rootgrp);
+  if (first == 0) {   // the tree's memory: height ho, the heights above, the root
+    if (from_side) {
+      float* lvl = sh.top_ptr[0] + (size_t)t * sh.top_stride[0];
+      for (uint32_t i = tid; i < sh.top_n[0]; i += BD) lvl[i] = top[sh.top_off[0] + i];
+    }
+#pragma unroll
+    for (int i = 1; i < kStepTop; ++i) {
+      if (i < n_top) {
+        float* lvl = sh.top_ptr[i] + (size_t)t * sh.top_stride[i];
+        for (uint32_t j = tid; j < sh.top_n[i]; j += BD) lvl[j] = top[sh.top_off[i] + j];
+      }
+    }
+    if (tid == 0) sh.root[(size_t)t * sh.root_stride] = total;
+  }
+  StepTable* tab = sh.tab + (size_t)t * sh.owners;
+  const uint32_t n_steps = (uint32_t)n_top * LOGK;
+  // one binary step of one owner per lane: step k halves the block of the child group of height ho + i that holds the
+  // owner's ancestor (i = n_top-1 first) and notes the sums of the two halves, in the order of the walk inside a group
+  for (uint32_t item = tid; item < count * n_steps; item += BD) {
+    const uint32_t b = first + item / n_steps, k = item % n_steps;
+    const uint32_t i = (uint32_t)n_top - 1u - k / LOGK, m = LOGK - 1u - k % LOGK;   // height ho + i; halves of 2^m nodes
+    uint32_t off_i = sh.top_off[0];
+#pragma unroll
+    for (int kk = 1; kk < kStepTop; ++kk)
+      if ((uint32_t)kk == i) off_i = sh.top_off[kk];
+    const uint32_t anc = shr64(b, i * LOGK);                 // the owner's ancestor at height ho + i
+    const uint32_t pos = anc & (uint32_t)(K - 1);
+    const float* blk = top + off_i + (size_t)(anc - pos) + ((pos >> (m + 1)) << (m + 1));
+    const float left = block_sum<LOGK>(blk, m), right = block_sum<LOGK>(blk + (1u << m), m);
+    const uint32_t turn = (pos >> m) & 1u;
+    tab[b].path[k] = make_float2(left, __uint_as_float(turn | (right != 0.0f ? 2u : 0u)));
+    skipped[item] = turn ? left : 0.0f;
+  }
+  __syncthreads();
+  // the mass in front of every owner's node: the left blocks its way from the root passes by (only used to guess
+  // where its run of samples starts); its own value; the total
+  for (uint32_t e = tid; e < count; e += BD) {
+    const uint32_t b = first + e;
+    double mass = 0.0;
+    for (uint32_t k = 0; k < n_steps; ++k) mass += (double)skipped[e * n_steps + k];
+    tab[b].mass = mass;
+    tab[b].total = total;
+    tab[b].node = top[sh.top_off[0] + b];
+  }
+}
+
+constexpr uint32_t kTableOwners = 8;   // owners whose tables one workgroup builds
+
+// In front of a step when another call has changed the tree since the tables were built.
+template <int LOGK>
 __global__ void __launch_bounds__(256)
-k_step_weights(Geom g, StepShape sh, uint32_t B, float beta, uint32_t weight_mode, float* __restrict__ w) {
+k_step_tables(StepShape sh) {
+  extern __shared__ __attribute__((aligned(16))) float top[];
+  const uint32_t t = blockIdx.y, first = blockIdx.x * kTableOwners;
+  const uint32_t count = sh.owners - first < kTableOwners ? sh.owners - first : kTableOwners;
+  __shared__ float skipped[kTableOwners * kStepPathMax];
+  build_tables<LOGK>(sh, t, sh.top_ptr[0] + (size_t)t * sh.top_stride[0], false, first, count, top, skipped);
+}
+
+// Ends a step: the first table_blocks workgroups take the owners' new nodes of height ho into the tree and build the
+// tables of the next call; beside them run the jobs of what is left of the sampling call (JobRanges: job 0 the
+// weights, jobs 2 + f the rows of field f): the weights job turns the sampled values the owners have left in w into importance weights
+// (the smallest of them sit in the slots of the call's parity; the call that has just finished is number
+// finished calls - 1).
+template <int LOGK, bool WIDE>
+__global__ void __launch_bounds__(256)
+k_step_epilogue(Geom g, StepShape sh, uint32_t table_blocks, uint32_t B, float beta, uint32_t weight_mode,
+                float* __restrict__ w, const uint32_t* __restrict__ idx, FieldTable ft, JobRanges jr) {
+  extern __shared__ __attribute__((aligned(16))) float top[];
   __shared__ uint32_t s_m[4];
+  __shared__ float skipped[kTableOwners * kStepPathMax];
   const uint32_t t = blockIdx.y;
+  if (blockIdx.x < table_blocks) {
+    const uint32_t first = blockIdx.x * kTableOwners;
+    const uint32_t count = sh.owners - first < kTableOwners ? sh.owners - first : kTableOwners;
+    build_tables<LOGK>(sh, t, sh.side + (size_t)t * sh.side_stride, true, first, count, top, skipped);
+    return;
+  }
+  const uint32_t job = blockIdx.x - table_blocks;
+  if (job >= jr.first[1]) {   // the rows of the sampled indices, one job per payload field
+    const uint32_t f = job_field(jr, job);
+    if (f < (uint32_t)kMaxFields)
+      rows_job<true, WIDE>(ft, f, t, B, idx, 0, g.N, g.status, job - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
+    return;
+  }
   const unsigned long long calls = sh.cnt[(size_t)t * kStepGroups] / owners_of_group(sh.owners, 0);
   const uint32_t par = (uint32_t)(calls - 1ull) & 1u;
   const uint32_t* slots = sh.vmin + ((size_t)t * 2 + par) * kVminSlots;
-  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t i = job * blockDim.x + threadIdx.x;
   const size_t o = (size_t)t * B + (i < B ? i : 0u);
   const float v = w[o];
   uint32_t m = wave_min_u32(slots[threadIdx.x % kVminSlots]);   // (256 lanes: every slot once)
@@ -833,31 +781,13 @@ k_step_weights(Geom g, StepShape sh, uint32_t B, float beta, uint32_t weight_mod
   if (i < B) w[o] = nothing_sampled ? 0.0f : importance_weight(v, __uint_as_float(m), beta);
 }
 
-// The side array's values become the level array's (for kernels that read height ho from the level array): when
-// an odd number of calls has run, one more is counted.  One workgroup per tree; nothing else runs on the buffer.
-__global__ void k_step_settle(StepShape sh) {
-  const uint32_t t = blockIdx.x;
-  unsigned long long* cnt = sh.cnt + (size_t)t * kStepGroups;
-  const unsigned long long calls = cnt[0] / owners_of_group(sh.owners, 0);
-  if (!(calls & 1ull)) return;   // (uniform over the workgroup)
-  const float* side = sh.side + (size_t)t * sh.side_stride;
-  float* lvl = sh.top_ptr[0] + (size_t)t * sh.top_stride[0];
-  for (uint32_t i = threadIdx.x; i < sh.top_n[0]; i += blockDim.x) lvl[i] = side[i];
-  // the words of the next parity start empty, as after a call
-  const uint32_t par = 1u;
-  for (uint32_t i = threadIdx.x; i < kVminSlots; i += blockDim.x) sh.vmin[((size_t)t * 2 + (par ^ 1u)) * kVminSlots + i] = 0x7F800000u;
-  if (threadIdx.x < kStepDoneSlots) sh.done[((size_t)t * 2 + (par ^ 1u)) * kStepDoneSlots + threadIdx.x] = 0u;
-  __syncthreads();
-  if (threadIdx.x < kStepGroups) cnt[threadIdx.x] += owners_of_group(sh.owners, threadIdx.x);
-}
-
 // The owner height of a tree for k_step, or 0 when the kernel does not fit it: the lowest height, not below the
 // tree pass's own workgroup roots, with at most 2048 nodes over all trees, whose subtrees (heights 1 .. ho-1)
 // and the heights from it to the root are small enough for LDS.
 uint32_t step_owner_height(const Geom& g) {
   if (g.logK < 3) return 0;
   for (uint32_t ho = tree_pass_height(g) < 2 ? 2 : tree_pass_height(g); ho + 1 <= g.H; ++ho) {
-    if ((uint64_t)g.n[ho] * g.T > 2048 || g.n[ho] > kLazyTopNodes) continue;
+    if ((uint64_t)g.n[ho] * g.T > kStepMaxOwners || g.n[ho] > kLazyTopNodes) continue;
     if (g.H - ho > (uint32_t)kStepTop || ho - 1 > (uint32_t)kStepSub) return 0;
     uint64_t sub = 0;
     for (uint32_t l = 1; l < ho; ++l) sub += 1ull << ((ho - l) * g.logK);
@@ -866,6 +796,7 @@ uint32_t step_owner_height(const Geom& g) {
   }
   return 0;
 }
+size_t step_table_bytes() { return (size_t)kStepMaxOwners * sizeof(StepTable); }
 
 // Workgroup size for a batch of B samples per tree: room for one and a half times the average run of samples
 // per owner, within what the staging rows leave of the LDS; 0 when the runs would be too long for one chunk
@@ -881,15 +812,18 @@ static uint32_t step_block(const Geom& g, uint32_t ho, uint32_t B) {
   return block < 64 ? 64 : block;
 }
 
+// Descriptors of both kernels' views of the tree; *step_lds: dynamic LDS of k_step with this block size; *table_lds: of
+// the kernels that build the tables.
 template <int LOGK>
-static void step_shape(const Geom& g, uint32_t block, uint32_t B, bool with_map, StepShape* out, size_t* lds_bytes) {
+static void step_shape(const Geom& g, uint32_t block, uint32_t B, bool with_map, StepShape* out, size_t* step_lds,
+                       size_t* table_lds) {
   constexpr int K = Fan<LOGK>::K;
   const uint32_t ho = g.step_ho;
   StepShape sh{};
   sh.n_top = g.H - ho;
   sh.n_sub = ho - 1;
   uint32_t off = 0;
-  for (uint32_t i = 0; i < sh.n_top; ++i) {
+  for (uint32_t i = 0; i < sh.n_top; ++i) {   // (LDS of the table kernels)
     const uint32_t l = ho + i;
     sh.top_ptr[i] = g.level[l];
     sh.top_stride[i] = g.stride[l];
@@ -898,7 +832,9 @@ static void step_shape(const Geom& g, uint32_t block, uint32_t B, bool with_map,
     sh.top_off[i] = off;
     off += sh.top_cnt[i];
   }
-  for (uint32_t i = 0; i < sh.n_sub; ++i) {
+  *table_lds = (size_t)off * 4;
+  off = 0;
+  for (uint32_t i = 0; i < sh.n_sub; ++i) {   // (LDS of k_step)
     const uint32_t l = 1 + i;
     sh.sub_ptr[i] = g.level[l];
     sh.sub_stride[i] = g.stride[l];
@@ -921,54 +857,63 @@ static void step_shape(const Geom& g, uint32_t block, uint32_t B, bool with_map,
     sh.builders = (B + 4u * block - 1u) / (4u * block);   // about four elements per builder lane
     if (sh.builders > 64) sh.builders = 64;
   }
+  sh.root = g.root;
+  sh.root_stride = g.root_stride;
   sh.side = g.step_side;
   sh.side_stride = g.step_side_stride;
+  sh.tab = reinterpret_cast<StepTable*>(g.step_tab);
   sh.cnt = g.step_cnt;
   sh.done = g.step_done;
   sh.vmin = g.step_vmin;
   sh.inv = reinterpret_cast<uint32_t*>(g.owner);
   sh.inv_stride = 2u * g.owner_stride;
   *out = sh;
-  *lds_bytes = (size_t)off * 4;
+  *step_lds = (size_t)off * 4;
 }
 
 template <int LOGK>
-static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block, uint32_t B, uint32_t size, float beta,
-                                uint32_t weight_mode, const float* u, const RngArgs& rng, uint32_t* out_idx,
+static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block, bool tables_valid, uint32_t B, uint32_t size,
+                                float beta, uint32_t weight_mode, const float* u, const RngArgs& rng, uint32_t* out_idx,
                                 float* out_prio, float* out_w, const float* upd_prio, const uint32_t* upd_pos,
-                                const FieldTable* rows, bool* refused, hipStream_t s) {
+                                const FieldTable* rows, hipStream_t s) {
   StepShape sh;
-  size_t bytes;
-  step_shape<LOGK>(g, block, B, upd_pos != nullptr, &sh, &bytes);
+  size_t bytes, table_bytes;
+  step_shape<LOGK>(g, block, B, upd_pos != nullptr, &sh, &bytes, &table_bytes);
   FieldTable ft{};
   if (rows) ft = *rows;
   const bool wide = any_field_moves_wide(rows ? &ft : nullptr);
-  hipError_t e = wide ? grant_lds<&k_step<LOGK, true>>(tn, bytes) : grant_lds<&k_step<LOGK, false>>(tn, bytes);
+  hipError_t e = grant_lds<&k_step<LOGK>>(tn, bytes);
   if (e != hipSuccess) return e;
-  const dim3 grid(sh.builders + sh.owners, g.T);
-  uint32_t early_field = 0xFFFFFFFFu, moved = 0;   // the single field that moves, if it moves 16 bytes at a time in at most 16 pieces
-  for (uint32_t f = 0; rows && f < ft.n_fields; ++f)
-    if (ft.io[f]) {
-      ++moved;
-      early_field = f;
-    }
-  if (moved != 1 || ft.vec[early_field] != 16 || ft.bytes[early_field] / 16u > 16u) early_field = 0xFFFFFFFFu;
-  if (wide) {
-    PER_LAUNCH(KID_STEP, (k_step<LOGK, true>), grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx,
-               out_prio, out_w, upd_prio, upd_pos, ft, rows ? 1u : 0u, early_field);
-  } else {
-    PER_LAUNCH(KID_STEP, (k_step<LOGK, false>), grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx,
-               out_prio, out_w, upd_prio, upd_pos, ft, rows ? 1u : 0u, early_field);
+  const uint32_t table_blocks = (sh.owners + kTableOwners - 1u) / kTableOwners;
+  if (!tables_valid) {
+    PER_LAUNCH(KID_STEP_TABLES, k_step_tables<LOGK>, dim3(table_blocks, g.T), dim3(256), table_bytes, s, sh);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
   }
+  const dim3 grid(sh.builders + sh.owners, g.T);
+  PER_LAUNCH(KID_STEP, k_step<LOGK>, grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx, out_prio, out_w,
+             upd_prio, upd_pos);
   e = hipGetLastError();
-  if (e != hipSuccess || !out_w) return e;
-  PER_LAUNCH(KID_STEP_WEIGHTS, k_step_weights, dim3((B + 255u) / 256u, g.T), dim3(256), 0, s, g, sh, B, beta, weight_mode, out_w);
+  if (e != hipSuccess) return e;
+  const JobRanges jr = job_ranges(rows ? &ft : nullptr, B, 256, out_w ? B : 0u, 0u, g.T);
+  const dim3 egrid(table_blocks + jr.first[2 + kMaxFields], g.T);
+  if (wide) {
+    PER_LAUNCH(KID_STEP_EPILOGUE, (k_step_epilogue<LOGK, true>), egrid, dim3(256), table_bytes, s, g, sh, table_blocks, B, beta,
+               weight_mode, out_w, out_idx, ft, jr);
+  } else {
+    PER_LAUNCH(KID_STEP_EPILOGUE, (k_step_epilogue<LOGK, false>), egrid, dim3(256), table_bytes, s, g, sh, table_blocks, B, beta,
+               weight_mode, out_w, out_idx, ft, jr);
+  }
   return hipGetLastError();
 }
 
-// Block size k_step would run a batch of B with, 0 when it does not take that batch (or that tree).
-uint32_t step_fits(const Geom& g, uint32_t B) {
+// Block size k_step would run a batch of B with, 0 when it does not take that batch (or that tree).  `always`
+// (a tuning value for tests) lifts the limits that are there for speed only: the kernel pays off for long runs
+// of samples per owner on few trees (measured: 65536 samples on one tree of 2^24 leaves 21 against 28 us per
+// step; batches of 32 .. 4096, or 64 trees with an insert between the steps, are faster as separate kernels).
+uint32_t step_fits(const Geom& g, uint32_t B, bool always) {
   if (!g.step_ho || B == 0 || (uint64_t)B > 2ull * g.owner_stride) return 0;
+  if (!always && (g.T > 8 || (uint64_t)B < 64ull * g.n[g.step_ho])) return 0;
   switch (g.logK) {
     case 3: return step_block<3>(g, g.step_ho, B);
     case 4: return step_block<4>(g, g.step_ho, B);
@@ -978,14 +923,13 @@ uint32_t step_fits(const Geom& g, uint32_t B) {
   }
 }
 
-// The whole step as one kernel.  *refused: the kernel was not launched because its workgroups would not all be
-// resident at once (nothing was enqueued).
-hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, uint32_t B, uint32_t size, float beta,
-                       const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio,
+// The whole step: [the tables, when tables_valid says they are not current], k_step, the epilogue.  Afterwards the
+// tree's memory is in order at every height and the tables are current.
+hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, bool tables_valid, uint32_t B, uint32_t size,
+                       float beta, const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio,
                        uint32_t weight_mode, const FieldTable* rows, const float* upd_prio, const uint32_t* upd_pos,
-                       bool* refused, hipStream_t s) {
-  *refused = false;
-#define CALL(L) launch_step_k<L>(g, tn, block, B, size, beta, weight_mode, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, rows, refused, s)
+                       hipStream_t s) {
+#define CALL(L) launch_step_k<L>(g, tn, block, tables_valid, B, size, beta, weight_mode, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, rows, s)
   switch (g.logK) {
     case 3: return CALL(3);
     case 4: return CALL(4);
@@ -994,21 +938,4 @@ hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, uint32_t
     default: return hipErrorInvalidValue;
   }
 #undef CALL
-}
-
-// Makes the level array of the owner height current again after k_step calls (see k_step_settle).
-hipError_t launch_step_settle(const Geom& g, const Tuning& tn, hipStream_t s) {
-  if (!g.step_ho) return hipSuccess;
-  StepShape sh{};
-  sh.top_ptr[0] = g.level[g.step_ho];
-  sh.top_stride[0] = g.stride[g.step_ho];
-  sh.top_n[0] = g.n[g.step_ho];
-  sh.owners = g.n[g.step_ho];
-  sh.side = g.step_side;
-  sh.side_stride = g.step_side_stride;
-  sh.cnt = g.step_cnt;
-  sh.done = g.step_done;
-  sh.vmin = g.step_vmin;
-  PER_LAUNCH(KID_STEP_SETTLE, k_step_settle, dim3(g.T), dim3(256), 0, s, sh);
-  return hipGetLastError();
 }

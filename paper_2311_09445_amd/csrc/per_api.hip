@@ -24,7 +24,8 @@ struct per_buffer {
   int weight_norm;           // PER_NORM_BATCH or PER_NORM_BUFFER
   bool min_stale;            // min1 does not describe the leaves (it is rebuilt when next needed)
   uint32_t stale_hb;         // != 0: the last update left the heights above this one to their next reader
-  bool side_maybe;           // the one-kernel step may have left the nodes of its owner height in the side array
+  bool tables_valid;         // the per-owner tables of the one-kernel step describe the tree as it is
+  unsigned long long capture_id;   // the stream capture the last call was recorded into (0: it ran eagerly)
   bool rng_on;               // per_set_rng was called: sampling calls without uniforms draw their own
   uint64_t rng_seed, rng_calls;   // key of the generator; number of sampling calls that drew from it
   int device;
@@ -43,7 +44,7 @@ struct Layout {
   uint32_t n[kMaxHeight + 1];
   uint32_t stride[kMaxHeight + 1];
   size_t level_off[kMaxHeight + 1];
-  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, min1_off, side_off, step_off, col_off[kMaxFields];
+  size_t scalars_off, owner_off, nclaim_off, dirty_off, arrive_off, min1_off, side_off, tab_off, step_off, col_off[kMaxFields];
   uint32_t dirty_stride, arrive_stride, arrive_level_off[kMaxHeight + 1];
   uint64_t col_stride[kMaxFields];
   uint32_t row_stride;        // bytes between stored rows
@@ -118,8 +119,10 @@ void make_layout(const per_config* c, Layout* L) {
   L->min1_stride = (uint32_t)round_up(L->n[1], 64);
   L->min1_off = off;
   off = round_up(off + (size_t)L->min1_stride * T * 4, kAlign);
-  L->side_off = off;                            // second array for the nodes of the one-kernel step's owner height
+  L->side_off = off;                            // where the owners of the one-kernel step leave their nodes of the owner height
   off = round_up(off + (size_t)kStepSideStride * T * 4, kAlign);
+  L->tab_off = off;                             // its per-owner tables
+  off = round_up(off + step_table_bytes(), kAlign);
   L->tree_end = off;
   // payload, row-major: every field at an offset aligned to the widest access its size allows, rows 16 bytes apart or a multiple
   uint32_t row = 0;
@@ -173,19 +176,8 @@ hipError_t reduce_min(per_t* p, hipStream_t s, uint32_t* weight_mode) {
   return launch_min_reduce(p->g, p->tn, weight_mode, s);
 }
 
-// After one-kernel steps the nodes of their owner height may live in the side array; every other kernel reads
-// the level array, so they are moved back first (a small kernel that looks at the device-side word itself).
-hipError_t settle_side(per_t* p, hipStream_t s) {
-  if (!p->side_maybe) return hipSuccess;
-  hipError_t e = launch_step_settle(p->g, p->tn, s);
-  if (e == hipSuccess) p->side_maybe = false;
-  return e;
-}
-
 // Rebuilds the heights an update left stale, for readers that take them from memory.
 hipError_t ensure_top(per_t* p, hipStream_t s) {
-  hipError_t e0 = settle_side(p, s);
-  if (e0 != hipSuccess) return e0;
   if (!p->stale_hb) return hipSuccess;
   hipError_t e = launch_resum_top(p->g, p->tn, p->stale_hb, s);
   if (e == hipSuccess) p->stale_hb = 0;
@@ -194,35 +186,36 @@ hipError_t ensure_top(per_t* p, hipStream_t s) {
 
 // A call made while its stream is being captured into a HIP graph does not run now and may run many times
 // later, in between other work on the buffer.  What the host has noted about the device (are the topmost
-// heights current, is the companion minimum current) therefore holds neither for the captured kernels nor
-// after the call: both are taken as "not current" on entry and left so on exit.  Rebuilding heights that
-// are current is harmless, so a captured call is correct on every replay whatever ran before it.
-bool stream_is_capturing(hipStream_t s) {
-  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
-  return hipStreamIsCapturing(s, &st) == hipSuccess && st == hipStreamCaptureStatusActive;
-}
+// heights current, is the companion minimum current, are the step tables current) therefore says nothing
+// about the state a replay starts from: it is all taken as "not current".  Rebuilding what is current is
+// harmless, so a captured call is correct on every replay whatever ran before it.
 void forget_device_notes(per_t* p) {
   const uint32_t hb = lazy_top_height(p->g, p->tn);
   if (hb) p->stale_hb = hb;
   p->min_stale = true;
-  if (p->g.step_ho) p->side_maybe = true;
+  p->tables_valid = false;
 }
-// Before a tree pass: the level array of every height it writes must be the current one, and the heights it
-// does not rewrite in full (up to its workgroup roots) must not be stale below those roots.
+// Before a tree pass: the heights it does not rewrite in full (up to its workgroup roots) must not be stale below
+// those roots.
 hipError_t prepare_tree_pass(per_t* p, hipStream_t s) {
   const uint32_t hb = lazy_top_height(p->g, p->tn);
+  p->tables_valid = false;   // (the pass changes the tree)
   if (p->stale_hb && (!hb || p->stale_hb < hb)) return ensure_top(p, s);
-  return settle_side(p, s);
+  return hipSuccess;
 }
 
+// The notes are dropped when a call is the first of a capture (whatever ran before the graph's replays is not
+// known) and when the first eager call follows captured ones (the graph may have been replayed any number of
+// times, or never).  Between the calls of one capture they are kept: a replay runs those calls in that order.
 struct CaptureGuard {
-  per_t* p;
-  bool on;
-  CaptureGuard(per_t* p_, hipStream_t s) : p(p_), on(p_ && stream_is_capturing(s)) {
-    if (on) forget_device_notes(p);
-  }
-  ~CaptureGuard() {
-    if (on) forget_device_notes(p);
+  CaptureGuard(per_t* p, hipStream_t s) {
+    if (!p) return;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    unsigned long long id = 0;
+    if (hipStreamGetCaptureInfo(s, &st, &id) != hipSuccess || st != hipStreamCaptureStatusActive) id = 0;
+    else if (id == 0) id = ~0ull;
+    if (id != p->capture_id) forget_device_notes(p);
+    p->capture_id = id;
   }
 };
 
@@ -289,6 +282,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.vmin_buf = g.vmin + (size_t)2 * kVminSlots * g.T;
   g.step_side = reinterpret_cast<float*>(p->arena + L.side_off);
   g.step_side_stride = kStepSideStride;
+  g.step_tab = p->arena + L.tab_off;
   g.step_ho = step_owner_height(g);
   g.min1 = reinterpret_cast<uint32_t*>(p->arena + L.min1_off);
   g.min1_stride = L.min1_stride;
@@ -310,7 +304,8 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->claims_left = false;
-  p->side_maybe = false;
+  p->tables_valid = false;
+  p->capture_id = 0;
   p->weight_norm = PER_NORM_BATCH;
   p->min_stale = true;
   if (hipGetDevice(&p->device) != hipSuccess) { delete p; return PER_EHIP; }
@@ -342,7 +337,7 @@ static int insert_impl(per_t* p, uint32_t n, const void* const* d_field_src, con
   if (!d_protect) n_protect = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   CaptureGuard capture(p, s);
-  if (settle_side(p, s) != hipSuccess) return PER_EHIP;
+  p->tables_valid = false;   // (the insert changes the tree)
   const uint64_t N = p->cfg.capacity;
   const uint32_t cursor = (uint32_t)p->cursor;
   FieldTable ft;
@@ -446,17 +441,17 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
     if (!ranges_overlap(d_upd_prio, n_out, d_out_idx, n_out) && !ranges_overlap(d_upd_prio, n_out, d_out_weight, n_out) &&
         !ranges_overlap(d_upd_prio, n_out, d_out_prio, n_out) && !ranges_overlap(d_upd_pos, n_out, d_out_idx, n_out) &&
         !ranges_overlap(d_upd_pos, n_out, d_out_weight, n_out) && !ranges_overlap(d_upd_pos, n_out, d_out_prio, n_out))
-      step_block = step_fits(p->g, B);
+      step_block = step_fits(p->g, B, p->tn.step_kernel == 2);
   }
   if (step_block) {
-    // the kernel reads the heights up to its owner height from memory: none of them may be stale
-    if (p->stale_hb && p->stale_hb < p->g.step_ho && ensure_top(p, s) != hipSuccess) return PER_EHIP;
-    if (p->claims_left) {   // (its scratch words alias the leaf stamps, which must be zero)
+    // the tables are built from the nodes of the owner height: when they are rebuilt, that height must not be stale
+    if (!p->tables_valid && p->stale_hb && p->stale_hb < p->g.step_ho && ensure_top(p, s) != hipSuccess) return PER_EHIP;
+    if (p->claims_left) {   // (the kernel's scratch words alias the leaf stamps, which must be zero)
       ClaimArgs none{};
       int rc = prepare_claim(p, B, s, &none);
       if (rc != PER_OK) return rc;
     }
-  } else if ((upd_B ? prepare_tree_pass(p, s) : settle_side(p, s)) != hipSuccess) {
+  } else if (upd_B && prepare_tree_pass(p, s) != hipSuccess) {
     return PER_EHIP;
   }
   uint32_t weight_mode = 0;
@@ -471,20 +466,20 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
       rng.seed_hi = (uint32_t)(p->rng_seed >> 32);
       rng.call_lo = (uint32_t)p->rng_calls;
       rng.call_hi = (uint32_t)(p->rng_calls >> 32);
+      ++p->rng_calls;
     }
-    bool refused = false;
-    hipError_t e = launch_step(p->g, p->tn, step_block, B, (uint32_t)p->size, beta, d_u, rng, d_out_idx, d_out_weight,
-                               d_out_prio, weight_mode, fused ? &ft : nullptr, d_upd_prio, d_upd_pos, &refused, s);
-    if (!refused) {
-      if (!d_u) ++p->rng_calls;
-      p->min_stale = true;          // (the kernel does not renew the companion minimum)
-      p->stale_hb = p->g.step_ho;   // the heights above the owner height are left to their next reader,
-      p->side_maybe = true;         // and the nodes of that height may be in the side array
-      if (e != hipSuccess) p->claims_left = true;
-      return hip_rc(e);
+    hipError_t e = launch_step(p->g, p->tn, step_block, p->tables_valid, B, (uint32_t)p->size, beta, d_u, rng, d_out_idx,
+                               d_out_weight, d_out_prio, weight_mode, fused ? &ft : nullptr, d_upd_prio, d_upd_pos, s);
+    p->min_stale = true;   // (the kernel does not renew the companion minimum)
+    if (e == hipSuccess) {
+      p->stale_hb = 0;          // its epilogue has put every height in order
+      p->tables_valid = true;   // and built the tables of the next step
+    } else {
+      p->tables_valid = false;
+      p->stale_hb = lazy_top_height(p->g, p->tn);
+      p->claims_left = true;
     }
-    // (nothing was enqueued: the separate kernels take over)
-    if (prepare_tree_pass(p, s) != hipSuccess) return PER_EHIP;
+    return hip_rc(e);
   }
   ClaimArgs claim{};
   int claim_mode = CLAIM_NONE;
@@ -625,6 +620,7 @@ int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx, const float* d
   hipStream_t s = static_cast<hipStream_t>(stream);
   CaptureGuard capture(p, s);
   p->min_stale = true;               // (changes added by atomics: min1 cannot follow them)
+  p->tables_valid = false;
   hipError_t e = ensure_top(p, s);   // changes are added to whole nodes: the top heights must be current
   if (e == hipSuccess) e = launch_update_delta(p->g, p->tn, B, (uint32_t)p->size, d_idx, d_delta, s);
   return hip_rc(e);
@@ -654,6 +650,7 @@ int per_run_steps(per_t* p, uint32_t n_steps, uint32_t n_insert, uint32_t B, con
   a.upd_is_sampled = io->d_upd_prio && !io->d_upd_idx ? 1u : 0u;
   a.buffer_norm = p->weight_norm == PER_NORM_BUFFER ? 1u : 0u;
   p->min_stale = true;   // (the kernel works on an LDS copy of the leaves and does not keep min1)
+  p->tables_valid = false;
   a.u = io->d_u;
   a.beta = io->d_beta;
   a.out_idx = io->d_out_idx;
@@ -712,6 +709,7 @@ int per_run_requests(per_t* p, uint32_t n_requests, const per_request* h_request
   a.n_requests = n_requests;
   a.buffer_norm = p->weight_norm == PER_NORM_BUFFER ? 1u : 0u;
   p->min_stale = true;   // (as per_run_steps)
+  p->tables_valid = false;
   a.cursor = (uint32_t)p->cursor;
   a.size = (uint32_t)p->size;
   a.queue = d_requests;
@@ -726,7 +724,7 @@ int per_rebuild(per_t* p, void* stream) {
   if (!p) return PER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   CaptureGuard capture(p, s);
-  if (settle_side(p, s) != hipSuccess) return PER_EHIP;   // (the word that names the side array goes back to "level array")
+  p->tables_valid = false;
   // all leaves count as touched: every height is recomputed in full, bottom-up
   hipError_t e = launch_resum_ranges(p->g, p->tn, Range2{0, p->g.N, 0, 0}, s);
   if (e != hipSuccess) return PER_EHIP;
@@ -748,7 +746,6 @@ int per_read_level(per_t* p, uint32_t tree, uint32_t height, float* d_out, uint6
   if (!d_out) return PER_OK;
   if (misaligned(d_out, 4)) return PER_EINVAL;
   CaptureGuard capture(p, static_cast<hipStream_t>(stream));
-  if (height == p->g.step_ho && settle_side(p, static_cast<hipStream_t>(stream)) != hipSuccess) return PER_EHIP;
   if (p->stale_hb && height > p->stale_hb && ensure_top(p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return PER_EHIP;
   const float* src = p->g.level[height] + (size_t)tree * p->g.stride[height];
@@ -798,6 +795,7 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size) {
   p->size = size;
   p->stale_hb = lazy_top_height(p->g, p->tn);   // a saved arena may predate the rebuild of its top heights
   p->min_stale = true;
+  p->tables_valid = false;
   return PER_OK;
 }
 
@@ -837,8 +835,7 @@ int per_min_priority_static(per_t* p, float* d_out, void* stream) {
 
 int per_note_replay(per_t* p) {
   if (!p) return PER_EINVAL;
-  p->stale_hb = lazy_top_height(p->g, p->tn);   // a replayed update has left the topmost heights to their next reader
-  p->min_stale = true;                          // and may not have renewed the companion minimum
+  forget_device_notes(p);   // a replayed update has left the topmost heights to their next reader, and so on
   return PER_OK;
 }
 
@@ -884,7 +881,7 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
     return PER_OK;
   }
   if (!strcmp(name, "step_kernel")) {
-    if (value != 0 && value != 1) return PER_EINVAL;
+    if (value < 0 || value > 2) return PER_EINVAL;
     p->tn.step_kernel = (uint32_t)value;
     return PER_OK;
   }

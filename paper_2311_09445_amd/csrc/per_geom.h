@@ -20,6 +20,7 @@ constexpr int kMaxFields = 8;
 constexpr uint32_t kVminSlots = 256;   // partial batch minima per tree and buffer
 constexpr uint32_t kStepGroups = 64;   // counters the owners of the one-kernel step are spread over (one wave reads them all)
 constexpr uint32_t kStepDoneSlots = 8; // counters its builders are spread over
+constexpr uint32_t kStepMaxOwners = 2048;   // most owner workgroups over all trees
 
 struct Geom {
   uint32_t K, logK, H, T;
@@ -49,7 +50,8 @@ struct Geom {
   uint32_t min1_stride;
   uint32_t* vmin_buf;               // [T][kMinParts] partial minima of min1 (fp32 bits), one per workgroup of k_min_reduce
   uint32_t step_ho;                 // owner height of the one-kernel step (0: that kernel does not fit this tree)
-  float*   step_side;               // [T][step_side_stride] second array for the nodes of height step_ho
+  float*   step_side;               // [T][step_side_stride] where its owners leave the new nodes of height step_ho
+  void*    step_tab;                // its per-owner tables
   uint32_t step_side_stride;
   unsigned long long* step_cnt;     // [T][kStepGroups] owners of the one-kernel step that have finished, over all calls
   uint32_t* step_done;              // [T][2][kStepDoneSlots] its builders that have finished (by parity of the call)
@@ -171,7 +173,7 @@ struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
   KID_RESUM_TAIL, KID_UPDATE_CLAIM, KID_UPDATE_TREE, KID_TREE_FINISH, KID_UPDATE_DELTA, KID_GET_PRIORITY,
-  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_MIN_REBUILD, KID_MIN_REDUCE, KID_STEP, KID_STEP_SETTLE, KID_STEP_WEIGHTS, KID_COUNT
+  KID_INSERT_SMALL, KID_RUN_STEPS, KID_RUN_REQUESTS, KID_MIN_REBUILD, KID_MIN_REDUCE, KID_STEP, KID_STEP_TABLES, KID_STEP_EPILOGUE, KID_COUNT
 };
 const char* kernel_name(int kid);
 
@@ -194,7 +196,7 @@ struct Tuning {
   uint32_t insert_small;      // small inserts run as one kernel (one workgroup per tree)
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   uint32_t group_claim;       // update batches claim through the group entries whenever they are short enough
-  uint32_t step_kernel;       // per_step runs sampling and update as one kernel where that kernel fits
+  uint32_t step_kernel;       // per_step runs sampling and update as one kernel: 0 never, 1 where it fits and pays off, 2 wherever it fits
   Profiler* prof;
   int device;                 // the device the buffer lives on
 };
@@ -225,12 +227,12 @@ uint32_t lazy_top_height(const Geom& g, const Tuning& tn);
 hipError_t launch_update(const Geom& g, const Tuning& tn, const ClaimArgs& c, hipStream_t s);
 hipError_t launch_update_delta(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, const uint32_t* idx,
                                const float* delta, hipStream_t s);
-uint32_t step_fits(const Geom& g, uint32_t B);
-hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, uint32_t B, uint32_t size, float beta,
-                       const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio,
+uint32_t step_fits(const Geom& g, uint32_t B, bool always);
+hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, bool tables_valid, uint32_t B, uint32_t size,
+                       float beta, const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio,
                        uint32_t weight_mode, const FieldTable* rows, const float* upd_prio, const uint32_t* upd_pos,
-                       bool* refused, hipStream_t s);
-hipError_t launch_step_settle(const Geom& g, const Tuning& tn, hipStream_t s);
+                       hipStream_t s);
+size_t step_table_bytes();
 uint32_t stream_tree_floats(const Geom& g, uint32_t* off);
 hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s);
 hipError_t launch_run_requests(const Geom& g, const Tuning& tn, const QueueArgs& a, hipStream_t s);

@@ -25,7 +25,7 @@ const char* kernel_name(int kid) {
       "k_fill_u32", "k_sample", "k_weights", "k_rows_gather", "k_finish", "k_rows_scatter", "k_insert_leaves",
       "k_resum_dense", "k_resum_tail", "k_update_claim", "k_update_tree", "k_tree_finish", "k_update_delta",
       "k_get_priority", "k_insert_small", "k_run_steps", "k_run_requests", "k_min_rebuild", "k_min_reduce", "k_step",
-      "k_step_settle", "k_step_weights"};
+      "k_step_tables", "k_step_epilogue"};
   return kid >= 0 && kid < KID_COUNT ? names[kid] : "?";
 }
 

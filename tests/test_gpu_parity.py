@@ -26,16 +26,18 @@ def log(msg):
     print(msg, flush=True)
 
 
-@pytest.fixture(autouse=True, params=["group", "leaf"])
+@pytest.fixture(autouse=True, params=["group", "leaf", "owner"])
 def claim_form(request, monkeypatch):
-    """Every test runs twice: update batches claim their leaves through the group entries (the default)
-    or leaf by leaf."""
-    if request.param == "leaf":
+    """Every test runs three times: update batches claim their leaves through the group entries (the default),
+    leaf by leaf, or (third run) steps that update the batch they sample run as the one-kernel step wherever the
+    tree fits it, not only where it pays off."""
+    if request.param != "group":
         created = PrioritizedReplay.__init__
+        name, value = ("group_claim", 0) if request.param == "leaf" else ("step_kernel", 2)
 
         def create_then_set(self, *a, **kw):
             created(self, *a, **kw)
-            self.set_tuning("group_claim", 0)
+            self.set_tuning(name, value)
 
         monkeypatch.setattr(PrioritizedReplay, "__init__", create_then_set)
     return request.param
@@ -766,7 +768,7 @@ def test_captured_step_replays(K, N, B):
 @pytest.mark.parametrize("K,N,T,B,fb", [(32, 1 << 20, 1, 30000, (128,)), (16, 1 << 18, 3, 1024, (68, 24, 4, 68, 1)),
                                         (2, 5000, 1, 64, ()), (4, 70001, 2, 3000, (12,)), (64, 300001, 1, 5000, (8,)),
                                         (8, 1 << 21, 1, 9000, ())])
-@pytest.mark.parametrize("one_kernel", [1, 0])
+@pytest.mark.parametrize("one_kernel", [2, 0])
 def test_step_call_updates_the_batch_it_draws(K, N, T, B, fb, one_kernel):
     """per_step: the update targets the leaves drawn by this very call, directly or through a position map
     (the duplicate map of the stress workload; maps with many elements on one sample; invalid positions).
@@ -809,6 +811,7 @@ def test_step_call_when_the_mass_sits_in_few_places(K, N, T, B):
     log(f"per_step, concentrated mass K={K} N={N} T={T} B={B}")
     rng = np.random.default_rng(K + B)
     m = Mirror(K, N, T, ())
+    m.gpu.set_tuning("step_kernel", 2)
     base = (rng.random((T, N)).astype(np.float32) * 0.5 + 0.25).astype(np.float32)
     m.insert(N, prio=base, chunk=1 << 18, with_rows=False)
     hot = N // 3 + 5
