@@ -445,6 +445,31 @@ def test_workload_c4_full_size():
     m.compare_status()
 
 
+@pytest.mark.parametrize("name,steps", [("c2_dqn", 10000), ("c3_ddpg", 2000), ("c4_stress", 600), ("c5_multi", 1000)])
+def test_workloads_at_full_length(name, steps, claim_form):
+    """The workloads over their whole length (the stress workload past the point where the stamp counter of the claim
+    group entries turns over, every 512 of its steps): indices, sampled values, weights and rows compared with the
+    oracle at every step, every stored node every 50th step and at the end; the first mismatch stops the run.
+    The steps rotate through the call forms (separate calls, sample + gather, the fused step with a separate
+    update array, per_step).  One run per workload (the default claim form)."""
+    if claim_form != "group":
+        pytest.skip("one run per workload")
+    import time
+    w = wl.WORKLOADS[name]
+    t0 = time.time()
+    log(f"workload {name}: all {steps} steps")
+    big = w.N * w.T >= 1 << 24
+    m = Mirror(w.K, w.N, w.T, w.field_bytes, oracle_payload=not big)
+    m.insert(w.N, prio=wl.initial_priorities(w, 0), chunk=1 << (20 if w.T == 1 else 16))
+    m.compare_tree()
+    for s in range(steps):
+        m.step(w, s, check_tree=False)
+        if s % 50 == 49 or s == steps - 1:
+            m.compare_tree()
+            log(f"  {name}: step {s + 1} of {steps}, tree equal, {time.time() - t0:.0f} s")
+    m.compare_status()
+
+
 # ---------------------------------------------------------------------------------------------
 # Priority update in the paper's form (per_update_delta, Section V-A).  Changes meet in no fixed order,
 # so: bit-exact against the oracle where every fp32 sum is exact (dyadic values: any order gives the same
