@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--no-delta-form", action="store_true",
                     help="skip the extra timing of the step with the paper's delta-propagation update")
     ap.add_argument("--tune", action="append", default=[], help="name=value passed to per_set_tuning")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="time only the headline form (for profiler runs: every kernel launch then belongs to it)")
     ap.add_argument("--weight-norm", choices=["batch", "buffer"], default="batch",
                     help="importance weights relative to the sampled batch (the metric's form) or to the whole buffer")
     return ap.parse_args()
@@ -278,8 +280,11 @@ def main():
     # (same trajectory: the array holds what the headline form derives inside the step)
     d_upd_idx.copy_(torch.from_numpy(rec_upd.view(np.int32)).cuda())
     overlap = args.overlap and not fused
-    ms_early, kernels_early, idx_early, root_early, _, _ = time_form(step, overlap=overlap)
-    assert np.array_equal(idx_early, rec_idx) and root_early.tobytes() == final_root.tobytes(), "the two forms disagree"
+    if args.only_headline:
+        ms_early, kernels_early = ms_per_step, kernels
+    else:
+        ms_early, kernels_early, idx_early, root_early, _, _ = time_form(step, overlap=overlap)
+        assert np.array_equal(idx_early, rec_idx) and root_early.tobytes() == final_root.tobytes(), "the two forms disagree"
     restore_ok = True
 
     # ---------------------------------------------------------------- algorithmic bytes and roofline
@@ -558,7 +563,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "cpu_workers_baseline": cpu_workers,
-        "earlier_batch_form": early_form,
+        "earlier_batch_form": None if args.only_headline else early_form,
         "paper_update_form": delta_form,
         "step_stream": step_stream,
         "step_algorithmic_bytes": int(a_step),
