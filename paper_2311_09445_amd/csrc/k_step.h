@@ -285,7 +285,6 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
 
   PER_TRACE_DECL;
   PER_MARK(0);
-  PER_MARK_HWID(15);
   // ---- trip 1: the number of finished calls, this owner's table, the own subtree's heights, the running maximum
   unsigned long long count0 = 0;
   {
