@@ -46,6 +46,8 @@ def parse():
                     help="call per_sample and per_gather separately instead of the fused per_sample_gather")
     ap.add_argument("--separate-update", action="store_true",
                     help="call per_update by itself instead of per_sample_gather_update")
+    ap.add_argument("--separate-insert", action="store_true",
+                    help="call per_insert and per_step instead of per_insert_step (workloads with a per-step insert)")
     ap.add_argument("--overlap", action="store_true",
                     help="with --separate-gather: run the row gather on a second stream beside the update")
     ap.add_argument("--no-delta-form", action="store_true",
@@ -180,10 +182,13 @@ def main():
     def step_in(s):
         """The loop of Listing 2 as it is: insert -> sample -> gather -> update of the batch just sampled (through the
         duplicate position map where the workload has one), one per_step call."""
-        if w.n_insert:
+        ins = None
+        if w.n_insert and args.separate_insert:
             buf.insert(w.n_insert, ins_rows[s])
+        elif w.n_insert:
+            ins = (w.n_insert, ins_rows[s], None, None)      # per_insert_step: the insertion inside the step call
         buf.step(d_u[s], inputs[s]["beta"], d_prio[s], None if d_pos is None else d_pos[s], want_weights=w.weights,
-                 want_prio=True, out_idx=d_idx[s], out_weight=d_w, out_prio=d_v, rows_out=d_rows)
+                 want_prio=True, out_idx=d_idx[s], out_weight=d_w, out_prio=d_v, rows_out=d_rows, insert=ins)
 
     def step(s, overlap=False):
         """The relaxed form: the update batch of step s is a separate array that exists before the step starts.
@@ -557,7 +562,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "K": K, "N": N, "T": T, "B": B, "row_bytes": w.row_bytes,
                    "insert_per_step": w.n_insert, "launch": "hip_graph" if graphed else "eager",
-                   "streams": 1, "weight_norm": args.weight_norm, "calls_per_step": "per_step",
+                   "streams": 1, "weight_norm": args.weight_norm,
+                   "calls_per_step": "per_insert_step" if w.n_insert and not args.separate_insert else
+                                     "per_insert, per_step" if w.n_insert else "per_step",
                    "update_indices": "this step's sampled indices" +
                                      (" through the duplicate position map, applied inside the step" if has_dup else "")},
         "roofline": roofline,

@@ -166,6 +166,22 @@ int per_step(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out
              float* d_out_prio, void* const* d_field_dst, const float* d_upd_prio, const uint32_t* d_upd_pos,
              void* stream);
 
+/* per_insert(n, d_field_src, d_ins_prio, d_ins_out_idx) followed by per_step(...) as one call with the same results:
+ * the iteration of Listing 2 (Section IV-D) with the Actors' new rows put in first (Section II-A: insertion at
+ * the maximum priority, or at given values).  Where the insertion is small (at most 1024 rows per tree, few
+ * touched nodes), the buffer's weights refer to the batch, and the tree's topmost heights are rebuilt lazily
+ * (tuning "lazy_top"), the sampling kernel of the step carries the insertion: each of its workgroups works out
+ * the few new nodes for itself and samples from the tree as the insertion leaves it, one of them stores them,
+ * one extra workgroup moves the rows; the step then takes two kernel launches, insertion included.  For that the
+ * insertion's arrays (d_field_src[f], d_ins_prio, d_ins_out_idx) must not overlap the step's outputs and
+ * d_ins_out_idx none of the step's inputs either; otherwise, and for any other shape, the two calls are made one
+ * after the other.  Arguments, flags and errors as for the two calls; an argument error of the step is
+ * reported before the insertion is enqueued. */
+int per_insert_step(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_ins_prio,
+                    uint32_t* d_ins_out_idx, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx,
+                    float* d_out_weight, float* d_out_prio, void* const* d_field_dst, const float* d_upd_prio,
+                    const uint32_t* d_upd_pos, void* stream);
+
 /* Priority update (Section V-A), in the set-and-re-sum form: every valid element sets its
  * leaf; when an index occurs more than once the element latest in the batch wins;
  * afterwards every ancestor of a touched leaf equals the pairwise sum of its children.
@@ -362,6 +378,7 @@ uint64_t per_rng_calls(const per_t* p);
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
  *                  the next call that reads them; 0 makes per_update finish them itself
  *   "insert_small" : 1 (default) runs an insert of few rows as a single kernel, one workgroup per tree
+ *   "insert_ride" : 1 (default) lets the sampling kernel of per_insert_step carry the insertion; 0: two calls
  *   "step_kernel" : how per_step (and per_sample_gather_update called with the sampled batch as its update batch)
  *                  runs.  1 (default): sampling and update as one kernel, one workgroup per subtree, with rows and
  *                  weights in a second, where the tree fits that kernel and the batch is large enough for it

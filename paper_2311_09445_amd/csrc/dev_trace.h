@@ -21,13 +21,19 @@ __device__ unsigned long long g_trace[kTraceBlocks * kTraceMarks];
     const unsigned long long now_ = wall_clock64();                                            \
     _Pragma("unroll") for (int k_ = 0; k_ < kTraceMarks; ++k_) if (k_ == (int)(i)) tm_[k_] = now_; \
   } while (0)
-#define PER_FLUSH()                                                                            \
+// Kernels flush under tag 0, or under a tag of their own; only the selected tag's flushes are kept.
+__device__ int g_trace_tag = 0;
+#define PER_FLUSH() PER_FLUSH_TAG(0)
+#define PER_FLUSH_TAG(tag)                                                                     \
   do {                                                                                         \
-    if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < kTraceBlocks) {                    \
+    if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < kTraceBlocks && g_trace_tag == (tag)) { \
       _Pragma("unroll") for (int k_ = 0; k_ < kTraceMarks; ++k_)                               \
         g_trace[blockIdx.x * kTraceMarks + k_] = tm_[k_];                                      \
     }                                                                                          \
   } while (0)
+extern "C" int per_trace_select(int tag) {
+  return hipMemcpyToSymbol(HIP_SYMBOL(g_trace_tag), &tag, sizeof(tag)) == hipSuccess ? 0 : -1;
+}
 extern "C" int per_trace_read(unsigned long long* host, int clear) {
   if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(g_trace)) != hipSuccess) return -1;
   if (clear) {
@@ -42,4 +48,5 @@ extern "C" int per_trace_read(unsigned long long* host, int clear) {
 #define PER_MARK_HWID(i) do { } while (0)
 #define PER_MARK_DYN(i) do { } while (0)
 #define PER_FLUSH() do { } while (0)
+#define PER_FLUSH_TAG(tag) do { } while (0)
 #endif

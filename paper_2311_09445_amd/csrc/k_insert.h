@@ -59,11 +59,6 @@ struct InsertArgs {                // one kernel argument, so that both parts si
   uint32_t track_min;              // also renew min1 (smallest positive leaf) of the touched height-1 nodes
 };
 
-// position of node among the touched nodes of its height (the two ranges back to back)
-__device__ __forceinline__ uint32_t plan_pos(const Range2& r, uint32_t node) {
-  return node >= r.a0 && node < r.b0 ? node - r.a0 : (r.b0 - r.a0) + (node - r.a1);
-}
-
 template <int LOGK>
 __global__ void __launch_bounds__(1024)
 k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const float* __restrict__ prio,

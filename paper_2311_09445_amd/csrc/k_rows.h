@@ -339,6 +339,15 @@ __device__ __forceinline__ bool move_rows_one_workgroup(const FieldTable& ft, ui
   return bad;
 }
 
+// The rows (and the slot numbers) of an insertion carried by a sampling kernel: the share of mover workgroup
+// `part` of `parts` (whole rows; a workgroup moves its share in as few sweeps as it has lanes for).
+__device__ __forceinline__ void ride_rows(const InsertRide& ride, uint32_t t, uint32_t N, uint32_t part, uint32_t parts) {
+  const uint32_t r0 = (uint32_t)((uint64_t)ride.n * part / parts), r1 = (uint32_t)((uint64_t)ride.n * (part + 1) / parts);
+  (void)move_rows_one_workgroup<false>(ride.rows, t, (uint64_t)t * ride.n + r0, r1 - r0, ride.cursor + r0, N, nullptr, nullptr);
+  if (ride.out_idx)
+    for (uint32_t j = r0 + threadIdx.x; j < r1; j += blockDim.x) ride.out_idx[(size_t)t * ride.n + j] = ride.cursor + j;
+}
+
 // Second kernel of the fused calls.  Its workgroups (blockIdx.x) split into jobs, each with as many
 // workgroups as it needs (JobRanges): first the importance weights of the batch just sampled (if
 // asked for), then the claim phase of a priority update (if one is fused in), then one job per

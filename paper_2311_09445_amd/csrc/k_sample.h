@@ -74,18 +74,42 @@ __device__ __forceinline__ void stage_groups(const float* __restrict__ lvl, uint
 // exactly the indices sampled here, element by element, so every lane claims its own sample when it has
 // it.  claim_mode 2: the update batch lies in other memory; the first claim_blocks workgroups of the
 // grid are claim workgroups.  claim_mode 0: no claim here.
-template <int LOGK>
+//
+// RIDE: the kernel carries the insertion that precedes the sampling call (a few rows at ring slots cursor ..).
+// Every sampling workgroup works the insertion out for itself: beside the top copy it fetches the child groups
+// of all touched nodes of heights 1 .. hp (hp: the height the stale top is rebuilt from) and the new priorities
+// of the leaves among them, sums the groups height by height, patches the sums into the top copy and rebuilds
+// the top from there; on its way down through memory a lane that comes to a touched group reads the patched
+// copy instead.  One more workgroup per tree, the last of the grid, does the same sums and stores them and the
+// new leaves, and moves the rows (nothing here reads rows).  Its stores race with the other workgroups' loads
+// of the same words, harmlessly: every word it writes is one that every reader replaces by the very value being
+// written, so a reader gets the same result from the old word and from the new one.  The running maximum must
+// not move while this kernel reads it as the inserted priority, so whatever would raise it here (claim lanes,
+// given insert priorities) raises max_pend instead, which the tree pass of the call folds in.
+// A single wave's chain of instructions is what a small batch waits for, so the patch is planned on the host
+// down to LDS offsets, and the kernel's share is kept short.
+struct NoRide { uint32_t none; };
+// position of node among the touched nodes of its height (the two ranges back to back)
+__device__ __forceinline__ uint32_t plan_pos(const Range2& r, uint32_t node) {
+  return node >= r.a0 && node < r.b0 ? node - r.a0 : (r.b0 - r.a0) + (node - r.a1);
+}
+template <bool RIDE> using RideParam = typename std::conditional<RIDE, InsertRide, NoRide>::type;
+__device__ __forceinline__ void ride_rows(const InsertRide& ride, uint32_t t, uint32_t N, uint32_t part, uint32_t parts);   // (k_rows.h)
+
+template <int LOGK, bool RIDE>
 __global__ void __launch_bounds__(1024)
 k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float* __restrict__ u,
          uint32_t* __restrict__ out_idx, float* __restrict__ out_prio, float* __restrict__ out_w,
-         uint32_t weight_mode, int stale, uint32_t claim_blocks, ClaimArgs c, int claim_mode, RngArgs rng) {
+         uint32_t weight_mode, int stale, uint32_t claim_blocks, ClaimArgs c, int claim_mode, RngArgs rng,
+         RideParam<RIDE> ride) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   constexpr int ROW = K + 4;                  // staging row, floats
   using Vec = typename std::conditional<LOGK == 1, float2, float4>::type;
   constexpr int VF = sizeof(Vec) / 4;
   touch_kernel_arguments<kernarg_lines<Geom, TopCopy, uint32_t, uint32_t, float, const float*, uint32_t*, float*, float*, uint32_t,
-                                       int, uint32_t, ClaimArgs, int, RngArgs>()>();
+                                       int, uint32_t, ClaimArgs, int, RngArgs,
+                                       typename std::conditional<RIDE, InsertRideHead, NoRide>::type>()>();
   extern __shared__ __attribute__((aligned(16))) float lds[];   // 16-byte LDS accesses need the alignment
   __shared__ uint32_t s_min[16];
   __shared__ float s_total;
@@ -98,8 +122,19 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
     claim_job(g, t, c, blockIdx.x, claim_blocks);
     return;
   }
+  bool is_mover = false;
+  uint32_t movers = 0;
+  if constexpr (RIDE) {   // the last workgroups move the rows; the first of them also stores what the insertion changes in the tree
+    movers = ride.movers;
+    const uint32_t first_mover = gridDim.x - movers;
+    if (blockIdx.x > first_mover) {
+      ride_rows(ride, t, g.N, blockIdx.x - first_mover, movers);
+      return;
+    }
+    is_mover = blockIdx.x == first_mover;
+  }
   const uint32_t bx = blockIdx.x - claim_blocks;            // sampling workgroup number
-  const uint32_t sample_blocks = gridDim.x - claim_blocks;
+  const uint32_t sample_blocks = gridDim.x - claim_blocks - movers;
 
   PER_TRACE_DECL;
   PER_MARK(0);
@@ -130,6 +165,42 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
 #pragma unroll
   for (int i = 0; i < kTopSlots; ++i) off[i + 1] = off[i] + (i < nslots ? tc.cnt[i] : 0u);
   const uint32_t top_floats = off[kTopSlots];
+  // the carried insertion's LDS: behind the top copy and the waves' staging rows
+  float* rl = lds + top_floats + (LOGK >= 3 ? (size_t)(blockDim.x >> 6) * 64 * ROW : (size_t)0);
+  // Everything it reads is fetched in the trip of the top copy: the loads are issued here, into registers, and
+  // parked in LDS once the top copy's own loads are under way (a store to LDS waits for its data).  Lane i takes
+  // element i of each height's run of child groups.  A staged leaf that the insertion rewrites is replaced as it
+  // is parked (by a valid new priority only).  The plan of all heights comes in one batch of scalar loads and
+  // stays in registers: a single wave's chain of instructions and scalar fetches is what a small batch waits for.
+  // (plain words, not structures: the compiler keeps structures that lambdas take by reference in memory)
+  [[maybe_unused]] uint32_t a1 = 0, c1 = 0, o1 = 0, t1 = 0, a2 = 0, c2 = 0, o2 = 0, t2 = 0, a3 = 0, c3 = 0, o3 = 0, t3 = 0,
+                            a4 = 0, c4 = 0, o4 = 0, t4 = 0;   // a: first touched node, c: how many, o: LDS offset, t: top-copy offset
+  [[maybe_unused]] float rv1 = 0, rv2 = 0, rv3 = 0, rv4 = 0;
+  [[maybe_unused]] float nv1 = -1.0f;   // new priority of this lane's leaf (invalid: the leaf stays)
+  static_assert(kRideHeights == 4, "one register per height");
+  if constexpr (RIDE) {
+    // (first nodes and LDS offsets follow from the lowest height's: fewer words to hold)
+    a1 = ride.h[0].a0; c1 = ride.h[0].cnt; t1 = ride.h[0].top_at;
+    c2 = ride.h[1].cnt; t2 = ride.h[1].top_at;
+    c3 = ride.h[2].cnt; t3 = ride.h[2].top_at;
+    c4 = ride.h[3].cnt; t4 = ride.h[3].top_at;
+    a2 = a1 >> LOGK; a3 = a2 >> LOGK; a4 = a3 >> LOGK;
+    o1 = 0; o2 = c1 * K; o3 = o2 + c2 * K; o4 = o3 + c3 * K;
+    if (threadIdx.x < c1 * K) rv1 = g.level[0][(size_t)t * g.stride[0] + (size_t)a1 * K + threadIdx.x];
+    if (threadIdx.x < c2 * K) rv2 = g.level[1][(size_t)t * g.stride[1] + (size_t)a2 * K + threadIdx.x];
+    if (threadIdx.x < c3 * K) rv3 = g.level[2][(size_t)t * g.stride[2] + (size_t)a3 * K + threadIdx.x];
+    if (threadIdx.x < c4 * K) rv4 = g.level[3][(size_t)t * g.stride[3] + (size_t)a4 * K + threadIdx.x];
+    const uint32_t j = a1 * K + threadIdx.x - ride.cursor;   // (slots below the cursor wrap to large numbers)
+    if (threadIdx.x < c1 * K && j < ride.n) nv1 = ride.prio ? ride.prio[(size_t)t * ride.n + j] : g.max_v[t];
+  }
+  auto park_ride = [&]() {
+    if constexpr (RIDE) {
+      if (threadIdx.x < c1 * K) rl[o1 + threadIdx.x] = valid_priority(nv1) ? nv1 : rv1;
+      if (threadIdx.x < c2 * K) rl[o2 + threadIdx.x] = rv2;
+      if (threadIdx.x < c3 * K) rl[o3 + threadIdx.x] = rv3;
+      if (threadIdx.x < c4 * K) rl[o4 + threadIdx.x] = rv4;
+    }
+  };
 
   if (nslots > 0) {
     // one flat loop over the vectors of all copied heights (stale ones are skipped)
@@ -149,8 +220,69 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
       }
       *reinterpret_cast<Vec*>(lds + f) = *reinterpret_cast<const Vec*>(src + (f - base));
     }
+    park_ride();
     __syncthreads();
     PER_MARK(1);
+    if constexpr (RIDE) {
+      PER_MARK(13);
+      // the touched nodes height by height: sums of the staged groups, into the groups of the height above,
+      // into the top copy where the height is part of it, and (last workgroup) aside for the stores
+      const unsigned q = threadIdx.x % LPS;
+      const uint32_t grp = threadIdx.x / LPS, ngrp = blockDim.x / LPS;
+      // (a, c, o, top: the height's touched nodes; up_a, up_o: those of the height above, if it is patched too)
+      auto sum_height = [&](uint32_t a, uint32_t cn, uint32_t o, uint32_t top, bool has_up, uint32_t up_a, uint32_t up_o) {
+        for (uint32_t base = 0; base < cn; base += ngrp) {
+          const uint32_t at = base + grp;
+          const bool ok = at < cn;
+          const float sum = group_sum<LOGK>(rl + o + (size_t)(ok ? at : 0u) * K, q);
+          if (ok && q == 0) {
+            const uint32_t nd = a + at;
+            if (is_mover) rl[ride.val_off + (o >> LOGK) + at] = sum;
+            if (has_up) rl[up_o + (nd - up_a * K)] = sum;
+            if (top != kRideNone) lds[top + nd] = sum;
+          }
+        }
+        __syncthreads();
+      };
+      const uint32_t hp = ride.hp;
+      sum_height(a1, c1, o1, t1, hp > 1, a2, o2);
+      if (hp > 1) sum_height(a2, c2, o2, t2, hp > 2, a3, o3);
+      if (hp > 2) sum_height(a3, c3, o3, t3, hp > 3, a4, o4);
+      if (hp > 3) sum_height(a4, c4, o4, t4, false, 0, 0);
+      if (is_mover) {   // the new leaves, the new sums of heights 1 .. hp, what the running maximum may rise to; the rows
+        uint32_t mx = 0;
+        bool bad = false;
+        float* leaves = g.level[0] + (size_t)t * g.stride[0];
+        for (uint32_t j = threadIdx.x; j < ride.n; j += blockDim.x) {
+          const uint32_t slot = ride.cursor + j;
+          leaves[slot] = rl[o1 + (slot - a1 * K)];   // (the old value again where the new one was invalid)
+          if (ride.prio) {
+            const float v = ride.prio[(size_t)t * ride.n + j];
+            if (!valid_priority(v)) bad = true;
+            else if (v > 0.0f) mx = __float_as_uint(v) > mx ? __float_as_uint(v) : mx;
+          }
+        }
+        auto store_height = [&](uint32_t a, uint32_t cn, uint32_t o, int height) {
+          float* lvl = g.level[height] + (size_t)t * g.stride[height];
+          for (uint32_t at = threadIdx.x; at < cn; at += blockDim.x) lvl[a + at] = rl[ride.val_off + (o >> LOGK) + at];
+        };
+        store_height(a1, c1, o1, 1);
+        if (hp > 1) store_height(a2, c2, o2, 2);
+        if (hp > 2) store_height(a3, c3, o3, 3);
+        if (hp > 3) store_height(a4, c4, o4, 4);
+        if (ride.prio) {
+          mx = wave_max_u32(mx);
+          if (lane == 0 && mx) atomicMax(&g.max_pend[t], mx);
+          if (bad) atomicOr(&g.status[t], 2u);
+        }
+        PER_MARK(14);
+        ride_rows(ride, t, g.N, 0, movers);
+        PER_MARK(12);
+        PER_FLUSH_TAG(1);
+        return;
+      }
+    }
+    PER_MARK(14);
     if (stale >= 0) {   // rebuild slots stale-1 .. 0 and the root, bottom-up
       const unsigned q = threadIdx.x % LPS;
       const uint32_t grp = threadIdx.x / LPS, ngrp = blockDim.x / LPS;
@@ -231,14 +363,24 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
     const float* lvl = lvl_next;
     if (l > 0) lvl_next = g.level[l - 1] + (size_t)t * g.stride[l - 1];
     unsigned child;
+    // (a carried insertion: the group of a touched node is read from the patched copy)
+    const float* patched = nullptr;
+    if constexpr (RIDE) {
+      // touched nodes of height l + 1 (l + 1 <= hp: the copy reaches down to hp)
+      const uint32_t pa = l == 0 ? a1 : l == 1 ? a2 : l == 2 ? a3 : a4;
+      const uint32_t pc = l == 0 ? c1 : l == 1 ? c2 : l == 2 ? c3 : c4;
+      const uint32_t po = l == 0 ? o1 : l == 1 ? o2 : l == 2 ? o3 : o4;
+      if (node - pa < pc) patched = rl + po + (size_t)(node - pa) * K;
+    }
     if constexpr (LOGK <= 2) {
-      descend_lane<LOGK>(lvl + (size_t)node * K, r, child, val);
+      if (RIDE && patched) descend_lane<LOGK>(patched, r, child, val);
+      else descend_lane<LOGK>(lvl + (size_t)node * K, r, child, val);
     } else {
       stage_groups<LOGK, 0>(lvl, node, lane, stage);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      descend_lane<LOGK>(stage + lane * ROW, r, child, val);
+      descend_lane<LOGK>(RIDE && patched ? patched : stage + lane * ROW, r, child, val);
       __builtin_amdgcn_wave_barrier();
     }
     node = node * K + child;
@@ -253,7 +395,7 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   // earlier store of the wave.
   store_rebuilt_top();
   PER_MARK(12);
-  PER_FLUSH();
+  PER_FLUSH_TAG(1);
   if (out_w) {
     // Importance weights need the batch minimum of the sampled values.
     const uint32_t m = wave_min_u32(active ? __float_as_uint(val) : 0x7F800000u);
@@ -275,7 +417,12 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   if (claim_mode == 1) {   // element s of the update batch is this lane's own sample
     uint32_t mx = 0, flags = 0;
     if (active) claim_element(g, t, size, c.group_mode, claim_first, s, node, upd_v, mx, flags);
-    raise_max(g, t, mx, max_seen);
+    if constexpr (RIDE) {
+      mx = wave_max_u32(mx);
+      if (lane == 0 && mx > max_seen) atomicMax(&g.max_pend[t], mx);
+    } else {
+      raise_max(g, t, mx, max_seen);
+    }
     if (flags) atomicOr(&g.status[t], flags);
     leave_claim_base(g, t, c.group_mode, bx == 0 && threadIdx.x == 0, claim_first);
   }
@@ -336,37 +483,35 @@ template <int LOGK>
 static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const ClaimArgs& c, const FieldTable* rows,
                                        const FinishArgs& a, hipStream_t s);
 
-// Sampling call with whatever is fused into it.  rows: gather of the sampled rows.  claim: a priority
-// update whose claim phase runs where claim_mode says (CLAIM_INLINE / CLAIM_BLOCKS: in the sampling
-// kernel, the tree pass then shares the second kernel with the weights and row jobs; CLAIM_FINISH: in
-// the second kernel, the tree pass is a third).
-template <int LOGK>
-static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
-                                  const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w,
-                                  float* out_prio, uint32_t weight_mode, uint32_t stale_hb, const FieldTable* rows,
-                                  const ClaimArgs* claim, int claim_mode, hipStream_t s) {
-  constexpr int K = Fan<LOGK>::K;
+// Workgroup size and top copy of a sampling launch for batch B (stale_hb: the height the stale top is rebuilt
+// from, or 0).  The copy: at most kTopSlots of the topmost heights (below the root), within the LDS budget, and
+// only while a height is small next to what the workgroup's samples would fetch from it one by one.
+struct SampleShape {
+  TopCopy tc;
+  uint32_t waves, wave_bytes, top_bytes;
+};
+static SampleShape sample_shape(const Geom& g, const Tuning& tn, uint32_t B, uint32_t stale_hb) {
   constexpr uint32_t kLdsCap = 128 * 1024;
-  const uint32_t wave_bytes = LOGK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
+  SampleShape sh{};
+  const uint32_t K = g.K;
+  sh.wave_bytes = g.logK >= 3 ? 64u * (K + 4) * 4u : 0u;   // staging per wave
   // workgroup size: the whole batch in one workgroup when it is small (the weights are then finished
   // in-kernel), else the configured size; bounded by the LDS the staging rows need
-  uint32_t max_waves = wave_bytes ? (uint32_t)(kLdsCap / 2 / wave_bytes) : 16u;
+  uint32_t max_waves = sh.wave_bytes ? (uint32_t)(kLdsCap / 2 / sh.wave_bytes) : 16u;
   if (max_waves > 16) max_waves = 16;
   if (max_waves < 1) max_waves = 1;
   uint32_t waves = tn.sample_block / 64;
   const uint32_t need = (B + 63) / 64;
   if (need <= max_waves) waves = need;
   if (waves > max_waves) waves = max_waves;
+  sh.waves = waves;
   const uint32_t block = waves * 64;
-  const uint32_t gx = (B + block - 1) / block;
-  // topmost heights (below the root) copied to LDS: at most kTopSlots, within the LDS budget, and only
-  // while a height is small next to what the workgroup's samples would fetch from it one by one
-  TopCopy tc{};
+  TopCopy& tc = sh.tc;
   uint64_t top = 0;
   for (int l = (int)g.H - 1; l >= 0 && tc.nslots < (uint32_t)kTopSlots; --l) {
     const uint64_t cnt = (uint64_t)g.n[l + 1] * K;
     const uint64_t add = cnt * 4;
-    if (top + add > tn.lds_budget_bytes || top + add + (uint64_t)waves * wave_bytes > kLdsCap) break;
+    if (top + add > tn.lds_budget_bytes || top + add + (uint64_t)waves * sh.wave_bytes > kLdsCap) break;
     const bool needed_for_rebuild = stale_hb && (uint32_t)l >= stale_hb;   // the rebuild of stale heights reads it
     if (cnt > 8ull * block && tn.lds_budget_bytes <= 64 * 1024 && !needed_for_rebuild) break;
     top += add;
@@ -378,8 +523,78 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
   }
   tc.root = g.root;
   tc.root_stride = g.root_stride;
-  size_t bytes = (size_t)top + (size_t)waves * wave_bytes;
-  if (bytes < tn.sample_min_lds) bytes = tn.sample_min_lds;   // asking for more LDS than needed spreads workgroups over more CUs
+  sh.top_bytes = (uint32_t)top;
+  return sh;
+}
+
+// A carried insertion: the touched nodes of heights 1 .. hp (two ranges per height, narrowed by K from one height
+// to the next) and where their child groups, their new sums and the new leaves sit in LDS.
+constexpr uint32_t kRideRows = 1024;          // most rows a sampling kernel carries
+constexpr uint32_t kRideLdsBytes = 16 * 1024; // most LDS its patch may take
+// False when the insertion runs past the ring's end or a run of child groups is longer than the workgroup (`block`
+// lanes): the insertion then goes by itself.
+static bool plan_ride(const Geom& g, const TopCopy& tc, uint32_t block, uint32_t hp, InsertRide* rd) {
+  const uint32_t L = g.logK;
+  if ((uint64_t)rd->cursor + rd->n > g.N || hp > (uint32_t)kRideHeights) return false;
+  uint32_t a = rd->cursor, b = rd->cursor + rd->n;   // touched nodes [a, b)
+  uint32_t floats = 0, vals = 0;
+  for (int i = 0; i < kRideHeights; ++i) rd->h[i] = RideHeight{0, 0, 0, kRideNone};
+  for (uint32_t h = 1; h <= hp; ++h) {
+    a >>= L;
+    b = ((b - 1) >> L) + 1;
+    RideHeight& P = rd->h[h - 1];
+    P.a0 = a;
+    P.cnt = b - a;
+    P.off = floats;
+    if ((uint64_t)P.cnt * g.K > block) return false;
+    uint32_t top = 0;   // where the sampling kernel's top copy holds this height
+    for (uint32_t i = 0; i < tc.nslots; ++i) {
+      if (g.H - 1 - i == h) P.top_at = top;
+      top += tc.cnt[i];
+    }
+    floats += P.cnt * g.K;
+    vals += P.cnt;
+  }
+  rd->hp = hp;
+  rd->val_off = floats;
+  rd->floats = floats + vals;
+  return true;
+}
+
+bool sample_can_carry_insert(const Geom& g, const Tuning& tn, uint32_t B, const FieldTable* ft, uint32_t n, uint32_t cursor) {
+  const uint32_t hb = lazy_top_height(g, tn);
+  if (!hb || hb > (uint32_t)kRideHeights || n == 0 || n > kRideRows || n > g.N) return false;
+  uint64_t bytes = 0;
+  if (ft)
+    for (uint32_t f = 0; f < ft->n_fields; ++f)
+      if (ft->io[f]) bytes += (uint64_t)n * ft->bytes[f];
+  if (bytes > 256 * 1024) return false;
+  // the top copy must reach down to the height the top is rebuilt from
+  const SampleShape sh = sample_shape(g, tn, B, hb);
+  if (sh.tc.nslots == 0 || g.H - sh.tc.nslots > hb) return false;
+  // the runs of the patch must fit the workgroup, and the patch its share of the LDS
+  InsertRide rd{};
+  rd.n = n;
+  rd.cursor = cursor;
+  return plan_ride(g, sh.tc, sh.waves * 64, hb, &rd) && (uint64_t)rd.floats * 4 <= kRideLdsBytes;
+}
+
+// Sampling call with whatever is fused into it.  rows: gather of the sampled rows.  claim: a priority
+// update whose claim phase runs where claim_mode says (CLAIM_INLINE / CLAIM_BLOCKS: in the sampling
+// kernel, the tree pass then shares the second kernel with the weights and row jobs; CLAIM_FINISH: in
+// the second kernel, the tree pass is a third).  ride: an insertion carried by the sampling kernel (the caller
+// has checked sample_can_carry_insert and passes the lazily rebuilt height as stale_hb).
+template <int LOGK>
+static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta,
+                                  const float* u, const RngArgs& rng, uint32_t* out_idx, float* out_w,
+                                  float* out_prio, uint32_t weight_mode, uint32_t stale_hb, const FieldTable* rows,
+                                  const ClaimArgs* claim, int claim_mode, const InsertRide* ride, hipStream_t s) {
+  const SampleShape sh = sample_shape(g, tn, B, stale_hb);
+  const TopCopy& tc = sh.tc;
+  const uint32_t waves = sh.waves;
+  const uint32_t block = waves * 64;
+  const uint32_t gx = (B + block - 1) / block;
+  size_t bytes = (size_t)sh.top_bytes + (size_t)waves * sh.wave_bytes;
   hipError_t e;
   int stale = -1;
   if (stale_hb) {
@@ -388,22 +603,47 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
     if (tc.nslots > 0 && lowest_copied <= (int)stale_hb) {
       stale = (int)g.H - 1 - (int)stale_hb;
     } else {
+      if (ride) return hipErrorInvalidValue;
       e = launch_resum_top_k<LOGK>(g, tn, stale_hb, s);
       if (e != hipSuccess) return e;
     }
   }
-  e = grant_lds<&k_sample<LOGK>>(tn, bytes);
-  if (e != hipSuccess) return e;
   if (!claim) claim_mode = CLAIM_NONE;
+  InsertRide rd{};
+  if (ride) {
+    if (stale < 0 || stale_hb != lazy_top_height(g, tn) || claim_mode == CLAIM_BLOCKS) return hipErrorInvalidValue;
+    rd = *ride;
+    if (!plan_ride(g, tc, block, stale_hb, &rd)) return hipErrorInvalidValue;
+    // movers: as many as it takes to move every row element in one sweep (whole rows each; at most 32)
+    uint64_t row_elements = 0;
+    for (uint32_t f = 0; f < rd.rows.n_fields; ++f)
+      if (rd.rows.io[f]) row_elements += (uint64_t)rd.n * (rd.rows.bytes[f] / rd.rows.vec[f]);
+    rd.movers = (uint32_t)((row_elements + block - 1) / block);
+    if (rd.movers > rd.n) rd.movers = rd.n;
+    if (rd.movers > 32) rd.movers = 32;
+    if (rd.movers < 1) rd.movers = 1;
+    bytes += (size_t)rd.floats * 4;
+  }
+  if (bytes < tn.sample_min_lds) bytes = tn.sample_min_lds;   // asking for more LDS than needed spreads workgroups over more CUs
   const bool claim_here = claim_mode == CLAIM_INLINE || claim_mode == CLAIM_BLOCKS;
   uint32_t claim_blocks = 0;
   if (claim_mode == CLAIM_BLOCKS) {
     claim_blocks = (claim->B + block - 1) / block;
     if (claim_blocks > 4096) claim_blocks = 4096;   // the claim job strides
   }
-  PER_LAUNCH(KID_SAMPLE, k_sample<LOGK>, dim3(gx + claim_blocks, g.T), dim3(block), bytes, s, g, tc, B, size, beta, u,
-             out_idx, out_prio, out_w, weight_mode, stale, claim_blocks, claim_here ? *claim : ClaimArgs{},
-             claim_here ? claim_mode : (int)CLAIM_NONE, rng);
+  if (ride) {
+    e = grant_lds<&k_sample<LOGK, true>>(tn, bytes);
+    if (e != hipSuccess) return e;
+    PER_LAUNCH(KID_SAMPLE, (k_sample<LOGK, true>), dim3(gx + claim_blocks + rd.movers, g.T), dim3(block), bytes, s, g, tc, B,
+               size, beta, u, out_idx, out_prio, out_w, weight_mode, stale, claim_blocks, claim_here ? *claim : ClaimArgs{},
+               claim_here ? claim_mode : (int)CLAIM_NONE, rng, rd);
+  } else {
+    e = grant_lds<&k_sample<LOGK, false>>(tn, bytes);
+    if (e != hipSuccess) return e;
+    PER_LAUNCH(KID_SAMPLE, (k_sample<LOGK, false>), dim3(gx + claim_blocks, g.T), dim3(block), bytes, s, g, tc, B, size,
+               beta, u, out_idx, out_prio, out_w, weight_mode, stale, claim_blocks, claim_here ? *claim : ClaimArgs{},
+               claim_here ? claim_mode : (int)CLAIM_NONE, rng, NoRide{});
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const bool finish_weights = out_w && gx > 1;
@@ -415,16 +655,21 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
     a.size = size;
     a.beta = beta;
     a.weight_mode = weight_mode;
+    ClaimArgs c2{};
+    if (claim) {
+      c2 = *claim;
+      c2.fold_max = ride ? 1u : 0u;   // the tree pass folds what this kernel has left in max_pend
+    }
     if (claim_here) {   // second kernel: tree pass beside the weights and the rows
-      if (rows || finish_weights) return launch_tree_finish_k<LOGK>(g, tn, *claim, rows, a, s);
-      return launch_tree_k<LOGK>(g, tn, *claim, s);
+      if (rows || finish_weights) return launch_tree_finish_k<LOGK>(g, tn, c2, rows, a, s);
+      return launch_tree_k<LOGK>(g, tn, c2, s);
     }
     // second kernel: rows, weights and the claim phase; the tree pass follows
     a.has_claim = claim ? 1u : 0u;
-    if (claim) a.claim = *claim;
+    if (claim) a.claim = c2;
     e = launch_finish(g, tn, rows, a, s);
     if (e != hipSuccess || !claim) return e;
-    return launch_tree_k<LOGK>(g, tn, *claim, s);
+    return launch_tree_k<LOGK>(g, tn, c2, s);
   }
   if (!finish_weights) return e;
   PER_LAUNCH(KID_WEIGHTS, k_weights, dim3((B + 255) / 256, g.T), dim3(256), 0, s, g, B, size, beta, out_w, weight_mode);
@@ -445,8 +690,8 @@ static hipError_t launch_sample_k(const Geom& g, const Tuning& tn, uint32_t B, u
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          const RngArgs& rng, uint32_t* out_idx, float* out_w, float* out_prio, uint32_t weight_mode,
                          uint32_t stale_hb, const FieldTable* rows, const ClaimArgs* claim, int claim_mode,
-                         hipStream_t s) {
-#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, rng, out_idx, out_w, out_prio, weight_mode, stale_hb, rows, claim, claim_mode, s)
+                         hipStream_t s, const InsertRide* ride) {
+#define CALL(L) launch_sample_k<L>(g, tn, B, size, beta, u, rng, out_idx, out_w, out_prio, weight_mode, stale_hb, rows, claim, claim_mode, ride, s)
   PER_DISPATCH_LOGK(g.logK, CALL)
 #undef CALL
 }

@@ -28,6 +28,7 @@ __global__ void k_init_scalars(Geom g, float init_max) {
   if (t >= g.T) return;
   g.max_v[t] = init_max;
   g.status[t] = 0;
+  g.max_pend[t] = 0;
   for (uint32_t k = 0; k < 2 * kVminSlots; ++k) g.vmin[((size_t)(k / kVminSlots) * g.T + t) * kVminSlots + k % kVminSlots] = kNoMin;
   g.vnext[t] = 0;
   g.vcur[t] = 0;

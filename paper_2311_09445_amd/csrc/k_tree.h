@@ -342,6 +342,16 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
   }
 }
 
+// What a sampling kernel that carried an insertion has left in max_pend (read by the caller when its workgroup
+// started) goes into the running maximum; one workgroup per tree does this, after its share of the tree pass.
+__device__ __forceinline__ void fold_pending_max(const Geom& g, uint32_t t, uint32_t pend_word) {
+  const uint32_t pend = not_before_here(pend_word);
+  if (threadIdx.x == 0 && pend) {
+    atomicMax(reinterpret_cast<uint32_t*>(&g.max_v[t]), pend);
+    g.max_pend[t] = 0u;
+  }
+}
+
 // Workgroups of at most 512 lanes: two 1024-lane workgroups share a compute unit only while a wave
 // stays within an eighth of the SIMD's scalar and vector registers (with one scalar register more the
 // second workgroup waits for the first to end and the kernel takes half as long again), and holding
@@ -349,7 +359,9 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
 template <int LOGK, bool TRACK_MIN>
 __global__ void __launch_bounds__(512)
 k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
-  tree_job<LOGK, TRACK_MIN>(g, sl, blockIdx.y, blockIdx.x, chain);
+  const uint32_t pend = (chain & 2u) && blockIdx.x == 0 ? read_word_with_the_loads(&g.max_pend[blockIdx.y]) : 0u;
+  tree_job<LOGK, TRACK_MIN>(g, sl, blockIdx.y, blockIdx.x, chain & 1u);
+  if ((chain & 2u) && blockIdx.x == 0) fold_pending_max(g, blockIdx.y, pend);
 }
 
 // Second kernel of a fused step whose claim phase rode in the sampling kernel: the tree pass
@@ -367,7 +379,9 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_num_sgpr(96)))
 k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldTable ft, JobRanges jr, FinishArgs a) {
   const uint32_t t = blockIdx.y;
   if (blockIdx.x < tree_blocks) {
-    tree_job<LOGK, TRACK_MIN>(g, sl, t, blockIdx.x, chain);
+    const uint32_t pend = (chain & 2u) && blockIdx.x == 0 ? read_word_with_the_loads(&g.max_pend[t]) : 0u;
+    tree_job<LOGK, TRACK_MIN>(g, sl, t, blockIdx.x, chain & 1u);
+    if ((chain & 2u) && blockIdx.x == 0) fold_pending_max(g, t, pend);
     return;
   }
   const uint32_t b = blockIdx.x - tree_blocks;
@@ -464,7 +478,7 @@ static hipError_t launch_tree_k(const Geom& g, const Tuning& tn, const ClaimArgs
   hipError_t e = tree_pass_shape<LOGK>(g, tn, c, &sl, &tblock);
   if (e != hipSuccess) return e;
   if (tblock > 512) tblock = 512;
-  const uint32_t chain = lazy_top_height(g, tn) ? 0u : 1u;
+  const uint32_t chain = (lazy_top_height(g, tn) ? 0u : 1u) | (c.fold_max ? 2u : 0u);
   if (c.track_min) {
     PER_LAUNCH(KID_UPDATE_TREE, (k_update_tree<LOGK, true>), dim3(g.n[sl.hb], g.T), dim3(tblock), tree_lds_bytes<LOGK>(sl),
                s, g, sl, chain);
@@ -488,7 +502,7 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const Cl
   if (rows) ft = *rows;
   const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u, g.T);
   const uint32_t tree_blocks = g.n[sl.hb];
-  const uint32_t chain = lazy_top_height(g, tn) ? 0u : 1u;
+  const uint32_t chain = (lazy_top_height(g, tn) ? 0u : 1u) | (c.fold_max ? 2u : 0u);
   const dim3 grid(tree_blocks + jr.first[2 + kMaxFields], g.T);
   const bool wide = any_field_moves_wide(rows ? &ft : nullptr);
 #define PER_TREE_FINISH(TM, WD)                                                                                        \

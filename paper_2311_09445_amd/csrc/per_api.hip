@@ -88,8 +88,8 @@ void make_layout(const per_config* c, Layout* L) {
   } while (n > 1);
   L->H = h;
   size_t off = 0;
-  L->scalars_off = off;                         // max_v, status, vnext, vcur, sbase, sfloor [T] each; vmin[2][T][kVminSlots], vmin_buf[T][kMinParts]
-  off = round_up(off + (size_t)(6 + 2 * kVminSlots + kMinParts) * T * 4, kAlign);
+  L->scalars_off = off;                         // max_v, status, vnext, vcur, sbase, sfloor, max_pend [T] each; vmin[2][T][kVminSlots], vmin_buf[T][kMinParts]
+  off = round_up(off + (size_t)(7 + 2 * kVminSlots + kMinParts) * T * 4, kAlign);
   L->step_off = off;                            // the one-kernel step's words: cnt[T][kStepGroups] (64-bit), done[T][2][kStepDoneSlots], vmin[T][2][kVminSlots]
   off = round_up(off + (size_t)(2 * kStepGroups + 2 * kStepDoneSlots + 2 * kVminSlots) * T * 4, kAlign);
   for (uint32_t l = 0; l <= L->H; ++l) {
@@ -275,7 +275,8 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.vcur = g.vnext + g.T;
   g.sbase = g.vcur + g.T;
   g.sfloor = g.sbase + g.T;
-  g.vmin = g.sfloor + g.T;
+  g.max_pend = g.sfloor + g.T;
+  g.vmin = g.max_pend + g.T;
   g.step_cnt = reinterpret_cast<unsigned long long*>(p->arena + L.step_off);
   g.step_done = reinterpret_cast<uint32_t*>(g.step_cnt + (size_t)kStepGroups * g.T);
   g.step_vmin = g.step_done + (size_t)2 * kStepDoneSlots * g.T;
@@ -301,6 +302,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.insert_small = 1;
   p->tn.group_claim = 1;
   p->tn.step_kernel = 1;
+  p->tn.insert_ride = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->claims_left = false;
@@ -420,7 +422,10 @@ static bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
 
 static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight,
                        float* d_out_prio, void* const* d_field_dst, uint32_t upd_B, const uint32_t* d_upd_idx,
-                       const float* d_upd_prio, void* stream, const uint32_t* d_upd_pos = nullptr) {
+                       const float* d_upd_prio, void* stream, const uint32_t* d_upd_pos = nullptr,
+                       const InsertRide* ride = nullptr) {
+  // ride: an insertion that the sampling kernel of this call carries.  The caller (per_insert_step) has checked
+  // the arguments and that the kernel can carry it, and has advanced the ring mirrors: p->size counts its rows.
   if (!p) return PER_EINVAL;
   if (B == 0) return PER_OK;
   if ((!d_u && !p->rng_on) || !d_out_idx || misaligned(d_u, 4) || misaligned(d_out_idx, 4) ||
@@ -436,7 +441,7 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
   // An update of exactly the batch drawn here (element for element, or through a position map), its values apart
   // from the outputs: sampling and update run as one kernel where that kernel fits the tree and the batch.
   uint32_t step_block = 0;
-  if (upd_B == B && d_upd_idx == d_out_idx && p->tn.step_kernel && p->tn.lazy_top) {
+  if (upd_B == B && d_upd_idx == d_out_idx && p->tn.step_kernel && p->tn.lazy_top && !ride) {
     const size_t n_out = (size_t)p->g.T * B * 4;
     if (!ranges_overlap(d_upd_prio, n_out, d_out_idx, n_out) && !ranges_overlap(d_upd_prio, n_out, d_out_weight, n_out) &&
         !ranges_overlap(d_upd_prio, n_out, d_out_prio, n_out) && !ranges_overlap(d_upd_pos, n_out, d_out_idx, n_out) &&
@@ -516,11 +521,13 @@ static int sample_impl(per_t* p, uint32_t B, float beta, const float* d_u, uint3
     rng.call_hi = (uint32_t)(p->rng_calls >> 32);
     ++p->rng_calls;
   }
-  const uint32_t stale = p->stale_hb;
+  // (a carried insertion changes the heights up to the lazily rebuilt one: the top is rebuilt from there whether
+  // it was stale or not)
+  const uint32_t stale = ride ? lazy_top_height(p->g, p->tn) : p->stale_hb;
   p->stale_hb = 0;   // the sampling kernel rebuilds and stores the stale heights
   hipError_t e = launch_sample(p->g, p->tn, B, (uint32_t)p->size, beta, d_u, rng, d_out_idx, d_out_weight, d_out_prio,
                                weight_mode, stale, fused ? &ft : nullptr, upd_B ? &claim : nullptr,
-                               claim_mode, s);
+                               claim_mode, s, ride);
   if (e == hipSuccess && upd_B) p->stale_hb = lazy_top_height(p->g, p->tn);   // the tree pass ran
   if (e != hipSuccess && upd_B) p->claims_left = true;   // (the claim phase may have run without its tree pass)
   return hip_rc(e);
@@ -560,6 +567,68 @@ int per_step(per_t* p, uint32_t B, float beta, const float* d_u, uint32_t* d_out
     if (ranges_overlap(d_upd_prio, n, o, n) || ranges_overlap(d_upd_pos, n, o, n)) return PER_EINVAL;
   return sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, B, d_out_idx, d_upd_prio, stream,
                      d_upd_pos);
+}
+
+int per_insert_step(per_t* p, uint32_t n, const void* const* d_field_src, const float* d_ins_prio, uint32_t* d_ins_out_idx,
+                    uint32_t B, float beta, const float* d_u, uint32_t* d_out_idx, float* d_out_weight, float* d_out_prio,
+                    void* const* d_field_dst, const float* d_upd_prio, const uint32_t* d_upd_pos, void* stream) {
+  if (!p) return PER_EINVAL;
+  if (n == 0 || B == 0) {
+    int rc = n ? per_insert(p, n, d_field_src, d_ins_prio, d_ins_out_idx, stream) : PER_OK;
+    if (rc != PER_OK) return rc;
+    return per_step(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, d_upd_prio, d_upd_pos, stream);
+  }
+  // The step's arguments are checked before anything of the insertion is enqueued.
+  if (n > p->cfg.capacity || (uint64_t)B * 16 > 0x7FFFFFFFull) return PER_ERANGE;
+  if ((!d_u && !p->rng_on) || !d_out_idx || !d_upd_prio || !isfinite(beta) || beta < 0.0f) return PER_EINVAL;
+  for (const void* a : {static_cast<const void*>(d_ins_prio), static_cast<const void*>(d_ins_out_idx),
+                        static_cast<const void*>(d_u), static_cast<const void*>(d_out_idx),
+                        static_cast<const void*>(d_out_weight), static_cast<const void*>(d_out_prio),
+                        static_cast<const void*>(d_upd_prio), static_cast<const void*>(d_upd_pos)})
+    if (misaligned(a, 4)) return PER_EINVAL;
+  const size_t n_ins = (size_t)p->g.T * n * 4, n_out = (size_t)p->g.T * B * 4;
+  const void* outs[3] = {d_out_idx, d_out_weight, d_out_prio};
+  for (const void* o : outs)
+    if (ranges_overlap(d_upd_prio, n_out, o, n_out) || ranges_overlap(d_upd_pos, n_out, o, n_out)) return PER_EINVAL;
+
+  // The sampling kernel of the step carries the insertion where it can.  What the insertion reads and writes then
+  // must lie apart from what the sampling kernel writes and reads, since the two run side by side.
+  InsertRide ride{};
+  const bool has_rows = fill_fields(p, const_cast<void* const*>(reinterpret_cast<const void* const*>(d_field_src)), &ride.rows);
+  if (!has_rows) ride.rows = FieldTable{};
+  bool carried = p->tn.insert_ride && p->weight_norm == PER_NORM_BATCH &&
+                 sample_can_carry_insert(p->g, p->tn, B, has_rows ? &ride.rows : nullptr, n, (uint32_t)p->cursor);
+  for (const void* o : outs) {
+    carried = carried && !ranges_overlap(d_ins_prio, n_ins, o, n_out);
+    if (has_rows)
+      for (uint32_t f = 0; f < p->cfg.n_fields; ++f)
+        carried = carried && !ranges_overlap(d_field_src[f], (size_t)p->g.T * n * p->cfg.field_bytes[f], o, n_out);
+  }
+  for (const void* a : {static_cast<const void*>(d_u), static_cast<const void*>(d_out_idx),
+                        static_cast<const void*>(d_out_weight), static_cast<const void*>(d_out_prio),
+                        static_cast<const void*>(d_upd_prio), static_cast<const void*>(d_upd_pos)})
+    carried = carried && !ranges_overlap(d_ins_out_idx, n_ins, a, n_out);
+  if (!carried) {
+    int rc = per_insert(p, n, d_field_src, d_ins_prio, d_ins_out_idx, stream);
+    if (rc != PER_OK) return rc;
+    return per_step(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, d_upd_prio, d_upd_pos, stream);
+  }
+  ride.n = n;
+  ride.cursor = (uint32_t)p->cursor;
+  ride.prio = d_ins_prio;
+  ride.out_idx = d_ins_out_idx;
+  const uint64_t N = p->cfg.capacity;
+  const uint64_t cursor0 = p->cursor, size0 = p->size;
+  p->cursor = (p->cursor + n) % N;                // (the step sees the ring as the insertion leaves it)
+  p->size = p->size + n > N ? N : p->size + n;
+  p->min_stale = true;                            // (the carried insertion does not renew the companion minimum)
+  const int rc = sample_impl(p, B, beta, d_u, d_out_idx, d_out_weight, d_out_prio, d_field_dst, B, d_out_idx, d_upd_prio, stream,
+                             d_upd_pos, &ride);
+  if (rc != PER_OK && rc != PER_EHIP) {           // refused before anything was enqueued
+    p->cursor = cursor0;
+    p->size = size0;
+  }
+  return rc;
 }
 
 int per_gather(per_t* p, uint32_t B, const uint32_t* d_idx, void* const* d_field_dst, void* stream) {
@@ -878,6 +947,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "group_claim")) {
     if (value != 0 && value != 1) return PER_EINVAL;
     p->tn.group_claim = (uint32_t)value;
+    return PER_OK;
+  }
+  if (!strcmp(name, "insert_ride")) {
+    if (value != 0 && value != 1) return PER_EINVAL;
+    p->tn.insert_ride = (uint32_t)value;
     return PER_OK;
   }
   if (!strcmp(name, "step_kernel")) {

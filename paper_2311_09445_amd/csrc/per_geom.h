@@ -42,6 +42,8 @@ struct Geom {
   uint32_t arrive_stride;
   uint32_t arrive_off[kMaxHeight + 1];   // offset of height h (>= 2) inside a tree's counters
   float*    max_v;                  // [T] running max priority
+  uint32_t* max_pend;               // [T] fp32 bits raised by a sampling kernel that carries an insertion (which reads max_v while
+                                    // its claim lanes would raise it); folded into max_v by the tree pass of the same call; else 0
   uint32_t* status;                 // [T] sticky flags
   uint32_t* vmin;                   // [2][T][kVminSlots] partial batch minima of sampled values (fp32 bits), two buffers
   uint32_t* vnext;                  // [T] which buffer the next sampling kernel fills (written by the weights job)
@@ -98,6 +100,7 @@ struct ClaimArgs {
   uint32_t B, size;
   uint32_t group_mode;     // the batch claims through the group entries (else leaf by leaf)
   uint32_t track_min;      // the tree pass also renews min1 of the height-1 nodes it rebuilds
+  uint32_t fold_max;       // the tree pass also folds max_pend into the running maximum
   const uint32_t* idx;     // [T][B]
   const uint32_t* pos;     // null, or [T][B] positions: element j targets idx[pos[j]] (the leaf drawn by sample pos[j] of the
                            // sampling call the update is fused with); a position >= B makes the element invalid
@@ -169,6 +172,31 @@ struct JobRanges {
 
 struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b0) u [a1,b1)
 
+// An insertion of a few rows carried by the sampling kernel of the call that follows it (see k_sample).  The
+// caller fills the first part; launch_sample plans the rest.  Only for insertions that do not run past the ring's
+// end: the touched nodes of a height are then one range, and their child groups one run of consecutive floats.
+constexpr int kRideHeights = 4;   // (no fanout whose sampling kernel reaches the lazily rebuilt height has it higher)
+constexpr uint32_t kRideNone = 0xFFFFFFFFu;
+struct RideHeight {                // the touched nodes of one height: [a0, a0 + cnt)
+  uint32_t a0, cnt;
+  uint32_t off;                    // where their child groups start in the patch (floats); their new sums: val_off + off / K
+  uint32_t top_at;                 // where this height starts in the sampling kernel's top copy (floats), or kRideNone
+};
+struct InsertRideHead {            // what the sampling workgroups read (the kernel fetches these argument lines first)
+  uint32_t n, cursor;              // rows per tree, first ring slot
+  const float* prio;               // [T][n] or null: the running maximum
+  uint32_t* out_idx;               // [T][n] or null
+  // planned by the launcher
+  uint32_t hp;                     // heights 1 .. hp are patched (hp = the height the stale top is rebuilt from)
+  uint32_t floats;                 // LDS floats of the patch: child groups, then new sums
+  uint32_t val_off;                // where the new sums start
+  uint32_t movers;                 // workgroups at the end of the grid that move the rows; the first also stores the patch
+  RideHeight h[kRideHeights];      // h[i]: height i + 1 (unused: cnt 0)
+};
+struct InsertRide : InsertRideHead {
+  FieldTable rows;                 // io all null: no rows to move (read by the one workgroup that moves them)
+};
+
 // Optional per-kernel timing with HIP events attached to each launch (off by default).
 enum KernelId {
   KID_FILL, KID_SAMPLE, KID_WEIGHTS, KID_GATHER, KID_FINISH, KID_SCATTER, KID_INSERT_LEAVES, KID_RESUM_DENSE,
@@ -196,6 +224,7 @@ struct Tuning {
   uint32_t insert_small;      // small inserts run as one kernel (one workgroup per tree)
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   uint32_t group_claim;       // update batches claim through the group entries whenever they are short enough
+  uint32_t insert_ride;       // per_insert_step lets its sampling kernel carry the insertion where that is possible
   uint32_t step_kernel;       // per_step runs sampling and update as one kernel: 0 never, 1 where it fits and pays off, 2 wherever it fits
   Profiler* prof;
   int device;                 // the device the buffer lives on
@@ -210,7 +239,11 @@ hipError_t static_scratch_address(int device, uint32_t** out);   // the static a
 hipError_t launch_sample(const Geom& g, const Tuning& tn, uint32_t B, uint32_t size, float beta, const float* u,
                          const RngArgs& rng,
                          uint32_t* out_idx, float* out_w, float* out_prio, uint32_t weight_mode, uint32_t stale_hb,
-                         const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s);
+                         const FieldTable* rows, const ClaimArgs* claim, int claim_mode, hipStream_t s,
+                         const InsertRide* ride = nullptr);
+// True when the sampling kernel of a call with batch B can carry an insertion of n rows at ring slot cursor (ft: their
+// fields, or null).
+bool sample_can_carry_insert(const Geom& g, const Tuning& tn, uint32_t B, const FieldTable* ft, uint32_t n, uint32_t cursor);
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s);
 hipError_t launch_scatter(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t n, uint32_t cursor,

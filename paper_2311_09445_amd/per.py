@@ -20,7 +20,7 @@ FLAG_BAD_INDEX, FLAG_BAD_PRIORITY, FLAG_ZERO_TOTAL = 1, 2, 4
 
 EXPORTS = [
     "per_arena_bytes", "per_create", "per_destroy", "per_insert", "per_insert_protected", "per_sample", "per_sample_gather",
-    "per_sample_gather_update", "per_step", "per_gather",
+    "per_sample_gather_update", "per_step", "per_insert_step", "per_gather",
     "per_update", "per_update_td", "per_update_delta", "per_rebuild", "per_set_rng", "per_rng_calls", "per_run_steps",
     "per_run_steps_fits", "per_run_requests", "per_set_weight_norm", "per_min_priority", "per_min_priority_static", "per_note_replay", "per_get_priority", "per_read_level", "per_total", "per_max_priority",
     "per_status", "per_clear_status", "per_height", "per_size", "per_cursor", "per_set_ring", "per_set_tuning",
@@ -105,6 +105,7 @@ def _lib():
         "per_sample_gather": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, vp]),
         "per_sample_gather_update": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, u32, vp, vp, vp]),
         "per_step": (C.c_int, [vp, u32, f32, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "per_insert_step": (C.c_int, [vp, u32, vp, vp, vp, u32, f32, vp, vp, vp, vp, vp, vp, vp, vp]),
         "per_gather": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update": (C.c_int, [vp, u32, vp, vp, vp]),
         "per_update_delta": (C.c_int, [vp, u32, vp, vp, vp]),
@@ -293,9 +294,12 @@ class PrioritizedReplay:
         return out_idx, (out_weight if want_weights else None), (out_prio if want_prio else None)
 
     def step(self, u, beta, upd_prio, upd_pos=None, want_weights: bool = True, want_prio: bool = True,
-             out_idx=None, out_weight=None, out_prio=None, rows_out=None, B=None):
+             out_idx=None, out_weight=None, out_prio=None, rows_out=None, B=None, insert=None):
         """per_step: sample, gather and update the batch just drawn; element j of ``upd_prio`` goes to the leaf
-        drawn by sample ``upd_pos[j]`` (``None``: sample j).  Returns (idx, weights or None, prio or None)."""
+        drawn by sample ``upd_pos[j]`` (``None``: sample j).  Returns (idx, weights or None, prio or None).
+
+        ``insert=(n, rows, prio, out_idx)`` (as for ``insert``; the last three may be None): per_insert_step, the
+        insertion of n rows per tree followed by the step, as one call."""
         torch = self._torch
         if u is None:
             if B is None:
@@ -314,6 +318,20 @@ class PrioritizedReplay:
         dst = None
         if rows_out is not None:
             _keep, dst = self._ptr_array(rows_out, B)
+        if insert is not None:
+            n, ins_rows, ins_prio, ins_out = insert
+            _keep_src, src = self._ptr_array(ins_rows, n)
+            if ins_prio is not None and ins_prio.numel() != self.T * n:
+                raise ValueError("the insertion's prio must hold T*n values")
+            if ins_out is not None and ins_out.numel() != self.T * n:
+                raise ValueError("the insertion's out_idx must hold T*n values")
+            rc = self.lib.per_insert_step(self._h, n, src, _dptr(ins_prio, torch.float32), _dptr(ins_out, torch.int32),
+                                          B, float(beta), _dptr(u, torch.float32), _dptr(out_idx, torch.int32),
+                                          _dptr(out_weight, torch.float32) if want_weights else None,
+                                          _dptr(out_prio, torch.float32) if want_prio else None, dst,
+                                          _dptr(upd_prio, torch.float32), _dptr(upd_pos, torch.int32), self._stream())
+            self._check(rc, "per_insert_step")
+            return out_idx, (out_weight if want_weights else None), (out_prio if want_prio else None)
         rc = self.lib.per_step(self._h, B, float(beta), _dptr(u, torch.float32), _dptr(out_idx, torch.int32),
                                _dptr(out_weight, torch.float32) if want_weights else None,
                                _dptr(out_prio, torch.float32) if want_prio else None, dst,

@@ -168,6 +168,44 @@ class Mirror:
         self.cpu.update(np.ascontiguousarray(upd_idx, dtype=np.uint32), upd_prio)
         return gi, ci
 
+    def insert_step_call(self, n, ins_prio, u, beta, want_weights, upd_prio, pos=None, with_rows=True):
+        """per_insert_step against oracle insert -> sample -> gather -> update (see step_call)."""
+        B = u.shape[-1]
+        counters = np.arange(self.counter, self.counter + n)
+        p = None if ins_prio is None else np.ascontiguousarray(ins_prio, dtype=np.float32)
+        g_rows = c_rows = None
+        if with_rows and self.fb:
+            cd = dev(counters)
+            g_rows = [torch.stack([wl.row_bytes_torch(t, cd, f, b) for t in range(self.T)]) for f, b in enumerate(self.fb)]
+            if self.oracle_payload:
+                c_rows = [np.stack([wl.row_bytes(t, counters, f, b) for t in range(self.T)]) for f, b in enumerate(self.fb)]
+        slots_dev = torch.full((self.T, n), -2, dtype=torch.int32, device="cuda")
+        slots = self.cpu.insert(n, c_rows, p)
+        if with_rows:
+            for t in range(self.T):
+                self.holder[t, slots[t]] = counters
+        self.counter += n
+        ci, cw, cv = self.cpu.sample(u, beta, want_weights)
+        if pos is None:
+            upd_idx = ci
+        else:
+            ok = pos < B
+            upd_idx = np.where(ok, np.take_along_axis(ci, np.where(ok, pos, 0).astype(np.int64), axis=1),
+                               np.uint32(0xFFFFFFFF)).astype(np.uint32)
+        rows = [torch.empty((self.T, B, b), dtype=torch.uint8, device="cuda") for b in self.fb]
+        gi, gw, gv = self.gpu.step(dev(u), beta, dev(upd_prio), None if pos is None else idx_to_dev(pos),
+                                   want_weights=want_weights, rows_out=rows if self.fb else None,
+                                   insert=(n, g_rows, None if p is None else dev(p), slots_dev))
+        assert np.array_equal(idx_to_host(slots_dev), slots), "insert slots (per_insert_step)"
+        assert np.array_equal(idx_to_host(gi), ci), "sampled indices (per_insert_step)"
+        assert gv.cpu().numpy().tobytes() == cv.tobytes(), "sampled leaf values (per_insert_step)"
+        if want_weights:
+            np.testing.assert_allclose(gw.cpu().numpy(), cw, rtol=WEIGHT_RTOL, atol=0)
+        if self.fb:
+            self.gather(gi, ci, got=rows)
+        self.cpu.update(np.ascontiguousarray(upd_idx, dtype=np.uint32), upd_prio)
+        return gi, ci
+
     def update(self, idx_host, prio):
         self.gpu.update(idx_to_dev(idx_host), dev(prio))
         self.cpu.update(np.ascontiguousarray(idx_host, dtype=np.uint32), prio)
@@ -192,9 +230,15 @@ class Mirror:
     def step(self, w: wl.Workload, step: int, seed: int = 0, B=None, check_tree=True):
         """One step in the order insert -> sample -> gather -> update (update targets the sampled rows)."""
         inp = wl.step_inputs(w, step, seed, B)
+        mode = step % 4           # rotate: separate calls, sample+gather fused, whole step fused (two call forms)
+        if w.n_insert and mode == 3:   # ... and the insertion inside the step call
+            self.insert_step_call(w.n_insert, None, inp["u"], inp["beta"], w.weights, inp["upd_prio"],
+                                  wl.dup_positions(inp, self.T, inp["u"].shape[-1]) if step % 8 == 3 else None)
+            if check_tree:
+                self.compare_tree()
+            return
         if w.n_insert:
             self.insert(w.n_insert)
-        mode = step % 4           # rotate: separate calls, sample+gather fused, whole step fused (two call forms)
         if mode == 3:
             self.step_call(inp["u"], inp["beta"], w.weights, inp["upd_prio"], wl.dup_positions(inp, self.T, inp["u"].shape[-1]))
         elif mode == 2:

@@ -828,6 +828,68 @@ def test_step_call_updates_the_batch_it_draws(K, N, T, B, fb, one_kernel):
     m.compare_status()
 
 
+def kernel_launches(m):
+    """{kernel name: launches} since profiling was switched on."""
+    return {k: int(v[1]) for k, v in m.gpu.profile_read().items() if v[1]}
+
+
+# shapes whose sampling kernel can carry an insertion (lazily rebuilt top within reach of its LDS copy), and two that cannot
+RIDE_SHAPES = [(16, 1 << 20, 1, 32, (4, 4, 1, 8, 8), True), (16, 1 << 20, 1, 4096, (68, 24, 4, 68, 1), True),
+               (16, 1 << 18, 4, 1024, (68, 24, 4, 68, 1), True), (32, 1 << 20, 1, 30000, (128,), True),
+               (4, 50001, 2, 700, (12,), True), (8, 300001, 1, 2500, (), True), (64, 1 << 19, 1, 3000, (8,), True),
+               (2, 5000, 1, 64, (3,), False), (4, 1 << 18, 1, 512, (), False)]
+
+
+@pytest.mark.parametrize("K,N,T,B,fb,rides", RIDE_SHAPES)
+def test_insert_carried_by_the_step(K, N, T, B, fb, rides):
+    """per_insert_step = per_insert, then per_step: few rows and many, at the running maximum and at given priorities
+    (above the running maximum, zero, invalid), slots that wrap around the ring's end, slots that are drawn and updated
+    by the same step, with and without a position map, on a ring that is still filling.  Where the shape and the
+    insertion's size allow it the sampling kernel carries the insertion (no insert kernel is launched); elsewhere the
+    same call makes two."""
+    log(f"per_insert_step K={K} N={N} T={T} B={B} rides={rides}")
+    rng = np.random.default_rng(K * 7 + B)
+    m = Mirror(K, N, T, fb)
+    m.gpu.set_tuning("step_kernel", 0)
+    filled = N - N // 8                                    # the ring fills up and wraps during the test
+    prio = wl._draw_priorities("pareto_1.5", rng, (T, filled))
+    prio[rng.random((T, filled)) < 0.01] = 0.0
+    m.insert(filled, prio=prio, chunk=1 << 18)
+    m.gpu.profile(True)
+    sizes = [1, 4, K, K + 1, 3 * K * K + 5, 700, 16, 2]
+    for it, n in enumerate(sizes):
+        if it == 4:                                        # next to the ring's end: this insertion or the next wraps
+            gap = N - (m.gpu.cursor % N)
+            m.insert(max(gap - n // 2 - 1, 1), prio=wl._draw_priorities("pareto_1.5", rng, (T, max(gap - n // 2 - 1, 1))),
+                     chunk=1 << 18)
+        n = min(n, N)
+        u = wl.uniform01(rng, (T, B))
+        pr = wl._draw_updates("absnormal1_eps_pow0.6", rng, (T, B))
+        ins = None
+        if it % 3 == 1:                                    # given priorities: far above the rest (so the new slots are drawn), one invalid, one zero
+            ins = (wl._draw_priorities("pareto_1.5", rng, (T, n)) * np.float32(1e4 if it == 1 else 1.0)).astype(np.float32)
+            if n > 2:
+                ins[:, 1] = np.float32(np.nan)
+                ins[:, 2] = 0.0
+        pos = None
+        if it % 2 == 1:
+            pos = np.stack([rng.permutation(B) for _ in range(T)]).astype(np.uint32)
+            pos[:, ::9] = pos[:, 0:1]
+        before = kernel_launches(m)
+        m.insert_step_call(n, ins, u, 0.4 + 0.05 * it, it % 2 == 0, pr, pos)
+        after = kernel_launches(m)
+        own = {k: v - before.get(k, 0) for k, v in after.items() if v != before.get(k, 0)}
+        log(f"  n={n}: launches {own}")
+        carried = not any(k.startswith("k_insert") or k in ("k_rows_scatter", "k_resum_dense", "k_resum_tail") for k in own)
+        if not rides:
+            assert not carried, own
+        elif n <= 4:                                       # (runs of child groups no longer than the sampling workgroup)
+            assert carried, own
+        m.compare_tree()
+    m.gpu.profile(False)
+    m.compare_status()
+
+
 @pytest.mark.parametrize("K,N,T,B", [(32, 1 << 20, 1, 8192), (16, 1 << 18, 2, 2048), (8, 1 << 18, 1, 4096), (64, 1 << 19, 1, 3000)])
 def test_step_call_when_the_mass_sits_in_few_places(K, N, T, B):
     """The samples of one subtree are one workgroup's work in the one-kernel step.  Here nearly all mass sits in one
