@@ -378,6 +378,9 @@ uint64_t per_rng_calls(const per_t* p);
  *   "lazy_top"   : 1 (default) lets per_update leave the few topmost heights to be rebuilt by
  *                  the next call that reads them; 0 makes per_update finish them itself
  *   "insert_small" : 1 (default) runs an insert of few rows as a single kernel, one workgroup per tree
+ *   "step_tail"  : 1 lets the one-kernel step end inside that kernel (rows, weights and the next call's tables after a
+ *                  wait of all its workgroups for each other) where all of them fit the GPU at once; 0 (default): a second
+ *                  kernel does that, which was measured faster
  *   "insert_ride" : 1 (default) lets the sampling kernel of per_insert_step carry the insertion; 0: two calls
  *   "step_kernel" : how per_step (and per_sample_gather_update called with the sampled batch as its update batch)
  *                  runs.  1 (default): sampling and update as one kernel, one workgroup per subtree, with rows and

@@ -115,19 +115,21 @@ __device__ __forceinline__ void sweep_store(const RowMove& m, uint64_t e0, Regs<
   }
 }
 
+// (row0, nrows: only the rows [row0, row0 + nrows) of the B rows per tree; gathers only)
 template <typename V, bool GATHER>
 __device__ __forceinline__ void move_rows(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
                                           const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
-                                          uint32_t* status, uint32_t job_block, uint32_t job_blocks) {
+                                          uint32_t* status, uint32_t job_block, uint32_t job_blocks, uint32_t row0 = 0,
+                                          uint32_t nrows = 0xFFFFFFFFu) {
   constexpr int U = InFlight<V>::U;
   RowMove m;
   const uint32_t E = ft.bytes[f];
   m.RS = ft.row_stride;
   m.epr = E / (uint32_t)sizeof(V);
-  m.total = (uint64_t)B * m.epr;
+  m.total = (uint64_t)(nrows < B - row0 ? nrows : B - row0) * m.epr;
   m.col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
-  m.io = ft.io[f] + (uint64_t)t * B * E;
-  m.idx = idx ? idx + (size_t)t * B : nullptr;
+  m.io = ft.io[f] + ((uint64_t)t * B + row0) * E;
+  m.idx = idx ? idx + (size_t)t * B + row0 : nullptr;
   m.stride = (uint64_t)job_blocks * blockDim.x;
   m.cursor = cursor;
   m.N = N;
@@ -198,17 +200,18 @@ __device__ __forceinline__ void wide_store(const WideMove& w, uint64_t e0, Regs<
 template <bool GATHER>
 __device__ __forceinline__ void move_rows_wide(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
                                                const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
-                                               uint32_t* status, uint32_t job_block, uint32_t job_blocks) {
+                                               uint32_t* status, uint32_t job_block, uint32_t job_blocks, uint32_t row0 = 0,
+                                               uint32_t nrows = 0xFFFFFFFFu) {
   constexpr int U = 2;
   WideMove w;
   RowMove& m = w.m;
   w.E = ft.bytes[f];
   m.RS = ft.row_stride;
   m.epr = (w.E + 15u) / 16u;
-  m.total = (uint64_t)B * m.epr;
+  m.total = (uint64_t)(nrows < B - row0 ? nrows : B - row0) * m.epr;
   m.col = ft.col[f] + (uint64_t)t * ft.col_stride[f];
-  m.io = ft.io[f] + (uint64_t)t * B * w.E;
-  m.idx = idx ? idx + (size_t)t * B : nullptr;
+  m.io = ft.io[f] + ((uint64_t)t * B + row0) * w.E;
+  m.idx = idx ? idx + (size_t)t * B + row0 : nullptr;
   m.stride = (uint64_t)job_blocks * blockDim.x;
   m.cursor = cursor;
   m.N = N;
@@ -239,21 +242,22 @@ __device__ __forceinline__ uint32_t job_field(const JobRanges& jr, uint32_t b) {
 template <bool GATHER, bool WIDE>
 __device__ __forceinline__ void rows_job(const FieldTable& ft, uint32_t f, uint32_t t, uint32_t B,
                                          const uint32_t* __restrict__ idx, uint32_t cursor, uint32_t N,
-                                         uint32_t* status, uint32_t job_block, uint32_t job_blocks) {
+                                         uint32_t* status, uint32_t job_block, uint32_t job_blocks, uint32_t row0 = 0,
+                                         uint32_t nrows = 0xFFFFFFFFu) {
   switch (ft.vec[f]) {
-    case 16: move_rows<uint4, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
-    case 8: move_rows<uint2, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
+    case 16: move_rows<uint4, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks, row0, nrows); break;
+    case 8: move_rows<uint2, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks, row0, nrows); break;
     case 4:
       if constexpr (WIDE) {
         if (moves_wide(ft.bytes[f], 4)) {
-          move_rows_wide<GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks);
+          move_rows_wide<GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks, row0, nrows);
           break;
         }
       }
-      move_rows<uint32_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks);
+      move_rows<uint32_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks, row0, nrows);
       break;
-    case 2: move_rows<uint16_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
-    default: move_rows<uint8_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks); break;
+    case 2: move_rows<uint16_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks, row0, nrows); break;
+    default: move_rows<uint8_t, GATHER>(ft, f, t, B, idx, cursor, N, status, job_block, job_blocks, row0, nrows); break;
   }
 }
 

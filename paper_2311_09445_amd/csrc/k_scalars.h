@@ -36,6 +36,8 @@ __global__ void k_init_scalars(Geom g, float init_max) {
   g.sfloor[t] = 1;
   if (g.step_ho) {
     for (uint32_t k = 0; k < kStepGroups; ++k) g.step_cnt[(size_t)t * kStepGroups + k] = 0ull;
+    g.step_cnt2[t] = 0ull;
+    g.step_rel[t] = 0u;
     for (uint32_t k = 0; k < 2 * kStepDoneSlots; ++k) g.step_done[(size_t)t * 2 * kStepDoneSlots + k] = 0u;
     for (uint32_t k = 0; k < 2 * kVminSlots; ++k) g.step_vmin[(size_t)t * 2 * kVminSlots + k] = kNoMin;
   }

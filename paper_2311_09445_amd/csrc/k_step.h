@@ -27,7 +27,10 @@
 // one address queue up), and a workgroup that reads its own group's counter when it starts gets the
 // number of finished calls whatever the others have already added.  (Owners that wait for each other
 // inside the kernel to finish the weights themselves were tried: 512 workgroups polling the counters
-// slowed the very atomics they waited for, + 9 us.)
+// slowed the very atomics they waited for, + 9 us.  The whole call inside this kernel, with a wait built as a tree of
+// counters and no memory fences, is there as an option (TAIL, tuning "step_tail"): 25.4 against 22.0 us per step
+// on the 65536-sample workload; between the last owner's last store and the moment every workgroup knows that
+// all have arrived lie 7 us, although that wait alone, with nothing else going on, takes 2 us.)
 //
 // Last writer: element j of the update targets the leaf drawn by sample pos[j] (no map: by sample j).  The
 // samples of one leaf are neighbours in a workgroup's run, so the winner of a leaf is the largest j among
@@ -78,7 +81,19 @@ struct StepShape {
   uint32_t* vmin;                  // [T][2][kVminSlots] smallest sampled values of this call (fp32 bits; by parity)
   uint32_t* inv;                   // [T][inv_stride] per sample: 1 + the largest update element aimed at it (zero between calls)
   uint32_t inv_stride;
+  // when the call ends inside k_step (TAIL)
+  uint32_t helpers;                // workgroups in front of the owners: builders and / or the builders of the next call's tables
+  uint32_t table_blocks;           // how many of them build tables once every owner has arrived
+  unsigned long long* cnt2;        // [T] groups of owners that have all arrived, over all such calls
+  uint32_t* rel;                   // [T] number of finished calls: written when the last owner of a call has arrived (or by the epilogue)
 };
+struct StepTail { FieldTable ft; };   // rows of the sampled indices (io all null: none)
+struct NoTail { uint32_t none; };
+template <bool TAIL> using TailParam = typename std::conditional<TAIL, StepTail, NoTail>::type;
+template <int LOGK, bool COHERENT>
+__device__ __forceinline__ void build_tables(const StepShape& sh, uint32_t t, const float* src, bool from_side, uint32_t first,
+                                             uint32_t count, float* top, float* skipped);
+constexpr uint32_t kTableOwners = 8;   // owners whose tables one workgroup builds
 
 __device__ __forceinline__ uint32_t owners_of_group(uint32_t owners, uint32_t i) {
   return i < owners ? (owners - i + kStepGroups - 1u) / kStepGroups : 0u;
@@ -213,11 +228,21 @@ __device__ __forceinline__ uint32_t chunk_groups(const ChunkLds& c, uint32_t slo
 }
 
 
-template <int LOGK>
+// TAIL: the call ends inside this kernel.  An owner that is done with its update announces it (its group's counter; the
+// last of a group goes on to a counter of groups; the last of all writes the call's number into a word everybody
+// polls), moves the rows of its own samples while the others arrive, and once all have, turns its samples' values
+// into weights; the helper workgroups in front of the grid wait for the same word and then do what the epilogue
+// kernel does otherwise (height ho from the side array, the heights above, the next call's tables).  Nothing of
+// this uses memory fences between workgroups, which on this GPU (several dies, each with its own second-level
+// cache) cost several microseconds each: the few words that travel between workgroups (the owners' new nodes, the
+// smallest sampled values, the counters) are written and read with device-scope atomic accesses, which go past
+// the caches, and a workgroup announces itself only after they have completed.  All waits are bounded; the host
+// launches this form only when all workgroups of the grid fit the GPU at once (a waiting workgroup holds its place).
+template <int LOGK, bool TAIL>
 __global__ void __launch_bounds__(512)
 k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t weight_mode, const float* __restrict__ u,
        RngArgs rng, uint32_t* out_idx, float* __restrict__ out_prio, float* out_w,
-       const float* __restrict__ upd_prio, const uint32_t* __restrict__ upd_pos) {
+       const float* __restrict__ upd_prio, const uint32_t* __restrict__ upd_pos, TailParam<TAIL> tail) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   constexpr int ROW = K + 4;
@@ -238,14 +263,44 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   float* side_ho = sh.side + (size_t)t * sh.side_stride;
   const StepTable* tab = sh.tab + (size_t)t * sh.owners;
 
-  // ------------------------------------------------------------------ builder workgroups (position map only)
-  if (blockIdx.x < sh.builders) {
-    // (the owners of this call cannot finish before every builder has, so the count of group 0 is still that of the calls before)
-    const unsigned long long calls = load_counter(cnt) / owners_of_group(sh.owners, 0);
+  // Waits (bounded) until the call's number `target` stands in the word that the last owner to arrive writes.
+  auto wait_release = [&](uint32_t target) -> bool {
+    if (wave == 0) {
+      uint32_t spins = 0, ok = 1;
+      for (;;) {
+        uint32_t v = lane == 0 ? __hip_atomic_load(sh.rel + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        v = (uint32_t)__shfl((int)v, 0);
+        if ((int32_t)(v - target) >= 0) break;
+        if (++spins > kStepSpinLimit) {
+          ok = 0;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+      }
+      if (lane == 0) {
+        s_u32[0] = ok;
+        if (!ok) atomicOr(&g.status[t], 8u);
+      }
+    }
+    __syncthreads();
+    const bool ok = s_u32[0] != 0;
+    __syncthreads();
+    return ok;
+  };
+
+  // ------------------------------------------------------------------ helper workgroups: builders (position map only), table builders (TAIL)
+  if (blockIdx.x < (TAIL ? sh.helpers : sh.builders)) {
+    // The number of finished calls.  Without TAIL: the owners of this call cannot finish before every builder has, so
+    // the count of group 0 is still that of the calls before.  With TAIL the owners' counters may already have moved
+    // when a helper starts late, so the word that ends a call is read instead: it cannot move before every helper
+    // has said (below) that it has read it.
+    unsigned long long calls;
+    if constexpr (TAIL) calls = __hip_atomic_load(sh.rel + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else calls = load_counter(cnt) / owners_of_group(sh.owners, 0);
     const uint32_t par = (uint32_t)calls & 1u;
     const uint32_t max_seen = read_max_bits(g, t);
     uint32_t mx = 0, f_idx = 0, f_prio = 0, acc = 0;
-    for (uint32_t j = blockIdx.x * BD + tid; j < B; j += sh.builders * BD) {
+    for (uint32_t j = blockIdx.x * BD + tid; blockIdx.x < sh.builders && j < B; j += sh.builders * BD) {
       const uint32_t at = upd_pos[(size_t)t * B + j];
       const float v = upd_prio[(size_t)t * B + j];
       if (!(at < B)) f_idx = 1u;
@@ -257,21 +312,31 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
       }
     }
     // nothing can be sampled (and no element is valid) when the tree's total is not positive
-    const bool positive = tab[0].total > 0.0f;
-    if (positive) {
-      raise_max(g, t, mx, max_seen);
-      if (f_idx | f_prio) atomicOr(&g.status[t], f_idx | f_prio);
-    } else if (B) {
-      if (tid == 0) atomicOr(&g.status[t], 1u);
+    if (blockIdx.x < sh.builders) {
+      const bool positive = tab[0].total > 0.0f;
+      if (positive) {
+        raise_max(g, t, mx, max_seen);
+        if (f_idx | f_prio) atomicOr(&g.status[t], f_idx | f_prio);
+      } else if (B) {
+        if (tid == 0) atomicOr(&g.status[t], 1u);
+      }
     }
     asm volatile("" ::"v"(acc));
     __syncthreads();   // every lane's atomics have returned
     if (tid == 0) atomicAdd(sh.done + ((size_t)t * 2 + par) * kStepDoneSlots + blockIdx.x % kStepDoneSlots, 1u);
+    if constexpr (TAIL) {
+      if (blockIdx.x < sh.table_blocks && wait_release((uint32_t)calls + 1u)) {
+        __shared__ float skipped[kTableOwners * kStepPathMax];
+        const uint32_t first = blockIdx.x * kTableOwners;
+        const uint32_t count = sh.owners - first < kTableOwners ? sh.owners - first : kTableOwners;
+        build_tables<LOGK, true>(sh, t, side_ho, true, first, count, lds, skipped);
+      }
+    }
     return;
   }
 
   // ------------------------------------------------------------------ owner workgroup b
-  const uint32_t b = blockIdx.x - sh.builders;
+  const uint32_t b = blockIdx.x - (TAIL ? sh.helpers : sh.builders);
   const uint32_t my_group = b % kStepGroups;
   float* sub = lds;                                   // heights 1 .. ho-1 of the own subtree, at sub_off[i]
   // per binary step from the root to b: the sum of the left block; bit 0: b lies to the right, bit 1: the right block is not zero
@@ -283,6 +348,9 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   c.wval = reinterpret_cast<float*>(c.wpos + (BD + 1));
   c.touch = reinterpret_cast<uint32_t*>(c.wval + (BD + 1));
 
+  bool tail_has_rows = false;
+  if constexpr (TAIL)
+    for (uint32_t f = 0; f < tail.ft.n_fields; ++f) tail_has_rows = tail_has_rows || tail.ft.io[f] != nullptr;
   PER_TRACE_DECL;
   PER_MARK(0);
   // ---- trip 1: the number of finished calls, this owner's table, the own subtree's heights, the running maximum
@@ -318,6 +386,45 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     __syncthreads();   // every lane of the workgroup has issued its stores
     if (tid == 0) atomicAdd(sh.cnt + (size_t)t * kStepGroups + my_group, 1ull);
   };
+  // TAIL: the same with an answer: the last owner of a group announces the group, the last group ends the call.
+  auto arrive = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // (each wave waits for its stores and atomics to complete)
+    __syncthreads();
+    if (wave == 0) {
+      uint32_t last = 0;
+      if (lane == 0) {
+        const uint32_t members = owners_of_group(sh.owners, my_group);
+        const unsigned long long old = atomicAdd(sh.cnt + (size_t)t * kStepGroups + my_group, 1ull);
+        if (old + 1ull == (calls + 1ull) * members) {
+          const uint32_t n_groups = sh.owners < kStepGroups ? sh.owners : kStepGroups;
+          const unsigned long long old2 = atomicAdd(sh.cnt2 + t, 1ull);
+          last = (old2 + 1ull) % n_groups == 0ull ? 1u : 0u;
+        }
+      }
+      if (__shfl((int)last, 0)) {
+        // every helper must have read the call's number before it changes (they say so when they have; bounded wait;
+        // the slots are read side by side, one per lane)
+        const uint32_t* slot = sh.done + ((size_t)t * 2 + par) * kStepDoneSlots;
+        uint32_t spins = 0;
+        bool ok = true;
+        for (;;) {
+          uint32_t d = lane < kStepDoneSlots ? __hip_atomic_load(slot + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+#pragma unroll
+          for (int m = 1; m < (int)kStepDoneSlots; m <<= 1) d += (uint32_t)__shfl_xor((int)d, m);
+          if (__shfl((int)d, 0) >= (int)sh.helpers) break;
+          if (++spins > kStepSpinLimit) {
+            ok = false;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(2);
+        }
+        if (lane == 0) {
+          if (!ok) atomicOr(&g.status[t], 8u);
+          __hip_atomic_store(sh.rel + t, (uint32_t)calls + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+  };
   // The words of the next call's parity start empty (nothing of this call touches them).
   auto arm_next_call = [&]() {
     if (b != 0) return;
@@ -335,7 +442,7 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
         uint32_t d = lane < kStepDoneSlots ? __hip_atomic_load(slot + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
 #pragma unroll
         for (int m = 1; m < (int)kStepDoneSlots; m <<= 1) d += (uint32_t)__shfl_xor((int)d, m);
-        if (__shfl((int)d, 0) >= (int)sh.builders) break;
+        if (__shfl((int)d, 0) >= (int)(TAIL ? sh.helpers : sh.builders)) break;
         if (++spins > kStepSpinLimit) {
           ok = 0;
           break;
@@ -354,7 +461,9 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   };
   if (!(total > 0.0f)) {   // nothing can be sampled from this tree; workgroup b reports a slice of the batch
     const bool waited = wait_for_builders();
-    for (uint32_t s = b * BD + tid; s < B; s += sh.owners * BD) {
+    const uint32_t share = (B + sh.owners - 1u) / sh.owners;   // (a contiguous share: its rows are this workgroup's too)
+    const uint32_t s_lo = b * share < B ? b * share : B, s_hi = s_lo + share < B ? s_lo + share : B;
+    for (uint32_t s = s_lo + tid; s < s_hi; s += BD) {
       const size_t o = (size_t)t * B + s;
       out_idx[o] = 0xFFFFFFFFu;
       if (out_prio) out_prio[o] = 0.0f;
@@ -362,10 +471,20 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
       if (sh.builders && waited) inv[s] = 0u;   // (what the builders have recorded goes unused: no element is valid)
     }
     // (without a map every element is out of range too; with one the builders have said so)
-    if (leader) atomicOr(&g.status[t], sh.builders ? 4u : 5u);
-    if (tid == 0) side_ho[b] = mine->node;   // (every owner leaves its node's value: the epilogue takes all of them)
+    if (leader) atomicOr(&g.status[t], sh.builders && !(TAIL && tail_has_rows) ? 4u : 5u);   // (rows of an index out of range: flag 1)
+    // (every owner leaves its node's value: whoever builds the next tables takes all of them)
+    if (tid == 0) __hip_atomic_store(&side_ho[b], mine->node, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     arm_next_call();
-    count_me_in();
+    if constexpr (TAIL) {
+      arrive();
+      for (uint32_t f = 0; f < tail.ft.n_fields; ++f) {   // (rows of zeros; the flag that says why is set above)
+        if (!tail.ft.io[f]) continue;
+        uint8_t* dst = tail.ft.io[f] + ((size_t)t * B + s_lo) * tail.ft.bytes[f];
+        for (size_t i = tid; i < (size_t)(s_hi - s_lo) * tail.ft.bytes[f]; i += BD) dst[i] = 0;
+      }
+    } else {
+      count_me_in();
+    }
     return;
   }
   const float seg = total / (float)B;
@@ -628,7 +747,7 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
       if (i == n_sub - 1) off_last = sh.sub_off[i];
     if (tid < 64) {
       const float sum = group_sum<LOGK>(sub + off_last, lane % LPS);
-      if (lane == 0) side_ho[b] = sum;
+      if (lane == 0) __hip_atomic_store(&side_ho[b], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // (past the caches: read by another workgroup of this kernel when the call ends in it)
     }
   }
   PER_MARK(8);
@@ -643,21 +762,87 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     if (lane == 0 && m != 0x7F800000u)
       atomicMin(sh.vmin + ((size_t)t * 2 + par) * kVminSlots + (b * (BD >> 6) + wave) % kVminSlots, m);
   }
-  count_me_in();
+  if constexpr (!TAIL) {
+    count_me_in();
+  } else {
+    arrive();
+    PER_MARK(10);
+    // the rows of this owner's own samples, while the other owners arrive
+    for (uint32_t f = 0; f < tail.ft.n_fields; ++f) {   // (a loop, not unrolled: the movers' code once)
+      if (!tail.ft.io[f]) continue;
+      if (tail.ft.vec[f] == 16) {
+        // fields that move in 16-byte pieces: four pieces per lane in flight, all loads before the first store; the
+        // index of a row comes from LDS where the run was one window (its lanes have left them there)
+        const uint32_t E = tail.ft.bytes[f], epr = E / 16u, RS = tail.ft.row_stride;
+        const uint32_t total_e = run_n * epr;
+        const uint8_t* col = tail.ft.col[f] + (uint64_t)t * tail.ft.col_stride[f];
+        uint8_t* io = tail.ft.io[f] + ((uint64_t)t * B + run_lo) * E;
+        bool bad = false;
+        for (uint32_t e0 = tid; e0 < total_e; e0 += 4u * BD) {
+          uint4 v[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const uint32_t e = e0 + (uint32_t)k * BD;
+            const bool live = e < total_e;
+            const uint32_t row = live ? e / epr : 0u, piece = e % epr;
+            const uint32_t at = searched ? out_idx[(size_t)t * B + run_lo + row] : c.key[1u + (run_lo - s0) + row];
+            const bool ok = at < g.N;
+            bad = bad || (live && !ok);
+            v[k] = *reinterpret_cast<const uint4*>(col + (uint64_t)(ok ? at : 0u) * RS + piece * 16u);
+            if (!ok) v[k] = make_uint4(0, 0, 0, 0);
+          }
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const uint32_t e = e0 + (uint32_t)k * BD;
+            if (e < total_e) *reinterpret_cast<uint4*>(io + (uint64_t)e * 16u) = v[k];
+          }
+        }
+        if (bad) atomicOr(&g.status[t], 1u);
+      } else {
+        rows_job<true, false>(tail.ft, f, t, B, out_idx, 0, g.N, g.status, 0, 1, run_lo, run_n);
+      }
+    }
+    PER_MARK(11);
+    const bool released = out_w && wait_release((uint32_t)calls + 1u);
+    PER_MARK(12);
+    if (released) {
+      // the batch's smallest sampled value: every owner's contribution is in the slots now
+      const uint32_t* slots = sh.vmin + ((size_t)t * 2 + par) * kVminSlots;
+      uint32_t m = 0x7F800000u;
+      for (uint32_t i = tid; i < kVminSlots; i += BD) m = min_u32(m, __hip_atomic_load(slots + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      m = wave_min_u32(m);
+      if (lane == 0) s_u32[wave] = m;
+      __syncthreads();
+      for (uint32_t wv = 0; wv < (BD >> 6); ++wv) m = min_u32(m, s_u32[wv]);
+      if (weight_mode & kWeightBufferNorm) m = buffer_min_bits(g, t, weight_mode);
+      for (uint32_t i = tid; i < run_n; i += BD) {
+        const size_t o = (size_t)t * B + run_lo + i;
+        out_w[o] = importance_weight(out_w[o], __uint_as_float(m), beta);
+      }
+    }
+    PER_MARK(13);
+    PER_FLUSH_TAG(2);
+  }
 }
 
 // The tables of the owners [first, first + count) of tree t from the nodes of height ho at src (the level array, or
 // the side array the owners of a call have just filled), by one workgroup; dynamic LDS holds the heights ho .. H-1.
 // The workgroup with first == 0 also puts the tree's memory in order: the level array of height ho takes src's values
 // (if src is the side array) and the heights above are recomputed and stored, so that nothing is left stale.
-template <int LOGK>
+// COHERENT: src was written by other workgroups of the running kernel (with device-scope atomic stores) and is read
+// the same way.
+template <int LOGK, bool COHERENT>
 __device__ __forceinline__ void build_tables(const StepShape& sh, uint32_t t, const float* src, bool from_side, uint32_t first,
                                              uint32_t count, float* top, float* skipped) {
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
   const uint32_t tid = threadIdx.x, BD = blockDim.x;
   const int n_top = (int)sh.n_top;
-  for (uint32_t i = tid; i < sh.top_cnt[0]; i += BD) top[sh.top_off[0] + i] = i < sh.top_n[0] ? src[i] : 0.0f;
+  for (uint32_t i = tid; i < sh.top_cnt[0]; i += BD) {
+    float v = 0.0f;
+    if (i < sh.top_n[0]) v = COHERENT ? __hip_atomic_load(src + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : src[i];
+    top[sh.top_off[0] + i] = v;
+  }
   __syncthreads();
   {
     const unsigned q = tid % LPS;
@@ -726,8 +911,6 @@ __device__ __forceinline__ void build_tables(const StepShape& sh, uint32_t t, co
   }
 }
 
-constexpr uint32_t kTableOwners = 8;   // owners whose tables one workgroup builds
-
 // In front of a step when another call has changed the tree since the tables were built.
 template <int LOGK>
 __global__ void __launch_bounds__(256)
@@ -736,7 +919,7 @@ k_step_tables(StepShape sh) {
   const uint32_t t = blockIdx.y, first = blockIdx.x * kTableOwners;
   const uint32_t count = sh.owners - first < kTableOwners ? sh.owners - first : kTableOwners;
   __shared__ float skipped[kTableOwners * kStepPathMax];
-  build_tables<LOGK>(sh, t, sh.top_ptr[0] + (size_t)t * sh.top_stride[0], false, first, count, top, skipped);
+  build_tables<LOGK, false>(sh, t, sh.top_ptr[0] + (size_t)t * sh.top_stride[0], false, first, count, top, skipped);
 }
 
 // Ends a step: the first table_blocks workgroups take the owners' new nodes of height ho into the tree and build the
@@ -748,6 +931,8 @@ template <int LOGK, bool WIDE>
 __global__ void __launch_bounds__(256)
 k_step_epilogue(Geom g, StepShape sh, uint32_t table_blocks, uint32_t B, float beta, uint32_t weight_mode,
                 float* __restrict__ w, const uint32_t* __restrict__ idx, FieldTable ft, JobRanges jr) {
+  touch_kernel_arguments<kernarg_lines<Geom, StepShape, uint32_t, uint32_t, float, uint32_t, float*, const uint32_t*, FieldTable,
+                                       JobRanges>()>();
   extern __shared__ __attribute__((aligned(16))) float top[];
   __shared__ uint32_t s_m[4];
   __shared__ float skipped[kTableOwners * kStepPathMax];
@@ -755,7 +940,9 @@ k_step_epilogue(Geom g, StepShape sh, uint32_t table_blocks, uint32_t B, float b
   if (blockIdx.x < table_blocks) {
     const uint32_t first = blockIdx.x * kTableOwners;
     const uint32_t count = sh.owners - first < kTableOwners ? sh.owners - first : kTableOwners;
-    build_tables<LOGK>(sh, t, sh.side + (size_t)t * sh.side_stride, true, first, count, top, skipped);
+    build_tables<LOGK, false>(sh, t, sh.side + (size_t)t * sh.side_stride, true, first, count, top, skipped);
+    if (blockIdx.x == 0 && threadIdx.x == 0)   // the number of finished calls, for calls that read it from this word
+      sh.rel[t] = (uint32_t)(sh.cnt[(size_t)t * kStepGroups] / owners_of_group(sh.owners, 0));
     return;
   }
   const uint32_t job = blockIdx.x - table_blocks;
@@ -866,8 +1053,24 @@ static void step_shape(const Geom& g, uint32_t block, uint32_t B, bool with_map,
   sh.vmin = g.step_vmin;
   sh.inv = reinterpret_cast<uint32_t*>(g.owner);
   sh.inv_stride = 2u * g.owner_stride;
+  sh.table_blocks = (sh.owners + kTableOwners - 1u) / kTableOwners;
+  sh.helpers = sh.builders > sh.table_blocks ? sh.builders : sh.table_blocks;
+  sh.cnt2 = g.step_cnt2;
+  sh.rel = g.step_rel;
   *out = sh;
   *step_lds = (size_t)off * 4;
+}
+
+// Compute units of `device` (0 if the query fails).
+static uint32_t compute_units(int device) {
+  static std::atomic<int> known[kMaxDevices];
+  if (device < 0 || device >= kMaxDevices) return 0;
+  int n = known[device].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n < 0) n = 0;
+    known[device].store(n, std::memory_order_relaxed);
+  }
+  return (uint32_t)n;
 }
 
 template <int LOGK>
@@ -881,26 +1084,47 @@ static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block,
   FieldTable ft{};
   if (rows) ft = *rows;
   const bool wide = any_field_moves_wide(rows ? &ft : nullptr);
-  hipError_t e = grant_lds<&k_step<LOGK>>(tn, bytes);
-  if (e != hipSuccess) return e;
-  const uint32_t table_blocks = (sh.owners + kTableOwners - 1u) / kTableOwners;
+  // The call ends inside k_step when every workgroup of its grid can be resident at once (its workgroups wait for
+  // each other at the end, and one that waits keeps its place).
+  bool tail = tn.step_tail && !wide;
+  const size_t tail_bytes = bytes > table_bytes ? bytes : table_bytes;
+  hipError_t e;
+  if (tail) {
+    e = grant_lds<&k_step<LOGK, true>>(tn, tail_bytes);
+    if (e != hipSuccess) return e;
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_step<LOGK, true>, (int)block, tail_bytes) != hipSuccess) per_cu = 0;
+    const uint64_t room = (uint64_t)(per_cu > 0 ? per_cu : 0) * compute_units(tn.device);
+    tail = (uint64_t)(sh.helpers + sh.owners) * g.T <= room;
+  }
+  if (!tail) {
+    e = grant_lds<&k_step<LOGK, false>>(tn, bytes);
+    if (e != hipSuccess) return e;
+  }
   if (!tables_valid) {
-    PER_LAUNCH(KID_STEP_TABLES, k_step_tables<LOGK>, dim3(table_blocks, g.T), dim3(256), table_bytes, s, sh);
+    PER_LAUNCH(KID_STEP_TABLES, k_step_tables<LOGK>, dim3(sh.table_blocks, g.T), dim3(256), table_bytes, s, sh);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  if (tail) {
+    StepTail tl{};
+    tl.ft = ft;
+    PER_LAUNCH(KID_STEP, (k_step<LOGK, true>), dim3(sh.helpers + sh.owners, g.T), dim3(block), tail_bytes, s, g, sh, B, size, beta,
+               weight_mode, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, tl);
+    return hipGetLastError();
+  }
   const dim3 grid(sh.builders + sh.owners, g.T);
-  PER_LAUNCH(KID_STEP, k_step<LOGK>, grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx, out_prio, out_w,
-             upd_prio, upd_pos);
+  PER_LAUNCH(KID_STEP, (k_step<LOGK, false>), grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx,
+             out_prio, out_w, upd_prio, upd_pos, NoTail{});
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const JobRanges jr = job_ranges(rows ? &ft : nullptr, B, 256, out_w ? B : 0u, 0u, g.T);
-  const dim3 egrid(table_blocks + jr.first[2 + kMaxFields], g.T);
+  const dim3 egrid(sh.table_blocks + jr.first[2 + kMaxFields], g.T);
   if (wide) {
-    PER_LAUNCH(KID_STEP_EPILOGUE, (k_step_epilogue<LOGK, true>), egrid, dim3(256), table_bytes, s, g, sh, table_blocks, B, beta,
+    PER_LAUNCH(KID_STEP_EPILOGUE, (k_step_epilogue<LOGK, true>), egrid, dim3(256), table_bytes, s, g, sh, sh.table_blocks, B, beta,
                weight_mode, out_w, out_idx, ft, jr);
   } else {
-    PER_LAUNCH(KID_STEP_EPILOGUE, (k_step_epilogue<LOGK, false>), egrid, dim3(256), table_bytes, s, g, sh, table_blocks, B, beta,
+    PER_LAUNCH(KID_STEP_EPILOGUE, (k_step_epilogue<LOGK, false>), egrid, dim3(256), table_bytes, s, g, sh, sh.table_blocks, B, beta,
                weight_mode, out_w, out_idx, ft, jr);
   }
   return hipGetLastError();

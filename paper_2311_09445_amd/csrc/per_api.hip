@@ -90,8 +90,8 @@ void make_layout(const per_config* c, Layout* L) {
   size_t off = 0;
   L->scalars_off = off;                         // max_v, status, vnext, vcur, sbase, sfloor, max_pend [T] each; vmin[2][T][kVminSlots], vmin_buf[T][kMinParts]
   off = round_up(off + (size_t)(7 + 2 * kVminSlots + kMinParts) * T * 4, kAlign);
-  L->step_off = off;                            // the one-kernel step's words: cnt[T][kStepGroups] (64-bit), done[T][2][kStepDoneSlots], vmin[T][2][kVminSlots]
-  off = round_up(off + (size_t)(2 * kStepGroups + 2 * kStepDoneSlots + 2 * kVminSlots) * T * 4, kAlign);
+  L->step_off = off;                            // the one-kernel step's words: cnt[T][kStepGroups] (64-bit), cnt2[T] (64-bit), done[T][2][kStepDoneSlots], vmin[T][2][kVminSlots], rel[T]
+  off = round_up(off + (size_t)(2 * kStepGroups + 2 * kStepDoneSlots + 2 * kVminSlots + 4) * T * 4, kAlign);   // (+ cnt2 (64-bit), rel, a spare word)
   for (uint32_t l = 0; l <= L->H; ++l) {
     const uint64_t padded = ((uint64_t)L->n[l] + K - 1) / K * K;
     L->stride[l] = (uint32_t)round_up(padded, 64);
@@ -278,8 +278,10 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.max_pend = g.sfloor + g.T;
   g.vmin = g.max_pend + g.T;
   g.step_cnt = reinterpret_cast<unsigned long long*>(p->arena + L.step_off);
-  g.step_done = reinterpret_cast<uint32_t*>(g.step_cnt + (size_t)kStepGroups * g.T);
+  g.step_cnt2 = g.step_cnt + (size_t)kStepGroups * g.T;
+  g.step_done = reinterpret_cast<uint32_t*>(g.step_cnt2 + g.T);
   g.step_vmin = g.step_done + (size_t)2 * kStepDoneSlots * g.T;
+  g.step_rel = g.step_vmin + (size_t)2 * kVminSlots * g.T;
   g.vmin_buf = g.vmin + (size_t)2 * kVminSlots * g.T;
   g.step_side = reinterpret_cast<float*>(p->arena + L.side_off);
   g.step_side_stride = kStepSideStride;
@@ -302,6 +304,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.insert_small = 1;
   p->tn.group_claim = 1;
   p->tn.step_kernel = 1;
+  p->tn.step_tail = 0;   // (measured slower than the second kernel: see k_step)
   p->tn.insert_ride = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
@@ -947,6 +950,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "group_claim")) {
     if (value != 0 && value != 1) return PER_EINVAL;
     p->tn.group_claim = (uint32_t)value;
+    return PER_OK;
+  }
+  if (!strcmp(name, "step_tail")) {
+    if (value != 0 && value != 1) return PER_EINVAL;
+    p->tn.step_tail = (uint32_t)value;
     return PER_OK;
   }
   if (!strcmp(name, "insert_ride")) {

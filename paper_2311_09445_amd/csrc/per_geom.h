@@ -58,6 +58,9 @@ struct Geom {
   unsigned long long* step_cnt;     // [T][kStepGroups] owners of the one-kernel step that have finished, over all calls
   uint32_t* step_done;              // [T][2][kStepDoneSlots] its builders that have finished (by parity of the call)
   uint32_t* step_vmin;              // [T][2][kVminSlots] smallest sampled values of its call (by parity)
+  unsigned long long* step_cnt2;    // [T] groups of owners that have all arrived at the end of their update, over all calls that
+                                    // finish inside the one kernel
+  uint32_t* step_rel;               // [T] number of the last call whose owners have all arrived (what its waiting workgroups poll)
 };
 uint32_t step_owner_height(const Geom& g);   // (needs K, logK, H, T, n[])
 constexpr uint32_t kMinParts = 1024;     // most workgroups k_min_reduce is launched with
@@ -225,6 +228,7 @@ struct Tuning {
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   uint32_t group_claim;       // update batches claim through the group entries whenever they are short enough
   uint32_t insert_ride;       // per_insert_step lets its sampling kernel carry the insertion where that is possible
+  uint32_t step_tail;         // the one-kernel step also ends inside that kernel (rows, weights, tables) where all its workgroups fit the GPU at once
   uint32_t step_kernel;       // per_step runs sampling and update as one kernel: 0 never, 1 where it fits and pays off, 2 wherever it fits
   Profiler* prof;
   int device;                 // the device the buffer lives on

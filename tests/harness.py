@@ -159,7 +159,8 @@ class Mirror:
         gi, gw, gv = self.gpu.step(dev(u), beta, dev(upd_prio),
                                    None if pos is None else idx_to_dev(pos), want_weights=want_weights,
                                    rows_out=rows if self.fb else None)
-        assert np.array_equal(idx_to_host(gi), ci), "sampled indices (per_step)"
+        gi_h = idx_to_host(gi)
+        assert np.array_equal(gi_h, ci), f"sampled indices (per_step) differ at {np.argwhere(gi_h != ci)[:8].tolist()}: {gi_h[gi_h != ci][:8]} vs {ci[gi_h != ci][:8]} ({int((gi_h != ci).sum())} in all)"
         assert gv.cpu().numpy().tobytes() == cv.tobytes(), "sampled leaf values (per_step)"
         if want_weights:
             np.testing.assert_allclose(gw.cpu().numpy(), cw, rtol=WEIGHT_RTOL, atol=0)
