@@ -428,7 +428,7 @@ def main():
         assert buf.total().cpu().numpy().tobytes() == final_root.tobytes(), "step kernel ended in a different state"
         step_stream = {"ms_per_step": round(ms_stream, 5), "value": round(T * B / (ms_stream * 1e-3), 1),
                        "unit": "transitions/s", "launches": 1, "steps_per_launch": steps,
-                       "call": "per_run_steps (tree held in LDS, one workgroup per tree)"}
+                       "call": "per_run_steps (tree, or its heights above the leaves, held in LDS; one workgroup per tree)"}
 
         # the same steps once more as a queue of op-coded requests (insert, sample, update per step)
         from paper_2311_09445_amd.per import OP_INSERT, OP_SAMPLE, OP_UPDATE

@@ -209,11 +209,14 @@ int per_update_td(per_t* p, uint32_t B, const uint32_t* d_idx /*[T][B]*/, const 
 int per_update_delta(per_t* p, uint32_t B, const uint32_t* d_idx /*[T][B]*/, const float* d_delta /*[T][B]*/,
                      void* stream);
 
-/* A list of steps in one launch, for buffers small enough that every height of a tree fits the LDS
- * of one compute unit (about 150 KB: e.g. 32768 leaves at fanout 16).  The paper keeps the sum tree of
- * its Replay Manager in on-chip memory and lets a kernel that is started once work through a stream
- * of requests (Section V-A, "RM on FPGA"); here one workgroup per tree loads the tree, runs step
- * after step against the LDS copy and stores it back at the end.  Step s is, in this order,
+/* A list of steps in one launch, for buffers small enough that a tree, or at least its heights above the
+ * leaves, fits the LDS of one compute unit (about 150 KB: all of a tree of 32768 leaves at fanout 16; the
+ * upper heights of one of 524288 leaves at fanout 16, of 2^20 at fanout 32, 2^21 at fanout 64).  The paper
+ * keeps the sum tree of its Replay Manager in on-chip memory and lets a kernel that is started once work
+ * through a stream of requests (Section V-A, "RM on FPGA": buffers of 10K to 100K entries); here one
+ * workgroup per tree loads the tree, runs step after step against the LDS copy and stores it back at the
+ * end; where only the upper heights fit, the leaves stay in memory and the workgroup, the only one that
+ * touches the tree meanwhile, reads and writes them there.  Step s is, in this order,
  *   per_insert(n_insert rows)  ->  per_sample(B)  ->  per_gather  ->  per_update(B),
  * with the same results as those calls.  All arrays carry a leading step dimension:
  *   d_ins_rows   : [n_fields] device pointers, each [steps][T][n_insert][field_bytes]; NULL entries or a
@@ -241,7 +244,7 @@ typedef struct {
   const float* d_upd_prio;
 } per_stream_io;
 int per_run_steps(per_t* p, uint32_t n_steps, uint32_t n_insert, uint32_t B, const per_stream_io* io, void* stream);
-int per_run_steps_fits(const per_t* p);   /* 1: the trees of this buffer fit, 0: they do not */
+int per_run_steps_fits(const per_t* p);   /* 1: the trees of this buffer fit (wholly, or above their leaves), 0: they do not */
 
 /* A queue of op-coded requests in one launch (Section V-A, "RM on FPGA": the requests fed to the Replay
  * Manager carry a unified operation code and are decoded and executed as they stream in, by kernels
@@ -330,8 +333,8 @@ int per_set_ring(per_t* p, uint64_t cursor, uint64_t size);
  * per_update, the fused step and small inserts for the nodes they touch while this mode is on, rebuilt
  * from the leaves after calls that cannot (large inserts, per_update_delta, per_run_steps,
  * per_run_requests, per_set_ring), and reduced to one value per tree by a kernel in front of every
- * sampling call that returns weights.  per_run_steps and per_run_requests sweep their LDS copy of the
- * leaves instead.  The mode applies to the calls made after it is set.
+ * sampling call that returns weights.  per_run_steps and per_run_requests sweep the leaves (their LDS copy,
+ * or memory) instead.  The mode applies to the calls made after it is set.
  * per_min_priority: d_out[t] = smallest positive leaf of tree t (+infinity if there is none). */
 #define PER_NORM_BATCH  0
 #define PER_NORM_BUFFER 1

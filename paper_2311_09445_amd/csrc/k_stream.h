@@ -12,6 +12,12 @@
 // the LDS copy, and stores the tree back at the end.  Every tree access of a step is then an LDS
 // access; only rows, inputs and outputs travel to memory.  Results are those of the separate calls.
 //
+// A tree whose leaves do not fit beside the rest (MEM) keeps heights 1 .. H in LDS and its leaves in memory: the
+// paper's 100K-entry buffers at small fanouts are of that size.  The workgroup is still the only one that
+// touches the tree while the kernel runs, so its own leaf stores, made visible to its other waves by a
+// barrier, are all the coherence that takes; every operation then costs a trip or two to memory for the leaf
+// groups it reads (sampling: the last level of the walk; insert and update: the groups whose sums change).
+//
 // Update inside one workgroup: a valid element raises the leaf (reinterpreted as an integer) to
 // a marker above every valid priority pattern, 0x80000001 + its position, by an LDS atomic max; the
 // element that finds its own marker afterwards is the last writer and stores its value; then
@@ -43,21 +49,25 @@ __device__ __forceinline__ float lane_group_sum(const float* grp) {
 }
 
 // Every active lane recomputes the ancestors of its leaf in the LDS tree, one height per barrier.
+// (leaves_mem: the leaves in memory, or null when they are part of the LDS copy)
 template <int LOGK>
-__device__ __forceinline__ void resum_paths_lds(float* tree, const uint32_t* off, uint32_t H, bool active, uint32_t leaf) {
+__device__ __forceinline__ void resum_paths_lds(float* tree, const uint32_t* off, uint32_t H, bool active, uint32_t leaf,
+                                                const float* leaves_mem) {
   constexpr int K = Fan<LOGK>::K;
   for (uint32_t h = 1; h <= H; ++h) {
-    __syncthreads();
+    __syncthreads();   // (also makes the leaf stores of the other waves visible: one compute unit, one first-level cache)
     if (active) {
       const uint32_t parent = leaf >> (h * LOGK);
-      tree[off[h] + parent] = lane_group_sum<LOGK>(tree + off[h - 1] + (size_t)parent * K);
+      if (h == 1 && leaves_mem) tree[off[h] + parent] = lane_group_sum<LOGK>(leaves_mem + (size_t)parent * K);
+      else tree[off[h] + parent] = lane_group_sum<LOGK>(tree + off[h - 1] + (size_t)parent * K);
     }
   }
 }
 
 // One tree in the LDS of its workgroup, and the few words the operations below share.
 struct LdsTree {
-  float* tree;              // heights 0 .. H back to back, zero padding included
+  float* tree;              // heights 0 .. H back to back, zero padding included (height 0 left out when leaves_mem is set)
+  float* leaves_mem;        // null, or the tree's leaves in memory (zero padded to whole groups)
   const uint32_t* off;      // off[h]: where height h starts (floats); off[H + 1]: all floats
   uint32_t* sampled;        // [1024] indices of the latest sampling operation
   uint32_t* max_bits;       // running maximum priority (fp32 bits)
@@ -112,10 +122,10 @@ __device__ __forceinline__ void lds_insert(const LdsTree& lt, const FieldTable& 
         if (ok && v > 0.0f) atomicMax(lt.max_bits, __float_as_uint(v));
         if (!ok) flags |= 2u;
       }
-      if (ok) lt.tree[lt.off[0] + slot] = v;
+      if (ok) (lt.leaves_mem ? lt.leaves_mem : lt.tree + lt.off[0])[slot] = v;
     }
   }
-  resum_paths_lds<LOGK>(lt.tree, lt.off, lt.H, ok, slot);
+  resum_paths_lds<LOGK>(lt.tree, lt.off, lt.H, ok, slot, lt.leaves_mem);
   const uint64_t end = (uint64_t)cursor + n;
   cursor = (uint32_t)(end >= N ? end - N : end);
   size = size + n > N ? N : size + n;
@@ -138,7 +148,8 @@ __device__ __forceinline__ uint32_t lds_sample(const LdsTree& lt, const FieldTab
   const float total = lt.tree[lt.off[lt.H]];
   if (buffer_norm && out_w) {   // weights relative to the whole tree: its smallest positive leaf, by a sweep over the LDS copy
     uint32_t m = kNoMin;
-    for (uint32_t e = tid; e < lt.N; e += blockDim.x) m = min_u32(m, positive_bits(lt.tree[lt.off[0] + e]));
+    const float* all_leaves = lt.leaves_mem ? lt.leaves_mem : lt.tree + lt.off[0];
+    for (uint32_t e = tid; e < lt.N; e += blockDim.x) m = min_u32(m, positive_bits(all_leaves[e]));
     m = wave_min_u32(m);
     if ((tid & 63u) == 0 && m != kNoMin) atomicMin(lt.bmin_bits, m);
   }
@@ -151,7 +162,8 @@ __device__ __forceinline__ uint32_t lds_sample(const LdsTree& lt, const FieldTab
     val = total;
     for (uint32_t h = lt.H; h-- > 0;) {
       unsigned child;
-      descend_lane<LOGK>(lt.tree + lt.off[h] + (size_t)node * K, r, child, val);
+      if (h == 0 && lt.leaves_mem) descend_lane<LOGK>(lt.leaves_mem + (size_t)node * K, r, child, val);
+      else descend_lane<LOGK>(lt.tree + lt.off[h] + (size_t)node * K, r, child, val);
       node = node * K + child;
     }
     if (out_w && tid < B) atomicMin(lt.vmin_bits, __float_as_uint(val));
@@ -181,7 +193,6 @@ template <int LOGK>
 __device__ __forceinline__ void lds_update(const LdsTree& lt, uint32_t B, uint32_t i, float v, uint32_t size,
                                            uint32_t& flags) {
   const uint32_t tid = threadIdx.x;
-  uint32_t* leaf_bits = reinterpret_cast<uint32_t*>(lt.tree + lt.off[0]);
   bool valid = false;
   if (tid < B) {
     if (!(i < size)) flags |= 1u;
@@ -189,18 +200,29 @@ __device__ __forceinline__ void lds_update(const LdsTree& lt, uint32_t B, uint32
     else valid = true;
   }
   const uint32_t mark = 0x80000001u + tid;
-  if (valid) atomicMax(&leaf_bits[i], mark);
-  __syncthreads();
-  const bool won = valid && leaf_bits[i] == mark;
-  __syncthreads();
-  if (won) lt.tree[lt.off[0] + i] = v;
+  bool won;
+  if (lt.leaves_mem) {   // (the markers go through memory: atomics there, and a read that passes by the first-level cache)
+    uint32_t* leaf_bits = reinterpret_cast<uint32_t*>(lt.leaves_mem);
+    if (valid) atomicMax(&leaf_bits[i], mark);
+    __syncthreads();
+    won = valid && __hip_atomic_load(&leaf_bits[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == mark;
+    __syncthreads();
+    if (won) lt.leaves_mem[i] = v;
+  } else {
+    uint32_t* leaf_bits = reinterpret_cast<uint32_t*>(lt.tree + lt.off[0]);
+    if (valid) atomicMax(&leaf_bits[i], mark);
+    __syncthreads();
+    won = valid && leaf_bits[i] == mark;
+    __syncthreads();
+    if (won) lt.tree[lt.off[0] + i] = v;
+  }
   if (valid && v > 0.0f) atomicMax(lt.max_bits, __float_as_uint(v));
-  resum_paths_lds<LOGK>(lt.tree, lt.off, lt.H, valid, i);
+  resum_paths_lds<LOGK>(lt.tree, lt.off, lt.H, valid, i, lt.leaves_mem);
 }
 
 // Loads every height of tree t into LDS (lanes 64 .. 64 + H + 1 have filled s_off, lane 0 the maximum).
 __device__ __forceinline__ void lds_tree_load(const LevelTable& tab, const LdsTree& lt) {
-  for (uint32_t h = 0; h <= lt.H; ++h) {   // the whole tree, zero padding included
+  for (uint32_t h = lt.leaves_mem ? 1u : 0u; h <= lt.H; ++h) {   // the whole tree, zero padding included
     const float* lvl = tab.lvl[h];
     float* dst = lt.tree + lt.off[h];
     for (uint32_t e = threadIdx.x; e < lt.off[h + 1] - lt.off[h]; e += blockDim.x) dst[e] = lvl[e];
@@ -209,7 +231,7 @@ __device__ __forceinline__ void lds_tree_load(const LevelTable& tab, const LdsTr
 // ... and back to memory, with the running maximum and the flags the lanes have collected.
 __device__ __forceinline__ void lds_tree_store(const Geom& g, uint32_t t, const LevelTable& tab, const LdsTree& lt,
                                                uint32_t flags, uint32_t* s_flags) {
-  for (uint32_t h = 0; h <= lt.H; ++h) {
+  for (uint32_t h = lt.leaves_mem ? 1u : 0u; h <= lt.H; ++h) {
     float* lvl = tab.lvl[h];
     const float* src = lt.tree + lt.off[h];
     for (uint32_t e = threadIdx.x; e < tab.n[h]; e += blockDim.x) lvl[e] = src[e];
@@ -242,6 +264,7 @@ k_run_steps(StreamKernelArgs ka) {
   __syncthreads();
   LdsTree lt;
   lt.tree = tree;
+  lt.leaves_mem = a.leaves_in_memory ? tab.lvl[0] : nullptr;
   lt.off = s_off;
   lt.sampled = reinterpret_cast<uint32_t*>(tree + s_off[H + 1]);
   lt.max_bits = &s_max;
@@ -318,6 +341,7 @@ k_run_requests(QueueKernelArgs ka) {
   __syncthreads();
   LdsTree lt;
   lt.tree = tree;
+  lt.leaves_mem = a.leaves_in_memory ? tab.lvl[0] : nullptr;
   lt.off = s_off;
   lt.sampled = reinterpret_cast<uint32_t*>(tree + s_off[H + 1]);
   lt.max_bits = &s_max;
@@ -359,18 +383,26 @@ k_run_requests(QueueKernelArgs ka) {
   lds_tree_store(g, t, tab, lt, flags, &s_flags);
 }
 
-// LDS floats of a whole tree (every height padded to whole child groups), or 0 if it cannot be
-// held beside the step kernel's other LDS data.
+// LDS floats of a tree's copy (every height padded to whole child groups), or 0 if it cannot be held beside the step
+// kernel's other LDS data.  The whole tree if that fits; else the heights 1 .. H, the leaves staying in memory
+// (*leaves_in_memory says which).
 constexpr uint32_t kStreamLdsBytes = 156 * 1024;
-uint32_t stream_tree_floats(const Geom& g, uint32_t* off) {
-  uint64_t floats = 0;
-  for (uint32_t h = 0; h <= g.H; ++h) {
-    if (off) off[h] = (uint32_t)floats;
-    floats += h < g.H ? ((uint64_t)g.n[h] + g.K - 1) / g.K * g.K : 4;   // (the root padded to 16 bytes)
-    if (floats * 4 > kStreamLdsBytes) return 0;
+uint32_t stream_tree_floats(const Geom& g, uint32_t* off, uint32_t* leaves_in_memory) {
+  for (uint32_t skip = 0; skip < 2; ++skip) {
+    uint64_t floats = 0;
+    bool fits = true;
+    for (uint32_t h = 0; h <= g.H && fits; ++h) {
+      if (off) off[h] = (uint32_t)floats;
+      if (h == 0 && skip) continue;
+      floats += h < g.H ? ((uint64_t)g.n[h] + g.K - 1) / g.K * g.K : 4;   // (the root padded to 16 bytes)
+      fits = floats * 4 <= kStreamLdsBytes;
+    }
+    if (!fits || (floats + 1024) * 4 > kStreamLdsBytes || (skip && g.H < 2)) continue;
+    if (off) off[g.H + 1] = (uint32_t)floats;
+    if (leaves_in_memory) *leaves_in_memory = skip;
+    return (uint32_t)floats;
   }
-  if (off) off[g.H + 1] = (uint32_t)floats;
-  return (floats + 1024) * 4 <= kStreamLdsBytes ? (uint32_t)floats : 0u;
+  return 0u;
 }
 
 template <int LOGK>
@@ -378,7 +410,7 @@ static hipError_t launch_run_steps_k(const Geom& g, const Tuning& tn, StreamArgs
   StreamKernelArgs ka{};
   ka.g = g;
   ka.a = a;
-  const uint32_t floats = stream_tree_floats(g, ka.a.off);
+  const uint32_t floats = stream_tree_floats(g, ka.a.off, &ka.a.leaves_in_memory);
   if (!floats) return hipErrorInvalidValue;
   const size_t bytes = ((size_t)floats + 1024) * 4;   // the tree and the sampled indices of one step
   hipError_t e = grant_lds<&k_run_steps<LOGK>>(tn, bytes);
@@ -400,7 +432,7 @@ static hipError_t launch_run_requests_k(const Geom& g, const Tuning& tn, const Q
   QueueKernelArgs ka{};
   ka.g = g;
   ka.a = a;
-  const uint32_t floats = stream_tree_floats(g, ka.a.off);
+  const uint32_t floats = stream_tree_floats(g, ka.a.off, &ka.a.leaves_in_memory);
   if (!floats) return hipErrorInvalidValue;
   const size_t bytes = ((size_t)floats + 1024) * 4;   // the tree and the indices of the latest sampling request
   hipError_t e = grant_lds<&k_run_requests<LOGK>>(tn, bytes);

@@ -155,6 +155,7 @@ struct StreamArgs {
   const float* ins_prio;            // [steps][T][n_insert] or null: running maximum
   FieldTable ins, rows;             // io arrays hold [steps][T][n][bytes]; io all null: nothing to move
   uint32_t off[kMaxHeight + 2];     // where height h starts in LDS (floats); off[H + 1] = all floats
+  uint32_t leaves_in_memory;        // the LDS copy holds heights 1 .. H only
 };
 
 // A queue of op-coded requests run by one workgroup per tree on an LDS copy of the tree (see k_run_requests).
@@ -165,6 +166,7 @@ struct QueueArgs {
   const per_request* queue;         // device copy of the requests
   FieldTable fields;                // columns, row sizes and access widths; the io pointers come from the requests
   uint32_t off[kMaxHeight + 2];     // as in StreamArgs
+  uint32_t leaves_in_memory;
 };
 
 // Workgroup ranges of the jobs sharing one launch: [first[j], first[j+1]) for job j, where job 0 is the
@@ -270,7 +272,7 @@ hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, bool tab
                        uint32_t weight_mode, const FieldTable* rows, const float* upd_prio, const uint32_t* upd_pos,
                        hipStream_t s);
 size_t step_table_bytes();
-uint32_t stream_tree_floats(const Geom& g, uint32_t* off);
+uint32_t stream_tree_floats(const Geom& g, uint32_t* off, uint32_t* leaves_in_memory = nullptr);
 hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s);
 hipError_t launch_run_requests(const Geom& g, const Tuning& tn, const QueueArgs& a, hipStream_t s);
 hipError_t launch_get_priority(const Geom& g, const Tuning& tn, uint32_t n, const uint32_t* idx, float* out, hipStream_t s);

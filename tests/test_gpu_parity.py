@@ -639,14 +639,17 @@ def test_sampling_with_uniforms_drawn_on_the_device(K, N, T, B):
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("K,N,T,B,n_ins,fb,explicit", [
     (2, 4096, 1, 64, 4, (16, 4, 4, 16, 1), False), (16, 30000, 2, 512, 16, (12,), True),
-    (32, 32768, 1, 1024, 0, (128,), False), (4, 1000, 3, 100, 7, (), True), (64, 20000, 1, 33, 1, (5,), False)])
+    (32, 32768, 1, 1024, 0, (128,), False), (4, 1000, 3, 100, 7, (), True), (64, 20000, 1, 33, 1, (5,), False),
+    # trees whose leaves stay in memory (heights 1 .. H in LDS): the paper's 100K entries and beyond
+    (16, 100000, 2, 512, 16, (12,), True), (8, 200001, 1, 300, 4, (4, 1), False), (32, 1 << 20, 1, 1024, 8, (), True),
+    (64, 1500000, 1, 700, 3, (8,), False)])
 @pytest.mark.parametrize("own_batch", [True, False])
 def test_run_steps_equals_the_separate_calls(K, N, T, B, n_ins, fb, explicit, own_batch):
     log(f"run_steps K={K} N={N} T={T} B={B} n_ins={n_ins} own_batch={own_batch}")
     rng = np.random.default_rng(K * N + B + n_ins)
     m = Mirror(K, N, T, fb)
     assert m.gpu.run_steps_fits()
-    m.insert(N - 10, prio=wl._draw_priorities("exponential_1", rng, (T, N - 10)), chunk=5000)   # the ring wraps below
+    m.insert(N - 10, prio=wl._draw_priorities("exponential_1", rng, (T, N - 10)), chunk=max(5000, N // 8))   # the ring wraps below
     steps = 6
     u = wl.uniform01(rng, (steps, T, B))
     beta = np.linspace(0.4, 1.0, steps).astype(np.float32)
@@ -1161,7 +1164,8 @@ def test_buffer_wide_weights_in_the_fused_step_and_the_one_launch_forms(K, N, B)
 # per_run_requests: a queue of op-coded requests in one launch.  Same results as the calls, in queue order.
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("K,N,T,fb,seed", [(2, 4096, 1, (16, 4, 4, 16, 1), 1), (16, 30000, 2, (12,), 2),
-                                           (32, 32768, 1, (128,), 3), (4, 1000, 3, (), 4), (64, 20000, 1, (5, 68), 5)])
+                                           (32, 32768, 1, (128,), 3), (4, 1000, 3, (), 4), (64, 20000, 1, (5, 68), 5),
+                                           (16, 100000, 2, (12,), 6), (32, 700001, 1, (), 7)])   # (leaves in memory)
 def test_run_requests_equals_the_separate_calls(K, N, T, fb, seed):
     """A random queue of insert (plain and collision-free), sample (+ weights, + rows) and update requests
     (given indices, or the batch sampled last).  The oracle gets every request as it is drawn, so later
@@ -1171,7 +1175,7 @@ def test_run_requests_equals_the_separate_calls(K, N, T, fb, seed):
     rng = np.random.default_rng(seed)
     m = Mirror(K, N, T, fb)
     first = N - 300
-    m.insert(first, prio=wl._draw_priorities("exponential_1", rng, (T, first)), chunk=5000)   # the ring wraps below
+    m.insert(first, prio=wl._draw_priorities("exponential_1", rng, (T, first)), chunk=max(5000, N // 8))   # the ring wraps below
     queue, checks = [], []
     sampled = None                  # indices of the latest sampling request (from the oracle)
     for r in range(40):
