@@ -220,12 +220,31 @@ __device__ __forceinline__ void lds_update(const LdsTree& lt, uint32_t B, uint32
   resum_paths_lds<LOGK>(lt.tree, lt.off, lt.H, valid, i, lt.leaves_mem);
 }
 
-// Loads every height of tree t into LDS (lanes 64 .. 64 + H + 1 have filled s_off, lane 0 the maximum).
+// Loads every height of tree t into LDS (lanes 64 .. 64 + H + 1 have filled s_off, lane 0 the maximum).  The heights
+// are arrays of their own in memory and lie back to back in LDS; the copy runs over the LDS floats as one range, eight
+// per lane in flight and all loads of a round before its first store, so that a tree of a dozen heights is not a dozen
+// trips to memory one after the other.
 __device__ __forceinline__ void lds_tree_load(const LevelTable& tab, const LdsTree& lt) {
-  for (uint32_t h = lt.leaves_mem ? 1u : 0u; h <= lt.H; ++h) {   // the whole tree, zero padding included
-    const float* lvl = tab.lvl[h];
-    float* dst = lt.tree + lt.off[h];
-    for (uint32_t e = threadIdx.x; e < lt.off[h + 1] - lt.off[h]; e += blockDim.x) dst[e] = lvl[e];
+  constexpr int R = 8;
+  const uint32_t h_first = lt.leaves_mem ? 1u : 0u;
+  const uint32_t begin = lt.off[h_first], end = lt.off[lt.H + 1];
+  for (uint32_t base = begin; base < end; base += (uint32_t)R * blockDim.x) {
+    float v[R];
+    uint32_t h = h_first;   // (the height of this lane's element: found anew per round, then it only grows)
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      const uint32_t e = base + (uint32_t)k * blockDim.x + threadIdx.x;
+      v[k] = 0.0f;
+      if (e < end) {
+        while (h < lt.H && e >= lt.off[h + 1]) ++h;
+        v[k] = tab.lvl[h][e - lt.off[h]];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      const uint32_t e = base + (uint32_t)k * blockDim.x + threadIdx.x;
+      if (e < end) lt.tree[e] = v[k];
+    }
   }
 }
 // ... and back to memory, with the running maximum and the flags the lanes have collected.
