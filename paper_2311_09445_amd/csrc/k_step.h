@@ -49,7 +49,7 @@ constexpr int kStepPathMax = kStepTop * 6;      // binary steps from the root to
 struct StepTable {
   float2 path[kStepPathMax];   // per binary step from the root to the node: (sum of the left block, flags); bit 0 of the flags:
                                // the node lies to the right; bit 1: the right block is not zero
-  double mass;                 // sum of the nodes of height ho in front of it
+  double mass;                 // sum of the nodes of height ho in front of it, as a fraction of the total (0 when that is 0)
   float total;                 // the root
   float node;                  // its own value
 };
@@ -538,7 +538,7 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   // where this workgroup's run of samples starts, to within a few: the mass in front of node b over seg
   uint32_t s0;
   {
-    const double est = mass / ((double)total / (double)B);
+    const double est = mass * (double)B;   // (the division is done where the table is built: it would stand in front of this workgroup's second trip)
     const uint32_t s_guess = est >= (double)B ? B : (est > 0.0 ? (uint32_t)est : 0u);   // (not a number: 0)
     s0 = s_guess > kStepPad ? s_guess - kStepPad : 0u;
   }
@@ -905,7 +905,7 @@ __device__ __forceinline__ void build_tables(const StepShape& sh, uint32_t t, co
     const uint32_t b = first + e;
     double mass = 0.0;
     for (uint32_t k = 0; k < n_steps; ++k) mass += (double)skipped[e * n_steps + k];
-    tab[b].mass = mass;
+    tab[b].mass = total > 0.0f ? mass / (double)total : 0.0;
     tab[b].total = total;
     tab[b].node = top[sh.top_off[0] + b];
   }
