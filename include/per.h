@@ -385,6 +385,10 @@ uint64_t per_rng_calls(const per_t* p);
  *                  wait of all its workgroups for each other) where all of them fit the GPU at once; 0 (default): a second
  *                  kernel does that, which was measured faster
  *   "insert_ride" : 1 (default) lets the sampling kernel of per_insert_step carry the insertion; 0: two calls
+ *   "whole_rows" : how a gather of two or more fields reads the stored rows.  0: one job per field; 1 (default):
+ *                  from 16384 rows per call (all trees together), and where the asked-for fields lie within 512
+ *                  bytes of a row, every sampled row is read once, as a whole, and each field's dense rows are
+ *                  written from a copy in LDS; 2: that form wherever the rows fit (tests)
  *   "step_kernel" : how per_step (and per_sample_gather_update called with the sampled batch as its update batch)
  *                  runs.  1 (default): sampling and update as one kernel, one workgroup per subtree, with rows and
  *                  weights in a second, where the tree fits that kernel and the batch is large enough for it

@@ -226,6 +226,113 @@ __device__ __forceinline__ void move_rows_wide(const FieldTable& ft, uint32_t f,
   if (bad) atomicOr(&status[t], 1u);
 }
 
+// Rows of several fields gathered whole.  One job per field reads every sampled row once per field, from
+// workgroups on different parts of the device, so the row's memory lines are fetched once per field.  Here a
+// workgroup takes `whole_rows` sampled rows per pass: the stored bytes that cover all asked-for fields come in
+// as 16-byte pieces (up to kWholePieces per lane in flight) and are parked in LDS, row after row; then each
+// field's dense span of those rows, which is contiguous in the caller's array, is written from LDS with
+// consecutive lanes on consecutive addresses, in 16-byte stores where the span starts on such a boundary.
+// `stage` holds whole_rows * whole_span bytes (at most kWholeRowsLds).
+constexpr int kWholePieces = 6;
+template <int K>
+__device__ __forceinline__ void whole_where(uint32_t lane, uint32_t block, uint32_t items, uint32_t P,
+                                            const uint32_t* __restrict__ idx, Regs<uint32_t, kWholePieces>& at,
+                                            Regs<uint32_t, kWholePieces>& piece) {
+  if constexpr (K < kWholePieces) {
+    const uint32_t i = lane + (uint32_t)K * block;
+    const uint32_t r = i < items ? i / P : 0u;
+    reg<K>(piece) = i < items ? i - r * P : 0u;
+    reg<K>(at) = idx[r];
+    whole_where<K + 1>(lane, block, items, P, idx, at, piece);
+  }
+}
+template <int K>
+__device__ __forceinline__ void whole_load(const uint8_t* base, uint32_t RS, uint32_t N, Regs<uint32_t, kWholePieces>& at,
+                                           Regs<uint32_t, kWholePieces>& piece, Regs<uint4, kWholePieces>& v, bool& bad) {
+  if constexpr (K < kWholePieces) {
+    const bool ok = reg<K>(at) < N;
+    bad |= !ok;
+    uint4 got = *reinterpret_cast<const uint4*>(base + (uint64_t)(ok ? reg<K>(at) : 0u) * RS + 16u * reg<K>(piece));
+    if (!ok) got = make_uint4(0, 0, 0, 0);
+    reg<K>(v) = got;
+    whole_load<K + 1>(base, RS, N, at, piece, v, bad);
+  }
+}
+template <int K>
+__device__ __forceinline__ void whole_park(uint32_t lane, uint32_t block, uint32_t items, uint4* stage,
+                                           Regs<uint4, kWholePieces>& v) {
+  if constexpr (K < kWholePieces) {
+    const uint32_t i = lane + (uint32_t)K * block;
+    if (i < items) stage[i] = reg<K>(v);
+    whole_park<K + 1>(lane, block, items, stage, v);
+  }
+}
+__device__ __forceinline__ void move_whole_rows(const FieldTable& ft, const JobRanges& jr, uint32_t t, uint32_t B,
+                                                const uint32_t* __restrict__ idx, uint32_t N, uint32_t* status,
+                                                uint32_t job_block, uint32_t job_blocks, uint8_t* stage) {
+  const uint32_t R = jr.whole_rows, span = jr.whole_span, P = span >> 4;
+  const uint32_t f0 = jr.whole_field;
+  const uint8_t* first = ft.col[f0] + (uint64_t)t * ft.col_stride[f0];
+  const uint8_t* base = first - jr.whole_lead;
+  const uint32_t lane = threadIdx.x, block = blockDim.x;
+  idx += (size_t)t * B;
+  bool bad = false;
+  for (uint32_t r0 = job_block * R; r0 < B; r0 += job_blocks * R) {
+    const uint32_t rows = B - r0 < R ? B - r0 : R;
+    const uint32_t items = rows * P;
+    if (r0 != job_block * R) __syncthreads();   // the pass before is done with the staging bytes
+    {
+      Regs<uint32_t, kWholePieces> at, piece;
+      Regs<uint4, kWholePieces> v;
+      whole_where<0>(lane, block, items, P, idx + r0, at, piece);
+      whole_load<0>(base, ft.row_stride, N, at, piece, v, bad);
+      whole_park<0>(lane, block, items, reinterpret_cast<uint4*>(stage), v);
+    }
+    __syncthreads();
+    for (uint32_t f = 0; f < ft.n_fields; ++f) {
+      if (!ft.io[f]) continue;
+      const uint32_t E = ft.bytes[f];
+      const uint32_t foff = (uint32_t)(ft.col[f] - ft.col[f0]) + jr.whole_lead;
+      uint8_t* dst = ft.io[f] + ((uint64_t)t * B + r0) * E;
+      const uint32_t S = rows * E;
+      if ((E & 3u) == 0 && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+        for (uint32_t c = lane; 16u * c < S; c += block) {
+          const uint32_t p = 16u * c;
+          uint32_t row = p / E, off = p - row * E;
+          uint32_t w[4];
+#pragma unroll
+          for (uint32_t k = 0; k < 4; ++k) {
+            w[k] = p + 4u * k < S ? *reinterpret_cast<const uint32_t*>(stage + row * span + foff + off) : 0u;
+            off += 4u;
+            if (off >= E) {
+              off = 0;
+              ++row;
+            }
+          }
+          if (p + 16u <= S) {
+            *reinterpret_cast<uint4*>(dst + p) = make_uint4(w[0], w[1], w[2], w[3]);
+          } else {
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+              if (p + 4u * k < S) *reinterpret_cast<uint32_t*>(dst + p + 4u * k) = w[k];
+          }
+        }
+      } else if ((E & 3u) == 0 && (reinterpret_cast<uintptr_t>(dst) & 3u) == 0) {
+        for (uint32_t p = 4u * lane; p < S; p += 4u * block) {
+          const uint32_t row = p / E, off = p - row * E;
+          *reinterpret_cast<uint32_t*>(dst + p) = *reinterpret_cast<const uint32_t*>(stage + row * span + foff + off);
+        }
+      } else {
+        for (uint32_t p = lane; p < S; p += block) {
+          const uint32_t row = p / E, off = p - row * E;
+          dst[p] = stage[row * span + foff + off];
+        }
+      }
+    }
+  }
+  if (bad) atomicOr(&status[t], 1u);
+}
+
 // The field whose row job workgroup b of the job grid belongs to (kMaxFields: none).  The ranges lie back to
 // back, so it is the number of ranges that end at or before b; written without an early exit so that the
 // range ends are read together, not one after the other.
@@ -370,7 +477,10 @@ __global__ void k_finish(FieldTable ft, JobRanges jr, Geom g, FinishArgs a) {
     return;
   }
   const uint32_t f = job_field(jr, b);
-  if (f < (uint32_t)kMaxFields)
+  if (jr.whole_rows) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t stage[];
+    move_whole_rows(ft, jr, t, a.B, a.idx, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f], stage);
+  } else if (f < (uint32_t)kMaxFields)
     rows_job<true, WIDE>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
 }
 
@@ -381,6 +491,13 @@ __global__ void k_rows(FieldTable ft, JobRanges jr, uint32_t B, const uint32_t* 
   const uint32_t t = blockIdx.y;
   const uint32_t b = blockIdx.x;
   const uint32_t f = job_field(jr, b);
+  if constexpr (GATHER) {
+    if (jr.whole_rows) {
+      extern __shared__ __attribute__((aligned(16))) uint8_t stage[];
+      move_whole_rows(ft, jr, t, B, idx, N, status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f], stage);
+      return;
+    }
+  }
   if (f < (uint32_t)kMaxFields)
     rows_job<GATHER, WIDE>(ft, f, t, B, idx, cursor, N, status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
 }
@@ -389,8 +506,40 @@ __global__ void k_rows(FieldTable ft, JobRanges jr, uint32_t B, const uint32_t* 
 // pass over its elements needs with as few elements per lane (1, 2, 4 .. what its mover keeps in flight)
 // as keep the field's workgroups over all trees within about one round of the device; the movers
 // stride when that is not enough.
+// Whether a gather of these fields moves whole rows (see move_whole_rows), and with what shape: at least two
+// fields asked for, their common span of a stored row short enough that 16 rows or more fit the staging bytes
+// and the pieces a workgroup keeps in flight.  Passes take a multiple of 16 rows, so that every field's dense
+// span of a pass starts on a 16-byte boundary when the field's array does.
+constexpr uint64_t kWholeRowsFrom = 16384;   // rows of a call (all trees) from which whole rows are the default
+static bool plan_whole_rows(const FieldTable* ft, uint32_t block, JobRanges* jr) {
+  if (!ft) return false;
+  uint32_t asked = 0, f0 = 0;
+  const uint8_t* lo = nullptr;
+  const uint8_t* hi = nullptr;
+  for (uint32_t f = 0; f < ft->n_fields; ++f) {
+    if (!ft->io[f]) continue;
+    if (!asked || ft->col[f] < lo) lo = ft->col[f], f0 = f;
+    if (!asked || ft->col[f] + ft->bytes[f] > hi) hi = ft->col[f] + ft->bytes[f];
+    ++asked;
+  }
+  if (asked < 2) return false;
+  const uint32_t lead = (uint32_t)(reinterpret_cast<uintptr_t>(lo) & 15u);
+  const uint64_t span = ((uint64_t)(hi - lo) + lead + 15u) / 16u * 16u;
+  if (span > ft->row_stride || span > kWholeRowsLds / 16u) return false;
+  uint32_t R = (uint32_t)kWholePieces * block / (uint32_t)(span / 16u);
+  if (R > kWholeRowsLds / (uint32_t)span) R = kWholeRowsLds / (uint32_t)span;
+  R = R / 16u * 16u;
+  if (R > 64u) R = 64u;
+  if (R < 16u) return false;
+  jr->whole_rows = R;
+  jr->whole_span = (uint32_t)span;
+  jr->whole_field = f0;
+  jr->whole_lead = lead;
+  return true;
+}
+
 static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block, uint32_t weights_B, uint32_t claim_B,
-                            uint32_t trees) {
+                            uint32_t trees, uint32_t whole_rows = 0) {
   JobRanges jr{};
   uint32_t at = 0;
   jr.first[0] = at;
@@ -398,8 +547,17 @@ static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block,
   jr.first[1] = at;
   at += (claim_B + block - 1) / block;
   jr.first[2] = at;
+  // (whole_rows: 0 never, 1 for batches long enough that the row traffic sets the time, 2 wherever the rows fit)
+  const bool whole = (whole_rows == 2 || (whole_rows == 1 && (uint64_t)rows * trees >= kWholeRowsFrom)) &&
+                     plan_whole_rows(ft, block, &jr);
   for (uint32_t f = 0; f < (uint32_t)kMaxFields; ++f) {
-    if (ft && f < ft->n_fields && ft->io[f]) {
+    if (whole) {
+      if (f == jr.whole_field) {
+        uint64_t n = ((uint64_t)rows + jr.whole_rows - 1) / jr.whole_rows;
+        if (n > (1u << 20)) n = 1u << 20;
+        at += (uint32_t)n;
+      }
+    } else if (ft && f < ft->n_fields && ft->io[f]) {
       const uint64_t elems = (uint64_t)rows * row_elements(ft->bytes[f], ft->vec[f]);
       const uint32_t most = field_in_flight(ft->bytes[f], ft->vec[f]);
       uint64_t n = 0;
@@ -415,6 +573,9 @@ static JobRanges job_ranges(const FieldTable* ft, uint32_t rows, uint32_t block,
   return jr;
 }
 
+// staging bytes of the workgroups of a launch with these job ranges
+static size_t whole_rows_lds(const JobRanges& jr) { return (size_t)jr.whole_rows * jr.whole_span; }
+
 // true when a field of the call moves in 16-byte pieces on 4-byte boundaries
 static bool any_field_moves_wide(const FieldTable* ft) {
   for (uint32_t f = 0; ft && f < ft->n_fields; ++f)
@@ -425,13 +586,14 @@ static bool any_field_moves_wide(const FieldTable* ft) {
 hipError_t launch_gather(const Geom& g, const Tuning& tn, const FieldTable& ft, uint32_t B, const uint32_t* idx,
                          hipStream_t s) {
   const uint32_t block = tn.gather_block;
-  const JobRanges jr = job_ranges(&ft, B, block, 0, 0, g.T);
+  const JobRanges jr = job_ranges(&ft, B, block, 0, 0, g.T, tn.whole_rows);
   const uint32_t gx = jr.first[2 + kMaxFields];
   if (gx == 0) return hipSuccess;
-  if (any_field_moves_wide(&ft)) {
-    PER_LAUNCH(KID_GATHER, (k_rows<true, true>), dim3(gx, g.T), dim3(block), 0, s, ft, jr, B, idx, 0, g.N, g.status);
+  const size_t lds = whole_rows_lds(jr);
+  if (!jr.whole_rows && any_field_moves_wide(&ft)) {
+    PER_LAUNCH(KID_GATHER, (k_rows<true, true>), dim3(gx, g.T), dim3(block), lds, s, ft, jr, B, idx, 0, g.N, g.status);
   } else {
-    PER_LAUNCH(KID_GATHER, (k_rows<true, false>), dim3(gx, g.T), dim3(block), 0, s, ft, jr, B, idx, 0, g.N, g.status);
+    PER_LAUNCH(KID_GATHER, (k_rows<true, false>), dim3(gx, g.T), dim3(block), lds, s, ft, jr, B, idx, 0, g.N, g.status);
   }
   return hipGetLastError();
 }
@@ -442,11 +604,13 @@ static hipError_t launch_finish(const Geom& g, const Tuning& tn, const FieldTabl
   if (rows) ft = *rows;
   if (!a.w && !a.has_claim) return rows ? launch_gather(g, tn, ft, a.B, a.idx, s) : hipSuccess;
   const uint32_t block = tn.gather_block;
-  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, block, a.w ? a.B : 0u, a.has_claim ? a.claim.B : 0u, g.T);
-  if (any_field_moves_wide(rows ? &ft : nullptr)) {
-    PER_LAUNCH(KID_FINISH, k_finish<true>, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), 0, s, ft, jr, g, a);
+  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, block, a.w ? a.B : 0u, a.has_claim ? a.claim.B : 0u, g.T,
+                                  tn.whole_rows);
+  const size_t lds = whole_rows_lds(jr);
+  if (!jr.whole_rows && any_field_moves_wide(rows ? &ft : nullptr)) {
+    PER_LAUNCH(KID_FINISH, k_finish<true>, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), lds, s, ft, jr, g, a);
   } else {
-    PER_LAUNCH(KID_FINISH, k_finish<false>, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), 0, s, ft, jr, g, a);
+    PER_LAUNCH(KID_FINISH, k_finish<false>, dim3(jr.first[2 + kMaxFields], g.T), dim3(block), lds, s, ft, jr, g, a);
   }
   return hipGetLastError();
 }

@@ -395,7 +395,10 @@ k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldT
     return;
   }
   const uint32_t f = job_field(jr, b);
-  if (f < (uint32_t)kMaxFields)
+  if (jr.whole_rows) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t stage[];
+    move_whole_rows(ft, jr, t, a.B, a.idx, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f], stage);
+  } else if (f < (uint32_t)kMaxFields)
     rows_job<true, WIDE>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
   PER_MARK(3);
   PER_FLUSH();
@@ -500,14 +503,15 @@ static hipError_t launch_tree_finish_k(const Geom& g, const Tuning& tn, const Cl
   if (tblock > 512) tblock = 512;   // half the lanes of a compute unit are left to the other jobs
   FieldTable ft{};
   if (rows) ft = *rows;
-  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u, g.T);
+  const JobRanges jr = job_ranges(rows ? &ft : nullptr, a.B, tblock, a.w ? a.B : 0u, 0u, g.T, tn.whole_rows);
   const uint32_t tree_blocks = g.n[sl.hb];
+  size_t lds = tree_lds_bytes<LOGK>(sl);
+  if (lds < whole_rows_lds(jr)) lds = whole_rows_lds(jr);
   const uint32_t chain = (lazy_top_height(g, tn) ? 0u : 1u) | (c.fold_max ? 2u : 0u);
   const dim3 grid(tree_blocks + jr.first[2 + kMaxFields], g.T);
-  const bool wide = any_field_moves_wide(rows ? &ft : nullptr);
+  const bool wide = !jr.whole_rows && any_field_moves_wide(rows ? &ft : nullptr);
 #define PER_TREE_FINISH(TM, WD)                                                                                        \
-  PER_LAUNCH(KID_TREE_FINISH, (k_tree_finish<LOGK, TM, WD>), grid, dim3(tblock), tree_lds_bytes<LOGK>(sl), s, g, sl, \
-             chain, tree_blocks, ft, jr, a)
+  PER_LAUNCH(KID_TREE_FINISH, (k_tree_finish<LOGK, TM, WD>), grid, dim3(tblock), lds, s, g, sl, chain, tree_blocks, ft, jr, a)
   if (c.track_min) {
     if (wide) { PER_TREE_FINISH(true, true); } else { PER_TREE_FINISH(true, false); }
   } else {

@@ -306,6 +306,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.step_kernel = 1;
   p->tn.step_tail = 0;   // (measured slower than the second kernel: see k_step)
   p->tn.insert_ride = 1;
+  p->tn.whole_rows = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->claims_left = false;
@@ -955,6 +956,11 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (!strcmp(name, "step_tail")) {
     if (value != 0 && value != 1) return PER_EINVAL;
     p->tn.step_tail = (uint32_t)value;
+    return PER_OK;
+  }
+  if (!strcmp(name, "whole_rows")) {
+    if (value < 0 || value > 2) return PER_EINVAL;
+    p->tn.whole_rows = (uint32_t)value;
     return PER_OK;
   }
   if (!strcmp(name, "insert_ride")) {

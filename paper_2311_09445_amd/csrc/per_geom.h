@@ -173,7 +173,12 @@ struct QueueArgs {
 // weights, job 1 the claim and job 2 + f the rows of payload field f.
 struct JobRanges {
   uint32_t first[3 + kMaxFields];
+  // Rows gathered whole (see move_whole_rows): rows per workgroup pass (0: every field has its own job), the
+  // bytes of a stored row that cover the asked-for fields (from a 16-byte boundary, a multiple of 16), the field
+  // that comes first in the row (its job range holds the workgroups) and the bytes between that boundary and it.
+  uint32_t whole_rows, whole_span, whole_field, whole_lead;
 };
+constexpr uint32_t kWholeRowsLds = 8192;   // staging bytes of a workgroup that gathers whole rows
 
 struct Range2 { uint32_t a0, b0, a1, b1; };   // two half-open node ranges [a0,b0) u [a1,b1)
 
@@ -230,6 +235,7 @@ struct Tuning {
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   uint32_t group_claim;       // update batches claim through the group entries whenever they are short enough
   uint32_t insert_ride;       // per_insert_step lets its sampling kernel carry the insertion where that is possible
+  uint32_t whole_rows;        // gathers of several fields move whole rows through LDS where the rows are short enough
   uint32_t step_tail;         // the one-kernel step also ends inside that kernel (rows, weights, tables) where all its workgroups fit the GPU at once
   uint32_t step_kernel;       // per_step runs sampling and update as one kernel: 0 never, 1 where it fits and pays off, 2 wherever it fits
   Profiler* prof;

@@ -1585,3 +1585,78 @@ def test_rows_in_16_byte_pieces_on_4_byte_boundaries(fb, shift):
     want = cpu.gather(ci)
     for f, b in enumerate(fb):
         assert np.array_equal(out[f].cpu().numpy().reshape(T, B, b), want[f]), f"fused field {f}"
+
+
+@pytest.mark.parametrize("shift", [0, 4, 13])
+@pytest.mark.parametrize("fb", [(68, 24, 4, 68, 1), (16, 4, 4, 1), (6, 2, 40, 8), (200, 8, 100, 3)])
+def test_rows_gathered_whole(fb, shift):
+    """Gathers of several fields that read each sampled row once and write every field's dense rows from a copy
+    of the rows in LDS: dense arrays on 16-byte, 4-byte and odd boundaries, batches with a ragged last pass and
+    shorter than one pass, a field left out, an index out of range, the stand-alone gather and the fused calls;
+    every byte compared with the oracle's rows, and the form with one job per field run beside it."""
+    log(f"whole rows fb={fb} shift={shift}")
+    rng = np.random.default_rng(sum(fb) * 7 + shift)
+    K, N, T = 16, 20000, 3
+    gpu = PrioritizedReplay(K, N, T, fb)
+    cpu = MultiOracle(T, K, N, fb, 1.0)
+
+    def shifted(n_bytes, b):   # n_bytes of field size b, as far into an allocation as the field's alignment allows
+        align = 16
+        while b % align:
+            align //= 2
+        sh = shift - shift % align
+        return torch.empty(n_bytes + sh, dtype=torch.uint8, device="cuda")[sh:]
+
+    rows = [rng.integers(0, 256, (T, N, b), dtype=np.uint8) for b in fb]
+    prio = (rng.random((T, N)) + 0.1).astype(np.float32)
+    gpu.insert(N, [dev(r) for r in rows], dev(prio))
+    cpu.insert(N, rows, prio)
+
+    def check(idx, leave_out=None):
+        B = idx.shape[1]
+        want = cpu.gather(idx)
+        for mode in (2, 0):
+            gpu.set_tuning("whole_rows", mode)
+            out = [None if f == leave_out else shifted(T * B * b, b) for f, b in enumerate(fb)]
+            for o in out:
+                if o is not None:
+                    o.fill_(0xEE)
+            gpu.gather(idx_to_dev(idx), out)
+            for f, b in enumerate(fb):
+                if out[f] is not None:
+                    assert np.array_equal(out[f].cpu().numpy().reshape(T, B, b), want[f]), f"mode {mode} field {f}"
+
+    check(rng.integers(0, N, (T, 5000)).astype(np.uint32))
+    check(rng.integers(0, N, (T, 1001)).astype(np.uint32), leave_out=0)
+    check(rng.integers(0, N, (T, 5)).astype(np.uint32), leave_out=len(fb) - 1)
+    bad = rng.integers(0, N, (T, 70)).astype(np.uint32)
+    bad[:, 5] = N + 1
+    bad[1, 69] = 0xFFFFFFFF
+    check(bad)
+    assert gpu.status() != 0
+    gpu.clear_status()
+    gpu.set_tuning("whole_rows", 2)
+    # fused: sampling + gather, then a whole step (sampling, gather and the update of the sampled batch)
+    B = 3001
+    u = wl.uniform01(rng, (T, B))
+    out = [shifted(T * B * b, b) for b in fb]
+    gi, _, _ = gpu.sample(dev(u), 0.4, rows_out=out)
+    ci, _, _ = cpu.sample(u, 0.4, True)
+    assert np.array_equal(idx_to_host(gi), ci)
+    want = cpu.gather(ci)
+    for f, b in enumerate(fb):
+        assert np.array_equal(out[f].cpu().numpy().reshape(T, B, b), want[f]), f"fused field {f}"
+    u = wl.uniform01(rng, (T, B))
+    newp = (rng.random((T, B)) + 0.05).astype(np.float32)
+    out = [shifted(T * B * b, b) for b in fb]
+    gi, _, _ = gpu.step(dev(u), 0.4, dev(newp), None, rows_out=out)
+    ci, _, _ = cpu.sample(u, 0.4, True)
+    assert np.array_equal(idx_to_host(gi), ci)
+    want = cpu.gather(ci)
+    cpu.update(ci, newp)
+    for f, b in enumerate(fb):
+        assert np.array_equal(out[f].cpu().numpy().reshape(T, B, b), want[f]), f"step field {f}"
+    u = wl.uniform01(rng, (T, 64))
+    gi, _, _ = gpu.sample(dev(u), 0.4)
+    ci, _, _ = cpu.sample(u, 0.4, True)
+    assert np.array_equal(idx_to_host(gi), ci)
