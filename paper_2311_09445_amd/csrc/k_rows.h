@@ -239,23 +239,28 @@ __device__ __forceinline__ void whole_where(uint32_t lane, uint32_t block, uint3
                                             const uint32_t* __restrict__ idx, Regs<uint32_t, kWholePieces>& at,
                                             Regs<uint32_t, kWholePieces>& piece) {
   if constexpr (K < kWholePieces) {
-    const uint32_t i = lane + (uint32_t)K * block;
-    const uint32_t r = i < items ? i / P : 0u;
-    reg<K>(piece) = i < items ? i - r * P : 0u;
-    reg<K>(at) = idx[r];
-    whole_where<K + 1>(lane, block, items, P, idx, at, piece);
+    if ((uint32_t)K * block < items) {   // (the same for all lanes: sweeps beyond the pass's pieces are skipped whole)
+      const uint32_t i = lane + (uint32_t)K * block;
+      const uint32_t r = i < items ? i / P : 0u;
+      reg<K>(piece) = i < items ? i - r * P : 0u;
+      reg<K>(at) = idx[r];
+      whole_where<K + 1>(lane, block, items, P, idx, at, piece);
+    }
   }
 }
 template <int K>
-__device__ __forceinline__ void whole_load(const uint8_t* base, uint32_t RS, uint32_t N, Regs<uint32_t, kWholePieces>& at,
-                                           Regs<uint32_t, kWholePieces>& piece, Regs<uint4, kWholePieces>& v, bool& bad) {
+__device__ __forceinline__ void whole_load(uint32_t block, uint32_t items, const uint8_t* base, uint32_t RS, uint32_t N,
+                                           Regs<uint32_t, kWholePieces>& at, Regs<uint32_t, kWholePieces>& piece,
+                                           Regs<uint4, kWholePieces>& v, bool& bad) {
   if constexpr (K < kWholePieces) {
-    const bool ok = reg<K>(at) < N;
-    bad |= !ok;
-    uint4 got = *reinterpret_cast<const uint4*>(base + (uint64_t)(ok ? reg<K>(at) : 0u) * RS + 16u * reg<K>(piece));
-    if (!ok) got = make_uint4(0, 0, 0, 0);
-    reg<K>(v) = got;
-    whole_load<K + 1>(base, RS, N, at, piece, v, bad);
+    if ((uint32_t)K * block < items) {
+      const bool ok = reg<K>(at) < N;
+      bad |= !ok;
+      uint4 got = *reinterpret_cast<const uint4*>(base + (uint64_t)(ok ? reg<K>(at) : 0u) * RS + 16u * reg<K>(piece));
+      if (!ok) got = make_uint4(0, 0, 0, 0);
+      reg<K>(v) = got;
+      whole_load<K + 1>(block, items, base, RS, N, at, piece, v, bad);
+    }
   }
 }
 template <int K>
@@ -263,8 +268,10 @@ __device__ __forceinline__ void whole_park(uint32_t lane, uint32_t block, uint32
                                            Regs<uint4, kWholePieces>& v) {
   if constexpr (K < kWholePieces) {
     const uint32_t i = lane + (uint32_t)K * block;
-    if (i < items) stage[i] = reg<K>(v);
-    whole_park<K + 1>(lane, block, items, stage, v);
+    if (i < items) {
+      stage[i] = reg<K>(v);
+      whole_park<K + 1>(lane, block, items, stage, v);   // (a lane without piece K has none beyond it)
+    }
   }
 }
 __device__ __forceinline__ void move_whole_rows(const FieldTable& ft, const JobRanges& jr, uint32_t t, uint32_t B,
@@ -285,7 +292,7 @@ __device__ __forceinline__ void move_whole_rows(const FieldTable& ft, const JobR
       Regs<uint32_t, kWholePieces> at, piece;
       Regs<uint4, kWholePieces> v;
       whole_where<0>(lane, block, items, P, idx + r0, at, piece);
-      whole_load<0>(base, ft.row_stride, N, at, piece, v, bad);
+      whole_load<0>(block, items, base, ft.row_stride, N, at, piece, v, bad);
       whole_park<0>(lane, block, items, reinterpret_cast<uint4*>(stage), v);
     }
     __syncthreads();
