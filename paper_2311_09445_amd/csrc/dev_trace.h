@@ -24,15 +24,26 @@ __device__ unsigned long long g_trace[kTraceBlocks * kTraceMarks];
 // Kernels flush under tag 0, or under a tag of their own; only the selected tag's flushes are kept.
 __device__ int g_trace_tag = 0;
 #define PER_FLUSH() PER_FLUSH_TAG(0)
+// Which workgroups are kept: those of tree 0 (g_trace_every == 0), or every g_trace_every-th of the whole grid,
+// numbered tree after tree.
+__device__ unsigned g_trace_every = 0;
 #define PER_FLUSH_TAG(tag)                                                                     \
   do {                                                                                         \
-    if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < kTraceBlocks && g_trace_tag == (tag)) { \
+    const unsigned every_ = g_trace_every;                                                     \
+    const unsigned long long lin_ = (unsigned long long)blockIdx.y * gridDim.x + blockIdx.x;   \
+    const bool keep_ = every_ ? lin_ % every_ == 0 && lin_ / every_ < kTraceBlocks             \
+                              : blockIdx.y == 0 && blockIdx.x < kTraceBlocks;                  \
+    if (threadIdx.x == 0 && keep_ && g_trace_tag == (tag)) {                                   \
+      const unsigned slot_ = every_ ? (unsigned)(lin_ / every_) : blockIdx.x;                  \
       _Pragma("unroll") for (int k_ = 0; k_ < kTraceMarks; ++k_)                               \
-        g_trace[blockIdx.x * kTraceMarks + k_] = tm_[k_];                                      \
+        g_trace[slot_ * kTraceMarks + k_] = tm_[k_];                                           \
     }                                                                                          \
   } while (0)
 extern "C" int per_trace_select(int tag) {
   return hipMemcpyToSymbol(HIP_SYMBOL(g_trace_tag), &tag, sizeof(tag)) == hipSuccess ? 0 : -1;
+}
+extern "C" int per_trace_every(unsigned every) {
+  return hipMemcpyToSymbol(HIP_SYMBOL(g_trace_every), &every, sizeof(every)) == hipSuccess ? 0 : -1;
 }
 extern "C" int per_trace_read(unsigned long long* host, int clear) {
   if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(g_trace)) != hipSuccess) return -1;
