@@ -469,8 +469,8 @@ __device__ __forceinline__ void ride_rows(const InsertRide& ride, uint32_t t, ui
 // Second kernel of the fused calls.  Its workgroups (blockIdx.x) split into jobs, each with as many
 // workgroups as it needs (JobRanges): first the importance weights of the batch just sampled (if
 // asked for), then the claim phase of a priority update (if one is fused in), then one job per
-// payload field of the sampled rows.  The small jobs come first, so their latency hides behind the
-// row traffic.
+// payload field of the sampled rows, or a single job over whole rows (move_whole_rows) in the first
+// asked-for field's range.  The small jobs come first, so their latency hides behind the row traffic.
 template <bool WIDE>
 __global__ void k_finish(FieldTable ft, JobRanges jr, Geom g, FinishArgs a) {
   const uint32_t t = blockIdx.y;
@@ -491,7 +491,7 @@ __global__ void k_finish(FieldTable ft, JobRanges jr, Geom g, FinishArgs a) {
     rows_job<true, WIDE>(ft, f, t, a.B, a.idx, 0, g.N, g.status, b - jr.first[2 + f], jr.first[3 + f] - jr.first[2 + f]);
 }
 
-// Stand-alone gather (GATHER) and insert scatter: one job per payload field.
+// Stand-alone gather (GATHER) and insert scatter: one job per payload field (gathers: or one over whole rows).
 template <bool GATHER, bool WIDE>
 __global__ void k_rows(FieldTable ft, JobRanges jr, uint32_t B, const uint32_t* __restrict__ idx, uint32_t cursor,
                        uint32_t N, uint32_t* status) {
