@@ -385,6 +385,14 @@ uint64_t per_rng_calls(const per_t* p);
  *                  wait of all its workgroups for each other) where all of them fit the GPU at once; 0 (default): a second
  *                  kernel does that, which was measured faster
  *   "insert_ride" : 1 (default) lets the sampling kernel of per_insert_step carry the insertion; 0: two calls
+ *   "static_tables" : the per-owner tables of the one-kernel step live in the arena, or, for ONE buffer per GPU at a
+ *                  time, in an array of the library's own at an address its kernels know without their arguments
+ *                  (an owner then fetches its entry while the arguments are still on their way: about half a
+ *                  microsecond per step).  per_create takes the array for a buffer with a single tree when nobody
+ *                  holds it (per_destroy gives it back; when it changes hands the GPU is drained first, so that work
+ *                  of the previous holder cannot meet the new one's).  0: give it back; 1: take it if it is free
+ *                  (PER_ERANGE if another buffer holds it or the buffer has several trees).  Not while a stream is
+ *                  being captured; graphs captured before the switch must not be replayed after it
  *   "whole_rows" : how a gather of two or more fields reads the stored rows.  0: one job per field; 1 (default):
  *                  from 16384 rows per call (all trees together), and where the asked-for fields lie within 512
  *                  bytes of a row, every sampled row is read once, as a whole, and each field's dense rows are

@@ -238,7 +238,63 @@ __device__ __forceinline__ uint32_t chunk_groups(const ChunkLds& c, uint32_t slo
 // smallest sampled values, the counters) are written and read with device-scope atomic accesses, which go past
 // the caches, and a workgroup announces itself only after they have completed.  All waits are bounded; the host
 // launches this form only when all workgroups of the grid fit the GPU at once (a waiting workgroup holds its place).
-template <int LOGK, bool TAIL>
+// The tables of one buffer per GPU (the first with a single tree that asks) sit in this array instead of its arena:
+// a kernel knows the array's address without its arguments, so an owner of k_step<.., .., true> fetches its entry
+// while the arguments are still on their way, and the trip that needs both (the window of samples) starts a trip
+// earlier.  That form has a fixed number of workgroups in front of the owners (kStepFront; those that are no
+// builders return at once), because the owner's number must not depend on an argument either.
+// (The host never names the array: a variable that host code refers to is reached through an address table in
+// memory, one more trip; its address is reported by a kernel instead.)
+static __device__ __align__(256) StepTable g_step_tab_static[kStepMaxOwners];
+constexpr uint32_t kStepFront = 64;
+__global__ void k_step_static_address(void** out) { *out = g_step_tab_static; }
+// Who holds the array on each GPU.  A buffer that held it before may still have work in flight that reads or writes
+// it, so a GPU whose array changes hands is drained first.
+namespace {
+struct StaticTables {
+  std::mutex mu;
+  const void* holder[kMaxDevices] = {};
+  bool used[kMaxDevices] = {};
+  void* addr[kMaxDevices] = {};
+};
+StaticTables& static_tables() {
+  static StaticTables st;
+  return st;
+}
+}  // namespace
+// Gives `holder` the array of `device` (which must be the current one) if nobody holds it: its address, else null.
+// `s`: a stream of the caller's that is not being captured (the address is asked for on it, once per GPU).
+void* step_static_claim(const void* holder, int device, hipStream_t s) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  int current = -1;
+  if (hipGetDevice(&current) != hipSuccess || current != device) return nullptr;
+  StaticTables& st = static_tables();
+  std::lock_guard<std::mutex> lock(st.mu);
+  if (st.holder[device]) return st.holder[device] == holder ? st.addr[device] : nullptr;
+  if (!st.addr[device]) {   // asked once per GPU: a kernel writes the address into pinned host memory
+    void** slot = nullptr;
+    if (hipHostMalloc(reinterpret_cast<void**>(&slot), sizeof(void*), hipHostMallocDefault) != hipSuccess) return nullptr;
+    *slot = nullptr;
+    hipLaunchKernelGGL(k_step_static_address, dim3(1), dim3(1), 0, s, slot);
+    const bool ok = hipGetLastError() == hipSuccess && hipStreamSynchronize(s) == hipSuccess;
+    void* got = ok ? *slot : nullptr;
+    (void)hipHostFree(slot);
+    if (!got) return nullptr;
+    st.addr[device] = got;
+  }
+  if (st.used[device] && hipDeviceSynchronize() != hipSuccess) return nullptr;
+  st.holder[device] = holder;
+  st.used[device] = true;
+  return st.addr[device];
+}
+void step_static_release(const void* holder, int device) {
+  if (device < 0 || device >= kMaxDevices) return;
+  StaticTables& st = static_tables();
+  std::lock_guard<std::mutex> lock(st.mu);
+  if (st.holder[device] == holder) st.holder[device] = nullptr;
+}
+
+template <int LOGK, bool TAIL, bool STATIC = false>
 __global__ void __launch_bounds__(512)
 k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t weight_mode, const float* __restrict__ u,
        RngArgs rng, uint32_t* out_idx, float* __restrict__ out_prio, float* out_w,
@@ -247,8 +303,24 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   constexpr int LPS = Fan<LOGK>::LPS;
   constexpr int ROW = K + 4;
   static_assert(LOGK >= 3, "the staged walk needs K >= 8");
-  touch_kernel_arguments<kernarg_lines<Geom, StepShape, uint32_t, uint32_t, float, uint32_t, const float*, RngArgs, uint32_t*,
-                                       float*, float*, const float*, const uint32_t*>()>();
+  static_assert(!(TAIL && STATIC), "the form that ends inside the kernel has its own helpers in front");
+  // STATIC: this owner's table entry, asked for before anything that needs an argument (one tree only)
+  [[maybe_unused]] float pre_total = 0.0f;
+  [[maybe_unused]] double pre_mass = 0.0;
+  [[maybe_unused]] float2 pre_path = make_float2(0.0f, 0.0f);
+  if constexpr (STATIC) {
+    uint32_t zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));   // (a lane offset the compiler cannot see through: vector loads, issued here)
+    const StepTable* early = g_step_tab_static + (blockIdx.x >= kStepFront ? blockIdx.x - kStepFront : 0u) + zero;
+    pre_total = early->total;
+    pre_mass = early->mass;
+    pre_path = early->path[threadIdx.x < (uint32_t)kStepPathMax ? threadIdx.x : (uint32_t)kStepPathMax - 1u];   // (no branch: every lane loads)
+    asm volatile("" ::: "memory");   // (the loads stay in front of this line, and so in front of everything that waits for an argument)
+  }
+  constexpr int kArgLines = kernarg_lines<Geom, StepShape, uint32_t, uint32_t, float, uint32_t, const float*, RngArgs, uint32_t*,
+                                         float*, float*, const float*, const uint32_t*>();
+  if constexpr (STATIC) touch_kernel_arguments_through_one_register<kArgLines>();
+  else touch_kernel_arguments<kArgLines>();
   extern __shared__ __attribute__((aligned(16))) float lds[];
   __shared__ uint32_t s_u32[8];
   const uint32_t t = blockIdx.y;
@@ -289,7 +361,9 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   };
 
   // ------------------------------------------------------------------ helper workgroups: builders (position map only), table builders (TAIL)
-  if (blockIdx.x < (TAIL ? sh.helpers : sh.builders)) {
+  const uint32_t front = STATIC ? kStepFront : (TAIL ? sh.helpers : sh.builders);   // workgroups in front of the owners
+  if (blockIdx.x < front) {
+    if (STATIC && blockIdx.x >= sh.builders) return;   // (there to keep the owners' numbers fixed)
     // The number of finished calls.  Without TAIL: the owners of this call cannot finish before every builder has, so
     // the count of group 0 is still that of the calls before.  With TAIL the owners' counters may already have moved
     // when a helper starts late, so the word that ends a call is read instead: it cannot move before every helper
@@ -336,7 +410,7 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   }
 
   // ------------------------------------------------------------------ owner workgroup b
-  const uint32_t b = blockIdx.x - (TAIL ? sh.helpers : sh.builders);
+  const uint32_t b = blockIdx.x - front;
   const uint32_t my_group = b % kStepGroups;
   float* sub = lds;                                   // heights 1 .. ho-1 of the own subtree, at sub_off[i]
   // per binary step from the root to b: the sum of the left block; bit 0: b lies to the right, bit 1: the right block is not zero
@@ -362,9 +436,31 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   }
   const uint32_t max_seen = read_max_bits(g, t);
   const StepTable* mine = tab + b;
-  const float total = mine->total;
-  const double mass = mine->mass;
-  if (tid < n_steps) path[tid] = mine->path[tid];
+  float total;
+  double mass;
+  // where this workgroup's run of samples starts, to within a few: the mass in front of node b over seg
+  auto window_start = [&](double m) -> uint32_t {
+    const double est = m * (double)B;   // (the division is done where the table is built: it would stand in front of this workgroup's second trip)
+    const uint32_t s_guess = est >= (double)B ? B : (est > 0.0 ? (uint32_t)est : 0u);   // (not a number: 0)
+    return s_guess > kStepPad ? s_guess - kStepPad : 0u;
+  };
+  [[maybe_unused]] float early_u = 0.0f, early_prio = 0.0f;
+  if constexpr (STATIC) {
+    total = pre_total;
+    mass = pre_mass;
+    if (tid < n_steps) path[tid] = pre_path;
+    // the window's inputs are asked for here, together with the subtree's heights: the entry that says where the
+    // window lies came in beside the arguments
+    const uint32_t sw = window_start(mass) + tid;
+    if (sw < B) {
+      early_u = rng.on ? 0.0f : u[(size_t)t * B + sw];
+      early_prio = upd_prio[(size_t)t * B + sw];
+    }
+  } else {
+    total = mine->total;
+    mass = mine->mass;
+    if (tid < n_steps) path[tid] = mine->path[tid];
+  }
 #pragma unroll
   for (int i = 0; i < kStepSub; ++i) {
     if (i < n_sub) {
@@ -535,20 +631,20 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     return lo;
   };
 
-  // where this workgroup's run of samples starts, to within a few: the mass in front of node b over seg
-  uint32_t s0;
-  {
-    const double est = mass * (double)B;   // (the division is done where the table is built: it would stand in front of this workgroup's second trip)
-    const uint32_t s_guess = est >= (double)B ? B : (est > 0.0 ? (uint32_t)est : 0u);   // (not a number: 0)
-    s0 = s_guess > kStepPad ? s_guess - kStepPad : 0u;
-  }
+  const uint32_t s0 = window_start(mass);
   PER_MARK(3);
 
   // ---- trip 2: the samples of the window [s0, s0 + BD): uniforms, their own new priorities
   uint32_t s = s0 + tid;
   const bool in = s < B;
-  float u_s = in ? uniform_of(s) : 0.0f;
-  float prio_s = in ? upd_prio[(size_t)t * B + s] : 0.0f;
+  float u_s, prio_s;
+  if constexpr (STATIC) {
+    u_s = in ? (rng.on ? uniform_of(s) : early_u) : 0.0f;
+    prio_s = in ? early_prio : 0.0f;
+  } else {
+    u_s = in ? uniform_of(s) : 0.0f;
+    prio_s = in ? upd_prio[(size_t)t * B + s] : 0.0f;
+  }
   float r = ((float)s + u_s) * seg, val = total;
   const uint32_t where = in ? landing(r) : 2u;
   // does the window hold the whole run?  its first sample must land in front of b (or be sample 0), and a sample
@@ -1113,9 +1209,16 @@ static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block,
                weight_mode, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, tl);
     return hipGetLastError();
   }
-  const dim3 grid(sh.builders + sh.owners, g.T);
-  PER_LAUNCH(KID_STEP, (k_step<LOGK, false>), grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx,
-             out_prio, out_w, upd_prio, upd_pos, NoTail{});
+  if (g.step_tab_static && g.T == 1) {   // (the tables sit in the static array: owners fetch their entry beside the arguments)
+    e = grant_lds<&k_step<LOGK, false, true>>(tn, bytes);
+    if (e != hipSuccess) return e;
+    PER_LAUNCH(KID_STEP, (k_step<LOGK, false, true>), dim3(kStepFront + sh.owners, 1), dim3(block), bytes, s, g, sh, B, size, beta,
+               weight_mode, u, rng, out_idx, out_prio, out_w, upd_prio, upd_pos, NoTail{});
+  } else {
+    const dim3 grid(sh.builders + sh.owners, g.T);
+    PER_LAUNCH(KID_STEP, (k_step<LOGK, false>), grid, dim3(block), bytes, s, g, sh, B, size, beta, weight_mode, u, rng, out_idx,
+               out_prio, out_w, upd_prio, upd_pos, NoTail{});
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const JobRanges jr = job_ranges(rows ? &ft : nullptr, B, 256, out_w ? B : 0u, 0u, g.T);

@@ -29,6 +29,7 @@ struct per_buffer {
   bool rng_on;               // per_set_rng was called: sampling calls without uniforms draw their own
   uint64_t rng_seed, rng_calls;   // key of the generator; number of sampling calls that drew from it
   int device;
+  uint8_t* arena_tab;        // where the arena keeps the tables of the one-kernel step (they may sit in the kernels' static array instead)
   uint32_t* static_scratch;   // this device's copy of the static array of per_min_priority_static (null: its address could not be had)
   Profiler prof;
 };
@@ -219,6 +220,28 @@ struct CaptureGuard {
   }
 };
 
+// The tables of the one-kernel step in the kernels' static array (one buffer per GPU, single tree; see k_step): taken
+// if free, never while `s` is being captured (changing hands may drain the device).
+bool take_static_tables(per_t* p, hipStream_t s) {
+  if (p->g.step_tab_static) return true;
+  if (p->g.T != 1 || !p->g.step_ho) return false;
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess || st != hipStreamCaptureStatusNone) return false;
+  void* addr = step_static_claim(p, p->device, s);
+  if (!addr) return false;
+  p->g.step_tab = addr;
+  p->g.step_tab_static = 1;
+  p->tables_valid = false;
+  return true;
+}
+void leave_static_tables(per_t* p) {
+  if (!p->g.step_tab_static) return;
+  step_static_release(p, p->device);
+  p->g.step_tab = p->arena_tab;
+  p->g.step_tab_static = 0;
+  p->tables_valid = false;
+}
+
 }  // namespace
 
 extern "C" {
@@ -285,7 +308,9 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   g.vmin_buf = g.vmin + (size_t)2 * kVminSlots * g.T;
   g.step_side = reinterpret_cast<float*>(p->arena + L.side_off);
   g.step_side_stride = kStepSideStride;
-  g.step_tab = p->arena + L.tab_off;
+  p->arena_tab = p->arena + L.tab_off;
+  g.step_tab = p->arena_tab;
+  g.step_tab_static = 0;
   g.step_ho = step_owner_height(g);
   g.min1 = reinterpret_cast<uint32_t*>(p->arena + L.min1_off);
   g.min1_stride = L.min1_stride;
@@ -323,12 +348,14 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   hipError_t e = launch_fill_u32(p->tn, reinterpret_cast<uint32_t*>(p->arena), L.total / 4, 0u, s);
   if (e == hipSuccess) e = launch_init_scalars(g, cfg->init_max_priority, s);
   if (e != hipSuccess) { delete p; return PER_EHIP; }
+  (void)take_static_tables(p, s);
   *out = p;
   return PER_OK;
 }
 
 int per_destroy(per_t* p) {
   if (!p) return PER_EINVAL;
+  leave_static_tables(p);
   p->prof.reset();
   delete p;
   return PER_OK;
@@ -957,6 +984,14 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
     if (value != 0 && value != 1) return PER_EINVAL;
     p->tn.step_tail = (uint32_t)value;
     return PER_OK;
+  }
+  if (!strcmp(name, "static_tables")) {
+    if (value != 0 && value != 1) return PER_EINVAL;
+    if (value == 0) {
+      leave_static_tables(p);
+      return PER_OK;
+    }
+    return take_static_tables(p, nullptr) ? PER_OK : PER_ERANGE;
   }
   if (!strcmp(name, "whole_rows")) {
     if (value < 0 || value > 2) return PER_EINVAL;

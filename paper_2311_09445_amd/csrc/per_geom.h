@@ -54,6 +54,7 @@ struct Geom {
   uint32_t step_ho;                 // owner height of the one-kernel step (0: that kernel does not fit this tree)
   float*   step_side;               // [T][step_side_stride] where its owners leave the new nodes of height step_ho
   void*    step_tab;                // its per-owner tables
+  uint32_t step_tab_static;         // 1: they sit in the kernels' static array (see k_step), not in the arena
   uint32_t step_side_stride;
   unsigned long long* step_cnt;     // [T][kStepGroups] owners of the one-kernel step that have finished, over all calls
   uint32_t* step_done;              // [T][2][kStepDoneSlots] its builders that have finished (by parity of the call)
@@ -278,6 +279,10 @@ hipError_t launch_step(const Geom& g, const Tuning& tn, uint32_t block, bool tab
                        uint32_t weight_mode, const FieldTable* rows, const float* upd_prio, const uint32_t* upd_pos,
                        hipStream_t s);
 size_t step_table_bytes();
+// The static array that holds one buffer's tables per GPU (see k_step): taken for `holder` if free (null otherwise,
+// or when `device` is not the current one), and given back.
+void* step_static_claim(const void* holder, int device, hipStream_t s);
+void step_static_release(const void* holder, int device);
 uint32_t stream_tree_floats(const Geom& g, uint32_t* off, uint32_t* leaves_in_memory = nullptr);
 hipError_t launch_run_steps(const Geom& g, const Tuning& tn, const StreamArgs& a, hipStream_t s);
 hipError_t launch_run_requests(const Geom& g, const Tuning& tn, const QueueArgs& a, hipStream_t s);

@@ -13,6 +13,7 @@
 #include <hip/hip_ext.h>
 
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 namespace per {

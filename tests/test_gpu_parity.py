@@ -1,6 +1,7 @@
 """Parity of the HIP path (through the C-ABI) with the CPU oracle, element by element."""
 import os
 
+import gc
 import numpy as np
 import pytest
 
@@ -796,17 +797,26 @@ def test_captured_step_replays(K, N, B):
 @pytest.mark.parametrize("K,N,T,B,fb", [(32, 1 << 20, 1, 30000, (128,)), (16, 1 << 18, 3, 1024, (68, 24, 4, 68, 1)),
                                         (2, 5000, 1, 64, ()), (4, 70001, 2, 3000, (12,)), (64, 300001, 1, 5000, (8,)),
                                         (8, 1 << 21, 1, 9000, ())])
-@pytest.mark.parametrize("one_kernel", [2, 3, 0])
+@pytest.mark.parametrize("one_kernel", [2, 3, 4, 0])
 def test_step_call_updates_the_batch_it_draws(K, N, T, B, fb, one_kernel):
     """per_step: the update targets the leaves drawn by this very call, directly or through a position map
     (the duplicate map of the stress workload; maps with many elements on one sample; invalid positions).
     Run with sampling and update as one kernel where the tree takes it (the call ending inside that kernel, or,
-    one_kernel = 3, in a second one) and as separate kernels."""
+    one_kernel = 3 and 4, in a second one: 3 with the owners' tables in the arena, 4 with the tables in the
+    library's static array, which a buffer with one tree gets when it is free) and as separate kernels."""
     log(f"per_step K={K} N={N} T={T} B={B} one_kernel={one_kernel}")
     rng = np.random.default_rng(K * 31 + B)
     m = Mirror(K, N, T, fb)
     m.gpu.set_tuning("step_kernel", min(one_kernel, 2))
-    m.gpu.set_tuning("step_tail", 0 if one_kernel == 3 else 1)
+    m.gpu.set_tuning("step_tail", 0 if one_kernel >= 3 else 1)
+    m.gpu.set_tuning("static_tables", 0)
+    if one_kernel == 4:
+        gc.collect()
+        if T == 1 and K >= 8:                      # (trees that the one-kernel form takes)
+            m.gpu.set_tuning("static_tables", 1)   # (free: every other buffer of this process has been destroyed or has given it back)
+        else:
+            with pytest.raises(Exception):
+                m.gpu.set_tuning("static_tables", 1)
     prio = wl._draw_priorities("pareto_1.5", rng, (T, N))
     prio[rng.random((T, N)) < 0.01] = 0.0
     m.insert(N, prio=prio, chunk=1 << 18)
