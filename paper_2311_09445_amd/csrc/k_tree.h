@@ -473,7 +473,13 @@ static hipError_t tree_pass_shape(const Geom& g, const Tuning& tn, const ClaimAr
     // cost a trip to memory of its own (measured on one tree of 2^20 leaves at K = 16:
     // 14.1 -> 13.1 us per step of 32 samples, 14.1 -> 13.6 of 4096).
     const uint64_t one_sweep = per_subtree > 1024 ? 1024 : (per_subtree + 63) / 64 * 64;
-    if (one_sweep > tblock && (uint64_t)g.n[hb] * g.T * (one_sweep / 64) <= 2048) tblock = (uint32_t)one_sweep;
+    if (one_sweep > tblock && (uint64_t)g.n[hb] * g.T * (one_sweep / 64) <= 4096) tblock = (uint32_t)one_sweep;
+    // ... and no more waves than that over the whole launch for a large batch either: workgroups that wait for a
+    // second round cost more than the sweeps that smaller ones add (2^22 leaves at K = 16, 65 536 elements: 8.1 us
+    // with 512 lanes, 5.6 with 256).
+    const uint64_t groups = (uint64_t)g.n[hb] * g.T;
+    const uint64_t room = groups >= 4096 ? 1 : 4096 / groups;   // waves per workgroup
+    if (tblock > room * 64) tblock = (uint32_t)(room * 64);
   }
   *out = sl;
   *tblock_out = tblock;
