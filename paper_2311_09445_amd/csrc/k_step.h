@@ -1239,7 +1239,9 @@ static hipError_t launch_step_k(const Geom& g, const Tuning& tn, uint32_t block,
 // step; batches of 32 .. 4096, or 64 trees with an insert between the steps, are faster as separate kernels).
 uint32_t step_fits(const Geom& g, uint32_t B, bool always) {
   if (!g.step_ho || B == 0 || (uint64_t)B > 2ull * g.owner_stride) return 0;
-  if (!always && (g.T > 8 || (uint64_t)B < 64ull * g.n[g.step_ho])) return 0;
+  // (and for batches of 32768 and more over all trees: 16384 samples on 2^20 leaves at K = 16, 64 per owner, take
+  // 11.4 us as separate kernels and 13.4 in this form)
+  if (!always && (g.T > 8 || (uint64_t)B < 64ull * g.n[g.step_ho] || (uint64_t)B * g.T < 32768)) return 0;
   switch (g.logK) {
     case 3: return step_block<3>(g, g.step_ho, B);
     case 4: return step_block<4>(g, g.step_ho, B);
