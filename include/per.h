@@ -368,7 +368,9 @@ uint64_t per_rng_calls(const per_t* p);
 
 /* Performance knobs; results never depend on them.
  *   "lds_budget_bytes" : upper tree levels are staged in LDS while they fit this many bytes
- *   "sample_block", "update_block", "gather_block" : workgroup sizes (multiples of 64, <= 1024)
+ *   "sample_block", "update_block", "gather_block" : workgroup sizes (multiples of 64, <= 1024).  Until "sample_block"
+ *                  is set, a sampling launch that carries an insertion on 8 or more trees takes 512 lanes instead of
+ *                  the default 128
  *   "tree_block" : workgroup size of the update's tree pass (multiple of 64, <= 1024; 0 = chosen per launch)
  *   "sample_min_lds" : lower bound in bytes of the sampling kernel's LDS request
  *   "group_stamp_next" : moves the device-side stamp counter of the claim group entries (1 .. 2^25; enqueued on

@@ -332,6 +332,7 @@ int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* s
   p->tn.step_tail = 0;   // (measured slower than the second kernel: see k_step)
   p->tn.insert_ride = 1;
   p->tn.whole_rows = 1;
+  p->tn.sample_block_auto = 1;
   p->tn.sample_min_lds = 0;
   p->tn.prof = &p->prof;
   p->claims_left = false;
@@ -1021,6 +1022,7 @@ int per_set_tuning(per_t* p, const char* name, int64_t value) {
   if (blk == &p->tn.tree_block && value == 0) { *blk = 0; return PER_OK; }
   if (value < 64 || value > 1024 || value % 64) return PER_EINVAL;
   *blk = (uint32_t)value;
+  if (blk == &p->tn.sample_block) p->tn.sample_block_auto = 0;
   return PER_OK;
 }
 

@@ -236,6 +236,7 @@ struct Tuning {
   uint32_t claim_in_sample;   // fused steps may run the claim phase in the sampling kernel (two kernels per step)
   uint32_t group_claim;       // update batches claim through the group entries whenever they are short enough
   uint32_t insert_ride;       // per_insert_step lets its sampling kernel carry the insertion where that is possible
+  uint32_t sample_block_auto; // sample_block is the default, not a size that was asked for
   uint32_t whole_rows;        // gathers of several fields move whole rows through LDS where the rows are short enough
   uint32_t step_tail;         // the one-kernel step also ends inside that kernel (rows, weights, tables) where all its workgroups fit the GPU at once
   uint32_t step_kernel;       // per_step runs sampling and update as one kernel: 0 never, 1 where it fits and pays off, 2 wherever it fits
