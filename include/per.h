@@ -82,7 +82,10 @@ int per_arena_bytes(const per_config* cfg, size_t* bytes, size_t* align);
 
 /* Lays the tree levels, payload columns and scratch out in `d_arena` (device memory,
  * at least per_arena_bytes large and aligned), zero-fills tree and scratch on `stream`
- * and returns a host handle.  The arena stays the caller's; it must outlive the handle. */
+ * and returns a host handle.  The arena stays the caller's; it must outlive the handle.
+ * Not for use while a stream is being captured.  A buffer with one tree may be given the library's static table
+ * array (tuning "static_tables" below): the first time on a GPU that costs a small kernel and a wait for `stream`,
+ * and when the array was held by another buffer before, a wait for the whole GPU. */
 int per_create(const per_config* cfg, void* d_arena, size_t arena_bytes, void* stream, per_t** out);
 
 /* Frees the host handle only. */
