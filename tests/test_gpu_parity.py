@@ -843,6 +843,39 @@ def test_step_call_updates_the_batch_it_draws(K, N, T, B, fb, one_kernel):
     m.compare_status()
 
 
+def test_static_tables_change_hands():
+    """Two buffers with one tree each, stepped in turn: the library's static table array belongs to one of them at
+    a time; it is taken, refused while the other holds it, given back and taken over, and every step of both
+    buffers matches the oracle whichever of them holds it."""
+    log("static tables change hands")
+    gc.collect()
+    rng = np.random.default_rng(77)
+    K, N, B = 16, 1 << 18, 40000
+    a = Mirror(K, N, 1, (8,))
+    b = Mirror(K, N, 1, (8,))
+    for m in (a, b):
+        m.gpu.set_tuning("step_kernel", 2)
+        m.insert(N, prio=wl._draw_priorities("pareto_1.5", rng, (1, N)), chunk=1 << 18)
+
+    def steps(m, n=2):
+        for _ in range(n):
+            m.step_call(wl.uniform01(rng, (1, B)), 0.5, True, wl._draw_updates("absnormal1_eps_pow0.6", rng, (1, B)))
+        m.compare_tree()
+
+    a.gpu.set_tuning("static_tables", 1)            # a holds it (it did already if nobody else did when it was created)
+    with pytest.raises(Exception):
+        b.gpu.set_tuning("static_tables", 1)        # refused: held
+    steps(a); steps(b); steps(a)
+    a.gpu.set_tuning("static_tables", 0)            # given back: a goes on with the tables in its arena
+    b.gpu.set_tuning("static_tables", 1)
+    steps(b); steps(a); steps(b)
+    del b, m                                        # destroyed while holding it (m: the loop variable above)
+    gc.collect()
+    a.gpu.set_tuning("static_tables", 1)
+    steps(a)
+    a.compare_status()
+
+
 def kernel_launches(m):
     """{kernel name: launches} since profiling was switched on."""
     return {k: int(v[1]) for k, v in m.gpu.profile_read().items() if v[1]}
