@@ -245,10 +245,35 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
         __syncthreads();
       };
       const uint32_t hp = ride.hp;
-      sum_height(a1, c1, o1, t1, hp > 1, a2, o2);
-      if (hp > 1) sum_height(a2, c2, o2, t2, hp > 2, a3, o3);
-      if (hp > 2) sum_height(a3, c3, o3, t3, hp > 3, a4, o4);
-      if (hp > 3) sum_height(a4, c4, o4, t4, false, 0, 0);
+      // One touched node per height (the rows lie under one height-1 node: the usual case of a few rows): one lane
+      // group works its way up by itself, each sum patched into the staged group of the height above and read back
+      // by the same wave, with no workgroup barrier between the heights.
+      const bool chain = c1 == 1 && (hp < 2 || c2 == 1) && (hp < 3 || c3 == 1) && (hp < 4 || c4 == 1);
+      if (chain) {
+        if (threadIdx.x < (uint32_t)LPS) {
+          auto one = [&](uint32_t a, uint32_t o, uint32_t top, bool has_up, uint32_t up_a, uint32_t up_o) {
+            const float sum = group_sum<LOGK>(rl + o, q);
+            if (q == 0) {
+              if (is_mover) rl[ride.val_off + (o >> LOGK)] = sum;
+              if (has_up) rl[up_o + (a - up_a * K)] = sum;
+              if (top != kRideNone) lds[top + a] = sum;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          };
+          one(a1, o1, t1, hp > 1, a2, o2);
+          if (hp > 1) one(a2, o2, t2, hp > 2, a3, o3);
+          if (hp > 2) one(a3, o3, t3, hp > 3, a4, o4);
+          if (hp > 3) one(a4, o4, t4, false, 0, 0);
+        }
+        __syncthreads();
+      } else {
+        sum_height(a1, c1, o1, t1, hp > 1, a2, o2);
+        if (hp > 1) sum_height(a2, c2, o2, t2, hp > 2, a3, o3);
+        if (hp > 2) sum_height(a3, c3, o3, t3, hp > 3, a4, o4);
+        if (hp > 3) sum_height(a4, c4, o4, t4, false, 0, 0);
+      }
       if (is_mover) {   // the new leaves, the new sums of heights 1 .. hp, what the running maximum may rise to; the rows
         uint32_t mx = 0;
         bool bad = false;
