@@ -17,6 +17,15 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// A pointer that the compiler cannot trace to a kernel argument (one kept in LDS, put together from lane registers)
+// is accessed with flat instructions, which count as LDS traffic as well: the wave's next wait for LDS data then
+// waits for that trip to memory too.  Every such pointer of this library points to device memory; saying so gives
+// plain global accesses.
+template <typename T>
+using GlobalPtr = T __attribute__((address_space(1)))*;
+template <typename T>
+__device__ __forceinline__ GlobalPtr<T> as_global(T* p) { return (GlobalPtr<T>)p; }
+
 __device__ __forceinline__ bool valid_priority(float v) {
   return v >= 0.0f && v <= 3.402823466e38f;   // finite and >= 0 (false for NaN); -0.0f passes
 }

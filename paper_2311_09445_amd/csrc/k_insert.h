@@ -52,6 +52,7 @@ constexpr uint32_t kInsertSmallRows = 4096;   // most rows one workgroup takes
 struct InsertPlan {
   Range2 r[kInsertHeights];        // touched nodes of height h + 1
   uint32_t off[kInsertHeights];    // where their child groups start in LDS (floats)
+  uint32_t chain_from;             // from this height on one wave holds a lane group per touched node of every height
 };
 struct InsertArgs {                // one kernel argument, so that both parts sit at known offsets of the segment
   Geom g;
@@ -100,14 +101,20 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
   __syncthreads();
   PER_MARK(1);
   // ---- everything that is read: the child groups of all touched nodes, the running maximum
-  for (uint32_t h = 1; h <= H; ++h) {
-    const Range2 r = s_r[h - 1];
-    const uint32_t c0 = r.b0 - r.a0, cnt = c0 + (r.b1 - r.a1);
-    const float* child = tab.lvl[h - 1];
-    for (uint32_t e = threadIdx.x; e < cnt * K; e += blockDim.x) {
+  // (one flat index space over the staged floats of all heights, so that every lane's loads are on their way before
+  // anything waits: a loop per height made a trip to memory per height)
+  {
+    const Range2 top_r = s_r[H - 1];
+    const uint32_t total = s_off[H - 1] + ((top_r.b0 - top_r.a0) + (top_r.b1 - top_r.a1)) * K;
+    for (uint32_t e0 = threadIdx.x; e0 < total; e0 += blockDim.x) {
+      uint32_t hi = 0;   // the height below the staged group: the number of heights whose groups start at or before e0, less one
+      for (uint32_t k = 1; k < H; ++k) hi += e0 >= s_off[k] ? 1u : 0u;
+      const Range2 r = s_r[hi];
+      const uint32_t e = e0 - s_off[hi];
+      const uint32_t c0 = r.b0 - r.a0;
       const uint32_t pos = e >> LOGK;
       const uint32_t node = pos < c0 ? r.a0 + pos : r.a1 + (pos - c0);
-      staged[s_off[h - 1] + e] = child[(size_t)node * K + (e & (K - 1))];
+      staged[e0] = as_global(tab.lvl[hi])[(size_t)node * K + (e & (K - 1))];
     }
   }
   const float max_on_entry = prio ? 0.0f : g.max_v[t];
@@ -134,7 +141,7 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
       bad = bad || !ok;
     }
     if (ok) {
-      tab.lvl[0][slot] = v;
+      as_global(tab.lvl[0])[slot] = v;
       staged[s_off[0] + plan_pos(s_r[0], (uint32_t)(slot >> LOGK)) * K + ((uint32_t)slot & (K - 1))] = v;
     }
   }
@@ -145,9 +152,51 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
   __syncthreads();
   PER_MARK(3);
   // ---- heights 1 .. H from the staged groups
+  // From chain_from on the first wave finishes the heights alone: what it patches into the staged groups of the
+  // next height it reads back itself, so no workgroup barrier stands between those heights (a barrier and the loop
+  // around it cost three times the sum itself).
   const unsigned q = threadIdx.x % LPS;
   const uint32_t grp = threadIdx.x / LPS, ngrp = blockDim.x / LPS;
+  const uint32_t chain_from = kernarg_at<InsertPlan>(offsetof(InsertArgs, plan))->chain_from;
+  // (what the chained heights need to know of each height sits in the registers of lane h - 1 and is read from
+  // there: fetched from LDS per height, it stood in front of every sum)
+  const uint32_t ml = (threadIdx.x & 63u) < H ? (threadIdx.x & 63u) : 0u;
+  const Range2 mr = s_r[ml];
+  const uint32_t moff = s_off[ml];
+  const unsigned long long mlvl = reinterpret_cast<unsigned long long>(tab.lvl[ml + 1]);
+  auto lane_word = [](uint32_t v, uint32_t l) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)l); };
   for (uint32_t h = 1; h <= H; ++h) {
+    const bool chained = h >= chain_from;
+    if (chained && threadIdx.x >= 64) break;
+    if (chained) {
+      const uint32_t a0 = lane_word(mr.a0, h - 1), b0 = lane_word(mr.b0, h - 1), a1 = lane_word(mr.a1, h - 1), b1 = lane_word(mr.b1, h - 1);
+      const uint32_t o = lane_word(moff, h - 1);
+      const uint32_t c0 = b0 - a0, cnt = c0 + (b1 - a1);
+      float* par = reinterpret_cast<float*>(((unsigned long long)lane_word((uint32_t)(mlvl >> 32), h - 1) << 32) |
+                                            lane_word((uint32_t)mlvl, h - 1));
+      const uint32_t pos = grp;
+      const bool ok = pos < cnt;
+      const float sum = group_sum<LOGK>(staged + o + (size_t)(ok ? pos : 0u) * K, q);
+      uint32_t mn = kNoMin;
+      if (a.track_min && h == 1) mn = group_min_positive<LOGK>(staged + s_off[0] + (size_t)(ok ? pos : 0u) * K, q);
+      if (ok && q == 0) {
+        const uint32_t node = pos < c0 ? a0 + pos : a1 + (pos - c0);
+        as_global(par)[node] = sum;
+        if (a.track_min && h == 1) g.min1[(size_t)t * g.min1_stride + node] = mn;
+        if (h < H) {
+          Range2 up;
+          up.a0 = lane_word(mr.a0, h);
+          up.b0 = lane_word(mr.b0, h);
+          up.a1 = lane_word(mr.a1, h);
+          up.b1 = lane_word(mr.b1, h);
+          staged[lane_word(moff, h) + plan_pos(up, node >> LOGK) * K + (node & (K - 1))] = sum;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      continue;
+    }
     const Range2 r = s_r[h - 1];
     const uint32_t c0 = r.b0 - r.a0, cnt = c0 + (r.b1 - r.a1);
     float* par = tab.lvl[h];
@@ -160,7 +209,7 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
         mn = group_min_positive<LOGK>(staged + s_off[0] + (size_t)(ok ? pos : 0u) * K, q);
       if (ok && q == 0) {
         const uint32_t node = pos < c0 ? r.a0 + pos : r.a1 + (pos - c0);
-        par[node] = sum;
+        as_global(par)[node] = sum;
         if (a.track_min && h == 1) g.min1[(size_t)t * g.min1_stride + node] = mn;
         if (h < H) staged[s_off[h] + plan_pos(s_r[h], node >> LOGK) * K + (node & (K - 1))] = sum;
       }
@@ -227,6 +276,12 @@ static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const F
     plan.r[h - 1] = r;
     plan.off[h - 1] = floats;
     floats += ((r.b0 - r.a0) + (r.b1 - r.a1)) * K;
+  }
+  plan.chain_from = g.H + 1;
+  for (uint32_t h = g.H; h >= 1; --h) {
+    const Range2& rr = plan.r[h - 1];
+    if ((uint64_t)((rr.b0 - rr.a0) + (rr.b1 - rr.a1)) * Fan<LOGK>::LPS > 64) break;
+    plan.chain_from = h;
   }
   uint32_t block = (n * Fan<LOGK>::LPS + 63) / 64 * 64;
   // (enough lanes to move all row elements in one sweep: a second sweep is a second trip to memory)
