@@ -53,6 +53,7 @@ struct InsertPlan {
   Range2 r[kInsertHeights];        // touched nodes of height h + 1
   uint32_t off[kInsertHeights];    // where their child groups start in LDS (floats)
   uint32_t chain_from;             // from this height on one wave holds a lane group per touched node of every height
+  uint32_t single_from;            // from this height on every height has one touched node, and one wave a lane group per height
 };
 struct InsertArgs {                // one kernel argument, so that both parts sit at known offsets of the segment
   Geom g;
@@ -165,7 +166,8 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
   const uint32_t moff = s_off[ml];
   const unsigned long long mlvl = reinterpret_cast<unsigned long long>(tab.lvl[ml + 1]);
   auto lane_word = [](uint32_t v, uint32_t l) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)l); };
-  for (uint32_t h = 1; h <= H; ++h) {
+  const uint32_t single_from = kernarg_at<InsertPlan>(offsetof(InsertArgs, plan))->single_from;
+  for (uint32_t h = 1; h < single_from && h <= H; ++h) {
     const bool chained = h >= chain_from;
     if (chained && threadIdx.x >= 64) break;
     if (chained) {
@@ -215,6 +217,58 @@ k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const f
       }
     }
     lds_barrier();   // the next height reads the staged groups only
+  }
+  // ---- the heights with a single touched node: lane group i of the first wave holds the staged group of height
+  // single_from + i in registers; going up, the sum of the height below is put into its place in the group above
+  // (a register select) and that group is summed, a handful of instructions per height (the loop above spends
+  // about sixty, which is what a height costs there, not its trip through LDS).
+  if (single_from <= H && threadIdx.x < 64u) {
+    const uint32_t mine = threadIdx.x / LPS;              // this lane's group
+    const uint32_t hs = single_from + mine;               // its height
+    const bool live = hs <= H;
+    const uint32_t src = live ? hs : single_from;
+    const float* grp_at = staged + s_off[src - 1];
+    float c0, c1v, c2v = 0.0f, c3v = 0.0f;
+    if constexpr (LOGK == 1) {
+      const float2 c = *reinterpret_cast<const float2*>(grp_at);
+      c0 = c.x;
+      c1v = c.y;
+    } else {
+      const float4 c = *reinterpret_cast<const float4*>(grp_at + 4 * q);
+      c0 = c.x;
+      c1v = c.y;
+      c2v = c.z;
+      c3v = c.w;
+    }
+    const uint32_t my_node = s_r[src - 1].a0;             // (one range of one node)
+    float* my_level = tab.lvl[src];
+    uint32_t mn = kNoMin;
+    if (a.track_min && single_from == 1) mn = group_min_positive<LOGK>(staged + s_off[0], q);   // (meant for lane group 0 only)
+    float fin = 0.0f, below = 0.0f;
+    uint32_t node_below = 0;
+    const uint32_t count = H - single_from + 1;
+    for (uint32_t i = 0; i < count; ++i) {
+      const uint32_t node_here = lane_word(my_node, i * LPS);
+      if (i > 0) {
+        const uint32_t ci = node_below - node_here * K;   // the node of the height below is child ci of this one
+        const bool here = mine == i && (LOGK == 1 || q == (ci >> 2));
+        const uint32_t e = LOGK == 1 ? ci : (ci & 3u);
+        c0 = here && e == 0 ? below : c0;
+        c1v = here && e == 1 ? below : c1v;
+        c2v = here && e == 2 ? below : c2v;
+        c3v = here && e == 3 ? below : c3v;
+      }
+      float sum;
+      if constexpr (LOGK == 1) sum = c0 + c1v;
+      else sum = butterfly_sum<Fan<LOGK>::LOGLPS>((c0 + c1v) + (c2v + c3v));
+      fin = mine == i ? sum : fin;
+      below = __int_as_float((int)lane_word((uint32_t)__float_as_int(sum), i * LPS));
+      node_below = node_here;
+    }
+    if (live && q == 0) {
+      as_global(my_level)[my_node] = fin;
+      if (a.track_min && hs == 1) g.min1[(size_t)t * g.min1_stride + my_node] = mn;
+    }
   }
   PER_MARK(4);
   PER_FLUSH();
@@ -276,6 +330,13 @@ static hipError_t launch_insert_small_k(const Geom& g, const Tuning& tn, const F
     plan.r[h - 1] = r;
     plan.off[h - 1] = floats;
     floats += ((r.b0 - r.a0) + (r.b1 - r.a1)) * K;
+  }
+  plan.single_from = g.H + 1;
+  for (uint32_t h = g.H; h >= 1; --h) {
+    const Range2& rr = plan.r[h - 1];
+    if ((rr.b0 - rr.a0) + (rr.b1 - rr.a1) != 1 || rr.b0 - rr.a0 != 1) break;
+    if ((uint64_t)(g.H - h + 1) * Fan<LOGK>::LPS > 64) break;
+    plan.single_from = h;
   }
   plan.chain_from = g.H + 1;
   for (uint32_t h = g.H; h >= 1; --h) {
