@@ -262,9 +262,13 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
     // ---- 2. heights 2 .. hb of this subtree, from LDS
     // (unrolled over the slots, so that the per-height facts come out of the kernel arguments at fixed
     // offsets; read through a table in LDS instead, they cost the pass 0.3 us)
+    // K = 2: the last six heights (at most 64 nodes below them) are a wave's reduction tree: lane i holds node i,
+    // and every step of the butterfly is one more height (left + right; the partner lane adds right + left, the
+    // same bits), so those heights cost a lane exchange each instead of a pass over LDS with a barrier.
+    [[maybe_unused]] const uint32_t j_wave = LOGK == 1 ? (hb > 7 ? hb - 6 : 1u) : hb;   // first slot the wave computes
 #pragma unroll
     for (int j = 1; j < kMaxPassHeight<LOGK>; ++j) {
-      if ((uint32_t)j < hb) {
+      if ((uint32_t)j < hb && (LOGK != 1 || (uint32_t)j < j_wave)) {
         __syncthreads();
         const uint32_t sh = (hb - 1 - (uint32_t)j) * LOGK;
         const uint32_t a = b << sh;
@@ -277,6 +281,24 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
           if (ok && q == 0) {
             par[a + e] = sum;
             sub[sl.lds_off[j] + e] = sum;
+          }
+        }
+      }
+    }
+    if constexpr (LOGK == 1) {
+      if (hb > 1) {
+        __syncthreads();
+        if (threadIdx.x < 64u) {
+          const uint32_t children = 1u << (hb - j_wave);   // nodes of slot j_wave - 1 under b (zeros beyond the real ones)
+          float v = lane < children ? sub[sl.lds_off[j_wave - 1] + lane] : 0.0f;
+          for (uint32_t k = 1; j_wave - 1 + k < hb; ++k) {
+            v = v + __shfl_xor(v, 1 << (k - 1));
+            const uint32_t js = j_wave - 1 + k;             // the slot (height js + 1) this step has made
+            const uint32_t sh = hb - 1 - js;
+            const uint32_t a = b << sh;
+            const uint32_t cnt = min(sl.n[js], (b + 1) << sh) - a;
+            const uint32_t e = lane >> k;
+            if ((lane & ((1u << k) - 1u)) == 0 && e < cnt) (sl.ptr[js] + (size_t)t * sl.stride[js])[a + e] = v;
           }
         }
       }
