@@ -108,16 +108,20 @@ __device__ __forceinline__ void tree_job(const Geom& g, const SubLevels& sl, uin
     entry_first = fetch_entry(f_first);
   }
   {
-    // slot 0 from memory, the rest zero.  The first two sweeps' loads are issued together (a sweep that
+    // slot 0 from memory, the rest zero.  The first four sweeps' loads are issued together (a sweep that
     // waits for its load before the next one starts costs a trip to memory each).
     auto from_memory = [&](uint32_t i) { return (i < sl.lds_off[1] || hb == 1) && lo1 + i < n1_pad; };
-    const uint32_t i0 = threadIdx.x, i1 = threadIdx.x + blockDim.x;
-    float v0 = 0.0f, v1 = 0.0f;
+    const uint32_t i0 = threadIdx.x, i1 = threadIdx.x + blockDim.x, i2 = i1 + blockDim.x, i3 = i2 + blockDim.x;
+    float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;
     if (i0 < sl.lds_floats && from_memory(i0)) v0 = lvl1[lo1 + i0];
     if (i1 < sl.lds_floats && from_memory(i1)) v1 = lvl1[lo1 + i1];
+    if (i2 < sl.lds_floats && from_memory(i2)) v2 = lvl1[lo1 + i2];
+    if (i3 < sl.lds_floats && from_memory(i3)) v3 = lvl1[lo1 + i3];
     if (i0 < sl.lds_floats) sub[i0] = v0;
     if (i1 < sl.lds_floats) sub[i1] = v1;
-    for (uint32_t i = threadIdx.x + 2 * blockDim.x; i < sl.lds_floats; i += blockDim.x)
+    if (i2 < sl.lds_floats) sub[i2] = v2;
+    if (i3 < sl.lds_floats) sub[i3] = v3;
+    for (uint32_t i = threadIdx.x + 4 * blockDim.x; i < sl.lds_floats; i += blockDim.x)
       sub[i] = from_memory(i) ? lvl1[lo1 + i] : 0.0f;
   }
   // compact the claimed nodes into s_list / s_bits / s_entry: ballot within the wave, wave totals through LDS
