@@ -21,8 +21,15 @@ __device__ __forceinline__ void lds_barrier() {
 // is accessed with flat instructions, which count as LDS traffic as well: the wave's next wait for LDS data then
 // waits for that trip to memory too.  Every such pointer of this library points to device memory; saying so gives
 // plain global accesses.
+// (The compiler's pass over this file for the host, which builds none of this code but checks it, does not convert
+// such pointers back to plain ones where a function takes those: there the type is the plain pointer.)
+#if defined(__HIP_DEVICE_COMPILE__)
 template <typename T>
 using GlobalPtr = T __attribute__((address_space(1)))*;
+#else
+template <typename T>
+using GlobalPtr = T*;
+#endif
 template <typename T>
 __device__ __forceinline__ GlobalPtr<T> as_global(T* p) { return (GlobalPtr<T>)p; }
 
