@@ -143,44 +143,49 @@ __device__ __forceinline__ void touch_kernel_arguments() {
 // The same through one scalar register: every line is asked for by a load into that register, and the wait for all
 // of them stands inside the statement, so that nothing is in flight into the register when the statement ends.  For
 // kernels that have no scalar registers to spare for a word per line.
-template <int LINES>
-__device__ __forceinline__ void touch_kernel_arguments_through_one_register() {
-  static_assert(LINES >= 1 && LINES <= kTouchLines, "more lines than the statement lists");
+template <uint32_t MASK>
+__device__ __forceinline__ void touch_kernel_argument_lines() {   // bit i of MASK: line i is asked for
+  static_assert(MASK != 0 && (MASK >> kTouchLines) == 0, "lines beyond those the statement lists");
   const uint32_t* ka = kernarg_at<uint32_t>(0);
   uint32_t w;
   asm volatile(
-    "s_load_dword %0, %1, 0x0\n"
-    ".if %2 > 1\n s_load_dword %0, %1, 0x40\n .endif\n"
-    ".if %2 > 2\n s_load_dword %0, %1, 0x80\n .endif\n"
-    ".if %2 > 3\n s_load_dword %0, %1, 0xc0\n .endif\n"
-    ".if %2 > 4\n s_load_dword %0, %1, 0x100\n .endif\n"
-    ".if %2 > 5\n s_load_dword %0, %1, 0x140\n .endif\n"
-    ".if %2 > 6\n s_load_dword %0, %1, 0x180\n .endif\n"
-    ".if %2 > 7\n s_load_dword %0, %1, 0x1c0\n .endif\n"
-    ".if %2 > 8\n s_load_dword %0, %1, 0x200\n .endif\n"
-    ".if %2 > 9\n s_load_dword %0, %1, 0x240\n .endif\n"
-    ".if %2 > 10\n s_load_dword %0, %1, 0x280\n .endif\n"
-    ".if %2 > 11\n s_load_dword %0, %1, 0x2c0\n .endif\n"
-    ".if %2 > 12\n s_load_dword %0, %1, 0x300\n .endif\n"
-    ".if %2 > 13\n s_load_dword %0, %1, 0x340\n .endif\n"
-    ".if %2 > 14\n s_load_dword %0, %1, 0x380\n .endif\n"
-    ".if %2 > 15\n s_load_dword %0, %1, 0x3c0\n .endif\n"
-    ".if %2 > 16\n s_load_dword %0, %1, 0x400\n .endif\n"
-    ".if %2 > 17\n s_load_dword %0, %1, 0x440\n .endif\n"
-    ".if %2 > 18\n s_load_dword %0, %1, 0x480\n .endif\n"
-    ".if %2 > 19\n s_load_dword %0, %1, 0x4c0\n .endif\n"
-    ".if %2 > 20\n s_load_dword %0, %1, 0x500\n .endif\n"
-    ".if %2 > 21\n s_load_dword %0, %1, 0x540\n .endif\n"
-    ".if %2 > 22\n s_load_dword %0, %1, 0x580\n .endif\n"
-    ".if %2 > 23\n s_load_dword %0, %1, 0x5c0\n .endif\n"
-    ".if %2 > 24\n s_load_dword %0, %1, 0x600\n .endif\n"
-    ".if %2 > 25\n s_load_dword %0, %1, 0x640\n .endif\n"
-    ".if %2 > 26\n s_load_dword %0, %1, 0x680\n .endif\n"
-    ".if %2 > 27\n s_load_dword %0, %1, 0x6c0\n .endif\n"
+    ".if (%2 >> 0) & 1\n s_load_dword %0, %1, 0x0\n .endif\n"
+    ".if (%2 >> 1) & 1\n s_load_dword %0, %1, 0x40\n .endif\n"
+    ".if (%2 >> 2) & 1\n s_load_dword %0, %1, 0x80\n .endif\n"
+    ".if (%2 >> 3) & 1\n s_load_dword %0, %1, 0xc0\n .endif\n"
+    ".if (%2 >> 4) & 1\n s_load_dword %0, %1, 0x100\n .endif\n"
+    ".if (%2 >> 5) & 1\n s_load_dword %0, %1, 0x140\n .endif\n"
+    ".if (%2 >> 6) & 1\n s_load_dword %0, %1, 0x180\n .endif\n"
+    ".if (%2 >> 7) & 1\n s_load_dword %0, %1, 0x1c0\n .endif\n"
+    ".if (%2 >> 8) & 1\n s_load_dword %0, %1, 0x200\n .endif\n"
+    ".if (%2 >> 9) & 1\n s_load_dword %0, %1, 0x240\n .endif\n"
+    ".if (%2 >> 10) & 1\n s_load_dword %0, %1, 0x280\n .endif\n"
+    ".if (%2 >> 11) & 1\n s_load_dword %0, %1, 0x2c0\n .endif\n"
+    ".if (%2 >> 12) & 1\n s_load_dword %0, %1, 0x300\n .endif\n"
+    ".if (%2 >> 13) & 1\n s_load_dword %0, %1, 0x340\n .endif\n"
+    ".if (%2 >> 14) & 1\n s_load_dword %0, %1, 0x380\n .endif\n"
+    ".if (%2 >> 15) & 1\n s_load_dword %0, %1, 0x3c0\n .endif\n"
+    ".if (%2 >> 16) & 1\n s_load_dword %0, %1, 0x400\n .endif\n"
+    ".if (%2 >> 17) & 1\n s_load_dword %0, %1, 0x440\n .endif\n"
+    ".if (%2 >> 18) & 1\n s_load_dword %0, %1, 0x480\n .endif\n"
+    ".if (%2 >> 19) & 1\n s_load_dword %0, %1, 0x4c0\n .endif\n"
+    ".if (%2 >> 20) & 1\n s_load_dword %0, %1, 0x500\n .endif\n"
+    ".if (%2 >> 21) & 1\n s_load_dword %0, %1, 0x540\n .endif\n"
+    ".if (%2 >> 22) & 1\n s_load_dword %0, %1, 0x580\n .endif\n"
+    ".if (%2 >> 23) & 1\n s_load_dword %0, %1, 0x5c0\n .endif\n"
+    ".if (%2 >> 24) & 1\n s_load_dword %0, %1, 0x600\n .endif\n"
+    ".if (%2 >> 25) & 1\n s_load_dword %0, %1, 0x640\n .endif\n"
+    ".if (%2 >> 26) & 1\n s_load_dword %0, %1, 0x680\n .endif\n"
+    ".if (%2 >> 27) & 1\n s_load_dword %0, %1, 0x6c0\n .endif\n"
     "s_waitcnt lgkmcnt(0)"
     : "=&s"(w)
-    : "s"(ka), "n"(LINES));
+    : "s"(ka), "n"(MASK));
   (void)w;
+}
+template <int LINES>
+__device__ __forceinline__ void touch_kernel_arguments_through_one_register() {
+  static_assert(LINES >= 1 && LINES <= kTouchLines, "more lines than the statement lists");
+  touch_kernel_argument_lines<(LINES >= 32 ? 0xFFFFFFFFu : (1u << LINES) - 1u)>();
 }
 __device__ __forceinline__ void fill_level_table(uint32_t H, uint32_t t, LevelTable* tab) {
   const Geom* gk = kernarg_at<Geom>(0);

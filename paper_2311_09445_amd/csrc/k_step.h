@@ -247,6 +247,8 @@ __device__ __forceinline__ uint32_t chunk_groups(const ChunkLds& c, uint32_t slo
 // memory, one more trip; its address is reported by a kernel instead.)
 static __device__ __align__(256) StepTable g_step_tab_static[kStepMaxOwners];
 constexpr uint32_t kStepFront = 64;
+constexpr uint32_t kStepEpilogueArgLines = (1u << 0) | (3u << 12) | (0x1FFu << 17);
+constexpr uint32_t kStepOwnerArgLines = (1u << 0) | (1u << 2) | (1u << 4) | (1u << 12) | (0x7Fu << 15);   // 64-byte lines of the kernel arguments
 __global__ void k_step_static_address(void** out) { *out = g_step_tab_static; }
 // Who holds the array on each GPU.  A buffer that held it before may still have work in flight that reads or writes
 // it, so a GPU whose array changes hands is drained first.
@@ -319,7 +321,10 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   }
   constexpr int kArgLines = kernarg_lines<Geom, StepShape, uint32_t, uint32_t, float, uint32_t, const float*, RngArgs, uint32_t*,
                                          float*, float*, const float*, const uint32_t*>();
-  if constexpr (STATIC) touch_kernel_arguments_through_one_register<kArgLines>();
+  // (STATIC: only the lines an owner reads: the first words of the geometry, the strides and pointers of heights 0
+  // and 1, the scalars' pointers, and everything from the subtree's description on; a line costs 35 to 60 ns even in a
+  // batch, and the builders, which read more, are not what the kernel waits for)
+  if constexpr (STATIC) touch_kernel_argument_lines<kStepOwnerArgLines>();
   else touch_kernel_arguments<kArgLines>();
   extern __shared__ __attribute__((aligned(16))) float lds[];
   __shared__ uint32_t s_u32[8];
@@ -1027,8 +1032,10 @@ template <int LOGK, bool WIDE>
 __global__ void __launch_bounds__(256)
 k_step_epilogue(Geom g, StepShape sh, uint32_t table_blocks, uint32_t B, float beta, uint32_t weight_mode,
                 float* __restrict__ w, const uint32_t* __restrict__ idx, FieldTable ft, JobRanges jr) {
-  touch_kernel_arguments<kernarg_lines<Geom, StepShape, uint32_t, uint32_t, float, uint32_t, float*, const uint32_t*, FieldTable,
-                                       JobRanges>()>();
+  // (only the lines that the row and weight workgroups read, which are what the kernel waits for: the first words of
+  // the geometry, the status and scalar pointers, the counters and minima of the step's shape, and everything from
+  // the call's own arguments on: field table, job ranges; the table builders fetch the rest as they go)
+  touch_kernel_argument_lines<kStepEpilogueArgLines>();
   extern __shared__ __attribute__((aligned(16))) float top[];
   __shared__ uint32_t s_m[4];
   __shared__ float skipped[kTableOwners * kStepPathMax];

@@ -403,6 +403,12 @@ k_update_tree(Geom g, SubLevels sl, uint32_t chain) {
 template <int LOGK, bool TRACK_MIN, bool WIDE>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_num_sgpr(96)))
 k_tree_finish(Geom g, SubLevels sl, uint32_t chain, uint32_t tree_blocks, FieldTable ft, JobRanges jr, FinishArgs a) {
+  // (the lines of the arguments asked for in one batch, through one scalar register: this kernel has none to spare;
+  // by the first four waves only: with every wave of a 512-lane workgroup at it, the step of 65 536 samples on 2^24
+  // leaves loses 0.3 us where the small workloads gain as much)
+  if (threadIdx.x < 256u)
+    touch_kernel_arguments_through_one_register<kernarg_lines<Geom, SubLevels, uint32_t, uint32_t, FieldTable, JobRanges, FinishArgs>() < kTouchLines
+                                                    ? kernarg_lines<Geom, SubLevels, uint32_t, uint32_t, FieldTable, JobRanges, FinishArgs>() : kTouchLines>();
   const uint32_t t = blockIdx.y;
   if (blockIdx.x < tree_blocks) {
     const uint32_t pend = (chain & 2u) && blockIdx.x == 0 ? read_word_with_the_loads(&g.max_pend[t]) : 0u;
