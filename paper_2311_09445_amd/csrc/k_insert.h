@@ -65,6 +65,7 @@ template <int LOGK>
 __global__ void __launch_bounds__(1024)
 k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const float* __restrict__ prio,
                uint32_t* __restrict__ out_idx, const uint32_t* __restrict__ protect, uint32_t n_protect) {
+  if (threadIdx.x < 256u) touch_kernel_arguments_through_one_register<kTouchLines>();   // (geometry and plan: about that many lines)
   const Geom& g = a.g;
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
