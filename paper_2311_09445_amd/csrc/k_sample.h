@@ -107,9 +107,12 @@ k_sample(Geom g, TopCopy tc, uint32_t B, uint32_t size, float beta, const float*
   constexpr int ROW = K + 4;                  // staging row, floats
   using Vec = typename std::conditional<LOGK == 1, float2, float4>::type;
   constexpr int VF = sizeof(Vec) / 4;
+  // (lines 1, 3, 6, 7, 10, 11 of the geometry hold what this kernel does not read on trees of few heights: the upper
+  // ends of the per-height arrays, the arrival counters, the one-kernel step's words)
   touch_kernel_arguments<kernarg_lines<Geom, TopCopy, uint32_t, uint32_t, float, const float*, uint32_t*, float*, float*, uint32_t,
                                        int, uint32_t, ClaimArgs, int, RngArgs,
-                                       typename std::conditional<RIDE, InsertRideHead, NoRide>::type>()>();
+                                       typename std::conditional<RIDE, InsertRideHead, NoRide>::type>(),
+                         LOGK >= 3 ? 0xCCAu : 0u>();
   extern __shared__ __attribute__((aligned(16))) float lds[];   // 16-byte LDS accesses need the alignment
   __shared__ uint32_t s_min[16];
   __shared__ float s_total;
