@@ -65,7 +65,9 @@ template <int LOGK>
 __global__ void __launch_bounds__(1024)
 k_insert_small(InsertArgs a, FieldTable ft, uint32_t n, uint32_t cursor, const float* __restrict__ prio,
                uint32_t* __restrict__ out_idx, const uint32_t* __restrict__ protect, uint32_t n_protect) {
-  if (threadIdx.x < 256u) touch_kernel_arguments_through_one_register<kTouchLines>();   // (geometry and plan: about that many lines)
+  // (the lines read through the scalar cache: the first words and the scalars' pointers of the geometry, and what
+  // follows the plan; the per-height tables of geometry and plan are fetched by vector loads, a lane per height)
+  if (threadIdx.x < 256u) touch_kernel_argument_lines<(1u << 0) | (3u << 12) | (0xFu << 24)>();
   const Geom& g = a.g;
   constexpr int K = Fan<LOGK>::K;
   constexpr int LPS = Fan<LOGK>::LPS;
