@@ -316,7 +316,8 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     const StepTable* early = g_step_tab_static + (blockIdx.x >= kStepFront ? blockIdx.x - kStepFront : 0u) + zero;
     pre_total = early->total;
     pre_mass = early->mass;
-    pre_path = early->path[threadIdx.x < (uint32_t)kStepPathMax ? threadIdx.x : (uint32_t)kStepPathMax - 1u];   // (no branch: every lane loads)
+    // (lane i of every wave: step i of the way; no branch: every lane loads)
+    pre_path = early->path[(threadIdx.x & 63u) < (uint32_t)kStepPathMax ? (threadIdx.x & 63u) : (uint32_t)kStepPathMax - 1u];
     asm volatile("" ::: "memory");   // (the loads stay in front of this line, and so in front of everything that waits for an argument)
   }
   constexpr int kArgLines = kernarg_lines<Geom, StepShape, uint32_t, uint32_t, float, uint32_t, const float*, RngArgs, uint32_t*,
@@ -479,7 +480,6 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   const uint32_t par = (uint32_t)calls & 1u;          // which set of slots and builder counters this call uses
   __syncthreads();
   PER_MARK(1);
-  PER_MARK(2);
   const bool leader = b == 0 && tid == 0;
 
   // This owner is done: one more in its group's counter (no answer is waited for).
@@ -593,21 +593,35 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
   // where a target lands relative to node b: 0 in front of it, 1 in its subtree (r then holds what is left of the
   // target inside it), 2 behind it.  The same comparisons and subtractions as the walk through the child groups.
   auto landing = [&](float& r) -> uint32_t {
+    uint32_t res = 1u;
+    bool open = true;   // still on the way to b
     for (int lv = 0; lv < n_top; ++lv) {   // the steps inside one child group: their table entries are read together
       float2 e[LOGK];
 #pragma unroll
-      for (int j = 0; j < LOGK; ++j) e[j] = path[lv * LOGK + j];
-#pragma unroll
       for (int j = 0; j < LOGK; ++j) {
-        const float L = e[j].x;
+        if constexpr (STATIC) {   // (the entries sit in the lanes of every wave: read from there, they are scalars)
+          e[j].x = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pre_path.x), lv * LOGK + j));
+          e[j].y = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pre_path.y), lv * LOGK + j));
+        } else {
+          e[j] = path[lv * LOGK + j];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < LOGK; ++j) {   // (selects, no early way out: lanes that leave at different steps made the steps cost a branch each)
+        // The step's facts are the same for every lane: whether b lies to the right (want), and the left block's sum,
+        // taken as infinite for the comparison when the right block is zero (nobody goes right then) and as zero for
+        // the subtraction when b lies to the left (lanes still on b's way keep their target; the others' is not used).
         const uint32_t fl = __float_as_uint(e[j].y);
-        const bool right = (fl & 2u) && !(r < L);
         const bool want = (fl & 1u) != 0u;
-        if (right != want) return want ? 0u : 2u;
-        if (right) r = r - L;
+        const float L_cmp = (fl & 2u) ? e[j].x : __builtin_huge_valf();
+        const float L_sub = want ? e[j].x : 0.0f;
+        const bool stay = !(r < L_cmp) == want;
+        res = open && !stay ? (want ? 0u : 2u) : res;
+        open = open && stay;
+        r = r - L_sub;
       }
     }
-    return 1u;
+    return res;
   };
   auto uniform_of = [&](uint32_t s) -> float { return rng.on ? counter_uniform(rng, s, t) : u[(size_t)t * B + s]; };
   auto landing_of = [&](uint32_t s) -> uint32_t {   // (samples beyond the batch: behind every node)
@@ -651,7 +665,9 @@ k_step(Geom g, StepShape sh, uint32_t B, uint32_t size, float beta, uint32_t wei
     prio_s = in ? upd_prio[(size_t)t * B + s] : 0.0f;
   }
   float r = ((float)s + u_s) * seg, val = total;
+  PER_MARK(2);
   const uint32_t where = in ? landing(r) : 2u;
+  PER_MARK(14);
   // does the window hold the whole run?  its first sample must land in front of b (or be sample 0), and a sample
   // of it must land behind b (or the batch must end in it)
   uint32_t run_lo, run_n;
